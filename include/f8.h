@@ -1,0 +1,188 @@
+/*
+ * f8.h - C ABI of the MI355X (gfx950) Float8 linear-layer library.
+ *
+ * The operation: the Float8 linear layer of the paper's section "Boosting
+ * throughput with mixed precision training and Float8 support": a linear
+ * layer whose three matrix products (forward Y = X W^T, backward dX = dY W and
+ * dW = dY^T X) run on fp8 operands with dynamic scaling, i.e. each bf16 tensor
+ * is scaled by FMAX / amax(tensor) computed from the tensor itself right before
+ * it is cast.  Number formats are the OCP FP8 formats the paper cites
+ * (Micikevicius et al., "FP8 formats for deep learning"): E4M3 (max 448, no
+ * infinity) and E5M2 (max 57344).  Products accumulate in fp32; outputs are
+ * bf16 (the experiments section notes that FP8 and BF16 matrix units both take
+ * part in a Float8 training step).
+ *
+ * Conventions that hold for every entry point
+ *   - Every data pointer is DEVICE memory on the current HIP device, owned by
+ *     the caller.  The library never allocates, frees or synchronises.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Every call only enqueues kernels on it and returns.
+ *   - Matrices are row-major; a leading dimension `ld*` is in elements.
+ *   - bf16 data is passed as `const void*` / `void*` (2 bytes per element),
+ *     fp8 data as uint8_t codes, scales as fp32 in device memory (they never
+ *     visit the host).
+ *   - Data pointers must be 16-byte aligned; rows, cols, leading dimensions and
+ *     M, N, K must be multiples of 16 (zero is allowed and is a no-op apart
+ *     from writing amax = 0 and its scale).  Violations return F8_ERR_ALIGN /
+ *     F8_ERR_SHAPE.
+ *   - Arguments are checked on the host before anything is launched; on an
+ *     error return nothing has been enqueued or written.  A failed launch
+ *     returns F8_ERR_LAUNCH.  No exception or abort crosses this boundary.
+ *   - No global mutable state: calls on different streams with disjoint
+ *     buffers (including disjoint workspaces) may run concurrently.
+ *   - Inputs are expected to be finite.  With a caller-given finite scale,
+ *     f8_cast maps NaN to a NaN code (0x7F or 0xFF) and +-Inf to the
+ *     +-FMAX code; amax over non-finite data is unspecified.
+ */
+#ifndef F8_H
+#define F8_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    F8_OK = 0,
+    F8_ERR_NULL = 1,      /* a required pointer is NULL                        */
+    F8_ERR_SHAPE = 2,     /* negative size, size or ld not a multiple of 16, ld too small */
+    F8_ERR_ALIGN = 3,     /* a data pointer is not 16-byte aligned             */
+    F8_ERR_ENUM = 4,      /* an enum argument is out of range                  */
+    F8_ERR_WORKSPACE = 5, /* workspace NULL or smaller than required           */
+    F8_ERR_LAUNCH = 6     /* the HIP runtime refused a kernel launch           */
+} f8_status;
+
+/* OCP FP8 formats.  E4M3: 4 exponent bits, bias 7, NaN = S.1111.111 only, max
+ * finite 0x7E = 448.  E5M2: 5 exponent bits, bias 15, IEEE-like, max finite
+ * 0x7B = 57344. */
+typedef enum { F8_E4M3 = 0, F8_E5M2 = 1 } f8_format;
+
+/* How many scales a [rows, cols] tensor has: one, one per row, one per column. */
+typedef enum { F8_TENSORWISE = 0, F8_ROWWISE = 1, F8_COLWISE = 2 } f8_granularity;
+
+/* Operand layouts of f8_gemm; D is always [M, N].
+ *   F8_NT: A[M,K], B[N,K]   (both contraction-contiguous)
+ *   F8_NN: A[M,K], B[K,N]
+ *   F8_TN: A[K,M], B[K,N] */
+typedef enum { F8_NT = 0, F8_NN = 1, F8_TN = 2 } f8_layout;
+
+/* Bytes of device workspace that is enough for any call of this library with
+ * rows, cols, M, N, K up to 2^20.  The workspace holds partial maxima only; it
+ * needs no initialisation and carries no state between calls. */
+size_t f8_workspace_bytes(void);
+
+const char* f8_status_string(f8_status s);
+
+/*
+ * Step 1 of dynamic scaling: amax = max |x| of a bf16 matrix [rows, cols].
+ *   g = F8_TENSORWISE: amax_out[0];  F8_ROWWISE: amax_out[rows] (max over the
+ *   columns of each row);  F8_COLWISE: amax_out[cols] (max over the rows of
+ *   each column).  Exact (it is one of the inputs' magnitudes).
+ * workspace: f8_workspace_bytes() bytes (unused for F8_ROWWISE; may be NULL then).
+ */
+f8_status f8_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, f8_granularity g,
+                  float* amax_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Step 2: scale[i] = FMAX(fmt) / max(amax[i], 1e-12f) and inv_scale[i] =
+ * 1.0f / scale[i], both single correctly rounded fp32 divisions.  n >= 0
+ * entries; inv_scale_out may be NULL.
+ */
+f8_status f8_scale(const float* amax, int64_t n, f8_format fmt, float* scale_out,
+                   float* inv_scale_out, void* stream);
+
+/*
+ * Step 3: code = fp8_rne( clamp( fp32(x) * scale, -FMAX, +FMAX ) ): one fp32
+ * multiply (rounded), saturation, then round-to-nearest-even to the fp8 grid.
+ *   scale: 1, rows or cols entries according to g.
+ *   out   [rows, cols] (ld_out >= cols) and/or
+ *   out_t [cols, rows] (ld_out_t >= rows), the same codes transposed.
+ * At least one of out / out_t must be non-NULL.
+ */
+f8_status f8_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+                  f8_granularity g, f8_format fmt, uint8_t* out, int64_t ld_out, uint8_t* out_t,
+                  int64_t ld_out_t, void* stream);
+
+/*
+ * Steps 1-3 fused as the hot path uses them (dynamic scaling): writes
+ * amax_out, scale_out, inv_scale_out (1, rows or cols entries; all required)
+ * and the codes.  Results are identical to f8_amax -> f8_scale -> f8_cast.
+ */
+f8_status f8_amax_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld,
+                       f8_granularity g, f8_format fmt, float* amax_out, float* scale_out,
+                       float* inv_scale_out, uint8_t* out, int64_t ld_out, uint8_t* out_t,
+                       int64_t ld_out_t, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * fp8 GEMM with fp32 accumulation and bf16 output:
+ *   D[m,n] = bf16_rne( (sum_k dec(A)[m,k] * dec(B)[n,k]) * inv_scale_a * inv_scale_b )
+ * fa / fb: format of A / B codes (mixed E5M2 x E4M3 is allowed).
+ * g = F8_TENSORWISE: inv_scale_a[0], inv_scale_b[0].
+ * g = F8_ROWWISE:    inv_scale_a[M] (per output row), inv_scale_b[N] (per output column).
+ * F8_COLWISE is not a GEMM mode (F8_ERR_ENUM).
+ * Summation order is unspecified (results agree with any fp32 order within
+ * accumulation rounding).
+ */
+f8_status f8_gemm(f8_layout layout, int64_t M, int64_t N, int64_t K, const uint8_t* A, f8_format fa,
+                  int64_t lda, const uint8_t* B, f8_format fb, int64_t ldb, const float* inv_scale_a,
+                  const float* inv_scale_b, f8_granularity g, void* D_bf16, int64_t ldd,
+                  void* stream);
+
+/*
+ * One quantised tensor T[rows, cols] as the linear layer keeps it between
+ * forward and backward.  All members are caller-allocated device memory.
+ *   Tensorwise: q [rows, cols] and q_t [cols, rows] hold the same codes;
+ *     amax / scale / inv_scale have 1 entry; the *_t scale members are unused
+ *     (may be NULL).
+ *   Rowwise: q is scaled per row (amax, scale, inv_scale: rows entries); q_t is
+ *     the transposed tensor scaled per ITS row, i.e. per column of T (amax_t,
+ *     scale_t, inv_scale_t: cols entries).  The two hold different codes.
+ */
+typedef struct f8_qtensor {
+    uint8_t* q;
+    uint8_t* q_t;
+    float* amax;
+    float* scale;
+    float* inv_scale;
+    float* amax_t;
+    float* scale_t;
+    float* inv_scale_t;
+} f8_qtensor;
+
+/* X [M,K], W [N,K], dY [M,N]. */
+typedef struct f8_saved {
+    f8_qtensor x;
+    f8_qtensor w;
+    f8_qtensor dy;
+} f8_saved;
+
+typedef struct f8_linear_desc {
+    int64_t M, K, N;
+    int32_t granularity; /* F8_TENSORWISE or F8_ROWWISE */
+    int32_t grad_format; /* f8_format of dY; X and W are always E4M3 */
+} f8_linear_desc;
+
+/*
+ * Forward of the Float8 linear: quantise X [M,K] and W [N,K] (bf16) with
+ * dynamic scaling into saved->x, saved->w (both orientations, for backward),
+ * then Y [M,N] (bf16) = X8 W8^T with the scales folded into the epilogue.
+ * Rowwise: Y uses X per row m and W per row n.
+ */
+f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, void* Y,
+                        f8_saved* saved, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward: quantise dY [M,N] into saved->dy, then
+ *   dX [M,K] = dY8 W8      (rowwise: dY per row m, W per column k)
+ *   dW [N,K] = dY8^T X8    (rowwise: dY per column n, X per column k)
+ * using saved->x and saved->w from the forward call.
+ */
+f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved, void* dX,
+                        void* dW, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* F8_H */

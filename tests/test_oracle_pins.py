@@ -1,0 +1,399 @@
+"""Pins of the CPU oracle against facts that do not come from the oracle:
+the OCP FP8 format table, hand-worked rounding cases, PyTorch's own CPU float8
+and bfloat16 conversions (on inputs where their definition coincides), numpy
+fp64 matrix products, brute-force nearest-value search and closed forms.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as o
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+FMTS = {"e4m3": o.E4M3, "e5m2": o.E5M2}
+TORCH_F8 = {o.E4M3: torch.float8_e4m3fn, o.E5M2: torch.float8_e5m2}
+
+
+def _lines(name):
+    with open(os.path.join(GOLD, name)) as f:
+        for ln in f:
+            ln = ln.strip()
+            if ln and not ln.startswith("#"):
+                yield ln.split()
+
+
+def _val(tok):
+    if tok.startswith("2^"):
+        return 2.0 ** int(tok[2:])
+    return float(tok)
+
+
+def bf16_bits(x):
+    return torch.as_tensor(np.asarray(x, dtype=np.float32)).to(torch.bfloat16).view(torch.uint16).numpy()
+
+
+ALL_BF16 = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+
+
+def finite_codes(fmt):
+    if fmt == o.E4M3:
+        return [c for c in range(256) if (c & 0x7F) != 0x7F]
+    return [c for c in range(256) if (c & 0x7F) < 0x7C]
+
+
+# ---- format facts -------------------------------------------------------------
+
+def test_format_table():
+    for fmt, code, val in _lines("fp8_format_facts.txt"):
+        got = float(o.decode(np.array([int(code, 16)], np.uint8), FMTS[fmt])[0])
+        assert got == _val(val), (fmt, code, got)
+        assert int(o.encode(np.array([_val(val)], np.float32), FMTS[fmt])[0]) == int(code, 16)
+    assert o.fmax(o.E4M3) == 448.0 and o.fmax(o.E5M2) == 57344.0
+
+
+def test_special_code_counts():
+    d4 = o.decode(np.arange(256, dtype=np.uint8), o.E4M3)
+    assert np.isnan(d4).sum() == 2 and np.isinf(d4).sum() == 0 and np.isfinite(d4).sum() == 254
+    assert np.isnan(d4[[0x7F, 0xFF]]).all()
+    d5 = o.decode(np.arange(256, dtype=np.uint8), o.E5M2)
+    assert np.isnan(d5).sum() == 6 and np.isinf(d5).sum() == 2 and np.isfinite(d5).sum() == 248
+    assert d5[0x7C] == np.inf and d5[0xFC] == -np.inf
+
+
+@pytest.mark.parametrize("fmt", [o.E4M3, o.E5M2])
+def test_decode_matches_torch_cpu_dtype(fmt):
+    codes = torch.arange(256, dtype=torch.int32).to(torch.uint8)
+    ref = codes.view(TORCH_F8[fmt]).to(torch.float32).numpy()
+    got = o.decode(codes.numpy(), fmt)
+    assert np.array_equal(np.isnan(ref), np.isnan(got))
+    m = ~np.isnan(ref)
+    assert np.array_equal(ref[m], got[m])
+
+
+@pytest.mark.parametrize("fmt", [o.E4M3, o.E5M2])
+def test_round_trip_monotone_symmetric(fmt):
+    fc = np.array(finite_codes(fmt), np.uint8)
+    vals = o.decode(fc, fmt)
+    assert np.array_equal(o.encode(vals, fmt), fc)          # exact round trip
+    pos = np.array([c for c in fc if c < 0x80], np.uint8)
+    pv = o.decode(pos, fmt)
+    assert np.all(np.diff(pv) > 0)                            # strictly increasing with the code
+    y = np.abs(np.random.default_rng(1).standard_normal(4000).astype(np.float32)) * 50
+    y = np.minimum(y, o.fmax(fmt))
+    assert np.array_equal(o.encode(-y, fmt), o.encode(y, fmt) | 0x80)
+
+
+@pytest.mark.parametrize("fmt", [o.E4M3, o.E5M2])
+def test_encode_monotone_over_all_bf16(fmt):
+    x = o.bf16_to_f32(ALL_BF16)
+    keep = np.isfinite(x) & (ALL_BF16 < 0x8000)        # non-negative, without -0.0
+    xs = np.sort(x[keep])
+    xs = np.minimum(xs, o.fmax(fmt))
+    codes = o.encode(xs, fmt).astype(np.int32)
+    assert np.all(np.diff(codes) >= 0)
+    assert codes[0] == 0 and codes[-1] == (0x7E if fmt == o.E4M3 else 0x7B)
+
+
+# ---- rounding -----------------------------------------------------------------
+
+def test_rne_and_saturation_cases():
+    n = 0
+    for tok in _lines("fp8_rne_cases.txt"):
+        fmt, y, code = FMTS[tok[0]], np.float32(float(tok[1])), int(tok[2], 16)
+        # through the saturating cast with scale 1 (bf16 input would round y, so call the
+        # scalar pieces: clamp then encode)
+        fm = np.float32(o.fmax(fmt))
+        c = np.float32(min(max(y, -fm), fm))
+        assert int(o.encode(np.array([c]), fmt)[0]) == code, tok
+        n += 1
+    assert n >= 25
+
+
+@pytest.mark.parametrize("fmt", [o.E4M3, o.E5M2])
+def test_encode_equals_brute_force_nearest(fmt):
+    """Nearest representable value found by exhaustive search over all finite codes in
+    fp64; ties resolved to the code with even last bit."""
+    fc = np.array([c for c in finite_codes(fmt) if c < 0x80], np.uint8)
+    vals = o.decode(fc, fmt).astype(np.float64)
+    rng = np.random.default_rng(2)
+    fm = o.fmax(fmt)
+    y = np.concatenate([
+        rng.uniform(0, fm, 3000), rng.uniform(0, 2.0 ** -5, 3000), rng.uniform(0, 2.0 ** -13, 3000),
+        (vals[:-1] + vals[1:]) / 2,                 # every tie point
+        np.nextafter(((vals[:-1] + vals[1:]) / 2).astype(np.float32), np.float32(np.inf)).astype(np.float64),
+        np.nextafter(((vals[:-1] + vals[1:]) / 2).astype(np.float32), np.float32(0)).astype(np.float64),
+    ]).astype(np.float32)
+    got = o.encode(y, fmt)
+    d = np.abs(y.astype(np.float64)[:, None] - vals[None, :])
+    dmin = d.min(axis=1, keepdims=True)
+    for i in range(y.size):
+        cand = fc[d[i] == dmin[i, 0]]
+        exp = cand[0] if cand.size == 1 else [c for c in cand if c % 2 == 0][0]
+        assert got[i] == exp, (y[i], got[i], exp)
+
+
+@pytest.mark.parametrize("fmt", [o.E4M3, o.E5M2])
+def test_cast_matches_torch_cpu_on_clamped_inputs(fmt):
+    """PyTorch's CPU float8 conversion rounds to nearest even but does not saturate, so it
+    is a second opinion only after clamping: all bf16 values times a sweep of scales."""
+    x = o.bf16_to_f32(ALL_BF16)
+    x = x[np.isfinite(x)]
+    fm = np.float32(o.fmax(fmt))
+    for s in [1.0, 112.0, 0.37, 448.0 / 3.3, 1e-3, 3.0e4, 2.0 ** -7, 57344.0 / 0.0123]:
+        y = np.clip(x * np.float32(s), -fm, fm).astype(np.float32)
+        ref = torch.from_numpy(y).to(TORCH_F8[fmt]).view(torch.uint8).numpy()
+        sub = slice(None, None, 7)                       # ~9k values per scale through the C encoder
+        assert np.array_equal(o.encode(y[sub], fmt), ref[sub]), s
+
+
+@pytest.mark.parametrize("fmt", [o.E4M3, o.E5M2])
+def test_full_cast_vs_torch_all_bf16(fmt):
+    """The array-level cast (multiply, clamp, encode) on every finite bf16 input."""
+    xb = ALL_BF16[np.isfinite(o.bf16_to_f32(ALL_BF16))].reshape(1, -1)
+    fm = np.float32(o.fmax(fmt))
+    for s in [1.0, 112.0, 0.0371, 5.1e3]:
+        got = o.cast(xb, np.float32(s), o.TENSORWISE, fmt)
+        y = np.clip(o.bf16_to_f32(xb) * np.float32(s), -fm, fm).astype(np.float32)
+        ref = torch.from_numpy(y).to(TORCH_F8[fmt]).view(torch.uint8).numpy()
+        assert np.array_equal(got, ref), s
+
+
+def test_cast_nan_inf_reading():
+    xb = np.array([[0x7FC0, 0xFFC0, 0x7F80, 0xFF80]], np.uint16)   # +NaN, -NaN, +Inf, -Inf
+    c4 = o.cast(xb, 1.0, o.TENSORWISE, o.E4M3)[0]
+    assert (c4[0] & 0x7F) == 0x7F and (c4[1] & 0x7F) == 0x7F          # a NaN code; sign not specified
+    assert c4[2] == 0x7E and c4[3] == 0xFE
+    c5 = o.cast(xb, 1.0, o.TENSORWISE, o.E5M2)[0]
+    assert (c5[0] & 0x7F) == 0x7F and c5[2] == 0x7B and c5[3] == 0xFB
+
+
+def test_bf16_rounding_matches_torch():
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.standard_normal(5000) * 10.0 ** rng.uniform(-30, 30, 5000),
+                        [1.00390625, 1.01171875, -1.00390625, 0.0, -0.0, 3.3895314e38, 3.4e38, 1e-40]]).astype(np.float32)
+    ref = torch.from_numpy(x).to(torch.bfloat16).view(torch.uint16).numpy()
+    assert np.array_equal(o.f32_to_bf16(x), ref)
+    # ties: 1 + 2^-8 is midway between 1.0 and 1+2^-7 -> even (1.0); 1 + 3*2^-8 -> 1+2^-6
+    assert o.f32_to_bf16(np.float32(1.00390625)) == 0x3F80
+    assert o.f32_to_bf16(np.float32(1.01171875)) == 0x3F82
+
+
+# ---- amax, scale ----------------------------------------------------------------
+
+def test_amax_brute_force_and_permutation():
+    rng = np.random.default_rng(4)
+    x = (rng.standard_normal((48, 80)) * 3).astype(np.float32)
+    xb = bf16_bits(x)
+    xf = o.bf16_to_f32(xb)
+    assert o.amax(xb)[0] == np.abs(xf).max()
+    assert np.array_equal(o.amax(xb, o.ROWWISE), np.abs(xf).max(axis=1))
+    assert np.array_equal(o.amax(xb, o.COLWISE), np.abs(xf).max(axis=0))
+    perm = rng.permutation(xb.size)
+    assert o.amax(xb.ravel()[perm].reshape(80, 48))[0] == np.abs(xf).max()
+    assert o.amax(xb)[0] in np.abs(xf)                    # it is one of the magnitudes
+    neg = bf16_bits(np.array([[0.5, -7.0, 3.0]]))
+    assert o.amax(neg)[0] == 7.0                          # sign dropped
+    assert o.amax(np.zeros((4, 16), np.uint16))[0] == 0.0
+
+
+def test_scale_closed_forms():
+    s, inv = o.scale(np.float32(4.0), o.E4M3)
+    assert s[0] == 112.0 and inv[0] == np.float32(1.0) / np.float32(112.0)
+    s, inv = o.scale(np.float32(448.0), o.E4M3)
+    assert s[0] == 1.0 and inv[0] == 1.0
+    s, _ = o.scale(np.float32(0.0), o.E4M3)
+    assert s[0] == np.float32(448.0) / np.float32(1e-12) and np.isfinite(s[0])
+    s, inv = o.scale(np.float32(3.5), o.E4M3)
+    assert s[0] == 128.0 and inv[0] == 2.0 ** -7
+    s, inv = o.scale(np.float32(7.0), o.E5M2)
+    assert s[0] == 8192.0 and inv[0] == 2.0 ** -13
+    a = np.array([0.1, 3.3, 1e-20, 5e4], np.float32)
+    s, inv = o.scale(a, o.E5M2)
+    ref = np.float32(57344.0) / np.maximum(a, np.float32(1e-12))
+    assert np.array_equal(s, ref.astype(np.float32)) and np.array_equal(inv, np.float32(1.0) / s)
+
+
+def test_worked_example():
+    rows = {t[0]: t[1:] for t in _lines("scale_cast_example.txt")}
+    xb = bf16_bits([[float(v) for v in rows["x"]]])
+    a, s, inv, q = o.amax_cast(xb, o.TENSORWISE, o.E4M3)
+    assert a[0] == float(rows["amax"][0]) and s[0] == float(rows["scale"][0])
+    assert [int(c) for c in q[0]] == [int(c, 16) for c in rows["codes"]]
+
+
+@pytest.mark.parametrize("fmt,mb,sub", [(o.E4M3, 3, 2.0 ** -10), (o.E5M2, 2, 2.0 ** -17)])
+def test_cast_invariants(fmt, mb, sub):
+    rng = np.random.default_rng(5)
+    x = (rng.standard_normal((64, 96)) * np.exp(rng.uniform(-8, 2, (64, 96)))).astype(np.float32)
+    x[3, 5] = 0.0
+    xb = bf16_bits(x)
+    xf = o.bf16_to_f32(xb).astype(np.float64)
+    a, s, inv, q = o.amax_cast(xb, o.TENSORWISE, fmt)
+    top = 0x7E if fmt == o.E4M3 else 0x7B
+    am = np.unravel_index(np.abs(xf).argmax(), xf.shape)
+    assert (q[am] & 0x7F) == top                           # the amax element lands on FMAX
+    back = o.decode(q, fmt).astype(np.float64) / float(s[0])
+    bound = np.maximum(2.0 ** -(mb + 1) * np.abs(xf), sub / float(s[0])) * (1 + 2.0 ** -20)
+    assert np.all(np.abs(back - xf) <= bound)              # half an ulp of the target format
+    assert np.array_equal(q >> 7, (xb >> 15).astype(np.uint8))   # sign kept, zero included
+    assert q[3, 5] == 0
+    q2, q2t = o.cast(xb, s, o.TENSORWISE, fmt, transposed=True)
+    assert np.array_equal(q2, q) and np.array_equal(q2t, q.T)
+
+
+def test_rowwise_reduces_to_tensorwise():
+    rng = np.random.default_rng(6)
+    x = bf16_bits(rng.standard_normal((24, 64)).astype(np.float32))
+    a, s, inv, q = o.amax_cast(x, o.ROWWISE, o.E4M3)
+    for r in range(x.shape[0]):                            # each row as its own 1 x C tensor
+        ar, sr, _, qr = o.amax_cast(x[r:r + 1], o.TENSORWISE, o.E4M3)
+        assert ar[0] == a[r] and sr[0] == s[r] and np.array_equal(qr[0], q[r])
+    ac, sc, _, qc = o.amax_cast(x, o.COLWISE, o.E4M3)
+    at, st, _, qt = o.amax_cast(np.ascontiguousarray(x.T), o.ROWWISE, o.E4M3)
+    assert np.array_equal(ac, at) and np.array_equal(sc, st) and np.array_equal(qc, qt.T)
+    same = np.repeat(x[:1], 8, axis=0)                     # equal rows: rowwise == tensorwise
+    _, s1, _, q1 = o.amax_cast(same, o.ROWWISE, o.E4M3)
+    _, s0, _, q0 = o.amax_cast(same, o.TENSORWISE, o.E4M3)
+    assert np.all(s1 == s0[0]) and np.array_equal(q1, q0)
+
+
+# ---- GEMM -----------------------------------------------------------------------
+
+def _rand_codes(rng, shape, fmt):
+    fc = np.array(finite_codes(fmt), np.uint8)
+    return fc[rng.integers(0, fc.size, shape)]
+
+
+def _np_ref(layout, A, fa, B, fb):
+    a = o.decode(A, fa).astype(np.float64)
+    b = o.decode(B, fb).astype(np.float64)
+    if layout == o.NT:
+        return a @ b.T, np.abs(a) @ np.abs(b).T
+    if layout == o.NN:
+        return a @ b, np.abs(a) @ np.abs(b)
+    return a.T @ b, np.abs(a).T @ np.abs(b)
+
+
+@pytest.mark.parametrize("layout", [o.NT, o.NN, o.TN])
+@pytest.mark.parametrize("fa,fb", [(o.E4M3, o.E4M3), (o.E5M2, o.E4M3)])
+@pytest.mark.parametrize("M,N,K", [(16, 16, 32), (32, 48, 128), (5, 7, 19)])
+def test_gemm_vs_numpy_fp64(layout, fa, fb, M, N, K):
+    rng = np.random.default_rng(M * 1000 + N * 10 + K + layout)
+    sa = {o.NT: (M, K), o.NN: (M, K), o.TN: (K, M)}[layout]
+    sb = {o.NT: (N, K), o.NN: (K, N), o.TN: (K, N)}[layout]
+    # keep magnitudes moderate so nothing overflows: codes below 0x60
+    A = (_rand_codes(rng, sa, fa) & 0xDF).astype(np.uint8)
+    B = (_rand_codes(rng, sb, fb) & 0xDF).astype(np.uint8)
+    isa, isb = np.float32(0.013), np.float32(1.7)
+    ref, refabs = _np_ref(layout, A, fa, B, fb)
+    s = float(isa) * float(isb)
+    d64, dabs = o.gemm_f64(layout, A, fa, B, fb, isa, isb)
+    assert np.allclose(d64, ref * s, rtol=1e-14, atol=0)
+    assert np.allclose(dabs, refabs * s, rtol=1e-14)
+    got = o.bf16_to_f32(o.gemm(layout, A, fa, B, fb, isa, isb)).astype(np.float64)
+    bound = 2.0 ** -8 * np.abs(ref * s) + 2 * K * 2.0 ** -24 * refabs * s + 1e-30
+    assert np.all(np.abs(got - ref * s) <= bound)
+    ms, ns = np.meshgrid(np.arange(M), np.arange(N), indexing="ij")
+    pts = o.gemm_points(layout, A, fa, B, fb, isa, isb, ms.ravel(), ns.ravel())
+    assert np.array_equal(pts.reshape(M, N), o.gemm(layout, A, fa, B, fb, isa, isb))
+
+
+def test_gemm_layouts_agree_with_explicit_transposes():
+    rng = np.random.default_rng(7)
+    M, N, K = 24, 40, 64
+    A = (_rand_codes(rng, (M, K), o.E5M2) & 0xDF).astype(np.uint8)
+    B = (_rand_codes(rng, (N, K), o.E4M3) & 0xDF).astype(np.uint8)
+    isa, isb = np.float32(0.5), np.float32(0.25)
+    nt = o.gemm(o.NT, A, o.E5M2, B, o.E4M3, isa, isb)
+    nn = o.gemm(o.NN, A, o.E5M2, np.ascontiguousarray(B.T), o.E4M3, isa, isb)
+    tn = o.gemm(o.TN, np.ascontiguousarray(A.T), o.E5M2, np.ascontiguousarray(B.T), o.E4M3, isa, isb)
+    assert np.array_equal(nt, nn) and np.array_equal(nt, tn)
+
+
+def test_gemm_rowwise_scales_and_asymmetry():
+    """Per-row / per-column scales land on the right axis, and A / B are not swapped."""
+    rng = np.random.default_rng(8)
+    M, N, K = 8, 12, 32
+    A = (_rand_codes(rng, (M, K), o.E4M3) & 0x5F).astype(np.uint8)
+    B = (_rand_codes(rng, (N, K), o.E4M3) & 0x5F).astype(np.uint8)
+    isa = (2.0 ** rng.integers(-3, 3, M)).astype(np.float32)
+    isb = (2.0 ** rng.integers(-3, 3, N)).astype(np.float32)
+    got = o.bf16_to_f32(o.gemm(o.NT, A, o.E4M3, B, o.E4M3, isa, isb, o.ROWWISE)).astype(np.float64)
+    one = o.bf16_to_f32(o.gemm(o.NT, A, o.E4M3, B, o.E4M3, np.float32(1), np.float32(1))).astype(np.float64)
+    assert np.array_equal(got, one * isa[:, None].astype(np.float64) * isb[None, :])  # powers of two: exact
+
+
+def exact_case(rng, M, K, N):
+    """Inputs on which the whole linear is exact: values in {0, +-0.5, +-1, +-2} with one
+    +-3.5 planted, so amax = 3.5, scale = 128, and every partial sum is an integer
+    multiple of 2^12 below 2^30."""
+    vals = np.array([0, 0.5, -0.5, 1, -1, 2, -2], np.float32)
+    def draw(shape):
+        t = vals[rng.integers(0, vals.size, shape)]
+        t.flat[rng.integers(0, t.size)] = 3.5 * (1 if rng.integers(0, 2) else -1)
+        return t
+    return draw((M, K)), draw((N, K)), draw((M, N))
+
+
+def test_linear_exact_arithmetic_case():
+    rng = np.random.default_rng(9)
+    M, K, N = 48, 256, 32
+    X, W, dY = exact_case(rng, M, K, N)
+    Y, xq, wq = o.linear_fwd(bf16_bits(X), bf16_bits(W))
+    assert xq.scale[0] == 128.0 and wq.scale[0] == 128.0 and xq.inv_scale[0] == 2.0 ** -7
+    assert np.array_equal(o.decode(xq.q, o.E4M3), X * 128)       # casts are lossless here
+    refY = torch.from_numpy(X.astype(np.float64) @ W.astype(np.float64).T).to(torch.bfloat16)
+    assert np.array_equal(Y, refY.view(torch.uint16).numpy())
+    for gf in (o.E4M3, o.E5M2):
+        dX, dW, dyq = o.linear_bwd(bf16_bits(dY), xq, wq, grad_fmt=gf)
+        refdX = torch.from_numpy(dY.astype(np.float64) @ W.astype(np.float64)).to(torch.bfloat16)
+        refdW = torch.from_numpy(dY.astype(np.float64).T @ X.astype(np.float64)).to(torch.bfloat16)
+        assert np.array_equal(dX, refdX.view(torch.uint16).numpy())
+        assert np.array_equal(dW, refdW.view(torch.uint16).numpy())
+
+
+def test_identity_weight():
+    """W = 3.5 * I: Y is the de-quantised X, element by element."""
+    rng = np.random.default_rng(10)
+    K = 64
+    X = bf16_bits(rng.standard_normal((32, K)).astype(np.float32))
+    W = bf16_bits(np.eye(K, dtype=np.float32) * 3.5)
+    Y, xq, wq = o.linear_fwd(X, W)
+    assert wq.scale[0] == 128.0
+    # dec(W8) = 448 on the diagonal; acc = dec(x8) * 448; times inv_sx * 2^-7
+    expect = (o.decode(xq.q, o.E4M3) * np.float32(448.0)) * (xq.inv_scale[0] * wq.inv_scale[0])
+    assert np.array_equal(Y, torch.from_numpy(expect.astype(np.float32)).to(torch.bfloat16).view(torch.uint16).numpy())
+
+
+@pytest.mark.parametrize("rowwise", [False, True])
+def test_linear_is_composition_of_steps(rowwise):
+    rng = np.random.default_rng(11)
+    M, K, N = 32, 64, 48
+    X = bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    W = bf16_bits((rng.standard_normal((N, K)) * 0.02).astype(np.float32))
+    dY = bf16_bits((rng.standard_normal((M, N)) * 1e-3).astype(np.float32))
+    Y, xq, wq = o.linear_fwd(X, W, rowwise)
+    dX, dW, dyq = o.linear_bwd(dY, xq, wq, rowwise, o.E5M2)
+    g = o.ROWWISE if rowwise else o.TENSORWISE
+    ax, sx, isx, qx = o.amax_cast(X, g, o.E4M3)
+    aw, sw, isw, qw = o.amax_cast(W, g, o.E4M3)
+    ady, sdy, isdy, qdy = o.amax_cast(dY, g, o.E5M2)
+    assert np.array_equal(xq.q, qx) and np.array_equal(wq.q, qw) and np.array_equal(dyq.q, qdy)
+    assert np.array_equal(xq.scale, sx) and np.array_equal(dyq.inv_scale, isdy)
+    assert np.array_equal(Y, o.gemm(o.NT, qx, o.E4M3, qw, o.E4M3, isx, isw, g))
+    if not rowwise:
+        assert np.array_equal(dX, o.gemm(o.NN, qdy, o.E5M2, qw, o.E4M3, isdy, isw))
+        assert np.array_equal(dW, o.gemm(o.TN, qdy, o.E5M2, qx, o.E4M3, isdy, isx))
+    else:
+        _, _, iswc, qwc = o.amax_cast(W, o.COLWISE, o.E4M3)
+        _, _, isxc, qxc = o.amax_cast(X, o.COLWISE, o.E4M3)
+        _, _, isdyc, qdyc = o.amax_cast(dY, o.COLWISE, o.E5M2)
+        assert np.array_equal(dX, o.gemm(o.NN, qdy, o.E5M2, qwc, o.E4M3, isdy, iswc, o.ROWWISE))
+        assert np.array_equal(dW, o.gemm(o.TN, qdyc, o.E5M2, qxc, o.E4M3, isdyc, isxc, o.ROWWISE))
+    # and the result is close to the unquantised product (fp8 has ~2 decimal digits)
+    xf, wf = o.bf16_to_f32(X).astype(np.float64), o.bf16_to_f32(W).astype(np.float64)
+    ref = xf @ wf.T
+    err = np.abs(o.bf16_to_f32(Y) - ref).max() / np.abs(ref).max()
+    assert err < 0.08
