@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the Float8 linear hot path on one MI355X.
+
+A step = forward + backward of the seven Float8 linears of the Llama-3.1-8B
+workload at M = 8192 tokens (casts included), every tensor already resident in
+HBM.  Prints ONE JSON line: whole-step TFLOP/s (6*M*K*N per linear), the
+roofline of the dominant kernel (the fp8 GEMM, timed per launch with HIP
+events on the launch stream), the amax+cast bandwidth, and the CPU oracle
+timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload KEY]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP8_TFLOPS = 5000.0   # MI355X dense fp8 MFMA (published: 5.0 PFLOP/s)
+PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama8b")
+    ap.add_argument("--variant", default=None, help="granularity:gradfmt, e.g. tensorwise:e4m3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-rows", type=int, default=2048)
+    return ap.parse_args()
+
+
+class LinearState:
+    """Device tensors of one linear of the workload."""
+
+    def __init__(self, f8, wl, w, li, rowwise, grad_fmt):
+        import torch
+        lin = w.linears[li]
+        X, W, dY = wl.make_linear_inputs(w, li)
+        self.lin = lin
+        self.X, self.W, self.dY = X.cuda(), W.cuda(), dY.cuda()
+        M, K, N = lin.M, lin.K, lin.N
+        bf = dict(dtype=torch.bfloat16, device="cuda")
+        self.Y = torch.empty((M, N), **bf)
+        self.dX = torch.empty((M, K), **bf)
+        self.dW = torch.empty((N, K), **bf)
+        self.saved = f8.Saved(M, K, N, rowwise)
+        self.desc = f8.linear_desc(M, K, N, rowwise, grad_fmt)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_06511_amd import f8, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    f8.lib()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    w = wl.WORKLOADS[args.workload]
+    gran, gfmt = (args.variant.split(":") if args.variant else w.variants[0])
+    rowwise = gran == "rowwise"
+    grad_fmt = f8.E5M2 if gfmt == "e5m2" else f8.E4M3
+
+    states = [LinearState(f8, wl, w, li, rowwise, grad_fmt) for li in range(len(w.linears))]
+    dmax = max(max(s.lin.M, s.lin.K, s.lin.N) for s in states)
+    ws = f8.new_workspace(dmax, dmax)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for s in states:                       # forward in model order
+            f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws, stream)
+        for s in reversed(states):             # backward in reverse
+            f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws, stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flops_step = sum(s.lin.flops for s in states)
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel legs, HIP events on the launch stream --------------------------------
+    # The same kernels the step launches, called through the same library, one launch per
+    # event pair: the three GEMMs of every linear (dominant kernel) and the amax+cast of
+    # every tensor.
+    def timed(fn, reps):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record(stream)
+            fn()
+            b.record(stream)
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in ev) / reps  # ms
+
+    g = f8.ROWWISE if rowwise else f8.TENSORWISE
+    reps = max(3, min(args.steps, 10))
+    gemm_ms, gemm_flops, gemm_launches = 0.0, 0, 0
+    cast_ms, cast_elems, cast_launch_bytes = 0.0, 0, 0
+    per_linear = []
+    for s in states:
+        M, K, N = s.lin.M, s.lin.K, s.lin.N
+        sv = s.saved
+        w_is_t = sv.w.inv_scale_t if rowwise else sv.w.inv_scale
+        dy_is_t = sv.dy.inv_scale_t if rowwise else sv.dy.inv_scale
+        x_is_t = sv.x.inv_scale_t if rowwise else sv.x.inv_scale
+        gemms = [
+            lambda: f8.gemm(f8.NT, M, N, K, sv.x.q, f8.E4M3, sv.w.q, f8.E4M3, sv.x.inv_scale, sv.w.inv_scale, g, s.Y, stream),
+            lambda: f8.gemm(f8.NT, M, K, N, sv.dy.q, grad_fmt, sv.w.q_t, f8.E4M3, sv.dy.inv_scale, w_is_t, g, s.dX, stream),
+            lambda: f8.gemm(f8.NT, N, K, M, sv.dy.q_t, grad_fmt, sv.x.q_t, f8.E4M3, dy_is_t, x_is_t, g, s.dW, stream),
+        ]
+        lin_gemm_ms = 0.0
+        for fn in gemms:
+            fn()
+            ms = timed(fn, reps)
+            lin_gemm_ms += ms
+            gemm_ms += ms
+            gemm_flops += 2 * M * K * N
+            gemm_launches += 1
+        lin_cast_ms = 0.0
+        if not rowwise:
+            for t, q, fmt in ((s.X, sv.x, f8.E4M3), (s.W, sv.w, f8.E4M3), (s.dY, sv.dy, grad_fmt)):
+                fn = lambda: f8.amax_cast(t, f8.TENSORWISE, fmt, q.amax, q.scale, q.inv_scale, q.q, q.q_t, ws, stream)
+                fn()
+                ms = timed(fn, reps)
+                lin_cast_ms += ms
+                cast_ms += ms
+                cast_elems += t.numel()
+        per_linear.append({"name": s.lin.name, "M": M, "K": K, "N": N,
+                           "gemm_ms": round(lin_gemm_ms, 4), "cast_ms": round(lin_cast_ms, 4),
+                           "gemm_tflops": round(6 * M * K * N / (lin_gemm_ms * 1e-3) / 1e12, 1)})
+
+    gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12
+    roofline = {
+        "kernel": "gemm_nt_kernel (fp8 MFMA 32x32x64)",
+        "bound": "mfma",
+        "achieved": round(gemm_tflops, 1),
+        "peak": PEAK_FP8_TFLOPS,
+        "unit": "TFLOP/s",
+        "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
+        "traffic": None,
+        "launches_per_step": gemm_launches,
+        "avg_launch_ms": round(gemm_ms / gemm_launches, 4),
+        "flops_per_launch": gemm_flops // gemm_launches,
+    }
+    cast = None
+    if cast_ms > 0:
+        # dynamic tensorwise amax+cast: 2 B amax read + 2 B cast re-read + 1 B write per element;
+        # the transposed fp8 copy (+1 B/elem) is a design cost and not counted.
+        gbs5 = 5 * cast_elems / (cast_ms * 1e-3) / 1e9
+        cast = {"bound": "hbm", "achieved": round(gbs5, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs5 / PEAK_HBM_GBS, 4), "bytes_per_elem": 5,
+                "moved_gbs_incl_transposed_copy": round(6 * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
+                "ms_per_step": round(cast_ms, 4)}
+
+    out = {
+        "metric": "Float8 linear fwd+bwd TFLOP/s (% FP8 MFMA peak) + amax/cast HBM GB/s",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "fp8 (e4m3" + ("/e5m2 grads" if grad_fmt == f8.E5M2 else "") + ") x fp8 -> fp32 accumulate -> bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{w.key}: " + ", ".join(f"{l.name}[M={l.M},K={l.K},N={l.N}]" for l in w.linears),
+                   "scaling_granularity": gran, "grad_format": gfmt,
+                   "flops_per_step": flops_step},
+        "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
+        "roofline": roofline,
+        "cast_roofline": cast,
+        "per_linear": per_linear,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_rows, rowwise, grad_fmt)
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, rows, rowwise, grad_fmt):
+    """The oracle as it stands, on the host cores, on a bounded sample: the narrowest linear
+    of the workload restricted to its first `rows` tokens, forward + backward, casts included."""
+    import oracle as o
+    from paper_2410_06511_amd import workloads as wl
+    li = min(range(len(w.linears)), key=lambda i: w.linears[i].K * w.linears[i].N)
+    lin = w.linears[li]
+    rows = min(rows, lin.M)
+    X, W, dY = wl.make_linear_inputs(w, li, M=rows)
+    xb, wb, dyb = wl.bits(X), wl.bits(W), wl.bits(dY)
+    t0 = time.perf_counter()
+    _, xq, wq = o.linear_fwd(xb, wb, rowwise)
+    o.linear_bwd(dyb, xq, wq, rowwise, grad_fmt)
+    dt = time.perf_counter() - t0
+    fl = 6 * rows * lin.K * lin.N
+    return {"value": round(fl / dt / 1e12, 6), "unit": "TFLOP/s", "cores": o.num_threads(), "kind": "oracle",
+            "sample": f"{w.key}/{lin.name} (K={lin.K}, N={lin.N}) first {rows} of {lin.M} tokens, fwd+bwd with casts",
+            "seconds": round(dt, 2)}
+
+
+if __name__ == "__main__":
+    main()

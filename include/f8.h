@@ -68,10 +68,11 @@ typedef enum { F8_TENSORWISE = 0, F8_ROWWISE = 1, F8_COLWISE = 2 } f8_granularit
  *   F8_TN: A[K,M], B[K,N] */
 typedef enum { F8_NT = 0, F8_NN = 1, F8_TN = 2 } f8_layout;
 
-/* Bytes of device workspace that is enough for any call of this library with
- * rows, cols, M, N, K up to 2^20.  The workspace holds partial maxima only; it
+/* Bytes of device workspace that is enough for any call of this library on
+ * tensors of at most max_rows x max_cols (for a linear layer: the largest of
+ * M, K, N in both arguments).  The workspace holds partial maxima only; it
  * needs no initialisation and carries no state between calls. */
-size_t f8_workspace_bytes(void);
+size_t f8_workspace_bytes(int64_t max_rows, int64_t max_cols);
 
 const char* f8_status_string(f8_status s);
 
@@ -80,7 +81,7 @@ const char* f8_status_string(f8_status s);
  *   g = F8_TENSORWISE: amax_out[0];  F8_ROWWISE: amax_out[rows] (max over the
  *   columns of each row);  F8_COLWISE: amax_out[cols] (max over the rows of
  *   each column).  Exact (it is one of the inputs' magnitudes).
- * workspace: f8_workspace_bytes() bytes (unused for F8_ROWWISE; may be NULL then).
+ * workspace: f8_workspace_bytes(rows, cols) bytes (unused for F8_ROWWISE; may be NULL then).
  */
 f8_status f8_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, f8_granularity g,
                   float* amax_out, void* workspace, size_t workspace_bytes, void* stream);
@@ -106,9 +107,20 @@ f8_status f8_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, co
                   int64_t ld_out_t, void* stream);
 
 /*
+ * The rounding of step 3 alone, on fp32 inputs that are already scaled:
+ * out[i] = fp8_rne( clamp( y[i], -FMAX, +FMAX ) ), n >= 0 elements, no
+ * alignment requirement.  use_hw_convert = 0 rounds with integer arithmetic,
+ * 1 with the chip's packed fp32->fp8 conversion instruction; the two must
+ * agree (this entry point exists so that tests can show they do).
+ */
+f8_status f8_encode_f32(const float* y, int64_t n, f8_format fmt, int use_hw_convert, uint8_t* out,
+                        void* stream);
+
+/*
  * Steps 1-3 fused as the hot path uses them (dynamic scaling): writes
  * amax_out, scale_out, inv_scale_out (1, rows or cols entries; all required)
  * and the codes.  Results are identical to f8_amax -> f8_scale -> f8_cast.
+ * workspace: f8_workspace_bytes(rows, cols) bytes (may be NULL for F8_ROWWISE).
  */
 f8_status f8_amax_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld,
                        f8_granularity g, f8_format fmt, float* amax_out, float* scale_out,

@@ -210,6 +210,7 @@ uint8_t f8o_cast_one(uint16_t x_bf16, float scale, int fmt)
 void f8o_cast(const uint16_t* x, int64_t rows, int64_t cols, int64_t ld, const float* scale,
               int gran, int fmt, uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t)
 {
+#pragma omp parallel for schedule(static)   /* rows are independent */
     for (int64_t r = 0; r < rows; ++r)
         for (int64_t c = 0; c < cols; ++c) {
             float s = gran == F8O_TENSORWISE ? scale[0] : (gran == F8O_ROWWISE ? scale[r] : scale[c]);

@@ -1,0 +1,628 @@
+// amax, scale and cast kernels (steps 1-3 of dynamic Float8 scaling) and their
+// C entry points.  All of them are HBM-bandwidth bound: 16-byte loads, one pass
+// per step, partial maxima combined without atomics.
+#include "f8_device.hpp"
+#include "f8_host.hpp"
+
+namespace f8 {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kMaxPartials = 2048;  // blocks of the tensorwise amax kernel (upper bound)
+constexpr int kColChunksMax = 64;   // row chunks of the per-column amax kernel (upper bound)
+
+// ---------------------------------------------------------------------------
+// tensorwise amax: each block writes one partial maximum (a 15-bit magnitude)
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void amax_tensor_partial_kernel(
+    const uint4* __restrict__ x, int64_t rows, int64_t chunks_per_row, int64_t ld_chunks,
+    uint32_t* __restrict__ partial)
+{
+    __shared__ uint32_t red[kWaves];
+    uint32_t acc = 0;
+    if (ld_chunks == chunks_per_row) {
+        const int64_t n = rows * chunks_per_row;
+        const int64_t stride = (int64_t)gridDim.x * kThreads;
+        int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+        // four independent 16-byte loads in flight per thread
+        for (; i + 3 * stride < n; i += 4 * stride) {
+            uint4 a = x[i], b = x[i + stride], c = x[i + 2 * stride], d = x[i + 3 * stride];
+            acc = absmax_acc(acc, a);
+            acc = absmax_acc(acc, b);
+            acc = absmax_acc(acc, c);
+            acc = absmax_acc(acc, d);
+        }
+        for (; i < n; i += stride) acc = absmax_acc(acc, x[i]);
+    } else {
+        for (int64_t r = blockIdx.x; r < rows; r += gridDim.x)
+            for (int64_t c = threadIdx.x; c < chunks_per_row; c += kThreads)
+                acc = absmax_acc(acc, x[r * ld_chunks + c]);
+    }
+    uint32_t m = block_max_u32<kWaves>(pk_collapse(acc), red);
+    if (threadIdx.x == 0) partial[blockIdx.x] = m;
+}
+
+// Every thread of the calling block gets max(partial[0..n)).
+__device__ inline uint32_t reduce_partials(const uint32_t* __restrict__ partial, int n, uint32_t* red)
+{
+    uint32_t m = 0;
+    for (int i = threadIdx.x; i < n; i += kThreads) {
+        uint32_t p = partial[i];
+        m = p > m ? p : m;
+    }
+    return block_max_u32<kWaves>(m, red);
+}
+
+__global__ __launch_bounds__(kThreads) void amax_tensor_final_kernel(
+    const uint32_t* __restrict__ partial, int n, float fm, float* __restrict__ amax_out,
+    float* __restrict__ scale_out, float* __restrict__ inv_out)
+{
+    __shared__ uint32_t red[kWaves];
+    uint32_t m = reduce_partials(partial, n, red);
+    if (threadIdx.x == 0) {
+        float a = mag_to_float(m);
+        amax_out[0] = a;
+        if (scale_out) {
+            float s = scale_from_amax(a, fm);
+            scale_out[0] = s;
+            if (inv_out) inv_out[0] = 1.0f / s;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// per-row amax: one wavefront per row; optionally writes scale and 1/scale too
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void amax_rows_kernel(
+    const uint4* __restrict__ x, int64_t rows, int64_t chunks_per_row, int64_t ld_chunks, float fm,
+    float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t r = (int64_t)blockIdx.x * kWaves + threadIdx.x / kWave;
+    if (r >= rows) return;
+    const uint4* row = x + r * ld_chunks;
+    uint32_t acc = 0;
+    int64_t c = lane;
+    for (; c + 3 * kWave < chunks_per_row; c += 4 * kWave) {
+        uint4 a = row[c], b = row[c + kWave], d = row[c + 2 * kWave], e = row[c + 3 * kWave];
+        acc = absmax_acc(acc, a);
+        acc = absmax_acc(acc, b);
+        acc = absmax_acc(acc, d);
+        acc = absmax_acc(acc, e);
+    }
+    for (; c < chunks_per_row; c += kWave) acc = absmax_acc(acc, row[c]);
+    uint32_t m = wave_max_u32(pk_collapse(acc));
+    if (lane == 0) {
+        float a = mag_to_float(m);
+        amax_out[r] = a;
+        if (scale_out) {
+            float s = scale_from_amax(a, fm);
+            scale_out[r] = s;
+            if (inv_out) inv_out[r] = 1.0f / s;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// per-column amax: grid (column strips of 128, row chunks); partial[chunk][col]
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void amax_cols_partial_kernel(
+    const uint4* __restrict__ x, int64_t rows, int64_t cols, int64_t ld_chunks, int64_t rows_per_chunk,
+    uint32_t* __restrict__ partial /* [gridDim.y][cols] */)
+{
+    __shared__ uint32_t red[16][64 + 1];  // [row lane][word of the strip: 64 words = 128 columns]
+    const int cc = threadIdx.x & 15;      // which 16-byte chunk (8 columns) of the strip
+    const int rl = threadIdx.x >> 4;      // row lane 0..15
+    const int64_t col0 = (int64_t)blockIdx.x * 128 + cc * 8;
+    const int64_t r_begin = (int64_t)blockIdx.y * rows_per_chunk;
+    int64_t r_end = r_begin + rows_per_chunk;
+    if (r_end > rows) r_end = rows;
+    uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;
+    if (col0 < cols) {
+        const uint4* p = x + (col0 >> 3);
+        int64_t r = r_begin + rl;
+        for (; r + 16 < r_end; r += 32) {
+            uint4 v = p[r * ld_chunks], w = p[(r + 16) * ld_chunks];
+            a0 = pkmax(a0, pkmax(v.x & 0x7FFF7FFFu, w.x & 0x7FFF7FFFu));
+            a1 = pkmax(a1, pkmax(v.y & 0x7FFF7FFFu, w.y & 0x7FFF7FFFu));
+            a2 = pkmax(a2, pkmax(v.z & 0x7FFF7FFFu, w.z & 0x7FFF7FFFu));
+            a3 = pkmax(a3, pkmax(v.w & 0x7FFF7FFFu, w.w & 0x7FFF7FFFu));
+        }
+        for (; r < r_end; r += 16) {
+            uint4 v = p[r * ld_chunks];
+            a0 = pkmax(a0, v.x & 0x7FFF7FFFu);
+            a1 = pkmax(a1, v.y & 0x7FFF7FFFu);
+            a2 = pkmax(a2, v.z & 0x7FFF7FFFu);
+            a3 = pkmax(a3, v.w & 0x7FFF7FFFu);
+        }
+    }
+    red[rl][cc * 4 + 0] = a0;
+    red[rl][cc * 4 + 1] = a1;
+    red[rl][cc * 4 + 2] = a2;
+    red[rl][cc * 4 + 3] = a3;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        uint32_t m = red[0][threadIdx.x];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) m = pkmax(m, red[i][threadIdx.x]);
+        const int64_t c = (int64_t)blockIdx.x * 128 + threadIdx.x * 2;
+        if (c < cols) {
+            uint32_t* out = partial + (int64_t)blockIdx.y * cols + c;
+            out[0] = m & 0xFFFFu;
+            out[1] = m >> 16;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void amax_cols_final_kernel(
+    const uint32_t* __restrict__ partial, int nchunks, int64_t cols, float fm,
+    float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out)
+{
+    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (c >= cols) return;
+    uint32_t m = 0;
+    for (int i = 0; i < nchunks; ++i) {
+        uint32_t p = partial[(int64_t)i * cols + c];
+        m = p > m ? p : m;
+    }
+    float a = mag_to_float(m);
+    amax_out[c] = a;
+    if (scale_out) {
+        float s = scale_from_amax(a, fm);
+        scale_out[c] = s;
+        if (inv_out) inv_out[c] = 1.0f / s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// scale
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void scale_kernel(const float* __restrict__ amax, int64_t n,
+                                                          float fm, float* __restrict__ scale_out,
+                                                          float* __restrict__ inv_out)
+{
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= n) return;
+    float s = scale_from_amax(amax[i], fm);
+    scale_out[i] = s;
+    if (inv_out) inv_out[i] = 1.0f / s;
+}
+
+// ---------------------------------------------------------------------------
+// cast, streaming form (no transposed output): tensorwise or per-row scales
+// ---------------------------------------------------------------------------
+// DYN: the scale is derived here from the partial maxima of the amax kernel
+// (tensorwise dynamic scaling); block 0 also publishes amax, scale, 1/scale.
+template <int FMT, int GRAN, bool DYN>
+__global__ __launch_bounds__(kThreads) void cast_stream_kernel(
+    const uint4* __restrict__ x, int64_t rows, int64_t chunks_per_row, int64_t ld_chunks,
+    const float* __restrict__ scale, const uint32_t* __restrict__ partial, int npartial,
+    float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out,
+    uint2* __restrict__ out, int64_t ldo_chunks)
+{
+    __shared__ uint32_t red[kWaves];
+    float s = 0.0f;
+    if constexpr (DYN) {
+        float a = mag_to_float(reduce_partials(partial, npartial, red));
+        s = scale_from_amax(a, Fmt<FMT>::fmax);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            amax_out[0] = a;
+            scale_out[0] = s;
+            inv_out[0] = 1.0f / s;
+        }
+    } else if constexpr (GRAN == F8_TENSORWISE) {
+        s = scale[0];
+    }
+    if constexpr (GRAN == F8_TENSORWISE) {
+        if (ld_chunks == chunks_per_row && ldo_chunks == chunks_per_row) {
+            const int64_t n = rows * chunks_per_row;
+            const int64_t stride = (int64_t)gridDim.x * kThreads;
+            int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+            for (; i + 3 * stride < n; i += 4 * stride) {
+                uint4 a = x[i], b = x[i + stride], c = x[i + 2 * stride], d = x[i + 3 * stride];
+                out[i] = cast8<FMT>(a, s);
+                out[i + stride] = cast8<FMT>(b, s);
+                out[i + 2 * stride] = cast8<FMT>(c, s);
+                out[i + 3 * stride] = cast8<FMT>(d, s);
+            }
+            for (; i < n; i += stride) out[i] = cast8<FMT>(x[i], s);
+            return;
+        }
+    }
+    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        if constexpr (GRAN == F8_ROWWISE) s = scale[r];
+        for (int64_t c = threadIdx.x; c < chunks_per_row; c += kThreads)
+            out[r * ldo_chunks + c] = cast8<FMT>(x[r * ld_chunks + c], s);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// cast, tiled form: 128 x 128 tile per block, writes out and/or out_t.
+// The transposed copy goes through LDS so that both global writes are made of
+// full 128-byte row segments.
+// ---------------------------------------------------------------------------
+constexpr int kTile = 128;
+constexpr int kLdsStride = 33;  // words per LDS tile row (32 data + 1 pad)
+
+// 4x4 byte transpose: in r[j] byte i = element (row j, col i); out c[i] byte j.
+__device__ inline void transpose4x4(const uint32_t r[4], uint32_t c[4])
+{
+    // interleave rows 0/1 and 2/3 bytewise, then gather 16-bit pairs
+    uint32_t t0 = __builtin_amdgcn_perm(r[1], r[0], 0x05010400u);  // r0b0 r1b0 r0b1 r1b1
+    uint32_t t1 = __builtin_amdgcn_perm(r[1], r[0], 0x07030602u);  // r0b2 r1b2 r0b3 r1b3
+    uint32_t t2 = __builtin_amdgcn_perm(r[3], r[2], 0x05010400u);
+    uint32_t t3 = __builtin_amdgcn_perm(r[3], r[2], 0x07030602u);
+    c[0] = (t0 & 0xFFFFu) | (t2 << 16);
+    c[1] = (t0 >> 16) | (t2 & 0xFFFF0000u);
+    c[2] = (t1 & 0xFFFFu) | (t3 << 16);
+    c[3] = (t1 >> 16) | (t3 & 0xFFFF0000u);
+}
+
+template <int FMT, int GRAN, bool DYN, bool OUT, bool OUT_T>
+__global__ __launch_bounds__(kThreads) void cast_tile_kernel(
+    const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ld,
+    const float* __restrict__ scale, const uint32_t* __restrict__ partial, int npartial,
+    float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out,
+    uint8_t* __restrict__ out, int64_t ld_out, uint8_t* __restrict__ out_t, int64_t ld_out_t,
+    int tiles_c)
+{
+    __shared__ uint32_t red[kWaves];
+    __shared__ uint32_t tile[kTile * kLdsStride];
+
+    float s = 0.0f;
+    if constexpr (DYN) {
+        float a = mag_to_float(reduce_partials(partial, npartial, red));
+        s = scale_from_amax(a, Fmt<FMT>::fmax);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            amax_out[0] = a;
+            scale_out[0] = s;
+            inv_out[0] = 1.0f / s;
+        }
+    } else if constexpr (GRAN == F8_TENSORWISE) {
+        s = scale[0];
+    }
+
+    const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kTile;
+    const int64_t c0 = (int64_t)(blockIdx.x % tiles_c) * kTile;
+
+    // phase 1: thread (rr, cc) converts the 16-byte chunk cc of rows rr, rr+16, ...
+    const int cc = threadIdx.x & 15, rr = threadIdx.x >> 4;
+    const int64_t col = c0 + cc * 8;
+    const bool col_ok = col < cols;  // cols is a multiple of 8: the chunk is all in or all out
+    float sc[8];
+    if constexpr (GRAN == F8_COLWISE) {
+        if (col_ok) {
+            const float4 s0 = *reinterpret_cast<const float4*>(scale + col);
+            const float4 s1 = *reinterpret_cast<const float4*>(scale + col + 4);
+            sc[0] = s0.x, sc[1] = s0.y, sc[2] = s0.z, sc[3] = s0.w;
+            sc[4] = s1.x, sc[5] = s1.y, sc[6] = s1.z, sc[7] = s1.w;
+        }
+    }
+    uint4 v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int64_t r = r0 + rr + 16 * i;
+        v[i] = make_uint4(0, 0, 0, 0);
+        if (col_ok && r < rows) v[i] = *reinterpret_cast<const uint4*>(x + r * ld + col);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int rl = rr + 16 * i;
+        const int64_t r = r0 + rl;
+        uint2 q;
+        if constexpr (GRAN == F8_COLWISE) {
+            q = cast8v<FMT>(v[i], sc);
+        } else {
+            if constexpr (GRAN == F8_ROWWISE) s = r < rows ? scale[r] : 0.0f;
+            q = cast8<FMT>(v[i], s);
+        }
+        if constexpr (OUT) {
+            if (col_ok && r < rows) *reinterpret_cast<uint2*>(out + r * ld_out + col) = q;
+        }
+        if constexpr (OUT_T) {
+            tile[rl * kLdsStride + cc * 2] = q.x;
+            tile[rl * kLdsStride + cc * 2 + 1] = q.y;
+        }
+    }
+    if constexpr (OUT_T) {
+        __syncthreads();
+        // phase 2: thread (rb, cb) owns rows 16*rb.. +15 and columns 4*cb.. +3 of the tile and
+        // writes four 16-byte pieces, one per column, into the transposed output.
+        const int rb = threadIdx.x & 7, cb = threadIdx.x >> 3;
+        uint32_t o[4][4];  // o[col i][row group g] = codes of rows 16rb+4g..+3, column 4cb+i
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            uint32_t rws[4], cls[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) rws[j] = tile[(16 * rb + 4 * g + j) * kLdsStride + cb];
+            transpose4x4(rws, cls);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i][g] = cls[i];
+        }
+        const int64_t rbase = r0 + 16 * rb;
+        if (rbase < rows) {  // rows is a multiple of 16: the piece is all in or all out
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t c = c0 + 4 * cb + i;
+                if (c < cols)
+                    *reinterpret_cast<uint4*>(out_t + c * ld_out_t + rbase) =
+                        make_uint4(o[i][0], o[i][1], o[i][2], o[i][3]);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// the rounding step alone, for validation: fp32 -> code (clamp, then round)
+// ---------------------------------------------------------------------------
+template <int FMT, bool HW>
+__global__ __launch_bounds__(kThreads) void encode_kernel(const float* __restrict__ y, int64_t n,
+                                                           uint8_t* __restrict__ out)
+{
+    constexpr float FM = Fmt<FMT>::fmax;
+    const int64_t i = ((int64_t)blockIdx.x * kThreads + threadIdx.x) * 2;
+    if (i >= n) return;
+    float a = y[i], b = (i + 1 < n) ? y[i + 1] : 0.0f;
+    a = a > FM ? FM : a;
+    a = a < -FM ? -FM : a;
+    b = b > FM ? FM : b;
+    b = b < -FM ? -FM : b;
+    uint32_t c;
+    if constexpr (HW)
+        c = encode_hw2<FMT>(a, b);
+    else
+        c = encode_sw<FMT>(a) | (encode_sw<FMT>(b) << 8);
+    out[i] = (uint8_t)(c & 0xFF);
+    if (i + 1 < n) out[i + 1] = (uint8_t)(c >> 8);
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+static int tensor_partial_blocks(int64_t rows, int64_t cols)
+{
+    const int64_t chunks = rows * (cols / 8);
+    int64_t b = (chunks + kThreads * 4 - 1) / (kThreads * 4);  // >= 4 chunks per thread
+    if (b < 1) b = 1;
+    if (b > kMaxPartials) b = kMaxPartials;
+    return (int)b;
+}
+
+static int col_chunks(int64_t rows, int64_t* rows_per_chunk)
+{
+    int64_t n = (rows + 255) / 256;
+    if (n < 1) n = 1;
+    if (n > kColChunksMax) n = kColChunksMax;
+    int64_t rpc = (rows + n - 1) / n;
+    rpc = (rpc + 15) / 16 * 16;
+    if (rpc < 16) rpc = 16;
+    *rows_per_chunk = rpc;
+    return (int)((rows + rpc - 1) / rpc > 0 ? (rows + rpc - 1) / rpc : 1);
+}
+
+size_t workspace_bytes(int64_t max_rows, int64_t max_cols)
+{
+    int64_t d = max_rows > max_cols ? max_rows : max_cols;
+    if (d < 0) d = 0;
+    size_t tensor = (size_t)kMaxPartials * sizeof(uint32_t);
+    size_t colw = (size_t)kColChunksMax * (size_t)d * sizeof(uint32_t);
+    size_t n = tensor > colw ? tensor : colw;
+    return (n + 255) / 256 * 256;
+}
+
+static f8_status check_matrix(const void* p, int64_t rows, int64_t cols, int64_t ld)
+{
+    if (!p) return F8_ERR_NULL;
+    if (rows < 0 || cols < 0 || (rows % 16) || (cols % 16) || (ld % 16) || ld < cols) return F8_ERR_SHAPE;
+    if (!aligned16(p)) return F8_ERR_ALIGN;
+    return F8_OK;
+}
+
+static inline int nscales(int64_t rows, int64_t cols, int g) { return g == F8_TENSORWISE ? 1 : (g == F8_ROWWISE ? rows : cols); }
+
+// amax (+ optionally scale and 1/scale) of a checked matrix.
+static f8_status launch_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int g, float fm,
+                             float* amax_out, float* scale_out, float* inv_out, void* ws,
+                             hipStream_t st)
+{
+    const uint4* xc = static_cast<const uint4*>(x);
+    if (g == F8_TENSORWISE) {
+        int nb = 0;
+        if (rows > 0 && cols > 0) {
+            nb = tensor_partial_blocks(rows, cols);
+            amax_tensor_partial_kernel<<<nb, kThreads, 0, st>>>(xc, rows, cols / 8, ld / 8, (uint32_t*)ws);
+        }
+        amax_tensor_final_kernel<<<1, kThreads, 0, st>>>((const uint32_t*)ws, nb, fm, amax_out, scale_out, inv_out);
+    } else if (g == F8_ROWWISE) {
+        if (rows > 0)
+            amax_rows_kernel<<<(unsigned)((rows + kWaves - 1) / kWaves), kThreads, 0, st>>>(
+                xc, rows, cols / 8, ld / 8, fm, amax_out, scale_out, inv_out);
+    } else {
+        if (cols > 0) {
+            int64_t rpc = 16;
+            int nch = 0;
+            if (rows > 0) {
+                nch = col_chunks(rows, &rpc);
+                dim3 grid((unsigned)((cols + 127) / 128), (unsigned)nch);
+                amax_cols_partial_kernel<<<grid, kThreads, 0, st>>>(xc, rows, cols, ld / 8, rpc, (uint32_t*)ws);
+            }
+            amax_cols_final_kernel<<<(unsigned)((cols + kThreads - 1) / kThreads), kThreads, 0, st>>>(
+                (const uint32_t*)ws, nch, cols, fm, amax_out, scale_out, inv_out);
+        }
+    }
+    return last_launch_status();
+}
+
+template <int FMT, int GRAN, bool DYN>
+static void launch_cast_t(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+                          const uint32_t* partial, int npartial, float* amax_out, float* scale_out,
+                          float* inv_out, uint8_t* out, int64_t ld_out, uint8_t* out_t,
+                          int64_t ld_out_t, hipStream_t st)
+{
+    if (rows == 0 || cols == 0) return;
+    if (!out_t && GRAN != F8_COLWISE) {
+        int64_t chunks = rows * (cols / 8);
+        int64_t nb = (chunks + kThreads * 4 - 1) / (kThreads * 4);
+        if (nb > 8192) nb = 8192;
+        if (GRAN == F8_ROWWISE && nb > rows) nb = rows;
+        cast_stream_kernel<FMT, GRAN, DYN><<<(unsigned)nb, kThreads, 0, st>>>(
+            (const uint4*)x, rows, cols / 8, ld / 8, scale, partial, npartial, amax_out, scale_out,
+            inv_out, (uint2*)out, ld_out / 8);
+        return;
+    }
+    const int tiles_r = (int)((rows + kTile - 1) / kTile), tiles_c = (int)((cols + kTile - 1) / kTile);
+    const unsigned nb = (unsigned)tiles_r * (unsigned)tiles_c;
+#define F8_LAUNCH_TILE(O, T)                                                                       \
+    cast_tile_kernel<FMT, GRAN, DYN, O, T><<<nb, kThreads, 0, st>>>(                               \
+        (const uint16_t*)x, rows, cols, ld, scale, partial, npartial, amax_out, scale_out, inv_out, \
+        out, ld_out, out_t, ld_out_t, tiles_c)
+    if (out && out_t)
+        F8_LAUNCH_TILE(true, true);
+    else if (out_t)
+        F8_LAUNCH_TILE(false, true);
+    else
+        F8_LAUNCH_TILE(true, false);
+#undef F8_LAUNCH_TILE
+}
+
+template <bool DYN>
+static f8_status launch_cast(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+                             int g, int fmt, const uint32_t* partial, int npartial, float* amax_out,
+                             float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,
+                             uint8_t* out_t, int64_t ld_out_t, hipStream_t st)
+{
+#define F8_CAST_CASE(F, G)                                                                        \
+    launch_cast_t<F, G, DYN && (G == F8_TENSORWISE)>(x, rows, cols, ld, scale, partial, npartial, \
+                                                     amax_out, scale_out, inv_out, out, ld_out,   \
+                                                     out_t, ld_out_t, st)
+    if (fmt == F8_E4M3) {
+        if (g == F8_TENSORWISE) F8_CAST_CASE(F8_E4M3, F8_TENSORWISE);
+        else if (g == F8_ROWWISE) F8_CAST_CASE(F8_E4M3, F8_ROWWISE);
+        else F8_CAST_CASE(F8_E4M3, F8_COLWISE);
+    } else {
+        if (g == F8_TENSORWISE) F8_CAST_CASE(F8_E5M2, F8_TENSORWISE);
+        else if (g == F8_ROWWISE) F8_CAST_CASE(F8_E5M2, F8_ROWWISE);
+        else F8_CAST_CASE(F8_E5M2, F8_COLWISE);
+    }
+#undef F8_CAST_CASE
+    return last_launch_status();
+}
+
+static f8_status check_cast_outputs(int64_t rows, int64_t cols, const uint8_t* out, int64_t ld_out,
+                                    const uint8_t* out_t, int64_t ld_out_t)
+{
+    if (!out && !out_t) return F8_ERR_NULL;
+    if (out) {
+        if ((ld_out % 16) || ld_out < cols) return F8_ERR_SHAPE;
+        if (!aligned16(out)) return F8_ERR_ALIGN;
+    }
+    if (out_t) {
+        if ((ld_out_t % 16) || ld_out_t < rows) return F8_ERR_SHAPE;
+        if (!aligned16(out_t)) return F8_ERR_ALIGN;
+    }
+    return F8_OK;
+}
+
+// Dynamic-scaling quantisation of one checked tensor (used by f8_amax_cast and the linear).
+f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g, int fmt,
+                   float* amax_out, float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,
+                   uint8_t* out_t, int64_t ld_out_t, void* ws, hipStream_t st)
+{
+    const float fm = fmax_of(fmt);
+    if (g == F8_TENSORWISE && rows > 0 && cols > 0) {
+        // partial maxima, then the cast derives the scale from them itself: two launches
+        const int nb = tensor_partial_blocks(rows, cols);
+        amax_tensor_partial_kernel<<<nb, kThreads, 0, st>>>((const uint4*)x, rows, cols / 8, ld / 8, (uint32_t*)ws);
+        return launch_cast<true>(x, rows, cols, ld, nullptr, g, fmt, (const uint32_t*)ws, nb, amax_out,
+                                 scale_out, inv_out, out, ld_out, out_t, ld_out_t, st);
+    }
+    f8_status s = launch_amax(x, rows, cols, ld, g, fm, amax_out, scale_out, inv_out, ws, st);
+    if (s != F8_OK) return s;
+    return launch_cast<false>(x, rows, cols, ld, scale_out, g, fmt, nullptr, 0, nullptr, nullptr, nullptr,
+                              out, ld_out, out_t, ld_out_t, st);
+}
+
+}  // namespace f8
+
+using namespace f8;
+
+extern "C" {
+
+size_t f8_workspace_bytes(int64_t max_rows, int64_t max_cols) { return workspace_bytes(max_rows, max_cols); }
+
+f8_status f8_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, f8_granularity g,
+                  float* amax_out, void* workspace, size_t workspace_bytes_, void* stream)
+{
+    if ((int)g < 0 || (int)g > F8_COLWISE) return F8_ERR_ENUM;
+    f8_status s = check_matrix(x_bf16, rows, cols, ld);
+    if (s != F8_OK) return s;
+    if (!amax_out) return F8_ERR_NULL;
+    if (g != F8_ROWWISE && (!workspace || workspace_bytes_ < workspace_bytes(rows, cols))) return F8_ERR_WORKSPACE;
+    return launch_amax(x_bf16, rows, cols, ld, g, 0.0f, amax_out, nullptr, nullptr, workspace, (hipStream_t)stream);
+}
+
+f8_status f8_scale(const float* amax, int64_t n, f8_format fmt, float* scale_out, float* inv_scale_out,
+                   void* stream)
+{
+    if ((int)fmt < 0 || (int)fmt > F8_E5M2) return F8_ERR_ENUM;
+    if (!amax || !scale_out) return F8_ERR_NULL;
+    if (n < 0) return F8_ERR_SHAPE;
+    if (n == 0) return F8_OK;
+    scale_kernel<<<(unsigned)((n + kThreads - 1) / kThreads), kThreads, 0, (hipStream_t)stream>>>(
+        amax, n, fmax_of(fmt), scale_out, inv_scale_out);
+    return last_launch_status();
+}
+
+f8_status f8_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+                  f8_granularity g, f8_format fmt, uint8_t* out, int64_t ld_out, uint8_t* out_t,
+                  int64_t ld_out_t, void* stream)
+{
+    if ((int)g < 0 || (int)g > F8_COLWISE || (int)fmt < 0 || (int)fmt > F8_E5M2) return F8_ERR_ENUM;
+    f8_status s = check_matrix(x_bf16, rows, cols, ld);
+    if (s != F8_OK) return s;
+    if (!scale) return F8_ERR_NULL;
+    if (g == F8_COLWISE && !aligned16(scale)) return F8_ERR_ALIGN;
+    s = check_cast_outputs(rows, cols, out, ld_out, out_t, ld_out_t);
+    if (s != F8_OK) return s;
+    return launch_cast<false>(x_bf16, rows, cols, ld, scale, g, fmt, nullptr, 0, nullptr, nullptr, nullptr,
+                              out, ld_out, out_t, ld_out_t, (hipStream_t)stream);
+}
+
+f8_status f8_amax_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, f8_granularity g,
+                       f8_format fmt, float* amax_out, float* scale_out, float* inv_scale_out,
+                       uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, void* workspace,
+                       size_t workspace_bytes_, void* stream)
+{
+    if ((int)g < 0 || (int)g > F8_COLWISE || (int)fmt < 0 || (int)fmt > F8_E5M2) return F8_ERR_ENUM;
+    f8_status s = check_matrix(x_bf16, rows, cols, ld);
+    if (s != F8_OK) return s;
+    if (!amax_out || !scale_out || !inv_scale_out) return F8_ERR_NULL;
+    if (g == F8_COLWISE && !aligned16(scale_out)) return F8_ERR_ALIGN;
+    s = check_cast_outputs(rows, cols, out, ld_out, out_t, ld_out_t);
+    if (s != F8_OK) return s;
+    if (g != F8_ROWWISE && (!workspace || workspace_bytes_ < workspace_bytes(rows, cols))) return F8_ERR_WORKSPACE;
+    return quantise(x_bf16, rows, cols, ld, g, fmt, amax_out, scale_out, inv_scale_out, out, ld_out, out_t,
+                    ld_out_t, workspace, (hipStream_t)stream);
+}
+
+f8_status f8_encode_f32(const float* y, int64_t n, f8_format fmt, int use_hw_convert, uint8_t* out,
+                        void* stream)
+{
+    if ((int)fmt < 0 || (int)fmt > F8_E5M2) return F8_ERR_ENUM;
+    if (!y || !out) return F8_ERR_NULL;
+    if (n < 0) return F8_ERR_SHAPE;
+    if (n == 0) return F8_OK;
+    const unsigned nb = (unsigned)(((n + 1) / 2 + kThreads - 1) / kThreads);
+    hipStream_t st = (hipStream_t)stream;
+    if (fmt == F8_E4M3) {
+        if (use_hw_convert) encode_kernel<F8_E4M3, true><<<nb, kThreads, 0, st>>>(y, n, out);
+        else encode_kernel<F8_E4M3, false><<<nb, kThreads, 0, st>>>(y, n, out);
+    } else {
+        if (use_hw_convert) encode_kernel<F8_E5M2, true><<<nb, kThreads, 0, st>>>(y, n, out);
+        else encode_kernel<F8_E5M2, false><<<nb, kThreads, 0, st>>>(y, n, out);
+    }
+    return last_launch_status();
+}
+
+}  // extern "C"

@@ -1,0 +1,124 @@
+// The Float8 linear layer: forward and backward as compositions of the
+// quantisation (amax -> scale -> cast) and the fp8 GEMM, all enqueued on one
+// stream with no host synchronisation in between.
+//
+// The GEMM kernels want both operands contraction-contiguous, so every tensor
+// is cast into both orientations while it is being read anyway:
+//   Y  [M,N] = X8  [M,K] . W8  [N,K]^T     contraction K
+//   dX [M,K] = dY8 [M,N] . W8t [K,N]^T     contraction N
+//   dW [N,K] = dY8t[N,M] . X8t [K,M]^T     contraction M
+#include "f8_host.hpp"
+
+namespace f8 {
+
+static f8_status check_desc(const f8_linear_desc* d)
+{
+    if (!d) return F8_ERR_NULL;
+    if (d->granularity != F8_TENSORWISE && d->granularity != F8_ROWWISE) return F8_ERR_ENUM;
+    if (d->grad_format != F8_E4M3 && d->grad_format != F8_E5M2) return F8_ERR_ENUM;
+    if (d->M < 0 || d->K < 0 || d->N < 0 || (d->M % 16) || (d->K % 16) || (d->N % 16)) return F8_ERR_SHAPE;
+    if (d->M >= (1 << 23) || d->K >= (1 << 23) || d->N >= (1 << 23)) return F8_ERR_SHAPE;
+    return F8_OK;
+}
+
+static f8_status check_q(const f8_qtensor* q, bool rowwise)
+{
+    if (!q->q || !q->q_t || !q->amax || !q->scale || !q->inv_scale) return F8_ERR_NULL;
+    if (rowwise && (!q->amax_t || !q->scale_t || !q->inv_scale_t)) return F8_ERR_NULL;
+    if (!aligned16(q->q) || !aligned16(q->q_t)) return F8_ERR_ALIGN;
+    if (rowwise && (!aligned16(q->scale) || !aligned16(q->inv_scale) || !aligned16(q->scale_t) ||
+                    !aligned16(q->inv_scale_t)))
+        return F8_ERR_ALIGN;
+    return F8_OK;
+}
+
+static size_t linear_workspace(const f8_linear_desc* d)
+{
+    int64_t m = d->M > d->K ? d->M : d->K;
+    m = m > d->N ? m : d->N;
+    return workspace_bytes(m, m);
+}
+
+// Quantise T[rows, cols] into q (and q_t).  Tensorwise: one pass writes both orientations.
+// Rowwise: q with per-row scales, q_t with per-column scales (two passes, different codes).
+static f8_status quantise_both(const void* T, int64_t rows, int64_t cols, bool rowwise, int fmt,
+                               const f8_qtensor* q, void* ws, hipStream_t st)
+{
+    if (!rowwise)
+        return quantise(T, rows, cols, cols, F8_TENSORWISE, fmt, q->amax, q->scale, q->inv_scale, q->q, cols,
+                        q->q_t, rows, ws, st);
+    f8_status s = quantise(T, rows, cols, cols, F8_ROWWISE, fmt, q->amax, q->scale, q->inv_scale, q->q, cols,
+                           nullptr, 0, ws, st);
+    if (s != F8_OK) return s;
+    return quantise(T, rows, cols, cols, F8_COLWISE, fmt, q->amax_t, q->scale_t, q->inv_scale_t, nullptr, 0,
+                    q->q_t, rows, ws, st);
+}
+
+}  // namespace f8
+
+using namespace f8;
+
+extern "C" {
+
+const char* f8_status_string(f8_status s)
+{
+    switch (s) {
+        case F8_OK: return "ok";
+        case F8_ERR_NULL: return "a required pointer is NULL";
+        case F8_ERR_SHAPE: return "bad shape: sizes and leading dimensions must be non-negative multiples of 16, ld >= cols";
+        case F8_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
+        case F8_ERR_ENUM: return "an enum argument is out of range";
+        case F8_ERR_WORKSPACE: return "workspace is NULL or too small (see f8_workspace_bytes)";
+        case F8_ERR_LAUNCH: return "kernel launch failed";
+    }
+    return "unknown status";
+}
+
+f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, void* Y, f8_saved* saved,
+                        void* workspace, size_t workspace_bytes_, void* stream)
+{
+    f8_status s = check_desc(d);
+    if (s != F8_OK) return s;
+    if (!X || !W || !Y || !saved) return F8_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return F8_ERR_ALIGN;
+    const bool rw = d->granularity == F8_ROWWISE;
+    if ((s = check_q(&saved->x, rw)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, rw)) != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t M = d->M, K = d->K, N = d->N;
+    if ((s = quantise_both(X, M, K, rw, F8_E4M3, &saved->x, workspace, st)) != F8_OK) return s;
+    if ((s = quantise_both(W, N, K, rw, F8_E4M3, &saved->w, workspace, st)) != F8_OK) return s;
+    return gemm(F8_NT, M, N, K, saved->x.q, F8_E4M3, K, saved->w.q, F8_E4M3, K, saved->x.inv_scale,
+                saved->w.inv_scale, d->granularity, Y, N, st);
+}
+
+f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved, void* dX, void* dW,
+                        void* workspace, size_t workspace_bytes_, void* stream)
+{
+    f8_status s = check_desc(d);
+    if (s != F8_OK) return s;
+    if (!dY || !dX || !dW || !saved) return F8_ERR_NULL;
+    if (!aligned16(dY) || !aligned16(dX) || !aligned16(dW)) return F8_ERR_ALIGN;
+    const bool rw = d->granularity == F8_ROWWISE;
+    if ((s = check_q(&saved->x, rw)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, rw)) != F8_OK) return s;
+    if ((s = check_q(&saved->dy, rw)) != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t M = d->M, K = d->K, N = d->N;
+    const int gf = d->grad_format;
+    if ((s = quantise_both(dY, M, N, rw, gf, &saved->dy, workspace, st)) != F8_OK) return s;
+    // dX = dY8 [M,N] . (W8t [K,N])^T : dY per row m; W per column k = per row of W8t
+    const float* w_is = rw ? saved->w.inv_scale_t : saved->w.inv_scale;
+    if ((s = gemm(F8_NT, M, K, N, saved->dy.q, gf, N, saved->w.q_t, F8_E4M3, N, saved->dy.inv_scale, w_is,
+                  d->granularity, dX, K, st)) != F8_OK)
+        return s;
+    // dW = dY8t [N,M] . (X8t [K,M])^T : dY per column n, X per column k
+    const float* dy_is = rw ? saved->dy.inv_scale_t : saved->dy.inv_scale;
+    const float* x_is = rw ? saved->x.inv_scale_t : saved->x.inv_scale;
+    return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, dy_is, x_is, d->granularity,
+                dW, K, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,184 @@
+"""ctypes binding of libf8.so: the same names as include/f8.h, argument
+marshalling only.  Tensors are torch tensors on the GPU (used for memory and
+streams); every step of the computation runs in the library's kernels.
+
+The library is loaded on first use; if it has not been built this raises
+(there is no fallback path).
+"""
+import ctypes as C
+import os
+
+import torch
+
+E4M3, E5M2 = 0, 1
+TENSORWISE, ROWWISE, COLWISE = 0, 1, 2
+NT, NN, TN = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libf8.so")
+_lib = None
+
+_i64, _int, _p = C.c_int64, C.c_int, C.c_void_p
+
+EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_cast", "f8_encode_f32",
+           "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd"]
+
+
+class F8Error(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"f8 status {code}: {msg}")
+        self.code = code
+
+
+class QTensorStruct(C.Structure):
+    _fields_ = [("q", _p), ("q_t", _p), ("amax", _p), ("scale", _p), ("inv_scale", _p),
+                ("amax_t", _p), ("scale_t", _p), ("inv_scale_t", _p)]
+
+
+class SavedStruct(C.Structure):
+    _fields_ = [("x", QTensorStruct), ("w", QTensorStruct), ("dy", QTensorStruct)]
+
+
+class LinearDesc(C.Structure):
+    _fields_ = [("M", _i64), ("K", _i64), ("N", _i64), ("granularity", C.c_int32), ("grad_format", C.c_int32)]
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2410_06511_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        l.f8_workspace_bytes.restype = C.c_size_t
+        l.f8_workspace_bytes.argtypes = [_i64, _i64]
+        l.f8_status_string.restype = C.c_char_p
+        l.f8_status_string.argtypes = [_int]
+        l.f8_amax.argtypes = [_p, _i64, _i64, _i64, _int, _p, _p, C.c_size_t, _p]
+        l.f8_scale.argtypes = [_p, _i64, _int, _p, _p, _p]
+        l.f8_cast.argtypes = [_p, _i64, _i64, _i64, _p, _int, _int, _p, _i64, _p, _i64, _p]
+        l.f8_encode_f32.argtypes = [_p, _i64, _int, _int, _p, _p]
+        l.f8_amax_cast.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _p, _p, _p, _i64, _p, _i64, _p,
+                                   C.c_size_t, _p]
+        l.f8_gemm.argtypes = [_int, _i64, _i64, _i64, _p, _int, _i64, _p, _int, _i64, _p, _p, _int, _p, _i64, _p]
+        l.f8_linear_fwd.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
+        l.f8_linear_bwd.argtypes = [C.POINTER(LinearDesc), _p, C.POINTER(SavedStruct), _p, _p, _p, C.c_size_t, _p]
+        for name in EXPORTS[2:]:
+            getattr(l, name).restype = _int
+        _lib = l
+    return _lib
+
+
+def _check(code):
+    if code != 0:
+        raise F8Error(code, lib().f8_status_string(code).decode())
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def status_string(code):
+    return lib().f8_status_string(code).decode()
+
+
+def workspace_bytes(max_rows, max_cols):
+    return int(lib().f8_workspace_bytes(max_rows, max_cols))
+
+
+def new_workspace(max_rows, max_cols, device="cuda"):
+    return torch.empty(workspace_bytes(max_rows, max_cols), dtype=torch.uint8, device=device)
+
+
+def _ws(ws):
+    return (None, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+
+
+# ---- the entry points, one to one --------------------------------------------
+
+def amax(x, g, amax_out, workspace=None, stream=None):
+    rows, cols = x.shape
+    wp, wb = _ws(workspace)
+    _check(lib().f8_amax(_ptr(x), rows, cols, x.stride(0), g, _ptr(amax_out), wp, wb, _stream(stream)))
+
+
+def scale(amax_t, fmt, scale_out, inv_scale_out=None, stream=None):
+    _check(lib().f8_scale(_ptr(amax_t), amax_t.numel(), fmt, _ptr(scale_out), _ptr(inv_scale_out), _stream(stream)))
+
+
+def cast(x, scale_t, g, fmt, out=None, out_t=None, stream=None):
+    rows, cols = x.shape
+    _check(lib().f8_cast(_ptr(x), rows, cols, x.stride(0), _ptr(scale_t), g, fmt,
+                         _ptr(out), 0 if out is None else out.stride(0),
+                         _ptr(out_t), 0 if out_t is None else out_t.stride(0), _stream(stream)))
+
+
+def encode_f32(y, fmt, use_hw_convert, out, stream=None):
+    _check(lib().f8_encode_f32(_ptr(y), y.numel(), fmt, int(use_hw_convert), _ptr(out), _stream(stream)))
+
+
+def amax_cast(x, g, fmt, amax_out, scale_out, inv_scale_out, out=None, out_t=None, workspace=None, stream=None):
+    rows, cols = x.shape
+    wp, wb = _ws(workspace)
+    _check(lib().f8_amax_cast(_ptr(x), rows, cols, x.stride(0), g, fmt, _ptr(amax_out), _ptr(scale_out),
+                              _ptr(inv_scale_out), _ptr(out), 0 if out is None else out.stride(0),
+                              _ptr(out_t), 0 if out_t is None else out_t.stride(0), wp, wb, _stream(stream)))
+
+
+def gemm(layout, M, N, K, A, fa, B, fb, inv_scale_a, inv_scale_b, g, D, stream=None):
+    _check(lib().f8_gemm(layout, M, N, K, _ptr(A), fa, A.stride(0), _ptr(B), fb, B.stride(0),
+                         _ptr(inv_scale_a), _ptr(inv_scale_b), g, _ptr(D), D.stride(0), _stream(stream)))
+
+
+class QTensor:
+    """Device buffers of one quantised tensor T[rows, cols] (see f8_qtensor)."""
+
+    def __init__(self, rows, cols, rowwise, device="cuda"):
+        u8 = dict(dtype=torch.uint8, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.q = torch.empty((rows, cols), **u8)
+        self.q_t = torch.empty((cols, rows), **u8)
+        n = rows if rowwise else 1
+        self.amax, self.scale, self.inv_scale = (torch.empty(n, **f32) for _ in range(3))
+        if rowwise:
+            self.amax_t, self.scale_t, self.inv_scale_t = (torch.empty(cols, **f32) for _ in range(3))
+        else:
+            self.amax_t = self.scale_t = self.inv_scale_t = None
+
+    def struct(self):
+        return QTensorStruct(_ptr(self.q), _ptr(self.q_t), _ptr(self.amax), _ptr(self.scale), _ptr(self.inv_scale),
+                             _ptr(self.amax_t), _ptr(self.scale_t), _ptr(self.inv_scale_t))
+
+
+class Saved:
+    """f8_saved for one linear: X [M,K], W [N,K], dY [M,N]."""
+
+    def __init__(self, M, K, N, rowwise=False, device="cuda"):
+        self.x = QTensor(M, K, rowwise, device)
+        self.w = QTensor(N, K, rowwise, device)
+        self.dy = QTensor(M, N, rowwise, device)
+        self._struct = SavedStruct(self.x.struct(), self.w.struct(), self.dy.struct())
+
+    def struct(self):
+        return self._struct
+
+
+def linear_desc(M, K, N, rowwise=False, grad_format=E4M3):
+    return LinearDesc(M, K, N, ROWWISE if rowwise else TENSORWISE, grad_format)
+
+
+def linear_fwd(desc, X, W, Y, saved, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().f8_linear_fwd(C.byref(desc), _ptr(X), _ptr(W), _ptr(Y), C.byref(saved.struct()), wp, wb,
+                               _stream(stream)))
+
+
+def linear_bwd(desc, dY, saved, dX, dW, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().f8_linear_bwd(C.byref(desc), _ptr(dY), C.byref(saved.struct()), _ptr(dX), _ptr(dW), wp, wb,
+                               _stream(stream)))

@@ -1,0 +1,50 @@
+"""Shared pieces of the GPU parity tests: moving seeded inputs to the device and
+comparing GEMM results with the oracle under the stated tolerances."""
+import numpy as np
+import torch
+
+import oracle as o
+
+# Tolerance of the GEMM outputs (stated by the benchmark spec): max-abs error relative to the max-abs
+# of the fp32-accumulating oracle, on identical fp8 inputs and scales.
+GEMM_REL_TOL = 1e-2
+
+
+def dev(t):
+    return t.cuda()
+
+
+def bits(t):
+    """bf16 tensor (any device) -> numpy uint16 bits."""
+    return t.detach().cpu().contiguous().view(torch.uint16).numpy()
+
+
+def u8(t):
+    return t.detach().cpu().contiguous().numpy()
+
+
+def f32(t):
+    return t.detach().cpu().contiguous().numpy()
+
+
+def bf16_from_f32(a):
+    return torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16)
+
+
+def assert_gemm_close(got_bits, ref_bits, what=""):
+    got = o.bf16_to_f32(got_bits).astype(np.float64)
+    ref = o.bf16_to_f32(ref_bits).astype(np.float64)
+    assert np.isfinite(got).all(), what
+    denom = np.abs(ref).max()
+    err = np.abs(got - ref).max()
+    assert err <= GEMM_REL_TOL * max(denom, 1e-30), (what, err, denom)
+    return err / max(denom, 1e-30)
+
+
+def assert_gemm_tight(got_bits, d64, dabs, K, what=""):
+    """Per element against the unrounded fp64 result: one bf16 rounding plus the classic
+    fp32 accumulation bound (any summation order)."""
+    got = o.bf16_to_f32(got_bits).astype(np.float64)
+    bound = 2.0 ** -8 * np.abs(d64) + 2.0 * K * 2.0 ** -24 * dabs + 1e-38
+    bad = np.abs(got - d64) > bound
+    assert not bad.any(), (what, int(bad.sum()), np.argwhere(bad)[:4])

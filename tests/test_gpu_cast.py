@@ -1,0 +1,227 @@
+"""GPU parity of steps 1-3 (amax, scale, cast) against the CPU oracle: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as o
+from paper_2410_06511_amd import f8
+from paper_2410_06511_amd import workloads as wl
+from helpers import bits, u8, f32
+
+pytestmark = pytest.mark.gpu
+
+FMTS = [f8.E4M3, f8.E5M2]
+
+
+def _rand(rows, cols, std=1.0, seed=0):
+    return wl.randn_bf16((rows, cols), std, seed)
+
+
+def _ws(rows, cols):
+    return f8.new_workspace(rows, cols)
+
+
+def run_amax(x, g):
+    rows, cols = x.shape
+    n = 1 if g == f8.TENSORWISE else (rows if g == f8.ROWWISE else cols)
+    out = torch.full((max(n, 1),), -1.0, dtype=torch.float32, device="cuda")
+    f8.amax(x, g, out, _ws(rows, cols))
+    torch.cuda.synchronize()
+    return f32(out)[:n]
+
+
+# sizes: one tile, several tiles with ragged tails (not multiples of 128), wide, tall
+SHAPES = [(16, 16), (128, 128), (144, 272), (400, 1040), (2048, 48), (48, 4096), (1024, 1024)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("g", [f8.TENSORWISE, f8.ROWWISE, f8.COLWISE])
+def test_amax_matches_oracle(shape, g):
+    x = _rand(*shape, std=3.0, seed=shape[0] + shape[1])
+    got = run_amax(x.cuda(), g)
+    assert np.array_equal(got, o.amax(bits(x), g))
+
+
+def test_amax_strided_rows():
+    x = _rand(96, 256, seed=5)
+    xd = x.cuda()
+    view = xd[:, 64:192]                       # ld = 256, cols = 128, 16-byte aligned start
+    for g in (f8.TENSORWISE, f8.ROWWISE, f8.COLWISE):
+        got = run_amax(view, g)
+        assert np.array_equal(got, o.amax(bits(x[:, 64:192]), g))
+
+
+def test_amax_of_zeros_and_empty():
+    z = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    assert run_amax(z, f8.TENSORWISE)[0] == 0.0
+    e = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
+    assert run_amax(e, f8.TENSORWISE)[0] == 0.0
+    assert np.array_equal(run_amax(e, f8.COLWISE), np.zeros(64, np.float32))
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_scale_matches_oracle(fmt):
+    a = np.concatenate([np.abs(np.random.default_rng(0).standard_normal(1000)).astype(np.float32) * 10,
+                        np.array([0.0, 1e-20, 1e-12, 4.0, 3.5, 448.0, 57344.0, 1e30, 2.0 ** -130], np.float32)])
+    ad = torch.from_numpy(a).cuda()
+    s, inv = torch.empty_like(ad), torch.empty_like(ad)
+    f8.scale(ad, fmt, s, inv)
+    torch.cuda.synchronize()
+    rs, rinv = o.scale(a, fmt)
+    assert np.array_equal(f32(s), rs) and np.array_equal(f32(inv), rinv)
+
+
+ALL_FINITE_BF16 = np.array([b for b in range(65536) if (b & 0x7F80) != 0x7F80], np.uint16)
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("hw", [0, 1])
+def test_rounding_step_all_bf16_times_scales(fmt, hw):
+    """The rounding step on fp32 products of every finite bf16 with a sweep of scales, plus
+    every tie point of the format and its fp32 neighbours, for both encoders."""
+    x = o.bf16_to_f32(ALL_FINITE_BF16)
+    ys = []
+    with np.errstate(over="ignore"):
+        for s in [1.0, 112.0, 0.37, 448.0 / 3.3, 1e-3, 3.0e4, 2.0 ** -7, 57344.0 / 0.0123, 7.77e-5, 1.9e7]:
+            ys.append((x * np.float32(s)).astype(np.float32))
+    codes = np.array([c for c in range(128) if np.isfinite(o.decode(np.array([c], np.uint8), fmt)[0])], np.uint8)
+    v = o.decode(codes, fmt).astype(np.float64)
+    ties = ((v[:-1] + v[1:]) / 2).astype(np.float32)
+    ys += [ties, np.nextafter(ties, np.float32(np.inf)), np.nextafter(ties, np.float32(0)), -ties,
+           np.array([0.0, -0.0, np.inf, -np.inf, 1e-45, -1e-45, 3e38], np.float32)]
+    y = np.concatenate(ys)
+    y = y[~np.isnan(y)]
+    yd = torch.from_numpy(y).cuda()
+    out = torch.empty(y.size, dtype=torch.uint8, device="cuda")
+    f8.encode_f32(yd, fmt, hw, out)
+    torch.cuda.synchronize()
+    fm = np.float32(o.fmax(fmt))
+    ref_in = np.clip(y, -fm, fm)
+    # the oracle encoder through torch-free C, on a stride to keep the CPU side short, plus
+    # every tie point in full
+    idx = np.unique(np.concatenate([np.arange(0, y.size, 5), np.arange(y.size - 4 * ties.size - 7, y.size)]))
+    assert np.array_equal(u8(out)[idx], o.encode(ref_in[idx], fmt)), (fmt, hw)
+
+
+def run_cast(x, s, g, fmt, want_out=True, want_t=True):
+    rows, cols = x.shape
+    out = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda") if want_out else None
+    out_t = torch.full((cols, rows), 0xAA, dtype=torch.uint8, device="cuda") if want_t else None
+    f8.cast(x, s, g, fmt, out, out_t)
+    torch.cuda.synchronize()
+    return out, out_t
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("g", [f8.TENSORWISE, f8.ROWWISE, f8.COLWISE])
+def test_cast_matches_oracle(shape, fmt, g):
+    x = _rand(*shape, std=2.0, seed=shape[0] * 7 + shape[1])
+    xb = bits(x)
+    a = o.amax(xb, g)
+    s, _ = o.scale(a, fmt)
+    ref = o.cast(xb, s, g, fmt)
+    sd = torch.from_numpy(s).cuda()
+    for want_out, want_t in [(True, True), (True, False), (False, True)]:
+        out, out_t = run_cast(x.cuda(), sd, g, fmt, want_out, want_t)
+        if want_out:
+            assert np.array_equal(u8(out), ref), (shape, fmt, g, want_out, want_t)
+        if want_t:
+            assert np.array_equal(u8(out_t), ref.T), (shape, fmt, g, want_out, want_t)
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+def test_cast_every_bf16_value(fmt):
+    """All 65536 bf16 patterns (NaN and Inf included) under a sweep of scales."""
+    allb = np.arange(65536, dtype=np.uint32).astype(np.uint16).reshape(256, 256)
+    x = torch.from_numpy(allb.view(np.int16)).view(torch.bfloat16)
+    for s in [1.0, 112.0, 0.0371, 5.1e3, 2.0 ** -9, 448.0 / 2.9e-3]:
+        sd = torch.tensor([s], dtype=torch.float32, device="cuda")
+        out, out_t = run_cast(x.cuda(), sd, f8.TENSORWISE, fmt)
+        ref = o.cast(allb, np.float32(s), o.TENSORWISE, fmt)
+        got = u8(out)
+        nan_in = np.isnan(o.bf16_to_f32(allb))
+        assert np.array_equal(got[~nan_in], ref[~nan_in]), s
+        assert np.all((got[nan_in] & 0x7F) == 0x7F)       # NaN -> a NaN code, sign unspecified
+        assert np.array_equal(u8(out_t), got.T)
+
+
+@pytest.mark.parametrize("shape", [(16, 16), (272, 400), (1024, 2048)])
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("g", [f8.TENSORWISE, f8.ROWWISE, f8.COLWISE])
+def test_amax_cast_matches_oracle(shape, fmt, g):
+    rows, cols = shape
+    x = _rand(rows, cols, std=0.02, seed=rows + cols + g)
+    n = 1 if g == f8.TENSORWISE else (rows if g == f8.ROWWISE else cols)
+    a, s, inv = (torch.full((n,), -1.0, dtype=torch.float32, device="cuda") for _ in range(3))
+    out = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+    out_t = torch.empty((cols, rows), dtype=torch.uint8, device="cuda")
+    f8.amax_cast(x.cuda(), g, fmt, a, s, inv, out, out_t, _ws(rows, cols))
+    torch.cuda.synchronize()
+    ra, rs, rinv, rq = o.amax_cast(bits(x), g, fmt)
+    assert np.array_equal(f32(a), ra) and np.array_equal(f32(s), rs) and np.array_equal(f32(inv), rinv)
+    assert np.array_equal(u8(out), rq) and np.array_equal(u8(out_t), rq.T)
+    # separate steps give the same bits
+    a2 = torch.empty_like(a)
+    f8.amax(x.cuda(), g, a2, _ws(rows, cols))
+    s2, inv2 = torch.empty_like(a), torch.empty_like(a)
+    f8.scale(a2, fmt, s2, inv2)
+    out2 = torch.empty_like(out)
+    f8.cast(x.cuda(), s2, g, fmt, out2, None)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out) and torch.equal(s2, s) and torch.equal(inv2, inv)
+
+
+def test_amax_cast_all_zero_and_outliers():
+    z = torch.zeros((128, 256), dtype=torch.bfloat16, device="cuda")
+    a, s, inv = (torch.empty(1, dtype=torch.float32, device="cuda") for _ in range(3))
+    out = torch.full((128, 256), 0xAA, dtype=torch.uint8, device="cuda")
+    f8.amax_cast(z, f8.TENSORWISE, f8.E4M3, a, s, inv, out, None, _ws(128, 256))
+    torch.cuda.synchronize()
+    rs, rinv = o.scale(np.float32(0), o.E4M3)
+    assert f32(a)[0] == 0 and f32(s)[0] == rs[0] and f32(inv)[0] == rinv[0] and int(out.max()) == 0
+    # the outlier mixture of the 70B workload: bulk lands near the bottom of the e4m3 range
+    x = wl.randn_bf16((512, 1024), 1.0, 3000, outlier_frac=1e-3, outlier_std=100.0)
+    out = torch.empty((512, 1024), dtype=torch.uint8, device="cuda")
+    f8.amax_cast(x.cuda(), f8.TENSORWISE, f8.E4M3, a, s, inv, out, None, _ws(512, 1024))
+    torch.cuda.synchronize()
+    ra, rs, rinv, rq = o.amax_cast(bits(x), o.TENSORWISE, o.E4M3)
+    assert f32(a)[0] == ra[0] and np.array_equal(u8(out), rq)
+    assert (rq & 0x7F).min() == 0 and ((rq & 0x78) == 0).mean() > 0.001   # subnormal codes do occur
+
+
+def test_full_size_llama_tensor_bit_exact():
+    """One full-size activation of the 8B workload (8192 x 4096) in the launch configuration
+    the benchmark uses: every code compared."""
+    w = wl.WORKLOADS["llama8b"]
+    X, _, _ = wl.make_linear_inputs(w, 0)
+    rows, cols = X.shape
+    a, s, inv = (torch.empty(1, dtype=torch.float32, device="cuda") for _ in range(3))
+    out = torch.empty((rows, cols), dtype=torch.uint8, device="cuda")
+    out_t = torch.empty((cols, rows), dtype=torch.uint8, device="cuda")
+    f8.amax_cast(X.cuda(), f8.TENSORWISE, f8.E4M3, a, s, inv, out, out_t, _ws(rows, cols))
+    torch.cuda.synchronize()
+    ra, rs, rinv, rq = o.amax_cast(bits(X), o.TENSORWISE, o.E4M3)
+    assert f32(a)[0] == ra[0] and f32(s)[0] == rs[0] and f32(inv)[0] == rinv[0]
+    assert np.array_equal(u8(out), rq)
+    assert torch.equal(out_t, out.t().contiguous())
+
+
+def test_idempotent_and_guard_bands():
+    """Two calls give identical bits, and nothing is written outside the outputs."""
+    rows, cols = 272, 400
+    x = _rand(rows, cols, seed=9).cuda()
+    pad = 4096
+    buf = torch.full((rows * cols + 2 * pad,), 0x5C, dtype=torch.uint8, device="cuda")
+    buf_t = torch.full((rows * cols + 2 * pad,), 0x5C, dtype=torch.uint8, device="cuda")
+    out = buf[pad:pad + rows * cols].view(rows, cols)
+    out_t = buf_t[pad:pad + rows * cols].view(cols, rows)
+    a, s, inv = (torch.empty(1, dtype=torch.float32, device="cuda") for _ in range(3))
+    ws = _ws(rows, cols)
+    f8.amax_cast(x, f8.TENSORWISE, f8.E5M2, a, s, inv, out, out_t, ws)
+    first = out.clone()
+    f8.amax_cast(x, f8.TENSORWISE, f8.E5M2, a, s, inv, out, out_t, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(first, out) and torch.equal(out_t, out.t().contiguous())
+    for b in (buf, buf_t):
+        assert int((b[:pad] != 0x5C).sum()) == 0 and int((b[-pad:] != 0x5C).sum()) == 0

@@ -1,0 +1,145 @@
+"""GPU parity of the fp8 GEMMs (steps 4-6) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as o
+from paper_2410_06511_amd import f8
+from helpers import bits, u8, assert_gemm_close, assert_gemm_tight
+
+pytestmark = pytest.mark.gpu
+
+
+def finite_codes(fmt):
+    if fmt == o.E4M3:
+        return np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)
+    return np.array([c for c in range(256) if (c & 0x7F) < 0x7C], np.uint8)
+
+
+def rand_codes(rng, shape, fmt, moderate=True):
+    fc = finite_codes(fmt)
+    c = fc[rng.integers(0, fc.size, shape)]
+    if moderate:
+        c = (c & 0xDF).astype(np.uint8)      # clear the top exponent bit: no fp32 overflow in long sums
+    return c
+
+
+def shapes_of(layout, M, N, K):
+    sa = (K, M) if layout == o.TN else (M, K)
+    sb = (N, K) if layout == o.NT else (K, N)
+    return sa, sb
+
+
+def run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, g):
+    Ad, Bd = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    sa = torch.from_numpy(np.atleast_1d(isa).astype(np.float32)).cuda()
+    sb = torch.from_numpy(np.atleast_1d(isb).astype(np.float32)).cuda()
+    D = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    f8.gemm(layout, M, N, K, Ad, fa, Bd, fb, sa, sb, g, D)
+    torch.cuda.synchronize()
+    return bits(D)
+
+
+# (M, N, K): single tile; several 64- and 256-tiles with ragged M and N; K not a multiple of
+# 64 (generic kernel even for NT); K a multiple of 64 but not 256 (tail steps of the fast
+# kernel); a shape that takes the 256x256 tiles with ragged edges.
+SMALL = [(16, 16, 16), (64, 64, 64), (80, 144, 208), (272, 400, 192), (144, 80, 576), (528, 784, 256)]
+
+
+@pytest.mark.parametrize("layout", [o.NT, o.NN, o.TN])
+@pytest.mark.parametrize("fa,fb", [(o.E4M3, o.E4M3), (o.E5M2, o.E4M3), (o.E4M3, o.E5M2), (o.E5M2, o.E5M2)])
+@pytest.mark.parametrize("M,N,K", SMALL)
+def test_gemm_small_full_compare(layout, fa, fb, M, N, K):
+    rng = np.random.default_rng(M + 3 * N + 7 * K + layout)
+    sa, sb = shapes_of(layout, M, N, K)
+    A, B = rand_codes(rng, sa, fa), rand_codes(rng, sb, fb)
+    isa, isb = np.float32(0.0131), np.float32(0.73)
+    got = run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, f8.TENSORWISE)
+    ref = o.gemm(layout, A, fa, B, fb, isa, isb)
+    assert_gemm_close(got, ref, (layout, fa, fb, M, N, K))
+    d64, dabs = o.gemm_f64(layout, A, fa, B, fb, isa, isb)
+    assert_gemm_tight(got, d64, dabs, K, (layout, fa, fb, M, N, K))
+
+
+@pytest.mark.parametrize("layout", [o.NT, o.NN, o.TN])
+@pytest.mark.parametrize("M,N,K", [(80, 144, 208), (272, 400, 256)])
+def test_gemm_rowwise_scales(layout, M, N, K):
+    rng = np.random.default_rng(11 + layout)
+    sa, sb = shapes_of(layout, M, N, K)
+    A, B = rand_codes(rng, sa, o.E4M3), rand_codes(rng, sb, o.E4M3)
+    isa = (rng.uniform(0.5, 2.0, M) * 1e-2).astype(np.float32)
+    isb = (rng.uniform(0.5, 2.0, N) * 1e-1).astype(np.float32)
+    got = run_gemm(layout, M, N, K, A, o.E4M3, B, o.E4M3, isa, isb, f8.ROWWISE)
+    d64, dabs = o.gemm_f64(layout, A, o.E4M3, B, o.E4M3, isa, isb, o.ROWWISE)
+    assert_gemm_tight(got, d64, dabs, K, (layout, M, N, K))
+    assert_gemm_close(got, o.gemm(layout, A, o.E4M3, B, o.E4M3, isa, isb, o.ROWWISE))
+
+
+@pytest.mark.parametrize("layout", [o.NT, o.NN, o.TN])
+@pytest.mark.parametrize("M,N,K", [(272, 400, 320), (512, 768, 1024)])
+def test_gemm_exact_arithmetic_bit_for_bit(layout, M, N, K):
+    """Operands on a grid where every partial sum is exact in fp32 in any order: codes of
+    {0, +-64, +-128, +-256, +-448} and scales 2^-7.  GPU, oracle and the fp64 closed form must
+    agree bit for bit: a tile-indexing and operand-layout test with zero tolerance."""
+    rng = np.random.default_rng(21 + layout)
+    vals = np.array([0, 64, -64, 128, -128, 256, -256, 448, -448], np.float32)
+    grid = o.encode(vals, o.E4M3)
+    sa, sb = shapes_of(layout, M, N, K)
+    A, B = grid[rng.integers(0, 9, sa)], grid[rng.integers(0, 9, sb)]
+    inv = np.float32(2.0 ** -7)
+    got = run_gemm(layout, M, N, K, A, o.E4M3, B, o.E4M3, inv, inv, f8.TENSORWISE)
+    a = o.decode(A, o.E4M3).astype(np.float64)
+    b = o.decode(B, o.E4M3).astype(np.float64)
+    exact = {o.NT: lambda: a @ b.T, o.NN: lambda: a @ b, o.TN: lambda: a.T @ b}[layout]() * 2.0 ** -14
+    closed = torch.from_numpy(exact).to(torch.bfloat16).view(torch.uint16).numpy()
+    assert np.array_equal(got, closed)
+    assert np.array_equal(got, o.gemm(layout, A, o.E4M3, B, o.E4M3, inv, inv))
+
+
+def test_gemm_output_guard_band_and_ldd():
+    """D with a leading dimension larger than N: columns beyond N stay untouched."""
+    rng = np.random.default_rng(5)
+    M, N, K, ldd = 272, 400, 256, 512
+    A, B = rand_codes(rng, (M, K), o.E4M3), rand_codes(rng, (N, K), o.E4M3)
+    Ad, Bd = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    one = torch.ones(1, dtype=torch.float32, device="cuda")
+    buf = torch.full((M + 2, ldd), -7.0, dtype=torch.bfloat16, device="cuda")
+    D = buf[1:M + 1, :N]                        # a view with stride ldd, 16-byte aligned (ldd*2*1 bytes offset)
+    f8.gemm(f8.NT, M, N, K, Ad, o.E4M3, Bd, o.E4M3, one, one, f8.TENSORWISE, D)
+    torch.cuda.synchronize()
+    assert bool((buf[0] == -7).all()) and bool((buf[M + 1] == -7).all()) and bool((buf[1:M + 1, N:] == -7).all())
+    assert_gemm_close(bits(D.contiguous()), o.gemm(o.NT, A, o.E4M3, B, o.E4M3, np.float32(1), np.float32(1)))
+
+
+def sample_points(rng, M, N, tile=256, nrows=64, ncols=64):
+    """>= 64 full rows and columns plus the first / last row and column of every tile boundary."""
+    rows = set(rng.integers(0, M, nrows).tolist())
+    cols = set(rng.integers(0, N, ncols).tolist())
+    for t in range(0, M, tile):
+        rows.update([t, min(t + tile, M) - 1])
+    for t in range(0, N, tile):
+        cols.update([t, min(t + tile, N) - 1])
+    return sorted(rows), sorted(cols)
+
+
+@pytest.mark.parametrize("M,N,K", [(8192, 4096, 4096), (8192, 1024, 4096), (4096, 14336, 8192)])
+def test_gemm_llama_shapes_sampled(M, N, K):
+    """Full-size GEMMs of the 8B workload (forward wq / wk shapes, and a dW-like shape with a
+    long contraction) in the launch configuration the benchmark uses; the oracle computes
+    whole sampled rows and columns one by one."""
+    rng = np.random.default_rng(M + N + K)
+    A = rand_codes(rng, (M, K), o.E4M3)
+    B = rand_codes(rng, (N, K), o.E4M3)
+    isa, isb = np.float32(1 / 97.0), np.float32(1 / 5120.0)
+    got = run_gemm(f8.NT, M, N, K, A, o.E4M3, B, o.E4M3, isa, isb, f8.TENSORWISE)
+    rows, cols = sample_points(rng, M, N, nrows=8, ncols=8)
+    rows, cols = rows[::4], cols[::4]           # keep the CPU side to seconds
+    ms = np.repeat(rows, N)
+    ns = np.tile(np.arange(N), len(rows))
+    ref = o.gemm_points(o.NT, A, o.E4M3, B, o.E4M3, isa, isb, ms, ns)
+    assert_gemm_close(got[ms, ns], ref, "rows")
+    ns = np.repeat(cols, M)
+    ms = np.tile(np.arange(M), len(cols))
+    ref = o.gemm_points(o.NT, A, o.E4M3, B, o.E4M3, isa, isb, ms, ns)
+    assert_gemm_close(got[ms, ns], ref, "cols")
+    assert np.isfinite(o.bf16_to_f32(got)).all()

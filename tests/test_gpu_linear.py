@@ -1,0 +1,147 @@
+"""GPU parity of the whole Float8 linear (forward + backward) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as o
+from paper_2410_06511_amd import f8
+from paper_2410_06511_amd import workloads as wl
+from helpers import bits, u8, f32, assert_gemm_close
+
+pytestmark = pytest.mark.gpu
+
+
+def run_linear(X, W, dY, rowwise=False, grad_fmt=f8.E4M3):
+    M, K = X.shape
+    N = W.shape[0]
+    desc = f8.linear_desc(M, K, N, rowwise, grad_fmt)
+    saved = f8.Saved(M, K, N, rowwise)
+    ws = f8.new_workspace(max(M, K, N), max(M, K, N))
+    Xd, Wd, dYd = X.cuda(), W.cuda(), dY.cuda()
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((M, K), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((N, K), dtype=torch.bfloat16, device="cuda")
+    f8.linear_fwd(desc, Xd, Wd, Y, saved, ws)
+    f8.linear_bwd(desc, dYd, saved, dX, dW, ws)
+    torch.cuda.synchronize()
+    return Y, dX, dW, saved
+
+
+def check_quantised(q, ref, rowwise):
+    """q: f8.QTensor on the GPU, ref: oracle Quantised.  Bit-exact."""
+    assert np.array_equal(f32(q.amax), ref.amax)
+    assert np.array_equal(f32(q.scale), ref.scale)
+    assert np.array_equal(f32(q.inv_scale), ref.inv_scale)
+    assert np.array_equal(u8(q.q), ref.q)
+    if rowwise:
+        assert np.array_equal(f32(q.amax_t), ref.amax_c)
+        assert np.array_equal(f32(q.scale_t), ref.scale_c)
+        assert np.array_equal(f32(q.inv_scale_t), ref.inv_scale_c)
+        assert np.array_equal(u8(q.q_t), ref.q_c.T)
+    else:
+        assert np.array_equal(u8(q.q_t), ref.q.T)
+
+
+@pytest.mark.parametrize("rowwise,grad_fmt", [(False, f8.E4M3), (False, f8.E5M2), (True, f8.E4M3), (True, f8.E5M2)])
+def test_single_linear_config(rowwise, grad_fmt):
+    """The small configuration: X [256,512] ~ N(0,1), W [1024,512] ~ N(0,0.02), dY [256,1024]
+    ~ N(0,1e-3), seed 0.  Scales and codes bit-exact, Y / dX / dW within tolerance, in full."""
+    X, W, dY = wl.make_linear_inputs(wl.WORKLOADS["single"], 0)
+    Y, dX, dW, saved = run_linear(X, W, dY, rowwise, grad_fmt)
+    rY, xq, wq = o.linear_fwd(bits(X), bits(W), rowwise)
+    rdX, rdW, dyq = o.linear_bwd(bits(dY), xq, wq, rowwise, grad_fmt)
+    check_quantised(saved.x, xq, rowwise)
+    check_quantised(saved.w, wq, rowwise)
+    check_quantised(saved.dy, dyq, rowwise)
+    assert_gemm_close(bits(Y), rY, "Y")
+    assert_gemm_close(bits(dX), rdX, "dX")
+    assert_gemm_close(bits(dW), rdW, "dW")
+
+
+def test_ragged_linear():
+    """Sizes that are multiples of 16 only: ragged tiles in every kernel."""
+    g = torch.Generator("cpu")
+    g.manual_seed(77)
+    M, K, N = 272, 336, 208
+    X = wl.randn_bf16((M, K), 1.0, 0, generator=g)
+    W = wl.randn_bf16((N, K), 0.02, 0, generator=g)
+    dY = wl.randn_bf16((M, N), 1e-3, 0, generator=g)
+    for rowwise in (False, True):
+        Y, dX, dW, saved = run_linear(X, W, dY, rowwise, f8.E5M2)
+        rY, xq, wq = o.linear_fwd(bits(X), bits(W), rowwise)
+        rdX, rdW, dyq = o.linear_bwd(bits(dY), xq, wq, rowwise, o.E5M2)
+        check_quantised(saved.x, xq, rowwise)
+        check_quantised(saved.w, wq, rowwise)
+        check_quantised(saved.dy, dyq, rowwise)
+        assert_gemm_close(bits(Y), rY), assert_gemm_close(bits(dX), rdX), assert_gemm_close(bits(dW), rdW)
+
+
+def test_linear_exact_case_bit_for_bit():
+    """Inputs in {0, +-0.5, +-1, +-2} with one +-3.5: amax 3.5, scale 128, lossless casts and
+    exact accumulation, so Y, dX, dW equal the bf16-rounded exact products bit for bit."""
+    rng = np.random.default_rng(31)
+    vals = np.array([0, 0.5, -0.5, 1, -1, 2, -2], np.float32)
+
+    def draw(shape):
+        t = vals[rng.integers(0, vals.size, shape)]
+        t.flat[rng.integers(0, t.size)] = 3.5
+        return t
+    M, K, N = 512, 768, 256
+    X, W, dY = draw((M, K)), draw((N, K)), draw((M, N))
+    tb = lambda a: torch.from_numpy(a).to(torch.bfloat16)
+    for gf in (f8.E4M3, f8.E5M2):
+        Y, dX, dW, saved = run_linear(tb(X), tb(W), tb(dY), False, gf)
+        assert f32(saved.x.scale)[0] == 128.0 and f32(saved.dy.scale)[0] == o.fmax(gf) / 3.5
+        x64, w64, d64 = X.astype(np.float64), W.astype(np.float64), dY.astype(np.float64)
+        ex = lambda a: torch.from_numpy(a).to(torch.bfloat16).view(torch.uint16).numpy()
+        assert np.array_equal(bits(Y), ex(x64 @ w64.T))
+        assert np.array_equal(bits(dX), ex(d64 @ w64))
+        assert np.array_equal(bits(dW), ex(d64.T @ x64))
+
+
+def _sampled_check(name, got, layout, A, fa, B, fb, isa, isb, g, rng, n=6):
+    M, N = got.shape
+    rows = sorted(set(rng.integers(0, M, n).tolist()) | {0, M - 1, 255, 256})
+    cols = sorted(set(rng.integers(0, N, n).tolist()) | {0, N - 1, 255, 256})
+    ms, ns = np.repeat(rows, N), np.tile(np.arange(N), len(rows))
+    assert_gemm_close(got[ms, ns], o.gemm_points(layout, A, fa, B, fb, isa, isb, ms, ns, g), name + " rows")
+    ns, ms = np.repeat(cols, M), np.tile(np.arange(M), len(cols))
+    assert_gemm_close(got[ms, ns], o.gemm_points(layout, A, fa, B, fb, isa, isb, ms, ns, g), name + " cols")
+
+
+@pytest.mark.parametrize("key,li,rowwise,grad_fmt", [
+    ("llama8b", 1, False, f8.E4M3),          # wk: K=4096, N=1024
+    ("llama70b_tp8", 3, False, f8.E5M2),     # wq slice with activation outliers, e5m2 gradients
+    ("llama405b_tp8", 3, True, f8.E4M3),     # wq slice, rowwise
+])
+def test_full_size_linear(key, li, rowwise, grad_fmt):
+    """Full-size linears of the Llama-shaped workloads, M = 8192, exactly as the benchmark
+    launches them.  amax / scales / codes compared in full; Y, dX, dW on sampled whole rows and
+    columns computed by the oracle from the same codes."""
+    w = wl.WORKLOADS[key]
+    X, W, dY = wl.make_linear_inputs(w, li)
+    Y, dX, dW, saved = run_linear(X, W, dY, rowwise, grad_fmt)
+    g = o.ROWWISE if rowwise else o.TENSORWISE
+    rng = np.random.default_rng(li)
+    xb, wb, dyb = bits(X), bits(W), bits(dY)
+    ax, sx, isx, qx = o.amax_cast(xb, g, o.E4M3)
+    aw, sw, isw, qw = o.amax_cast(wb, g, o.E4M3)
+    ady, sdy, isdy, qdy = o.amax_cast(dyb, g, grad_fmt)
+    for q, (a, s, i, c) in ((saved.x, (ax, sx, isx, qx)), (saved.w, (aw, sw, isw, qw)), (saved.dy, (ady, sdy, isdy, qdy))):
+        assert np.array_equal(f32(q.amax), a) and np.array_equal(f32(q.scale), s) and np.array_equal(f32(q.inv_scale), i)
+        assert np.array_equal(u8(q.q), c)
+    _sampled_check("Y", bits(Y), o.NT, qx, o.E4M3, qw, o.E4M3, isx, isw, g, rng)
+    if not rowwise:
+        assert torch.equal(saved.x.q_t, saved.x.q.t().contiguous())
+        assert torch.equal(saved.w.q_t, saved.w.q.t().contiguous())
+        assert torch.equal(saved.dy.q_t, saved.dy.q.t().contiguous())
+        _sampled_check("dX", bits(dX), o.NN, qdy, grad_fmt, qw, o.E4M3, isdy, isw, g, rng)
+        _sampled_check("dW", bits(dW), o.TN, qdy, grad_fmt, qx, o.E4M3, isdy, isx, g, rng)
+    else:
+        _, _, iswc, qwc = o.amax_cast(wb, o.COLWISE, o.E4M3)
+        _, _, isxc, qxc = o.amax_cast(xb, o.COLWISE, o.E4M3)
+        _, _, isdyc, qdyc = o.amax_cast(dyb, o.COLWISE, grad_fmt)
+        assert np.array_equal(u8(saved.w.q_t), qwc.T) and np.array_equal(u8(saved.x.q_t), qxc.T)
+        assert np.array_equal(u8(saved.dy.q_t), qdyc.T)
+        _sampled_check("dX", bits(dX), o.NN, qdy, grad_fmt, qwc, o.E4M3, isdy, iswc, g, rng)
+        _sampled_check("dW", bits(dW), o.TN, qdyc, grad_fmt, qxc, o.E4M3, isdyc, isxc, g, rng)
