@@ -54,9 +54,20 @@ def test_amax_strided_rows():
 def test_amax_of_zeros_and_empty():
     z = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     assert run_amax(z, f8.TENSORWISE)[0] == 0.0
-    e = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
-    assert run_amax(e, f8.TENSORWISE)[0] == 0.0
-    assert np.array_equal(run_amax(e, f8.COLWISE), np.zeros(64, np.float32))
+    # zero rows with a valid pointer (torch reports a NULL data_ptr for empty tensors, so the
+    # raw entry point is called with the address of a real buffer)
+    base = torch.zeros((16, 64), dtype=torch.bfloat16, device="cuda")
+    ws = _ws(16, 64)
+    st = torch.cuda.current_stream().cuda_stream
+    for g, n in ((f8.TENSORWISE, 1), (f8.COLWISE, 64)):
+        out = torch.full((n,), -1.0, dtype=torch.float32, device="cuda")
+        rc = f8.lib().f8_amax(base.data_ptr(), 0, 64, 64, g, out.data_ptr(), ws.data_ptr(), ws.numel(), st)
+        torch.cuda.synchronize()
+        assert rc == 0 and np.array_equal(f32(out), np.zeros(n, np.float32))
+    out = torch.full((4,), -1.0, dtype=torch.float32, device="cuda")
+    rc = f8.lib().f8_amax(base.data_ptr(), 0, 64, 64, f8.ROWWISE, out.data_ptr(), None, 0, st)
+    torch.cuda.synchronize()
+    assert rc == 0 and np.array_equal(f32(out), np.full(4, -1.0, np.float32))   # nothing to write
 
 
 @pytest.mark.parametrize("fmt", FMTS)
