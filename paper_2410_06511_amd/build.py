@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libf8.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU ops
     "-ffp-contract=off",                                            # the cast's multiply must stay one rounding
     "-Wall", "-Wno-unused-function", "-Wno-unknown-attributes",

@@ -3,10 +3,11 @@
 //
 // Two kernels:
 //   gemm_nt_kernel      the fast path.  Both operands contraction-contiguous
-//                       ("NT"), K a multiple of 64.  Global -> LDS direct
-//                       loads (no VGPR staging), a ring of four LDS stages,
-//                       XOR-swizzled 64-byte rows, v_mfma_f32_32x32x64_f8f6f4,
-//                       scales folded into the fp32 epilogue, bf16 stores.
+//                       ("NT"), K a multiple of 256.  Persistent workgroups,
+//                       global -> LDS direct loads (no VGPR staging), two LDS
+//                       stages of XOR-swizzled 128-byte rows,
+//                       v_mfma_f32_32x32x64_f8f6f4, scales folded into the
+//                       fp32 epilogue, bf16 stores staged through LDS.
 //   gemm_generic_kernel any layout, any multiple-of-16 shape; 64x64 tiles and
 //                       the 16x16x32 fp8 MFMA.  The fallback.
 //
@@ -15,11 +16,20 @@
 // hold four consecutive n for one m, so the bf16 results leave as 8-byte pieces
 // of a row of D.
 #include <type_traits>
+#include <utility>
 
 #include "f8_device.hpp"
 #include "f8_host.hpp"
 
 namespace f8 {
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), unrolled at compile time
+template <int N, class F>
+__device__ inline void static_for(F&& f)
+{
+    [&]<int... Is>(std::integer_sequence<int, Is...>) { (f(std::integral_constant<int, Is>{}), ...); }
+    (std::make_integer_sequence<int, N>{});
+}
 
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -74,24 +84,28 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
 // ---------------------------------------------------------------------------
 // fast NT kernel
 // ---------------------------------------------------------------------------
-// Block tile BM x BN, K step 64 bytes, a ring of four LDS stages filled by
-// direct global->LDS loads three steps ahead; v_mfma_f32_32x32x64_f8f6f4; the
-// fragments of step t+1 are read from LDS into a second register set while the
-// MFMAs of step t run, so neither the barrier nor LDS latency sits on the MFMA
-// critical path.
-constexpr int kBK = 64;     // bytes of K per LDS stage = one 32x32x64 MFMA step
-constexpr int kStages = 4;
+// Persistent workgroups (one or two per CU) walk over BM x BN output tiles.  K
+// advances in steps of 128 bytes = one LDS stage of 128-byte rows (a full cache
+// line per row and load), two stages, filled by direct global->LDS loads.  Each
+// stage feeds two v_mfma_f32_32x32x64_f8f6f4 half-steps.  The load stream runs
+// two K steps ahead of the MFMAs and does not stop at tile boundaries, so the
+// next tile's first stages arrive while the current tile's epilogue runs.
+// Fragments of the next half-step are read from LDS into a second register set
+// while the MFMAs of the current one run; there is one barrier per K step.
+constexpr int kBK = 128;  // bytes of K per LDS stage
 
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 b2 __attribute__((ext_vector_type(2)));
 
-// XOR swizzle of the four 16-byte chunks of a 64-byte LDS row: lanes that read
-// the same logical chunk of consecutive rows spread over all bank groups, for
-// any aligned group of 8 lanes (128-byte bank window) and of 16 lanes (256-byte).
-__device__ inline int swz(int row) { return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1); }
+// XOR swizzle of the eight 16-byte chunks of a 128-byte LDS row: the lanes that read the
+// same logical chunk of consecutive rows spread over all bank groups, for any aligned 8
+// rows (128-byte bank window) and any aligned 16 rows (256-byte window).
+__device__ inline int swz(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2); }
 
-// s_waitcnt immediate for "vmcnt <= n", other counters unconstrained (gfx9 encoding:
-// vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14, expcnt 6:4, lgkmcnt 11:8).
-constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0070 | 0x0F00; }
+// s_waitcnt immediate (gfx9 encoding: vmcnt[3:0] bits 3:0, vmcnt[5:4] bits 15:14, expcnt 6:4,
+// lgkmcnt 11:8): wait for all vector-memory operations and all LDS operations.
+constexpr int kWaitAllVmLgkm = 0x0070;
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
@@ -103,114 +117,140 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
     constexpr int A_BYTES = BM * kBK, STAGE = (BM + BN) * kBK;
-    constexpr int A_LOADS = BM / 16 / NW, B_LOADS = BN / 16 / NW;  // 1 KB (16 rows) per wave load
-    constexpr int LOADS = A_LOADS + B_LOADS;
-    static_assert(BM % (16 * NW) == 0 && BN % (16 * NW) == 0, "tile rows must split over the waves");
-    static_assert(LOADS * (kStages - 1) < 64, "vmcnt is a 6-bit counter");
+    constexpr int A_LOADS = BM / 8 / NW, B_LOADS = BN / 8 / NW;  // 1 KB (8 rows) per wave load
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
+    static_assert(NW == 4, "four waves");
+    constexpr int EP_STRIDE = 64 * 2 + 16;    // bytes per staged epilogue row: 64 bf16 + padding
+    static_assert(TN % 2 == 0, "the epilogue stages two MFMA tiles side by side");
 
     // One array per stage: the compiler then knows that a load into one stage does not alias
-    // reads of another and does not serialise them.
+    // LDS reads of the other and does not serialise them.
     __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE];
     __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE];
-    __shared__ __attribute__((aligned(1024))) uint8_t st2[STAGE];
-    __shared__ __attribute__((aligned(1024))) uint8_t st3[STAGE];
-
-    int tm, tn;
-    tile_coords(blockIdx.x, tiles_m, tiles_n, &tm, &tn);
-    const int m0 = tm * BM, n0 = tn * BN;
+    __shared__ __attribute__((aligned(16))) uint8_t epb[NW * 32 * EP_STRIDE];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-
-    // ---- global -> LDS addressing: wave w fills rows [w*R, (w+1)*R) of each operand tile in
-    // 16-row (1 KB) pieces; lane i lands at row i/4, physical chunk i%4 of its piece.
-    uint32_t a_off[A_LOADS], b_off[B_LOADS];
-#pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) {
-        const int row = wave * (BM / NW) + 16 * j + (lane >> 2);
-        const int c = (lane & 3) ^ swz(row);
-        int gr = m0 + row;
-        gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
-        a_off[j] = (uint32_t)((int64_t)(gr - m0) * lda + 16 * c);
-    }
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j) {
-        const int row = wave * (BN / NW) + 16 * j + (lane >> 2);
-        const int c = (lane & 3) ^ swz(row);
-        int gr = n0 + row;
-        gr = gr < N ? gr : N - 1;
-        b_off[j] = (uint32_t)((int64_t)(gr - n0) * ldb + 16 * c);
-    }
-    const uint8_t* a_base = A + (int64_t)m0 * lda;
-    const uint8_t* b_base = B + (int64_t)n0 * ldb;
+    const int total_tiles = tiles_m * tiles_n;
     const int KT = K / kBK;
 
+    using std::integral_constant;
     auto stage_ptr = [&](auto S) -> uint8_t* {
         if constexpr (decltype(S)::value == 0) return st0;
-        else if constexpr (decltype(S)::value == 1) return st1;
-        else if constexpr (decltype(S)::value == 2) return st2;
-        else return st3;
+        else return st1;
     };
 
-    // Every step issues exactly LOADS loads (past the end of K the last step is loaded again
-    // into a stage nobody reads), so the vmcnt arithmetic below is the same for every step.
-    auto issue_loads = [&](int kt, auto S) {
-        kt = kt < KT ? kt : KT - 1;
-        const uint8_t* ap = a_base + (int64_t)kt * kBK;
-        const uint8_t* bp = b_base + (int64_t)kt * kBK;
-        uint8_t* la = stage_ptr(S) + wave * (BM / NW) * kBK;
-        uint8_t* lb = stage_ptr(S) + A_BYTES + wave * (BN / NW) * kBK;
+    // ---- load stream: (tile, K step) of the next stage to fetch -------------------------
+    // wave w fills rows [w*R, (w+1)*R) of each operand tile in 8-row (1 KB) pieces; lane i
+    // lands at row i/8, physical chunk i%8 of its piece.
+    int ld_tile = blockIdx.x;
+    uint32_t a_off[A_LOADS], b_off[B_LOADS];
+    const uint8_t* a_base = A;
+    const uint8_t* b_base = B;
+    auto load_context = [&](int tile) {
+        int tm, tn;
+        tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
+#ifdef F8_EXP_SAME_TILE
+        tm = tn = 0;  // perf probe only: every tile loads the same rows (all loads hit in L2)
+#endif
+        const int m0 = tm * BM, n0 = tn * BN;
 #pragma unroll
-        for (int j = 0; j < A_LOADS; ++j)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(ap + a_off[j]),
-                (__attribute__((address_space(3))) void*)(la + j * 1024), 16, 0, 0);
+        for (int j = 0; j < A_LOADS; ++j) {
+            const int row = wave * (BM / NW) + 8 * j + (lane >> 3);
+            const int c = (lane & 7) ^ swz(row);
+            int gr = m0 + row;
+            gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
+            a_off[j] = (uint32_t)((int64_t)(gr - m0) * lda + 16 * c);
+        }
 #pragma unroll
-        for (int j = 0; j < B_LOADS; ++j)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(bp + b_off[j]),
-                (__attribute__((address_space(3))) void*)(lb + j * 1024), 16, 0, 0);
+        for (int j = 0; j < B_LOADS; ++j) {
+            const int row = wave * (BN / NW) + 8 * j + (lane >> 3);
+            const int c = (lane & 7) ^ swz(row);
+            int gr = n0 + row;
+            gr = gr < N ? gr : N - 1;
+            b_off[j] = (uint32_t)((int64_t)(gr - n0) * ldb + 16 * c);
+        }
+        a_base = A + (int64_t)m0 * lda;
+        b_base = B + (int64_t)n0 * ldb;
+    };
+    // Load number `idx` (0 .. LOADS-1: first the A pieces, then the B pieces) of K step `kt` of
+    // the stream's current tile, into stage S.  Written as asm: 32-bit lane offset next to a
+    // scalar base, LDS target in M0.  The compiler therefore does not see these as LDS writes;
+    // ordering against the LDS reads is by the barriers and explicit waits of kstep.
+    bool ld_valid = ld_tile < total_tiles;
+    auto issue_one = [&](int kt, auto S, auto IDX) {
+        constexpr int idx = decltype(IDX)::value;
+        if constexpr (idx < A_LOADS) {
+            const uint8_t* gp = a_base + (int64_t)kt * kBK;
+            uint8_t* lp = stage_ptr(S) + wave * (BM / NW) * kBK + idx * 1024;
+            const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
+            const uint32_t o = a_off[idx];
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
+        } else {
+            constexpr int j = idx - A_LOADS;
+            const uint8_t* gp = b_base + (int64_t)kt * kBK;
+            uint8_t* lp = stage_ptr(S) + A_BYTES + wave * (BN / NW) * kBK + j * 1024;
+            const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
+            const uint32_t o = b_off[j];
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
+        }
+    };
+    auto issue_all = [&](int kt, auto S) {
+        if (!ld_valid) return;
+        static_for<A_LOADS + B_LOADS>([&](auto L) { issue_one(kt, S, L); });
+    };
+    // move the load stream to this workgroup's next tile
+    auto next_load_tile = [&]() {
+        ld_tile += gridDim.x;
+        ld_valid = ld_tile < total_tiles;
+        if (ld_valid) load_context(ld_tile);
     };
 
-    // ---- LDS -> register addressing: lane reads row (l % 32) of a 32-row MFMA tile, logical
-    // chunks 2g and 2g+1 (g = l / 32): 32 consecutive K bytes.
+    // ---- LDS -> register addressing: lane reads row (l % 32) of a 32-row MFMA tile; in
+    // half-step h the logical chunks 4h + 2g and 4h + 2g + 1 (g = l / 32): 32 K bytes.
     const int fr = lane & 31, fg = lane >> 5;
     const int pc0 = (2 * fg) ^ swz(fr);
-    const int a_rd = (wm * WM + fr) * kBK + 16 * pc0;  // + 32-row tile * 2048
+    const int a_rd = (wm * WM + fr) * kBK + 16 * pc0;  // + 32-row tile * 4096
     const int b_rd = A_BYTES + (wn * WN + fr) * kBK + 16 * pc0;
-    const int rd_flip = ((pc0 ^ 1) - pc0) * 16;        // to the second chunk
+    const int flip1 = ((pc0 ^ 1) - pc0) * 16;          // to the second chunk of the pair
+    const int fliph = ((pc0 ^ 4) - pc0) * 16;          // to the same chunk of half-step 1
 
     struct Frags {
         v8i a[TM];
         v8i b[TN];
     };
-    auto read_frags = [&](Frags& f, auto S) {
-        const uint8_t* sa = stage_ptr(S) + a_rd;
-        const uint8_t* sb = stage_ptr(S) + b_rd;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int4 lo = *reinterpret_cast<const int4*>(sa + i * 32 * kBK);
-            const int4 hi = *reinterpret_cast<const int4*>(sa + i * 32 * kBK + rd_flip);
-            f.a[i] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    // fragment number `idx` of a half-step: 0 .. TM-1 are the A fragments, TM .. TM+TN-1 the B ones
+    auto read_frag = [&](Frags& f, auto S, auto H, auto IDX) {
+        constexpr int idx = decltype(IDX)::value;
+        const int hoff = decltype(H)::value ? fliph : 0;
+        if constexpr (idx < TM) {
+            const uint8_t* sa = stage_ptr(S) + a_rd + hoff + idx * 32 * kBK;
+            const int4 lo = *reinterpret_cast<const int4*>(sa);
+            const int4 hi = *reinterpret_cast<const int4*>(sa + flip1);
+            f.a[idx] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        } else {
+            const uint8_t* sb = stage_ptr(S) + b_rd + hoff + (idx - TM) * 32 * kBK;
+            const int4 lo = *reinterpret_cast<const int4*>(sb);
+            const int4 hi = *reinterpret_cast<const int4*>(sb + flip1);
+            f.b[idx - TM] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
         }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int4 lo = *reinterpret_cast<const int4*>(sb + j * 32 * kBK);
-            const int4 hi = *reinterpret_cast<const int4*>(sb + j * 32 * kBK + rd_flip);
-            f.b[j] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-        }
+    };
+    auto read_frags = [&](Frags& f, auto S, auto H) {
+        static_for<TM + TN>([&](auto F) { read_frag(f, S, H, F); });
     };
 
     v16f acc[TM][TN];
+    auto zero_acc = [&]() {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    };
 
-    // MFMAs number lo..hi-1 of a step (numbered i * TN + j)
+    // MFMAs number lo..hi-1 of a half-step (numbered i * TN + j)
     auto mfmas = [&](const Frags& f, auto LO, auto HI) {
 #pragma unroll
         for (int q = decltype(LO)::value; q < decltype(HI)::value; ++q) {
@@ -219,82 +259,185 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                                                                           0, 0);
         }
     };
-
-    // wait until at most `keep` of this wave's loads are in flight and all of its LDS reads
-    // have returned, then meet the other waves
-    auto sync_step = [&](auto KEEP) {
-        __builtin_amdgcn_s_waitcnt(vmcnt_imm(decltype(KEEP)::value) & 0xF0FF);  // lgkmcnt(0) too
-        __builtin_amdgcn_s_barrier();
-    };
-    using std::integral_constant;
-    constexpr int L = LOADS;
     constexpr int NMFMA = TM * TN;
-    constexpr int HEAD = NMFMA >= 8 ? 4 : 1;  // MFMAs queued before the barrier, to cover its wait
+    using I0 = integral_constant<int, 0>;
+    using I1 = integral_constant<int, 1>;
 
-    // One K step.  On entry `cur` holds the fragments of step t (stage S).  A few MFMAs are
-    // queued first so that the matrix pipe has work while the wave sits at the barrier; after
-    // the barrier step t+1 is complete in stage S+1 for every wave, stage S is free for step
-    // t+4, and the LDS reads of step t+1 and the new loads are interleaved with the remaining
-    // MFMAs of step t.
-    auto step = [&](int t, auto S, Frags& cur, Frags& next) {
-        constexpr int s = decltype(S)::value;
-        mfmas(cur, integral_constant<int, 0>{}, integral_constant<int, HEAD>{});
-        __builtin_amdgcn_sched_barrier(0);
-        sync_step(integral_constant<int, (kStages - 2) * L>{});
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(next, integral_constant<int, (s + 1) % kStages>{});
-        issue_loads(t + kStages, S);
-        mfmas(cur, integral_constant<int, HEAD>{}, integral_constant<int, NMFMA>{});
-        // schedule shape for the compiler: after each MFMA up to two LDS reads and one load
+    // ---- epilogue of one tile.  Of each 32x32 MFMA tile, lane l holds m = l % 32 and
+    // n = 8 * (r / 4) + 4 * (l / 32) + r % 4 for accumulator register r.  Each wave turns a
+    // 32-row, 64-column piece of its tile at a time into bf16, parks it in its private piece
+    // of LDS and writes it out as 16-byte row pieces: every global store instruction then
+    // covers whole 128-byte row segments.
+    auto epilogue = [&](int tile) {
+        int tm, tn;
+        tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
+        const int m0 = tm * BM + wm * WM, n0 = tn * BN + wn * WN;  // of this wave's tile
+        uint8_t* ep = epb + wave * (32 * EP_STRIDE);
+        float s_tensor = 0.f;
+        if constexpr (GRAN == F8_TENSORWISE) s_tensor = isa[0] * isb[0];
 #pragma unroll
-        for (int q = 0; q < NMFMA - HEAD; ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // two DS reads
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // one VMEM read
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    };
-
-    // prologue: steps 0..3 in flight, step 0 into registers
-    issue_loads(0, integral_constant<int, 0>{});
-    issue_loads(1, integral_constant<int, 1>{});
-    issue_loads(2, integral_constant<int, 2>{});
-    issue_loads(3, integral_constant<int, 3>{});
-    Frags f0, f1;
-    sync_step(integral_constant<int, (kStages - 1) * L>{});
-    read_frags(f0, integral_constant<int, 0>{});
-
-    const int KT4 = KT & ~3;
-    for (int t = 0; t < KT4; t += 4) {
-        step(t, integral_constant<int, 0>{}, f0, f1);
-        step(t + 1, integral_constant<int, 1>{}, f1, f0);
-        step(t + 2, integral_constant<int, 2>{}, f0, f1);
-        step(t + 3, integral_constant<int, 3>{}, f1, f0);
-    }
-    if (KT4 < KT) step(KT4, integral_constant<int, 0>{}, f0, f1);
-    if (KT4 + 1 < KT) step(KT4 + 1, integral_constant<int, 1>{}, f1, f0);
-    if (KT4 + 2 < KT) step(KT4 + 2, integral_constant<int, 2>{}, f0, f1);
-    // no load may still be writing LDS when the block ends
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-
-    // ---- epilogue: of each 32x32 tile, lane l holds m = l % 32 and
-    // n = 8 * (r / 4) + 4 * (l / 32) + r % 4 for accumulator register r
-    float s_tensor = 0.f;
-    if constexpr (GRAN == F8_TENSORWISE) s_tensor = isa[0] * isb[0];
+        for (int i = 0; i < TM; ++i) {
+            const int m_lane = m0 + 32 * i + fr;
+            float sa = 0.f;
+            if constexpr (GRAN != F8_TENSORWISE) sa = isa[m_lane < M ? m_lane : M - 1];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + wm * WM + 32 * i + fr;
-        if (m >= M) continue;
+            for (int jp = 0; jp < TN; jp += 2) {  // two MFMA tiles = 64 columns per pass
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = jp + jj;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = n0 + wn * WN + 32 * j + 8 * q + 4 * fg;
-                const v4f v = v4f{acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                if (n < N) store4<GRAN>(D, ldd, m, n, v, s_tensor, isa, isb);
+                    for (int q = 0; q < 4; ++q) {
+                        const int nl = 32 * jj + 8 * q + 4 * fg;  // column inside the pass
+                        f2 lo, hi;
+                        if constexpr (GRAN == F8_TENSORWISE) {
+                            lo = f2{acc[i][j][4 * q] * s_tensor, acc[i][j][4 * q + 1] * s_tensor};
+                            hi = f2{acc[i][j][4 * q + 2] * s_tensor, acc[i][j][4 * q + 3] * s_tensor};
+                        } else {
+                            int n = n0 + 32 * jp + nl;
+                            n = n < N ? n : N - 4;
+                            const float4 sb = *reinterpret_cast<const float4*>(isb + n);
+                            lo = f2{(acc[i][j][4 * q] * sa) * sb.x, (acc[i][j][4 * q + 1] * sa) * sb.y};
+                            hi = f2{(acc[i][j][4 * q + 2] * sa) * sb.z, (acc[i][j][4 * q + 3] * sa) * sb.w};
+                        }
+                        // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
+                        const b2 blo = __builtin_convertvector(lo, b2), bhi = __builtin_convertvector(hi, b2);
+                        uint2 o;
+                        o.x = __builtin_bit_cast(uint32_t, blo);
+                        o.y = __builtin_bit_cast(uint32_t, bhi);
+                        *reinterpret_cast<uint2*>(ep + fr * EP_STRIDE + nl * 2) = o;
+                    }
+                }
+                // 32 rows x 8 pieces of 16 bytes = 256 pieces, four per lane
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int idx = t * 64 + lane;
+                    const int row = idx >> 3, ch = idx & 7;
+                    const uint4 v = *reinterpret_cast<const uint4*>(ep + row * EP_STRIDE + ch * 16);
+                    const int m = m0 + 32 * i + row;
+                    const int n = n0 + 32 * jp + ch * 8;
+                    if (m < M && n < N) *reinterpret_cast<uint4*>(D + (int64_t)m * ldd + n) = v;
+                }
+                __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps register pressure low
             }
         }
+    };
+
+    // ---- prologue: two stages in flight, first half-step into registers ----------------
+    if (ld_valid) load_context(ld_tile);
+    issue_all(0, I0{});
+    issue_all(1, I1{});
+    Frags f0, f1;
+    zero_acc();
+    __builtin_amdgcn_s_waitcnt(kWaitAllVmLgkm);
+    __syncthreads();
+    read_frags(f0, I0{}, I0{});
+
+    // One K step out of stage S = 2 * NMFMA MFMA slots, in a fixed order (every slot ends with a
+    // scheduling fence).  On entry f0 holds the fragments of the first half-step.
+    //   slots [0, NF):        + LDS reads of the second half-step's fragments (stage S) into f1
+    //   after slot SYNC_A-1:  barrier: every wave is done reading stage S
+    //   slots [SYNC_A, ...):  + the loads that refill stage S with the stream's next K step,
+    //                         at most one per slot and with gaps: a wave's load blocks its
+    //                         instruction issue until the CU's address unit accepts it (16 cycles
+    //                         per 1 KB load, shared by the four waves), so bunched loads would
+    //                         starve the matrix pipe
+    //   after slot SYNC_B-1:  wait until only this step's PRE_B loads are in flight (the
+    //                         previous step's have then landed), barrier: the other stage is
+    //                         complete for every wave
+    //   slots [2*NMFMA-NF, 2*NMFMA): + LDS reads of the next K step's first fragments into f0
+    // The MFMAs issued just before a barrier keep the matrix pipe busy while the wave waits.
+    constexpr int NF = TM + TN;                       // fragments per half-step
+    constexpr int SLOTS = 2 * NMFMA;
+    constexpr int NFS = NF < NMFMA / 2 ? NF : NMFMA / 2;  // slots that carry fragment reads
+    constexpr int FPS = (NF + NFS - 1) / NFS;             // fragments per such slot
+    constexpr int SYNC_A = NFS + (NMFMA >= 16 ? 4 : 1);
+    constexpr int SYNC_B = SLOTS - NFS;
+    constexpr int LOADS = A_LOADS + B_LOADS;
+    constexpr int LOAD_SLOTS = SLOTS - SYNC_A;
+    static_assert(SYNC_A <= SYNC_B && LOAD_SLOTS > 0, "schedule does not fit");
+    // load l goes into slot SYNC_A + floor(l * LOAD_SLOTS / LOADS): evenly spread
+    constexpr auto slot_of_load = [](int l) { return SYNC_A + l * LOAD_SLOTS / LOADS; };
+    constexpr int PRE_B = [&] {
+        int n = 0;
+        for (int l = 0; l < LOADS; ++l) n += slot_of_load(l) < SYNC_B;
+        return n;
+    }();
+    // i-major MFMA order needs fragments in the order a0, b0 .. b(TN-1), a1 .. a(TM-1)
+    constexpr auto frag_order = [](int n) { return n == 0 ? 0 : (n <= TN ? TM + n - 1 : n - TN); };
+    // s_waitcnt vmcnt(PRE_B) lgkmcnt(0)
+    constexpr int kWaitB = (PRE_B & 15) | ((PRE_B >> 4) << 14) | 0x0070;
+
+    auto kstep = [&](auto S, int fetch_kt) {
+        constexpr int s = decltype(S)::value;
+        static_for<SLOTS>([&](auto SLOT) {
+            constexpr int slot = decltype(SLOT)::value;
+            if constexpr (slot == SYNC_A) {
+                __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): my reads of stage S are back
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (slot == SYNC_B) {
+                if (ld_valid)
+                    __builtin_amdgcn_s_waitcnt(kWaitB);
+                else
+                    __builtin_amdgcn_s_waitcnt(kWaitAllVmLgkm);  // nothing was issued this step
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (slot < NMFMA)
+                mfmas(f0, SLOT, integral_constant<int, slot + 1>{});
+            else
+                mfmas(f1, integral_constant<int, slot - NMFMA>{}, integral_constant<int, slot - NMFMA + 1>{});
+            static_for<FPS>([&](auto F) {
+                constexpr int n = (slot < NFS ? slot : slot - SYNC_B) * FPS + decltype(F)::value;
+                if constexpr (n < NF) {
+                    if constexpr (slot < NFS) read_frag(f1, S, I1{}, integral_constant<int, frag_order(n)>{});
+                    if constexpr (slot >= SYNC_B)
+                        read_frag(f0, integral_constant<int, 1 - s>{}, I0{}, integral_constant<int, frag_order(n)>{});
+                }
+            });
+            static_for<LOADS>([&](auto L) {
+                if constexpr (slot_of_load(decltype(L)::value) == slot) {
+                    if (ld_valid) issue_one(fetch_kt, S, L);
+                }
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
+#ifdef F8_EXP_CLOCK
+    const uint64_t exp_c0 = __builtin_readcyclecounter(), exp_r0 = __builtin_amdgcn_s_memrealtime();
+#endif
+    // ---- main loop over this workgroup's tiles.  KT is even, so every tile starts in stage 0.
+    // The step computed at kt fetches step kt + 2; the last two steps of a tile fetch the first
+    // two of the next tile.
+    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+        // Retire every earlier vector-memory operation (the previous tile's stores, register
+        // spills) once per tile.  Otherwise the compiler, which must protect the data
+        // registers of pending stores, places its own full wait inside the K loop, where it
+        // would also wait for the freshly issued loads on every step.  The loads in flight
+        // here are this tile's first two K steps, requested a whole epilogue ago.
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        for (int kt = 0; kt < KT - 2; kt += 2) {
+            kstep(I0{}, kt + 2);
+            kstep(I1{}, kt + 3);
+        }
+        next_load_tile();
+        kstep(I0{}, 0);
+        kstep(I1{}, 1);
+        epilogue(tile);
+        zero_acc();
     }
+#ifdef F8_EXP_CLOCK
+    // perf probe only: shader-clock ticks and 100 MHz ticks of this workgroup, into the first
+    // bytes of D (corrupts the result)
+    if (blockIdx.x == 17 && threadIdx.x == 0) {
+        __builtin_amdgcn_s_waitcnt(0);
+        uint64_t* o = reinterpret_cast<uint64_t*>(D);
+        o[0] = __builtin_readcyclecounter() - exp_c0;
+        o[1] = __builtin_amdgcn_s_memrealtime() - exp_r0;
+    }
+#endif
 }
 
 // ---------------------------------------------------------------------------
@@ -393,24 +536,37 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN>
 static void launch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
-                      const float* isa, const float* isb, uint16_t* D, int64_t ldd, hipStream_t st)
+                      const float* isa, const float* isb, uint16_t* D, int64_t ldd, int max_blocks, hipStream_t st)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN><<<tiles_m * tiles_n, WAVES_M * WAVES_N * 64, 0, st>>>(
+    const int total = tiles_m * tiles_n;
+    const int grid = total < max_blocks ? total : max_blocks;
+    gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
         A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tiles_m, tiles_n);
+}
+
+static int cu_count()
+{
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        n = 256;
+    return n - n % kXcds;  // the persistent tile order assumes a multiple of the XCD count
 }
 
 template <int FA, int FB, int GRAN>
 static void dispatch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
                         const float* isa, const float* isb, uint16_t* D, int64_t ldd, hipStream_t st)
 {
-    // 256x256 tiles when they give at least one full wave of workgroups over the 256 CUs,
-    // otherwise 128x128 to keep more CUs busy.
-    const int64_t big_tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
-    if (big_tiles >= 256)
-        launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, st);
+    // The largest tile that still gives every CU work: 256x256 (one persistent workgroup per
+    // CU), else 256x128, else 128x128 (LDS allows two workgroups per CU there).
+    const int cus = cu_count();
+    auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    if (tiles(256, 256) >= cus)
+        launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, cus, st);
+    else if (tiles(256, 128) >= cus)
+        launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, cus, st);
     else
-        launch_nt<128, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, st);
+        launch_nt<128, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, 2 * cus, st);
 }
 
 template <int LAYOUT, int FA, int FB, int GRAN>
@@ -427,7 +583,7 @@ static void dispatch_layout(int layout, int M, int N, int K, const uint8_t* A, i
                             hipStream_t st)
 {
     if (layout == F8_NT) {
-        if (K % kBK == 0 && K > 0)
+        if (K % (2 * kBK) == 0 && K > 0)  // the fast kernel alternates two LDS stages per tile
             dispatch_nt<FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, st);
         else
             launch_generic<F8_NT, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, st);
