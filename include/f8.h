@@ -31,7 +31,7 @@
  *   - No global mutable state: calls on different streams with disjoint
  *     buffers (including disjoint workspaces) may run concurrently.
  *   - Inputs are expected to be finite.  With a caller-given finite scale,
- *     f8_cast maps NaN to a NaN code (0x7F or 0xFF) and +-Inf to the
+ *     f8_cast maps NaN to one of the format's NaN codes and +-Inf to the
  *     +-FMAX code; amax over non-finite data is unspecified.
  */
 #ifndef F8_H

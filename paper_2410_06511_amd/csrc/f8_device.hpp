@@ -86,8 +86,11 @@ __device__ inline uint32_t encode_hw2(float y0, float y1)
     return (uint32_t)r & 0xFFFFu;
 }
 
+// The casts use the conversion instruction: the software rounding costs about a dozen integer
+// operations per element, which makes the cast ALU-bound instead of HBM-bound.  The GPU tests
+// compare the two encoders over every fp32 bit pattern.
 #ifndef F8_ENCODE_HW
-#define F8_ENCODE_HW 0
+#define F8_ENCODE_HW 1
 #endif
 
 // scale, saturate, round: two bf16 (one 32-bit word) -> two codes in bits 0..15.

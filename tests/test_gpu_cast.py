@@ -114,6 +114,27 @@ def test_rounding_step_all_bf16_times_scales(fmt, hw):
     assert np.array_equal(u8(out)[idx], o.encode(ref_in[idx], fmt)), (fmt, hw)
 
 
+@pytest.mark.parametrize("fmt", FMTS)
+def test_hw_and_sw_rounding_agree_on_every_fp32(fmt):
+    """The casts round with the chip's conversion instruction; the integer-arithmetic rounding is
+    the one checked against the oracle above.  Here the two are compared with each other on all
+    2^32 fp32 bit patterns (NaNs: both must give a NaN code), in chunks, on the GPU."""
+    chunk = 1 << 26
+    out_hw = torch.empty(chunk, dtype=torch.uint8, device="cuda")
+    out_sw = torch.empty(chunk, dtype=torch.uint8, device="cuda")
+    base = torch.arange(chunk, dtype=torch.int64, device="cuda")
+    for c in range((1 << 32) // chunk):
+        bits = (base + c * chunk - (1 << 31)).to(torch.int32)      # every int32 pattern once
+        y = bits.view(torch.float32)
+        f8.encode_f32(y, fmt, 1, out_hw)
+        f8.encode_f32(y, fmt, 0, out_sw)
+        nan = torch.isnan(y)
+        same = (out_hw == out_sw) | (nan & ((out_hw & 0x7F) == 0x7F) & ((out_sw & 0x7F) == 0x7F))
+        if fmt == f8.E5M2:   # e5m2 has several NaN codes
+            same |= nan & ((out_hw & 0x7F) > 0x7C) & ((out_sw & 0x7F) > 0x7C)
+        assert bool(same.all()), (fmt, c, int((~same).sum()), y[~same][:4], out_hw[~same][:4], out_sw[~same][:4])
+
+
 def run_cast(x, s, g, fmt, want_out=True, want_t=True):
     rows, cols = x.shape
     out = torch.full((rows, cols), 0xAA, dtype=torch.uint8, device="cuda") if want_out else None
@@ -153,7 +174,8 @@ def test_cast_every_bf16_value(fmt):
         got = u8(out)
         nan_in = np.isnan(o.bf16_to_f32(allb))
         assert np.array_equal(got[~nan_in], ref[~nan_in]), s
-        assert np.all((got[nan_in] & 0x7F) == 0x7F)       # NaN -> a NaN code, sign unspecified
+        # NaN -> one of the format's NaN codes (e4m3: S.1111.111; e5m2: S.11111.01/10/11)
+        assert np.all(np.isnan(o.decode(got[nan_in], fmt)))
         assert np.array_equal(u8(out_t), got.T)
 
 
