@@ -178,7 +178,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     // the stream's current tile, into stage S.  Written as asm: 32-bit lane offset next to a
     // scalar base, LDS target in M0.  The compiler therefore does not see these as LDS writes;
     // ordering against the LDS reads is by the barriers and explicit waits of kstep.
-    bool ld_valid = ld_tile < total_tiles;
     auto issue_one = [&](int kt, auto S, auto IDX) {
         constexpr int idx = decltype(IDX)::value;
         if constexpr (idx < A_LOADS) {
@@ -196,15 +195,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
         }
     };
-    auto issue_all = [&](int kt, auto S) {
-        if (!ld_valid) return;
-        static_for<A_LOADS + B_LOADS>([&](auto L) { issue_one(kt, S, L); });
-    };
-    // move the load stream to this workgroup's next tile
+    auto issue_all = [&](int kt, auto S) { static_for<A_LOADS + B_LOADS>([&](auto L) { issue_one(kt, S, L); }); };
+    // Move the load stream to this workgroup's next tile.  Past the last tile the stream
+    // stays where it is: the same K steps are fetched again into stages nobody reads, so that
+    // every K step issues the same number of loads and the wait counts below hold throughout.
     auto next_load_tile = [&]() {
         ld_tile += gridDim.x;
-        ld_valid = ld_tile < total_tiles;
-        if (ld_valid) load_context(ld_tile);
+        if (ld_tile < total_tiles) load_context(ld_tile);
     };
 
     // ---- LDS -> register addressing: lane reads row (l % 32) of a 32-row MFMA tile; in
@@ -317,13 +314,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                     const int n = n0 + 32 * jp + ch * 8;
                     if (m < M && n < N) *reinterpret_cast<uint4*>(D + (int64_t)m * ldd + n) = v;
                 }
-                __builtin_amdgcn_sched_barrier(0);  // one pass at a time: keeps register pressure low
+                // one pass at a time: measured faster than letting the compiler interleave passes
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
 
     // ---- prologue: two stages in flight, first half-step into registers ----------------
-    if (ld_valid) load_context(ld_tile);
+    load_context(ld_tile);  // the grid never exceeds the tile count
     issue_all(0, I0{});
     issue_all(1, I1{});
     Frags f0, f1;
@@ -377,10 +375,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                 __builtin_amdgcn_sched_barrier(0);
             }
             if constexpr (slot == SYNC_B) {
-                if (ld_valid)
-                    __builtin_amdgcn_s_waitcnt(kWaitB);
-                else
-                    __builtin_amdgcn_s_waitcnt(kWaitAllVmLgkm);  // nothing was issued this step
+                __builtin_amdgcn_s_waitcnt(kWaitB);
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -397,9 +392,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                 }
             });
             static_for<LOADS>([&](auto L) {
-                if constexpr (slot_of_load(decltype(L)::value) == slot) {
-                    if (ld_valid) issue_one(fetch_kt, S, L);
-                }
+                if constexpr (slot_of_load(decltype(L)::value) == slot) issue_one(fetch_kt, S, L);
             });
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -407,6 +400,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
 
 #ifdef F8_EXP_CLOCK
     const uint64_t exp_c0 = __builtin_readcyclecounter(), exp_r0 = __builtin_amdgcn_s_memrealtime();
+    uint64_t exp_loop = 0, exp_epi = 0, exp_wait = 0;
 #endif
     // ---- main loop over this workgroup's tiles.  KT is even, so every tile starts in stage 0.
     // The step computed at kt fetches step kt + 2; the last two steps of a tile fetch the first
@@ -417,7 +411,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         // registers of pending stores, places its own full wait inside the K loop, where it
         // would also wait for the freshly issued loads on every step.  The loads in flight
         // here are this tile's first two K steps, requested a whole epilogue ago.
+#ifdef F8_EXP_CLOCK
+        const uint64_t exp_t0 = __builtin_readcyclecounter();
+#endif
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+#ifdef F8_EXP_CLOCK
+        const uint64_t exp_t1 = __builtin_readcyclecounter();
+#endif
         for (int kt = 0; kt < KT - 2; kt += 2) {
             kstep(I0{}, kt + 2);
             kstep(I1{}, kt + 3);
@@ -425,9 +425,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         next_load_tile();
         kstep(I0{}, 0);
         kstep(I1{}, 1);
+#ifdef F8_EXP_CLOCK
+        const uint64_t exp_t2 = __builtin_readcyclecounter();
+#endif
         epilogue(tile);
         zero_acc();
+#ifdef F8_EXP_CLOCK
+        const uint64_t exp_t3 = __builtin_readcyclecounter();
+        exp_wait += exp_t1 - exp_t0, exp_loop += exp_t2 - exp_t1, exp_epi += exp_t3 - exp_t2;
+#endif
     }
+    // no load may still be writing LDS when the workgroup ends
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 #ifdef F8_EXP_CLOCK
     // perf probe only: shader-clock ticks and 100 MHz ticks of this workgroup, into the first
     // bytes of D (corrupts the result)
@@ -436,6 +445,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         uint64_t* o = reinterpret_cast<uint64_t*>(D);
         o[0] = __builtin_readcyclecounter() - exp_c0;
         o[1] = __builtin_amdgcn_s_memrealtime() - exp_r0;
+        o[2] = exp_wait, o[3] = exp_loop, o[4] = exp_epi;
     }
 #endif
 }
