@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--workload", default="llama8b")
     ap.add_argument("--variant", default=None, help="granularity:gradfmt, e.g. tensorwise:e4m3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a device copy of known size (reference for the HBM byte counters)")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
     return ap.parse_args()
 
@@ -69,6 +71,18 @@ def main():
         sys.exit(1)
     f8.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        # 1 GiB read + 1 GiB written per launch, by a plain elementwise copy kernel
+        n = 1 << 29
+        x = torch.ones(n, dtype=torch.bfloat16, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(4):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_launch": 2 * n, "bytes_written_per_launch": 2 * n,
+                                                "launches": 4}}))
+        return
 
     w = wl.WORKLOADS[args.workload]
     gran, gfmt = (args.variant.split(":") if args.variant else w.variants[0])
@@ -156,7 +170,7 @@ def main():
         "peak": PEAK_FP8_TFLOPS,
         "unit": "TFLOP/s",
         "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
-        "traffic": None,
+        "traffic": committed_traffic(),
         "launches_per_step": gemm_launches,
         "avg_launch_ms": round(gemm_ms / gemm_launches, 4),
         "flops_per_launch": gemm_flops // gemm_launches,
@@ -196,6 +210,20 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_rows, rowwise, grad_fmt)
     print(json.dumps(out))
+
+
+def committed_traffic():
+    """Bytes per GEMM launch between L2 and the fabric / HBM, from the two rocprofv3 --pmc runs
+    (FETCH_SIZE, WRITE_SIZE, scaled by a copy of known size) summarised under profiles/; None if
+    that summary is absent.  It is measured on this workload, not in this process."""
+    path = os.path.join(ROOT, "profiles", "gemm_cast_llama8b_hbm_traffic.md")
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_gemm_launch:"):
+                return int(ln.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(w, rows, rowwise, grad_fmt):
