@@ -143,36 +143,30 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
 
     // ---- load stream: (tile, K step) of the next stage to fetch -------------------------
     // wave w fills rows [w*R, (w+1)*R) of each operand tile in 8-row (1 KB) pieces; lane i
-    // lands at row i/8, physical chunk i%8 of its piece.
+    // lands at row i/8, physical chunk i%8 of its piece.  Per tile only scalars change (tile
+    // origin, row limits); the lane's byte offset of a piece is rebuilt for every load from
+    // its row and chunk (three VALU operations), which is cheaper than carrying sixteen offsets
+    // in registers across the whole K loop.
     int ld_tile = blockIdx.x;
-    uint32_t a_off[A_LOADS], b_off[B_LOADS];
+    const int a_row = wave * (BM / NW) + (lane >> 3);  // row of piece 0 in the A tile
+    const int b_row = wave * (BN / NW) + (lane >> 3);
+    // chunk terms: the swizzle of row + 8 * j differs from that of row only for odd j (bit 2)
+    const uint32_t a_c0 = 16 * ((lane & 7) ^ swz(a_row)), a_c1 = 16 * ((lane & 7) ^ swz(a_row + 8));
+    const uint32_t b_c0 = 16 * ((lane & 7) ^ swz(b_row)), b_c1 = 16 * ((lane & 7) ^ swz(b_row + 8));
+    static_assert((BM / NW) % 16 == 0 && (BN / NW) % 16 == 0, "swizzle period");
     const uint8_t* a_base = A;
     const uint8_t* b_base = B;
+    int a_rmax = 0, b_rmax = 0;  // last valid row of the current load tile, relative to its origin
     auto load_context = [&](int tile) {
         int tm, tn;
         tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
 #ifdef F8_EXP_SAME_TILE
         tm = tn = 0;  // perf probe only: every tile loads the same rows (all loads hit in L2)
 #endif
-        const int m0 = tm * BM, n0 = tn * BN;
-#pragma unroll
-        for (int j = 0; j < A_LOADS; ++j) {
-            const int row = wave * (BM / NW) + 8 * j + (lane >> 3);
-            const int c = (lane & 7) ^ swz(row);
-            int gr = m0 + row;
-            gr = gr < M ? gr : M - 1;  // rows past the edge re-read the last row; never stored
-            a_off[j] = (uint32_t)((int64_t)(gr - m0) * lda + 16 * c);
-        }
-#pragma unroll
-        for (int j = 0; j < B_LOADS; ++j) {
-            const int row = wave * (BN / NW) + 8 * j + (lane >> 3);
-            const int c = (lane & 7) ^ swz(row);
-            int gr = n0 + row;
-            gr = gr < N ? gr : N - 1;
-            b_off[j] = (uint32_t)((int64_t)(gr - n0) * ldb + 16 * c);
-        }
-        a_base = A + (int64_t)m0 * lda;
-        b_base = B + (int64_t)n0 * ldb;
+        a_base = A + (int64_t)tm * BM * lda;
+        b_base = B + (int64_t)tn * BN * ldb;
+        a_rmax = M - 1 - tm * BM;  // rows past the edge re-read the last row; never stored
+        b_rmax = N - 1 - tn * BN;
     };
     // Load number `idx` (0 .. LOADS-1: first the A pieces, then the B pieces) of K step `kt` of
     // the stream's current tile, into stage S.  Written as asm: 32-bit lane offset next to a
@@ -184,14 +178,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
             const uint8_t* gp = a_base + (int64_t)kt * kBK;
             uint8_t* lp = stage_ptr(S) + wave * (BM / NW) * kBK + idx * 1024;
             const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
-            const uint32_t o = a_off[idx];
+            int r = a_row + 8 * idx;
+            r = r < a_rmax ? r : a_rmax;
+            const uint32_t o = (uint32_t)r * (uint32_t)lda + ((idx & 1) ? a_c1 : a_c0);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
         } else {
             constexpr int j = idx - A_LOADS;
             const uint8_t* gp = b_base + (int64_t)kt * kBK;
             uint8_t* lp = stage_ptr(S) + A_BYTES + wave * (BN / NW) * kBK + j * 1024;
             const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
-            const uint32_t o = b_off[j];
+            int r = b_row + 8 * j;
+            r = r < b_rmax ? r : b_rmax;
+            const uint32_t o = (uint32_t)r * (uint32_t)ldb + ((j & 1) ? b_c1 : b_c0);
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
         }
     };
@@ -272,52 +270,66 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         uint8_t* ep = epb + wave * (32 * EP_STRIDE);
         float s_tensor = 0.f;
         if constexpr (GRAN == F8_TENSORWISE) s_tensor = isa[0] * isb[0];
+        // A lane stores four 16-byte pieces per pass: rows 8 t + lane / 8 of the 32-row band,
+        // columns 8 * (lane % 8) .. +7 of the 64-column pass: uniform base + 32-bit lane offset.
+        uint8_t* dbase = reinterpret_cast<uint8_t*>(D + (int64_t)m0 * ldd + n0);
+        const uint32_t ldd_b = (uint32_t)ldd * 2;
+        const uint32_t voff = (uint32_t)(lane >> 3) * ldd_b + (uint32_t)(lane & 7) * 16;
+        const bool interior = tm * BM + BM <= M && tn * BN + BN <= N;  // no edge checks needed
+
+        auto run = [&](auto INTERIOR) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int m_lane = m0 + 32 * i + fr;
-            float sa = 0.f;
-            if constexpr (GRAN != F8_TENSORWISE) sa = isa[m_lane < M ? m_lane : M - 1];
+            for (int i = 0; i < TM; ++i) {
+                float sa = 0.f;
+                if constexpr (GRAN != F8_TENSORWISE) {
+                    const int m_lane = m0 + 32 * i + fr;
+                    sa = isa[m_lane < M ? m_lane : M - 1];
+                }
 #pragma unroll
-            for (int jp = 0; jp < TN; jp += 2) {  // two MFMA tiles = 64 columns per pass
+                for (int jp = 0; jp < TN; jp += 2) {  // two MFMA tiles = 64 columns per pass
 #pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int j = jp + jj;
+                    for (int jj = 0; jj < 2; ++jj) {
+                        const int j = jp + jj;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int nl = 32 * jj + 8 * q + 4 * fg;  // column inside the pass
-                        f2 lo, hi;
-                        if constexpr (GRAN == F8_TENSORWISE) {
-                            lo = f2{acc[i][j][4 * q] * s_tensor, acc[i][j][4 * q + 1] * s_tensor};
-                            hi = f2{acc[i][j][4 * q + 2] * s_tensor, acc[i][j][4 * q + 3] * s_tensor};
-                        } else {
-                            int n = n0 + 32 * jp + nl;
-                            n = n < N ? n : N - 4;
-                            const float4 sb = *reinterpret_cast<const float4*>(isb + n);
-                            lo = f2{(acc[i][j][4 * q] * sa) * sb.x, (acc[i][j][4 * q + 1] * sa) * sb.y};
-                            hi = f2{(acc[i][j][4 * q + 2] * sa) * sb.z, (acc[i][j][4 * q + 3] * sa) * sb.w};
+                        for (int q = 0; q < 4; ++q) {
+                            const int nl = 32 * jj + 8 * q + 4 * fg;  // column inside the pass
+                            f2 lo, hi;
+                            if constexpr (GRAN == F8_TENSORWISE) {
+                                lo = f2{acc[i][j][4 * q] * s_tensor, acc[i][j][4 * q + 1] * s_tensor};
+                                hi = f2{acc[i][j][4 * q + 2] * s_tensor, acc[i][j][4 * q + 3] * s_tensor};
+                            } else {
+                                int n = n0 + 32 * jp + nl;
+                                n = n < N ? n : N - 4;
+                                const float4 sb = *reinterpret_cast<const float4*>(isb + n);
+                                lo = f2{(acc[i][j][4 * q] * sa) * sb.x, (acc[i][j][4 * q + 1] * sa) * sb.y};
+                                hi = f2{(acc[i][j][4 * q + 2] * sa) * sb.z, (acc[i][j][4 * q + 3] * sa) * sb.w};
+                            }
+                            // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
+                            uint2 o;
+                            o.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, b2));
+                            o.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, b2));
+                            *reinterpret_cast<uint2*>(ep + fr * EP_STRIDE + nl * 2) = o;
                         }
-                        // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
-                        const b2 blo = __builtin_convertvector(lo, b2), bhi = __builtin_convertvector(hi, b2);
-                        uint2 o;
-                        o.x = __builtin_bit_cast(uint32_t, blo);
-                        o.y = __builtin_bit_cast(uint32_t, bhi);
-                        *reinterpret_cast<uint2*>(ep + fr * EP_STRIDE + nl * 2) = o;
                     }
-                }
-                // 32 rows x 8 pieces of 16 bytes = 256 pieces, four per lane
+                    uint8_t* pbase = dbase + ((int64_t)(32 * i) * ldd + 32 * jp) * 2;  // uniform
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const int idx = t * 64 + lane;
-                    const int row = idx >> 3, ch = idx & 7;
-                    const uint4 v = *reinterpret_cast<const uint4*>(ep + row * EP_STRIDE + ch * 16);
-                    const int m = m0 + 32 * i + row;
-                    const int n = n0 + 32 * jp + ch * 8;
-                    if (m < M && n < N) *reinterpret_cast<uint4*>(D + (int64_t)m * ldd + n) = v;
+                    for (int t = 0; t < 4; ++t) {
+                        const int idx = t * 64 + lane;
+                        const uint4 v = *reinterpret_cast<const uint4*>(ep + (idx >> 3) * EP_STRIDE + (idx & 7) * 16);
+                        bool ok = true;
+                        if constexpr (!decltype(INTERIOR)::value)
+                            ok = m0 + 32 * i + (idx >> 3) < M && n0 + 32 * jp + (idx & 7) * 8 < N;
+                        if (ok) *reinterpret_cast<uint4*>(pbase + (voff + (uint32_t)(8 * t) * ldd_b)) = v;
+                    }
+                    // one pass at a time: measured faster than letting the compiler interleave passes
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                // one pass at a time: measured faster than letting the compiler interleave passes
-                __builtin_amdgcn_sched_barrier(0);
             }
-        }
+        };
+        if (interior)
+            run(std::true_type{});
+        else
+            run(std::false_type{});
     };
 
     // ---- prologue: two stages in flight, first half-step into registers ----------------
@@ -346,10 +358,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     // The MFMAs issued just before a barrier keep the matrix pipe busy while the wave waits.
     constexpr int NF = TM + TN;                       // fragments per half-step
     constexpr int SLOTS = 2 * NMFMA;
-    constexpr int NFS = NF < NMFMA / 2 ? NF : NMFMA / 2;  // slots that carry fragment reads
-    constexpr int FPS = (NF + NFS - 1) / NFS;             // fragments per such slot
-    constexpr int SYNC_A = NFS + (NMFMA >= 16 ? 4 : 1);
-    constexpr int SYNC_B = SLOTS - NFS;
+    // f1's fragment reads are spread over slots [0, F1_SPAN), f0's over [SYNC_B, SLOTS).  The two
+    // tunables (for the 16-MFMA half-steps of the 256x256 tile) were chosen by measurement.
+#ifndef F8_SCHED_COVER
+#define F8_SCHED_COVER 2
+#endif
+#ifndef F8_SCHED_F0_SPAN
+#define F8_SCHED_F0_SPAN 12
+#endif
+    constexpr int F1_SPAN = NF < NMFMA / 2 ? NF : NMFMA / 2;
+    constexpr int F0_SPAN = NMFMA >= 16 ? F8_SCHED_F0_SPAN : F1_SPAN;
+    constexpr int SYNC_A = F1_SPAN + (NMFMA >= 16 ? F8_SCHED_COVER : 1);
+    constexpr int SYNC_B = SLOTS - F0_SPAN;
+    constexpr auto f1_slot = [](int n) { return n * F1_SPAN / NF; };            // fragment n (in read order)
+    constexpr auto f0_slot = [](int n) { return SYNC_B + n * F0_SPAN / NF; };
     constexpr int LOADS = A_LOADS + B_LOADS;
     constexpr int LOAD_SLOTS = SLOTS - SYNC_A;
     static_assert(SYNC_A <= SYNC_B && LOAD_SLOTS > 0, "schedule does not fit");
@@ -383,13 +405,11 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                 mfmas(f0, SLOT, integral_constant<int, slot + 1>{});
             else
                 mfmas(f1, integral_constant<int, slot - NMFMA>{}, integral_constant<int, slot - NMFMA + 1>{});
-            static_for<FPS>([&](auto F) {
-                constexpr int n = (slot < NFS ? slot : slot - SYNC_B) * FPS + decltype(F)::value;
-                if constexpr (n < NF) {
-                    if constexpr (slot < NFS) read_frag(f1, S, I1{}, integral_constant<int, frag_order(n)>{});
-                    if constexpr (slot >= SYNC_B)
-                        read_frag(f0, integral_constant<int, 1 - s>{}, I0{}, integral_constant<int, frag_order(n)>{});
-                }
+            static_for<NF>([&](auto F) {
+                constexpr int n = decltype(F)::value;
+                if constexpr (f1_slot(n) == slot) read_frag(f1, S, I1{}, integral_constant<int, frag_order(n)>{});
+                if constexpr (f0_slot(n) == slot)
+                    read_frag(f0, integral_constant<int, 1 - s>{}, I0{}, integral_constant<int, frag_order(n)>{});
             });
             static_for<LOADS>([&](auto L) {
                 if constexpr (slot_of_load(decltype(L)::value) == slot) issue_one(fetch_kt, S, L);
@@ -418,18 +438,21 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
 #ifdef F8_EXP_CLOCK
         const uint64_t exp_t1 = __builtin_readcyclecounter();
 #endif
-        for (int kt = 0; kt < KT - 2; kt += 2) {
-            kstep(I0{}, kt + 2);
-            kstep(I1{}, kt + 3);
+        for (int kt = 0; kt < KT; kt += 2) {
+            if (kt == KT - 2) next_load_tile();  // the last two steps fetch the next tile's first two
+            const int f = kt == KT - 2 ? 0 : kt + 2;
+            kstep(I0{}, f);
+            kstep(I1{}, f + 1);
         }
-        next_load_tile();
-        kstep(I0{}, 0);
-        kstep(I1{}, 1);
 #ifdef F8_EXP_CLOCK
         const uint64_t exp_t2 = __builtin_readcyclecounter();
 #endif
         epilogue(tile);
         zero_acc();
+        // The next tile's first fragments are read again here rather than kept in registers
+        // across the epilogue (the last K step already fetched them once): 64 registers less
+        // for the epilogue to fight over.  Stage 0 is complete since that step's second barrier.
+        read_frags(f0, I0{}, I0{});
 #ifdef F8_EXP_CLOCK
         const uint64_t exp_t3 = __builtin_readcyclecounter();
         exp_wait += exp_t1 - exp_t0, exp_loop += exp_t2 - exp_t1, exp_epi += exp_t3 - exp_t2;
