@@ -319,6 +319,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                         bool ok = true;
                         if constexpr (!decltype(INTERIOR)::value)
                             ok = m0 + 32 * i + (idx >> 3) < M && n0 + 32 * jp + (idx & 7) * 8 < N;
+#ifdef F8_EXP_NO_STORE
+                        ok = ok && v.x == 0x7fc17fc3u;  // perf probe only: (almost) never stores
+#endif
                         if (ok) *reinterpret_cast<uint4*>(pbase + (voff + (uint32_t)(8 * t) * ldd_b)) = v;
                     }
                     // one pass at a time: measured faster than letting the compiler interleave passes

@@ -99,25 +99,50 @@ def test_linear_exact_case_bit_for_bit():
         assert np.array_equal(bits(dW), ex(d64.T @ x64))
 
 
-def _sampled_check(name, got, layout, A, fa, B, fb, isa, isb, g, rng, n=6):
+def _sample_lines(n_lines, rng, n=64, tile=256):
+    """Indices of whole output rows (or columns) to compare: n seeded random ones, the first
+    and the last, and both sides of the first, the last and three random 256-tile boundaries."""
+    picks = set(rng.integers(0, n_lines, n).tolist()) | {0, n_lines - 1}
+    nb = (n_lines - 1) // tile  # boundaries at tile, 2 * tile, ..., nb * tile
+    if nb >= 1:
+        for t in {1, nb} | set(rng.integers(1, nb + 1, 3).tolist()):
+            picks |= {t * tile - 1, t * tile}
+    return sorted(picks)
+
+
+def _sampled_check(name, got, layout, A, fa, B, fb, isa, isb, g, rng):
     M, N = got.shape
-    rows = sorted(set(rng.integers(0, M, n).tolist()) | {0, M - 1, 255, 256})
-    cols = sorted(set(rng.integers(0, N, n).tolist()) | {0, N - 1, 255, 256})
+    rows, cols = _sample_lines(M, rng), _sample_lines(N, rng)
     ms, ns = np.repeat(rows, N), np.tile(np.arange(N), len(rows))
     assert_gemm_close(got[ms, ns], o.gemm_points(layout, A, fa, B, fb, isa, isb, ms, ns, g), name + " rows")
     ns, ms = np.repeat(cols, M), np.tile(np.arange(M), len(cols))
     assert_gemm_close(got[ms, ns], o.gemm_points(layout, A, fa, B, fb, isa, isb, ms, ns, g), name + " cols")
 
 
-@pytest.mark.parametrize("key,li,rowwise,grad_fmt", [
-    ("llama8b", 1, False, f8.E4M3),          # wk: K=4096, N=1024
-    ("llama70b_tp8", 3, False, f8.E5M2),     # wq slice with activation outliers, e5m2 gradients
-    ("llama405b_tp8", 3, True, f8.E4M3),     # wq slice, rowwise
-])
+def _full_size_cases():
+    """Every distinct linear shape of every Llama-shaped workload, in each of the variants the
+    workload is run in (tensorwise / rowwise scaling, e4m3 / e5m2 gradients)."""
+    cases = []
+    for key, w in wl.WORKLOADS.items():
+        if key == "single":
+            continue
+        seen = set()
+        for li, lin in enumerate(w.linears):
+            if (lin.K, lin.N) in seen:
+                continue  # w3 repeats w1's shape, wv wk's, wo wq's
+            seen.add((lin.K, lin.N))
+            for gran, gfmt in w.variants:
+                cases.append(pytest.param(key, li, gran == "rowwise", f8.E5M2 if gfmt == "e5m2" else f8.E4M3,
+                                          id=f"{key}-{lin.name}-{gran}-{gfmt}"))
+    return cases
+
+
+@pytest.mark.parametrize("key,li,rowwise,grad_fmt", _full_size_cases())
 def test_full_size_linear(key, li, rowwise, grad_fmt):
-    """Full-size linears of the Llama-shaped workloads, M = 8192, exactly as the benchmark
-    launches them.  amax / scales / codes compared in full; Y, dX, dW on sampled whole rows and
-    columns computed by the oracle from the same codes."""
+    """Full-size linears of the Llama-shaped workloads, exactly as the benchmark launches them.
+    amax / scales / codes compared in full; Y, dX, dW on at least 64 whole rows and 64 whole
+    columns each (seeded, plus the lines on both sides of 256-tile boundaries), computed by the
+    oracle from the same codes."""
     w = wl.WORKLOADS[key]
     X, W, dY = wl.make_linear_inputs(w, li)
     Y, dX, dW, saved = run_linear(X, W, dY, rowwise, grad_fmt)
