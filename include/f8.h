@@ -128,6 +128,38 @@ f8_status f8_amax_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t l
                        int64_t ld_out_t, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The other two per-tensor scaling strategies the paper's Float8 section names
+ * beside dynamic scaling: DELAYED (the scale comes from the amax values of
+ * earlier steps) and STATIC (the scale is a constant the caller chose).  In
+ * both the scale is known before the tensor is read, so the cast is a single
+ * pass over x (2 B read + 1 B written per element and orientation) instead of
+ * dynamic scaling's two.  Tensorwise only.
+ *
+ * f8_cast_amax: f8_cast with a tensorwise scale[0] that also measures
+ * amax_out[0] = max |x| in the same pass (the value delayed scaling records for
+ * later steps).  Codes are identical to f8_cast with the same scale; values
+ * beyond the scale's range saturate to +-FMAX.
+ * workspace: f8_workspace_bytes(rows, cols) bytes.
+ */
+f8_status f8_cast_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+                       f8_format fmt, uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t,
+                       float* amax_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Delayed scaling's amax history: history[0] is the newest entry,
+ * history[len-1] the oldest, 1 <= len <= F8_MAX_HISTORY.  The call drops the
+ * oldest entry, shifts the rest by one, stores amax_new[0] at history[0], then
+ * writes scale_out[0] = FMAX(fmt) / max(max(history), 1e-12f) and
+ * inv_scale_out[0] = 1 / scale_out[0] (inv_scale_out may be NULL).  A fresh
+ * history is all zeros; an all-zero history gives the scale of an all-zero
+ * tensor (FMAX / 1e-12f), so seed it with one measured amax before the first
+ * delayed cast.
+ */
+#define F8_MAX_HISTORY 1024
+f8_status f8_amax_history_push(float* history, int64_t len, const float* amax_new, f8_format fmt,
+                               float* scale_out, float* inv_scale_out, void* stream);
+
+/*
  * fp8 GEMM with fp32 accumulation and bf16 output:
  *   D[m,n] = bf16_rne( (sum_k dec(A)[m,k] * dec(B)[n,k]) * inv_scale_a * inv_scale_b )
  * fa / fb: format of A / B codes (mixed E5M2 x E4M3 is allowed).
@@ -193,6 +225,46 @@ f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, v
  */
 f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved, void* dX,
                         void* dW, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The linear layer under delayed or static scaling (tensorwise; the
+ * descriptor's granularity must be F8_TENSORWISE).
+ *
+ * state->mode = F8_DELAYED: every tensor T in {X, W, dY} is cast with the
+ *   scale found in state->scale_T[0] when the call starts.  saved->T then
+ *   holds the codes, that scale, its reciprocal, and the amax of THIS step's
+ *   tensor; the amax is pushed into state->hist_T (f8_amax_history_push) and
+ *   state->scale_T[0] becomes the scale for the next step.  Seed each
+ *   scale_T / hist_T before the first step (e.g. f8_amax on a first batch, then
+ *   f8_amax_history_push).
+ * state->mode = F8_STATIC: every tensor is cast with state->scale_T[0], which
+ *   is never modified; saved->T gets the codes, the scale and its reciprocal;
+ *   saved->T.amax is not written and the hist_* members are unused.
+ * state->mode = F8_DYNAMIC: same as f8_linear_fwd / f8_linear_bwd; the state's
+ *   pointers are unused.
+ * The forward call uses the x and w members of the state, the backward call
+ * the dy members.  All state members are caller-owned device memory.
+ */
+typedef enum { F8_DYNAMIC = 0, F8_DELAYED = 1, F8_STATIC = 2 } f8_scaling;
+
+typedef struct f8_scaling_state {
+    int32_t mode;        /* f8_scaling */
+    int32_t history_len; /* entries of each hist_* array (F8_DELAYED), 1 .. F8_MAX_HISTORY */
+    float* hist_x;
+    float* hist_w;
+    float* hist_dy;
+    float* scale_x; /* 1 entry each: the scale the next cast of that tensor uses */
+    float* scale_w;
+    float* scale_dy;
+} f8_scaling_state;
+
+f8_status f8_linear_fwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* X,
+                               const void* W, void* Y, f8_saved* saved, void* workspace,
+                               size_t workspace_bytes, void* stream);
+
+f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* dY,
+                               f8_saved* saved, void* dX, void* dW, void* workspace,
+                               size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

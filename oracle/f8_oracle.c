@@ -398,6 +398,32 @@ void f8o_linear_bwd(int64_t M, int64_t K, int64_t N, int rowwise, int grad_fmt,
     }
 }
 
+/* ---- delayed and static scaling --------------------------------------------
+ * The paper's Float8 section names three per-tensor scaling strategies: dynamic,
+ * delayed and static, without spelling out the last two.  The reading used
+ * here:
+ *   static  - the scale is a constant chosen beforehand; the cast is
+ *             f8o_cast with that scale, nothing else changes.
+ *   delayed - the scale used at a step comes from the amax values recorded at
+ *             EARLIER steps: FMAX / max(max(history), 1e-12) over a window of
+ *             the last `len` recorded values.  The tensor of the current step is
+ *             cast with that scale (values beyond its range saturate) and its
+ *             own amax is recorded afterwards, for later steps.
+ * history[0] is the newest entry, history[len-1] the oldest. */
+
+/* Record amax_new (dropping the oldest entry), then derive the scale of the
+ * next step from the updated window. */
+void f8o_history_push(float* history, int64_t len, float amax_new, int fmt, float* scale,
+                      float* inv_scale)
+{
+    for (int64_t i = len - 1; i >= 1; --i) history[i] = history[i - 1];
+    history[0] = amax_new;
+    float window_max = 0.0f;
+    for (int64_t i = 0; i < len; ++i)
+        if (history[i] > window_max) window_max = history[i];
+    f8o_scale(&window_max, 1, fmt, scale, inv_scale);
+}
+
 int f8o_num_threads(void)
 {
     int n = 1;

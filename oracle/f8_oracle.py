@@ -56,6 +56,8 @@ def _declare(l):
     l.f8o_amax.argtypes = [_p, _i64, _i64, _i64, _int, _p]
     l.f8o_scale.restype = None
     l.f8o_scale.argtypes = [_p, _i64, _int, _p, _p]
+    l.f8o_history_push.restype = None
+    l.f8o_history_push.argtypes = [_p, _i64, _f32, _int, _p, _p]
     l.f8o_cast.restype = None
     l.f8o_cast.argtypes = [_p, _i64, _i64, _i64, _p, _int, _int, _p, _i64, _p, _i64]
     l.f8o_gemm.restype = None
@@ -252,6 +254,64 @@ def linear_bwd(dY_bits, xq, wq, rowwise=False, grad_fmt=E4M3):
     xs, ws, ds = xq.struct(), wq.struct(), dyq.struct()
     lib().f8o_linear_bwd(M, K, N, int(rowwise), grad_fmt, _ptr(dY), C.byref(xs), C.byref(ws),
                          C.byref(ds), _ptr(dX), _ptr(dW))
+    return dX, dW, dyq
+
+
+# ---- delayed / static scaling (tensorwise) ------------------------------------------
+
+DYNAMIC, DELAYED, STATIC = 0, 1, 2
+
+
+def history_push(history, amax_new, fmt):
+    """In place: record amax_new in `history` (float32, newest first).  Returns the scale of
+    the next step and its reciprocal, as float32 arrays of one element."""
+    assert history.dtype == np.float32 and history.flags.c_contiguous
+    s, inv = np.empty(1, np.float32), np.empty(1, np.float32)
+    lib().f8o_history_push(_ptr(history), history.size, float(np.float32(amax_new)), fmt, _ptr(s), _ptr(inv))
+    return s, inv
+
+
+class ScalingState:
+    """Per tensor (x, w, dy): the amax history (zeros at first) and the scale the next cast uses."""
+
+    def __init__(self, mode, history_len=16):
+        self.mode = mode
+        self.hist = {k: np.zeros(history_len, np.float32) for k in ("x", "w", "dy")}
+        self.scale = {k: np.ones(1, np.float32) for k in ("x", "w", "dy")}
+
+
+def _quantise_scaled(bits, fmt, state, key):
+    """One tensor under delayed or static scaling.  Returns a tensorwise Quantised whose scale
+    is the one the codes were made with; amax is this step's (delayed) or None (static)."""
+    rows, cols = bits.shape
+    q = Quantised(rows, cols, False)
+    s = state.scale[key].copy()
+    q.scale[:] = s
+    q.inv_scale[:] = np.float32(1.0) / s
+    q.q[:] = cast(bits, s, TENSORWISE, fmt)
+    if state.mode == DELAYED:
+        q.amax[:] = amax(bits, TENSORWISE)
+        state.scale[key], _ = history_push(state.hist[key], q.amax[0], fmt)
+    else:
+        q.amax = None
+    return q
+
+
+def linear_fwd_scaled(X_bits, W_bits, state):
+    """Forward under delayed / static scaling.  Returns (Y bits, xq, wq); updates `state`."""
+    X, W = _c(X_bits, np.uint16), _c(W_bits, np.uint16)
+    xq = _quantise_scaled(X, E4M3, state, "x")
+    wq = _quantise_scaled(W, E4M3, state, "w")
+    Y = gemm(NT, xq.q, E4M3, wq.q, E4M3, xq.inv_scale, wq.inv_scale, TENSORWISE)
+    return Y, xq, wq
+
+
+def linear_bwd_scaled(dY_bits, xq, wq, state, grad_fmt=E4M3):
+    """Backward under delayed / static scaling.  Returns (dX bits, dW bits, dyq)."""
+    dY = _c(dY_bits, np.uint16)
+    dyq = _quantise_scaled(dY, grad_fmt, state, "dy")
+    dX = gemm(NN, dyq.q, grad_fmt, wq.q, E4M3, dyq.inv_scale, wq.inv_scale, TENSORWISE)
+    dW = gemm(TN, dyq.q, grad_fmt, xq.q, E4M3, dyq.inv_scale, xq.inv_scale, TENSORWISE)
     return dX, dW, dyq
 
 

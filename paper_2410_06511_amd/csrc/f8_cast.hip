@@ -189,6 +189,55 @@ __global__ __launch_bounds__(kThreads) void scale_kernel(const float* __restrict
 }
 
 // ---------------------------------------------------------------------------
+// delayed scaling: amax history (one block)
+// ---------------------------------------------------------------------------
+// The step's amax is max(partial[0..npartial)) if partial is given, else amax_in[0].
+//   used_scale (nullable): the scale this step's cast used; it and its reciprocal are
+//     copied to saved_scale / saved_inv for the GEMM epilogues of this step.
+//   history[0..len): newest first; shifted by one, the step's amax enters at [0].
+//   next_scale / next_inv (nullable inv): FMAX / max(max(history), eps) for the next step.
+// used_scale and next_scale may be the same address: it is read before it is written.
+__global__ __launch_bounds__(kThreads) void history_push_kernel(
+    const uint32_t* __restrict__ partial, int npartial, const float* __restrict__ amax_in,
+    float* __restrict__ history, int len, float fm, float* __restrict__ amax_out,
+    const float* used_scale, float* __restrict__ saved_scale, float* __restrict__ saved_inv,
+    float* next_scale, float* __restrict__ next_inv)
+{
+    __shared__ uint32_t red[kWaves];
+    float a;
+    if (partial) a = mag_to_float(reduce_partials(partial, npartial, red));
+    else a = amax_in[0];
+    if (threadIdx.x != 0) return;
+    if (amax_out) amax_out[0] = a;
+    if (used_scale) {
+        const float s = used_scale[0];
+        saved_scale[0] = s;
+        saved_inv[0] = 1.0f / s;
+    }
+    float m = a;
+    for (int i = len - 1; i >= 1; --i) {
+        const float h = history[i - 1];
+        history[i] = h;
+        m = h > m ? h : m;
+    }
+    if (len > 0) history[0] = a;
+    if (next_scale) {
+        const float s = scale_from_amax(m, fm);
+        next_scale[0] = s;
+        if (next_inv) next_inv[0] = 1.0f / s;
+    }
+}
+
+// copies a given scale and its reciprocal (static scaling: the GEMM epilogue reads 1/scale)
+__global__ void publish_scale_kernel(const float* __restrict__ s_in, float* __restrict__ s_out,
+                                     float* __restrict__ inv_out)
+{
+    const float s = s_in[0];
+    s_out[0] = s;
+    inv_out[0] = 1.0f / s;
+}
+
+// ---------------------------------------------------------------------------
 // cast, streaming form (no transposed output): tensorwise or per-row scales
 // ---------------------------------------------------------------------------
 // DYN: the scale is derived here from the partial maxima of the amax kernel
@@ -258,13 +307,16 @@ __device__ inline void transpose4x4(const uint32_t r[4], uint32_t c[4])
     c[3] = (t1 >> 16) | (t3 & 0xFFFF0000u);
 }
 
-template <int FMT, int GRAN, bool DYN, bool OUT, bool OUT_T>
+// MEASURE (delayed scaling): the scale is given, and the block also writes the largest
+// magnitude of its own tile to partial_out[blockIdx.x], so that the tensor's amax of this step
+// comes out of the same single pass over x.
+template <int FMT, int GRAN, bool DYN, bool OUT, bool OUT_T, bool MEASURE = false>
 __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ld,
     const float* __restrict__ scale, const uint32_t* __restrict__ partial, int npartial,
     float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out,
     uint8_t* __restrict__ out, int64_t ld_out, uint8_t* __restrict__ out_t, int64_t ld_out_t,
-    int tiles_c)
+    int tiles_c, uint32_t* __restrict__ partial_out = nullptr)
 {
     __shared__ uint32_t red[kWaves];
     __shared__ uint32_t tile[kTile * kLdsStride];
@@ -304,6 +356,13 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
         const int64_t r = r0 + rr + 16 * i;
         v[i] = make_uint4(0, 0, 0, 0);
         if (col_ok && r < rows) v[i] = *reinterpret_cast<const uint4*>(x + r * ld + col);
+    }
+    if constexpr (MEASURE) {
+        uint32_t acc = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = absmax_acc(acc, v[i]);  // out-of-range chunks are zero
+        const uint32_t m = block_max_u32<kWaves>(pk_collapse(acc), red);
+        if (threadIdx.x == 0) partial_out[blockIdx.x] = m;
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -408,6 +467,10 @@ size_t workspace_bytes(int64_t max_rows, int64_t max_cols)
     size_t tensor = (size_t)kMaxPartials * sizeof(uint32_t);
     size_t colw = (size_t)kColChunksMax * (size_t)d * sizeof(uint32_t);
     size_t n = tensor > colw ? tensor : colw;
+    // one partial per 128x128 tile of the measuring cast (delayed scaling)
+    const int64_t r = max_rows > 0 ? max_rows : 0, c = max_cols > 0 ? max_cols : 0;
+    size_t tiles = (size_t)((r + kTile - 1) / kTile) * (size_t)((c + kTile - 1) / kTile) * sizeof(uint32_t);
+    n = tiles > n ? tiles : n;
     return (n + 255) / 256 * 256;
 }
 
@@ -543,6 +606,58 @@ f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g,
                               out, ld_out, out_t, ld_out_t, st);
 }
 
+// Tensorwise cast with a given scale that also leaves one partial maximum per 128x128 tile in
+// ws (checked tensor).  *npartial = number of partials written (0 for an empty tensor).
+f8_status cast_measure(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
+                       uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, void* ws,
+                       size_t ws_bytes, int* npartial, hipStream_t st)
+{
+    *npartial = 0;
+    if (rows == 0 || cols == 0) return F8_OK;
+    const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (cols + kTile - 1) / kTile;
+    const int64_t nb = tiles_r * tiles_c;
+    if (nb > (int64_t)0x7FFFFFFF || (size_t)nb * sizeof(uint32_t) > ws_bytes) return F8_ERR_WORKSPACE;
+#define F8_LAUNCH_MEASURE(F, O, T)                                                                   \
+    cast_tile_kernel<F, F8_TENSORWISE, false, O, T, true><<<(unsigned)nb, kThreads, 0, st>>>(        \
+        (const uint16_t*)x, rows, cols, ld, scale, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, \
+        out_t, ld_out_t, (int)tiles_c, (uint32_t*)ws)
+#define F8_MEASURE_FMT(F)                               \
+    do {                                                \
+        if (out && out_t) F8_LAUNCH_MEASURE(F, true, true);  \
+        else if (out_t) F8_LAUNCH_MEASURE(F, false, true);   \
+        else F8_LAUNCH_MEASURE(F, true, false);              \
+    } while (0)
+    if (fmt == F8_E4M3) F8_MEASURE_FMT(F8_E4M3);
+    else F8_MEASURE_FMT(F8_E5M2);
+#undef F8_MEASURE_FMT
+#undef F8_LAUNCH_MEASURE
+    *npartial = (int)nb;
+    return last_launch_status();
+}
+
+f8_status history_push(const void* partial, int npartial, const float* amax_in, float* history, int64_t len,
+                       int fmt, float* amax_out, const float* used_scale, float* saved_scale,
+                       float* saved_inv, float* next_scale, float* next_inv, hipStream_t st)
+{
+    history_push_kernel<<<1, kThreads, 0, st>>>((const uint32_t*)partial, npartial, amax_in, history, (int)len,
+                                                fmax_of(fmt), amax_out, used_scale, saved_scale, saved_inv,
+                                                next_scale, next_inv);
+    return last_launch_status();
+}
+
+f8_status publish_scale(const float* s_in, float* s_out, float* inv_out, hipStream_t st)
+{
+    publish_scale_kernel<<<1, 1, 0, st>>>(s_in, s_out, inv_out);
+    return last_launch_status();
+}
+
+f8_status cast_given(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
+                     uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, hipStream_t st)
+{
+    return launch_cast<false>(x, rows, cols, ld, scale, F8_TENSORWISE, fmt, nullptr, 0, nullptr, nullptr, nullptr,
+                              out, ld_out, out_t, ld_out_t, st);
+}
+
 }  // namespace f8
 
 using namespace f8;
@@ -604,6 +719,36 @@ f8_status f8_amax_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t l
     if (g != F8_ROWWISE && (!workspace || workspace_bytes_ < workspace_bytes(rows, cols))) return F8_ERR_WORKSPACE;
     return quantise(x_bf16, rows, cols, ld, g, fmt, amax_out, scale_out, inv_scale_out, out, ld_out, out_t,
                     ld_out_t, workspace, (hipStream_t)stream);
+}
+
+f8_status f8_cast_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, const float* scale,
+                       f8_format fmt, uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t,
+                       float* amax_out, void* workspace, size_t workspace_bytes_, void* stream)
+{
+    if ((int)fmt < 0 || (int)fmt > F8_E5M2) return F8_ERR_ENUM;
+    f8_status s = check_matrix(x_bf16, rows, cols, ld);
+    if (s != F8_OK) return s;
+    if (!scale || !amax_out) return F8_ERR_NULL;
+    s = check_cast_outputs(rows, cols, out, ld_out, out_t, ld_out_t);
+    if (s != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return F8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    int np = 0;
+    s = cast_measure(x_bf16, rows, cols, ld, scale, fmt, out, ld_out, out_t, ld_out_t, workspace,
+                     workspace_bytes_, &np, st);
+    if (s != F8_OK) return s;
+    amax_tensor_final_kernel<<<1, kThreads, 0, st>>>((const uint32_t*)workspace, np, 0.0f, amax_out, nullptr, nullptr);
+    return last_launch_status();
+}
+
+f8_status f8_amax_history_push(float* history, int64_t len, const float* amax_new, f8_format fmt,
+                               float* scale_out, float* inv_scale_out, void* stream)
+{
+    if ((int)fmt < 0 || (int)fmt > F8_E5M2) return F8_ERR_ENUM;
+    if (!history || !amax_new || !scale_out) return F8_ERR_NULL;
+    if (len < 1 || len > F8_MAX_HISTORY) return F8_ERR_SHAPE;
+    return history_push(nullptr, 0, amax_new, history, len, fmt, nullptr, nullptr, nullptr, nullptr, scale_out,
+                        inv_scale_out, (hipStream_t)stream);
 }
 
 f8_status f8_encode_f32(const float* y, int64_t n, f8_format fmt, int use_hw_convert, uint8_t* out,

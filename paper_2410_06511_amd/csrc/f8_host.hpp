@@ -19,6 +19,20 @@ f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g,
                    float* amax_out, float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,
                    uint8_t* out_t, int64_t ld_out_t, void* ws, hipStream_t st);
 
+// Delayed / static scaling pieces (tensorwise, validated arguments).
+// cast with a given scale, leaving one partial maximum per 128x128 tile in ws
+f8_status cast_measure(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
+                       uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, void* ws,
+                       size_t ws_bytes, int* npartial, hipStream_t st);
+// step amax (from partials, or amax_in) -> amax_out; used_scale -> saved_scale, 1/x -> saved_inv;
+// history shifted and extended; FMAX / max(history) -> next_scale (, 1/x -> next_inv)
+f8_status history_push(const void* partial, int npartial, const float* amax_in, float* history, int64_t len,
+                       int fmt, float* amax_out, const float* used_scale, float* saved_scale,
+                       float* saved_inv, float* next_scale, float* next_inv, hipStream_t st);
+f8_status publish_scale(const float* s_in, float* s_out, float* inv_out, hipStream_t st);
+f8_status cast_given(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
+                     uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, hipStream_t st);
+
 // Validated GEMM launch (see f8_gemm).
 f8_status gemm(int layout, int64_t M, int64_t N, int64_t K, const uint8_t* A, int fa, int64_t lda,
                const uint8_t* B, int fb, int64_t ldb, const float* isa, const float* isb, int g,

@@ -54,6 +54,38 @@ static f8_status quantise_both(const void* T, int64_t rows, int64_t cols, bool r
                     q->q_t, rows, ws, st);
 }
 
+// One tensor under delayed or static scaling: cast with the state's scale into both
+// orientations; delayed also records the tensor's amax and derives the next scale.
+static f8_status quantise_scaled(const void* T, int64_t rows, int64_t cols, int fmt, int mode, int64_t hist_len,
+                                 float* hist, float* state_scale, const f8_qtensor* q, void* ws,
+                                 size_t ws_bytes, hipStream_t st)
+{
+    f8_status s;
+    if (mode == F8_STATIC) {
+        if ((s = cast_given(T, rows, cols, cols, state_scale, fmt, q->q, cols, q->q_t, rows, st)) != F8_OK) return s;
+        return publish_scale(state_scale, q->scale, q->inv_scale, st);
+    }
+    int np = 0;
+    if ((s = cast_measure(T, rows, cols, cols, state_scale, fmt, q->q, cols, q->q_t, rows, ws, ws_bytes, &np,
+                          st)) != F8_OK)
+        return s;
+    return history_push(ws, np, nullptr, hist, hist_len, fmt, q->amax, state_scale, q->scale, q->inv_scale,
+                        state_scale, nullptr, st);
+}
+
+static f8_status check_state(const f8_scaling_state* st, bool fwd)
+{
+    if (!st) return F8_ERR_NULL;
+    if (st->mode != F8_DYNAMIC && st->mode != F8_DELAYED && st->mode != F8_STATIC) return F8_ERR_ENUM;
+    if (st->mode == F8_DYNAMIC) return F8_OK;
+    if (fwd ? (!st->scale_x || !st->scale_w) : !st->scale_dy) return F8_ERR_NULL;
+    if (st->mode == F8_DELAYED) {
+        if (st->history_len < 1 || st->history_len > F8_MAX_HISTORY) return F8_ERR_SHAPE;
+        if (fwd ? (!st->hist_x || !st->hist_w) : !st->hist_dy) return F8_ERR_NULL;
+    }
+    return F8_OK;
+}
+
 }  // namespace f8
 
 using namespace f8;
@@ -119,6 +151,60 @@ f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved
     const float* x_is = rw ? saved->x.inv_scale_t : saved->x.inv_scale;
     return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, dy_is, x_is, d->granularity,
                 dW, K, st);
+}
+
+f8_status f8_linear_fwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* X,
+                               const void* W, void* Y, f8_saved* saved, void* workspace,
+                               size_t workspace_bytes_, void* stream)
+{
+    f8_status s = check_state(state, true);
+    if (s != F8_OK) return s;
+    if (state->mode == F8_DYNAMIC) return f8_linear_fwd(d, X, W, Y, saved, workspace, workspace_bytes_, stream);
+    if ((s = check_desc(d)) != F8_OK) return s;
+    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
+    if (!X || !W || !Y || !saved) return F8_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return F8_ERR_ALIGN;
+    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t M = d->M, K = d->K, N = d->N;
+    if ((s = quantise_scaled(X, M, K, F8_E4M3, state->mode, state->history_len, state->hist_x, state->scale_x,
+                             &saved->x, workspace, workspace_bytes_, st)) != F8_OK)
+        return s;
+    if ((s = quantise_scaled(W, N, K, F8_E4M3, state->mode, state->history_len, state->hist_w, state->scale_w,
+                             &saved->w, workspace, workspace_bytes_, st)) != F8_OK)
+        return s;
+    return gemm(F8_NT, M, N, K, saved->x.q, F8_E4M3, K, saved->w.q, F8_E4M3, K, saved->x.inv_scale,
+                saved->w.inv_scale, F8_TENSORWISE, Y, N, st);
+}
+
+f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* dY,
+                               f8_saved* saved, void* dX, void* dW, void* workspace,
+                               size_t workspace_bytes_, void* stream)
+{
+    f8_status s = check_state(state, false);
+    if (s != F8_OK) return s;
+    if (state->mode == F8_DYNAMIC) return f8_linear_bwd(d, dY, saved, dX, dW, workspace, workspace_bytes_, stream);
+    if ((s = check_desc(d)) != F8_OK) return s;
+    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
+    if (!dY || !dX || !dW || !saved) return F8_ERR_NULL;
+    if (!aligned16(dY) || !aligned16(dX) || !aligned16(dW)) return F8_ERR_ALIGN;
+    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
+    if ((s = check_q(&saved->dy, false)) != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t M = d->M, K = d->K, N = d->N;
+    const int gf = d->grad_format;
+    if ((s = quantise_scaled(dY, M, N, gf, state->mode, state->history_len, state->hist_dy, state->scale_dy,
+                             &saved->dy, workspace, workspace_bytes_, st)) != F8_OK)
+        return s;
+    if ((s = gemm(F8_NT, M, K, N, saved->dy.q, gf, N, saved->w.q_t, F8_E4M3, N, saved->dy.inv_scale,
+                  saved->w.inv_scale, F8_TENSORWISE, dX, K, st)) != F8_OK)
+        return s;
+    return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, saved->dy.inv_scale,
+                saved->x.inv_scale, F8_TENSORWISE, dW, K, st);
 }
 
 }  // extern "C"

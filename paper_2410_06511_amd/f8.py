@@ -13,6 +13,8 @@ import torch
 E4M3, E5M2 = 0, 1
 TENSORWISE, ROWWISE, COLWISE = 0, 1, 2
 NT, NN, TN = 0, 1, 2
+DYNAMIC, DELAYED, STATIC = 0, 1, 2
+MAX_HISTORY = 1024
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libf8.so")
@@ -21,7 +23,8 @@ _lib = None
 _i64, _int, _p = C.c_int64, C.c_int, C.c_void_p
 
 EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_cast", "f8_encode_f32",
-           "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd"]
+           "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
+           "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled"]
 
 
 class F8Error(RuntimeError):
@@ -43,6 +46,11 @@ class LinearDesc(C.Structure):
     _fields_ = [("M", _i64), ("K", _i64), ("N", _i64), ("granularity", C.c_int32), ("grad_format", C.c_int32)]
 
 
+class ScalingStateStruct(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("history_len", C.c_int32), ("hist_x", _p), ("hist_w", _p), ("hist_dy", _p),
+                ("scale_x", _p), ("scale_w", _p), ("scale_dy", _p)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -62,6 +70,12 @@ def lib():
         l.f8_gemm.argtypes = [_int, _i64, _i64, _i64, _p, _int, _i64, _p, _int, _i64, _p, _p, _int, _p, _i64, _p]
         l.f8_linear_fwd.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         l.f8_linear_bwd.argtypes = [C.POINTER(LinearDesc), _p, C.POINTER(SavedStruct), _p, _p, _p, C.c_size_t, _p]
+        l.f8_cast_amax.argtypes = [_p, _i64, _i64, _i64, _p, _int, _p, _i64, _p, _i64, _p, _p, C.c_size_t, _p]
+        l.f8_amax_history_push.argtypes = [_p, _i64, _p, _int, _p, _p, _p]
+        l.f8_linear_fwd_scaled.argtypes = [C.POINTER(LinearDesc), C.POINTER(ScalingStateStruct), _p, _p, _p,
+                                           C.POINTER(SavedStruct), _p, C.c_size_t, _p]
+        l.f8_linear_bwd_scaled.argtypes = [C.POINTER(LinearDesc), C.POINTER(ScalingStateStruct), _p,
+                                           C.POINTER(SavedStruct), _p, _p, _p, C.c_size_t, _p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
         _lib = l
@@ -182,3 +196,47 @@ def linear_bwd(desc, dY, saved, dX, dW, workspace, stream=None):
     wp, wb = _ws(workspace)
     _check(lib().f8_linear_bwd(C.byref(desc), _ptr(dY), C.byref(saved.struct()), _ptr(dX), _ptr(dW), wp, wb,
                                _stream(stream)))
+
+
+# ---- delayed / static scaling ----------------------------------------------------
+
+def cast_amax(x, scale_t, fmt, amax_out, out=None, out_t=None, workspace=None, stream=None):
+    rows, cols = x.shape
+    wp, wb = _ws(workspace)
+    _check(lib().f8_cast_amax(_ptr(x), rows, cols, x.stride(0), _ptr(scale_t), fmt,
+                              _ptr(out), 0 if out is None else out.stride(0),
+                              _ptr(out_t), 0 if out_t is None else out_t.stride(0), _ptr(amax_out), wp, wb,
+                              _stream(stream)))
+
+
+def amax_history_push(history, amax_new, fmt, scale_out, inv_scale_out=None, stream=None):
+    _check(lib().f8_amax_history_push(_ptr(history), history.numel(), _ptr(amax_new), fmt, _ptr(scale_out),
+                                      _ptr(inv_scale_out), _stream(stream)))
+
+
+class ScalingState:
+    """Device buffers of f8_scaling_state: per tensor (x, w, dy) an amax history (newest first,
+    zero-initialised) and the scale the next cast uses."""
+
+    def __init__(self, mode, history_len=16, device="cuda"):
+        f32 = dict(dtype=torch.float32, device=device)
+        self.mode, self.history_len = mode, history_len
+        self.hist_x, self.hist_w, self.hist_dy = (torch.zeros(history_len, **f32) for _ in range(3))
+        self.scale_x, self.scale_w, self.scale_dy = (torch.ones(1, **f32) for _ in range(3))
+        self._struct = ScalingStateStruct(mode, history_len, _ptr(self.hist_x), _ptr(self.hist_w), _ptr(self.hist_dy),
+                                          _ptr(self.scale_x), _ptr(self.scale_w), _ptr(self.scale_dy))
+
+    def struct(self):
+        return self._struct
+
+
+def linear_fwd_scaled(desc, state, X, W, Y, saved, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().f8_linear_fwd_scaled(C.byref(desc), C.byref(state.struct()), _ptr(X), _ptr(W), _ptr(Y),
+                                      C.byref(saved.struct()), wp, wb, _stream(stream)))
+
+
+def linear_bwd_scaled(desc, state, dY, saved, dX, dW, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().f8_linear_bwd_scaled(C.byref(desc), C.byref(state.struct()), _ptr(dY), C.byref(saved.struct()),
+                                      _ptr(dX), _ptr(dW), wp, wb, _stream(stream)))

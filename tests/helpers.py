@@ -57,3 +57,23 @@ def assert_gemm_tight(got_bits, d64, dabs, K, what=""):
     bound = 2.0 ** -8 * np.abs(d64) * (1 + 2.0 ** -7) + (MFMA_GROUP_REL + 2.0 * K * 2.0 ** -24) * dabs + 1e-38
     bad = np.abs(got - d64) > bound
     assert not bad.any(), (what, int(bad.sum()), np.argwhere(bad)[:4])
+
+
+def sample_lines(n_lines, rng, n=64, tile=256):
+    """Indices of whole output rows (or columns) to compare: n seeded random ones, the first
+    and the last, and both sides of the first, the last and three random 256-tile boundaries."""
+    picks = set(rng.integers(0, n_lines, n).tolist()) | {0, n_lines - 1}
+    nb = (n_lines - 1) // tile  # boundaries at tile, 2 * tile, ..., nb * tile
+    if nb >= 1:
+        for t in {1, nb} | set(rng.integers(1, nb + 1, 3).tolist()):
+            picks |= {t * tile - 1, t * tile}
+    return sorted(picks)
+
+
+def sampled_check(name, got, layout, A, fa, B, fb, isa, isb, g, rng):
+    M, N = got.shape
+    rows, cols = sample_lines(M, rng), sample_lines(N, rng)
+    ms, ns = np.repeat(rows, N), np.tile(np.arange(N), len(rows))
+    assert_gemm_close(got[ms, ns], o.gemm_points(layout, A, fa, B, fb, isa, isb, ms, ns, g), name + " rows")
+    ns, ms = np.repeat(cols, M), np.tile(np.arange(M), len(cols))
+    assert_gemm_close(got[ms, ns], o.gemm_points(layout, A, fa, B, fb, isa, isb, ms, ns, g), name + " cols")

@@ -6,7 +6,7 @@ import torch
 import oracle as o
 from paper_2410_06511_amd import f8
 from paper_2410_06511_amd import workloads as wl
-from helpers import bits, u8, f32, assert_gemm_close
+from helpers import bits, u8, f32, assert_gemm_close, sampled_check
 
 pytestmark = pytest.mark.gpu
 
@@ -99,26 +99,6 @@ def test_linear_exact_case_bit_for_bit():
         assert np.array_equal(bits(dW), ex(d64.T @ x64))
 
 
-def _sample_lines(n_lines, rng, n=64, tile=256):
-    """Indices of whole output rows (or columns) to compare: n seeded random ones, the first
-    and the last, and both sides of the first, the last and three random 256-tile boundaries."""
-    picks = set(rng.integers(0, n_lines, n).tolist()) | {0, n_lines - 1}
-    nb = (n_lines - 1) // tile  # boundaries at tile, 2 * tile, ..., nb * tile
-    if nb >= 1:
-        for t in {1, nb} | set(rng.integers(1, nb + 1, 3).tolist()):
-            picks |= {t * tile - 1, t * tile}
-    return sorted(picks)
-
-
-def _sampled_check(name, got, layout, A, fa, B, fb, isa, isb, g, rng):
-    M, N = got.shape
-    rows, cols = _sample_lines(M, rng), _sample_lines(N, rng)
-    ms, ns = np.repeat(rows, N), np.tile(np.arange(N), len(rows))
-    assert_gemm_close(got[ms, ns], o.gemm_points(layout, A, fa, B, fb, isa, isb, ms, ns, g), name + " rows")
-    ns, ms = np.repeat(cols, M), np.tile(np.arange(M), len(cols))
-    assert_gemm_close(got[ms, ns], o.gemm_points(layout, A, fa, B, fb, isa, isb, ms, ns, g), name + " cols")
-
-
 def _full_size_cases():
     """Every distinct linear shape of every Llama-shaped workload, in each of the variants the
     workload is run in (tensorwise / rowwise scaling, e4m3 / e5m2 gradients)."""
@@ -155,18 +135,18 @@ def test_full_size_linear(key, li, rowwise, grad_fmt):
     for q, (a, s, i, c) in ((saved.x, (ax, sx, isx, qx)), (saved.w, (aw, sw, isw, qw)), (saved.dy, (ady, sdy, isdy, qdy))):
         assert np.array_equal(f32(q.amax), a) and np.array_equal(f32(q.scale), s) and np.array_equal(f32(q.inv_scale), i)
         assert np.array_equal(u8(q.q), c)
-    _sampled_check("Y", bits(Y), o.NT, qx, o.E4M3, qw, o.E4M3, isx, isw, g, rng)
+    sampled_check("Y", bits(Y), o.NT, qx, o.E4M3, qw, o.E4M3, isx, isw, g, rng)
     if not rowwise:
         assert torch.equal(saved.x.q_t, saved.x.q.t().contiguous())
         assert torch.equal(saved.w.q_t, saved.w.q.t().contiguous())
         assert torch.equal(saved.dy.q_t, saved.dy.q.t().contiguous())
-        _sampled_check("dX", bits(dX), o.NN, qdy, grad_fmt, qw, o.E4M3, isdy, isw, g, rng)
-        _sampled_check("dW", bits(dW), o.TN, qdy, grad_fmt, qx, o.E4M3, isdy, isx, g, rng)
+        sampled_check("dX", bits(dX), o.NN, qdy, grad_fmt, qw, o.E4M3, isdy, isw, g, rng)
+        sampled_check("dW", bits(dW), o.TN, qdy, grad_fmt, qx, o.E4M3, isdy, isx, g, rng)
     else:
         _, _, iswc, qwc = o.amax_cast(wb, o.COLWISE, o.E4M3)
         _, _, isxc, qxc = o.amax_cast(xb, o.COLWISE, o.E4M3)
         _, _, isdyc, qdyc = o.amax_cast(dyb, o.COLWISE, grad_fmt)
         assert np.array_equal(u8(saved.w.q_t), qwc.T) and np.array_equal(u8(saved.x.q_t), qxc.T)
         assert np.array_equal(u8(saved.dy.q_t), qdyc.T)
-        _sampled_check("dX", bits(dX), o.NN, qdy, grad_fmt, qwc, o.E4M3, isdy, iswc, g, rng)
-        _sampled_check("dW", bits(dW), o.TN, qdyc, grad_fmt, qxc, o.E4M3, isdyc, isxc, g, rng)
+        sampled_check("dX", bits(dX), o.NN, qdy, grad_fmt, qwc, o.E4M3, isdy, iswc, g, rng)
+        sampled_check("dW", bits(dW), o.TN, qdyc, grad_fmt, qxc, o.E4M3, isdyc, isxc, g, rng)

@@ -397,3 +397,116 @@ def test_linear_is_composition_of_steps(rowwise):
     ref = xf @ wf.T
     err = np.abs(o.bf16_to_f32(Y) - ref).max() / np.abs(ref).max()
     assert err < 0.08
+
+
+# ---- delayed and static scaling ---------------------------------------------------------
+# The paper only names these two strategies; the reading (window maximum of earlier steps'
+# amax values; a constant scale) is the oracle's own.  The pins below tie it to things the
+# reading fixes independently: a sliding-window maximum by another route, the shift order,
+# the dynamic path (already pinned above) at the points where the strategies must coincide,
+# and saturation when the recorded history underestimates the tensor.
+
+@pytest.mark.parametrize("fmt", [o.E4M3, o.E5M2])
+@pytest.mark.parametrize("H", [1, 3, 16])
+def test_history_push_is_a_sliding_window_maximum(fmt, H):
+    rng = np.random.default_rng(H)
+    a = np.abs(rng.standard_normal(40)).astype(np.float32) * np.float32(3.0)
+    a[7] = 0.0
+    hist = np.zeros(H, np.float32)
+    padded = np.concatenate([np.zeros(H - 1, np.float32), a])
+    window_max = np.lib.stride_tricks.sliding_window_view(padded, H).max(axis=1)
+    for t in range(a.size):
+        s, inv = o.history_push(hist, a[t], fmt)
+        want = np.float32(o.fmax(fmt)) / np.maximum(window_max[t], np.float32(1e-12))
+        assert s[0] == want and inv[0] == np.float32(1.0) / want
+        newest_first = a[max(0, t - H + 1):t + 1][::-1]
+        assert np.array_equal(hist[:newest_first.size], newest_first)
+        assert np.all(hist[newest_first.size:] == 0)
+
+
+def test_history_push_order_worked_by_hand():
+    hist = np.zeros(4, np.float32)
+    for v in (1.0, 2.0, 3.0):
+        s, _ = o.history_push(hist, v, o.E4M3)
+    assert hist.tolist() == [3.0, 2.0, 1.0, 0.0] and s[0] == np.float32(448.0 / 3.0)
+    for v in (0.5, 0.25, 0.125):   # 3.0, then 2.0 leave the window of four
+        s, _ = o.history_push(hist, v, o.E4M3)
+    assert hist.tolist() == [0.125, 0.25, 0.5, 3.0] and s[0] == np.float32(448.0 / 3.0)
+    s, _ = o.history_push(hist, 0.0625, o.E4M3)
+    assert hist.tolist() == [0.0625, 0.125, 0.25, 0.5] and s[0] == 896.0
+
+
+def _small_linear_inputs(seed, M=32, K=64, N=48):
+    rng = np.random.default_rng(seed)
+    X = bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    W = bf16_bits((rng.standard_normal((N, K)) * 0.02).astype(np.float32))
+    dY = bf16_bits((rng.standard_normal((M, N)) * 1e-3).astype(np.float32))
+    return X, W, dY
+
+
+def _seed_state(state, X, W, dY, gfmt):
+    """First-step initialisation: record the first batch's amax values."""
+    for key, t, fmt in (("x", X, o.E4M3), ("w", W, o.E4M3), ("dy", dY, gfmt)):
+        state.scale[key], _ = o.history_push(state.hist[key], o.amax(t)[0], fmt)
+
+
+@pytest.mark.parametrize("gfmt", [o.E4M3, o.E5M2])
+def test_delayed_equals_dynamic_on_a_constant_stream(gfmt):
+    """If every step sees the same tensors, the window maximum is that tensor's amax, so the
+    delayed scale, the codes and the outputs equal dynamic scaling's at every step."""
+    X, W, dY = _small_linear_inputs(3)
+    Yd, xqd, wqd = o.linear_fwd(X, W)
+    dXd, dWd, dyqd = o.linear_bwd(dY, xqd, wqd, False, gfmt)
+    st = o.ScalingState(o.DELAYED, history_len=4)
+    _seed_state(st, X, W, dY, gfmt)
+    for _ in range(6):
+        Y, xq, wq = o.linear_fwd_scaled(X, W, st)
+        dX, dW, dyq = o.linear_bwd_scaled(dY, xq, wq, st, gfmt)
+        for a, b in ((xq, xqd), (wq, wqd), (dyq, dyqd)):
+            assert np.array_equal(a.q, b.q) and a.scale[0] == b.scale[0] and a.inv_scale[0] == b.inv_scale[0]
+            assert a.amax[0] == b.amax[0]
+        assert np.array_equal(Y, Yd) and np.array_equal(dX, dXd) and np.array_equal(dW, dWd)
+
+
+def test_delayed_uses_the_previous_steps_only():
+    """History length 1: step t is cast with FMAX / amax(step t-1), whatever step t holds.
+    A tensor four times larger than the recorded one saturates: the clamp, not the scale,
+    bounds the codes."""
+    X, W, dY = _small_linear_inputs(4)
+    X4 = bf16_bits(o.bf16_to_f32(X) * np.float32(4.0))          # exact in bf16
+    st = o.ScalingState(o.DELAYED, history_len=1)
+    _seed_state(st, X, W, dY, o.E4M3)
+    s_first = o.scale(o.amax(X), o.E4M3)[0]
+    _, xq, _ = o.linear_fwd_scaled(X4, W, st)
+    assert xq.scale[0] == s_first[0] and xq.amax[0] == o.amax(X4)[0]
+    assert np.array_equal(xq.q, o.cast(X4, s_first, o.TENSORWISE, o.E4M3))
+    mag = xq.q & 0x7F
+    y = np.abs(o.bf16_to_f32(X4) * s_first[0])
+    assert mag.max() == 0x7E and np.array_equal(mag == 0x7E, y >= 432.0)  # 432 = tie between 416 and 448, goes to the even 448
+    # the next step sees the larger amax
+    _, xq2, _ = o.linear_fwd_scaled(X, W, st)
+    assert xq2.scale[0] == o.scale(o.amax(X4), o.E4M3)[0][0]
+    assert (xq2.q & 0x7F).max() <= 0x7E - 16  # a quarter of the range: two binades below 448
+
+
+def test_static_with_the_dynamic_scale_is_dynamic():
+    X, W, dY = _small_linear_inputs(5)
+    Yd, xqd, wqd = o.linear_fwd(X, W)
+    dXd, dWd, dyqd = o.linear_bwd(dY, xqd, wqd, False, o.E5M2)
+    st = o.ScalingState(o.STATIC)
+    st.scale["x"], st.scale["w"], st.scale["dy"] = xqd.scale.copy(), wqd.scale.copy(), dyqd.scale.copy()
+    for _ in range(2):  # static: nothing changes from step to step
+        Y, xq, wq = o.linear_fwd_scaled(X, W, st)
+        dX, dW, dyq = o.linear_bwd_scaled(dY, xq, wq, st, o.E5M2)
+        assert np.array_equal(Y, Yd) and np.array_equal(dX, dXd) and np.array_equal(dW, dWd)
+        assert np.array_equal(dyq.q, dyqd.q) and xq.amax is None
+    assert st.scale["x"][0] == xqd.scale[0] and np.all(st.hist["x"] == 0)
+
+
+def test_static_power_of_two_scale_is_lossless_on_the_grid():
+    """Values k * 2^-3 with |k| <= 15 times a scale of 2^4 are e4m3 values (k * 2 with at most
+    four significant bits): decode(cast(x)) / scale == x exactly."""
+    k = np.arange(-15, 16, dtype=np.float32)
+    x = np.tile(k * np.float32(0.125), (16, 1))[:, :16]
+    codes = o.cast(bf16_bits(x), np.array([16.0], np.float32), o.TENSORWISE, o.E4M3)
+    assert np.array_equal(o.decode(codes, o.E4M3) / np.float32(16.0), x)
