@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama8b")
     ap.add_argument("--variant", default=None, help="granularity:gradfmt, e.g. tensorwise:e4m3")
+    ap.add_argument("--scaling", default="dynamic", choices=["dynamic", "delayed", "static"],
+                    help="per-tensor scaling strategy (delayed/static: tensorwise only, single-pass casts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a device copy of known size (reference for the HBM byte counters)")
@@ -41,7 +43,7 @@ def parse():
 class LinearState:
     """Device tensors of one linear of the workload."""
 
-    def __init__(self, f8, wl, w, li, rowwise, grad_fmt):
+    def __init__(self, f8, wl, w, li, rowwise, grad_fmt, scaling="dynamic", ws=None):
         import torch
         lin = w.linears[li]
         X, W, dY = wl.make_linear_inputs(w, li)
@@ -54,6 +56,15 @@ class LinearState:
         self.dW = torch.empty((N, K), **bf)
         self.saved = f8.Saved(M, K, N, rowwise)
         self.desc = f8.linear_desc(M, K, N, rowwise, grad_fmt)
+        self.state = None
+        if scaling != "dynamic":
+            # delayed: histories seeded with this batch's amax values (the first-step
+            # initialisation); static: constant scales FMAX / amax of this batch
+            self.state = f8.ScalingState(f8.DELAYED if scaling == "delayed" else f8.STATIC, 16)
+            a = torch.empty(1, device="cuda")
+            for key, t, fmt in (("x", self.X, f8.E4M3), ("w", self.W, f8.E4M3), ("dy", self.dY, grad_fmt)):
+                f8.amax(t, f8.TENSORWISE, a, ws)
+                f8.amax_history_push(getattr(self.state, "hist_" + key), a, fmt, getattr(self.state, "scale_" + key))
 
 
 def main():
@@ -89,16 +100,27 @@ def main():
     rowwise = gran == "rowwise"
     grad_fmt = f8.E5M2 if gfmt == "e5m2" else f8.E4M3
 
-    states = [LinearState(f8, wl, w, li, rowwise, grad_fmt) for li in range(len(w.linears))]
-    dmax = max(max(s.lin.M, s.lin.K, s.lin.N) for s in states)
+    if args.scaling != "dynamic" and rowwise:
+        print("bench.py: delayed and static scaling are per-tensor strategies; use a tensorwise variant",
+              file=sys.stderr)
+        sys.exit(2)
+    dmax = max(max(l.M, l.K, l.N) for l in w.linears)
     ws = f8.new_workspace(dmax, dmax)
+    states = [LinearState(f8, wl, w, li, rowwise, grad_fmt, args.scaling, ws) for li in range(len(w.linears))]
     stream = torch.cuda.current_stream()
 
-    def step():
-        for s in states:                       # forward in model order
-            f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws, stream)
-        for s in reversed(states):             # backward in reverse
-            f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws, stream)
+    if args.scaling == "dynamic":
+        def step():
+            for s in states:                       # forward in model order
+                f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws, stream)
+            for s in reversed(states):             # backward in reverse
+                f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws, stream)
+    else:
+        def step():
+            for s in states:
+                f8.linear_fwd_scaled(s.desc, s.state, s.X, s.W, s.Y, s.saved, ws, stream)
+            for s in reversed(states):
+                f8.linear_bwd_scaled(s.desc, s.state, s.dY, s.saved, s.dX, s.dW, ws, stream)
 
     for _ in range(args.warmup):
         step()
@@ -152,7 +174,12 @@ def main():
         lin_cast_ms = 0.0
         if not rowwise:
             for t, q, fmt in ((s.X, sv.x, f8.E4M3), (s.W, sv.w, f8.E4M3), (s.dY, sv.dy, grad_fmt)):
-                fn = lambda: f8.amax_cast(t, f8.TENSORWISE, fmt, q.amax, q.scale, q.inv_scale, q.q, q.q_t, ws, stream)
+                if args.scaling == "dynamic":
+                    fn = lambda: f8.amax_cast(t, f8.TENSORWISE, fmt, q.amax, q.scale, q.inv_scale, q.q, q.q_t, ws, stream)
+                elif args.scaling == "delayed":
+                    fn = lambda: f8.cast_amax(t, q.scale, fmt, q.amax, q.q, q.q_t, ws, stream)
+                else:
+                    fn = lambda: f8.cast(t, q.scale, f8.TENSORWISE, fmt, q.q, q.q_t, stream)
                 fn()
                 ms = timed(fn, reps)
                 lin_cast_ms += ms
@@ -179,10 +206,12 @@ def main():
     if cast_ms > 0:
         # dynamic tensorwise amax+cast: 2 B amax read + 2 B cast re-read + 1 B write per element;
         # the transposed fp8 copy (+1 B/elem) is a design cost and not counted.
-        gbs5 = 5 * cast_elems / (cast_ms * 1e-3) / 1e9
-        cast = {"bound": "hbm", "achieved": round(gbs5, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": round(gbs5 / PEAK_HBM_GBS, 4), "bytes_per_elem": 5,
-                "moved_gbs_incl_transposed_copy": round(6 * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
+        # delayed / static scaling: the scale is known beforehand, one pass: 2 B read + 1 B write.
+        bpe = 5 if args.scaling == "dynamic" else 3
+        gbs = bpe * cast_elems / (cast_ms * 1e-3) / 1e9
+        cast = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_elem": bpe,
+                "moved_gbs_incl_transposed_copy": round((bpe + 1) * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
                 "ms_per_step": round(cast_ms, 4)}
 
     out = {
@@ -199,7 +228,7 @@ def main():
         "dtype": "fp8 (e4m3" + ("/e5m2 grads" if grad_fmt == f8.E5M2 else "") + ") x fp8 -> fp32 accumulate -> bf16",
         "data": "synthetic",
         "config": {"workload": f"{w.key}: " + ", ".join(f"{l.name}[M={l.M},K={l.K},N={l.N}]" for l in w.linears),
-                   "scaling_granularity": gran, "grad_format": gfmt,
+                   "scaling_granularity": gran, "scaling_strategy": args.scaling, "grad_format": gfmt,
                    "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
         "roofline": roofline,
@@ -208,7 +237,7 @@ def main():
     }
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_rows, rowwise, grad_fmt)
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_rows, rowwise, grad_fmt, args.scaling)
     print(json.dumps(out))
 
 
@@ -226,7 +255,7 @@ def committed_traffic():
     return None
 
 
-def cpu_baseline(w, rows, rowwise, grad_fmt):
+def cpu_baseline(w, rows, rowwise, grad_fmt, scaling="dynamic"):
     """The oracle as it stands, on the host cores, on a bounded sample: the narrowest linear
     of the workload restricted to its first `rows` tokens, forward + backward, casts included."""
     import oracle as o
@@ -236,10 +265,19 @@ def cpu_baseline(w, rows, rowwise, grad_fmt):
     rows = min(rows, lin.M)
     X, W, dY = wl.make_linear_inputs(w, li, M=rows)
     xb, wb, dyb = wl.bits(X), wl.bits(W), wl.bits(dY)
-    t0 = time.perf_counter()
-    _, xq, wq = o.linear_fwd(xb, wb, rowwise)
-    o.linear_bwd(dyb, xq, wq, rowwise, grad_fmt)
-    dt = time.perf_counter() - t0
+    if scaling == "dynamic":
+        t0 = time.perf_counter()
+        _, xq, wq = o.linear_fwd(xb, wb, rowwise)
+        o.linear_bwd(dyb, xq, wq, rowwise, grad_fmt)
+        dt = time.perf_counter() - t0
+    else:
+        st = o.ScalingState(o.DELAYED if scaling == "delayed" else o.STATIC, 16)
+        for key, t, fmt in (("x", xb, o.E4M3), ("w", wb, o.E4M3), ("dy", dyb, grad_fmt)):
+            st.scale[key], _ = o.history_push(st.hist[key], o.amax(t)[0], fmt)
+        t0 = time.perf_counter()
+        _, xq, wq = o.linear_fwd_scaled(xb, wb, st)
+        o.linear_bwd_scaled(dyb, xq, wq, st, grad_fmt)
+        dt = time.perf_counter() - t0
     fl = 6 * rows * lin.K * lin.N
     return {"value": round(fl / dt / 1e12, 6), "unit": "TFLOP/s", "cores": o.num_threads(), "kind": "oracle",
             "sample": f"{w.key}/{lin.name} (K={lin.K}, N={lin.N}) first {rows} of {lin.M} tokens, fwd+bwd with casts",

@@ -357,12 +357,10 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
         v[i] = make_uint4(0, 0, 0, 0);
         if (col_ok && r < rows) v[i] = *reinterpret_cast<const uint4*>(x + r * ld + col);
     }
+    uint32_t macc = 0;
     if constexpr (MEASURE) {
-        uint32_t acc = 0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) acc = absmax_acc(acc, v[i]);  // out-of-range chunks are zero
-        const uint32_t m = block_max_u32<kWaves>(pk_collapse(acc), red);
-        if (threadIdx.x == 0) partial_out[blockIdx.x] = m;
+        for (int i = 0; i < 8; ++i) macc = absmax_acc(macc, v[i]);  // out-of-range chunks are zero
     }
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -408,6 +406,11 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
                         make_uint4(o[i][0], o[i][1], o[i][2], o[i][3]);
             }
         }
+    }
+    if constexpr (MEASURE) {
+        // after the stores are on their way: the reduction's barriers then stall nothing
+        const uint32_t m = block_max_u32<kWaves>(pk_collapse(macc), red);
+        if (threadIdx.x == 0) partial_out[blockIdx.x] = m;
     }
 }
 
