@@ -34,6 +34,8 @@ def parse():
     ap.add_argument("--scaling", default="dynamic", choices=["dynamic", "delayed", "static"],
                     help="per-tensor scaling strategy (delayed/static: tensorwise only, single-pass casts)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-bf16-context", action="store_true",
+                    help="skip timing torch.matmul in bf16 on the same shapes (context only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a device copy of known size (reference for the HBM byte counters)")
     ap.add_argument("--cpu-sample-rows", type=int, default=2048)
@@ -236,9 +238,27 @@ def main():
         "per_linear": per_linear,
     }
 
+    if not args.no_bf16_context:
+        out["bf16_matmul_context"] = bf16_context(states, timed, reps, flops_step)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_rows, rowwise, grad_fmt, args.scaling)
     print(json.dumps(out))
+
+
+def bf16_context(states, timed, reps, flops_step):
+    """Context, not part of the path: the three matrix products of every linear as plain bf16
+    torch.matmul calls (the library GEMM that the Float8 linear replaces), no casts."""
+    import torch
+    total = 0.0
+    for s in states:
+        fns = [lambda: torch.matmul(s.X, s.W.t(), out=s.Y),
+               lambda: torch.matmul(s.dY, s.W, out=s.dX),
+               lambda: torch.matmul(s.dY.t(), s.X, out=s.dW)]
+        for fn in fns:
+            fn()
+            total += timed(fn, reps)
+    return {"ms_per_step": round(total, 4), "tflops": round(flops_step / (total * 1e-3) / 1e12, 1),
+            "what": "torch.matmul bf16 (hipBLASLt), same 21 products, no casts"}
 
 
 def committed_traffic():
