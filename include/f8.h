@@ -168,11 +168,16 @@ f8_status f8_amax_history_push(float* history, int64_t len, const float* amax_ne
  * F8_COLWISE is not a GEMM mode (F8_ERR_ENUM).
  * Summation order is unspecified (results agree with any fp32 order within
  * accumulation rounding).
+ * amax_d (nullable, device, 1 float): if given, receives max |D[m,n]| over the
+ * bf16 values stored by this call, taken in the epilogue while they are still
+ * in registers: the amax a following Float8 linear (dynamic or delayed
+ * scaling) needs of its input, without another pass over D.  It is the exact
+ * maximum of the stored values (0 for an empty D).
  */
 f8_status f8_gemm(f8_layout layout, int64_t M, int64_t N, int64_t K, const uint8_t* A, f8_format fa,
                   int64_t lda, const uint8_t* B, f8_format fb, int64_t ldb, const float* inv_scale_a,
                   const float* inv_scale_b, f8_granularity g, void* D_bf16, int64_t ldd,
-                  void* stream);
+                  float* amax_d, void* stream);
 
 /*
  * One quantised tensor T[rows, cols] as the linear layer keeps it between

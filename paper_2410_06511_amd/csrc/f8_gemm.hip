@@ -38,9 +38,9 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 // epilogue helper: four fp32 accumulators -> four bf16 at D[m, n..n+3]
 // ---------------------------------------------------------------------------
 template <int GRAN>
-__device__ inline void store4(uint16_t* __restrict__ D, int64_t ldd, int64_t m, int64_t n, v4f acc,
-                              float s_tensor, const float* __restrict__ isa,
-                              const float* __restrict__ isb)
+__device__ inline uint2 store4(uint16_t* __restrict__ D, int64_t ldd, int64_t m, int64_t n, v4f acc,
+                               float s_tensor, const float* __restrict__ isa,
+                               const float* __restrict__ isb)
 {
     float r0, r1, r2, r3;
     if constexpr (GRAN == F8_TENSORWISE) {
@@ -55,7 +55,28 @@ __device__ inline void store4(uint16_t* __restrict__ D, int64_t ldd, int64_t m, 
     o.x = f32_to_bf16_bits(r0) | (f32_to_bf16_bits(r1) << 16);
     o.y = f32_to_bf16_bits(r2) | (f32_to_bf16_bits(r3) << 16);
     *reinterpret_cast<uint2*>(D + m * ldd + n) = o;
+    return o;
 }
+
+// amax of the bf16 output, kept as a bf16 magnitude in the upper half of a word so that the
+// unsigned integer order of the words is the order of the magnitudes; combined across
+// wavefronts with one atomic max per wavefront (the entry point zeroes the word first).
+__device__ inline uint32_t amax_pair(uint32_t acc, uint2 o)
+{
+    return pkmax(pkmax(acc, o.x & 0x7FFF7FFFu), o.y & 0x7FFF7FFFu);
+}
+// `red`: one word of LDS per wavefront, free for use.  Called by every thread of the block.
+// Same-address atomics from a thousand wavefronts serialise at the memory side, so the block
+// combines its wavefronts first and skips the atomic when the published value is already at
+// least as large (the value only ever grows, so a stale read costs one extra atomic, nothing else).
+template <int NW>
+__device__ inline void amax_publish(uint32_t acc, uint32_t* amax_bits, uint32_t* red)
+{
+    const uint32_t m = block_max_u32<NW>(pk_collapse(acc), red) << 16;
+    if (threadIdx.x == 0 && m > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, m);
+}
+
+__global__ void zero_word_kernel(uint32_t* p) { p[0] = 0; }
 
 // ---------------------------------------------------------------------------
 // Tile order: consecutive workgroup ids go round-robin to the 8 XCDs, each with
@@ -107,11 +128,11 @@ __device__ inline int swz(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 
 // lgkmcnt 11:8): wait for all vector-memory operations and all LDS operations.
 constexpr int kWaitAllVmLgkm = 0x0070;
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN, bool AMAX = false>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ D, int M,
     int N, int K, int64_t lda, int64_t ldb, int64_t ldd, const float* __restrict__ isa,
-    const float* __restrict__ isb, int tiles_m, int tiles_n)
+    const float* __restrict__ isb, int tiles_m, int tiles_n, uint32_t* __restrict__ amax_bits = nullptr)
 {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
@@ -235,6 +256,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         static_for<TM + TN>([&](auto F) { read_frag(f, S, H, F); });
     };
 
+    uint32_t amax_acc = 0;  // AMAX: largest |bf16 output| this wavefront has produced (packed pairs)
     v16f acc[TM][TN];
     auto zero_acc = [&]() {
 #pragma unroll
@@ -308,6 +330,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                             uint2 o;
                             o.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, b2));
                             o.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, b2));
+                            if constexpr (AMAX) {
+                                // edge tiles hold results of re-read rows past M / N: not output
+                                bool counted = true;
+                                if constexpr (!decltype(INTERIOR)::value)
+                                    counted = m0 + 32 * i + fr < M && n0 + 32 * jp + nl < N;
+                                if (counted) amax_acc = amax_pair(amax_acc, o);
+                            }
                             *reinterpret_cast<uint2*>(ep + fr * EP_STRIDE + nl * 2) = o;
                         }
                     }
@@ -463,6 +492,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     }
     // no load may still be writing LDS when the workgroup ends
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    if constexpr (AMAX) {
+        __syncthreads();  // every wave is past its last epilogue pass: the staging buffer is free
+        amax_publish<NW>(amax_acc, amax_bits, reinterpret_cast<uint32_t*>(epb));
+    }
 #ifdef F8_EXP_CLOCK
     // perf probe only: shader-clock ticks and 100 MHz ticks of this workgroup, into the first
     // bytes of D (corrupts the result)
@@ -518,7 +551,7 @@ template <int LAYOUT, int FA, int FB, int GRAN>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ D, int M,
     int N, int K, int64_t lda, int64_t ldb, int64_t ldd, const float* __restrict__ isa,
-    const float* __restrict__ isb)
+    const float* __restrict__ isb, uint32_t* __restrict__ amax_bits)
 {
     __shared__ __attribute__((aligned(16))) uint8_t As[kGT * kGStride];
     __shared__ __attribute__((aligned(16))) uint8_t Bs[kGT * kGStride];
@@ -554,6 +587,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
     }
     float s_tensor = 0.f;
     if constexpr (GRAN == F8_TENSORWISE) s_tensor = isa[0] * isb[0];
+    uint32_t amax_acc = 0;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int m = m0 + wm * 32 + 16 * i + fr;
@@ -561,8 +595,12 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int n = n0 + wn * 32 + 16 * j + 4 * fg;
-            if (n < N) store4<GRAN>(D, ldd, m, n, acc[i][j], s_tensor, isa, isb);
+            if (n < N) amax_acc = amax_pair(amax_acc, store4<GRAN>(D, ldd, m, n, acc[i][j], s_tensor, isa, isb));
         }
+    }
+    if (amax_bits) {  // uniform branch; every thread of the block takes part
+        __syncthreads();
+        amax_publish<4>(amax_acc, amax_bits, reinterpret_cast<uint32_t*>(As));
     }
 }
 
@@ -572,13 +610,18 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN>
 static void launch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
-                      const float* isa, const float* isb, uint16_t* D, int64_t ldd, int max_blocks, hipStream_t st)
+                      const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                      int max_blocks, hipStream_t st)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
     const int grid = total < max_blocks ? total : max_blocks;
-    gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
-        A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tiles_m, tiles_n);
+    if (amax_bits)
+        gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN, true><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
+            A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tiles_m, tiles_n, amax_bits);
+    else
+        gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN, false><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
+            A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tiles_m, tiles_n, nullptr);
 }
 
 static int cu_count()
@@ -591,58 +634,63 @@ static int cu_count()
 
 template <int FA, int FB, int GRAN>
 static void dispatch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
-                        const float* isa, const float* isb, uint16_t* D, int64_t ldd, hipStream_t st)
+                        const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                        hipStream_t st)
 {
     // The largest tile that still gives every CU work: 256x256 (one persistent workgroup per
     // CU), else 256x128, else 128x128 (LDS allows two workgroups per CU there).
     const int cus = cu_count();
     auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
     if (tiles(256, 256) >= cus)
-        launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, cus, st);
+        launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
     else if (tiles(256, 128) >= cus)
-        launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, cus, st);
+        launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
     else
-        launch_nt<128, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, 2 * cus, st);
+        launch_nt<128, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, 2 * cus, st);
 }
 
 template <int LAYOUT, int FA, int FB, int GRAN>
 static void launch_generic(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
-                           const float* isa, const float* isb, uint16_t* D, int64_t ldd, hipStream_t st)
+                           const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                           hipStream_t st)
 {
     dim3 grid((N + kGT - 1) / kGT, (M + kGT - 1) / kGT);
-    gemm_generic_kernel<LAYOUT, FA, FB, GRAN><<<grid, 256, 0, st>>>(A, B, D, M, N, K, lda, ldb, ldd, isa, isb);
+    gemm_generic_kernel<LAYOUT, FA, FB, GRAN><<<grid, 256, 0, st>>>(A, B, D, M, N, K, lda, ldb, ldd, isa, isb,
+                                                                    amax_bits);
 }
 
 template <int FA, int FB, int GRAN>
 static void dispatch_layout(int layout, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B,
                             int64_t ldb, const float* isa, const float* isb, uint16_t* D, int64_t ldd,
-                            hipStream_t st)
+                            uint32_t* amax_bits, hipStream_t st)
 {
     if (layout == F8_NT) {
         if (K % (2 * kBK) == 0 && K > 0)  // the fast kernel alternates two LDS stages per tile
-            dispatch_nt<FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, st);
+            dispatch_nt<FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
         else
-            launch_generic<F8_NT, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, st);
+            launch_generic<F8_NT, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
     } else if (layout == F8_NN) {
-        launch_generic<F8_NN, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, st);
+        launch_generic<F8_NN, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
     } else {
-        launch_generic<F8_TN, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, st);
+        launch_generic<F8_TN, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
     }
 }
 
 f8_status gemm(int layout, int64_t M, int64_t N, int64_t K, const uint8_t* A, int fa, int64_t lda,
                const uint8_t* B, int fb, int64_t ldb, const float* isa, const float* isb, int g, void* D,
-               int64_t ldd, hipStream_t st)
+               int64_t ldd, float* amax_d, hipStream_t st)
 {
-    if (M == 0 || N == 0) return F8_OK;
+    uint32_t* amax_bits = reinterpret_cast<uint32_t*>(amax_d);
+    if (amax_bits) zero_word_kernel<<<1, 1, 0, st>>>(amax_bits);
+    if (M == 0 || N == 0) return last_launch_status();
     uint16_t* d = static_cast<uint16_t*>(D);
     const int m = (int)M, n = (int)N, k = (int)K;
 #define F8_GEMM_CASE(FA_, FB_)                                                                     \
     do {                                                                                           \
         if (g == F8_TENSORWISE)                                                                    \
-            dispatch_layout<FA_, FB_, F8_TENSORWISE>(layout, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, st); \
+            dispatch_layout<FA_, FB_, F8_TENSORWISE>(layout, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, amax_bits, st); \
         else                                                                                       \
-            dispatch_layout<FA_, FB_, F8_ROWWISE>(layout, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, st);    \
+            dispatch_layout<FA_, FB_, F8_ROWWISE>(layout, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, amax_bits, st);    \
     } while (0)
     if (fa == F8_E4M3 && fb == F8_E4M3) F8_GEMM_CASE(F8_E4M3, F8_E4M3);
     else if (fa == F8_E5M2 && fb == F8_E4M3) F8_GEMM_CASE(F8_E5M2, F8_E4M3);
@@ -659,7 +707,7 @@ using namespace f8;
 extern "C" f8_status f8_gemm(f8_layout layout, int64_t M, int64_t N, int64_t K, const uint8_t* A,
                              f8_format fa, int64_t lda, const uint8_t* B, f8_format fb, int64_t ldb,
                              const float* inv_scale_a, const float* inv_scale_b, f8_granularity g,
-                             void* D_bf16, int64_t ldd, void* stream)
+                             void* D_bf16, int64_t ldd, float* amax_d, void* stream)
 {
     if ((int)layout < 0 || (int)layout > F8_TN || (int)fa < 0 || (int)fa > F8_E5M2 || (int)fb < 0 ||
         (int)fb > F8_E5M2 || ((int)g != F8_TENSORWISE && (int)g != F8_ROWWISE))
@@ -675,6 +723,6 @@ extern "C" f8_status f8_gemm(f8_layout layout, int64_t M, int64_t N, int64_t K, 
     if (K == 0) {
         // empty contraction: D = 0.  The generic kernel's K loop does not run and stores zeros.
     }
-    return gemm(layout, M, N, K, A, fa, lda, B, fb, ldb, inv_scale_a, inv_scale_b, g, D_bf16, ldd,
+    return gemm(layout, M, N, K, A, fa, lda, B, fb, ldb, inv_scale_a, inv_scale_b, g, D_bf16, ldd, amax_d,
                 (hipStream_t)stream);
 }

@@ -122,7 +122,7 @@ f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, v
     if ((s = quantise_both(X, M, K, rw, F8_E4M3, &saved->x, workspace, st)) != F8_OK) return s;
     if ((s = quantise_both(W, N, K, rw, F8_E4M3, &saved->w, workspace, st)) != F8_OK) return s;
     return gemm(F8_NT, M, N, K, saved->x.q, F8_E4M3, K, saved->w.q, F8_E4M3, K, saved->x.inv_scale,
-                saved->w.inv_scale, d->granularity, Y, N, st);
+                saved->w.inv_scale, d->granularity, Y, N, nullptr, st);
 }
 
 f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved, void* dX, void* dW,
@@ -144,13 +144,13 @@ f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved
     // dX = dY8 [M,N] . (W8t [K,N])^T : dY per row m; W per column k = per row of W8t
     const float* w_is = rw ? saved->w.inv_scale_t : saved->w.inv_scale;
     if ((s = gemm(F8_NT, M, K, N, saved->dy.q, gf, N, saved->w.q_t, F8_E4M3, N, saved->dy.inv_scale, w_is,
-                  d->granularity, dX, K, st)) != F8_OK)
+                  d->granularity, dX, K, nullptr, st)) != F8_OK)
         return s;
     // dW = dY8t [N,M] . (X8t [K,M])^T : dY per column n, X per column k
     const float* dy_is = rw ? saved->dy.inv_scale_t : saved->dy.inv_scale;
     const float* x_is = rw ? saved->x.inv_scale_t : saved->x.inv_scale;
     return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, dy_is, x_is, d->granularity,
-                dW, K, st);
+                dW, K, nullptr, st);
 }
 
 f8_status f8_linear_fwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* X,
@@ -176,7 +176,7 @@ f8_status f8_linear_fwd_scaled(const f8_linear_desc* d, const f8_scaling_state* 
                              &saved->w, workspace, workspace_bytes_, st)) != F8_OK)
         return s;
     return gemm(F8_NT, M, N, K, saved->x.q, F8_E4M3, K, saved->w.q, F8_E4M3, K, saved->x.inv_scale,
-                saved->w.inv_scale, F8_TENSORWISE, Y, N, st);
+                saved->w.inv_scale, F8_TENSORWISE, Y, N, nullptr, st);
 }
 
 f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* dY,
@@ -201,10 +201,10 @@ f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* 
                              &saved->dy, workspace, workspace_bytes_, st)) != F8_OK)
         return s;
     if ((s = gemm(F8_NT, M, K, N, saved->dy.q, gf, N, saved->w.q_t, F8_E4M3, N, saved->dy.inv_scale,
-                  saved->w.inv_scale, F8_TENSORWISE, dX, K, st)) != F8_OK)
+                  saved->w.inv_scale, F8_TENSORWISE, dX, K, nullptr, st)) != F8_OK)
         return s;
     return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, saved->dy.inv_scale,
-                saved->x.inv_scale, F8_TENSORWISE, dW, K, st);
+                saved->x.inv_scale, F8_TENSORWISE, dW, K, nullptr, st);
 }
 
 }  // extern "C"

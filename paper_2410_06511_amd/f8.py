@@ -67,7 +67,7 @@ def lib():
         l.f8_encode_f32.argtypes = [_p, _i64, _int, _int, _p, _p]
         l.f8_amax_cast.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _p, _p, _p, _i64, _p, _i64, _p,
                                    C.c_size_t, _p]
-        l.f8_gemm.argtypes = [_int, _i64, _i64, _i64, _p, _int, _i64, _p, _int, _i64, _p, _p, _int, _p, _i64, _p]
+        l.f8_gemm.argtypes = [_int, _i64, _i64, _i64, _p, _int, _i64, _p, _int, _i64, _p, _p, _int, _p, _i64, _p, _p]
         l.f8_linear_fwd.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         l.f8_linear_bwd.argtypes = [C.POINTER(LinearDesc), _p, C.POINTER(SavedStruct), _p, _p, _p, C.c_size_t, _p]
         l.f8_cast_amax.argtypes = [_p, _i64, _i64, _i64, _p, _int, _p, _i64, _p, _i64, _p, _p, C.c_size_t, _p]
@@ -144,9 +144,10 @@ def amax_cast(x, g, fmt, amax_out, scale_out, inv_scale_out, out=None, out_t=Non
                               _ptr(out_t), 0 if out_t is None else out_t.stride(0), wp, wb, _stream(stream)))
 
 
-def gemm(layout, M, N, K, A, fa, B, fb, inv_scale_a, inv_scale_b, g, D, stream=None):
+def gemm(layout, M, N, K, A, fa, B, fb, inv_scale_a, inv_scale_b, g, D, stream=None, amax_d=None):
     _check(lib().f8_gemm(layout, M, N, K, _ptr(A), fa, A.stride(0), _ptr(B), fb, B.stride(0),
-                         _ptr(inv_scale_a), _ptr(inv_scale_b), g, _ptr(D), D.stride(0), _stream(stream)))
+                         _ptr(inv_scale_a), _ptr(inv_scale_b), g, _ptr(D), D.stride(0), _ptr(amax_d),
+                         _stream(stream)))
 
 
 class QTensor:

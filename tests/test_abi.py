@@ -66,10 +66,10 @@ def test_argument_errors_are_reported_before_any_launch():
     assert l.f8_cast(FAKE, 32, 16, 16, FAKE, 0, 0, None, 0, FAKE, 16, None) == 2
     assert l.f8_cast(FAKE, 16, 16, 16, None, 0, 0, FAKE, 16, None, 0, None) == 1
     # gemm: colwise is not a GEMM mode; K not a multiple of 16; ld too small
-    assert l.f8_gemm(0, 16, 16, 16, FAKE, 0, 16, FAKE, 0, 16, FAKE, FAKE, 2, FAKE, 16, None) == 4
-    assert l.f8_gemm(0, 16, 16, 24, FAKE, 0, 32, FAKE, 0, 32, FAKE, FAKE, 0, FAKE, 16, None) == 2
-    assert l.f8_gemm(1, 16, 32, 16, FAKE, 0, 16, FAKE, 0, 16, FAKE, FAKE, 0, FAKE, 32, None) == 2
-    assert l.f8_gemm(0, 16, 16, 16, None, 0, 16, FAKE, 0, 16, FAKE, FAKE, 0, FAKE, 16, None) == 1
+    assert l.f8_gemm(0, 16, 16, 16, FAKE, 0, 16, FAKE, 0, 16, FAKE, FAKE, 2, FAKE, 16, None, None) == 4
+    assert l.f8_gemm(0, 16, 16, 24, FAKE, 0, 32, FAKE, 0, 32, FAKE, FAKE, 0, FAKE, 16, None, None) == 2
+    assert l.f8_gemm(1, 16, 32, 16, FAKE, 0, 16, FAKE, 0, 16, FAKE, FAKE, 0, FAKE, 32, None, None) == 2
+    assert l.f8_gemm(0, 16, 16, 16, None, 0, 16, FAKE, 0, 16, FAKE, FAKE, 0, FAKE, 16, None, None) == 1
     # linear: bad descriptor / missing saved buffers / workspace
     d = f8.linear_desc(32, 32, 32)
     sv = f8.SavedStruct()

@@ -36,7 +36,14 @@ def run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, g):
     sb = torch.from_numpy(np.atleast_1d(isb).astype(np.float32)).cuda()
     D = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
     f8.gemm(layout, M, N, K, Ad, fa, Bd, fb, sa, sb, g, D)
+    # the same product with the output amax taken in the epilogue: identical D, and the amax
+    # is exactly the largest magnitude among the stored bf16 values
+    D2 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    amax = torch.full((1,), -1.0, device="cuda")
+    f8.gemm(layout, M, N, K, Ad, fa, Bd, fb, sa, sb, g, D2, amax_d=amax)
     torch.cuda.synchronize()
+    assert torch.equal(D.view(torch.int16), D2.view(torch.int16))
+    assert amax.item() == o.amax(bits(D2))[0]
     return bits(D)
 
 
@@ -143,3 +150,30 @@ def test_gemm_llama_shapes_sampled(M, N, K):
     ref = o.gemm_points(o.NT, A, o.E4M3, B, o.E4M3, isa, isb, ms, ns)
     assert_gemm_close(got[ms, ns], ref, "cols")
     assert np.isfinite(o.bf16_to_f32(got)).all()
+
+
+def test_gemm_output_amax_full_size_and_oracle():
+    """8B wk forward shape: the epilogue amax equals the amax of the stored output exactly and the
+    oracle's amax of its own output within the GEMM tolerance."""
+    rng = np.random.default_rng(12)
+    M, N, K = 2048, 1024, 4096
+    A, B = rand_codes(rng, (M, K), o.E4M3), rand_codes(rng, (N, K), o.E4M3)
+    isa, isb = np.float32(2.0 ** -6), np.float32(2.0 ** -5)
+    got = run_gemm(o.NT, M, N, K, A, o.E4M3, B, o.E4M3, isa, isb, o.TENSORWISE)   # checks exactness
+    rows = np.arange(0, M, 16)
+    ms, ns = np.repeat(rows, N), np.tile(np.arange(N), len(rows))
+    ref = o.gemm_points(o.NT, A, o.E4M3, B, o.E4M3, np.array([isa]), np.array([isb]), ms, ns, o.TENSORWISE)
+    a_got = o.amax(got[rows])[0]
+    a_ref = o.amax(ref.reshape(len(rows), N))[0]
+    assert abs(a_got - a_ref) <= 1e-2 * a_ref
+
+
+def test_gemm_amax_of_empty_output_is_zero():
+    one = torch.ones(1, device="cuda")
+    buf = torch.zeros((16, 16), dtype=torch.uint8, device="cuda")
+    D = torch.zeros((16, 16), dtype=torch.bfloat16, device="cuda")
+    amax = torch.full((1,), 3.0, device="cuda")
+    code = f8.lib().f8_gemm(0, 0, 16, 16, buf.data_ptr(), 0, 16, buf.data_ptr(), 0, 16, one.data_ptr(), one.data_ptr(),
+                            0, D.data_ptr(), 16, amax.data_ptr(), None)
+    torch.cuda.synchronize()
+    assert code == 0 and amax.item() == 0.0
