@@ -137,9 +137,10 @@ def main():
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
 
     # ---- per-kernel legs, HIP events on the launch stream --------------------------------
-    # The same kernels the step launches, called through the same library, one launch per
-    # event pair: the three GEMMs of every linear (dominant kernel) and the amax+cast of
-    # every tensor.
+    # An instrumented pass issues the step's own sequence of library calls (every tensor's
+    # amax+cast and every GEMM, forward in model order, backward in reverse, through the same
+    # C entry points the linear composes), each call between two events.  Same kernels, same
+    # order and therefore the same cache state as in the timed steps.
     def timed(fn, reps):
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for a, b in ev:
@@ -151,45 +152,66 @@ def main():
 
     g = f8.ROWWISE if rowwise else f8.TENSORWISE
     reps = max(3, min(args.steps, 10))
-    gemm_ms, gemm_flops, gemm_launches = 0.0, 0, 0
-    cast_ms, cast_elems, cast_launch_bytes = 0.0, 0, 0
-    per_linear = []
-    for s in states:
+
+    def cast_op(t, q, fmt):
+        if rowwise:
+            def fn():
+                f8.amax_cast(t, f8.ROWWISE, fmt, q.amax, q.scale, q.inv_scale, q.q, None, ws, stream)
+                f8.amax_cast(t, f8.COLWISE, fmt, q.amax_t, q.scale_t, q.inv_scale_t, None, q.q_t, ws, stream)
+            return fn
+        if args.scaling == "dynamic":
+            return lambda: f8.amax_cast(t, f8.TENSORWISE, fmt, q.amax, q.scale, q.inv_scale, q.q, q.q_t, ws, stream)
+        if args.scaling == "delayed":
+            return lambda: f8.cast_amax(t, q.scale, fmt, q.amax, q.q, q.q_t, ws, stream)
+        return lambda: f8.cast(t, q.scale, f8.TENSORWISE, fmt, q.q, q.q_t, stream)
+
+    ops = []  # (kind, linear index, call, flop or elements)
+    for li, s in enumerate(states):
+        M, K, N = s.lin.M, s.lin.K, s.lin.N
+        sv = s.saved
+        ops.append(("cast", li, cast_op(s.X, sv.x, f8.E4M3), s.X.numel()))
+        ops.append(("cast", li, cast_op(s.W, sv.w, f8.E4M3), s.W.numel()))
+        ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N: f8.gemm(
+            f8.NT, M, N, K, sv.x.q, f8.E4M3, sv.w.q, f8.E4M3, sv.x.inv_scale, sv.w.inv_scale, g, s.Y, stream)),
+            2 * M * K * N))
+    for li, s in reversed(list(enumerate(states))):
         M, K, N = s.lin.M, s.lin.K, s.lin.N
         sv = s.saved
         w_is_t = sv.w.inv_scale_t if rowwise else sv.w.inv_scale
         dy_is_t = sv.dy.inv_scale_t if rowwise else sv.dy.inv_scale
         x_is_t = sv.x.inv_scale_t if rowwise else sv.x.inv_scale
-        gemms = [
-            lambda: f8.gemm(f8.NT, M, N, K, sv.x.q, f8.E4M3, sv.w.q, f8.E4M3, sv.x.inv_scale, sv.w.inv_scale, g, s.Y, stream),
-            lambda: f8.gemm(f8.NT, M, K, N, sv.dy.q, grad_fmt, sv.w.q_t, f8.E4M3, sv.dy.inv_scale, w_is_t, g, s.dX, stream),
-            lambda: f8.gemm(f8.NT, N, K, M, sv.dy.q_t, grad_fmt, sv.x.q_t, f8.E4M3, dy_is_t, x_is_t, g, s.dW, stream),
-        ]
-        lin_gemm_ms = 0.0
-        for fn in gemms:
+        ops.append(("cast", li, cast_op(s.dY, sv.dy, grad_fmt), s.dY.numel()))
+        ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, w_is_t=w_is_t: f8.gemm(
+            f8.NT, M, K, N, sv.dy.q, grad_fmt, sv.w.q_t, f8.E4M3, sv.dy.inv_scale, w_is_t, g, s.dX, stream)),
+            2 * M * K * N))
+        ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, dy_is_t=dy_is_t, x_is_t=x_is_t: f8.gemm(
+            f8.NT, N, K, M, sv.dy.q_t, grad_fmt, sv.x.q_t, f8.E4M3, dy_is_t, x_is_t, g, s.dW, stream)),
+            2 * M * K * N))
+
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
+           for _ in range(reps)]
+    for _, _, fn, _ in ops:   # one untimed pass
+        fn()
+    for r in range(reps):
+        for (a, b), (_, _, fn, _) in zip(evs[r], ops):
+            a.record(stream)
             fn()
-            ms = timed(fn, reps)
-            lin_gemm_ms += ms
-            gemm_ms += ms
-            gemm_flops += 2 * M * K * N
-            gemm_launches += 1
-        lin_cast_ms = 0.0
-        if not rowwise:
-            for t, q, fmt in ((s.X, sv.x, f8.E4M3), (s.W, sv.w, f8.E4M3), (s.dY, sv.dy, grad_fmt)):
-                if args.scaling == "dynamic":
-                    fn = lambda: f8.amax_cast(t, f8.TENSORWISE, fmt, q.amax, q.scale, q.inv_scale, q.q, q.q_t, ws, stream)
-                elif args.scaling == "delayed":
-                    fn = lambda: f8.cast_amax(t, q.scale, fmt, q.amax, q.q, q.q_t, ws, stream)
-                else:
-                    fn = lambda: f8.cast(t, q.scale, f8.TENSORWISE, fmt, q.q, q.q_t, stream)
-                fn()
-                ms = timed(fn, reps)
-                lin_cast_ms += ms
-                cast_ms += ms
-                cast_elems += t.numel()
-        per_linear.append({"name": s.lin.name, "M": M, "K": K, "N": N,
-                           "gemm_ms": round(lin_gemm_ms, 4), "cast_ms": round(lin_cast_ms, 4),
-                           "gemm_tflops": round(6 * M * K * N / (lin_gemm_ms * 1e-3) / 1e12, 1)})
+            b.record(stream)
+    torch.cuda.synchronize()
+    op_ms = [sum(evs[r][i][0].elapsed_time(evs[r][i][1]) for r in range(reps)) / reps for i in range(len(ops))]
+
+    gemm_ms = sum(ms for ms, op in zip(op_ms, ops) if op[0] == "gemm")
+    gemm_flops = sum(op[3] for op in ops if op[0] == "gemm")
+    gemm_launches = sum(op[0] == "gemm" for op in ops)
+    cast_ms = sum(ms for ms, op in zip(op_ms, ops) if op[0] == "cast")
+    cast_elems = sum(op[3] for op in ops if op[0] == "cast")
+    per_linear = []
+    for li, s in enumerate(states):
+        lg = sum(ms for ms, op in zip(op_ms, ops) if op[0] == "gemm" and op[1] == li)
+        lc = sum(ms for ms, op in zip(op_ms, ops) if op[0] == "cast" and op[1] == li)
+        per_linear.append({"name": s.lin.name, "M": s.lin.M, "K": s.lin.K, "N": s.lin.N,
+                           "gemm_ms": round(lg, 4), "cast_ms": round(lc, 4),
+                           "gemm_tflops": round(s.lin.flops / (lg * 1e-3) / 1e12, 1)})
 
     gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12
     roofline = {
@@ -209,11 +231,12 @@ def main():
         # dynamic tensorwise amax+cast: 2 B amax read + 2 B cast re-read + 1 B write per element;
         # the transposed fp8 copy (+1 B/elem) is a design cost and not counted.
         # delayed / static scaling: the scale is known beforehand, one pass: 2 B read + 1 B write.
-        bpe = 5 if args.scaling == "dynamic" else 3
+        # rowwise: every tensor is quantised twice (per row, per column), 5 B/elem each.
+        bpe = (10 if rowwise else 5) if args.scaling == "dynamic" else 3
         gbs = bpe * cast_elems / (cast_ms * 1e-3) / 1e9
         cast = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_elem": bpe,
-                "moved_gbs_incl_transposed_copy": round((bpe + 1) * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
+                "moved_gbs_incl_transposed_copy": round((bpe + (0 if rowwise else 1)) * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
                 "ms_per_step": round(cast_ms, 4)}
 
     out = {

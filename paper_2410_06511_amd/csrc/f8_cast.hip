@@ -355,7 +355,13 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     for (int i = 0; i < 8; ++i) {
         const int64_t r = r0 + rr + 16 * i;
         v[i] = make_uint4(0, 0, 0, 0);
-        if (col_ok && r < rows) v[i] = *reinterpret_cast<const uint4*>(x + r * ld + col);
+        // Streaming load: this is the last read of x by the quantisation; lines it would leave in
+        // the caches only push out the codes that the GEMM reads next.
+        typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+        if (col_ok && r < rows) {
+            const u4v t = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(x + r * ld + col));
+            v[i] = make_uint4(t.x, t.y, t.z, t.w);
+        }
     }
     uint32_t macc = 0;
     if constexpr (MEASURE) {

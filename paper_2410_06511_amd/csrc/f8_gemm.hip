@@ -351,7 +351,13 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
 #ifdef F8_EXP_NO_STORE
                         ok = ok && v.x == 0x7fc17fc3u;  // perf probe only: (almost) never stores
 #endif
-                        if (ok) *reinterpret_cast<uint4*>(pbase + (voff + (uint32_t)(8 * t) * ldd_b)) = v;
+                        // Streaming store: D is not read again by this library, and lines that
+                        // linger dirty in the L2 / Infinity Cache would be written back during the
+                        // next, bandwidth-bound kernel instead of during this compute-bound one.
+                        typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+                        if (ok)
+                            __builtin_nontemporal_store(u4v{v.x, v.y, v.z, v.w},
+                                                        reinterpret_cast<u4v*>(pbase + (voff + (uint32_t)(8 * t) * ldd_b)));
                     }
                     // one pass at a time: measured faster than letting the compiler interleave passes
                     __builtin_amdgcn_sched_barrier(0);
