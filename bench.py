@@ -38,7 +38,7 @@ def parse():
                     help="skip timing torch.matmul in bf16 on the same shapes (context only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a device copy of known size (reference for the HBM byte counters)")
-    ap.add_argument("--cpu-sample-rows", type=int, default=2048)
+    ap.add_argument("--cpu-sample-rows", type=int, default=8192)
     return ap.parse_args()
 
 
@@ -281,7 +281,7 @@ def bf16_context(states, timed, reps, flops_step):
             fn()
             total += timed(fn, reps)
     return {"ms_per_step": round(total, 4), "tflops": round(flops_step / (total * 1e-3) / 1e12, 1),
-            "what": "torch.matmul bf16 (hipBLASLt), same 21 products, no casts"}
+            "what": f"torch.matmul bf16 (hipBLASLt), the same {3 * len(states)} products, no casts"}
 
 
 def committed_traffic():

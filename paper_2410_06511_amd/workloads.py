@@ -68,6 +68,14 @@ WORKLOADS = {
         w_std=0.01, variants=(("tensorwise", "e4m3"), ("rowwise", "e4m3"))),
     "llama8b_block": Workload("llama8b_block", 5, _llama8b(16384),
                               note="seven linears forward in model order, then backward in reverse"),
+    # The same block with the projections that share an input fused along N: one X cast and one
+    # wide GEMM for q|k|v (4096 + 1024 + 1024) and for w1|w3 (2 x 14336).  The fused dY then has
+    # ONE tensorwise scale, so results differ from the unfused linears by quantisation noise.
+    "llama8b_fused": Workload(
+        "llama8b_fused", 6,
+        [Linear("wqkv", 16384, 4096, 6144), Linear("wo", 16384, 4096, 4096),
+         Linear("w13", 16384, 4096, 28672), Linear("w2", 16384, 14336, 4096)],
+        note="llama8b_block with q|k|v and w1|w3 fused along N"),
 }
 
 

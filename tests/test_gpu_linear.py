@@ -103,14 +103,14 @@ def _full_size_cases():
     """Every distinct linear shape of every Llama-shaped workload, in each of the variants the
     workload is run in (tensorwise / rowwise scaling, e4m3 / e5m2 gradients)."""
     cases = []
+    seen = set()
     for key, w in wl.WORKLOADS.items():
         if key == "single":
             continue
-        seen = set()
         for li, lin in enumerate(w.linears):
-            if (lin.K, lin.N) in seen:
-                continue  # w3 repeats w1's shape, wv wk's, wo wq's
-            seen.add((lin.K, lin.N))
+            if (lin.M, lin.K, lin.N, w.variants) in seen:
+                continue  # w3 repeats w1's shape, wv wk's, wo wq's; the fused block repeats wo and w2
+            seen.add((lin.M, lin.K, lin.N, w.variants))
             for gran, gfmt in w.variants:
                 cases.append(pytest.param(key, li, gran == "rowwise", f8.E5M2 if gfmt == "e5m2" else f8.E4M3,
                                           id=f"{key}-{lin.name}-{gran}-{gfmt}"))
