@@ -181,9 +181,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     auto load_context = [&](int tile) {
         int tm, tn;
         tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
-#ifdef F8_EXP_SAME_TILE
-        tm = tn = 0;  // perf probe only: every tile loads the same rows (all loads hit in L2)
-#endif
         a_base = A + (int64_t)tm * BM * lda;
         b_base = B + (int64_t)tn * BN * ldb;
         a_rmax = M - 1 - tm * BM;  // rows past the edge re-read the last row; never stored
@@ -348,9 +345,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
                         bool ok = true;
                         if constexpr (!decltype(INTERIOR)::value)
                             ok = m0 + 32 * i + (idx >> 3) < M && n0 + 32 * jp + (idx & 7) * 8 < N;
-#ifdef F8_EXP_NO_STORE
-                        ok = ok && v.x == 0x7fc17fc3u;  // perf probe only: (almost) never stores
-#endif
                         // Streaming store: D is not read again by this library, and lines that
                         // linger dirty in the L2 / Infinity Cache would be written back during the
                         // next, bandwidth-bound kernel instead of during this compute-bound one.
@@ -456,10 +450,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         });
     };
 
-#ifdef F8_EXP_CLOCK
-    const uint64_t exp_c0 = __builtin_readcyclecounter(), exp_r0 = __builtin_amdgcn_s_memrealtime();
-    uint64_t exp_loop = 0, exp_epi = 0, exp_wait = 0;
-#endif
     // ---- main loop over this workgroup's tiles.  KT is even, so every tile starts in stage 0.
     // The step computed at kt fetches step kt + 2; the last two steps of a tile fetch the first
     // two of the next tile.
@@ -469,32 +459,19 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         // registers of pending stores, places its own full wait inside the K loop, where it
         // would also wait for the freshly issued loads on every step.  The loads in flight
         // here are this tile's first two K steps, requested a whole epilogue ago.
-#ifdef F8_EXP_CLOCK
-        const uint64_t exp_t0 = __builtin_readcyclecounter();
-#endif
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-#ifdef F8_EXP_CLOCK
-        const uint64_t exp_t1 = __builtin_readcyclecounter();
-#endif
         for (int kt = 0; kt < KT; kt += 2) {
             if (kt == KT - 2) next_load_tile();  // the last two steps fetch the next tile's first two
             const int f = kt == KT - 2 ? 0 : kt + 2;
             kstep(I0{}, f);
             kstep(I1{}, f + 1);
         }
-#ifdef F8_EXP_CLOCK
-        const uint64_t exp_t2 = __builtin_readcyclecounter();
-#endif
         epilogue(tile);
         zero_acc();
         // The next tile's first fragments are read again here rather than kept in registers
         // across the epilogue (the last K step already fetched them once): 64 registers less
         // for the epilogue to fight over.  Stage 0 is complete since that step's second barrier.
         read_frags(f0, I0{}, I0{});
-#ifdef F8_EXP_CLOCK
-        const uint64_t exp_t3 = __builtin_readcyclecounter();
-        exp_wait += exp_t1 - exp_t0, exp_loop += exp_t2 - exp_t1, exp_epi += exp_t3 - exp_t2;
-#endif
     }
     // no load may still be writing LDS when the workgroup ends
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -502,17 +479,6 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         __syncthreads();  // every wave is past its last epilogue pass: the staging buffer is free
         amax_publish<NW>(amax_acc, amax_bits, reinterpret_cast<uint32_t*>(epb));
     }
-#ifdef F8_EXP_CLOCK
-    // perf probe only: shader-clock ticks and 100 MHz ticks of this workgroup, into the first
-    // bytes of D (corrupts the result)
-    if (blockIdx.x == 17 && threadIdx.x == 0) {
-        __builtin_amdgcn_s_waitcnt(0);
-        uint64_t* o = reinterpret_cast<uint64_t*>(D);
-        o[0] = __builtin_readcyclecounter() - exp_c0;
-        o[1] = __builtin_amdgcn_s_memrealtime() - exp_r0;
-        o[2] = exp_wait, o[3] = exp_loop, o[4] = exp_epi;
-    }
-#endif
 }
 
 // ---------------------------------------------------------------------------
