@@ -166,6 +166,8 @@ f8_status f8_amax_history_push(float* history, int64_t len, const float* amax_ne
  * g = F8_TENSORWISE: inv_scale_a[0], inv_scale_b[0].
  * g = F8_ROWWISE:    inv_scale_a[M] (per output row), inv_scale_b[N] (per output column).
  * F8_COLWISE is not a GEMM mode (F8_ERR_ENUM).
+ * M, N, K and the leading dimensions must be below 2^23 (F8_ERR_SHAPE); the
+ * same bound holds for M, K, N of the linear-layer calls.
  * Summation order is unspecified (results agree with any fp32 order within
  * accumulation rounding).
  * amax_d (nullable, device, 1 float): if given, receives max |D[m,n]| over the

@@ -687,7 +687,8 @@ extern "C" f8_status f8_gemm(f8_layout layout, int64_t M, int64_t N, int64_t K, 
     if (!A || !B || !D_bf16 || !inv_scale_a || !inv_scale_b) return F8_ERR_NULL;
     if (M < 0 || N < 0 || K < 0 || (M % 16) || (N % 16) || (K % 16) || (lda % 16) || (ldb % 16) || (ldd % 16))
         return F8_ERR_SHAPE;
-    if (M >= (1 << 23) || N >= (1 << 23) || K >= (1 << 23) || lda >= (1 << 23) || ldb >= (1 << 23)) return F8_ERR_SHAPE;
+    if (M >= (1 << 23) || N >= (1 << 23) || K >= (1 << 23) || lda >= (1 << 23) || ldb >= (1 << 23) || ldd >= (1 << 23))
+        return F8_ERR_SHAPE;  // the kernels keep lane offsets inside a tile in 32 bits
     const int64_t a_cols = layout == F8_TN ? M : K, b_cols = layout == F8_NT ? K : N;
     if (lda < a_cols || ldb < b_cols || ldd < N) return F8_ERR_SHAPE;
     if (!aligned16(A) || !aligned16(B) || !aligned16(D_bf16)) return F8_ERR_ALIGN;
