@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--variant", default=None, help="granularity:gradfmt, e.g. tensorwise:e4m3")
     ap.add_argument("--scaling", default="dynamic", choices=["dynamic", "delayed", "static"],
                     help="per-tensor scaling strategy (delayed/static: tensorwise only, single-pass casts)")
+    ap.add_argument("--chain", action="store_true",
+                    help="llama8b shapes only: feed wq's Y to wo and w1's Y to w2 (and the gradients back), "
+                         "handing the amax from the producing GEMM's epilogue to the consumer's cast")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16-context", action="store_true",
                     help="skip timing torch.matmul in bf16 on the same shapes (context only)")
@@ -111,7 +114,35 @@ def main():
     states = [LinearState(f8, wl, w, li, rowwise, grad_fmt, args.scaling, ws) for li in range(len(w.linears))]
     stream = torch.cuda.current_stream()
 
-    if args.scaling == "dynamic":
+    chain_pairs = []
+    if args.chain:
+        names = [s.lin.name for s in states]
+        if args.scaling != "dynamic" or rowwise or names != ["wq", "wk", "wv", "wo", "w1", "w3", "w2"]:
+            print("bench.py: --chain needs an 8B-shaped workload with dynamic tensorwise scaling", file=sys.stderr)
+            sys.exit(2)
+        chain_pairs = [(0, 3), (4, 6)]   # producer -> consumer: wq -> wo, w1 -> w2
+    if chain_pairs:
+        prod = {p: c for p, c in chain_pairs}
+        cons = {c: p for p, c in chain_pairs}
+        amax_y = {p: torch.empty(1, device="cuda") for p in prod}      # max |Y| of the producer
+        amax_dx = {c: torch.empty(1, device="cuda") for c in cons}     # max |dX| of the consumer
+
+        def step():
+            for i, s in enumerate(states):
+                if i in prod:
+                    f8.linear_fwd_chained(s.desc, s.X, None, s.W, s.Y, amax_y[i], s.saved, ws, stream)
+                elif i in cons:
+                    f8.linear_fwd_chained(s.desc, states[cons[i]].Y, amax_y[cons[i]], s.W, s.Y, None, s.saved, ws, stream)
+                else:
+                    f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws, stream)
+            for i, s in reversed(list(enumerate(states))):
+                if i in cons:
+                    f8.linear_bwd_chained(s.desc, s.dY, None, s.saved, s.dX, amax_dx[i], s.dW, ws, stream)
+                elif i in prod:
+                    f8.linear_bwd_chained(s.desc, states[prod[i]].dX, amax_dx[prod[i]], s.saved, s.dX, None, s.dW, ws, stream)
+                else:
+                    f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws, stream)
+    elif args.scaling == "dynamic":
         def step():
             for s in states:                       # forward in model order
                 f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws, stream)
@@ -253,7 +284,7 @@ def main():
         "dtype": "fp8 (e4m3" + ("/e5m2 grads" if grad_fmt == f8.E5M2 else "") + ") x fp8 -> fp32 accumulate -> bf16",
         "data": "synthetic",
         "config": {"workload": f"{w.key}: " + ", ".join(f"{l.name}[M={l.M},K={l.K},N={l.N}]" for l in w.linears),
-                   "scaling_granularity": gran, "scaling_strategy": args.scaling, "grad_format": gfmt,
+                   "scaling_granularity": gran, "scaling_strategy": args.scaling, "grad_format": gfmt, "chained": bool(args.chain),
                    "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
         "roofline": roofline,

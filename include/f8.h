@@ -273,6 +273,29 @@ f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* 
                                f8_saved* saved, void* dX, void* dW, void* workspace,
                                size_t workspace_bytes, void* stream);
 
+/*
+ * The dynamic-scaling linear for a chain of Float8 linears, where one layer's
+ * output is the next layer's input: the amax of a GEMM output is taken in that
+ * GEMM's epilogue (see f8_gemm, amax_d) and handed to the consumer, whose
+ * quantisation of that tensor then needs a single pass (cast only) instead of
+ * two (amax, then cast).  Tensorwise only.
+ *
+ * f8_linear_fwd_chained: as f8_linear_fwd, but
+ *   x_amax (nullable, device, 1 float): amax of X, e.g. the y_amax of the
+ *     producing layer.  It must be exactly max |X| for the result to equal
+ *     f8_linear_fwd's; NULL: the amax pass runs as usual.
+ *   y_amax (nullable, device, 1 float): receives max |Y|.
+ * f8_linear_bwd_chained: as f8_linear_bwd, with dy_amax given (nullable) and
+ *   dx_amax (nullable) receiving max |dX| for the layer below.
+ */
+f8_status f8_linear_fwd_chained(const f8_linear_desc* d, const void* X, const float* x_amax,
+                                const void* W, void* Y, float* y_amax, f8_saved* saved,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
+f8_status f8_linear_bwd_chained(const f8_linear_desc* d, const void* dY, const float* dy_amax,
+                                f8_saved* saved, void* dX, float* dx_amax, void* dW,
+                                void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -228,6 +228,17 @@ __global__ __launch_bounds__(kThreads) void history_push_kernel(
     }
 }
 
+// dynamic scaling with the amax already known: amax -> scale, 1/scale
+__global__ void known_amax_kernel(const float* __restrict__ amax_in, float fm, float* __restrict__ amax_out,
+                                  float* __restrict__ scale_out, float* __restrict__ inv_out)
+{
+    const float a = amax_in[0];
+    const float s = scale_from_amax(a, fm);
+    amax_out[0] = a;
+    scale_out[0] = s;
+    inv_out[0] = 1.0f / s;
+}
+
 // copies a given scale and its reciprocal (static scaling: the GEMM epilogue reads 1/scale)
 __global__ void publish_scale_kernel(const float* __restrict__ s_in, float* __restrict__ s_out,
                                      float* __restrict__ inv_out)
@@ -658,6 +669,18 @@ f8_status publish_scale(const float* s_in, float* s_out, float* inv_out, hipStre
 {
     publish_scale_kernel<<<1, 1, 0, st>>>(s_in, s_out, inv_out);
     return last_launch_status();
+}
+
+// amax is known (taken by the producer of x): publish amax / scale / 1/scale, then one cast pass.
+f8_status quantise_known_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, const float* amax_in,
+                              float* amax_out, float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,
+                              uint8_t* out_t, int64_t ld_out_t, hipStream_t st)
+{
+    known_amax_kernel<<<1, 1, 0, st>>>(amax_in, fmax_of(fmt), amax_out, scale_out, inv_out);
+    f8_status s = last_launch_status();
+    if (s != F8_OK) return s;
+    return launch_cast<false>(x, rows, cols, ld, scale_out, F8_TENSORWISE, fmt, nullptr, 0, nullptr, nullptr, nullptr,
+                              out, ld_out, out_t, ld_out_t, st);
 }
 
 f8_status cast_given(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,

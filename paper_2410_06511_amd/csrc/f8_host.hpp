@@ -33,6 +33,11 @@ f8_status publish_scale(const float* s_in, float* s_out, float* inv_out, hipStre
 f8_status cast_given(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
                      uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, hipStream_t st);
 
+// Dynamic scaling of a tensorwise tensor whose amax the producer already took: one cast pass.
+f8_status quantise_known_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, const float* amax_in,
+                              float* amax_out, float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,
+                              uint8_t* out_t, int64_t ld_out_t, hipStream_t st);
+
 // Validated GEMM launch (see f8_gemm); amax_d may be null.
 f8_status gemm(int layout, int64_t M, int64_t N, int64_t K, const uint8_t* A, int fa, int64_t lda,
                const uint8_t* B, int fb, int64_t ldb, const float* isa, const float* isb, int g,

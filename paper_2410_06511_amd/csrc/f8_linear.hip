@@ -207,4 +207,58 @@ f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* 
                 saved->x.inv_scale, F8_TENSORWISE, dW, K, nullptr, st);
 }
 
+f8_status f8_linear_fwd_chained(const f8_linear_desc* d, const void* X, const float* x_amax, const void* W,
+                                void* Y, float* y_amax, f8_saved* saved, void* workspace,
+                                size_t workspace_bytes_, void* stream)
+{
+    f8_status s = check_desc(d);
+    if (s != F8_OK) return s;
+    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
+    if (!X || !W || !Y || !saved) return F8_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return F8_ERR_ALIGN;
+    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t M = d->M, K = d->K, N = d->N;
+    if (x_amax)
+        s = quantise_known_amax(X, M, K, K, F8_E4M3, x_amax, saved->x.amax, saved->x.scale, saved->x.inv_scale,
+                                saved->x.q, K, saved->x.q_t, M, st);
+    else
+        s = quantise_both(X, M, K, false, F8_E4M3, &saved->x, workspace, st);
+    if (s != F8_OK) return s;
+    if ((s = quantise_both(W, N, K, false, F8_E4M3, &saved->w, workspace, st)) != F8_OK) return s;
+    return gemm(F8_NT, M, N, K, saved->x.q, F8_E4M3, K, saved->w.q, F8_E4M3, K, saved->x.inv_scale,
+                saved->w.inv_scale, F8_TENSORWISE, Y, N, y_amax, st);
+}
+
+f8_status f8_linear_bwd_chained(const f8_linear_desc* d, const void* dY, const float* dy_amax, f8_saved* saved,
+                                void* dX, float* dx_amax, void* dW, void* workspace, size_t workspace_bytes_,
+                                void* stream)
+{
+    f8_status s = check_desc(d);
+    if (s != F8_OK) return s;
+    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
+    if (!dY || !dX || !dW || !saved) return F8_ERR_NULL;
+    if (!aligned16(dY) || !aligned16(dX) || !aligned16(dW)) return F8_ERR_ALIGN;
+    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
+    if ((s = check_q(&saved->dy, false)) != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t M = d->M, K = d->K, N = d->N;
+    const int gf = d->grad_format;
+    if (dy_amax)
+        s = quantise_known_amax(dY, M, N, N, gf, dy_amax, saved->dy.amax, saved->dy.scale, saved->dy.inv_scale,
+                                saved->dy.q, N, saved->dy.q_t, M, st);
+    else
+        s = quantise_both(dY, M, N, false, gf, &saved->dy, workspace, st);
+    if (s != F8_OK) return s;
+    if ((s = gemm(F8_NT, M, K, N, saved->dy.q, gf, N, saved->w.q_t, F8_E4M3, N, saved->dy.inv_scale,
+                  saved->w.inv_scale, F8_TENSORWISE, dX, K, dx_amax, st)) != F8_OK)
+        return s;
+    return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, saved->dy.inv_scale,
+                saved->x.inv_scale, F8_TENSORWISE, dW, K, nullptr, st);
+}
+
 }  // extern "C"

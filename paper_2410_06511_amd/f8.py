@@ -24,7 +24,8 @@ _i64, _int, _p = C.c_int64, C.c_int, C.c_void_p
 
 EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_cast", "f8_encode_f32",
            "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
-           "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled"]
+           "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled",
+           "f8_linear_fwd_chained", "f8_linear_bwd_chained"]
 
 
 class F8Error(RuntimeError):
@@ -76,6 +77,10 @@ def lib():
                                            C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         l.f8_linear_bwd_scaled.argtypes = [C.POINTER(LinearDesc), C.POINTER(ScalingStateStruct), _p,
                                            C.POINTER(SavedStruct), _p, _p, _p, C.c_size_t, _p]
+        l.f8_linear_fwd_chained.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, _p, _p, C.POINTER(SavedStruct), _p,
+                                            C.c_size_t, _p]
+        l.f8_linear_bwd_chained.argtypes = [C.POINTER(LinearDesc), _p, _p, C.POINTER(SavedStruct), _p, _p, _p, _p,
+                                            C.c_size_t, _p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
         _lib = l
@@ -241,3 +246,17 @@ def linear_bwd_scaled(desc, state, dY, saved, dX, dW, workspace, stream=None):
     wp, wb = _ws(workspace)
     _check(lib().f8_linear_bwd_scaled(C.byref(desc), C.byref(state.struct()), _ptr(dY), C.byref(saved.struct()),
                                       _ptr(dX), _ptr(dW), wp, wb, _stream(stream)))
+
+
+# ---- chained linears: amax handed from the producing GEMM to the consumer ----------
+
+def linear_fwd_chained(desc, X, x_amax, W, Y, y_amax, saved, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().f8_linear_fwd_chained(C.byref(desc), _ptr(X), _ptr(x_amax), _ptr(W), _ptr(Y), _ptr(y_amax),
+                                       C.byref(saved.struct()), wp, wb, _stream(stream)))
+
+
+def linear_bwd_chained(desc, dY, dy_amax, saved, dX, dx_amax, dW, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().f8_linear_bwd_chained(C.byref(desc), _ptr(dY), _ptr(dy_amax), C.byref(saved.struct()), _ptr(dX),
+                                       _ptr(dx_amax), _ptr(dW), wp, wb, _stream(stream)))
