@@ -25,6 +25,10 @@
  *   - NaN input to the cast gives a NaN code (0x7F or 0xFF; the sign is not specified).
  *   - rowwise scaling: each GEMM operand has one scale per index of its
  *     non-contracted dimension, amax taken along the contracted dimension.
+ *   - delayed scaling (f8o_history_push): the scale of a step is FMAX over the
+ *     maximum of the amax values recorded at earlier steps (a window of `len`),
+ *     the step's own amax is recorded after its cast.  Static scaling: a
+ *     constant scale.  The paper only names the two strategies.
  *
  * Every function takes host pointers.  Matrices are row-major with a leading
  * dimension in elements.  bf16 values travel as uint16_t bit patterns, fp8
