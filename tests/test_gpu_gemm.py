@@ -177,3 +177,50 @@ def test_gemm_amax_of_empty_output_is_zero():
                             0, D.data_ptr(), 16, amax.data_ptr(), None)
     torch.cuda.synchronize()
     assert code == 0 and amax.item() == 0.0
+
+
+# Ragged shapes large enough to be dispatched to each tile configuration of the fast kernel
+# (which one is chosen depends on how many tiles the shape has against the number of compute
+# units): 256x256 tiles with a ragged last tile row and column, 256x128 tiles likewise, and
+# shapes whose edges are narrower than one MFMA tile.  Compared in full.
+@pytest.mark.parametrize("g", [f8.TENSORWISE, f8.ROWWISE])
+@pytest.mark.parametrize("M,N,K", [(4112, 4144, 256), (2064, 3600, 512), (4368, 4112, 512), (272, 65552, 256)])
+def test_gemm_fast_kernel_ragged_big_tiles(M, N, K, g):
+    rng = np.random.default_rng(M + N)
+    A, B = rand_codes(rng, (M, K), o.E4M3), rand_codes(rng, (N, K), o.E5M2)
+    if g == f8.TENSORWISE:
+        isa, isb = np.float32(2.0 ** -5), np.float32(2.0 ** -9)
+    else:
+        isa = (rng.uniform(0.5, 2.0, M) * 2.0 ** -5).astype(np.float32)
+        isb = (rng.uniform(0.5, 2.0, N) * 2.0 ** -9).astype(np.float32)
+    got = run_gemm(o.NT, M, N, K, A, o.E4M3, B, o.E5M2, isa, isb, g)
+    ref = o.gemm(o.NT, A, o.E4M3, B, o.E5M2, isa, isb, g)
+    assert_gemm_close(got, ref, (M, N, K, g))
+    # per-row check as well, so that a wrong edge row cannot hide behind the global maximum
+    gf, rf = o.bf16_to_f32(got).astype(np.float64), o.bf16_to_f32(ref).astype(np.float64)
+    row_err = np.abs(gf - rf).max(axis=1)
+    assert (row_err <= 1e-2 * np.abs(rf).max()).all()
+    col_err = np.abs(gf - rf).max(axis=0)
+    assert (col_err <= 1e-2 * np.abs(rf).max()).all()
+
+
+@pytest.mark.parametrize("M,N,K", [(8192, 4096, 4096), (8192, 1024, 4096), (1024, 4096, 8192)])
+def test_gemm_is_deterministic(M, N, K):
+    """The persistent kernel's LDS pipeline has no run-to-run freedom: repeated launches (one per
+    tile configuration of the 8B shapes), interleaved with a launch that disturbs the caches,
+    give identical bits."""
+    rng = np.random.default_rng(K)
+    Ad = torch.from_numpy(rand_codes(rng, (M, K), o.E4M3)).cuda()
+    Bd = torch.from_numpy(rand_codes(rng, (N, K), o.E4M3)).cuda()
+    one = torch.ones(1, device="cuda")
+    big = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    outs = []
+    for i in range(6):
+        D = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+        if i % 2:
+            big.fill_(i)
+        f8.gemm(f8.NT, M, N, K, Ad, o.E4M3, Bd, o.E4M3, one, one, f8.TENSORWISE, D)
+        outs.append(D)
+    torch.cuda.synchronize()
+    for D in outs[1:]:
+        assert torch.equal(D.view(torch.int16), outs[0].view(torch.int16))
