@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--chain", action="store_true",
                     help="llama8b shapes only: feed wq's Y to wo and w1's Y to w2 (and the gradients back), "
                          "handing the amax from the producing GEMM's epilogue to the consumer's cast")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step into a HIP graph once and time its replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16-context", action="store_true",
                     help="skip timing torch.matmul in bf16 on the same shapes (context only)")
@@ -112,7 +114,7 @@ def main():
     dmax = max(max(l.M, l.K, l.N) for l in w.linears)
     ws = f8.new_workspace(dmax, dmax)
     states = [LinearState(f8, wl, w, li, rowwise, grad_fmt, args.scaling, ws) for li in range(len(w.linears))]
-    stream = torch.cuda.current_stream()
+    stream = torch.cuda.current_stream()   # the per-kernel legs below; the step uses the current stream
 
     chain_pairs = []
     if args.chain:
@@ -130,37 +132,47 @@ def main():
         def step():
             for i, s in enumerate(states):
                 if i in prod:
-                    f8.linear_fwd_chained(s.desc, s.X, None, s.W, s.Y, amax_y[i], s.saved, ws, stream)
+                    f8.linear_fwd_chained(s.desc, s.X, None, s.W, s.Y, amax_y[i], s.saved, ws)
                 elif i in cons:
-                    f8.linear_fwd_chained(s.desc, states[cons[i]].Y, amax_y[cons[i]], s.W, s.Y, None, s.saved, ws, stream)
+                    f8.linear_fwd_chained(s.desc, states[cons[i]].Y, amax_y[cons[i]], s.W, s.Y, None, s.saved, ws)
                 else:
-                    f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws, stream)
+                    f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws)
             for i, s in reversed(list(enumerate(states))):
                 if i in cons:
-                    f8.linear_bwd_chained(s.desc, s.dY, None, s.saved, s.dX, amax_dx[i], s.dW, ws, stream)
+                    f8.linear_bwd_chained(s.desc, s.dY, None, s.saved, s.dX, amax_dx[i], s.dW, ws)
                 elif i in prod:
-                    f8.linear_bwd_chained(s.desc, states[prod[i]].dX, amax_dx[prod[i]], s.saved, s.dX, None, s.dW, ws, stream)
+                    f8.linear_bwd_chained(s.desc, states[prod[i]].dX, amax_dx[prod[i]], s.saved, s.dX, None, s.dW, ws)
                 else:
-                    f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws, stream)
+                    f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws)
     elif args.scaling == "dynamic":
         def step():
             for s in states:                       # forward in model order
-                f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws, stream)
+                f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws)
             for s in reversed(states):             # backward in reverse
-                f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws, stream)
+                f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws)
     else:
         def step():
             for s in states:
-                f8.linear_fwd_scaled(s.desc, s.state, s.X, s.W, s.Y, s.saved, ws, stream)
+                f8.linear_fwd_scaled(s.desc, s.state, s.X, s.W, s.Y, s.saved, ws)
             for s in reversed(states):
-                f8.linear_bwd_scaled(s.desc, s.state, s.dY, s.saved, s.dX, s.dW, ws, stream)
+                f8.linear_bwd_scaled(s.desc, s.state, s.dY, s.saved, s.dX, s.dW, ws)
 
-    for _ in range(args.warmup):
+    run_step = step
+    if args.graph:
+        # the library only enqueues kernels, so the whole step can be captured; the replay
+        # issues the same kernels on the same buffers with one launch call
         step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
+            step()
+        run_step = graph.replay
+    for _ in range(args.warmup):
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -284,7 +296,7 @@ def main():
         "dtype": "fp8 (e4m3" + ("/e5m2 grads" if grad_fmt == f8.E5M2 else "") + ") x fp8 -> fp32 accumulate -> bf16",
         "data": "synthetic",
         "config": {"workload": f"{w.key}: " + ", ".join(f"{l.name}[M={l.M},K={l.K},N={l.N}]" for l in w.linears),
-                   "scaling_granularity": gran, "scaling_strategy": args.scaling, "grad_format": gfmt, "chained": bool(args.chain),
+                   "scaling_granularity": gran, "scaling_strategy": args.scaling, "grad_format": gfmt, "chained": bool(args.chain), "hip_graph": bool(args.graph),
                    "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
         "roofline": roofline,
