@@ -297,66 +297,84 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         const bool interior = tm * BM + BM <= M && tn * BN + BN <= N;  // no edge checks needed
 
         auto run = [&](auto INTERIOR) {
+            // One pass = rows 32 i .. 32 i + 31, columns 32 jp .. 32 jp + 63 of the wave's tile.
+            // Tensorwise: row bands outermost.  Per-row / per-column scales: column pairs
+            // outermost, so that the eight 4-float pieces of the column scales a lane needs are
+            // loaded once per column pair (and the row scales once per tile) instead of in every
+            // pass, where their latency would sit in front of each conversion.
+            constexpr int NP = TM * (TN / 2);
+            float sav[TM];
+            float4 sbv[8];
+            if constexpr (GRAN != F8_TENSORWISE) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                float sa = 0.f;
-                if constexpr (GRAN != F8_TENSORWISE) {
+                for (int i = 0; i < TM; ++i) {
                     const int m_lane = m0 + 32 * i + fr;
-                    sa = isa[m_lane < M ? m_lane : M - 1];
-                }
-#pragma unroll
-                for (int jp = 0; jp < TN; jp += 2) {  // two MFMA tiles = 64 columns per pass
-#pragma unroll
-                    for (int jj = 0; jj < 2; ++jj) {
-                        const int j = jp + jj;
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int nl = 32 * jj + 8 * q + 4 * fg;  // column inside the pass
-                            f2 lo, hi;
-                            if constexpr (GRAN == F8_TENSORWISE) {
-                                lo = f2{acc[i][j][4 * q] * s_tensor, acc[i][j][4 * q + 1] * s_tensor};
-                                hi = f2{acc[i][j][4 * q + 2] * s_tensor, acc[i][j][4 * q + 3] * s_tensor};
-                            } else {
-                                int n = n0 + 32 * jp + nl;
-                                n = n < N ? n : N - 4;
-                                const float4 sb = *reinterpret_cast<const float4*>(isb + n);
-                                lo = f2{(acc[i][j][4 * q] * sa) * sb.x, (acc[i][j][4 * q + 1] * sa) * sb.y};
-                                hi = f2{(acc[i][j][4 * q + 2] * sa) * sb.z, (acc[i][j][4 * q + 3] * sa) * sb.w};
-                            }
-                            // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
-                            uint2 o;
-                            o.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, b2));
-                            o.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, b2));
-                            if constexpr (AMAX) {
-                                // edge tiles hold results of re-read rows past M / N: not output
-                                bool counted = true;
-                                if constexpr (!decltype(INTERIOR)::value)
-                                    counted = m0 + 32 * i + fr < M && n0 + 32 * jp + nl < N;
-                                if (counted) amax_acc = amax_pair(amax_acc, o);
-                            }
-                            *reinterpret_cast<uint2*>(ep + fr * EP_STRIDE + nl * 2) = o;
-                        }
-                    }
-                    uint8_t* pbase = dbase + ((int64_t)(32 * i) * ldd + 32 * jp) * 2;  // uniform
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const int idx = t * 64 + lane;
-                        const uint4 v = *reinterpret_cast<const uint4*>(ep + (idx >> 3) * EP_STRIDE + (idx & 7) * 16);
-                        bool ok = true;
-                        if constexpr (!decltype(INTERIOR)::value)
-                            ok = m0 + 32 * i + (idx >> 3) < M && n0 + 32 * jp + (idx & 7) * 8 < N;
-                        // Streaming store: D is not read again by this library, and lines that
-                        // linger dirty in the L2 / Infinity Cache would be written back during the
-                        // next, bandwidth-bound kernel instead of during this compute-bound one.
-                        typedef unsigned int u4v __attribute__((ext_vector_type(4)));
-                        if (ok)
-                            __builtin_nontemporal_store(u4v{v.x, v.y, v.z, v.w},
-                                                        reinterpret_cast<u4v*>(pbase + (voff + (uint32_t)(8 * t) * ldd_b)));
-                    }
-                    // one pass at a time: measured faster than letting the compiler interleave passes
-                    __builtin_amdgcn_sched_barrier(0);
+                    sav[i] = isa[m_lane < M ? m_lane : M - 1];
                 }
             }
+            static_for<NP>([&](auto P) {
+                constexpr int p = decltype(P)::value;
+                constexpr int i = GRAN == F8_TENSORWISE ? p / (TN / 2) : p % TM;
+                constexpr int jp = GRAN == F8_TENSORWISE ? (p % (TN / 2)) * 2 : (p / TM) * 2;
+                if constexpr (GRAN != F8_TENSORWISE && i == 0) {
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            int n = n0 + 32 * jp + 32 * jj + 8 * q + 4 * fg;
+                            n = n < N ? n : N - 4;
+                            sbv[jj * 4 + q] = *reinterpret_cast<const float4*>(isb + n);
+                        }
+                }
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = jp + jj;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int nl = 32 * jj + 8 * q + 4 * fg;  // column inside the pass
+                        f2 lo, hi;
+                        if constexpr (GRAN == F8_TENSORWISE) {
+                            lo = f2{acc[i][j][4 * q] * s_tensor, acc[i][j][4 * q + 1] * s_tensor};
+                            hi = f2{acc[i][j][4 * q + 2] * s_tensor, acc[i][j][4 * q + 3] * s_tensor};
+                        } else {
+                            const float sa = sav[i];
+                            const float4 sb = sbv[jj * 4 + q];
+                            lo = f2{(acc[i][j][4 * q] * sa) * sb.x, (acc[i][j][4 * q + 1] * sa) * sb.y};
+                            hi = f2{(acc[i][j][4 * q + 2] * sa) * sb.z, (acc[i][j][4 * q + 3] * sa) * sb.w};
+                        }
+                        // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
+                        uint2 o;
+                        o.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, b2));
+                        o.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, b2));
+                        if constexpr (AMAX) {
+                            // edge tiles hold results of re-read rows past M / N: not output
+                            bool counted = true;
+                            if constexpr (!decltype(INTERIOR)::value)
+                                counted = m0 + 32 * i + fr < M && n0 + 32 * jp + nl < N;
+                            if (counted) amax_acc = amax_pair(amax_acc, o);
+                        }
+                        *reinterpret_cast<uint2*>(ep + fr * EP_STRIDE + nl * 2) = o;
+                    }
+                }
+                uint8_t* pbase = dbase + ((int64_t)(32 * i) * ldd + 32 * jp) * 2;  // uniform
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int idx = t * 64 + lane;
+                    const uint4 v = *reinterpret_cast<const uint4*>(ep + (idx >> 3) * EP_STRIDE + (idx & 7) * 16);
+                    bool ok = true;
+                    if constexpr (!decltype(INTERIOR)::value)
+                        ok = m0 + 32 * i + (idx >> 3) < M && n0 + 32 * jp + (idx & 7) * 8 < N;
+                    // Streaming store: D is not read again by this library, and lines that
+                    // linger dirty in the L2 / Infinity Cache would be written back during the
+                    // next, bandwidth-bound kernel instead of during this compute-bound one.
+                    typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+                    if (ok)
+                        __builtin_nontemporal_store(u4v{v.x, v.y, v.z, v.w},
+                                                    reinterpret_cast<u4v*>(pbase + (voff + (uint32_t)(8 * t) * ldd_b)));
+                }
+                // one pass at a time: measured faster than letting the compiler interleave passes
+                __builtin_amdgcn_sched_barrier(0);
+            });
         };
         if (interior)
             run(std::true_type{});
