@@ -209,6 +209,19 @@ typedef struct f8_saved {
     f8_qtensor dy;
 } f8_saved;
 
+/*
+ * The quantisation the linear layer applies to one bf16 tensor T [rows, cols]
+ * (leading dimension cols) under dynamic scaling, both orientations at once:
+ *   g = F8_TENSORWISE: q->amax / scale / inv_scale (1 entry), q->q [rows, cols]
+ *     and q->q_t [cols, rows] with the same codes.
+ *   g = F8_ROWWISE: q->q with one scale per row (amax, scale, inv_scale: rows
+ *     entries) and q->q_t with one scale per column of T (amax_t, scale_t,
+ *     inv_scale_t: cols entries); T is read once for both casts.
+ * workspace: f8_workspace_bytes(rows, cols) bytes.
+ */
+f8_status f8_quantise(const void* t_bf16, int64_t rows, int64_t cols, f8_granularity g, f8_format fmt,
+                      const f8_qtensor* q, void* workspace, size_t workspace_bytes, void* stream);
+
 typedef struct f8_linear_desc {
     int64_t M, K, N;
     int32_t granularity; /* F8_TENSORWISE or F8_ROWWISE */

@@ -106,9 +106,24 @@ __global__ __launch_bounds__(kThreads) void amax_rows_kernel(
 // ---------------------------------------------------------------------------
 // per-column amax: grid (column strips of 128, row chunks); partial[chunk][col]
 // ---------------------------------------------------------------------------
+// ROWS: the same pass also leaves, for every row, the maximum over this block's 128 columns in
+// row_partial[strip][row] (both amax sets of rowwise scaling from one read of x).
+__device__ inline uint32_t row_piece_max(uint4 v)
+{
+    // largest magnitude of the eight bf16 of a chunk, then of the 16 lanes that share the row
+    uint32_t m = pk_collapse(pkmax(pkmax(v.x & 0x7FFF7FFFu, v.y & 0x7FFF7FFFu), pkmax(v.z & 0x7FFF7FFFu, v.w & 0x7FFF7FFFu)));
+#pragma unroll
+    for (int off = 8; off >= 1; off >>= 1) {
+        const uint32_t o = (uint32_t)__shfl_xor((int)m, off, kWave);
+        m = o > m ? o : m;
+    }
+    return m;
+}
+
+template <bool ROWS>
 __global__ __launch_bounds__(kThreads) void amax_cols_partial_kernel(
     const uint4* __restrict__ x, int64_t rows, int64_t cols, int64_t ld_chunks, int64_t rows_per_chunk,
-    uint32_t* __restrict__ partial /* [gridDim.y][cols] */)
+    uint32_t* __restrict__ partial /* [gridDim.y][cols] */, uint32_t* __restrict__ row_partial /* [gridDim.x][rows] */)
 {
     __shared__ uint32_t red[16][64 + 1];  // [row lane][word of the strip: 64 words = 128 columns]
     const int cc = threadIdx.x & 15;      // which 16-byte chunk (8 columns) of the strip
@@ -118,22 +133,48 @@ __global__ __launch_bounds__(kThreads) void amax_cols_partial_kernel(
     int64_t r_end = r_begin + rows_per_chunk;
     if (r_end > rows) r_end = rows;
     uint32_t a0 = 0, a1 = 0, a2 = 0, a3 = 0;
-    if (col0 < cols) {
-        const uint4* p = x + (col0 >> 3);
-        int64_t r = r_begin + rl;
-        for (; r + 16 < r_end; r += 32) {
-            uint4 v = p[r * ld_chunks], w = p[(r + 16) * ld_chunks];
+    if constexpr (!ROWS) {
+        if (col0 < cols) {
+            const uint4* p = x + (col0 >> 3);
+            int64_t r = r_begin + rl;
+            for (; r + 16 < r_end; r += 32) {
+                uint4 v = p[r * ld_chunks], w = p[(r + 16) * ld_chunks];
+                a0 = pkmax(a0, pkmax(v.x & 0x7FFF7FFFu, w.x & 0x7FFF7FFFu));
+                a1 = pkmax(a1, pkmax(v.y & 0x7FFF7FFFu, w.y & 0x7FFF7FFFu));
+                a2 = pkmax(a2, pkmax(v.z & 0x7FFF7FFFu, w.z & 0x7FFF7FFFu));
+                a3 = pkmax(a3, pkmax(v.w & 0x7FFF7FFFu, w.w & 0x7FFF7FFFu));
+            }
+            for (; r < r_end; r += 16) {
+                uint4 v = p[r * ld_chunks];
+                a0 = pkmax(a0, v.x & 0x7FFF7FFFu);
+                a1 = pkmax(a1, v.y & 0x7FFF7FFFu);
+                a2 = pkmax(a2, v.z & 0x7FFF7FFFu);
+                a3 = pkmax(a3, v.w & 0x7FFF7FFFu);
+            }
+        }
+    } else {
+        // Every lane takes part in the row reduction (the 16 lanes of a row form one shuffle
+        // group); lanes past the last column contribute zeros.  rows_per_chunk is a multiple of
+        // 16 and so is rows, hence all 16 row lanes of the block run the same number of steps.
+        const bool col_ok = col0 < cols;
+        const uint4* p = x + (col_ok ? (col0 >> 3) : 0);
+        uint32_t* rp = row_partial + (int64_t)blockIdx.x * rows;
+        for (int64_t r = r_begin + rl; r < r_end; r += 32) {
+            const bool two = r + 16 < r_end;
+            uint4 v = make_uint4(0, 0, 0, 0), w = make_uint4(0, 0, 0, 0);
+            if (col_ok) {
+                v = p[r * ld_chunks];
+                if (two) w = p[(r + 16) * ld_chunks];
+            }
             a0 = pkmax(a0, pkmax(v.x & 0x7FFF7FFFu, w.x & 0x7FFF7FFFu));
             a1 = pkmax(a1, pkmax(v.y & 0x7FFF7FFFu, w.y & 0x7FFF7FFFu));
             a2 = pkmax(a2, pkmax(v.z & 0x7FFF7FFFu, w.z & 0x7FFF7FFFu));
             a3 = pkmax(a3, pkmax(v.w & 0x7FFF7FFFu, w.w & 0x7FFF7FFFu));
-        }
-        for (; r < r_end; r += 16) {
-            uint4 v = p[r * ld_chunks];
-            a0 = pkmax(a0, v.x & 0x7FFF7FFFu);
-            a1 = pkmax(a1, v.y & 0x7FFF7FFFu);
-            a2 = pkmax(a2, v.z & 0x7FFF7FFFu);
-            a3 = pkmax(a3, v.w & 0x7FFF7FFFu);
+            const uint32_t mv = row_piece_max(v), mw = row_piece_max(w);
+            if (cc == 0) {
+                rp[r] = mv;
+                if (two) rp[r + 16] = mw;
+            }
         }
     }
     red[rl][cc * 4 + 0] = a0;
@@ -154,23 +195,44 @@ __global__ __launch_bounds__(kThreads) void amax_cols_partial_kernel(
     }
 }
 
-__global__ __launch_bounds__(kThreads) void amax_cols_final_kernel(
-    const uint32_t* __restrict__ partial, int nchunks, int64_t cols, float fm,
+// out[j] = max over i < n_outer of partial[i * n_inner + j], with scale and 1/scale: the second
+// stage of the per-column maxima (n_outer row chunks, n_inner = cols) and of the per-row maxima
+// (n_outer column strips, n_inner = rows).  A block owns 64 consecutive j (coalesced reads)
+// and splits the outer index over its four wavefronts, which meet in LDS.
+__global__ __launch_bounds__(kThreads) void amax_vector_final_kernel(
+    const uint32_t* __restrict__ partial, int n_outer, int64_t n_inner, float fm,
     float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out)
 {
-    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (c >= cols) return;
+    __shared__ uint32_t red[kWaves][kWave];
+    const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
+    const int64_t j = (int64_t)blockIdx.x * kWave + lane;
     uint32_t m = 0;
-    for (int i = 0; i < nchunks; ++i) {
-        uint32_t p = partial[(int64_t)i * cols + c];
-        m = p > m ? p : m;
+    if (j < n_inner) {
+        int i = w;
+        for (; i + 3 * kWaves < n_outer; i += 4 * kWaves) {
+            const uint32_t p0 = partial[(int64_t)i * n_inner + j], p1 = partial[(int64_t)(i + kWaves) * n_inner + j];
+            const uint32_t p2 = partial[(int64_t)(i + 2 * kWaves) * n_inner + j];
+            const uint32_t p3 = partial[(int64_t)(i + 3 * kWaves) * n_inner + j];
+            const uint32_t a = p0 > p1 ? p0 : p1, b = p2 > p3 ? p2 : p3;
+            m = a > m ? a : m;
+            m = b > m ? b : m;
+        }
+        for (; i < n_outer; i += kWaves) {
+            const uint32_t p = partial[(int64_t)i * n_inner + j];
+            m = p > m ? p : m;
+        }
     }
-    float a = mag_to_float(m);
-    amax_out[c] = a;
+    red[w][lane] = m;
+    __syncthreads();
+    if (w != 0 || j >= n_inner) return;
+#pragma unroll
+    for (int k = 1; k < kWaves; ++k) m = red[k][lane] > m ? red[k][lane] : m;
+    const float a = mag_to_float(m);
+    amax_out[j] = a;
     if (scale_out) {
-        float s = scale_from_amax(a, fm);
-        scale_out[c] = s;
-        if (inv_out) inv_out[c] = 1.0f / s;
+        const float s = scale_from_amax(a, fm);
+        scale_out[j] = s;
+        if (inv_out) inv_out[j] = 1.0f / s;
     }
 }
 
@@ -302,6 +364,9 @@ __global__ __launch_bounds__(kThreads) void cast_stream_kernel(
 // full 128-byte row segments.
 // ---------------------------------------------------------------------------
 constexpr int kTile = 128;
+// Internal granularity of the tiled cast: `out` with one scale per row (scale[rows]) and, from
+// the same read of x, `out_t` with one scale per column (scale_col[cols]): different codes.
+constexpr int kGranBoth = 3;
 constexpr int kLdsStride = 33;  // words per LDS tile row (32 data + 1 pad)
 
 // 4x4 byte transpose: in r[j] byte i = element (row j, col i); out c[i] byte j.
@@ -327,7 +392,7 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     const float* __restrict__ scale, const uint32_t* __restrict__ partial, int npartial,
     float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out,
     uint8_t* __restrict__ out, int64_t ld_out, uint8_t* __restrict__ out_t, int64_t ld_out_t,
-    int tiles_c, uint32_t* __restrict__ partial_out = nullptr)
+    int tiles_c, uint32_t* __restrict__ partial_out = nullptr, const float* __restrict__ scale_col = nullptr)
 {
     __shared__ uint32_t red[kWaves];
     __shared__ uint32_t tile[kTile * kLdsStride];
@@ -353,10 +418,11 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     const int64_t col = c0 + cc * 8;
     const bool col_ok = col < cols;  // cols is a multiple of 8: the chunk is all in or all out
     float sc[8];
-    if constexpr (GRAN == F8_COLWISE) {
+    if constexpr (GRAN == F8_COLWISE || GRAN == kGranBoth) {
+        const float* cs = GRAN == kGranBoth ? scale_col : scale;
         if (col_ok) {
-            const float4 s0 = *reinterpret_cast<const float4*>(scale + col);
-            const float4 s1 = *reinterpret_cast<const float4*>(scale + col + 4);
+            const float4 s0 = *reinterpret_cast<const float4*>(cs + col);
+            const float4 s1 = *reinterpret_cast<const float4*>(cs + col + 4);
             sc[0] = s0.x, sc[1] = s0.y, sc[2] = s0.z, sc[3] = s0.w;
             sc[4] = s1.x, sc[5] = s1.y, sc[6] = s1.z, sc[7] = s1.w;
         }
@@ -383,19 +449,23 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     for (int i = 0; i < 8; ++i) {
         const int rl = rr + 16 * i;
         const int64_t r = r0 + rl;
-        uint2 q;
+        uint2 q, qt;
         if constexpr (GRAN == F8_COLWISE) {
-            q = cast8v<FMT>(v[i], sc);
+            q = qt = cast8v<FMT>(v[i], sc);
+        } else if constexpr (GRAN == kGranBoth) {
+            s = r < rows ? scale[r] : 0.0f;
+            q = cast8<FMT>(v[i], s);
+            qt = cast8v<FMT>(v[i], sc);
         } else {
             if constexpr (GRAN == F8_ROWWISE) s = r < rows ? scale[r] : 0.0f;
-            q = cast8<FMT>(v[i], s);
+            q = qt = cast8<FMT>(v[i], s);
         }
         if constexpr (OUT) {
             if (col_ok && r < rows) *reinterpret_cast<uint2*>(out + r * ld_out + col) = q;
         }
         if constexpr (OUT_T) {
-            tile[rl * kLdsStride + cc * 2] = q.x;
-            tile[rl * kLdsStride + cc * 2 + 1] = q.y;
+            tile[rl * kLdsStride + cc * 2] = qt.x;
+            tile[rl * kLdsStride + cc * 2 + 1] = qt.y;
         }
     }
     if constexpr (OUT_T) {
@@ -487,6 +557,10 @@ size_t workspace_bytes(int64_t max_rows, int64_t max_cols)
     size_t tensor = (size_t)kMaxPartials * sizeof(uint32_t);
     size_t colw = (size_t)kColChunksMax * (size_t)d * sizeof(uint32_t);
     size_t n = tensor > colw ? tensor : colw;
+    // per-column partials and per-row partials side by side (rowwise scaling, both from one pass)
+    const size_t strips = (size_t)((max_cols > 0 ? max_cols : 0) + 127) / 128;
+    const size_t both = colw + strips * (size_t)(max_rows > 0 ? max_rows : 0) * sizeof(uint32_t);
+    n = both > n ? both : n;
     // one partial per 128x128 tile of the measuring cast (delayed scaling)
     const int64_t r = max_rows > 0 ? max_rows : 0, c = max_cols > 0 ? max_cols : 0;
     size_t tiles = (size_t)((r + kTile - 1) / kTile) * (size_t)((c + kTile - 1) / kTile) * sizeof(uint32_t);
@@ -528,9 +602,9 @@ static f8_status launch_amax(const void* x, int64_t rows, int64_t cols, int64_t 
             if (rows > 0) {
                 nch = col_chunks(rows, &rpc);
                 dim3 grid((unsigned)((cols + 127) / 128), (unsigned)nch);
-                amax_cols_partial_kernel<<<grid, kThreads, 0, st>>>(xc, rows, cols, ld / 8, rpc, (uint32_t*)ws);
+                amax_cols_partial_kernel<false><<<grid, kThreads, 0, st>>>(xc, rows, cols, ld / 8, rpc, (uint32_t*)ws, nullptr);
             }
-            amax_cols_final_kernel<<<(unsigned)((cols + kThreads - 1) / kThreads), kThreads, 0, st>>>(
+            amax_vector_final_kernel<<<(unsigned)((cols + kWave - 1) / kWave), kThreads, 0, st>>>(
                 (const uint32_t*)ws, nch, cols, fm, amax_out, scale_out, inv_out);
         }
     }
@@ -669,6 +743,54 @@ f8_status publish_scale(const float* s_in, float* s_out, float* inv_out, hipStre
 {
     publish_scale_kernel<<<1, 1, 0, st>>>(s_in, s_out, inv_out);
     return last_launch_status();
+}
+
+// Rowwise quantisation of both orientations from ONE read of x: out [rows, cols] with the
+// per-row scales, out_t [cols, rows] with the per-column scales (checked arguments).
+f8_status cast_rows_and_cols(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt,
+                             const float* scale_rows, const float* scale_cols, uint8_t* out, int64_t ld_out,
+                             uint8_t* out_t, int64_t ld_out_t, hipStream_t st)
+{
+    if (rows == 0 || cols == 0) return F8_OK;
+    const int tiles_r = (int)((rows + kTile - 1) / kTile), tiles_c = (int)((cols + kTile - 1) / kTile);
+    const unsigned nb = (unsigned)tiles_r * (unsigned)tiles_c;
+    if (fmt == F8_E4M3)
+        cast_tile_kernel<F8_E4M3, kGranBoth, false, true, true><<<nb, kThreads, 0, st>>>(
+            (const uint16_t*)x, rows, cols, ld, scale_rows, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, out_t,
+            ld_out_t, tiles_c, nullptr, scale_cols);
+    else
+        cast_tile_kernel<F8_E5M2, kGranBoth, false, true, true><<<nb, kThreads, 0, st>>>(
+            (const uint16_t*)x, rows, cols, ld, scale_rows, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, out_t,
+            ld_out_t, tiles_c, nullptr, scale_cols);
+    return last_launch_status();
+}
+
+// Rowwise scaling: per-row and per-column amax, scale and 1/scale of x from ONE read (checked
+// arguments, rows and cols > 0).  ws: workspace_bytes(rows, cols).
+f8_status amax_rows_and_cols(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, float* amax_r,
+                             float* scale_r, float* inv_r, float* amax_c, float* scale_c, float* inv_c, void* ws,
+                             hipStream_t st)
+{
+    const float fm = fmax_of(fmt);
+    int64_t rpc = 16;
+    const int nch = col_chunks(rows, &rpc);
+    const unsigned strips = (unsigned)((cols + 127) / 128);
+    uint32_t* colp = (uint32_t*)ws;
+    uint32_t* rowp = colp + (size_t)kColChunksMax * (size_t)(rows > cols ? rows : cols);
+    dim3 grid(strips, (unsigned)nch);
+    amax_cols_partial_kernel<true><<<grid, kThreads, 0, st>>>((const uint4*)x, rows, cols, ld / 8, rpc, colp, rowp);
+    amax_vector_final_kernel<<<(unsigned)((cols + kWave - 1) / kWave), kThreads, 0, st>>>(colp, nch, cols, fm, amax_c,
+                                                                                         scale_c, inv_c);
+    amax_vector_final_kernel<<<(unsigned)((rows + kWave - 1) / kWave), kThreads, 0, st>>>(rowp, (int)strips, rows, fm,
+                                                                                         amax_r, scale_r, inv_r);
+    return last_launch_status();
+}
+
+// per-row or per-column amax with scales (no cast), for callers that cast both orientations at once
+f8_status amax_scales(const void* x, int64_t rows, int64_t cols, int64_t ld, int g, int fmt, float* amax_out,
+                      float* scale_out, float* inv_out, void* ws, hipStream_t st)
+{
+    return launch_amax(x, rows, cols, ld, g, fmax_of(fmt), amax_out, scale_out, inv_out, ws, st);
 }
 
 // amax is known (taken by the producer of x): publish amax / scale / 1/scale, then one cast pass.

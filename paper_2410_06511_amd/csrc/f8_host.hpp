@@ -33,6 +33,16 @@ f8_status publish_scale(const float* s_in, float* s_out, float* inv_out, hipStre
 f8_status cast_given(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
                      uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, hipStream_t st);
 
+// Rowwise scaling, both orientations: the two amax passes, then one cast that reads x once.
+f8_status amax_scales(const void* x, int64_t rows, int64_t cols, int64_t ld, int g, int fmt, float* amax_out,
+                      float* scale_out, float* inv_out, void* ws, hipStream_t st);
+f8_status amax_rows_and_cols(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, float* amax_r,
+                             float* scale_r, float* inv_r, float* amax_c, float* scale_c, float* inv_c, void* ws,
+                             hipStream_t st);
+f8_status cast_rows_and_cols(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt,
+                             const float* scale_rows, const float* scale_cols, uint8_t* out, int64_t ld_out,
+                             uint8_t* out_t, int64_t ld_out_t, hipStream_t st);
+
 // Dynamic scaling of a tensorwise tensor whose amax the producer already took: one cast pass.
 f8_status quantise_known_amax(const void* x, int64_t rows, int64_t cols, int64_t ld, int fmt, const float* amax_in,
                               float* amax_out, float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,

@@ -40,18 +40,25 @@ static size_t linear_workspace(const f8_linear_desc* d)
 }
 
 // Quantise T[rows, cols] into q (and q_t).  Tensorwise: one pass writes both orientations.
-// Rowwise: q with per-row scales, q_t with per-column scales (two passes, different codes).
+// Rowwise: q with per-row scales, q_t with per-column scales (different codes): the two amax
+// sets from one pass over T, then one cast pass that writes both.
 static f8_status quantise_both(const void* T, int64_t rows, int64_t cols, bool rowwise, int fmt,
                                const f8_qtensor* q, void* ws, hipStream_t st)
 {
     if (!rowwise)
         return quantise(T, rows, cols, cols, F8_TENSORWISE, fmt, q->amax, q->scale, q->inv_scale, q->q, cols,
                         q->q_t, rows, ws, st);
-    f8_status s = quantise(T, rows, cols, cols, F8_ROWWISE, fmt, q->amax, q->scale, q->inv_scale, q->q, cols,
-                           nullptr, 0, ws, st);
+    f8_status s;
+    if (rows > 0 && cols > 0) {
+        s = amax_rows_and_cols(T, rows, cols, cols, fmt, q->amax, q->scale, q->inv_scale, q->amax_t, q->scale_t,
+                               q->inv_scale_t, ws, st);
+    } else {  // an empty tensor still publishes amax 0 and its scale along the non-empty axis
+        s = amax_scales(T, rows, cols, cols, F8_ROWWISE, fmt, q->amax, q->scale, q->inv_scale, ws, st);
+        if (s != F8_OK) return s;
+        s = amax_scales(T, rows, cols, cols, F8_COLWISE, fmt, q->amax_t, q->scale_t, q->inv_scale_t, ws, st);
+    }
     if (s != F8_OK) return s;
-    return quantise(T, rows, cols, cols, F8_COLWISE, fmt, q->amax_t, q->scale_t, q->inv_scale_t, nullptr, 0,
-                    q->q_t, rows, ws, st);
+    return cast_rows_and_cols(T, rows, cols, cols, fmt, q->scale, q->scale_t, q->q, cols, q->q_t, rows, st);
 }
 
 // One tensor under delayed or static scaling: cast with the state's scale into both
@@ -104,6 +111,19 @@ const char* f8_status_string(f8_status s)
         case F8_ERR_LAUNCH: return "kernel launch failed";
     }
     return "unknown status";
+}
+
+f8_status f8_quantise(const void* t_bf16, int64_t rows, int64_t cols, f8_granularity g, f8_format fmt,
+                      const f8_qtensor* q, void* workspace, size_t workspace_bytes_, void* stream)
+{
+    if (((int)g != F8_TENSORWISE && (int)g != F8_ROWWISE) || (int)fmt < 0 || (int)fmt > F8_E5M2) return F8_ERR_ENUM;
+    if (!t_bf16 || !q) return F8_ERR_NULL;
+    if (rows < 0 || cols < 0 || (rows % 16) || (cols % 16)) return F8_ERR_SHAPE;
+    if (!aligned16(t_bf16)) return F8_ERR_ALIGN;
+    f8_status s = check_q(q, g == F8_ROWWISE);
+    if (s != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return F8_ERR_WORKSPACE;
+    return quantise_both(t_bf16, rows, cols, g == F8_ROWWISE, fmt, q, workspace, (hipStream_t)stream);
 }
 
 f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, void* Y, f8_saved* saved,

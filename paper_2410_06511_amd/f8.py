@@ -25,7 +25,7 @@ _i64, _int, _p = C.c_int64, C.c_int, C.c_void_p
 EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_cast", "f8_encode_f32",
            "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
            "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled",
-           "f8_linear_fwd_chained", "f8_linear_bwd_chained"]
+           "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise"]
 
 
 class F8Error(RuntimeError):
@@ -81,6 +81,7 @@ def lib():
                                             C.c_size_t, _p]
         l.f8_linear_bwd_chained.argtypes = [C.POINTER(LinearDesc), _p, _p, C.POINTER(SavedStruct), _p, _p, _p, _p,
                                             C.c_size_t, _p]
+        l.f8_quantise.argtypes = [_p, _i64, _i64, _int, _int, C.POINTER(QTensorStruct), _p, C.c_size_t, _p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
         _lib = l
@@ -186,6 +187,14 @@ class Saved:
 
     def struct(self):
         return self._struct
+
+
+def quantise(t, g, fmt, q, workspace, stream=None):
+    """q: QTensor.  Both orientations of t under dynamic scaling (see f8_quantise)."""
+    rows, cols = t.shape
+    wp, wb = _ws(workspace)
+    st = q.struct()
+    _check(lib().f8_quantise(_ptr(t), rows, cols, g, fmt, C.byref(st), wp, wb, _stream(stream)))
 
 
 def linear_desc(M, K, N, rowwise=False, grad_format=E4M3):

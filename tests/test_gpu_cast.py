@@ -258,3 +258,32 @@ def test_idempotent_and_guard_bands():
     assert torch.equal(first, out) and torch.equal(out_t, out.t().contiguous())
     for b in (buf, buf_t):
         assert int((b[:pad] != 0x5C).sum()) == 0 and int((b[-pad:] != 0x5C).sum()) == 0
+
+
+@pytest.mark.parametrize("fmt", [f8.E4M3, f8.E5M2])
+@pytest.mark.parametrize("rows,cols", [(16, 16), (272, 336), (128, 1024), (1040, 400)])
+def test_quantise_both_orientations(rows, cols, fmt):
+    """f8_quantise: what the linear does to one tensor.  Tensorwise: one scale, the same codes in
+    both orientations.  Rowwise: per-row scales for q, per-column scales for q_t (x read once)."""
+    g = torch.Generator("cpu")
+    g.manual_seed(rows * 7 + cols)
+    x = wl.randn_bf16((rows, cols), 1.5, 0, generator=g)
+    x[3, :] *= 8.0            # rows and columns of different magnitude: the two scale sets differ
+    x[:, 5] *= 0.01
+    xb = bits(x)
+    ws = f8.new_workspace(rows, cols)
+    q = f8.QTensor(rows, cols, False)
+    f8.quantise(x.cuda(), f8.TENSORWISE, fmt, q, ws)
+    torch.cuda.synchronize()
+    a, s, inv, codes = o.amax_cast(xb, o.TENSORWISE, fmt)
+    assert f32(q.amax)[0] == a[0] and f32(q.scale)[0] == s[0] and f32(q.inv_scale)[0] == inv[0]
+    assert np.array_equal(u8(q.q), codes) and np.array_equal(u8(q.q_t), codes.T)
+    q = f8.QTensor(rows, cols, True)
+    f8.quantise(x.cuda(), f8.ROWWISE, fmt, q, ws)
+    torch.cuda.synchronize()
+    a, s, inv, codes = o.amax_cast(xb, o.ROWWISE, fmt)
+    assert np.array_equal(f32(q.amax), a) and np.array_equal(f32(q.scale), s) and np.array_equal(f32(q.inv_scale), inv)
+    assert np.array_equal(u8(q.q), codes)
+    a, s, inv, codes = o.amax_cast(xb, o.COLWISE, fmt)
+    assert np.array_equal(f32(q.amax_t), a) and np.array_equal(f32(q.scale_t), s) and np.array_equal(f32(q.inv_scale_t), inv)
+    assert np.array_equal(u8(q.q_t), codes.T)
