@@ -401,17 +401,7 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     __shared__ uint32_t tile[kTile * kLdsStride];
 
     float s = 0.0f;
-    if constexpr (DYN) {
-        float a = mag_to_float(reduce_partials(partial, npartial, red));
-        s = scale_from_amax(a, Fmt<FMT>::fmax);
-        if (blockIdx.x == 0 && threadIdx.x == 0) {
-            amax_out[0] = a;
-            scale_out[0] = s;
-            inv_out[0] = 1.0f / s;
-        }
-    } else if constexpr (GRAN == F8_TENSORWISE) {
-        s = scale[0];
-    }
+    if constexpr (!DYN && GRAN == F8_TENSORWISE) s = scale[0];
 
     const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kTile;
     const int64_t c0 = (int64_t)(blockIdx.x % tiles_c) * kTile;
@@ -441,6 +431,17 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
         if (col_ok && r < rows) {
             const u4v t = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(x + r * ld + col));
             v[i] = make_uint4(t.x, t.y, t.z, t.w);
+        }
+    }
+    if constexpr (DYN) {
+        // After the loads of x have been issued: the reduction of the partial maxima (an L2 read
+        // and two barriers) then overlaps their latency instead of preceding it.
+        float a = mag_to_float(reduce_partials(partial, npartial, red));
+        s = scale_from_amax(a, Fmt<FMT>::fmax);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            amax_out[0] = a;
+            scale_out[0] = s;
+            inv_out[0] = 1.0f / s;
         }
     }
     uint32_t macc = 0;
