@@ -309,6 +309,28 @@ f8_status f8_linear_bwd_chained(const f8_linear_desc* d, const void* dY, const f
                                 f8_saved* saved, void* dX, float* dx_amax, void* dW,
                                 void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * The bf16 glue between the two Float8 linears of a Llama feed-forward block
+ * (the paper trains Llama 3.1 models; their feed-forward is
+ * Y = W2 ( silu(W1 x) * (W3 x) ), silu(t) = t / (1 + e^-t)).  W1 and W3 are
+ * stacked into one linear of width 2H whose output row is [a | b].
+ *
+ * f8_silu_mul:     ab [M, 2H] bf16 -> h [M, H] bf16, h = silu(a) * b.
+ * f8_silu_mul_bwd: ab [M, 2H], dh [M, H] -> dab [M, 2H] = [dh * b * silu'(a) | dh * silu(a)].
+ * Arithmetic is fp32 with one rounding to bf16 at the end; results agree with
+ * the exact functions to within one bf16 unit in the last place.
+ * amax_h / amax_dab (nullable, device, 1 float): receives the exact maximum
+ * magnitude of the bf16 values written, for f8_linear_fwd_chained /
+ * f8_linear_bwd_chained of the consuming linear.  workspace (needed only with
+ * an amax output): f8_workspace_bytes(M, 2 * H) bytes.  M and H multiples of 16.
+ */
+f8_status f8_silu_mul(const void* ab_bf16, int64_t M, int64_t H, void* h_bf16, float* amax_h,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+f8_status f8_silu_mul_bwd(const void* ab_bf16, const void* dh_bf16, int64_t M, int64_t H,
+                          void* dab_bf16, float* amax_dab, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -428,6 +428,53 @@ void f8o_history_push(float* history, int64_t len, float amax_new, int fmt, floa
     f8o_scale(&window_max, 1, fmt, scale, inv_scale);
 }
 
+/* ---- the feed-forward glue between two Float8 linears ------------------------
+ * Llama's feed-forward block is  Y = W2 ( silu(W1 x) * (W3 x) ),  silu(t) = t / (1 + e^-t).
+ * With W1 and W3 stacked into one linear its output row is [a | b] (H values each) and the
+ * next linear's input is h = silu(a) * b.  The paper does not spell this out (it trains
+ * Llama 3.1 models); it is the textbook definition, evaluated here in double precision and
+ * rounded once to bf16.  The backward formulas are its derivatives:
+ *   dh/da = b * s'(a),  s'(t) = sig(t) * (1 + t * (1 - sig(t))),  sig(t) = 1 / (1 + e^-t)
+ *   dh/db = silu(a).
+ * Each function also returns the amax of what it wrote (the next cast's input). */
+static double sigmoid64(double t) { return 1.0 / (1.0 + exp(-t)); }
+
+void f8o_silu_mul(const uint16_t* ab, int64_t M, int64_t H, uint16_t* h, float* amax_h)
+{
+    float amax = 0.0f;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t j = 0; j < H; ++j) {
+            double a = (double)f8o_bf16_to_f32(ab[m * 2 * H + j]);
+            double b = (double)f8o_bf16_to_f32(ab[m * 2 * H + H + j]);
+            uint16_t o = f8o_f32_to_bf16((float)(a * sigmoid64(a) * b));
+            h[m * H + j] = o;
+            float v = fabsf(f8o_bf16_to_f32(o));
+            if (v > amax) amax = v;
+        }
+    if (amax_h) *amax_h = amax;
+}
+
+void f8o_silu_mul_bwd(const uint16_t* ab, const uint16_t* dh, int64_t M, int64_t H, uint16_t* dab,
+                      float* amax_dab)
+{
+    float amax = 0.0f;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t j = 0; j < H; ++j) {
+            double a = (double)f8o_bf16_to_f32(ab[m * 2 * H + j]);
+            double b = (double)f8o_bf16_to_f32(ab[m * 2 * H + H + j]);
+            double g = (double)f8o_bf16_to_f32(dh[m * H + j]);
+            double sg = sigmoid64(a);
+            uint16_t da = f8o_f32_to_bf16((float)(g * b * (sg * (1.0 + a * (1.0 - sg)))));
+            uint16_t db = f8o_f32_to_bf16((float)(g * (a * sg)));
+            dab[m * 2 * H + j] = da;
+            dab[m * 2 * H + H + j] = db;
+            float v = fabsf(f8o_bf16_to_f32(da)), w = fabsf(f8o_bf16_to_f32(db));
+            if (v > amax) amax = v;
+            if (w > amax) amax = w;
+        }
+    if (amax_dab) *amax_dab = amax;
+}
+
 int f8o_num_threads(void)
 {
     int n = 1;

@@ -56,6 +56,10 @@ def _declare(l):
     l.f8o_amax.argtypes = [_p, _i64, _i64, _i64, _int, _p]
     l.f8o_scale.restype = None
     l.f8o_scale.argtypes = [_p, _i64, _int, _p, _p]
+    l.f8o_silu_mul.restype = None
+    l.f8o_silu_mul.argtypes = [_p, _i64, _i64, _p, _p]
+    l.f8o_silu_mul_bwd.restype = None
+    l.f8o_silu_mul_bwd.argtypes = [_p, _p, _i64, _i64, _p, _p]
     l.f8o_history_push.restype = None
     l.f8o_history_push.argtypes = [_p, _i64, _f32, _int, _p, _p]
     l.f8o_cast.restype = None
@@ -313,6 +317,29 @@ def linear_bwd_scaled(dY_bits, xq, wq, state, grad_fmt=E4M3):
     dX = gemm(NN, dyq.q, grad_fmt, wq.q, E4M3, dyq.inv_scale, wq.inv_scale, TENSORWISE)
     dW = gemm(TN, dyq.q, grad_fmt, xq.q, E4M3, dyq.inv_scale, xq.inv_scale, TENSORWISE)
     return dX, dW, dyq
+
+
+# ---- feed-forward glue ----------------------------------------------------------------
+
+def silu_mul(ab_bits):
+    """ab [M, 2H] = [a | b] bf16 bits -> (h [M, H] bits = bf16(silu(a) * b), amax of h)."""
+    ab = _c(ab_bits, np.uint16)
+    M, H2 = ab.shape
+    h = np.empty((M, H2 // 2), np.uint16)
+    am = np.empty(1, np.float32)
+    lib().f8o_silu_mul(_ptr(ab), M, H2 // 2, _ptr(h), _ptr(am))
+    return h, am
+
+
+def silu_mul_bwd(ab_bits, dh_bits):
+    """-> (dab [M, 2H] bits = [dh * b * silu'(a) | dh * silu(a)], amax of dab)."""
+    ab, dh = _c(ab_bits, np.uint16), _c(dh_bits, np.uint16)
+    M, H2 = ab.shape
+    assert dh.shape == (M, H2 // 2)
+    dab = np.empty((M, H2), np.uint16)
+    am = np.empty(1, np.float32)
+    lib().f8o_silu_mul_bwd(_ptr(ab), _ptr(dh), M, H2 // 2, _ptr(dab), _ptr(am))
+    return dab, am
 
 
 def num_threads():

@@ -558,7 +558,8 @@ size_t workspace_bytes(int64_t max_rows, int64_t max_cols)
 {
     int64_t d = max_rows > max_cols ? max_rows : max_cols;
     if (d < 0) d = 0;
-    size_t tensor = (size_t)kMaxPartials * sizeof(uint32_t);
+    static_assert((size_t)kMaxPartials * sizeof(uint32_t) <= kMinWorkspaceBytes, "tensorwise partials fit the minimum");
+    size_t tensor = kMinWorkspaceBytes;
     size_t colw = (size_t)kColChunksMax * (size_t)d * sizeof(uint32_t);
     size_t n = tensor > colw ? tensor : colw;
     // per-column partials and per-row partials side by side (rowwise scaling, both from one pass)

@@ -12,6 +12,9 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // Launch errors are sticky in the HIP runtime until read; reading also clears them.
 inline f8_status last_launch_status() { return hipGetLastError() == hipSuccess ? F8_OK : F8_ERR_LAUNCH; }
 
+// Never less than kMinWorkspaceBytes: room for the per-block partial maxima of the kernels
+// whose grid does not depend on the shape (tensorwise amax, feed-forward glue).
+constexpr size_t kMinWorkspaceBytes = 8192;
 size_t workspace_bytes(int64_t max_rows, int64_t max_cols);
 
 // amax -> scale -> cast of one validated tensor (dynamic scaling), any granularity.

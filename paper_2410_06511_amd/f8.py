@@ -25,7 +25,8 @@ _i64, _int, _p = C.c_int64, C.c_int, C.c_void_p
 EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_cast", "f8_encode_f32",
            "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
            "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled",
-           "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise"]
+           "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise",
+           "f8_silu_mul", "f8_silu_mul_bwd"]
 
 
 class F8Error(RuntimeError):
@@ -82,6 +83,8 @@ def lib():
         l.f8_linear_bwd_chained.argtypes = [C.POINTER(LinearDesc), _p, _p, C.POINTER(SavedStruct), _p, _p, _p, _p,
                                             C.c_size_t, _p]
         l.f8_quantise.argtypes = [_p, _i64, _i64, _int, _int, C.POINTER(QTensorStruct), _p, C.c_size_t, _p]
+        l.f8_silu_mul.argtypes = [_p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
+        l.f8_silu_mul_bwd.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
         _lib = l
@@ -269,3 +272,17 @@ def linear_bwd_chained(desc, dY, dy_amax, saved, dX, dx_amax, dW, workspace, str
     wp, wb = _ws(workspace)
     _check(lib().f8_linear_bwd_chained(C.byref(desc), _ptr(dY), _ptr(dy_amax), C.byref(saved.struct()), _ptr(dX),
                                        _ptr(dx_amax), _ptr(dW), wp, wb, _stream(stream)))
+
+
+# ---- feed-forward glue ---------------------------------------------------------------
+
+def silu_mul(ab, h, amax_h=None, workspace=None, stream=None):
+    M, H2 = ab.shape
+    wp, wb = _ws(workspace)
+    _check(lib().f8_silu_mul(_ptr(ab), M, H2 // 2, _ptr(h), _ptr(amax_h), wp, wb, _stream(stream)))
+
+
+def silu_mul_bwd(ab, dh, dab, amax_dab=None, workspace=None, stream=None):
+    M, H2 = ab.shape
+    wp, wb = _ws(workspace)
+    _check(lib().f8_silu_mul_bwd(_ptr(ab), _ptr(dh), M, H2 // 2, _ptr(dab), _ptr(amax_dab), wp, wb, _stream(stream)))

@@ -1,0 +1,197 @@
+"""The feed-forward glue between two Float8 linears (h = silu(a) * b and its backward) and the
+whole feed-forward chain X -> [W1; W3] -> glue -> W2 -> Y, forward and backward."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as o
+from paper_2410_06511_amd import f8
+from paper_2410_06511_amd import workloads as wl
+from helpers import bits, u8, f32, assert_gemm_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _from_bits(b):
+    return torch.from_numpy(np.ascontiguousarray(b).view(np.int16)).view(torch.bfloat16)
+
+
+def assert_bf16_close(got_bits, ref_bits, what=""):
+    """fp32 arithmetic against the fp64 definition: equal up to one bf16 unit in the last place
+    (a rounding boundary can fall between the two), and never off in sign or by a binade."""
+    got = o.bf16_to_f32(got_bits).astype(np.float64)
+    ref = o.bf16_to_f32(ref_bits).astype(np.float64)
+    assert np.isfinite(got).all(), what
+    ulp = np.maximum(np.abs(ref), 2.0 ** -126) * 2.0 ** -7          # >= one bf16 ulp at |ref|
+    bad = np.abs(got - ref) > ulp
+    assert not bad.any(), (what, int(bad.sum()), np.argwhere(bad)[:3])
+    # the overwhelming majority is bit-identical
+    assert (got_bits == ref_bits).mean() > 0.98, what
+
+
+@pytest.mark.parametrize("M,H", [(16, 16), (272, 336), (512, 1792)])
+def test_silu_mul_forward_and_backward(M, H):
+    g = torch.Generator("cpu")
+    g.manual_seed(M + H)
+    ab = wl.randn_bf16((M, 2 * H), 2.0, 0, generator=g)
+    ab[0, :8] = torch.tensor([0.0, -0.0, 30.0, -30.0, 100.0, -100.0, 1e-3, -1e-3]).bfloat16()
+    dh = wl.randn_bf16((M, H), 1e-3, 0, generator=g)
+    ws = f8.new_workspace(M, 2 * H)
+    h = torch.empty((M, H), dtype=torch.bfloat16, device="cuda")
+    dab = torch.empty((M, 2 * H), dtype=torch.bfloat16, device="cuda")
+    a_h, a_d = torch.full((1,), -1.0, device="cuda"), torch.full((1,), -1.0, device="cuda")
+    f8.silu_mul(ab.cuda(), h, a_h, ws)
+    f8.silu_mul_bwd(ab.cuda(), dh.cuda(), dab, a_d, ws)
+    torch.cuda.synchronize()
+    rh, ra_h = o.silu_mul(bits(ab))
+    rd, ra_d = o.silu_mul_bwd(bits(ab), bits(dh))
+    assert_bf16_close(bits(h), rh, "h")
+    assert_bf16_close(bits(dab), rd, "dab")
+    # the amax is exactly that of the values written, and within an ulp of the oracle's
+    assert a_h.item() == o.amax(bits(h))[0] and a_d.item() == o.amax(bits(dab))[0]
+    assert abs(a_h.item() - ra_h[0]) <= 2.0 ** -7 * ra_h[0] and abs(a_d.item() - ra_d[0]) <= 2.0 ** -7 * ra_d[0]
+    # without an amax output no workspace is needed and the values are the same
+    h2 = torch.empty_like(h)
+    f8.silu_mul(ab.cuda(), h2)
+    torch.cuda.synchronize()
+    assert torch.equal(h.view(torch.int16), h2.view(torch.int16))
+
+
+def test_glue_argument_errors():
+    t = torch.zeros((16, 32), dtype=torch.bfloat16, device="cuda")
+    h = torch.zeros((16, 16), dtype=torch.bfloat16, device="cuda")
+    a = torch.zeros(1, device="cuda")
+    with pytest.raises(f8.F8Error) as e:       # amax requested without a workspace
+        f8.silu_mul(t, h, a, None)
+    assert e.value.code == 5
+    with pytest.raises(f8.F8Error) as e:
+        f8._check(f8.lib().f8_silu_mul(t.data_ptr(), 16, 24, h.data_ptr(), None, None, 0, None))
+    assert e.value.code == 2
+
+
+class FFN:
+    """Device buffers and the call sequence of one feed-forward block."""
+
+    def __init__(self, M, D, H, gfmt=f8.E4M3):
+        bf = dict(dtype=torch.bfloat16, device="cuda")
+        self.M, self.D, self.H = M, D, H
+        self.d13, self.d2 = f8.linear_desc(M, D, 2 * H, False, gfmt), f8.linear_desc(M, H, D, False, gfmt)
+        self.s13, self.s2 = f8.Saved(M, D, 2 * H), f8.Saved(M, H, D)
+        self.ws = f8.new_workspace(max(M, D, 2 * H), max(M, D, 2 * H))
+        self.AB, self.Hh, self.Y = torch.empty((M, 2 * H), **bf), torch.empty((M, H), **bf), torch.empty((M, D), **bf)
+        self.dH, self.dAB, self.dX = torch.empty((M, H), **bf), torch.empty((M, 2 * H), **bf), torch.empty((M, D), **bf)
+        self.dW13, self.dW2 = torch.empty((2 * H, D), **bf), torch.empty((D, H), **bf)
+        self.a_h, self.a_dab = torch.empty(1, device="cuda"), torch.empty(1, device="cuda")
+
+    def forward(self, X, W13, W2, chained=True):
+        if chained:
+            f8.linear_fwd_chained(self.d13, X, None, W13, self.AB, None, self.s13, self.ws)
+            f8.silu_mul(self.AB, self.Hh, self.a_h, self.ws)
+            f8.linear_fwd_chained(self.d2, self.Hh, self.a_h, W2, self.Y, None, self.s2, self.ws)
+        else:
+            f8.linear_fwd(self.d13, X, W13, self.AB, self.s13, self.ws)
+            f8.silu_mul(self.AB, self.Hh)
+            f8.linear_fwd(self.d2, self.Hh, W2, self.Y, self.s2, self.ws)
+
+    def backward(self, dY, chained=True):
+        if chained:
+            f8.linear_bwd_chained(self.d2, dY, None, self.s2, self.dH, None, self.dW2, self.ws)
+            f8.silu_mul_bwd(self.AB, self.dH, self.dAB, self.a_dab, self.ws)
+            f8.linear_bwd_chained(self.d13, self.dAB, self.a_dab, self.s13, self.dX, None, self.dW13, self.ws)
+        else:
+            f8.linear_bwd(self.d2, dY, self.s2, self.dH, self.dW2, self.ws)
+            f8.silu_mul_bwd(self.AB, self.dH, self.dAB)
+            f8.linear_bwd(self.d13, self.dAB, self.s13, self.dX, self.dW13, self.ws)
+
+
+def _ffn_inputs(M, D, H, seed):
+    g = torch.Generator("cpu")
+    g.manual_seed(seed)
+    return (wl.randn_bf16((M, D), 1.0, 0, generator=g), wl.randn_bf16((2 * H, D), 0.02, 0, generator=g),
+            wl.randn_bf16((D, H), 0.02, 0, generator=g), wl.randn_bf16((M, D), 1e-3, 0, generator=g))
+
+
+@pytest.mark.parametrize("M,D,H", [(272, 336, 208), (1024, 1024, 1792)])
+def test_ffn_chained_equals_unchained(M, D, H):
+    X, W13, W2, dY = (t.cuda() for t in _ffn_inputs(M, D, H, 5))
+    outs = []
+    for chained in (True, False):
+        f = FFN(M, D, H)
+        f.forward(X, W13, W2, chained)
+        f.backward(dY, chained)
+        torch.cuda.synchronize()
+        outs.append((f.Y, f.dX, f.dW13, f.dW2, f.Hh, f.dAB, f.s2.x.q, f.s13.dy.q_t, f.s2.x.scale, f.s13.dy.scale))
+    for a, b in zip(*outs):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+def test_ffn_stage_by_stage_against_oracle():
+    """Every stage of the chain is fed the ORACLE's output of the stage before and compared with
+    the oracle's output of this stage: codes and scales bit-exact, GEMMs and glue within their
+    tolerances."""
+    M, D, H = 512, 768, 1024
+    X, W13, W2, dY = _ffn_inputs(M, D, H, 6)
+    # oracle chain
+    rAB, xq, w13q = o.linear_fwd(bits(X), bits(W13))
+    rH, ra_h = o.silu_mul(rAB)
+    rY, hq, w2q = o.linear_fwd(rH, bits(W2))
+    rdH, rdW2, dyq = o.linear_bwd(bits(dY), hq, w2q)
+    rdAB, ra_dab = o.silu_mul_bwd(rAB, rdH)
+    rdX, rdW13, dabq = o.linear_bwd(rdAB, xq, w13q)
+
+    f = FFN(M, D, H)
+    # stage 1: stacked linear
+    f8.linear_fwd_chained(f.d13, X.cuda(), None, W13.cuda(), f.AB, None, f.s13, f.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(u8(f.s13.x.q), xq.q) and np.array_equal(u8(f.s13.w.q), w13q.q)
+    assert_gemm_close(bits(f.AB), rAB, "AB")
+    # stage 2: glue on the oracle's AB
+    f.AB.copy_(_from_bits(rAB))
+    f8.silu_mul(f.AB, f.Hh, f.a_h, f.ws)
+    torch.cuda.synchronize()
+    assert_bf16_close(bits(f.Hh), rH, "h")
+    # stage 3: second linear on the oracle's h and its amax
+    f.Hh.copy_(_from_bits(rH))
+    f.a_h.copy_(torch.from_numpy(ra_h))
+    f8.linear_fwd_chained(f.d2, f.Hh, f.a_h, W2.cuda(), f.Y, None, f.s2, f.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(u8(f.s2.x.q), hq.q) and f32(f.s2.x.scale)[0] == hq.scale[0] and f32(f.s2.x.amax)[0] == hq.amax[0]
+    assert_gemm_close(bits(f.Y), rY, "Y")
+    # stage 4: backward of the second linear
+    f8.linear_bwd_chained(f.d2, dY.cuda(), None, f.s2, f.dH, None, f.dW2, f.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(u8(f.s2.dy.q), dyq.q)
+    assert_gemm_close(bits(f.dH), rdH, "dH"), assert_gemm_close(bits(f.dW2), rdW2, "dW2")
+    # stage 5: glue backward on the oracle's dH
+    f.dH.copy_(_from_bits(rdH))
+    f8.silu_mul_bwd(f.AB, f.dH, f.dAB, f.a_dab, f.ws)
+    torch.cuda.synchronize()
+    assert_bf16_close(bits(f.dAB), rdAB, "dAB")
+    # stage 6: backward of the stacked linear on the oracle's dAB and its amax
+    f.dAB.copy_(_from_bits(rdAB))
+    f.a_dab.copy_(torch.from_numpy(ra_dab))
+    f8.linear_bwd_chained(f.d13, f.dAB, f.a_dab, f.s13, f.dX, None, f.dW13, f.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(u8(f.s13.dy.q), dabq.q) and f32(f.s13.dy.scale)[0] == dabq.scale[0]
+    assert_gemm_close(bits(f.dX), rdX, "dX"), assert_gemm_close(bits(f.dW13), rdW13, "dW13")
+
+
+def test_ffn_end_to_end_close_to_oracle():
+    """The whole chain on the GPU against the whole chain in the oracle: quantisation noise of
+    one stage moves the next stage's inputs, so the bar is the fp8 noise level, not the GEMM
+    tolerance: relative error of Y and dX below 3 %."""
+    M, D, H = 512, 768, 1024
+    X, W13, W2, dY = _ffn_inputs(M, D, H, 7)
+    rAB, xq, w13q = o.linear_fwd(bits(X), bits(W13))
+    rH, _ = o.silu_mul(rAB)
+    rY, hq, w2q = o.linear_fwd(rH, bits(W2))
+    rdH, rdW2, _ = o.linear_bwd(bits(dY), hq, w2q)
+    rdAB, _ = o.silu_mul_bwd(rAB, rdH)
+    rdX, rdW13, _ = o.linear_bwd(rdAB, xq, w13q)
+    f = FFN(M, D, H)
+    f.forward(X.cuda(), W13.cuda(), W2.cuda())
+    f.backward(dY.cuda())
+    torch.cuda.synchronize()
+    for name, got, ref in (("Y", f.Y, rY), ("dX", f.dX, rdX), ("dW13", f.dW13, rdW13), ("dW2", f.dW2, rdW2)):
+        gv, rv = o.bf16_to_f32(bits(got)).astype(np.float64), o.bf16_to_f32(ref).astype(np.float64)
+        assert np.abs(gv - rv).max() <= 3e-2 * np.abs(rv).max(), name

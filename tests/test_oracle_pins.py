@@ -510,3 +510,52 @@ def test_static_power_of_two_scale_is_lossless_on_the_grid():
     x = np.tile(k * np.float32(0.125), (16, 1))[:, :16]
     codes = o.cast(bf16_bits(x), np.array([16.0], np.float32), o.TENSORWISE, o.E4M3)
     assert np.array_equal(o.decode(codes, o.E4M3) / np.float32(16.0), x)
+
+
+# ---- feed-forward glue (silu(a) * b between two Float8 linears) ----------------------------
+
+def test_silu_mul_against_torch_and_identities():
+    rng = np.random.default_rng(8)
+    M, H = 24, 48
+    ab = bf16_bits(np.concatenate([rng.standard_normal((M, H)) * 3.0, rng.standard_normal((M, H))], axis=1).astype(np.float32))
+    ab[0, :4] = bf16_bits(np.array([0.0, -0.0, 30.0, -30.0], np.float32))
+    h, amax = o.silu_mul(ab)
+    a = torch.from_numpy(o.bf16_to_f32(ab[:, :H]).astype(np.float64))
+    b = torch.from_numpy(o.bf16_to_f32(ab[:, H:]).astype(np.float64))
+    ref = torch.nn.functional.silu(a) * b                                  # PyTorch's own silu, in fp64
+    assert np.array_equal(h, ref.to(torch.float32).to(torch.bfloat16).view(torch.uint16).numpy())
+    assert amax[0] == np.abs(o.bf16_to_f32(h)).max()
+    # silu(t) - silu(-t) = t: with b = 1 the definition must satisfy it to rounding
+    t = (rng.standard_normal(64) * 4).astype(np.float32)
+    tb = bf16_bits(t)
+    one = bf16_bits(np.ones(64, np.float32))
+    pos, _ = o.silu_mul(np.concatenate([tb, one])[None, :])
+    neg, _ = o.silu_mul(np.concatenate([tb ^ 0x8000, one])[None, :])
+    tv = o.bf16_to_f32(tb).astype(np.float64)
+    assert np.allclose(o.bf16_to_f32(pos)[0] - o.bf16_to_f32(neg)[0], tv, rtol=2.0 ** -7, atol=1e-30)
+    # silu(0) = 0, silu(30) ~ 30, silu(-30) ~ -2.8e-12 (times b)
+    hv = o.bf16_to_f32(h)[0, :4] / o.bf16_to_f32(ab[0, H:H + 4])
+    assert hv[0] == 0 and hv[1] == 0 and abs(hv[2] - 30) < 0.2 and -1e-11 < hv[3] < 0
+
+
+def test_silu_mul_bwd_is_the_derivative():
+    """Backward against central differences of the forward definition in fp64."""
+    rng = np.random.default_rng(9)
+    M, H = 8, 32
+    a = o.bf16_to_f32(bf16_bits((rng.standard_normal((M, H)) * 2).astype(np.float32))).astype(np.float64)
+    b = o.bf16_to_f32(bf16_bits(rng.standard_normal((M, H)).astype(np.float32))).astype(np.float64)
+    g = o.bf16_to_f32(bf16_bits(rng.standard_normal((M, H)).astype(np.float32))).astype(np.float64)
+    f = lambda a_, b_: a_ / (1.0 + np.exp(-a_)) * b_
+    eps = 1e-6
+    da_num = g * (f(a + eps, b) - f(a - eps, b)) / (2 * eps)
+    db_num = g * (f(a, b + eps) - f(a, b - eps)) / (2 * eps)
+    ab = np.concatenate([bf16_bits(a.astype(np.float32)), bf16_bits(b.astype(np.float32))], axis=1)
+    dab, amax = o.silu_mul_bwd(ab, bf16_bits(g.astype(np.float32)))
+    got = o.bf16_to_f32(dab).astype(np.float64)
+    want = np.concatenate([da_num, db_num], axis=1)
+    assert np.all(np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 1e-6)      # one bf16 rounding + the difference quotient
+    assert amax[0] == np.abs(got).max()
+    # at a = 0: silu'(0) = 1/2, silu(0) = 0
+    z = np.concatenate([bf16_bits(np.zeros((1, 4), np.float32)), bf16_bits(np.full((1, 4), 3.0, np.float32))], axis=1)
+    d0, _ = o.silu_mul_bwd(z, bf16_bits(np.full((1, 4), 2.0, np.float32)))
+    assert np.array_equal(o.bf16_to_f32(d0), np.array([[3.0, 3.0, 3.0, 3.0, 0.0, 0.0, 0.0, 0.0]], np.float32))
