@@ -103,6 +103,8 @@ def main():
         return
 
     w = wl.WORKLOADS[args.workload]
+    if w.key == "llama8b_ffn":
+        return ffn_main(args, w)
     gran, gfmt = (args.variant.split(":") if args.variant else w.variants[0])
     rowwise = gran == "rowwise"
     grad_fmt = f8.E5M2 if gfmt == "e5m2" else f8.E4M3
@@ -304,6 +306,91 @@ def main():
         out["bf16_matmul_context"] = bf16_context(states, timed, reps, flops_step)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_rows, rowwise, grad_fmt, args.scaling)
+    print(json.dumps(out))
+
+
+def ffn_main(args, w):
+    """The chained feed-forward block: stacked w1|w3 linear, silu(a) * b glue with the amax of
+    its output taken in the same pass, w2 linear; then the backward chain.  FLOPs counted are
+    the linears' (6 M K N each); the glue's time is inside the step."""
+    import torch
+    from paper_2410_06511_amd import f8, workloads as wl
+    l13, l2 = w.linears
+    M, D, H = l13.M, l13.K, l2.K
+    assert l13.N == 2 * H and l2.N == D
+    X, W13, _ = wl.make_linear_inputs(w, 0)
+    _, W2, dY = wl.make_linear_inputs(w, 1)
+    X, W13, W2, dY = X.cuda(), W13.cuda(), W2.cuda(), dY.cuda()
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    d13, d2 = f8.linear_desc(M, D, 2 * H), f8.linear_desc(M, H, D)
+    s13, s2 = f8.Saved(M, D, 2 * H), f8.Saved(M, H, D)
+    ws = f8.new_workspace(max(M, D, 2 * H), max(M, D, 2 * H))
+    AB, Hh, Y = torch.empty((M, 2 * H), **bf), torch.empty((M, H), **bf), torch.empty((M, D), **bf)
+    dH, dAB, dX = torch.empty((M, H), **bf), torch.empty((M, 2 * H), **bf), torch.empty((M, D), **bf)
+    dW13, dW2 = torch.empty((2 * H, D), **bf), torch.empty((D, H), **bf)
+    a_h, a_dab = torch.empty(1, device="cuda"), torch.empty(1, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    calls = [
+        ("linear w13 fwd", lambda: f8.linear_fwd_chained(d13, X, None, W13, AB, None, s13, ws, stream), 2 * M * D * 2 * H, 0),
+        ("silu_mul", lambda: f8.silu_mul(AB, Hh, a_h, ws, stream), 0, 6 * M * H),
+        ("linear w2 fwd", lambda: f8.linear_fwd_chained(d2, Hh, a_h, W2, Y, None, s2, ws, stream), 2 * M * H * D, 0),
+        ("linear w2 bwd", lambda: f8.linear_bwd_chained(d2, dY, None, s2, dH, None, dW2, ws, stream), 4 * M * H * D, 0),
+        ("silu_mul_bwd", lambda: f8.silu_mul_bwd(AB, dH, dAB, a_dab, ws, stream), 0, 10 * M * H),
+        ("linear w13 bwd", lambda: f8.linear_bwd_chained(d13, dAB, a_dab, s13, dX, None, dW13, ws, stream), 4 * M * D * 2 * H, 0),
+    ]
+
+    def step():
+        for _, fn, _, _ in calls:
+            fn()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops_step = sum(l.flops for l in w.linears)
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    reps = max(3, min(args.steps, 10))
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls] for _ in range(reps)]
+    for r in range(reps):
+        for (a, b), (_, fn, _, _) in zip(evs[r], calls):
+            a.record(stream)
+            fn()
+            b.record(stream)
+    torch.cuda.synchronize()
+    legs = []
+    for i, (name, _, fl, by) in enumerate(calls):
+        ms = sum(evs[r][i][0].elapsed_time(evs[r][i][1]) for r in range(reps)) / reps
+        leg = {"call": name, "ms": round(ms, 4)}
+        if fl:
+            leg["tflops_incl_casts"] = round(fl / (ms * 1e-3) / 1e12, 1)
+        if by:
+            leg["gbs"] = round(by / (ms * 1e-3) / 1e9, 1)
+            leg["bytes_per_elem"] = by // (M * H)
+        legs.append(leg)
+    glue_ms = sum(l["ms"] for l in legs if "gbs" in l)
+    glue_bytes = sum(by for _, _, _, by in calls)
+    out = {
+        "metric": "Float8 linear fwd+bwd TFLOP/s (% FP8 MFMA peak) + amax/cast HBM GB/s",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8 (e4m3) x fp8 -> fp32 accumulate -> bf16", "data": "synthetic",
+        "config": {"workload": f"{w.key}: chained feed-forward block, M={M}, hidden {D}, FFN {H}: "
+                               "w1|w3 stacked [N=2*FFN] -> silu(a)*b -> w2, forward and backward",
+                   "scaling_granularity": "tensorwise", "scaling_strategy": "dynamic", "grad_format": "e4m3",
+                   "chained": True, "flops_per_step": flops_step},
+        "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
+        "roofline": {"kernel": "silu_mul_kernel + silu_mul_bwd_kernel (the glue; the GEMM figures are those of the "
+                               "linear workloads)", "bound": "hbm",
+                     "achieved": round(glue_bytes / (glue_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(glue_bytes / (glue_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None},
+        "legs": legs,
+    }
     print(json.dumps(out))
 
 

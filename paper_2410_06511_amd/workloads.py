@@ -76,6 +76,12 @@ WORKLOADS = {
         [Linear("wqkv", 16384, 4096, 6144), Linear("wo", 16384, 4096, 4096),
          Linear("w13", 16384, 4096, 28672), Linear("w2", 16384, 14336, 4096)],
         note="llama8b_block with q|k|v and w1|w3 fused along N"),
+    # The feed-forward block as a real chain: X -> [w1; w3] -> silu(a) * b -> w2 -> Y and back,
+    # each linear's input amax handed over by its producer (the bench runs it with --workload).
+    "llama8b_ffn": Workload(
+        "llama8b_ffn", 7,
+        [Linear("w13", 8192, 4096, 28672), Linear("w2", 8192, 14336, 4096)],
+        note="chained feed-forward block; X and the weights are seeded, the intermediate tensors are computed"),
 }
 
 
