@@ -631,9 +631,35 @@ static void dispatch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, cons
     // CU), else 256x128, else 128x128 (LDS allows two workgroups per CU there).
     const int cus = cu_count();
     auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    if (tiles(256, 256) >= cus)
+    if (tiles(256, 256) >= cus) {
+        // Wave quantisation: T tiles on `cus` persistent workgroups take ceil(T / cus) rounds, and a
+        // last round with at most half of the workgroups busy (e.g. 896 tiles = 3.5 rounds) costs
+        // a whole one.  Then the whole rounds are launched on their own sub-matrix (a range of
+        // tile rows or tile columns holding exactly floor(T / cus) * cus tiles) and the rest is
+        // launched with 256x128 tiles: twice as many, still one per workgroup, each about
+        // 0.6 of a full tile's time.
+        const int tm = (M + 255) / 256, tn = (N + 255) / 256;
+        const int64_t T = (int64_t)tm * tn, whole = T / cus * cus, rest = T - whole;
+        if (rest > 0 && 2 * rest <= cus) {
+            const bool rw = GRAN != F8_TENSORWISE;
+            if (whole % tn == 0) {  // split off the last tile rows
+                const int m1 = (int)(whole / tn) * 256;
+                launch_nt<256, 256, 2, 2, FA, FB, GRAN>(m1, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+                launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M - m1, N, K, A + (int64_t)m1 * lda, lda, B, ldb,
+                                                        rw ? isa + m1 : isa, isb, D + (int64_t)m1 * ldd, ldd,
+                                                        amax_bits, cus, st);
+                return;
+            }
+            if (whole % tm == 0) {  // split off the last tile columns
+                const int n1 = (int)(whole / tm) * 256;
+                launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, n1, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+                launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N - n1, K, A, lda, B + (int64_t)n1 * ldb, ldb, isa,
+                                                        rw ? isb + n1 : isb, D + n1, ldd, amax_bits, cus, st);
+                return;
+            }
+        }
         launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
-    else if (tiles(256, 128) >= cus)
+    } else if (tiles(256, 128) >= cus)
         launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
     else
         launch_nt<128, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, 2 * cus, st);

@@ -184,7 +184,11 @@ def test_gemm_amax_of_empty_output_is_zero():
 # units): 256x256 tiles with a ragged last tile row and column, 256x128 tiles likewise, and
 # shapes whose edges are narrower than one MFMA tile.  Compared in full.
 @pytest.mark.parametrize("g", [f8.TENSORWISE, f8.ROWWISE])
-@pytest.mark.parametrize("M,N,K", [(4112, 4144, 256), (2064, 3600, 512), (4368, 4112, 512), (272, 65552, 256)])
+# The last two have a partial last round of 256x256 tiles (18 x 16 and 16 x 18 tiles on 256 compute
+# units): the whole rounds run on a sub-matrix, the remaining tile rows / tile columns as a
+# second launch with 256x128 tiles, ragged edge included.
+@pytest.mark.parametrize("M,N,K", [(4112, 4144, 256), (2064, 3600, 512), (4368, 4112, 512), (272, 65552, 256),
+                                   (4368, 4000, 256), (4000, 4368, 256)])
 def test_gemm_fast_kernel_ragged_big_tiles(M, N, K, g):
     rng = np.random.default_rng(M + N)
     A, B = rand_codes(rng, (M, K), o.E4M3), rand_codes(rng, (N, K), o.E5M2)
