@@ -328,11 +328,14 @@ def ffn_main(args, w):
     AB, Hh, Y = torch.empty((M, 2 * H), **bf), torch.empty((M, H), **bf), torch.empty((M, D), **bf)
     dH, dAB, dX = torch.empty((M, H), **bf), torch.empty((M, 2 * H), **bf), torch.empty((M, D), **bf)
     dW13, dW2 = torch.empty((2 * H, D), **bf), torch.empty((D, H), **bf)
-    a_h, a_dab = torch.empty(1, device="cuda"), torch.empty(1, device="cuda")
+    a_h, a_dab, a_xn = (torch.empty(1, device="cuda") for _ in range(3))
+    Xn, gw = torch.empty((M, D), **bf), torch.ones(D, **bf)
     stream = torch.cuda.current_stream()
 
+    # (name, call, linear flop, algorithmic bytes of a glue kernel)
     calls = [
-        ("linear w13 fwd", lambda: f8.linear_fwd_chained(d13, X, None, W13, AB, None, s13, ws, stream), 2 * M * D * 2 * H, 0),
+        ("rmsnorm", lambda: f8.rmsnorm(X, gw, 1e-5, Xn, None, a_xn, ws, stream), 0, 4 * M * D),
+        ("linear w13 fwd", lambda: f8.linear_fwd_chained(d13, Xn, a_xn, W13, AB, None, s13, ws, stream), 2 * M * D * 2 * H, 0),
         ("silu_mul", lambda: f8.silu_mul(AB, Hh, a_h, ws, stream), 0, 6 * M * H),
         ("linear w2 fwd", lambda: f8.linear_fwd_chained(d2, Hh, a_h, W2, Y, None, s2, ws, stream), 2 * M * H * D, 0),
         ("linear w2 bwd", lambda: f8.linear_bwd_chained(d2, dY, None, s2, dH, None, dW2, ws, stream), 4 * M * H * D, 0),
@@ -371,7 +374,7 @@ def ffn_main(args, w):
             leg["tflops_incl_casts"] = round(fl / (ms * 1e-3) / 1e12, 1)
         if by:
             leg["gbs"] = round(by / (ms * 1e-3) / 1e9, 1)
-            leg["bytes_per_elem"] = by // (M * H)
+            leg["bytes_per_elem"] = by // (M * D if name == "rmsnorm" else M * H)
         legs.append(leg)
     glue_ms = sum(l["ms"] for l in legs if "gbs" in l)
     glue_bytes = sum(by for _, _, _, by in calls)
@@ -381,12 +384,12 @@ def ffn_main(args, w):
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "fp8 (e4m3) x fp8 -> fp32 accumulate -> bf16", "data": "synthetic",
         "config": {"workload": f"{w.key}: chained feed-forward block, M={M}, hidden {D}, FFN {H}: "
-                               "w1|w3 stacked [N=2*FFN] -> silu(a)*b -> w2, forward and backward",
+                               "rmsnorm -> w1|w3 stacked [N=2*FFN] -> silu(a)*b -> w2, and the backward of the three linear stages",
                    "scaling_granularity": "tensorwise", "scaling_strategy": "dynamic", "grad_format": "e4m3",
                    "chained": True, "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
-        "roofline": {"kernel": "silu_mul_kernel + silu_mul_bwd_kernel (the glue; the GEMM figures are those of the "
-                               "linear workloads)", "bound": "hbm",
+        "roofline": {"kernel": "rmsnorm_kernel + silu_mul_kernel + silu_mul_bwd_kernel (the glue; the GEMM figures "
+                               "are those of the linear workloads)", "bound": "hbm",
                      "achieved": round(glue_bytes / (glue_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": round(glue_bytes / (glue_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None},
         "legs": legs,

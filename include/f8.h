@@ -331,6 +331,22 @@ f8_status f8_silu_mul_bwd(const void* ab_bf16, const void* dh_bf16, int64_t M, i
                           void* dab_bf16, float* amax_dab, void* workspace, size_t workspace_bytes,
                           void* stream);
 
+/*
+ * RMS normalisation in front of a Llama block's attention and feed-forward
+ * linears, forward only (the producer of a Float8 linear's input; its backward
+ * does not touch the Float8 path and is not part of this library):
+ *   y[m, :] = x[m, :] * rstd[m] * g,   rstd[m] = 1 / sqrt(mean_d x[m, d]^2 + eps)
+ * x, y [M, D] bf16, g [D] bf16; rstd (nullable) [M] fp32, kept for a backward
+ * pass; amax_y (nullable, 1 float) receives the exact maximum magnitude of
+ * the bf16 values written, for f8_linear_fwd_chained of the consuming linear.
+ * fp32 arithmetic, one rounding to bf16: within one bf16 unit in the last
+ * place of the exact result.  workspace (only with amax_y):
+ * f8_workspace_bytes(M, D) bytes.  M and D multiples of 16, eps >= 0.
+ */
+f8_status f8_rmsnorm(const void* x_bf16, const void* g_bf16, int64_t M, int64_t D, float eps,
+                     void* y_bf16, float* rstd, float* amax_y, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -475,6 +475,34 @@ void f8o_silu_mul_bwd(const uint16_t* ab, const uint16_t* dh, int64_t M, int64_t
     if (amax_dab) *amax_dab = amax;
 }
 
+/* RMS normalisation in front of the attention and feed-forward linears of a Llama block:
+ *   y[m, :] = x[m, :] * rstd[m] * g,   rstd[m] = 1 / sqrt(mean_d x[m, d]^2 + eps)
+ * The textbook definition, in double precision, one rounding to bf16 (y) or fp32 (rstd).  Only
+ * the forward is here: it is the producer of a Float8 linear's input; the backward of the
+ * normalisation does not touch the Float8 path. */
+void f8o_rmsnorm(const uint16_t* x, const uint16_t* g, int64_t M, int64_t D, double eps, uint16_t* y,
+                 float* rstd, float* amax_y)
+{
+    float amax = 0.0f;
+    for (int64_t m = 0; m < M; ++m) {
+        double ss = 0.0;
+        for (int64_t d = 0; d < D; ++d) {
+            double v = (double)f8o_bf16_to_f32(x[m * D + d]);
+            ss += v * v;
+        }
+        double r = 1.0 / sqrt(ss / (double)D + eps);
+        if (rstd) rstd[m] = (float)r;
+        for (int64_t d = 0; d < D; ++d) {
+            double v = (double)f8o_bf16_to_f32(x[m * D + d]) * r * (double)f8o_bf16_to_f32(g[d]);
+            uint16_t o = f8o_f32_to_bf16((float)v);
+            y[m * D + d] = o;
+            float a = fabsf(f8o_bf16_to_f32(o));
+            if (a > amax) amax = a;
+        }
+    }
+    if (amax_y) *amax_y = amax;
+}
+
 int f8o_num_threads(void)
 {
     int n = 1;

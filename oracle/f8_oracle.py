@@ -60,6 +60,8 @@ def _declare(l):
     l.f8o_silu_mul.argtypes = [_p, _i64, _i64, _p, _p]
     l.f8o_silu_mul_bwd.restype = None
     l.f8o_silu_mul_bwd.argtypes = [_p, _p, _i64, _i64, _p, _p]
+    l.f8o_rmsnorm.restype = None
+    l.f8o_rmsnorm.argtypes = [_p, _p, _i64, _i64, C.c_double, _p, _p, _p]
     l.f8o_history_push.restype = None
     l.f8o_history_push.argtypes = [_p, _i64, _f32, _int, _p, _p]
     l.f8o_cast.restype = None
@@ -340,6 +342,16 @@ def silu_mul_bwd(ab_bits, dh_bits):
     am = np.empty(1, np.float32)
     lib().f8o_silu_mul_bwd(_ptr(ab), _ptr(dh), M, H2 // 2, _ptr(dab), _ptr(am))
     return dab, am
+
+
+def rmsnorm(x_bits, g_bits, eps=1e-5):
+    """-> (y [M, D] bf16 bits, rstd [M] fp32, amax of y)."""
+    x, g = _c(x_bits, np.uint16), _c(g_bits, np.uint16)
+    M, D = x.shape
+    assert g.shape == (D,)
+    y, rstd, am = np.empty((M, D), np.uint16), np.empty(M, np.float32), np.empty(1, np.float32)
+    lib().f8o_rmsnorm(_ptr(x), _ptr(g), M, D, float(eps), _ptr(y), _ptr(rstd), _ptr(am))
+    return y, rstd, am
 
 
 def num_threads():

@@ -91,6 +91,53 @@ __global__ __launch_bounds__(kGlueThreads) void glue_amax_final_kernel(const uin
     if (threadIdx.x == 0) amax_out[0] = mag_to_float(m);
 }
 
+// RMS normalisation, forward: y[m, :] = x[m, :] * rstd[m] * g, rstd[m] = 1 / sqrt(mean x[m, :]^2 + eps).
+// One wavefront per row, rows strided over the grid; the row is read twice (the second time
+// from the caches it has just been loaded into): once for the sum of squares, once to scale.
+__device__ inline float sumsq_word(uint32_t w)
+{
+    const float a = bf16_lo(w), b = bf16_hi(w);
+    return a * a + b * b;
+}
+__device__ inline uint32_t scale_word(uint32_t x, uint32_t g, float r)
+{
+    return pack_bf16((bf16_lo(x) * r) * bf16_lo(g), (bf16_hi(x) * r) * bf16_hi(g));
+}
+
+__global__ __launch_bounds__(kGlueThreads) void rmsnorm_kernel(const uint4* __restrict__ x, const uint4* __restrict__ g,
+                                                              int64_t M, int64_t dc /* 16-byte chunks per row */,
+                                                              float inv_d, float eps, uint4* __restrict__ y,
+                                                              float* __restrict__ rstd, uint32_t* __restrict__ partial)
+{
+    __shared__ uint32_t red[kGlueWaves];
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    uint32_t acc = 0;
+    for (int64_t m = (int64_t)blockIdx.x * kGlueWaves + wave; m < M; m += (int64_t)gridDim.x * kGlueWaves) {
+        const uint4* row = x + m * dc;
+        float ss = 0.0f;
+        for (int64_t c = lane; c < dc; c += kWave) {
+            const uint4 v = row[c];
+            ss += (sumsq_word(v.x) + sumsq_word(v.y)) + (sumsq_word(v.z) + sumsq_word(v.w));
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, kWave);
+        const float r = 1.0f / sqrtf(ss * inv_d + eps);
+        if (lane == 0 && rstd) rstd[m] = r;
+        for (int64_t c = lane; c < dc; c += kWave) {
+            const uint4 v = row[c], w = g[c];
+            uint4 o;
+            o.x = scale_word(v.x, w.x, r), o.y = scale_word(v.y, w.y, r);
+            o.z = scale_word(v.z, w.z, r), o.w = scale_word(v.w, w.w, r);
+            y[m * dc + c] = o;
+            acc = absmax_acc(acc, o);
+        }
+    }
+    if (partial) {
+        const uint32_t mx = block_max_u32<kGlueWaves>(pk_collapse(acc), red);
+        if (threadIdx.x == 0) partial[blockIdx.x] = mx;
+    }
+}
+
 static int glue_blocks(int64_t chunks)
 {
     int64_t b = (chunks + kGlueThreads * 2 - 1) / (kGlueThreads * 2);
@@ -146,6 +193,25 @@ f8_status f8_silu_mul_bwd(const void* ab_bf16, const void* dh_bf16, int64_t M, i
                                                          (uint4*)dab_bf16, amax_dab ? (uint32_t*)workspace : nullptr);
     }
     if (amax_dab) glue_amax_final_kernel<<<1, kGlueThreads, 0, st>>>((const uint32_t*)workspace, nb, amax_dab);
+    return last_launch_status();
+}
+
+f8_status f8_rmsnorm(const void* x_bf16, const void* g_bf16, int64_t M, int64_t D, float eps, void* y_bf16,
+                     float* rstd, float* amax_y, void* workspace, size_t workspace_bytes_, void* stream)
+{
+    if (!x_bf16 || !g_bf16 || !y_bf16) return F8_ERR_NULL;
+    if (M < 0 || D < 0 || (M % 16) || (D % 16) || !(eps >= 0.0f)) return F8_ERR_SHAPE;
+    if (!aligned16(x_bf16) || !aligned16(g_bf16) || !aligned16(y_bf16)) return F8_ERR_ALIGN;
+    if (amax_y && (!workspace || workspace_bytes_ < (size_t)kGlueMaxBlocks * sizeof(uint32_t))) return F8_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    int nb = 0;
+    if (M > 0 && D > 0) {
+        int64_t b = (M + kGlueWaves - 1) / kGlueWaves;
+        nb = (int)(b > kGlueMaxBlocks ? kGlueMaxBlocks : b);
+        rmsnorm_kernel<<<nb, kGlueThreads, 0, st>>>((const uint4*)x_bf16, (const uint4*)g_bf16, M, D / 8, 1.0f / (float)D, eps,
+                                                    (uint4*)y_bf16, rstd, amax_y ? (uint32_t*)workspace : nullptr);
+    }
+    if (amax_y) glue_amax_final_kernel<<<1, kGlueThreads, 0, st>>>((const uint32_t*)workspace, nb, amax_y);
     return last_launch_status();
 }
 

@@ -26,7 +26,7 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
            "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled",
            "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise",
-           "f8_silu_mul", "f8_silu_mul_bwd"]
+           "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm"]
 
 
 class F8Error(RuntimeError):
@@ -85,6 +85,7 @@ def lib():
         l.f8_quantise.argtypes = [_p, _i64, _i64, _int, _int, C.POINTER(QTensorStruct), _p, C.c_size_t, _p]
         l.f8_silu_mul.argtypes = [_p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_silu_mul_bwd.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
+        l.f8_rmsnorm.argtypes = [_p, _p, _i64, _i64, C.c_float, _p, _p, _p, _p, C.c_size_t, _p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
         _lib = l
@@ -286,3 +287,10 @@ def silu_mul_bwd(ab, dh, dab, amax_dab=None, workspace=None, stream=None):
     M, H2 = ab.shape
     wp, wb = _ws(workspace)
     _check(lib().f8_silu_mul_bwd(_ptr(ab), _ptr(dh), M, H2 // 2, _ptr(dab), _ptr(amax_dab), wp, wb, _stream(stream)))
+
+
+def rmsnorm(x, g, eps, y, rstd=None, amax_y=None, workspace=None, stream=None):
+    M, D = x.shape
+    wp, wb = _ws(workspace)
+    _check(lib().f8_rmsnorm(_ptr(x), _ptr(g), M, D, float(eps), _ptr(y), _ptr(rstd), _ptr(amax_y), wp, wb,
+                            _stream(stream)))

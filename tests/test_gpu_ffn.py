@@ -195,3 +195,51 @@ def test_ffn_end_to_end_close_to_oracle():
     for name, got, ref in (("Y", f.Y, rY), ("dX", f.dX, rdX), ("dW13", f.dW13, rdW13), ("dW2", f.dW2, rdW2)):
         gv, rv = o.bf16_to_f32(bits(got)).astype(np.float64), o.bf16_to_f32(ref).astype(np.float64)
         assert np.abs(gv - rv).max() <= 3e-2 * np.abs(rv).max(), name
+
+
+@pytest.mark.parametrize("M,D", [(16, 16), (272, 336), (512, 4096), (64, 16384)])
+def test_rmsnorm_forward(M, D):
+    g_ = torch.Generator("cpu")
+    g_.manual_seed(M + D)
+    x = wl.randn_bf16((M, D), 3.0, 0, generator=g_)
+    x[1] = 0.0                                    # an all-zero row: rstd = 1 / sqrt(eps), y = 0
+    gw = (1.0 + 0.1 * torch.randn(D, generator=g_)).to(torch.bfloat16)
+    eps = 1e-5
+    ws = f8.new_workspace(M, D)
+    y = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+    rstd = torch.empty(M, device="cuda")
+    amax = torch.full((1,), -1.0, device="cuda")
+    f8.rmsnorm(x.cuda(), gw.cuda(), eps, y, rstd, amax, ws)
+    torch.cuda.synchronize()
+    ry, rr, ra = o.rmsnorm(bits(x), bits(gw), eps)
+    assert_bf16_close(bits(y), ry, "y")
+    assert np.allclose(f32(rstd), rr, rtol=2e-6)
+    assert amax.item() == o.amax(bits(y))[0] and abs(amax.item() - ra[0]) <= 2.0 ** -7 * ra[0]
+    y2 = torch.empty_like(y)
+    f8.rmsnorm(x.cuda(), gw.cuda(), eps, y2)      # no rstd, no amax, no workspace
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+
+def test_norm_then_feed_forward_chain():
+    """rmsnorm -> w1|w3 -> silu(a) * b -> w2 with every amax handed over: identical to the same
+    sequence with each linear taking its own amax."""
+    M, D, H = 512, 768, 1024
+    X, W13, W2, _ = (t.cuda() for t in _ffn_inputs(M, D, H, 8))
+    gw = torch.ones(D, dtype=torch.bfloat16, device="cuda")
+    outs = []
+    for chained in (True, False):
+        f = FFN(M, D, H)
+        xn = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+        a_xn = torch.empty(1, device="cuda")
+        f8.rmsnorm(X, gw, 1e-5, xn, None, a_xn if chained else None, f.ws)
+        if chained:
+            f8.linear_fwd_chained(f.d13, xn, a_xn, W13, f.AB, None, f.s13, f.ws)
+            f8.silu_mul(f.AB, f.Hh, f.a_h, f.ws)
+            f8.linear_fwd_chained(f.d2, f.Hh, f.a_h, W2, f.Y, None, f.s2, f.ws)
+        else:
+            f.forward(xn, W13, W2, chained=False)
+        torch.cuda.synchronize()
+        outs.append((f.Y, f.s13.x.q, f.s13.x.scale, f.s2.x.q_t))
+    for a, b in zip(*outs):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))

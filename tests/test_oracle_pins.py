@@ -559,3 +559,24 @@ def test_silu_mul_bwd_is_the_derivative():
     z = np.concatenate([bf16_bits(np.zeros((1, 4), np.float32)), bf16_bits(np.full((1, 4), 3.0, np.float32))], axis=1)
     d0, _ = o.silu_mul_bwd(z, bf16_bits(np.full((1, 4), 2.0, np.float32)))
     assert np.array_equal(o.bf16_to_f32(d0), np.array([[3.0, 3.0, 3.0, 3.0, 0.0, 0.0, 0.0, 0.0]], np.float32))
+
+
+# ---- RMS normalisation in front of the linears ---------------------------------------------
+
+def test_rmsnorm_against_torch_and_closed_forms():
+    rng = np.random.default_rng(10)
+    M, D = 12, 96
+    x = bf16_bits((rng.standard_normal((M, D)) * 3).astype(np.float32))
+    g = bf16_bits((1 + 0.1 * rng.standard_normal(D)).astype(np.float32))
+    y, rstd, amax = o.rmsnorm(x, g, 1e-5)
+    xt = torch.from_numpy(o.bf16_to_f32(x).astype(np.float64))
+    gt = torch.from_numpy(o.bf16_to_f32(g).astype(np.float64))
+    ref = torch.nn.functional.rms_norm(xt, (D,), gt, 1e-5)                    # PyTorch's own, in fp64
+    assert np.array_equal(y, ref.to(torch.float32).to(torch.bfloat16).view(torch.uint16).numpy())
+    assert np.allclose(rstd, (1.0 / torch.sqrt((xt * xt).mean(1) + 1e-5)).numpy(), rtol=1e-6)
+    assert amax[0] == np.abs(o.bf16_to_f32(y)).max()
+    # a row of constant magnitude c has rms c: y = sign(x) * g (eps negligible)
+    c = bf16_bits(np.full((1, D), 4.0, np.float32))
+    c[0, ::2] ^= 0x8000
+    yc, rc, _ = o.rmsnorm(c, bf16_bits(np.full(D, 0.5, np.float32)), 1e-12)
+    assert rc[0] == 0.25 and np.array_equal(o.bf16_to_f32(yc)[0], np.where(np.arange(D) % 2 == 0, -0.5, 0.5))
