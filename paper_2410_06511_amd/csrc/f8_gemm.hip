@@ -627,42 +627,46 @@ static void dispatch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, cons
                         const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
                         hipStream_t st)
 {
-    // The largest tile that still gives every CU work: 256x256 (one persistent workgroup per
-    // CU), else 256x128, else 128x128 (LDS allows two workgroups per CU there).
+    // Tile configuration by estimated time, in units of one 256x256 tile's time on one compute
+    // unit: T tiles on `cus` persistent workgroups take ceil(T / cus) rounds; a 256x128 tile costs
+    // about 0.63 and a 128x128 tile about 0.58 of a 256x256 one (measured: their wave tiles need
+    // more LDS bytes per MFMA).  Ties go to the larger tile.
     const int cus = cu_count();
     auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
-    if (tiles(256, 256) >= cus) {
-        // Wave quantisation: T tiles on `cus` persistent workgroups take ceil(T / cus) rounds, and a
-        // last round with at most half of the workgroups busy (e.g. 896 tiles = 3.5 rounds) costs
-        // a whole one.  Then the whole rounds are launched on their own sub-matrix (a range of
-        // tile rows or tile columns holding exactly floor(T / cus) * cus tiles) and the rest is
-        // launched with 256x128 tiles: twice as many, still one per workgroup, each about
-        // 0.6 of a full tile's time.
-        const int tm = (M + 255) / 256, tn = (N + 255) / 256;
-        const int64_t T = (int64_t)tm * tn, whole = T / cus * cus, rest = T - whole;
-        if (rest > 0 && 2 * rest <= cus) {
-            const bool rw = GRAN != F8_TENSORWISE;
-            if (whole % tn == 0) {  // split off the last tile rows
-                const int m1 = (int)(whole / tn) * 256;
-                launch_nt<256, 256, 2, 2, FA, FB, GRAN>(m1, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
-                launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M - m1, N, K, A + (int64_t)m1 * lda, lda, B, ldb,
-                                                        rw ? isa + m1 : isa, isb, D + (int64_t)m1 * ldd, ldd,
-                                                        amax_bits, cus, st);
-                return;
-            }
-            if (whole % tm == 0) {  // split off the last tile columns
-                const int n1 = (int)(whole / tm) * 256;
-                launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, n1, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
-                launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N - n1, K, A, lda, B + (int64_t)n1 * ldb, ldb, isa,
-                                                        rw ? isb + n1 : isb, D + n1, ldd, amax_bits, cus, st);
-                return;
-            }
+    auto rounds = [&](int64_t t) { return (double)((t + cus - 1) / cus); };
+    constexpr double kHalfTile = 0.63, kQuarterTile = 0.58;
+    const int tm = (M + 255) / 256, tn = (N + 255) / 256;
+    const int64_t T = (int64_t)tm * tn, whole = T / cus * cus, rest = T - whole;
+    // Wave quantisation: a last round with at most half of the workgroups busy (e.g. 896 tiles =
+    // 3.5 rounds) costs a whole one.  Then the whole rounds are launched on their own sub-matrix
+    // (a range of tile rows or tile columns holding exactly `whole` tiles) and the rest with
+    // 256x128 tiles: twice as many, still at most one per workgroup.
+    const bool split_rows = whole > 0 && rest > 0 && 2 * rest <= cus && whole % tn == 0;
+    const bool split_cols = !split_rows && whole > 0 && rest > 0 && 2 * rest <= cus && whole % tm == 0;
+    const double c_full = (split_rows || split_cols) ? (double)(whole / cus) + kHalfTile : rounds(T);
+    const double c_half = rounds(tiles(256, 128)) * kHalfTile;
+    const double c_quarter = rounds(tiles(128, 128)) * kQuarterTile;
+    const bool rw = GRAN != F8_TENSORWISE;
+    if (c_full <= c_half && c_full <= c_quarter) {
+        if (split_rows) {
+            const int m1 = (int)(whole / tn) * 256;
+            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(m1, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+            launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M - m1, N, K, A + (int64_t)m1 * lda, lda, B, ldb, rw ? isa + m1 : isa,
+                                                    isb, D + (int64_t)m1 * ldd, ldd, amax_bits, cus, st);
+        } else if (split_cols) {
+            const int n1 = (int)(whole / tm) * 256;
+            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, n1, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+            launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N - n1, K, A, lda, B + (int64_t)n1 * ldb, ldb, isa,
+                                                    rw ? isb + n1 : isb, D + n1, ldd, amax_bits, cus, st);
+        } else {
+            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
         }
-        launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
-    } else if (tiles(256, 128) >= cus)
+    } else if (c_half <= c_quarter) {
         launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
-    else
+    } else {
+        // LDS allows two 128x128 workgroups per compute unit
         launch_nt<128, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, 2 * cus, st);
+    }
 }
 
 template <int LAYOUT, int FA, int FB, int GRAN>
