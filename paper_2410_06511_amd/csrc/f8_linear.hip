@@ -93,6 +93,60 @@ static f8_status check_state(const f8_scaling_state* st, bool fwd)
     return F8_OK;
 }
 
+// Argument checks shared by the forward entry points (every check before any launch).
+static f8_status check_fwd(const f8_linear_desc* d, bool tensorwise_only, const void* X, const void* W, const void* Y,
+                           const f8_saved* saved, const void* ws, size_t ws_bytes)
+{
+    f8_status s = check_desc(d);
+    if (s != F8_OK) return s;
+    if (tensorwise_only && d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
+    if (!X || !W || !Y || !saved) return F8_ERR_NULL;
+    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return F8_ERR_ALIGN;
+    const bool rw = d->granularity == F8_ROWWISE;
+    if ((s = check_q(&saved->x, rw)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, rw)) != F8_OK) return s;
+    if (!ws || ws_bytes < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    return F8_OK;
+}
+
+static f8_status check_bwd(const f8_linear_desc* d, bool tensorwise_only, const void* dY, const f8_saved* saved,
+                           const void* dX, const void* dW, const void* ws, size_t ws_bytes)
+{
+    f8_status s = check_desc(d);
+    if (s != F8_OK) return s;
+    if (tensorwise_only && d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
+    if (!dY || !dX || !dW || !saved) return F8_ERR_NULL;
+    if (!aligned16(dY) || !aligned16(dX) || !aligned16(dW)) return F8_ERR_ALIGN;
+    const bool rw = d->granularity == F8_ROWWISE;
+    if ((s = check_q(&saved->x, rw)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, rw)) != F8_OK) return s;
+    if ((s = check_q(&saved->dy, rw)) != F8_OK) return s;
+    if (!ws || ws_bytes < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    return F8_OK;
+}
+
+// Y [M,N] = X8 [M,K] . (W8 [N,K])^T, scales in the epilogue; y_amax may be null.
+static f8_status gemm_fwd(const f8_linear_desc* d, const f8_saved* sv, void* Y, float* y_amax, hipStream_t st)
+{
+    return gemm(F8_NT, d->M, d->N, d->K, sv->x.q, F8_E4M3, d->K, sv->w.q, F8_E4M3, d->K, sv->x.inv_scale,
+                sv->w.inv_scale, d->granularity, Y, d->N, y_amax, st);
+}
+
+// dX [M,K] = dY8 [M,N] . (W8t [K,N])^T : dY per row m; W per column k = per row of W8t
+// dW [N,K] = dY8t [N,M] . (X8t [K,M])^T : dY per column n, X per column k
+static f8_status gemms_bwd(const f8_linear_desc* d, const f8_saved* sv, void* dX, float* dx_amax, void* dW,
+                           hipStream_t st)
+{
+    const int64_t M = d->M, K = d->K, N = d->N;
+    const int gf = d->grad_format;
+    const bool rw = d->granularity == F8_ROWWISE;
+    f8_status s = gemm(F8_NT, M, K, N, sv->dy.q, gf, N, sv->w.q_t, F8_E4M3, N, sv->dy.inv_scale,
+                       rw ? sv->w.inv_scale_t : sv->w.inv_scale, d->granularity, dX, K, dx_amax, st);
+    if (s != F8_OK) return s;
+    return gemm(F8_NT, N, K, M, sv->dy.q_t, gf, M, sv->x.q_t, F8_E4M3, M, rw ? sv->dy.inv_scale_t : sv->dy.inv_scale,
+                rw ? sv->x.inv_scale_t : sv->x.inv_scale, d->granularity, dW, K, nullptr, st);
+}
+
 }  // namespace f8
 
 using namespace f8;
@@ -129,48 +183,24 @@ f8_status f8_quantise(const void* t_bf16, int64_t rows, int64_t cols, f8_granula
 f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, void* Y, f8_saved* saved,
                         void* workspace, size_t workspace_bytes_, void* stream)
 {
-    f8_status s = check_desc(d);
+    f8_status s = check_fwd(d, false, X, W, Y, saved, workspace, workspace_bytes_);
     if (s != F8_OK) return s;
-    if (!X || !W || !Y || !saved) return F8_ERR_NULL;
-    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return F8_ERR_ALIGN;
-    const bool rw = d->granularity == F8_ROWWISE;
-    if ((s = check_q(&saved->x, rw)) != F8_OK) return s;
-    if ((s = check_q(&saved->w, rw)) != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t M = d->M, K = d->K, N = d->N;
-    if ((s = quantise_both(X, M, K, rw, F8_E4M3, &saved->x, workspace, st)) != F8_OK) return s;
-    if ((s = quantise_both(W, N, K, rw, F8_E4M3, &saved->w, workspace, st)) != F8_OK) return s;
-    return gemm(F8_NT, M, N, K, saved->x.q, F8_E4M3, K, saved->w.q, F8_E4M3, K, saved->x.inv_scale,
-                saved->w.inv_scale, d->granularity, Y, N, nullptr, st);
+    const bool rw = d->granularity == F8_ROWWISE;
+    if ((s = quantise_both(X, d->M, d->K, rw, F8_E4M3, &saved->x, workspace, st)) != F8_OK) return s;
+    if ((s = quantise_both(W, d->N, d->K, rw, F8_E4M3, &saved->w, workspace, st)) != F8_OK) return s;
+    return gemm_fwd(d, saved, Y, nullptr, st);
 }
 
 f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved, void* dX, void* dW,
                         void* workspace, size_t workspace_bytes_, void* stream)
 {
-    f8_status s = check_desc(d);
+    f8_status s = check_bwd(d, false, dY, saved, dX, dW, workspace, workspace_bytes_);
     if (s != F8_OK) return s;
-    if (!dY || !dX || !dW || !saved) return F8_ERR_NULL;
-    if (!aligned16(dY) || !aligned16(dX) || !aligned16(dW)) return F8_ERR_ALIGN;
-    const bool rw = d->granularity == F8_ROWWISE;
-    if ((s = check_q(&saved->x, rw)) != F8_OK) return s;
-    if ((s = check_q(&saved->w, rw)) != F8_OK) return s;
-    if ((s = check_q(&saved->dy, rw)) != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t M = d->M, K = d->K, N = d->N;
-    const int gf = d->grad_format;
-    if ((s = quantise_both(dY, M, N, rw, gf, &saved->dy, workspace, st)) != F8_OK) return s;
-    // dX = dY8 [M,N] . (W8t [K,N])^T : dY per row m; W per column k = per row of W8t
-    const float* w_is = rw ? saved->w.inv_scale_t : saved->w.inv_scale;
-    if ((s = gemm(F8_NT, M, K, N, saved->dy.q, gf, N, saved->w.q_t, F8_E4M3, N, saved->dy.inv_scale, w_is,
-                  d->granularity, dX, K, nullptr, st)) != F8_OK)
+    if ((s = quantise_both(dY, d->M, d->N, d->granularity == F8_ROWWISE, d->grad_format, &saved->dy, workspace, st)) != F8_OK)
         return s;
-    // dW = dY8t [N,M] . (X8t [K,M])^T : dY per column n, X per column k
-    const float* dy_is = rw ? saved->dy.inv_scale_t : saved->dy.inv_scale;
-    const float* x_is = rw ? saved->x.inv_scale_t : saved->x.inv_scale;
-    return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, dy_is, x_is, d->granularity,
-                dW, K, nullptr, st);
+    return gemms_bwd(d, saved, dX, nullptr, dW, st);
 }
 
 f8_status f8_linear_fwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* X,
@@ -180,23 +210,15 @@ f8_status f8_linear_fwd_scaled(const f8_linear_desc* d, const f8_scaling_state* 
     f8_status s = check_state(state, true);
     if (s != F8_OK) return s;
     if (state->mode == F8_DYNAMIC) return f8_linear_fwd(d, X, W, Y, saved, workspace, workspace_bytes_, stream);
-    if ((s = check_desc(d)) != F8_OK) return s;
-    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
-    if (!X || !W || !Y || !saved) return F8_ERR_NULL;
-    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return F8_ERR_ALIGN;
-    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
-    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    if ((s = check_fwd(d, true, X, W, Y, saved, workspace, workspace_bytes_)) != F8_OK) return s;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t M = d->M, K = d->K, N = d->N;
-    if ((s = quantise_scaled(X, M, K, F8_E4M3, state->mode, state->history_len, state->hist_x, state->scale_x,
+    if ((s = quantise_scaled(X, d->M, d->K, F8_E4M3, state->mode, state->history_len, state->hist_x, state->scale_x,
                              &saved->x, workspace, workspace_bytes_, st)) != F8_OK)
         return s;
-    if ((s = quantise_scaled(W, N, K, F8_E4M3, state->mode, state->history_len, state->hist_w, state->scale_w,
+    if ((s = quantise_scaled(W, d->N, d->K, F8_E4M3, state->mode, state->history_len, state->hist_w, state->scale_w,
                              &saved->w, workspace, workspace_bytes_, st)) != F8_OK)
         return s;
-    return gemm(F8_NT, M, N, K, saved->x.q, F8_E4M3, K, saved->w.q, F8_E4M3, K, saved->x.inv_scale,
-                saved->w.inv_scale, F8_TENSORWISE, Y, N, nullptr, st);
+    return gemm_fwd(d, saved, Y, nullptr, st);
 }
 
 f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* dY,
@@ -206,39 +228,20 @@ f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* 
     f8_status s = check_state(state, false);
     if (s != F8_OK) return s;
     if (state->mode == F8_DYNAMIC) return f8_linear_bwd(d, dY, saved, dX, dW, workspace, workspace_bytes_, stream);
-    if ((s = check_desc(d)) != F8_OK) return s;
-    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
-    if (!dY || !dX || !dW || !saved) return F8_ERR_NULL;
-    if (!aligned16(dY) || !aligned16(dX) || !aligned16(dW)) return F8_ERR_ALIGN;
-    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
-    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
-    if ((s = check_q(&saved->dy, false)) != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    if ((s = check_bwd(d, true, dY, saved, dX, dW, workspace, workspace_bytes_)) != F8_OK) return s;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t M = d->M, K = d->K, N = d->N;
-    const int gf = d->grad_format;
-    if ((s = quantise_scaled(dY, M, N, gf, state->mode, state->history_len, state->hist_dy, state->scale_dy,
-                             &saved->dy, workspace, workspace_bytes_, st)) != F8_OK)
+    if ((s = quantise_scaled(dY, d->M, d->N, d->grad_format, state->mode, state->history_len, state->hist_dy,
+                             state->scale_dy, &saved->dy, workspace, workspace_bytes_, st)) != F8_OK)
         return s;
-    if ((s = gemm(F8_NT, M, K, N, saved->dy.q, gf, N, saved->w.q_t, F8_E4M3, N, saved->dy.inv_scale,
-                  saved->w.inv_scale, F8_TENSORWISE, dX, K, nullptr, st)) != F8_OK)
-        return s;
-    return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, saved->dy.inv_scale,
-                saved->x.inv_scale, F8_TENSORWISE, dW, K, nullptr, st);
+    return gemms_bwd(d, saved, dX, nullptr, dW, st);
 }
 
 f8_status f8_linear_fwd_chained(const f8_linear_desc* d, const void* X, const float* x_amax, const void* W,
                                 void* Y, float* y_amax, f8_saved* saved, void* workspace,
                                 size_t workspace_bytes_, void* stream)
 {
-    f8_status s = check_desc(d);
+    f8_status s = check_fwd(d, true, X, W, Y, saved, workspace, workspace_bytes_);
     if (s != F8_OK) return s;
-    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
-    if (!X || !W || !Y || !saved) return F8_ERR_NULL;
-    if (!aligned16(X) || !aligned16(W) || !aligned16(Y)) return F8_ERR_ALIGN;
-    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
-    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const int64_t M = d->M, K = d->K, N = d->N;
     if (x_amax)
@@ -248,25 +251,17 @@ f8_status f8_linear_fwd_chained(const f8_linear_desc* d, const void* X, const fl
         s = quantise_both(X, M, K, false, F8_E4M3, &saved->x, workspace, st);
     if (s != F8_OK) return s;
     if ((s = quantise_both(W, N, K, false, F8_E4M3, &saved->w, workspace, st)) != F8_OK) return s;
-    return gemm(F8_NT, M, N, K, saved->x.q, F8_E4M3, K, saved->w.q, F8_E4M3, K, saved->x.inv_scale,
-                saved->w.inv_scale, F8_TENSORWISE, Y, N, y_amax, st);
+    return gemm_fwd(d, saved, Y, y_amax, st);
 }
 
 f8_status f8_linear_bwd_chained(const f8_linear_desc* d, const void* dY, const float* dy_amax, f8_saved* saved,
                                 void* dX, float* dx_amax, void* dW, void* workspace, size_t workspace_bytes_,
                                 void* stream)
 {
-    f8_status s = check_desc(d);
+    f8_status s = check_bwd(d, true, dY, saved, dX, dW, workspace, workspace_bytes_);
     if (s != F8_OK) return s;
-    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
-    if (!dY || !dX || !dW || !saved) return F8_ERR_NULL;
-    if (!aligned16(dY) || !aligned16(dX) || !aligned16(dW)) return F8_ERR_ALIGN;
-    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
-    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
-    if ((s = check_q(&saved->dy, false)) != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < linear_workspace(d)) return F8_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t M = d->M, K = d->K, N = d->N;
+    const int64_t M = d->M, N = d->N;
     const int gf = d->grad_format;
     if (dy_amax)
         s = quantise_known_amax(dY, M, N, N, gf, dy_amax, saved->dy.amax, saved->dy.scale, saved->dy.inv_scale,
@@ -274,11 +269,7 @@ f8_status f8_linear_bwd_chained(const f8_linear_desc* d, const void* dY, const f
     else
         s = quantise_both(dY, M, N, false, gf, &saved->dy, workspace, st);
     if (s != F8_OK) return s;
-    if ((s = gemm(F8_NT, M, K, N, saved->dy.q, gf, N, saved->w.q_t, F8_E4M3, N, saved->dy.inv_scale,
-                  saved->w.inv_scale, F8_TENSORWISE, dX, K, dx_amax, st)) != F8_OK)
-        return s;
-    return gemm(F8_NT, N, K, M, saved->dy.q_t, gf, M, saved->x.q_t, F8_E4M3, M, saved->dy.inv_scale,
-                saved->x.inv_scale, F8_TENSORWISE, dW, K, nullptr, st);
+    return gemms_bwd(d, saved, dX, dx_amax, dW, st);
 }
 
 }  // extern "C"
