@@ -209,31 +209,31 @@ def main():
     for li, s in enumerate(states):
         M, K, N = s.lin.M, s.lin.K, s.lin.N
         sv = s.saved
-        ops.append(("cast", li, cast_op(s.X, sv.x, f8.E4M3), s.X.numel()))
-        ops.append(("cast", li, cast_op(s.W, sv.w, f8.E4M3), s.W.numel()))
+        ops.append(("cast", li, cast_op(s.X, sv.x, f8.E4M3), s.X.numel(), "X"))
+        ops.append(("cast", li, cast_op(s.W, sv.w, f8.E4M3), s.W.numel(), "W"))
         ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N: f8.gemm(
             f8.NT, M, N, K, sv.x.q, f8.E4M3, sv.w.q, f8.E4M3, sv.x.inv_scale, sv.w.inv_scale, g, s.Y, stream)),
-            2 * M * K * N))
+            2 * M * K * N, "Y = X W^T"))
     for li, s in reversed(list(enumerate(states))):
         M, K, N = s.lin.M, s.lin.K, s.lin.N
         sv = s.saved
         w_is_t = sv.w.inv_scale_t if rowwise else sv.w.inv_scale
         dy_is_t = sv.dy.inv_scale_t if rowwise else sv.dy.inv_scale
         x_is_t = sv.x.inv_scale_t if rowwise else sv.x.inv_scale
-        ops.append(("cast", li, cast_op(s.dY, sv.dy, grad_fmt), s.dY.numel()))
+        ops.append(("cast", li, cast_op(s.dY, sv.dy, grad_fmt), s.dY.numel(), "dY"))
         ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, w_is_t=w_is_t: f8.gemm(
             f8.NT, M, K, N, sv.dy.q, grad_fmt, sv.w.q_t, f8.E4M3, sv.dy.inv_scale, w_is_t, g, s.dX, stream)),
-            2 * M * K * N))
+            2 * M * K * N, "dX = dY W"))
         ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, dy_is_t=dy_is_t, x_is_t=x_is_t: f8.gemm(
             f8.NT, N, K, M, sv.dy.q_t, grad_fmt, sv.x.q_t, f8.E4M3, dy_is_t, x_is_t, g, s.dW, stream)),
-            2 * M * K * N))
+            2 * M * K * N, "dW = dY^T X"))
 
     evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
            for _ in range(reps)]
-    for _, _, fn, _ in ops:   # one untimed pass
+    for _, _, fn, _, _ in ops:   # one untimed pass
         fn()
     for r in range(reps):
-        for (a, b), (_, _, fn, _) in zip(evs[r], ops):
+        for (a, b), (_, _, fn, _, _) in zip(evs[r], ops):
             a.record(stream)
             fn()
             b.record(stream)
@@ -251,7 +251,16 @@ def main():
         lc = sum(ms for ms, op in zip(op_ms, ops) if op[0] == "cast" and op[1] == li)
         per_linear.append({"name": s.lin.name, "M": s.lin.M, "K": s.lin.K, "N": s.lin.N,
                            "gemm_ms": round(lg, 4), "cast_ms": round(lc, 4),
-                           "gemm_tflops": round(s.lin.flops / (lg * 1e-3) / 1e12, 1)})
+                           "gemm_tflops": round(s.lin.flops / (lg * 1e-3) / 1e12, 1),
+                           "tflops_by_product": {op[4]: round(op[3] / (ms * 1e-3) / 1e12, 1)
+                                                 for ms, op in zip(op_ms, ops) if op[0] == "gemm" and op[1] == li},
+                           "cast_us_by_tensor": {op[4]: round(ms * 1e3, 1)
+                                                 for ms, op in zip(op_ms, ops) if op[0] == "cast" and op[1] == li}})
+    by_product = {}
+    for name in ("Y = X W^T", "dX = dY W", "dW = dY^T X"):
+        fl = sum(op[3] for op in ops if op[0] == "gemm" and op[4] == name)
+        t = sum(ms for ms, op in zip(op_ms, ops) if op[0] == "gemm" and op[4] == name)
+        by_product[name] = round(fl / (t * 1e-3) / 1e12, 1)
 
     gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12
     roofline = {
@@ -263,6 +272,7 @@ def main():
         "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
         "traffic": committed_traffic(),
         "launches_per_step": gemm_launches,
+        "tflops_by_product": by_product,
         "avg_launch_ms": round(gemm_ms / gemm_launches, 4),
         "flops_per_launch": gemm_flops // gemm_launches,
     }

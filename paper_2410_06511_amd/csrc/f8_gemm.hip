@@ -112,7 +112,8 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
 // two K steps ahead of the MFMAs and does not stop at tile boundaries, so the
 // next tile's first stages arrive while the current tile's epilogue runs.
 // Fragments of the next half-step are read from LDS into a second register set
-// while the MFMAs of the current one run; there is one barrier per K step.
+// while the MFMAs of the current one run; there are two barriers per K step (this stage is free
+// to refill; the other stage has landed), each with MFMAs queued in front of it.
 constexpr int kBK = 128;  // bytes of K per LDS stage
 
 typedef float v16f __attribute__((ext_vector_type(16)));
