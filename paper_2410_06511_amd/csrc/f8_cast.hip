@@ -577,6 +577,7 @@ static f8_status check_matrix(const void* p, int64_t rows, int64_t cols, int64_t
 {
     if (!p) return F8_ERR_NULL;
     if (rows < 0 || cols < 0 || (rows % 16) || (cols % 16) || (ld % 16) || ld < cols) return F8_ERR_SHAPE;
+    if (((rows + 127) / 128) * ((cols + 127) / 128) > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;  // one block per 128x128 tile
     if (!aligned16(p)) return F8_ERR_ALIGN;
     return F8_OK;
 }

@@ -546,7 +546,9 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 {
     __shared__ __attribute__((aligned(16))) uint8_t As[kGT * kGStride];
     __shared__ __attribute__((aligned(16))) uint8_t Bs[kGT * kGStride];
-    const int m0 = blockIdx.y * kGT, n0 = blockIdx.x * kGT;
+    // one-dimensional grid (the y dimension of a grid stops at 65535 blocks): tile = m-tile * tiles_n + n-tile
+    const int tiles_n = (N + kGT - 1) / kGT;
+    const int m0 = (int)(blockIdx.x / (unsigned)tiles_n) * kGT, n0 = (int)(blockIdx.x % (unsigned)tiles_n) * kGT;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int fr = lane & 15, fg = lane >> 4;
@@ -675,7 +677,7 @@ static void launch_generic(int M, int N, int K, const uint8_t* A, int64_t lda, c
                            const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
                            hipStream_t st)
 {
-    dim3 grid((N + kGT - 1) / kGT, (M + kGT - 1) / kGT);
+    const unsigned grid = (unsigned)((int64_t)((N + kGT - 1) / kGT) * ((M + kGT - 1) / kGT));
     gemm_generic_kernel<LAYOUT, FA, FB, GRAN><<<grid, 256, 0, st>>>(A, B, D, M, N, K, lda, ldb, ldd, isa, isb,
                                                                     amax_bits);
 }
@@ -740,6 +742,7 @@ extern "C" f8_status f8_gemm(f8_layout layout, int64_t M, int64_t N, int64_t K, 
         return F8_ERR_SHAPE;  // the kernels keep lane offsets inside a tile in 32 bits
     const int64_t a_cols = layout == F8_TN ? M : K, b_cols = layout == F8_NT ? K : N;
     if (lda < a_cols || ldb < b_cols || ldd < N) return F8_ERR_SHAPE;
+    if (((M + 63) / 64) * ((N + 63) / 64) > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;  // one block per 64x64 tile at most
     if (!aligned16(A) || !aligned16(B) || !aligned16(D_bf16)) return F8_ERR_ALIGN;
     if (g == F8_ROWWISE && !aligned16(inv_scale_b)) return F8_ERR_ALIGN;
     if (K == 0) {
