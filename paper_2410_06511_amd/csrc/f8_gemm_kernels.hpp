@@ -1,0 +1,714 @@
+// fp8 GEMM kernels for gfx950 (steps 4-6 of the Float8 linear: Y = X W^T,
+// dX = dY W, dW = dY^T X) (kernels and launch logic; f8_gemm.hip holds the entry point,
+// f8_gemm_inst_*.hip one operand-format pair each, so that they compile in parallel).
+//
+// Two kernels:
+//   gemm_nt_kernel      the fast path.  Both operands contraction-contiguous
+//                       ("NT"), K a multiple of 256.  Persistent workgroups,
+//                       global -> LDS direct loads (no VGPR staging), two LDS
+//                       stages of XOR-swizzled 128-byte rows,
+//                       v_mfma_f32_32x32x64_f8f6f4, scales folded into the
+//                       fp32 epilogue, bf16 stores staged through LDS.
+//   gemm_generic_kernel any layout, any multiple-of-16 shape; 64x64 tiles and
+//                       the 16x16x32 fp8 MFMA.  The fallback.
+//
+// In both, the MFMA's first operand is fed from the B matrix (n index) and the
+// second from the A matrix (m index): the accumulator registers of a lane then
+// hold four consecutive n for one m, so the bf16 results leave as 8-byte pieces
+// of a row of D.
+#pragma once
+#include <type_traits>
+#include <utility>
+
+#include "f8_device.hpp"
+#include "f8_host.hpp"
+
+namespace f8 {
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), unrolled at compile time
+template <int N, class F>
+__device__ inline void static_for(F&& f)
+{
+    [&]<int... Is>(std::integer_sequence<int, Is...>) { (f(std::integral_constant<int, Is>{}), ...); }
+    (std::make_integer_sequence<int, N>{});
+}
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------
+// epilogue helper: four fp32 accumulators -> four bf16 at D[m, n..n+3]
+// ---------------------------------------------------------------------------
+template <int GRAN>
+__device__ inline uint2 store4(uint16_t* __restrict__ D, int64_t ldd, int64_t m, int64_t n, v4f acc,
+                               float s_tensor, const float* __restrict__ isa,
+                               const float* __restrict__ isb)
+{
+    float r0, r1, r2, r3;
+    if constexpr (GRAN == F8_TENSORWISE) {
+        r0 = acc[0] * s_tensor, r1 = acc[1] * s_tensor, r2 = acc[2] * s_tensor, r3 = acc[3] * s_tensor;
+    } else {
+        const float sa = isa[m];
+        const float4 sb = *reinterpret_cast<const float4*>(isb + n);
+        r0 = (acc[0] * sa) * sb.x, r1 = (acc[1] * sa) * sb.y;
+        r2 = (acc[2] * sa) * sb.z, r3 = (acc[3] * sa) * sb.w;
+    }
+    uint2 o;
+    o.x = f32_to_bf16_bits(r0) | (f32_to_bf16_bits(r1) << 16);
+    o.y = f32_to_bf16_bits(r2) | (f32_to_bf16_bits(r3) << 16);
+    *reinterpret_cast<uint2*>(D + m * ldd + n) = o;
+    return o;
+}
+
+// amax of the bf16 output, kept as a bf16 magnitude in the upper half of a word so that the
+// unsigned integer order of the words is the order of the magnitudes; combined across
+// wavefronts with one atomic max per wavefront (the entry point zeroes the word first).
+__device__ inline uint32_t amax_pair(uint32_t acc, uint2 o)
+{
+    return pkmax(pkmax(acc, o.x & 0x7FFF7FFFu), o.y & 0x7FFF7FFFu);
+}
+// `red`: one word of LDS per wavefront, free for use.  Called by every thread of the block.
+// Same-address atomics from a thousand wavefronts serialise at the memory side, so the block
+// combines its wavefronts first and skips the atomic when the published value is already at
+// least as large (the value only ever grows, so a stale read costs one extra atomic, nothing else).
+template <int NW>
+__device__ inline void amax_publish(uint32_t acc, uint32_t* amax_bits, uint32_t* red)
+{
+    const uint32_t m = block_max_u32<NW>(pk_collapse(acc), red) << 16;
+    if (threadIdx.x == 0 && m > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, m);
+}
+
+// ---------------------------------------------------------------------------
+// Tile order: consecutive workgroup ids go round-robin to the 8 XCDs, each with
+// its own L2.  Give every XCD one contiguous run of logical tile ids, and walk
+// the tiles in bands of kGroupM tile-rows so that the 32 CUs of an XCD share A
+// rows and B rows.
+// ---------------------------------------------------------------------------
+constexpr int kXcds = 8;
+constexpr int kGroupM = 8;
+
+__device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, int* tn)
+{
+    const int total = tiles_m * tiles_n;
+    const int q = total / kXcds, r = total % kXcds;
+    const int xcd = pid % kXcds, idx = pid / kXcds;
+    const int logical = xcd * q + (xcd < r ? xcd : r) + idx;
+    const int band = kGroupM * tiles_n;
+    const int g = logical / band;
+    const int first_m = g * kGroupM;
+    const int gsz = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
+    const int in = logical % band;
+    *tm = first_m + in % gsz;
+    *tn = in / gsz;
+}
+
+// ---------------------------------------------------------------------------
+// fast NT kernel
+// ---------------------------------------------------------------------------
+// Persistent workgroups (one or two per CU) walk over BM x BN output tiles.  K
+// advances in steps of 128 bytes = one LDS stage of 128-byte rows (a full cache
+// line per row and load), two stages, filled by direct global->LDS loads.  Each
+// stage feeds two v_mfma_f32_32x32x64_f8f6f4 half-steps.  The load stream runs
+// two K steps ahead of the MFMAs and does not stop at tile boundaries, so the
+// next tile's first stages arrive while the current tile's epilogue runs.
+// Fragments of the next half-step are read from LDS into a second register set
+// while the MFMAs of the current one run; there are two barriers per K step (this stage is free
+// to refill; the other stage has landed), each with MFMAs queued in front of it.
+constexpr int kBK = 128;  // bytes of K per LDS stage
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float f2 __attribute__((ext_vector_type(2)));
+typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+
+// XOR swizzle of the eight 16-byte chunks of a 128-byte LDS row: the lanes that read the
+// same logical chunk of consecutive rows spread over all bank groups, for any aligned 8
+// rows (128-byte bank window) and any aligned 16 rows (256-byte window).
+__device__ inline int swz(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2); }
+
+// s_waitcnt immediate (gfx9 encoding: vmcnt[3:0] bits 3:0, vmcnt[5:4] bits 15:14, expcnt 6:4,
+// lgkmcnt 11:8): wait for all vector-memory operations and all LDS operations.
+constexpr int kWaitAllVmLgkm = 0x0070;
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN, bool AMAX = false>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ D, int M,
+    int N, int K, int64_t lda, int64_t ldb, int64_t ldd, const float* __restrict__ isa,
+    const float* __restrict__ isb, int tiles_m, int tiles_n, uint32_t* __restrict__ amax_bits = nullptr)
+{
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
+    constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
+    constexpr int A_BYTES = BM * kBK, STAGE = (BM + BN) * kBK;
+    constexpr int A_LOADS = BM / 8 / NW, B_LOADS = BN / 8 / NW;  // 1 KB (8 rows) per wave load
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
+    static_assert(NW == 4, "four waves");
+    constexpr int EP_STRIDE = 64 * 2 + 16;    // bytes per staged epilogue row: 64 bf16 + padding
+    static_assert(TN % 2 == 0, "the epilogue stages two MFMA tiles side by side");
+
+    // One array per stage: the compiler then knows that a load into one stage does not alias
+    // LDS reads of the other and does not serialise them.
+    __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE];
+    __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE];
+    __shared__ __attribute__((aligned(16))) uint8_t epb[NW * 32 * EP_STRIDE];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int total_tiles = tiles_m * tiles_n;
+    const int KT = K / kBK;
+
+    using std::integral_constant;
+    auto stage_ptr = [&](auto S) -> uint8_t* {
+        if constexpr (decltype(S)::value == 0) return st0;
+        else return st1;
+    };
+
+    // ---- load stream: (tile, K step) of the next stage to fetch -------------------------
+    // wave w fills rows [w*R, (w+1)*R) of each operand tile in 8-row (1 KB) pieces; lane i
+    // lands at row i/8, physical chunk i%8 of its piece.  Per tile only scalars change (tile
+    // origin, row limits); the lane's byte offset of a piece is rebuilt for every load from
+    // its row and chunk (three VALU operations), which is cheaper than carrying sixteen offsets
+    // in registers across the whole K loop.
+    int ld_tile = blockIdx.x;
+    const int a_row = wave * (BM / NW) + (lane >> 3);  // row of piece 0 in the A tile
+    const int b_row = wave * (BN / NW) + (lane >> 3);
+    // chunk terms: the swizzle of row + 8 * j differs from that of row only for odd j (bit 2)
+    const uint32_t a_c0 = 16 * ((lane & 7) ^ swz(a_row)), a_c1 = 16 * ((lane & 7) ^ swz(a_row + 8));
+    const uint32_t b_c0 = 16 * ((lane & 7) ^ swz(b_row)), b_c1 = 16 * ((lane & 7) ^ swz(b_row + 8));
+    static_assert((BM / NW) % 16 == 0 && (BN / NW) % 16 == 0, "swizzle period");
+    const uint8_t* a_base = A;
+    const uint8_t* b_base = B;
+    int a_rmax = 0, b_rmax = 0;  // last valid row of the current load tile, relative to its origin
+    auto load_context = [&](int tile) {
+        int tm, tn;
+        tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
+        a_base = A + (int64_t)tm * BM * lda;
+        b_base = B + (int64_t)tn * BN * ldb;
+        a_rmax = M - 1 - tm * BM;  // rows past the edge re-read the last row; never stored
+        b_rmax = N - 1 - tn * BN;
+    };
+    // Load number `idx` (0 .. LOADS-1: first the A pieces, then the B pieces) of K step `kt` of
+    // the stream's current tile, into stage S.  Written as asm: 32-bit lane offset next to a
+    // scalar base, LDS target in M0.  The compiler therefore does not see these as LDS writes;
+    // ordering against the LDS reads is by the barriers and explicit waits of kstep.
+    auto issue_one = [&](int kt, auto S, auto IDX) {
+        constexpr int idx = decltype(IDX)::value;
+        if constexpr (idx < A_LOADS) {
+            const uint8_t* gp = a_base + (int64_t)kt * kBK;
+            uint8_t* lp = stage_ptr(S) + wave * (BM / NW) * kBK + idx * 1024;
+            const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
+            int r = a_row + 8 * idx;
+            r = r < a_rmax ? r : a_rmax;
+            const uint32_t o = (uint32_t)r * (uint32_t)lda + ((idx & 1) ? a_c1 : a_c0);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
+        } else {
+            constexpr int j = idx - A_LOADS;
+            const uint8_t* gp = b_base + (int64_t)kt * kBK;
+            uint8_t* lp = stage_ptr(S) + A_BYTES + wave * (BN / NW) * kBK + j * 1024;
+            const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
+            int r = b_row + 8 * j;
+            r = r < b_rmax ? r : b_rmax;
+            const uint32_t o = (uint32_t)r * (uint32_t)ldb + ((j & 1) ? b_c1 : b_c0);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
+        }
+    };
+    auto issue_all = [&](int kt, auto S) { static_for<A_LOADS + B_LOADS>([&](auto L) { issue_one(kt, S, L); }); };
+    // Move the load stream to this workgroup's next tile.  Past the last tile the stream
+    // stays where it is: the same K steps are fetched again into stages nobody reads, so that
+    // every K step issues the same number of loads and the wait counts below hold throughout.
+    auto next_load_tile = [&]() {
+        ld_tile += gridDim.x;
+        if (ld_tile < total_tiles) load_context(ld_tile);
+    };
+
+    // ---- LDS -> register addressing: lane reads row (l % 32) of a 32-row MFMA tile; in
+    // half-step h the logical chunks 4h + 2g and 4h + 2g + 1 (g = l / 32): 32 K bytes.
+    const int fr = lane & 31, fg = lane >> 5;
+    const int pc0 = (2 * fg) ^ swz(fr);
+    const int a_rd = (wm * WM + fr) * kBK + 16 * pc0;  // + 32-row tile * 4096
+    const int b_rd = A_BYTES + (wn * WN + fr) * kBK + 16 * pc0;
+    const int flip1 = ((pc0 ^ 1) - pc0) * 16;          // to the second chunk of the pair
+    const int fliph = ((pc0 ^ 4) - pc0) * 16;          // to the same chunk of half-step 1
+
+    struct Frags {
+        v8i a[TM];
+        v8i b[TN];
+    };
+    // fragment number `idx` of a half-step: 0 .. TM-1 are the A fragments, TM .. TM+TN-1 the B ones
+    auto read_frag = [&](Frags& f, auto S, auto H, auto IDX) {
+        constexpr int idx = decltype(IDX)::value;
+        const int hoff = decltype(H)::value ? fliph : 0;
+        if constexpr (idx < TM) {
+            const uint8_t* sa = stage_ptr(S) + a_rd + hoff + idx * 32 * kBK;
+            const int4 lo = *reinterpret_cast<const int4*>(sa);
+            const int4 hi = *reinterpret_cast<const int4*>(sa + flip1);
+            f.a[idx] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        } else {
+            const uint8_t* sb = stage_ptr(S) + b_rd + hoff + (idx - TM) * 32 * kBK;
+            const int4 lo = *reinterpret_cast<const int4*>(sb);
+            const int4 hi = *reinterpret_cast<const int4*>(sb + flip1);
+            f.b[idx - TM] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+        }
+    };
+    auto read_frags = [&](Frags& f, auto S, auto H) {
+        static_for<TM + TN>([&](auto F) { read_frag(f, S, H, F); });
+    };
+
+    uint32_t amax_acc = 0;  // AMAX: largest |bf16 output| this wavefront has produced (packed pairs)
+    v16f acc[TM][TN];
+    auto zero_acc = [&]() {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    };
+
+    // MFMAs number lo..hi-1 of a half-step (numbered i * TN + j)
+    auto mfmas = [&](const Frags& f, auto LO, auto HI) {
+#pragma unroll
+        for (int q = decltype(LO)::value; q < decltype(HI)::value; ++q) {
+            const int i = q / TN, j = q % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.b[j], f.a[i], acc[i][j], FB, FA, 0, 0,
+                                                                          0, 0);
+        }
+    };
+    constexpr int NMFMA = TM * TN;
+    using I0 = integral_constant<int, 0>;
+    using I1 = integral_constant<int, 1>;
+
+    // ---- epilogue of one tile.  Of each 32x32 MFMA tile, lane l holds m = l % 32 and
+    // n = 8 * (r / 4) + 4 * (l / 32) + r % 4 for accumulator register r.  Each wave turns a
+    // 32-row, 64-column piece of its tile at a time into bf16, parks it in its private piece
+    // of LDS and writes it out as 16-byte row pieces: every global store instruction then
+    // covers whole 128-byte row segments.
+    auto epilogue = [&](int tile) {
+        int tm, tn;
+        tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
+        const int m0 = tm * BM + wm * WM, n0 = tn * BN + wn * WN;  // of this wave's tile
+        uint8_t* ep = epb + wave * (32 * EP_STRIDE);
+        float s_tensor = 0.f;
+        if constexpr (GRAN == F8_TENSORWISE) s_tensor = isa[0] * isb[0];
+        // A lane stores four 16-byte pieces per pass: rows 8 t + lane / 8 of the 32-row band,
+        // columns 8 * (lane % 8) .. +7 of the 64-column pass: uniform base + 32-bit lane offset.
+        uint8_t* dbase = reinterpret_cast<uint8_t*>(D + (int64_t)m0 * ldd + n0);
+        const uint32_t ldd_b = (uint32_t)ldd * 2;
+        const uint32_t voff = (uint32_t)(lane >> 3) * ldd_b + (uint32_t)(lane & 7) * 16;
+        const bool interior = tm * BM + BM <= M && tn * BN + BN <= N;  // no edge checks needed
+
+        auto run = [&](auto INTERIOR) {
+            // One pass = rows 32 i .. 32 i + 31, columns 32 jp .. 32 jp + 63 of the wave's tile.
+            // Tensorwise: row bands outermost.  Per-row / per-column scales: column pairs
+            // outermost, so that the eight 4-float pieces of the column scales a lane needs are
+            // loaded once per column pair (and the row scales once per tile) instead of in every
+            // pass, where their latency would sit in front of each conversion.
+            constexpr int NP = TM * (TN / 2);
+            float sav[TM];
+            float4 sbv[8];
+            if constexpr (GRAN != F8_TENSORWISE) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    const int m_lane = m0 + 32 * i + fr;
+                    sav[i] = isa[m_lane < M ? m_lane : M - 1];
+                }
+            }
+            static_for<NP>([&](auto P) {
+                constexpr int p = decltype(P)::value;
+                constexpr int i = GRAN == F8_TENSORWISE ? p / (TN / 2) : p % TM;
+                constexpr int jp = GRAN == F8_TENSORWISE ? (p % (TN / 2)) * 2 : (p / TM) * 2;
+                if constexpr (GRAN != F8_TENSORWISE && i == 0) {
+#pragma unroll
+                    for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            int n = n0 + 32 * jp + 32 * jj + 8 * q + 4 * fg;
+                            n = n < N ? n : N - 4;
+                            sbv[jj * 4 + q] = *reinterpret_cast<const float4*>(isb + n);
+                        }
+                }
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = jp + jj;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int nl = 32 * jj + 8 * q + 4 * fg;  // column inside the pass
+                        f2 lo, hi;
+                        if constexpr (GRAN == F8_TENSORWISE) {
+                            lo = f2{acc[i][j][4 * q] * s_tensor, acc[i][j][4 * q + 1] * s_tensor};
+                            hi = f2{acc[i][j][4 * q + 2] * s_tensor, acc[i][j][4 * q + 3] * s_tensor};
+                        } else {
+                            const float sa = sav[i];
+                            const float4 sb = sbv[jj * 4 + q];
+                            lo = f2{(acc[i][j][4 * q] * sa) * sb.x, (acc[i][j][4 * q + 1] * sa) * sb.y};
+                            hi = f2{(acc[i][j][4 * q + 2] * sa) * sb.z, (acc[i][j][4 * q + 3] * sa) * sb.w};
+                        }
+                        // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
+                        uint2 o;
+                        o.x = __builtin_bit_cast(uint32_t, __builtin_convertvector(lo, b2));
+                        o.y = __builtin_bit_cast(uint32_t, __builtin_convertvector(hi, b2));
+                        if constexpr (AMAX) {
+                            // edge tiles hold results of re-read rows past M / N: not output
+                            bool counted = true;
+                            if constexpr (!decltype(INTERIOR)::value)
+                                counted = m0 + 32 * i + fr < M && n0 + 32 * jp + nl < N;
+                            if (counted) amax_acc = amax_pair(amax_acc, o);
+                        }
+                        *reinterpret_cast<uint2*>(ep + fr * EP_STRIDE + nl * 2) = o;
+                    }
+                }
+                uint8_t* pbase = dbase + ((int64_t)(32 * i) * ldd + 32 * jp) * 2;  // uniform
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int idx = t * 64 + lane;
+                    const uint4 v = *reinterpret_cast<const uint4*>(ep + (idx >> 3) * EP_STRIDE + (idx & 7) * 16);
+                    bool ok = true;
+                    if constexpr (!decltype(INTERIOR)::value)
+                        ok = m0 + 32 * i + (idx >> 3) < M && n0 + 32 * jp + (idx & 7) * 8 < N;
+                    // Streaming store: D is not read again by this library, and lines that
+                    // linger dirty in the L2 / Infinity Cache would be written back during the
+                    // next, bandwidth-bound kernel instead of during this compute-bound one.
+                    typedef unsigned int u4v __attribute__((ext_vector_type(4)));
+                    if (ok)
+                        __builtin_nontemporal_store(u4v{v.x, v.y, v.z, v.w},
+                                                    reinterpret_cast<u4v*>(pbase + (voff + (uint32_t)(8 * t) * ldd_b)));
+                }
+                // one pass at a time: measured faster than letting the compiler interleave passes
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        };
+        if (interior)
+            run(std::true_type{});
+        else
+            run(std::false_type{});
+    };
+
+    // ---- prologue: two stages in flight, first half-step into registers ----------------
+    load_context(ld_tile);  // the grid never exceeds the tile count
+    issue_all(0, I0{});
+    issue_all(1, I1{});
+    Frags f0, f1;
+    zero_acc();
+    __builtin_amdgcn_s_waitcnt(kWaitAllVmLgkm);
+    __syncthreads();
+    read_frags(f0, I0{}, I0{});
+
+    // One K step out of stage S = 2 * NMFMA MFMA slots, in a fixed order (every slot ends with a
+    // scheduling fence).  On entry f0 holds the fragments of the first half-step.
+    //   slots [0, NF):        + LDS reads of the second half-step's fragments (stage S) into f1
+    //   after slot SYNC_A-1:  barrier: every wave is done reading stage S
+    //   slots [SYNC_A, ...):  + the loads that refill stage S with the stream's next K step,
+    //                         at most one per slot and with gaps: a wave's load blocks its
+    //                         instruction issue until the CU's address unit accepts it (16 cycles
+    //                         per 1 KB load, shared by the four waves), so bunched loads would
+    //                         starve the matrix pipe
+    //   after slot SYNC_B-1:  wait until only this step's PRE_B loads are in flight (the
+    //                         previous step's have then landed), barrier: the other stage is
+    //                         complete for every wave
+    //   slots [2*NMFMA-NF, 2*NMFMA): + LDS reads of the next K step's first fragments into f0
+    // The MFMAs issued just before a barrier keep the matrix pipe busy while the wave waits.
+    constexpr int NF = TM + TN;                       // fragments per half-step
+    constexpr int SLOTS = 2 * NMFMA;
+    // f1's fragment reads are spread over slots [0, F1_SPAN), f0's over [SYNC_B, SLOTS).  The two
+    // tunables (for the 16-MFMA half-steps of the 256x256 tile) were chosen by measurement.
+#ifndef F8_SCHED_COVER
+#define F8_SCHED_COVER 2
+#endif
+#ifndef F8_SCHED_F0_SPAN
+#define F8_SCHED_F0_SPAN 12
+#endif
+    constexpr int F1_SPAN = NF < NMFMA / 2 ? NF : NMFMA / 2;
+    constexpr int F0_SPAN = NMFMA >= 16 ? F8_SCHED_F0_SPAN : F1_SPAN;
+    constexpr int SYNC_A = F1_SPAN + (NMFMA >= 16 ? F8_SCHED_COVER : 1);
+    constexpr int SYNC_B = SLOTS - F0_SPAN;
+    constexpr auto f1_slot = [](int n) { return n * F1_SPAN / NF; };            // fragment n (in read order)
+    constexpr auto f0_slot = [](int n) { return SYNC_B + n * F0_SPAN / NF; };
+    constexpr int LOADS = A_LOADS + B_LOADS;
+    constexpr int LOAD_SLOTS = SLOTS - SYNC_A;
+    static_assert(SYNC_A <= SYNC_B && LOAD_SLOTS > 0, "schedule does not fit");
+    // load l goes into slot SYNC_A + floor(l * LOAD_SLOTS / LOADS): evenly spread
+    constexpr auto slot_of_load = [](int l) { return SYNC_A + l * LOAD_SLOTS / LOADS; };
+    constexpr int PRE_B = [&] {
+        int n = 0;
+        for (int l = 0; l < LOADS; ++l) n += slot_of_load(l) < SYNC_B;
+        return n;
+    }();
+    // i-major MFMA order needs fragments in the order a0, b0 .. b(TN-1), a1 .. a(TM-1)
+    constexpr auto frag_order = [](int n) { return n == 0 ? 0 : (n <= TN ? TM + n - 1 : n - TN); };
+    // s_waitcnt vmcnt(PRE_B) lgkmcnt(0)
+    constexpr int kWaitB = (PRE_B & 15) | ((PRE_B >> 4) << 14) | 0x0070;
+
+    auto kstep = [&](auto S, int fetch_kt) {
+        constexpr int s = decltype(S)::value;
+        static_for<SLOTS>([&](auto SLOT) {
+            constexpr int slot = decltype(SLOT)::value;
+            if constexpr (slot == SYNC_A) {
+                __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0): my reads of stage S are back
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (slot == SYNC_B) {
+                __builtin_amdgcn_s_waitcnt(kWaitB);
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if constexpr (slot < NMFMA)
+                mfmas(f0, SLOT, integral_constant<int, slot + 1>{});
+            else
+                mfmas(f1, integral_constant<int, slot - NMFMA>{}, integral_constant<int, slot - NMFMA + 1>{});
+            static_for<NF>([&](auto F) {
+                constexpr int n = decltype(F)::value;
+                if constexpr (f1_slot(n) == slot) read_frag(f1, S, I1{}, integral_constant<int, frag_order(n)>{});
+                if constexpr (f0_slot(n) == slot)
+                    read_frag(f0, integral_constant<int, 1 - s>{}, I0{}, integral_constant<int, frag_order(n)>{});
+            });
+            static_for<LOADS>([&](auto L) {
+                if constexpr (slot_of_load(decltype(L)::value) == slot) issue_one(fetch_kt, S, L);
+            });
+            __builtin_amdgcn_sched_barrier(0);
+        });
+    };
+
+    // ---- main loop over this workgroup's tiles.  KT is even, so every tile starts in stage 0.
+    // The step computed at kt fetches step kt + 2; the last two steps of a tile fetch the first
+    // two of the next tile.
+    for (int tile = blockIdx.x; tile < total_tiles; tile += gridDim.x) {
+        // Retire every earlier vector-memory operation (the previous tile's stores, register
+        // spills) once per tile.  Otherwise the compiler, which must protect the data
+        // registers of pending stores, places its own full wait inside the K loop, where it
+        // would also wait for the freshly issued loads on every step.  The loads in flight
+        // here are this tile's first two K steps, requested a whole epilogue ago.
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        for (int kt = 0; kt < KT; kt += 2) {
+            if (kt == KT - 2) next_load_tile();  // the last two steps fetch the next tile's first two
+            const int f = kt == KT - 2 ? 0 : kt + 2;
+            kstep(I0{}, f);
+            kstep(I1{}, f + 1);
+        }
+        epilogue(tile);
+        zero_acc();
+        // The next tile's first fragments are read again here rather than kept in registers
+        // across the epilogue (the last K step already fetched them once): 64 registers less
+        // for the epilogue to fight over.  Stage 0 is complete since that step's second barrier.
+        read_frags(f0, I0{}, I0{});
+    }
+    // no load may still be writing LDS when the workgroup ends
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    if constexpr (AMAX) {
+        __syncthreads();  // every wave is past its last epilogue pass: the staging buffer is free
+        amax_publish<NW>(amax_acc, amax_bits, reinterpret_cast<uint32_t*>(epb));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// generic kernel: 64x64 tile, 4 waves of 32x32, K step 64, 16x16x32 MFMA
+// ---------------------------------------------------------------------------
+template <int FOP_A, int FOP_B>  // formats of the MFMA's first / second operand
+__device__ inline v4f mfma32(long a, long b, v4f c)
+{
+    if constexpr (FOP_A == F8_E4M3 && FOP_B == F8_E4M3) return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a, b, c, 0, 0, 0);
+    else if constexpr (FOP_A == F8_E4M3 && FOP_B == F8_E5M2) return __builtin_amdgcn_mfma_f32_16x16x32_fp8_bf8(a, b, c, 0, 0, 0);
+    else if constexpr (FOP_A == F8_E5M2 && FOP_B == F8_E4M3) return __builtin_amdgcn_mfma_f32_16x16x32_bf8_fp8(a, b, c, 0, 0, 0);
+    else return __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(a, b, c, 0, 0, 0);
+}
+
+constexpr int kGT = 64;        // generic tile (rows and K bytes)
+constexpr int kGStride = 80;   // LDS row stride in bytes (64 + 16 pad, keeps 16-byte alignment)
+
+// Fill a 64 x 64 (rows x K) LDS tile from an operand stored either [rows, K] (KCONTIG) or [K, rows].
+template <bool KCONTIG>
+__device__ inline void generic_load(uint8_t* __restrict__ tile, const uint8_t* __restrict__ P, int64_t ld,
+                                    int row0, int nrows, int k0, int K)
+{
+    const int t = threadIdx.x;
+    if constexpr (KCONTIG) {
+        const int r = t >> 2, c = (t & 3) * 16;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (row0 + r < nrows && k0 + c < K)  // K is a multiple of 16: whole chunk in or out
+            v = *reinterpret_cast<const uint4*>(P + (int64_t)(row0 + r) * ld + k0 + c);
+        *reinterpret_cast<uint4*>(tile + r * kGStride + c) = v;
+    } else {
+        const int k = t >> 2, c = (t & 3) * 16;  // 16 consecutive rows of the tile at one k
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (k0 + k < K && row0 + c < nrows)
+            v = *reinterpret_cast<const uint4*>(P + (int64_t)(k0 + k) * ld + row0 + c);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) tile[(c + i) * kGStride + k] = (uint8_t)(w[i >> 2] >> (8 * (i & 3)));
+    }
+}
+
+template <int LAYOUT, int FA, int FB, int GRAN>
+__global__ __launch_bounds__(256) void gemm_generic_kernel(
+    const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ D, int M,
+    int N, int K, int64_t lda, int64_t ldb, int64_t ldd, const float* __restrict__ isa,
+    const float* __restrict__ isb, uint32_t* __restrict__ amax_bits)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t As[kGT * kGStride];
+    __shared__ __attribute__((aligned(16))) uint8_t Bs[kGT * kGStride];
+    // one-dimensional grid (the y dimension of a grid stops at 65535 blocks): tile = m-tile * tiles_n + n-tile
+    const int tiles_n = (N + kGT - 1) / kGT;
+    const int m0 = (int)(blockIdx.x / (unsigned)tiles_n) * kGT, n0 = (int)(blockIdx.x % (unsigned)tiles_n) * kGT;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int fr = lane & 15, fg = lane >> 4;
+
+    v4f acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    for (int k0 = 0; k0 < K; k0 += kGT) {
+        __syncthreads();
+        generic_load<LAYOUT != F8_TN>(As, A, lda, m0, M, k0, K);
+        generic_load<LAYOUT == F8_NT>(Bs, B, ldb, n0, N, k0, K);
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < kGT; ks += 32) {
+            long af[2], bf[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                af[i] = *reinterpret_cast<const long*>(As + (wm * 32 + 16 * i + fr) * kGStride + ks + 8 * fg);
+                bf[i] = *reinterpret_cast<const long*>(Bs + (wn * 32 + 16 * i + fr) * kGStride + ks + 8 * fg);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = mfma32<FB, FA>(bf[j], af[i], acc[i][j]);
+        }
+    }
+    float s_tensor = 0.f;
+    if constexpr (GRAN == F8_TENSORWISE) s_tensor = isa[0] * isb[0];
+    uint32_t amax_acc = 0;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int m = m0 + wm * 32 + 16 * i + fr;
+        if (m >= M) continue;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn * 32 + 16 * j + 4 * fg;
+            if (n < N) amax_acc = amax_pair(amax_acc, store4<GRAN>(D, ldd, m, n, acc[i][j], s_tensor, isa, isb));
+        }
+    }
+    if (amax_bits) {  // uniform branch; every thread of the block takes part
+        __syncthreads();
+        amax_publish<4>(amax_acc, amax_bits, reinterpret_cast<uint32_t*>(As));
+    }
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN>
+static void launch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                      const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                      int max_blocks, hipStream_t st)
+{
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int total = tiles_m * tiles_n;
+    const int grid = total < max_blocks ? total : max_blocks;
+    if (amax_bits)
+        gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN, true><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
+            A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tiles_m, tiles_n, amax_bits);
+    else
+        gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN, false><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
+            A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tiles_m, tiles_n, nullptr);
+}
+
+static int cu_count()
+{
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+        n = 256;
+    return n - n % kXcds;  // the persistent tile order assumes a multiple of the XCD count
+}
+
+template <int FA, int FB, int GRAN>
+static void dispatch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                        const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                        hipStream_t st)
+{
+    // Tile configuration by estimated time, in units of one 256x256 tile's time on one compute
+    // unit: T tiles on `cus` persistent workgroups take ceil(T / cus) rounds; a 256x128 tile costs
+    // about 0.63 and a 128x128 tile about 0.58 of a 256x256 one (measured: their wave tiles need
+    // more LDS bytes per MFMA).  Ties go to the larger tile.
+    const int cus = cu_count();
+    auto tiles = [&](int bm, int bn) { return (int64_t)((M + bm - 1) / bm) * ((N + bn - 1) / bn); };
+    auto rounds = [&](int64_t t) { return (double)((t + cus - 1) / cus); };
+    constexpr double kHalfTile = 0.63, kQuarterTile = 0.58;
+    const int tm = (M + 255) / 256, tn = (N + 255) / 256;
+    const int64_t T = (int64_t)tm * tn, whole = T / cus * cus, rest = T - whole;
+    // Wave quantisation: a last round with at most half of the workgroups busy (e.g. 896 tiles =
+    // 3.5 rounds) costs a whole one.  Then the whole rounds are launched on their own sub-matrix
+    // (a range of tile rows or tile columns holding exactly `whole` tiles) and the rest with
+    // 256x128 tiles: twice as many, still at most one per workgroup.
+    const bool split_rows = whole > 0 && rest > 0 && 2 * rest <= cus && whole % tn == 0;
+    const bool split_cols = !split_rows && whole > 0 && rest > 0 && 2 * rest <= cus && whole % tm == 0;
+    const double c_full = (split_rows || split_cols) ? (double)(whole / cus) + kHalfTile : rounds(T);
+    const double c_half = rounds(tiles(256, 128)) * kHalfTile;
+    const double c_quarter = rounds(tiles(128, 128)) * kQuarterTile;
+    const bool rw = GRAN != F8_TENSORWISE;
+    if (c_full <= c_half && c_full <= c_quarter) {
+        if (split_rows) {
+            const int m1 = (int)(whole / tn) * 256;
+            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(m1, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+            launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M - m1, N, K, A + (int64_t)m1 * lda, lda, B, ldb, rw ? isa + m1 : isa,
+                                                    isb, D + (int64_t)m1 * ldd, ldd, amax_bits, cus, st);
+        } else if (split_cols) {
+            const int n1 = (int)(whole / tm) * 256;
+            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, n1, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+            launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N - n1, K, A, lda, B + (int64_t)n1 * ldb, ldb, isa,
+                                                    rw ? isb + n1 : isb, D + n1, ldd, amax_bits, cus, st);
+        } else {
+            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+        }
+    } else if (c_half <= c_quarter) {
+        launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+    } else {
+        // LDS allows two 128x128 workgroups per compute unit
+        launch_nt<128, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, 2 * cus, st);
+    }
+}
+
+template <int LAYOUT, int FA, int FB, int GRAN>
+static void launch_generic(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                           const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                           hipStream_t st)
+{
+    const unsigned grid = (unsigned)((int64_t)((N + kGT - 1) / kGT) * ((M + kGT - 1) / kGT));
+    gemm_generic_kernel<LAYOUT, FA, FB, GRAN><<<grid, 256, 0, st>>>(A, B, D, M, N, K, lda, ldb, ldd, isa, isb,
+                                                                    amax_bits);
+}
+
+template <int FA, int FB, int GRAN>
+static void dispatch_layout(int layout, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B,
+                            int64_t ldb, const float* isa, const float* isb, uint16_t* D, int64_t ldd,
+                            uint32_t* amax_bits, hipStream_t st)
+{
+    if (layout == F8_NT) {
+        if (K % (2 * kBK) == 0 && K > 0)  // the fast kernel alternates two LDS stages per tile
+            dispatch_nt<FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+        else
+            launch_generic<F8_NT, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+    } else if (layout == F8_NN) {
+        launch_generic<F8_NN, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+    } else {
+        launch_generic<F8_TN, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+    }
+}
+
+// All launches of one operand-format pair: granularity and layout are run-time choices.
+template <int FA, int FB>
+static void gemm_formats(int layout, int g, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B,
+                         int64_t ldb, const float* isa, const float* isb, uint16_t* D, int64_t ldd,
+                         uint32_t* amax_bits, hipStream_t st)
+{
+    if (g == F8_TENSORWISE)
+        dispatch_layout<FA, FB, F8_TENSORWISE>(layout, M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+    else
+        dispatch_layout<FA, FB, F8_ROWWISE>(layout, M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+}
+
+}  // namespace f8
