@@ -85,3 +85,14 @@ def test_binding_raises_with_message():
     with pytest.raises(f8.F8Error) as e:
         f8._check(5)
     assert "workspace" in str(e.value)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    """There is no fallback path: without the built HIP library every call raises."""
+    monkeypatch.setattr(f8, "_lib", None)
+    monkeypatch.setattr(f8, "LIB_PATH", "/nonexistent/libf8.so")
+    import pytest
+    with pytest.raises(RuntimeError, match="is missing"):
+        f8.lib()
+    with pytest.raises(RuntimeError, match="is missing"):
+        f8.workspace_bytes(16, 16)
