@@ -342,8 +342,36 @@ def ffn_main(args, w):
     Xn, gw = torch.empty((M, D), **bf), torch.ones(D, **bf)
     stream = torch.cuda.current_stream()
 
+    delayed = args.scaling == "delayed"
+    if args.scaling == "static":
+        print("bench.py: the feed-forward chain runs with dynamic or delayed scaling", file=sys.stderr)
+        sys.exit(2)
+    if delayed:
+        # delayed scaling: every scale is known beforehand, so the glue is fused into the cast of
+        # w2's input (h is never written) and no amax has to be handed over
+        st13, st2 = f8.ScalingState(f8.DELAYED, 16), f8.ScalingState(f8.DELAYED, 16)
+        calls = [
+            ("rmsnorm", lambda: f8.rmsnorm(X, gw, 1e-5, Xn, None, None, None, stream), 0, 4 * M * D),
+            ("linear w13 fwd", lambda: f8.linear_fwd_scaled(d13, st13, Xn, W13, AB, s13, ws, stream), 2 * M * D * 2 * H, 0),
+            ("silu_mul fused into the cast of h", lambda: f8.silu_mul_quantise_delayed(AB, f8.E4M3, st2.hist_x, st2.scale_x, s2.x, ws, stream), 0, 6 * M * H),
+            ("linear w2 fwd (input already quantised)", lambda: f8.linear_fwd_xq(d2, st2, W2, Y, s2, ws, stream), 2 * M * H * D, 0),
+            ("linear w2 bwd", lambda: f8.linear_bwd_scaled(d2, st2, dY, s2, dH, dW2, ws, stream), 4 * M * H * D, 0),
+            ("silu_mul_bwd", lambda: f8.silu_mul_bwd(AB, dH, dAB, None, None, stream), 0, 10 * M * H),
+            ("linear w13 bwd", lambda: f8.linear_bwd_scaled(d13, st13, dAB, s13, dX, dW13, ws, stream), 4 * M * D * 2 * H, 0),
+        ]
+        # seed the histories with one dynamic pass (the first-step initialisation)
+        a = torch.empty(1, device="cuda")
+        f8.rmsnorm(X, gw, 1e-5, Xn, None, None, None, stream)
+        f8.linear_fwd_chained(d13, Xn, None, W13, AB, None, s13, ws, stream)
+        f8.silu_mul(AB, Hh, a_h, ws, stream)
+        f8.linear_fwd_chained(d2, Hh, a_h, W2, Y, None, s2, ws, stream)
+        f8.linear_bwd_chained(d2, dY, None, s2, dH, None, dW2, ws, stream)
+        f8.silu_mul_bwd(AB, dH, dAB, a_dab, ws, stream)
+        for stt, key, src, fmt in ((st13, "x", s13.x.amax, f8.E4M3), (st13, "w", s13.w.amax, f8.E4M3), (st13, "dy", a_dab, f8.E4M3),
+                                   (st2, "x", a_h, f8.E4M3), (st2, "w", s2.w.amax, f8.E4M3), (st2, "dy", s2.dy.amax, f8.E4M3)):
+            f8.amax_history_push(getattr(stt, "hist_" + key), src, fmt, getattr(stt, "scale_" + key), None, stream)
     # (name, call, linear flop, algorithmic bytes of a glue kernel)
-    calls = [
+    calls = calls if delayed else [
         ("rmsnorm", lambda: f8.rmsnorm(X, gw, 1e-5, Xn, None, a_xn, ws, stream), 0, 4 * M * D),
         ("linear w13 fwd", lambda: f8.linear_fwd_chained(d13, Xn, a_xn, W13, AB, None, s13, ws, stream), 2 * M * D * 2 * H, 0),
         ("silu_mul", lambda: f8.silu_mul(AB, Hh, a_h, ws, stream), 0, 6 * M * H),
@@ -385,6 +413,8 @@ def ffn_main(args, w):
         if by:
             leg["gbs"] = round(by / (ms * 1e-3) / 1e9, 1)
             leg["bytes_per_elem"] = by // (M * D if name == "rmsnorm" else M * H)
+            if name.startswith("silu_mul fused"):
+                leg["note"] = "reads [a | b] (4 B), writes the codes of h in both orientations (2 B); replaces silu_mul (6 B) + the cast of h (4 B)"
         legs.append(leg)
     glue_ms = sum(l["ms"] for l in legs if "gbs" in l)
     glue_bytes = sum(by for _, _, _, by in calls)
@@ -395,7 +425,7 @@ def ffn_main(args, w):
         "dtype": "fp8 (e4m3) x fp8 -> fp32 accumulate -> bf16", "data": "synthetic",
         "config": {"workload": f"{w.key}: chained feed-forward block, M={M}, hidden {D}, FFN {H}: "
                                "rmsnorm -> w1|w3 stacked [N=2*FFN] -> silu(a)*b -> w2, and the backward of the three linear stages",
-                   "scaling_granularity": "tensorwise", "scaling_strategy": "dynamic", "grad_format": "e4m3",
+                   "scaling_granularity": "tensorwise", "scaling_strategy": args.scaling, "grad_format": "e4m3",
                    "chained": True, "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
         "roofline": {"kernel": "rmsnorm_kernel + silu_mul_kernel + silu_mul_bwd_kernel (the glue; the GEMM figures "

@@ -347,6 +347,32 @@ f8_status f8_rmsnorm(const void* x_bf16, const void* g_bf16, int64_t M, int64_t 
                      void* y_bf16, float* rstd, float* amax_y, void* workspace,
                      size_t workspace_bytes, void* stream);
 
+/*
+ * The feed-forward glue fused into the cast of its consumer, for delayed
+ * scaling (where the scale is known before the tensor exists; this is the kind
+ * of producer/cast fusion the paper gets from torch.compile): from ab [M, 2H]
+ * = [a | b] it forms h = bf16(silu(a) * b) in registers and writes only its fp8
+ * codes: q->q [M, H], q->q_t [H, M], cast with scale[0]; q->scale / inv_scale
+ * receive the scale used, q->amax the amax of h, which is then pushed into
+ * history (f8_amax_history_push) and scale[0] becomes the next step's scale.
+ * Same results as f8_silu_mul followed by the delayed-scaling quantisation of
+ * h, without writing and re-reading h.  workspace: f8_workspace_bytes(M, H).
+ */
+f8_status f8_silu_mul_quantise_delayed(const void* ab_bf16, int64_t M, int64_t H, f8_format fmt,
+                                       float* history, int64_t history_len, float* scale,
+                                       const f8_qtensor* q, void* workspace, size_t workspace_bytes,
+                                       void* stream);
+
+/*
+ * Forward of the linear whose input is already quantised in saved->x (codes in
+ * both orientations, scale, inv_scale; e.g. by f8_silu_mul_quantise_delayed):
+ * quantises W [N,K] as state->mode says (the w members of the state; for
+ * F8_DYNAMIC they are unused), then Y = X8 W8^T.  Tensorwise only.
+ */
+f8_status f8_linear_fwd_xq(const f8_linear_desc* d, const f8_scaling_state* state, const void* W,
+                           void* Y, f8_saved* saved, void* workspace, size_t workspace_bytes,
+                           void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -389,7 +389,10 @@ __device__ inline void transpose4x4(const uint32_t r[4], uint32_t c[4])
 // MEASURE (delayed scaling): the scale is given, and the block also writes the largest
 // magnitude of its own tile to partial_out[blockIdx.x], so that the tensor's amax of this step
 // comes out of the same single pass over x.
-template <int FMT, int GRAN, bool DYN, bool OUT, bool OUT_T, bool MEASURE = false>
+// SILU (with MEASURE): x is the output [rows, 2 * cols] = [a | b] of a stacked w1|w3 linear (ld = its
+// row length) and the tensor that is cast is h = bf16(silu(a) * b), formed in registers: the
+// feed-forward glue fused into the cast of its consumer, h itself is never written.
+template <int FMT, int GRAN, bool DYN, bool OUT, bool OUT_T, bool MEASURE = false, bool SILU = false>
 __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ld,
     const float* __restrict__ scale, const uint32_t* __restrict__ partial, int npartial,
@@ -429,8 +432,14 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
         // the caches only push out the codes that the GEMM reads next.
         typedef unsigned int u4v __attribute__((ext_vector_type(4)));
         if (col_ok && r < rows) {
-            const u4v t = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(x + r * ld + col));
-            v[i] = make_uint4(t.x, t.y, t.z, t.w);
+            if constexpr (SILU) {
+                const uint4 a = *reinterpret_cast<const uint4*>(x + r * ld + col);   // read again by the backward
+                const uint4 b = *reinterpret_cast<const uint4*>(x + r * ld + cols + col);
+                v[i] = make_uint4(silu_mul2(a.x, b.x), silu_mul2(a.y, b.y), silu_mul2(a.z, b.z), silu_mul2(a.w, b.w));
+            } else {
+                const u4v t = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(x + r * ld + col));
+                v[i] = make_uint4(t.x, t.y, t.z, t.w);
+            }
         }
     }
     if constexpr (DYN) {
@@ -710,17 +719,24 @@ f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g,
 // ws (checked tensor).  *npartial = number of partials written (0 for an empty tensor).
 f8_status cast_measure(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
                        uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, void* ws,
-                       size_t ws_bytes, int* npartial, hipStream_t st)
+                       size_t ws_bytes, int* npartial, hipStream_t st, bool silu)
 {
     *npartial = 0;
     if (rows == 0 || cols == 0) return F8_OK;
     const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (cols + kTile - 1) / kTile;
     const int64_t nb = tiles_r * tiles_c;
     if (nb > (int64_t)0x7FFFFFFF || (size_t)nb * sizeof(uint32_t) > ws_bytes) return F8_ERR_WORKSPACE;
-#define F8_LAUNCH_MEASURE(F, O, T)                                                                   \
-    cast_tile_kernel<F, F8_TENSORWISE, false, O, T, true><<<(unsigned)nb, kThreads, 0, st>>>(        \
-        (const uint16_t*)x, rows, cols, ld, scale, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, \
-        out_t, ld_out_t, (int)tiles_c, (uint32_t*)ws)
+#define F8_LAUNCH_MEASURE(F, O, T)                                                                       \
+    do {                                                                                                 \
+        if (silu)                                                                                        \
+            cast_tile_kernel<F, F8_TENSORWISE, false, O, T, true, true><<<(unsigned)nb, kThreads, 0, st>>>( \
+                (const uint16_t*)x, rows, cols, ld, scale, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, \
+                out_t, ld_out_t, (int)tiles_c, (uint32_t*)ws);                                           \
+        else                                                                                             \
+            cast_tile_kernel<F, F8_TENSORWISE, false, O, T, true><<<(unsigned)nb, kThreads, 0, st>>>(     \
+                (const uint16_t*)x, rows, cols, ld, scale, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, \
+                out_t, ld_out_t, (int)tiles_c, (uint32_t*)ws);                                           \
+    } while (0)
 #define F8_MEASURE_FMT(F)                               \
     do {                                                \
         if (out && out_t) F8_LAUNCH_MEASURE(F, true, true);  \
@@ -895,7 +911,7 @@ f8_status f8_cast_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t l
     hipStream_t st = (hipStream_t)stream;
     int np = 0;
     s = cast_measure(x_bf16, rows, cols, ld, scale, fmt, out, ld_out, out_t, ld_out_t, workspace,
-                     workspace_bytes_, &np, st);
+                     workspace_bytes_, &np, st, false);
     if (s != F8_OK) return s;
     amax_tensor_final_kernel<<<1, kThreads, 0, st>>>((const uint32_t*)workspace, np, 0.0f, amax_out, nullptr, nullptr);
     return last_launch_status();

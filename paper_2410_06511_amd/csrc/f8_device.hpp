@@ -192,4 +192,17 @@ __device__ inline float scale_from_amax(float amax, float fm)
     return fm / (amax > kEps ? amax : kEps);
 }
 
+// ---- feed-forward glue arithmetic (shared by the glue kernels and the cast that fuses it) ----
+
+__device__ inline float sigmoidf_fast(float t) { return 1.0f / (1.0f + __expf(-t)); }
+
+__device__ inline uint32_t pack_bf16(float lo, float hi) { return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16); }
+
+// one 32-bit word = two bf16: h = bf16(silu(a) * b), silu(t) = t / (1 + e^-t)
+__device__ inline uint32_t silu_mul2(uint32_t a, uint32_t b)
+{
+    const float a0 = bf16_lo(a), a1 = bf16_hi(a);
+    return pack_bf16((a0 * sigmoidf_fast(a0)) * bf16_lo(b), (a1 * sigmoidf_fast(a1)) * bf16_hi(b));
+}
+
 }  // namespace f8

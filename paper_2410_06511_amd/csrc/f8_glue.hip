@@ -16,17 +16,6 @@ constexpr int kGlueWaves = kGlueThreads / kWave;
 constexpr int kGlueMaxBlocks = 2048;
 static_assert((size_t)kGlueMaxBlocks * sizeof(uint32_t) <= kMinWorkspaceBytes, "one partial per block fits the minimum workspace");
 
-__device__ inline float sigmoidf_fast(float t) { return 1.0f / (1.0f + __expf(-t)); }
-
-__device__ inline uint32_t pack_bf16(float lo, float hi) { return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16); }
-
-// one 32-bit word = two bf16: h = silu(a) * b
-__device__ inline uint32_t silu_mul2(uint32_t a, uint32_t b)
-{
-    const float a0 = bf16_lo(a), a1 = bf16_hi(a);
-    return pack_bf16((a0 * sigmoidf_fast(a0)) * bf16_lo(b), (a1 * sigmoidf_fast(a1)) * bf16_hi(b));
-}
-
 __device__ inline void silu_mul_bwd2(uint32_t a, uint32_t b, uint32_t g, uint32_t* da, uint32_t* db)
 {
     const float a0 = bf16_lo(a), a1 = bf16_hi(a), g0 = bf16_lo(g), g1 = bf16_hi(g);

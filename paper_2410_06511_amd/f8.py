@@ -26,7 +26,7 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
            "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled",
            "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise",
-           "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm"]
+           "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq"]
 
 
 class F8Error(RuntimeError):
@@ -86,6 +86,10 @@ def lib():
         l.f8_silu_mul.argtypes = [_p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_silu_mul_bwd.argtypes = [_p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_rmsnorm.argtypes = [_p, _p, _i64, _i64, C.c_float, _p, _p, _p, _p, C.c_size_t, _p]
+        l.f8_silu_mul_quantise_delayed.argtypes = [_p, _i64, _i64, _int, _p, _i64, _p, C.POINTER(QTensorStruct), _p,
+                                                   C.c_size_t, _p]
+        l.f8_linear_fwd_xq.argtypes = [C.POINTER(LinearDesc), C.POINTER(ScalingStateStruct), _p, _p,
+                                       C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
         _lib = l
@@ -294,3 +298,17 @@ def rmsnorm(x, g, eps, y, rstd=None, amax_y=None, workspace=None, stream=None):
     wp, wb = _ws(workspace)
     _check(lib().f8_rmsnorm(_ptr(x), _ptr(g), M, D, float(eps), _ptr(y), _ptr(rstd), _ptr(amax_y), wp, wb,
                             _stream(stream)))
+
+
+def silu_mul_quantise_delayed(ab, fmt, history, scale_t, q, workspace, stream=None):
+    M, H2 = ab.shape
+    wp, wb = _ws(workspace)
+    st = q.struct()
+    _check(lib().f8_silu_mul_quantise_delayed(_ptr(ab), M, H2 // 2, fmt, _ptr(history), history.numel(), _ptr(scale_t),
+                                              C.byref(st), wp, wb, _stream(stream)))
+
+
+def linear_fwd_xq(desc, state, W, Y, saved, workspace, stream=None):
+    wp, wb = _ws(workspace)
+    _check(lib().f8_linear_fwd_xq(C.byref(desc), C.byref(state.struct()), _ptr(W), _ptr(Y), C.byref(saved.struct()),
+                                  wp, wb, _stream(stream)))

@@ -243,3 +243,48 @@ def test_norm_then_feed_forward_chain():
         outs.append((f.Y, f.s13.x.q, f.s13.x.scale, f.s2.x.q_t))
     for a, b in zip(*outs):
         assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+@pytest.mark.parametrize("M,D,H", [(272, 336, 208), (512, 768, 1024)])
+def test_glue_fused_into_the_delayed_cast(M, D, H):
+    """silu(a) * b formed inside the cast of the next linear's input (delayed scaling): over
+    several steps, codes, scales, amax, history, next scale and Y are bit-identical to writing h
+    with f8_silu_mul and quantising it in the linear."""
+    g = torch.Generator("cpu")
+    g.manual_seed(M)
+    W2 = wl.randn_bf16((D, H), 0.02, 0, generator=g).cuda()
+    desc = f8.linear_desc(M, H, D)
+    ws = f8.new_workspace(max(M, D, H), max(M, D, 2 * H))
+    results = []
+    steps = [wl.randn_bf16((M, 2 * H), 1.0 + 0.7 * i, 0, generator=g).cuda() for i in range(4)]
+    for fused in (False, True):
+        st = f8.ScalingState(f8.DELAYED, 2)
+        st.scale_x.fill_(300.0), st.scale_w.fill_(5000.0)
+        saved = f8.Saved(M, H, D)
+        Y = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+        h = torch.empty((M, H), dtype=torch.bfloat16, device="cuda")
+        snaps = []
+        for AB in steps:
+            if fused:
+                f8.silu_mul_quantise_delayed(AB, f8.E4M3, st.hist_x, st.scale_x, saved.x, ws)
+                f8.linear_fwd_xq(desc, st, W2, Y, saved, ws)
+            else:
+                f8.silu_mul(AB, h)
+                f8.linear_fwd_scaled(desc, st, h, W2, Y, saved, ws)
+            torch.cuda.synchronize()
+            snaps.append([t.clone() for t in (Y, saved.x.q, saved.x.q_t, saved.x.amax, saved.x.scale, saved.x.inv_scale,
+                                              saved.w.q, st.hist_x, st.scale_x, st.hist_w, st.scale_w)])
+        results.append(snaps)
+    for a_step, b_step in zip(*results):
+        for a, b in zip(a_step, b_step):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    # and against the oracle on the last step: where the GPU's h equals the oracle's h bit for bit
+    # (almost everywhere), the codes are the oracle's codes for the scale that was used
+    rh, _ = o.silu_mul(bits(steps[-1]))
+    used_scale = f32(results[1][-1][4])
+    ref_codes = o.cast(rh, used_scale, o.TENSORWISE, o.E4M3)
+    got_codes = u8(results[1][-1][1])
+    f8.silu_mul(steps[-1], h)
+    torch.cuda.synchronize()
+    same_h = bits(h) == rh
+    assert same_h.mean() > 0.98 and np.array_equal(got_codes[same_h], ref_codes[same_h])
