@@ -347,8 +347,9 @@ def ffn_main(args, w):
         print("bench.py: the feed-forward chain runs with dynamic or delayed scaling", file=sys.stderr)
         sys.exit(2)
     if delayed:
-        # delayed scaling: every scale is known beforehand, so the glue is fused into the cast of
-        # w2's input (h is never written) and no amax has to be handed over
+        # delayed scaling: every scale is known beforehand, so the glue is fused into the casts of
+        # w2's input and of w13's output gradient (h and dAB are never written) and no amax has
+        # to be handed over
         st13, st2 = f8.ScalingState(f8.DELAYED, 16), f8.ScalingState(f8.DELAYED, 16)
         calls = [
             ("rmsnorm", lambda: f8.rmsnorm(X, gw, 1e-5, Xn, None, None, None, stream), 0, 4 * M * D),
@@ -356,8 +357,8 @@ def ffn_main(args, w):
             ("silu_mul fused into the cast of h", lambda: f8.silu_mul_quantise_delayed(AB, f8.E4M3, st2.hist_x, st2.scale_x, s2.x, ws, stream), 0, 6 * M * H),
             ("linear w2 fwd (input already quantised)", lambda: f8.linear_fwd_xq(d2, st2, W2, Y, s2, ws, stream), 2 * M * H * D, 0),
             ("linear w2 bwd", lambda: f8.linear_bwd_scaled(d2, st2, dY, s2, dH, dW2, ws, stream), 4 * M * H * D, 0),
-            ("silu_mul_bwd", lambda: f8.silu_mul_bwd(AB, dH, dAB, None, None, stream), 0, 10 * M * H),
-            ("linear w13 bwd", lambda: f8.linear_bwd_scaled(d13, st13, dAB, s13, dX, dW13, ws, stream), 4 * M * D * 2 * H, 0),
+            ("silu_mul_bwd fused into the cast of dAB", lambda: f8.silu_mul_bwd_quantise_delayed(AB, dH, f8.E4M3, st13.hist_dy, st13.scale_dy, s13.dy, ws, stream), 0, 10 * M * H),
+            ("linear w13 bwd (gradient already quantised)", lambda: f8.linear_bwd_dyq(d13, s13, dX, dW13, stream), 4 * M * D * 2 * H, 0),
         ]
         # seed the histories with one dynamic pass (the first-step initialisation)
         a = torch.empty(1, device="cuda")
@@ -415,6 +416,8 @@ def ffn_main(args, w):
             leg["bytes_per_elem"] = by // (M * D if name == "rmsnorm" else M * H)
             if name.startswith("silu_mul fused"):
                 leg["note"] = "reads [a | b] (4 B), writes the codes of h in both orientations (2 B); replaces silu_mul (6 B) + the cast of h (4 B)"
+            if name.startswith("silu_mul_bwd fused"):
+                leg["note"] = "reads [a | b] and dh (6 B), writes the codes of dAB in both orientations (4 B); replaces silu_mul_bwd (10 B) + the cast of dAB (8 B)"
         legs.append(leg)
     glue_ms = sum(l["ms"] for l in legs if "gbs" in l)
     glue_bytes = sum(by for _, _, _, by in calls)

@@ -364,6 +364,25 @@ f8_status f8_silu_mul_quantise_delayed(const void* ab_bf16, int64_t M, int64_t H
                                        void* stream);
 
 /*
+ * The same fusion for the backward of the glue: from ab [M, 2H] and dh [M, H]
+ * it forms dab = [dh * b * silu'(a) | dh * silu(a)] in registers and writes
+ * only its fp8 codes q->q [M, 2H], q->q_t [2H, M] (delayed scaling as above;
+ * fmt is the gradient format).  Same results as f8_silu_mul_bwd followed by the
+ * delayed-scaling quantisation of dab.  workspace: f8_workspace_bytes(M, 2H).
+ */
+f8_status f8_silu_mul_bwd_quantise_delayed(const void* ab_bf16, const void* dh_bf16, int64_t M, int64_t H,
+                                           f8_format fmt, float* history, int64_t history_len,
+                                           float* scale, const f8_qtensor* q, void* workspace,
+                                           size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of the linear whose output gradient is already quantised in
+ * saved->dy (codes in both orientations, inv_scale; in d->grad_format): the
+ * two GEMMs dX = dY8 W8, dW = dY8^T X8 only.  Tensorwise only.
+ */
+f8_status f8_linear_bwd_dyq(const f8_linear_desc* d, f8_saved* saved, void* dX, void* dW, void* stream);
+
+/*
  * Forward of the linear whose input is already quantised in saved->x (codes in
  * both orientations, scale, inv_scale; e.g. by f8_silu_mul_quantise_delayed):
  * quantises W [N,K] as state->mode says (the w members of the state; for

@@ -389,16 +389,20 @@ __device__ inline void transpose4x4(const uint32_t r[4], uint32_t c[4])
 // MEASURE (delayed scaling): the scale is given, and the block also writes the largest
 // magnitude of its own tile to partial_out[blockIdx.x], so that the tensor's amax of this step
 // comes out of the same single pass over x.
-// SILU (with MEASURE): x is the output [rows, 2 * cols] = [a | b] of a stacked w1|w3 linear (ld = its
-// row length) and the tensor that is cast is h = bf16(silu(a) * b), formed in registers: the
-// feed-forward glue fused into the cast of its consumer, h itself is never written.
-template <int FMT, int GRAN, bool DYN, bool OUT, bool OUT_T, bool MEASURE = false, bool SILU = false>
+// GLUE (with MEASURE): the tensor that is cast is formed in registers from the feed-forward glue's
+// inputs and never written itself.
+//   GLUE = 1: x = [a | b], [rows, 2 * cols] with ld = its row length; cast h = bf16(silu(a) * b).
+//   GLUE = 2: x = [a | b] as above, x2 = dh [rows, cols]; cast dab = [bf16(dh * b * silu'(a)) |
+//             bf16(dh * silu(a))], [rows, 2 * cols]: a block reads its tile of a, b and dh once and
+//             emits the matching tiles of both halves (out, out_t have 2 * cols columns / rows).
+template <int FMT, int GRAN, bool DYN, bool OUT, bool OUT_T, bool MEASURE = false, int GLUE = 0>
 __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     const uint16_t* __restrict__ x, int64_t rows, int64_t cols, int64_t ld,
     const float* __restrict__ scale, const uint32_t* __restrict__ partial, int npartial,
     float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out,
     uint8_t* __restrict__ out, int64_t ld_out, uint8_t* __restrict__ out_t, int64_t ld_out_t,
-    int tiles_c, uint32_t* __restrict__ partial_out = nullptr, const float* __restrict__ scale_col = nullptr)
+    int tiles_c, uint32_t* __restrict__ partial_out = nullptr, const float* __restrict__ scale_col = nullptr,
+    const uint16_t* __restrict__ x2 = nullptr)
 {
     __shared__ uint32_t red[kWaves];
     __shared__ uint32_t tile[kTile * kLdsStride];
@@ -424,18 +428,28 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
         }
     }
     uint4 v[8];
+    uint4 v2[GLUE == 2 ? 8 : 1];  // second half of dab
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const int64_t r = r0 + rr + 16 * i;
         v[i] = make_uint4(0, 0, 0, 0);
+        if constexpr (GLUE == 2) v2[i] = make_uint4(0, 0, 0, 0);
         // Streaming load: this is the last read of x by the quantisation; lines it would leave in
         // the caches only push out the codes that the GEMM reads next.
         typedef unsigned int u4v __attribute__((ext_vector_type(4)));
         if (col_ok && r < rows) {
-            if constexpr (SILU) {
+            if constexpr (GLUE == 1) {
                 const uint4 a = *reinterpret_cast<const uint4*>(x + r * ld + col);   // read again by the backward
                 const uint4 b = *reinterpret_cast<const uint4*>(x + r * ld + cols + col);
                 v[i] = make_uint4(silu_mul2(a.x, b.x), silu_mul2(a.y, b.y), silu_mul2(a.z, b.z), silu_mul2(a.w, b.w));
+            } else if constexpr (GLUE == 2) {
+                const uint4 a = *reinterpret_cast<const uint4*>(x + r * ld + col);
+                const uint4 b = *reinterpret_cast<const uint4*>(x + r * ld + cols + col);
+                const uint4 g = *reinterpret_cast<const uint4*>(x2 + r * cols + col);
+                silu_mul_bwd2(a.x, b.x, g.x, &v[i].x, &v2[i].x);
+                silu_mul_bwd2(a.y, b.y, g.y, &v[i].y, &v2[i].y);
+                silu_mul_bwd2(a.z, b.z, g.z, &v[i].z, &v2[i].z);
+                silu_mul_bwd2(a.w, b.w, g.w, &v[i].w, &v2[i].w);
             } else {
                 const u4v t = __builtin_nontemporal_load(reinterpret_cast<const u4v*>(x + r * ld + col));
                 v[i] = make_uint4(t.x, t.y, t.z, t.w);
@@ -457,55 +471,67 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     if constexpr (MEASURE) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) macc = absmax_acc(macc, v[i]);  // out-of-range chunks are zero
-    }
+        if constexpr (GLUE == 2) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int rl = rr + 16 * i;
-        const int64_t r = r0 + rl;
-        uint2 q, qt;
-        if constexpr (GRAN == F8_COLWISE) {
-            q = qt = cast8v<FMT>(v[i], sc);
-        } else if constexpr (GRAN == kGranBoth) {
-            s = r < rows ? scale[r] : 0.0f;
-            q = cast8<FMT>(v[i], s);
-            qt = cast8v<FMT>(v[i], sc);
-        } else {
-            if constexpr (GRAN == F8_ROWWISE) s = r < rows ? scale[r] : 0.0f;
-            q = qt = cast8<FMT>(v[i], s);
-        }
-        if constexpr (OUT) {
-            if (col_ok && r < rows) *reinterpret_cast<uint2*>(out + r * ld_out + col) = q;
-        }
-        if constexpr (OUT_T) {
-            tile[rl * kLdsStride + cc * 2] = qt.x;
-            tile[rl * kLdsStride + cc * 2 + 1] = qt.y;
+            for (int i = 0; i < 8; ++i) macc = absmax_acc(macc, v2[i]);
         }
     }
-    if constexpr (OUT_T) {
-        __syncthreads();
-        // phase 2: thread (rb, cb) owns rows 16*rb.. +15 and columns 4*cb.. +3 of the tile and
-        // writes four 16-byte pieces, one per column, into the transposed output.
-        const int rb = threadIdx.x & 7, cb = threadIdx.x >> 3;
-        uint32_t o[4][4];  // o[col i][row group g] = codes of rows 16rb+4g..+3, column 4cb+i
+    // codes of one tile of values vv, written at column offset coff of out (row offset of out_t)
+    auto emit = [&](const uint4* vv, int64_t coff) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            uint32_t rws[4], cls[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) rws[j] = tile[(16 * rb + 4 * g + j) * kLdsStride + cb];
-            transpose4x4(rws, cls);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) o[i][g] = cls[i];
-        }
-        const int64_t rbase = r0 + 16 * rb;
-        if (rbase < rows) {  // rows is a multiple of 16: the piece is all in or all out
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int64_t c = c0 + 4 * cb + i;
-                if (c < cols)
-                    *reinterpret_cast<uint4*>(out_t + c * ld_out_t + rbase) =
-                        make_uint4(o[i][0], o[i][1], o[i][2], o[i][3]);
+        for (int i = 0; i < 8; ++i) {
+            const int rl = rr + 16 * i;
+            const int64_t r = r0 + rl;
+            uint2 q, qt;
+            if constexpr (GRAN == F8_COLWISE) {
+                q = qt = cast8v<FMT>(vv[i], sc);
+            } else if constexpr (GRAN == kGranBoth) {
+                s = r < rows ? scale[r] : 0.0f;
+                q = cast8<FMT>(vv[i], s);
+                qt = cast8v<FMT>(vv[i], sc);
+            } else {
+                if constexpr (GRAN == F8_ROWWISE) s = r < rows ? scale[r] : 0.0f;
+                q = qt = cast8<FMT>(vv[i], s);
+            }
+            if constexpr (OUT) {
+                if (col_ok && r < rows) *reinterpret_cast<uint2*>(out + r * ld_out + coff + col) = q;
+            }
+            if constexpr (OUT_T) {
+                tile[rl * kLdsStride + cc * 2] = qt.x;
+                tile[rl * kLdsStride + cc * 2 + 1] = qt.y;
             }
         }
+        if constexpr (OUT_T) {
+            __syncthreads();
+            // phase 2: thread (rb, cb) owns rows 16*rb.. +15 and columns 4*cb.. +3 of the tile and
+            // writes four 16-byte pieces, one per column, into the transposed output.
+            const int rb = threadIdx.x & 7, cb = threadIdx.x >> 3;
+            uint32_t o[4][4];  // o[col i][row group g] = codes of rows 16rb+4g..+3, column 4cb+i
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                uint32_t rws[4], cls[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) rws[j] = tile[(16 * rb + 4 * g + j) * kLdsStride + cb];
+                transpose4x4(rws, cls);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i][g] = cls[i];
+            }
+            const int64_t rbase = r0 + 16 * rb;
+            if (rbase < rows) {  // rows is a multiple of 16: the piece is all in or all out
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int64_t c = c0 + 4 * cb + i;
+                    if (c < cols)
+                        *reinterpret_cast<uint4*>(out_t + (coff + c) * ld_out_t + rbase) =
+                            make_uint4(o[i][0], o[i][1], o[i][2], o[i][3]);
+                }
+            }
+        }
+    };
+    emit(v, 0);
+    if constexpr (GLUE == 2) {
+        if constexpr (OUT_T) __syncthreads();  // the tile in LDS has been read before it is rewritten
+        emit(v2, cols);
     }
     if constexpr (MEASURE) {
         // after the stores are on their way: the reduction's barriers then stall nothing
@@ -719,23 +745,23 @@ f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g,
 // ws (checked tensor).  *npartial = number of partials written (0 for an empty tensor).
 f8_status cast_measure(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
                        uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, void* ws,
-                       size_t ws_bytes, int* npartial, hipStream_t st, bool silu)
+                       size_t ws_bytes, int* npartial, hipStream_t st, int glue, const void* x2)
 {
     *npartial = 0;
     if (rows == 0 || cols == 0) return F8_OK;
-    const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (cols + kTile - 1) / kTile;
+    const int64_t kcols = glue == 2 ? cols / 2 : cols;  // the kernel's tile grid covers one half of dab
+    const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (kcols + kTile - 1) / kTile;
     const int64_t nb = tiles_r * tiles_c;
     if (nb > (int64_t)0x7FFFFFFF || (size_t)nb * sizeof(uint32_t) > ws_bytes) return F8_ERR_WORKSPACE;
-#define F8_LAUNCH_MEASURE(F, O, T)                                                                       \
-    do {                                                                                                 \
-        if (silu)                                                                                        \
-            cast_tile_kernel<F, F8_TENSORWISE, false, O, T, true, true><<<(unsigned)nb, kThreads, 0, st>>>( \
-                (const uint16_t*)x, rows, cols, ld, scale, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, \
-                out_t, ld_out_t, (int)tiles_c, (uint32_t*)ws);                                           \
-        else                                                                                             \
-            cast_tile_kernel<F, F8_TENSORWISE, false, O, T, true><<<(unsigned)nb, kThreads, 0, st>>>(     \
-                (const uint16_t*)x, rows, cols, ld, scale, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, \
-                out_t, ld_out_t, (int)tiles_c, (uint32_t*)ws);                                           \
+#define F8_LAUNCH_MEASURE_G(F, O, T, G)                                                                  \
+    cast_tile_kernel<F, F8_TENSORWISE, false, O, T, true, G><<<(unsigned)nb, kThreads, 0, st>>>(         \
+        (const uint16_t*)x, rows, kcols, ld, scale, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, out_t, \
+        ld_out_t, (int)tiles_c, (uint32_t*)ws, nullptr, (const uint16_t*)x2)
+#define F8_LAUNCH_MEASURE(F, O, T)                       \
+    do {                                                 \
+        if (glue == 1) F8_LAUNCH_MEASURE_G(F, O, T, 1);  \
+        else if (glue == 2) F8_LAUNCH_MEASURE_G(F, O, T, 2); \
+        else F8_LAUNCH_MEASURE_G(F, O, T, 0);            \
     } while (0)
 #define F8_MEASURE_FMT(F)                               \
     do {                                                \
@@ -747,6 +773,7 @@ f8_status cast_measure(const void* x, int64_t rows, int64_t cols, int64_t ld, co
     else F8_MEASURE_FMT(F8_E5M2);
 #undef F8_MEASURE_FMT
 #undef F8_LAUNCH_MEASURE
+#undef F8_LAUNCH_MEASURE_G
     *npartial = (int)nb;
     return last_launch_status();
 }
@@ -911,7 +938,7 @@ f8_status f8_cast_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t l
     hipStream_t st = (hipStream_t)stream;
     int np = 0;
     s = cast_measure(x_bf16, rows, cols, ld, scale, fmt, out, ld_out, out_t, ld_out_t, workspace,
-                     workspace_bytes_, &np, st, false);
+                     workspace_bytes_, &np, st, 0, nullptr);
     if (s != F8_OK) return s;
     amax_tensor_final_kernel<<<1, kThreads, 0, st>>>((const uint32_t*)workspace, np, 0.0f, amax_out, nullptr, nullptr);
     return last_launch_status();

@@ -205,4 +205,13 @@ __device__ inline uint32_t silu_mul2(uint32_t a, uint32_t b)
     return pack_bf16((a0 * sigmoidf_fast(a0)) * bf16_lo(b), (a1 * sigmoidf_fast(a1)) * bf16_hi(b));
 }
 
+// backward of h = silu(a) * b for one word (two bf16): da = g * b * silu'(a), db = g * silu(a)
+__device__ inline void silu_mul_bwd2(uint32_t a, uint32_t b, uint32_t g, uint32_t* da, uint32_t* db)
+{
+    const float a0 = bf16_lo(a), a1 = bf16_hi(a), g0 = bf16_lo(g), g1 = bf16_hi(g);
+    const float s0 = sigmoidf_fast(a0), s1 = sigmoidf_fast(a1);
+    *da = pack_bf16((g0 * bf16_lo(b)) * (s0 * (1.0f + a0 * (1.0f - s0))), (g1 * bf16_hi(b)) * (s1 * (1.0f + a1 * (1.0f - s1))));
+    *db = pack_bf16(g0 * (a0 * s0), g1 * (a1 * s1));
+}
+
 }  // namespace f8

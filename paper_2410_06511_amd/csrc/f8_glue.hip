@@ -16,14 +16,6 @@ constexpr int kGlueWaves = kGlueThreads / kWave;
 constexpr int kGlueMaxBlocks = 2048;
 static_assert((size_t)kGlueMaxBlocks * sizeof(uint32_t) <= kMinWorkspaceBytes, "one partial per block fits the minimum workspace");
 
-__device__ inline void silu_mul_bwd2(uint32_t a, uint32_t b, uint32_t g, uint32_t* da, uint32_t* db)
-{
-    const float a0 = bf16_lo(a), a1 = bf16_hi(a), g0 = bf16_lo(g), g1 = bf16_hi(g);
-    const float s0 = sigmoidf_fast(a0), s1 = sigmoidf_fast(a1);
-    *da = pack_bf16((g0 * bf16_lo(b)) * (s0 * (1.0f + a0 * (1.0f - s0))), (g1 * bf16_hi(b)) * (s1 * (1.0f + a1 * (1.0f - s1))));
-    *db = pack_bf16(g0 * (a0 * s0), g1 * (a1 * s1));
-}
-
 // ab [M, 2H] as 16-byte chunks: row m has 2 * hc chunks, a first; h [M, H]: hc chunks per row.
 __global__ __launch_bounds__(kGlueThreads) void silu_mul_kernel(const uint4* __restrict__ ab, int64_t M, int64_t hc,
                                                                uint4* __restrict__ h, uint32_t* __restrict__ partial)

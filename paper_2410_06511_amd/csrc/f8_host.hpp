@@ -24,10 +24,11 @@ f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g,
 
 // Delayed / static scaling pieces (tensorwise, validated arguments).
 // cast with a given scale, leaving one partial maximum per 128x128 tile in ws
-// silu: x is [rows, 2 * cols] = [a | b] (ld = its row length) and the tensor cast is bf16(silu(a) * b)
+// glue = 1: x is [rows, 2 * cols] = [a | b] (ld = its row length), the tensor cast is bf16(silu(a) * b);
+// glue = 2: x is [a | b] [rows, cols], x2 is dh [rows, cols / 2], the tensor cast is the glue's backward
 f8_status cast_measure(const void* x, int64_t rows, int64_t cols, int64_t ld, const float* scale, int fmt,
                        uint8_t* out, int64_t ld_out, uint8_t* out_t, int64_t ld_out_t, void* ws,
-                       size_t ws_bytes, int* npartial, hipStream_t st, bool silu = false);
+                       size_t ws_bytes, int* npartial, hipStream_t st, int glue = 0, const void* x2 = nullptr);
 // step amax (from partials, or amax_in) -> amax_out; used_scale -> saved_scale, 1/x -> saved_inv;
 // history shifted and extended; FMAX / max(history) -> next_scale (, 1/x -> next_inv)
 f8_status history_push(const void* partial, int npartial, const float* amax_in, float* history, int64_t len,

@@ -65,7 +65,7 @@ static f8_status quantise_both(const void* T, int64_t rows, int64_t cols, bool r
 // orientations; delayed also records the tensor's amax and derives the next scale.
 static f8_status quantise_scaled(const void* T, int64_t rows, int64_t cols, int fmt, int mode, int64_t hist_len,
                                  float* hist, float* state_scale, const f8_qtensor* q, void* ws,
-                                 size_t ws_bytes, hipStream_t st, bool silu = false)
+                                 size_t ws_bytes, hipStream_t st, int glue = 0, const void* T2 = nullptr)
 {
     f8_status s;
     if (mode == F8_STATIC) {
@@ -73,8 +73,8 @@ static f8_status quantise_scaled(const void* T, int64_t rows, int64_t cols, int 
         return publish_scale(state_scale, q->scale, q->inv_scale, st);
     }
     int np = 0;
-    if ((s = cast_measure(T, rows, cols, silu ? 2 * cols : cols, state_scale, fmt, q->q, cols, q->q_t, rows, ws,
-                          ws_bytes, &np, st, silu)) != F8_OK)
+    if ((s = cast_measure(T, rows, cols, glue == 1 ? 2 * cols : cols, state_scale, fmt, q->q, cols, q->q_t, rows, ws,
+                          ws_bytes, &np, st, glue, T2)) != F8_OK)
         return s;
     return history_push(ws, np, nullptr, hist, hist_len, fmt, q->amax, state_scale, q->scale, q->inv_scale,
                         state_scale, nullptr, st);
@@ -284,7 +284,36 @@ f8_status f8_silu_mul_quantise_delayed(const void* ab_bf16, int64_t M, int64_t H
     if (s != F8_OK) return s;
     if (!workspace || workspace_bytes_ < workspace_bytes(M, H)) return F8_ERR_WORKSPACE;
     return quantise_scaled(ab_bf16, M, H, fmt, F8_DELAYED, history_len, history, scale, q, workspace, workspace_bytes_,
-                           (hipStream_t)stream, true);
+                           (hipStream_t)stream, 1);
+}
+
+f8_status f8_silu_mul_bwd_quantise_delayed(const void* ab_bf16, const void* dh_bf16, int64_t M, int64_t H,
+                                           f8_format fmt, float* history, int64_t history_len, float* scale,
+                                           const f8_qtensor* q, void* workspace, size_t workspace_bytes_,
+                                           void* stream)
+{
+    if ((int)fmt < 0 || (int)fmt > F8_E5M2) return F8_ERR_ENUM;
+    if (!ab_bf16 || !dh_bf16 || !history || !scale || !q) return F8_ERR_NULL;
+    if (M < 0 || H < 0 || (M % 16) || (H % 16) || history_len < 1 || history_len > F8_MAX_HISTORY) return F8_ERR_SHAPE;
+    if (!aligned16(ab_bf16) || !aligned16(dh_bf16)) return F8_ERR_ALIGN;
+    f8_status s = check_q(q, false);
+    if (s != F8_OK) return s;
+    if (!workspace || workspace_bytes_ < workspace_bytes(M, 2 * H)) return F8_ERR_WORKSPACE;
+    return quantise_scaled(ab_bf16, M, 2 * H, fmt, F8_DELAYED, history_len, history, scale, q, workspace,
+                           workspace_bytes_, (hipStream_t)stream, 2, dh_bf16);
+}
+
+f8_status f8_linear_bwd_dyq(const f8_linear_desc* d, f8_saved* saved, void* dX, void* dW, void* stream)
+{
+    f8_status s = check_desc(d);
+    if (s != F8_OK) return s;
+    if (d->granularity != F8_TENSORWISE) return F8_ERR_ENUM;
+    if (!dX || !dW || !saved) return F8_ERR_NULL;
+    if (!aligned16(dX) || !aligned16(dW)) return F8_ERR_ALIGN;
+    if ((s = check_q(&saved->x, false)) != F8_OK) return s;
+    if ((s = check_q(&saved->w, false)) != F8_OK) return s;
+    if ((s = check_q(&saved->dy, false)) != F8_OK) return s;
+    return gemms_bwd(d, saved, dX, nullptr, dW, (hipStream_t)stream);
 }
 
 f8_status f8_linear_fwd_xq(const f8_linear_desc* d, const f8_scaling_state* state, const void* W, void* Y,

@@ -26,7 +26,8 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
            "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled",
            "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise",
-           "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq"]
+           "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq",
+           "f8_silu_mul_bwd_quantise_delayed", "f8_linear_bwd_dyq"]
 
 
 class F8Error(RuntimeError):
@@ -90,6 +91,9 @@ def lib():
                                                    C.c_size_t, _p]
         l.f8_linear_fwd_xq.argtypes = [C.POINTER(LinearDesc), C.POINTER(ScalingStateStruct), _p, _p,
                                        C.POINTER(SavedStruct), _p, C.c_size_t, _p]
+        l.f8_silu_mul_bwd_quantise_delayed.argtypes = [_p, _p, _i64, _i64, _int, _p, _i64, _p, C.POINTER(QTensorStruct),
+                                                       _p, C.c_size_t, _p]
+        l.f8_linear_bwd_dyq.argtypes = [C.POINTER(LinearDesc), C.POINTER(SavedStruct), _p, _p, _p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
         _lib = l
@@ -312,3 +316,15 @@ def linear_fwd_xq(desc, state, W, Y, saved, workspace, stream=None):
     wp, wb = _ws(workspace)
     _check(lib().f8_linear_fwd_xq(C.byref(desc), C.byref(state.struct()), _ptr(W), _ptr(Y), C.byref(saved.struct()),
                                   wp, wb, _stream(stream)))
+
+
+def silu_mul_bwd_quantise_delayed(ab, dh, fmt, history, scale_t, q, workspace, stream=None):
+    M, H2 = ab.shape
+    wp, wb = _ws(workspace)
+    st = q.struct()
+    _check(lib().f8_silu_mul_bwd_quantise_delayed(_ptr(ab), _ptr(dh), M, H2 // 2, fmt, _ptr(history), history.numel(),
+                                                  _ptr(scale_t), C.byref(st), wp, wb, _stream(stream)))
+
+
+def linear_bwd_dyq(desc, saved, dX, dW, stream=None):
+    _check(lib().f8_linear_bwd_dyq(C.byref(desc), C.byref(saved.struct()), _ptr(dX), _ptr(dW), _stream(stream)))

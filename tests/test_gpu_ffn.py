@@ -288,3 +288,75 @@ def test_glue_fused_into_the_delayed_cast(M, D, H):
     torch.cuda.synchronize()
     same_h = bits(h) == rh
     assert same_h.mean() > 0.98 and np.array_equal(got_codes[same_h], ref_codes[same_h])
+
+
+@pytest.mark.parametrize("M,D,H", [(272, 336, 208), (512, 768, 1024)])
+def test_glue_backward_fused_into_the_delayed_cast(M, D, H):
+    """The backward of silu(a) * b formed inside the cast of dAB, the output gradient of the stacked
+    w1|w3 linear (delayed scaling): over several steps the codes in both orientations, scales,
+    amax, history, next scale, dX and dW are bit-identical to writing dAB with f8_silu_mul_bwd and
+    quantising it in the linear's backward."""
+    g = torch.Generator("cpu")
+    g.manual_seed(M + 1)
+    W13 = wl.randn_bf16((2 * H, D), 0.02, 0, generator=g).cuda()
+    X = wl.randn_bf16((M, D), 1.0, 0, generator=g).cuda()
+    desc = f8.linear_desc(M, D, 2 * H)
+    ws = f8.new_workspace(max(M, D, 2 * H), max(M, D, 2 * H))
+    steps = [(wl.randn_bf16((M, 2 * H), 1.0 + 0.5 * i, 0, generator=g).cuda(),
+              wl.randn_bf16((M, H), 1e-3 * (1 + i), 0, generator=g).cuda()) for i in range(4)]
+    results = []
+    for fused in (False, True):
+        st = f8.ScalingState(f8.DELAYED, 2)
+        st.scale_x.fill_(100.0), st.scale_w.fill_(5000.0), st.scale_dy.fill_(2.0e4)
+        saved = f8.Saved(M, D, 2 * H)
+        AB0 = torch.empty((M, 2 * H), dtype=torch.bfloat16, device="cuda")
+        f8.linear_fwd_scaled(desc, st, X, W13, AB0, saved, ws)       # fills saved.x, saved.w
+        dAB = torch.empty((M, 2 * H), dtype=torch.bfloat16, device="cuda")
+        dX = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+        dW = torch.empty((2 * H, D), dtype=torch.bfloat16, device="cuda")
+        snaps = []
+        for AB, dh in steps:
+            if fused:
+                f8.silu_mul_bwd_quantise_delayed(AB, dh, f8.E4M3, st.hist_dy, st.scale_dy, saved.dy, ws)
+                f8.linear_bwd_dyq(desc, saved, dX, dW)
+            else:
+                f8.silu_mul_bwd(AB, dh, dAB)
+                f8.linear_bwd_scaled(desc, st, dAB, saved, dX, dW, ws)
+            torch.cuda.synchronize()
+            snaps.append([t.clone() for t in (dX, dW, saved.dy.q, saved.dy.q_t, saved.dy.amax, saved.dy.scale,
+                                              saved.dy.inv_scale, st.hist_dy, st.scale_dy)])
+        results.append(snaps)
+    for a_step, b_step in zip(*results):
+        for a, b in zip(a_step, b_step):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    # against the oracle on the last step, where the GPU's dAB equals the oracle's bit for bit
+    AB, dh = steps[-1]
+    rd, _ = o.silu_mul_bwd(bits(AB), bits(dh))
+    used_scale = f32(results[1][-1][5])
+    ref_codes = o.cast(rd, used_scale, o.TENSORWISE, o.E4M3)
+    got = u8(results[1][-1][2])
+    got_t = u8(results[1][-1][3])
+    f8.silu_mul_bwd(AB, dh, dAB)
+    torch.cuda.synchronize()
+    same = bits(dAB) == rd
+    assert same.mean() > 0.97 and np.array_equal(got[same], ref_codes[same])
+    assert np.array_equal(got_t, got.T)
+
+
+def test_fused_glue_backward_argument_checks():
+    M, D, H = 64, 64, 64
+    ws = f8.new_workspace(256, 256)
+    ab = torch.zeros((M, 2 * H), dtype=torch.bfloat16, device="cuda")
+    dh = torch.zeros((M, H), dtype=torch.bfloat16, device="cuda")
+    st = f8.ScalingState(f8.DELAYED, 2)
+    saved = f8.Saved(M, D, 2 * H)
+    with pytest.raises(f8.F8Error):
+        f8.silu_mul_bwd_quantise_delayed(ab, dh, 7, st.hist_dy, st.scale_dy, saved.dy, ws)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(f8.F8Error):
+        f8.silu_mul_bwd_quantise_delayed(ab, dh, f8.E4M3, st.hist_dy, st.scale_dy, saved.dy, small)
+    rw = f8.linear_desc(M, D, 2 * H, rowwise=True)
+    dX = torch.empty((M, D), dtype=torch.bfloat16, device="cuda")
+    dW = torch.empty((2 * H, D), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(f8.F8Error):
+        f8.linear_bwd_dyq(rw, saved, dX, dW)
