@@ -333,8 +333,8 @@ f8_status f8_silu_mul_bwd(const void* ab_bf16, const void* dh_bf16, int64_t M, i
 
 /*
  * RMS normalisation in front of a Llama block's attention and feed-forward
- * linears, forward only (the producer of a Float8 linear's input; its backward
- * does not touch the Float8 path and is not part of this library):
+ * linears (the producer of a Float8 linear's input; f8_rmsnorm_bwd is its
+ * backward):
  *   y[m, :] = x[m, :] * rstd[m] * g,   rstd[m] = 1 / sqrt(mean_d x[m, d]^2 + eps)
  * x, y [M, D] bf16, g [D] bf16; rstd (nullable) [M] fp32, kept for a backward
  * pass; amax_y (nullable, 1 float) receives the exact maximum magnitude of
@@ -381,6 +381,43 @@ f8_status f8_silu_mul_bwd_quantise_delayed(const void* ab_bf16, const void* dh_b
  * two GEMMs dX = dY8 W8, dW = dY8^T X8 only.  Tensorwise only.
  */
 f8_status f8_linear_bwd_dyq(const f8_linear_desc* d, f8_saved* saved, void* dX, void* dW, void* stream);
+
+/*
+ * The bf16 operations that join the Float8 linears of one transformer block
+ * (Section 2.2.2 applies Float8 to the linear layers only; Section 2.1 names
+ * the TransformerBlock as the unit that is wrapped, sharded and recomputed).
+ *
+ * f8_rope: rotary position embedding of x [M, n_heads * hd] bf16 (row pitch
+ * ldx elements): row m is position m % S of its sequence; within each head
+ * the adjacent pair (x[2i], x[2i+1]) is turned by the angle
+ * pos * theta^(-2i/hd) (by its negative when inverse != 0: the backward).
+ * out (nullable) [M, n_heads * hd], row pitch ldo; out_t (nullable) the same
+ * values transposed, [n_heads * hd, M] packed: the copy that the attention
+ * backward contracts over tokens.  Angle and its reduction in fp64, sine and
+ * cosine and the rotation in fp32, one rounding to bf16.  hd a multiple of 8
+ * and <= 256, M and the pitches multiples of 8.
+ *
+ * f8_transpose_bf16: out_t [cols, rows] packed = x [rows, cols]^T (pitch ldx).
+ * f8_add: out = bf16(a + b) over n elements (the residual), n multiple of 8.
+ */
+f8_status f8_rope(const void* x_bf16, int64_t ldx, int64_t M, int64_t S, int64_t n_heads, int64_t hd,
+                  double theta, int inverse, void* out_bf16, int64_t ldo, void* out_t_bf16, void* stream);
+f8_status f8_transpose_bf16(const void* x_bf16, int64_t ldx, int64_t rows, int64_t cols, void* out_t_bf16,
+                            void* stream);
+f8_status f8_add(const void* a_bf16, const void* b_bf16, int64_t n, void* out_bf16, void* stream);
+
+/*
+ * Backward of f8_rmsnorm: with r = rstd[m] from the forward,
+ *   dx[m, :] = r * (g . dy[m, :]) - x[m, :] * r^3 * mean_d(x . g . dy)[m]
+ *   dg[d]    = sum_m dy[m, d] * x[m, d] * r[m]
+ * x, dy, dx [M, D] bf16, g [D] bf16, rstd [M] fp32, dg [D] fp32.  dx or dg may
+ * be NULL (not both).  fp32 arithmetic; the sums over rows are taken in a fixed
+ * order (results are reproducible).  workspace (only with dg):
+ * f8_workspace_bytes(M, D) bytes.  M and D multiples of 16.
+ */
+f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16,
+                         int64_t M, int64_t D, void* dx_bf16, float* dg, void* workspace,
+                         size_t workspace_bytes, void* stream);
 
 /*
  * Forward of the linear whose input is already quantised in saved->x (codes in

@@ -27,7 +27,8 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled",
            "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise",
            "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq",
-           "f8_silu_mul_bwd_quantise_delayed", "f8_linear_bwd_dyq"]
+           "f8_silu_mul_bwd_quantise_delayed", "f8_linear_bwd_dyq",
+           "f8_rope", "f8_transpose_bf16", "f8_add", "f8_rmsnorm_bwd"]
 
 
 class F8Error(RuntimeError):
@@ -94,6 +95,10 @@ def lib():
         l.f8_silu_mul_bwd_quantise_delayed.argtypes = [_p, _p, _i64, _i64, _int, _p, _i64, _p, C.POINTER(QTensorStruct),
                                                        _p, C.c_size_t, _p]
         l.f8_linear_bwd_dyq.argtypes = [C.POINTER(LinearDesc), C.POINTER(SavedStruct), _p, _p, _p]
+        l.f8_rope.argtypes = [_p, _i64, _i64, _i64, _i64, _i64, C.c_double, _int, _p, _i64, _p, _p]
+        l.f8_transpose_bf16.argtypes = [_p, _i64, _i64, _i64, _p, _p]
+        l.f8_add.argtypes = [_p, _p, _i64, _p, _p]
+        l.f8_rmsnorm_bwd.argtypes = [_p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
         _lib = l
@@ -328,3 +333,26 @@ def silu_mul_bwd_quantise_delayed(ab, dh, fmt, history, scale_t, q, workspace, s
 
 def linear_bwd_dyq(desc, saved, dX, dW, stream=None):
     _check(lib().f8_linear_bwd_dyq(C.byref(desc), C.byref(saved.struct()), _ptr(dX), _ptr(dW), _stream(stream)))
+
+
+# ---- the bf16 operations between the Float8 linears of a transformer block -----------
+
+def rope(x, S, n_heads, hd, out=None, out_t=None, theta=500000.0, inverse=False, stream=None):
+    """x, out: 2-D (possibly column slices of wider tensors: the row pitch is taken from stride(0))."""
+    M = x.shape[0]
+    _check(lib().f8_rope(_ptr(x), x.stride(0), M, S, n_heads, hd, float(theta), int(bool(inverse)), _ptr(out),
+                         out.stride(0) if out is not None else 0, _ptr(out_t), _stream(stream)))
+
+
+def transpose_bf16(x, out_t, stream=None):
+    _check(lib().f8_transpose_bf16(_ptr(x), x.stride(0), x.shape[0], x.shape[1], _ptr(out_t), _stream(stream)))
+
+
+def add(a, b, out, stream=None):
+    _check(lib().f8_add(_ptr(a), _ptr(b), a.numel(), _ptr(out), _stream(stream)))
+
+
+def rmsnorm_bwd(x, g, rstd, dy, dx, dg, workspace=None, stream=None):
+    M, D = x.shape
+    wp, wb = _ws(workspace)
+    _check(lib().f8_rmsnorm_bwd(_ptr(x), _ptr(g), _ptr(rstd), _ptr(dy), M, D, _ptr(dx), _ptr(dg), wp, wb, _stream(stream)))
