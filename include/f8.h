@@ -407,6 +407,23 @@ f8_status f8_transpose_bf16(const void* x_bf16, int64_t ldx, int64_t rows, int64
 f8_status f8_add(const void* a_bf16, const void* b_bf16, int64_t n, void* out_bf16, void* stream);
 
 /*
+ * Causal grouped-query attention of B sequences of S tokens (token m = b * S +
+ * position), Hq query heads, Hkv key/value heads (query head h reads key/value
+ * head h / (Hq / Hkv)), head dimension hd = 128:
+ *   O[q, h] = sum_k P[q, k] v[k],  P = softmax over k <= q of (q . k) / sqrt(hd)
+ * q [B*S, Hq*hd] (pitch ldq), k [B*S, Hkv*hd] (pitch ldk): bf16, after the
+ * rotary embedding; vt [Hkv*hd, B*S] packed: the values TRANSPOSED
+ * (f8_transpose_bf16 of v); o [B*S, Hq*hd] (pitch ldo) bf16; lse [Hq, B*S]
+ * fp32: the log of the softmax denominator (natural log, scaled scores), kept
+ * for the backward.  Scores and probabilities are never written: bf16 matrix
+ * instructions with fp32 accumulation, online softmax, probabilities rounded to
+ * bf16 before they multiply the values.  S and the pitches multiples of 8.
+ */
+f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64_t ldk, const void* vt_bf16,
+                      int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t hd, void* o_bf16,
+                      int64_t ldo, float* lse, void* stream);
+
+/*
  * Backward of f8_rmsnorm: with r = rstd[m] from the forward,
  *   dx[m, :] = r * (g . dy[m, :]) - x[m, :] * r^3 * mean_d(x . g . dy)[m]
  *   dg[d]    = sum_m dy[m, d] * x[m, d] * r[m]

@@ -1,0 +1,269 @@
+// Causal grouped-query attention in bf16 between the Float8 linears of a transformer block
+// (Section 2.2.2 keeps everything but the linear layers in bf16).  Flash-style: scores are never
+// written; bf16 MFMA (v_mfma_f32_32x32x16_bf16) with fp32 accumulation and an online softmax.
+//
+// Orientation.  Of a 32x32 MFMA result, a lane holds one column (the row index of the SECOND
+// operand) and 16 rows (row indices of the FIRST operand: 8 * (r / 4) + 4 * (lane / 32) + r % 4
+// for register r).  The kernels form S^T = K Q^T (keys along registers, one query per lane), so
+// the softmax statistics of a query live in one lane (plus its partner lane + 32), and the
+// probabilities are already laid out as the operand of the next product, whose contraction runs
+// over keys: 8 consecutive registers are the 8 contraction slots of a lane.  The other operand
+// only has to present the same keys in the same slots: it is read from a copy that is contiguous
+// along tokens (V^T here; Q^T, K^T, dO^T in the backward), which the producers write on the way
+// (f8_rope's transposed output, f8_transpose_bf16).  No operand is transposed in registers.
+#include "f8_device.hpp"
+#include "f8_host.hpp"
+
+namespace f8 {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kAttnThreads = 256;
+constexpr int kHd = 128;   // head dimension of every model the paper trains
+constexpr int kBq = 128;   // queries per block: 32 per wave
+constexpr int kBk = 64;    // keys per step
+constexpr int kKp = kHd + 8;   // LDS row pitch (bf16) of a [tokens][hd] tile: 272 bytes
+constexpr int kTp = kBk + 8;   // LDS row pitch (bf16) of a [hd][tokens] tile: 144 bytes
+
+__device__ inline f32x16 mma(uint4 first, uint4 second, f32x16 acc)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, first), __builtin_bit_cast(bf16x8, second), acc,
+                                                   0, 0, 0);
+}
+
+__device__ inline uint32_t pack2(float lo, float hi)
+{
+    // v_cvt_pk_bf16_f32: round to nearest even
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 r = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, r);
+}
+
+// registers 8u .. 8u+7 of an accumulator as a bf16 operand (8 contraction slots)
+__device__ inline uint4 slots(const f32x16& c, int u)
+{
+    return make_uint4(pack2(c[8 * u], c[8 * u + 1]), pack2(c[8 * u + 2], c[8 * u + 3]), pack2(c[8 * u + 4], c[8 * u + 5]),
+                      pack2(c[8 * u + 6], c[8 * u + 7]));
+}
+
+// the operand that matches slots(c, u) of a 32-token block starting at column t0 of a
+// [rows][tokens] LDS tile: tokens t0 + 16u + 4g + {0..3} and t0 + 16u + 8 + 4g + {0..3}
+__device__ inline uint4 token_slots(const uint16_t* tile_row, int t0, int u, int g)
+{
+    const uint2 a = *reinterpret_cast<const uint2*>(tile_row + t0 + 16 * u + 4 * g);
+    const uint2 b = *reinterpret_cast<const uint2*>(tile_row + t0 + 16 * u + 8 + 4 * g);
+    return make_uint4(a.x, a.y, b.x, b.y);
+}
+
+// Tile loaders: global -> registers (issued early) -> LDS (after the barrier that frees it).
+// [ROWS tokens][kHd] from a token-major tensor; rows at or beyond `limit` read as zero.
+template <int ROWS>
+struct RowTile {
+    static constexpr int N = ROWS * (kHd / 8) / kAttnThreads;
+    uint4 v[N];
+    __device__ void load(const uint16_t* base, int64_t ld, int row0, int limit)
+    {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = threadIdx.x + kAttnThreads * i, r = c / (kHd / 8), cc = c % (kHd / 8);
+            v[i] = (row0 + r < limit) ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + r) * ld + cc * 8) : make_uint4(0, 0, 0, 0);
+        }
+    }
+    __device__ void store(uint16_t* lds) const
+    {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = threadIdx.x + kAttnThreads * i, r = c / (kHd / 8), cc = c % (kHd / 8);
+            *reinterpret_cast<uint4*>(lds + r * kKp + cc * 8) = v[i];
+        }
+    }
+};
+// [kHd][COLS tokens] from a transposed (token-minor) tensor with row pitch ld; columns at or beyond
+// `limit` read as zero (limit and col0 are multiples of 8).
+template <int COLS>
+struct ColTile {
+    static constexpr int N = kHd * (COLS / 8) / kAttnThreads;
+    static constexpr int P = COLS + 8;
+    uint4 v[N];
+    __device__ void load(const uint16_t* base, int64_t ld, int col0, int limit)
+    {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = threadIdx.x + kAttnThreads * i, r = c / (COLS / 8), cc = c % (COLS / 8);
+            v[i] = (col0 + cc * 8 < limit) ? *reinterpret_cast<const uint4*>(base + (int64_t)r * ld + col0 + cc * 8) : make_uint4(0, 0, 0, 0);
+        }
+    }
+    __device__ void store(uint16_t* lds) const
+    {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int c = threadIdx.x + kAttnThreads * i, r = c / (COLS / 8), cc = c % (COLS / 8);
+            *reinterpret_cast<uint4*>(lds + r * P + cc * 8) = v[i];
+        }
+    }
+};
+
+// ---- forward ------------------------------------------------------------------------------
+// One block: 128 queries of one (sequence, head); each wave owns 32 of them.  Loop over 64-key
+// steps up to the diagonal; K and V^T tiles double-buffered in LDS.
+__global__ __launch_bounds__(kAttnThreads) void sdpa_fwd_kernel(const uint16_t* __restrict__ Q, int64_t ldq,
+                                                                const uint16_t* __restrict__ K, int64_t ldk,
+                                                                const uint16_t* __restrict__ Vt, int64_t M, int S, int Hq,
+                                                                int group, float scale_log2e, uint16_t* __restrict__ O,
+                                                                int64_t ldo, float* __restrict__ lse, int nqt)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t sK[2][kBk * kKp];
+    __shared__ __attribute__((aligned(16))) uint16_t sV[2][kHd * kTp];
+
+    const int qt = nqt - 1 - (int)(blockIdx.x % nqt);  // long (late) query tiles first
+    const int bh = blockIdx.x / nqt, h = bh % Hq, b = bh / Hq, kvh = h / group;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
+    const int q_first = qt * kBq + wave * 32;  // of this wave
+    const int q_pos = q_first + ln;            // position of this lane's query in its sequence
+    const int64_t tok0 = (int64_t)b * S;
+    const uint16_t* Kb = K + tok0 * ldk + (int64_t)kvh * kHd;
+    const uint16_t* Vb = Vt + (int64_t)kvh * kHd * M + tok0;
+
+    uint4 qf[kHd / 16];
+    {
+        const bool ok = q_pos < S;
+        const uint16_t* row = Q + (tok0 + (ok ? q_pos : 0)) * ldq + (int64_t)h * kHd + 8 * g;
+#pragma unroll
+        for (int s = 0; s < kHd / 16; ++s) qf[s] = ok ? *reinterpret_cast<const uint4*>(row + 16 * s) : make_uint4(0, 0, 0, 0);
+    }
+
+    int key_end = (qt + 1) * kBq;  // keys at or beyond it are masked for every query of the block
+    if (key_end > S) key_end = S;
+    const int nkt = (key_end + kBk - 1) / kBk;
+
+    f32x16 acc_o[kHd / 32];
+#pragma unroll
+    for (int d = 0; d < kHd / 32; ++d) acc_o[d] = f32x16{0};
+    float m_run = -INFINITY, l_run = 0.0f;  // running maximum (log2 domain) and this lane's share of the sum
+
+    RowTile<kBk> kt_regs;
+    ColTile<kBk> vt_regs;
+    kt_regs.load(Kb, ldk, 0, S);
+    vt_regs.load(Vb, M, 0, S);
+    for (int t = 0; t < nkt; ++t) {
+        const int buf = t & 1, key0 = t * kBk;
+        kt_regs.store(sK[buf]);
+        vt_regs.store(sV[buf]);
+        __syncthreads();
+        if (t + 1 < nkt) {
+            kt_regs.load(Kb, ldk, key0 + kBk, S);
+            vt_regs.load(Vb, M, key0 + kBk, S);
+        }
+        if (key0 > q_first + 31) continue;  // every key of the step lies after every query of the wave
+
+        // S^T = K Q^T: [64 keys][32 queries] as two 32x32 results
+        f32x16 sc[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            sc[kb] = f32x16{0};
+#pragma unroll
+            for (int s = 0; s < kHd / 16; ++s) {
+                const uint4 kf = *reinterpret_cast<const uint4*>(&sK[buf][(32 * kb + ln) * kKp + 16 * s + 8 * g]);
+                sc[kb] = mma(kf, qf[s], sc[kb]);
+            }
+        }
+        const bool diagonal = key0 + kBk - 1 > q_first;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float v = sc[kb][r] * scale_log2e;
+                if (diagonal) {
+                    const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (key > q_pos) v = -INFINITY;
+                }
+                sc[kb][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float p = __builtin_amdgcn_exp2f(sc[kb][r] - m_new);
+                sc[kb][r] = p;
+                psum += p;
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int d = 0; d < kHd / 32; ++d)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc_o[d][r] *= alpha;
+
+        // O^T += V^T P^T: [128 hd][32 queries], contraction over the 64 keys in four 16-slot steps
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint4 pf = slots(sc[kb], u);
+#pragma unroll
+                for (int d = 0; d < kHd / 32; ++d) {
+                    const uint4 vf = token_slots(&sV[buf][(32 * d + ln) * kTp], 32 * kb, u, g);
+                    acc_o[d] = mma(vf, pf, acc_o[d]);
+                }
+            }
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    if (q_pos < S) {
+        const float inv = 1.0f / l_tot;
+        uint16_t* orow = O + (tok0 + q_pos) * ldo + (int64_t)h * kHd + 4 * g;
+#pragma unroll
+        for (int d = 0; d < kHd / 32; ++d)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint2 w = make_uint2(pack2(acc_o[d][4 * j] * inv, acc_o[d][4 * j + 1] * inv),
+                                           pack2(acc_o[d][4 * j + 2] * inv, acc_o[d][4 * j + 3] * inv));
+                *reinterpret_cast<uint2*>(orow + 32 * d + 8 * j) = w;
+            }
+        if (g == 0) lse[(int64_t)h * M + tok0 + q_pos] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+    }
+}
+
+static f8_status check_attn(const void* q, int64_t ldq, const void* k, int64_t ldk, int64_t B, int64_t S, int64_t Hq,
+                            int64_t Hkv, int64_t hd)
+{
+    if (!q || !k) return F8_ERR_NULL;
+    if (hd != kHd || B < 0 || S < 0 || (S % 8) || Hq < 1 || Hkv < 1 || (Hq % Hkv)) return F8_ERR_SHAPE;
+    if (S >= (1 << 24) || Hq >= (1 << 16) || B * S >= ((int64_t)1 << 31)) return F8_ERR_SHAPE;
+    if (ldq < Hq * hd || ldk < Hkv * hd || (ldq % 8) || (ldk % 8)) return F8_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k)) return F8_ERR_ALIGN;
+    return F8_OK;
+}
+
+}  // namespace f8
+
+using namespace f8;
+
+extern "C" {
+
+f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64_t ldk, const void* vt_bf16, int64_t B,
+                      int64_t S, int64_t Hq, int64_t Hkv, int64_t hd, void* o_bf16, int64_t ldo, float* lse, void* stream)
+{
+    f8_status s = check_attn(q_bf16, ldq, k_bf16, ldk, B, S, Hq, Hkv, hd);
+    if (s != F8_OK) return s;
+    if (!vt_bf16 || !o_bf16 || !lse) return F8_ERR_NULL;
+    if (ldo < Hq * hd || (ldo % 8)) return F8_ERR_SHAPE;
+    if (!aligned16(vt_bf16) || !aligned16(o_bf16)) return F8_ERR_ALIGN;
+    if (B == 0 || S == 0) return F8_OK;
+    const int64_t nqt = (S + kBq - 1) / kBq, nb = nqt * Hq * B;
+    if (nb > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
+    const float scale_log2e = (float)(1.4426950408889634074 / sqrt((double)hd));
+    sdpa_fwd_kernel<<<(unsigned)nb, kAttnThreads, 0, (hipStream_t)stream>>>(
+        (const uint16_t*)q_bf16, ldq, (const uint16_t*)k_bf16, ldk, (const uint16_t*)vt_bf16, B * S, (int)S, (int)Hq,
+        (int)(Hq / Hkv), scale_log2e, (uint16_t*)o_bf16, ldo, lse, (int)nqt);
+    return last_launch_status();
+}
+
+}  // extern "C"

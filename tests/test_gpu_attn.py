@@ -1,0 +1,102 @@
+"""Causal grouped-query attention (forward and backward) through the C ABI against
+oracle/block_oracle.py."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as o
+from oracle import block_oracle as bo
+from paper_2410_06511_amd import f8
+from paper_2410_06511_amd import workloads as wl
+from helpers import bits
+
+pytestmark = pytest.mark.gpu
+HD = 128
+
+
+def gen(shape, seed, std=1.0):
+    g = torch.Generator("cpu")
+    g.manual_seed(seed)
+    return wl.randn_bf16(shape, std, 0, generator=g)
+
+
+def f64(t_bits):
+    return o.bf16_to_f32(t_bits).astype(np.float64)
+
+
+class Attn:
+    """Device buffers and the call sequence: q, k, v are column slices of one [M, (Hq + 2 Hkv) hd]
+    tensor, as they are slices of the fused q|k|v linear's output."""
+
+    def __init__(self, B, S, Hq, Hkv, seed, std=1.0):
+        self.B, self.S, self.Hq, self.Hkv = B, S, Hq, Hkv
+        M = B * S
+        self.qkv = gen((M, (Hq + 2 * Hkv) * HD), seed, std)
+        d = self.qkv.cuda()
+        self.q, self.k, self.v = d[:, :Hq * HD], d[:, Hq * HD:(Hq + Hkv) * HD], d[:, (Hq + Hkv) * HD:]
+        bf = dict(dtype=torch.bfloat16, device="cuda")
+        self.vt = torch.empty((Hkv * HD, M), **bf)
+        self.o = torch.empty((M, Hq * HD), **bf)
+        self.lse = torch.empty((Hq, M), device="cuda")
+
+    def host_bits(self):
+        b = bits(self.qkv)
+        Hq, Hkv = self.Hq, self.Hkv
+        return b[:, :Hq * HD], b[:, Hq * HD:(Hq + Hkv) * HD], b[:, (Hq + Hkv) * HD:]
+
+    def forward(self):
+        f8.transpose_bf16(self.v, self.vt)
+        f8.sdpa_fwd(self.q, self.k, self.vt, self.B, self.S, self.Hq, self.Hkv, HD, self.o, self.lse)
+        torch.cuda.synchronize()
+
+
+def check_forward(a):
+    qb, kb, vb = a.host_bits()
+    B, S, Hq, Hkv = a.B, a.S, a.Hq, a.Hkv
+    ref, lse = bo.sdpa_f64(f64(qb), f64(kb), f64(vb), B, S, Hq, Hkv, HD)
+    # the probabilities are rounded to bf16 (2^-9 each, relative), so is the output: the error of
+    # an output is bounded by 2^-8 of the probability-weighted mean of |v|; twice that is allowed
+    weight, _ = bo.sdpa_f64(f64(qb), f64(kb), np.abs(f64(vb)), B, S, Hq, Hkv, HD)
+    got = f64(bits(a.o))
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref)
+    assert (err <= 2.0 ** -7 * weight + 1e-30).all(), (err.max(), np.unravel_index(err.argmax(), err.shape))
+    assert err.mean() <= 2.0 ** -10 * weight.mean()
+    got_lse = a.lse.cpu().numpy().astype(np.float64).reshape(Hq, B, S).transpose(1, 0, 2)
+    assert np.abs(got_lse - lse).max() <= 1e-4 * (1.0 + np.abs(lse).max())
+
+
+@pytest.mark.parametrize("B,S,Hq,Hkv", [(1, 8, 1, 1), (1, 128, 2, 1), (2, 200, 4, 2), (1, 520, 8, 2), (3, 64, 2, 2)])
+def test_sdpa_forward(B, S, Hq, Hkv):
+    a = Attn(B, S, Hq, Hkv, seed=S + Hq)
+    a.forward()
+    check_forward(a)
+
+
+def test_sdpa_forward_peaked_scores_and_first_token():
+    """Large scores (a softmax close to one-hot, running maximum that keeps moving) and the first
+    token of each sequence, which attends to itself only: its output is its value, bit for bit."""
+    a = Attn(2, 264, 2, 1, seed=3, std=4.0)
+    a.forward()
+    check_forward(a)
+    vb = a.host_bits()[2]
+    got = bits(a.o)
+    for b in range(2):
+        for h in range(2):
+            assert np.array_equal(got[b * 264, h * HD:(h + 1) * HD], vb[b * 264, :HD])
+
+
+def test_sdpa_argument_errors():
+    a = Attn(1, 64, 2, 1, seed=1)
+    with pytest.raises(f8.F8Error) as e:
+        f8.sdpa_fwd(a.q, a.k, a.vt, 1, 64, 2, 1, 64, a.o, a.lse)       # head dimension other than 128
+    assert e.value.code == 2
+    with pytest.raises(f8.F8Error) as e:
+        f8.sdpa_fwd(a.q, a.k, a.vt, 1, 60, 2, 1, HD, a.o, a.lse)       # S not a multiple of 8
+    assert e.value.code == 2
+    with pytest.raises(f8.F8Error) as e:
+        f8.sdpa_fwd(a.q, a.k, a.vt, 1, 64, 3, 2, HD, a.o, a.lse)       # heads do not group
+    assert e.value.code == 2
+    with pytest.raises(f8.F8Error) as e:
+        f8.sdpa_fwd(a.q, a.k, None, 1, 64, 2, 1, HD, a.o, a.lse)
+    assert e.value.code == 1
