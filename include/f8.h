@@ -424,6 +424,27 @@ f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64
                       int64_t ldo, float* lse, void* stream);
 
 /*
+ * Backward of f8_sdpa_fwd.  With P recomputed from lse and delta[q] = sum_d dO O:
+ *   dV = P^T dO,  dP = dO V^T,  dS = P (dP - delta),
+ *   dQ = dS K / sqrt(hd),  dK = dS^T Q / sqrt(hd)
+ * (the gradients of the query heads that share a key/value head are summed).
+ * Token-major inputs: q, k, v, o, do (with their pitches); the copies that are
+ * contiguous along tokens, packed with pitch B*S: qt [Hq*hd, B*S], kt
+ * [Hkv*hd, B*S] (f8_rope's transposed outputs) and dot [Hq*hd, B*S]
+ * (f8_transpose_bf16 of do); lse from the forward.  Outputs: dq [B*S, Hq*hd],
+ * dk, dv [B*S, Hkv*hd] bf16 with their pitches (dq and dk are gradients of the
+ * ROTATED q and k: f8_rope with inverse != 0 turns them back), and delta
+ * [Hq, B*S] fp32, scratch that the call fills.  No atomics: results are
+ * reproducible.  dS and P are rounded to bf16 before they enter a product.
+ */
+f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, const void* k_bf16, int64_t ldk,
+                      const void* kt_bf16, const void* v_bf16, int64_t ldv, const void* o_bf16,
+                      int64_t ldo, const void* do_bf16, int64_t lddo, const void* dot_bf16,
+                      const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t hd,
+                      void* dq_bf16, int64_t lddq, void* dk_bf16, int64_t lddk, void* dv_bf16,
+                      int64_t lddv, float* delta, void* stream);
+
+/*
  * Backward of f8_rmsnorm: with r = rstd[m] from the forward,
  *   dx[m, :] = r * (g . dy[m, :]) - x[m, :] * r^3 * mean_d(x . g . dy)[m]
  *   dg[d]    = sum_m dy[m, d] * x[m, d] * r[m]

@@ -231,6 +231,252 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_fwd_kernel(const uint16_t* 
     }
 }
 
+// ---- backward -----------------------------------------------------------------------------
+// With P = exp(S / sqrt(hd) - lse) recomputed from the saved lse and delta[q] = sum_d dO O:
+//   dV = P^T dO,  dP = dO V^T,  dS = P (dP - delta),  dQ = dS K / sqrt(hd),  dK = dS^T Q / sqrt(hd)
+// Two kernels, neither with atomics: dQ per query tile (loop over keys, S^T orientation, which
+// also produces delta), then dK and dV per key tile (loop over the queries of every query head
+// of the group, S orientation: one key per lane).
+
+// dQ^T = K^T dS^T.  Per 64-key step: S^T = K Q^T, dP^T = V dO^T, dS^T, then the product over keys.
+__global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dq_kernel(
+    const uint16_t* __restrict__ Q, int64_t ldq, const uint16_t* __restrict__ K, int64_t ldk, const uint16_t* __restrict__ Kt,
+    const uint16_t* __restrict__ V, int64_t ldv, const uint16_t* __restrict__ O, int64_t ldo, const uint16_t* __restrict__ dO,
+    int64_t lddo, const float* __restrict__ lse, int64_t M, int S, int Hq, int group, float scale_log2e, float scale,
+    uint16_t* __restrict__ dQ, int64_t lddq, float* __restrict__ delta, int nqt)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t* sK = smem;                       // [2][kBk * kKp]
+    uint16_t* sV = sK + 2 * kBk * kKp;         // [2][kBk * kKp]
+    uint16_t* sKt = sV + 2 * kBk * kKp;        // [2][kHd * kTp]
+
+    const int qt = nqt - 1 - (int)(blockIdx.x % nqt);
+    const int bh = blockIdx.x / nqt, h = bh % Hq, b = bh / Hq, kvh = h / group;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
+    const int q_first = qt * kBq + wave * 32, q_pos = q_first + ln;
+    const int64_t tok0 = (int64_t)b * S;
+    const uint16_t* Kb = K + tok0 * ldk + (int64_t)kvh * kHd;
+    const uint16_t* Vb = V + tok0 * ldv + (int64_t)kvh * kHd;
+    const uint16_t* Ktb = Kt + (int64_t)kvh * kHd * M + tok0;
+    const bool q_ok = q_pos < S;
+    const int64_t tok = tok0 + (q_ok ? q_pos : 0);
+
+    uint4 qf[kHd / 16], dof[kHd / 16];
+    float dl = 0.0f;
+    {
+        const uint16_t* qrow = Q + tok * ldq + (int64_t)h * kHd + 8 * g;
+        const uint16_t* drow = dO + tok * lddo + (int64_t)h * kHd + 8 * g;
+        const uint16_t* orow = O + tok * ldo + (int64_t)h * kHd + 8 * g;
+#pragma unroll
+        for (int s = 0; s < kHd / 16; ++s) {
+            qf[s] = q_ok ? *reinterpret_cast<const uint4*>(qrow + 16 * s) : make_uint4(0, 0, 0, 0);
+            dof[s] = q_ok ? *reinterpret_cast<const uint4*>(drow + 16 * s) : make_uint4(0, 0, 0, 0);
+            const uint4 ov = q_ok ? *reinterpret_cast<const uint4*>(orow + 16 * s) : make_uint4(0, 0, 0, 0);
+            const uint32_t dw[4] = {dof[s].x, dof[s].y, dof[s].z, dof[s].w}, ow[4] = {ov.x, ov.y, ov.z, ov.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dl += bf16_lo(dw[j]) * bf16_lo(ow[j]) + bf16_hi(dw[j]) * bf16_hi(ow[j]);
+        }
+    }
+    dl += __shfl_xor(dl, 32, kWave);
+    if (q_ok && g == 0) delta[(int64_t)h * M + tok] = dl;
+    const float lse2 = q_ok ? lse[(int64_t)h * M + tok] * 1.4426950408889634074f : 0.0f;
+
+    int key_end = (qt + 1) * kBq;
+    if (key_end > S) key_end = S;
+    const int nkt = (key_end + kBk - 1) / kBk;
+
+    f32x16 acc[kHd / 32];
+#pragma unroll
+    for (int d = 0; d < kHd / 32; ++d) acc[d] = f32x16{0};
+
+    RowTile<kBk> k_regs, v_regs;
+    ColTile<kBk> kt_regs;
+    k_regs.load(Kb, ldk, 0, S);
+    v_regs.load(Vb, ldv, 0, S);
+    kt_regs.load(Ktb, M, 0, S);
+    for (int t = 0; t < nkt; ++t) {
+        const int buf = t & 1, key0 = t * kBk;
+        k_regs.store(sK + buf * kBk * kKp);
+        v_regs.store(sV + buf * kBk * kKp);
+        kt_regs.store(sKt + buf * kHd * kTp);
+        __syncthreads();
+        if (t + 1 < nkt) {
+            k_regs.load(Kb, ldk, key0 + kBk, S);
+            v_regs.load(Vb, ldv, key0 + kBk, S);
+            kt_regs.load(Ktb, M, key0 + kBk, S);
+        }
+        if (key0 > q_first + 31) continue;
+        const uint16_t *tK = sK + buf * kBk * kKp, *tV = sV + buf * kBk * kKp, *tKt = sKt + buf * kHd * kTp;
+        const bool diagonal = key0 + kBk - 1 > q_first;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {  // one 32-key block at a time
+            f32x16 sc = f32x16{0}, dp = f32x16{0};
+#pragma unroll
+            for (int s = 0; s < kHd / 16; ++s) {
+                const uint4 kf = *reinterpret_cast<const uint4*>(tK + (32 * kb + ln) * kKp + 16 * s + 8 * g);
+                const uint4 vf = *reinterpret_cast<const uint4*>(tV + (32 * kb + ln) * kKp + 16 * s + 8 * g);
+                sc = mma(kf, qf[s], sc);
+                dp = mma(vf, dof[s], dp);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - lse2);
+                if (diagonal) {
+                    const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (key > q_pos) p = 0.0f;
+                }
+                sc[r] = p * (dp[r] - dl);
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint4 df = slots(sc, u);
+#pragma unroll
+                for (int d = 0; d < kHd / 32; ++d) acc[d] = mma(token_slots(tKt + (32 * d + ln) * kTp, 32 * kb, u, g), df, acc[d]);
+            }
+        }
+    }
+    if (q_ok) {
+        uint16_t* row = dQ + tok * lddq + (int64_t)h * kHd + 4 * g;
+#pragma unroll
+        for (int d = 0; d < kHd / 32; ++d)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<uint2*>(row + 32 * d + 8 * j) =
+                    make_uint2(pack2(acc[d][4 * j] * scale, acc[d][4 * j + 1] * scale),
+                               pack2(acc[d][4 * j + 2] * scale, acc[d][4 * j + 3] * scale));
+    }
+}
+
+// dK^T = Q^T dS, dV^T = dO^T P.  One block: 128 keys of one (sequence, key/value head), 32 per
+// wave, one key per lane; loop over 64-query steps from the diagonal on, for every query head of
+// the group.
+__global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dkv_kernel(
+    const uint16_t* __restrict__ Q, int64_t ldq, const uint16_t* __restrict__ Qt, const uint16_t* __restrict__ K, int64_t ldk,
+    const uint16_t* __restrict__ V, int64_t ldv, const uint16_t* __restrict__ dO, int64_t lddo, const uint16_t* __restrict__ dOt,
+    const float* __restrict__ lse, const float* __restrict__ delta, int64_t M, int S, int Hkv, int group, float scale_log2e,
+    float scale, uint16_t* __restrict__ dK, int64_t lddk, uint16_t* __restrict__ dV, int64_t lddv, int nkt)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+    uint16_t* sQ = smem;                        // [2][kBk * kKp]   (kBk = queries per step here)
+    uint16_t* sD = sQ + 2 * kBk * kKp;          // [2][kBk * kKp]
+    uint16_t* sQt = sD + 2 * kBk * kKp;         // [2][kHd * kTp]
+    uint16_t* sDt = sQt + 2 * kHd * kTp;        // [2][kHd * kTp]
+    float* sLse = reinterpret_cast<float*>(sDt + 2 * kHd * kTp);  // [2][kBk], already times log2(e)
+    float* sDel = sLse + 2 * kBk;                                // [2][kBk]
+
+    const int kt = blockIdx.x % nkt;  // early key tiles see the most queries and come first
+    const int bk = blockIdx.x / nkt, kvh = bk % Hkv, b = bk / Hkv;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
+    const int key_first = kt * kBq + wave * 32, key_pos = key_first + ln;
+    const int64_t tok0 = (int64_t)b * S;
+    const bool k_ok = key_pos < S;
+    const int64_t tok = tok0 + (k_ok ? key_pos : 0);
+
+    uint4 kf[kHd / 16], vf[kHd / 16];
+    {
+        const uint16_t* krow = K + tok * ldk + (int64_t)kvh * kHd + 8 * g;
+        const uint16_t* vrow = V + tok * ldv + (int64_t)kvh * kHd + 8 * g;
+#pragma unroll
+        for (int s = 0; s < kHd / 16; ++s) {
+            kf[s] = k_ok ? *reinterpret_cast<const uint4*>(krow + 16 * s) : make_uint4(0, 0, 0, 0);
+            vf[s] = k_ok ? *reinterpret_cast<const uint4*>(vrow + 16 * s) : make_uint4(0, 0, 0, 0);
+        }
+    }
+    f32x16 acc_k[kHd / 32], acc_v[kHd / 32];
+#pragma unroll
+    for (int d = 0; d < kHd / 32; ++d) acc_k[d] = f32x16{0}, acc_v[d] = f32x16{0};
+
+    const int q_start = kt * kBq;                       // a multiple of the 64-query step
+    const int nqs = (S - q_start + kBk - 1) / kBk;      // >= 1: the block exists only if q_start < S
+    const int steps = nqs * group;
+
+    RowTile<kBk> q_regs, d_regs;
+    ColTile<kBk> qt_regs, dt_regs;
+    float stat_reg = 0.0f;  // threads 0..63: lse of query threadIdx.x of the step; 64..127: delta
+    auto load_step = [&](int it) {
+        const int hq = kvh * group + it / nqs, q0 = q_start + (it % nqs) * kBk;
+        q_regs.load(Q + tok0 * ldq + (int64_t)hq * kHd, ldq, q0, S);
+        d_regs.load(dO + tok0 * lddo + (int64_t)hq * kHd, lddo, q0, S);
+        qt_regs.load(Qt + (int64_t)hq * kHd * M + tok0, M, q0, S);
+        dt_regs.load(dOt + (int64_t)hq * kHd * M + tok0, M, q0, S);
+        if (threadIdx.x < 2 * kBk) {
+            const int i = threadIdx.x & (kBk - 1);
+            const float* src = threadIdx.x < kBk ? lse : delta;
+            stat_reg = (q0 + i < S) ? src[(int64_t)hq * M + tok0 + q0 + i] : 0.0f;
+            if (threadIdx.x < kBk) stat_reg *= 1.4426950408889634074f;
+        }
+    };
+    load_step(0);
+    for (int it = 0; it < steps; ++it) {
+        const int buf = it & 1, q0 = q_start + (it % nqs) * kBk;
+        q_regs.store(sQ + buf * kBk * kKp);
+        d_regs.store(sD + buf * kBk * kKp);
+        qt_regs.store(sQt + buf * kHd * kTp);
+        dt_regs.store(sDt + buf * kHd * kTp);
+        if (threadIdx.x < kBk) sLse[buf * kBk + threadIdx.x] = stat_reg;
+        else if (threadIdx.x < 2 * kBk) sDel[buf * kBk + threadIdx.x - kBk] = stat_reg;
+        __syncthreads();
+        if (it + 1 < steps) load_step(it + 1);
+        if (q0 + kBk - 1 < key_first) continue;  // every query of the step lies before every key of the wave
+        const uint16_t *tQ = sQ + buf * kBk * kKp, *tD = sD + buf * kBk * kKp;
+        const uint16_t *tQt = sQt + buf * kHd * kTp, *tDt = sDt + buf * kHd * kTp;
+        // one 32-query block at a time; registers: queries 32 qb + 8 j + 4 g + i of the step; lane: one key
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            f32x16 sc = f32x16{0}, dp = f32x16{0};
+#pragma unroll
+            for (int s = 0; s < kHd / 16; ++s) {
+                const uint4 qfr = *reinterpret_cast<const uint4*>(tQ + (32 * qb + ln) * kKp + 16 * s + 8 * g);
+                const uint4 dfr = *reinterpret_cast<const uint4*>(tD + (32 * qb + ln) * kKp + 16 * s + 8 * g);
+                sc = mma(qfr, kf[s], sc);
+                dp = mma(dfr, vf[s], dp);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int ql = 32 * qb + 8 * j + 4 * g;
+                const float4 l4 = *reinterpret_cast<const float4*>(sLse + buf * kBk + ql);
+                const float4 d4 = *reinterpret_cast<const float4*>(sDel + buf * kBk + ql);
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int r = 4 * j + i, qp = q0 + ql + i;
+                    float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - lv[i]);
+                    if (key_pos > qp || qp >= S) p = 0.0f;
+                    sc[r] = p;
+                    dp[r] = p * (dp[r] - dv[i]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint4 pf = slots(sc, u), df = slots(dp, u);
+#pragma unroll
+                for (int d = 0; d < kHd / 32; ++d) {
+                    acc_v[d] = mma(token_slots(tDt + (32 * d + ln) * kTp, 32 * qb, u, g), pf, acc_v[d]);
+                    acc_k[d] = mma(token_slots(tQt + (32 * d + ln) * kTp, 32 * qb, u, g), df, acc_k[d]);
+                }
+            }
+        }
+    }
+    if (k_ok) {
+        uint16_t* krow = dK + tok * lddk + (int64_t)kvh * kHd + 4 * g;
+        uint16_t* vrow = dV + tok * lddv + (int64_t)kvh * kHd + 4 * g;
+#pragma unroll
+        for (int d = 0; d < kHd / 32; ++d)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                *reinterpret_cast<uint2*>(krow + 32 * d + 8 * j) =
+                    make_uint2(pack2(acc_k[d][4 * j] * scale, acc_k[d][4 * j + 1] * scale),
+                               pack2(acc_k[d][4 * j + 2] * scale, acc_k[d][4 * j + 3] * scale));
+                *reinterpret_cast<uint2*>(vrow + 32 * d + 8 * j) =
+                    make_uint2(pack2(acc_v[d][4 * j], acc_v[d][4 * j + 1]), pack2(acc_v[d][4 * j + 2], acc_v[d][4 * j + 3]));
+            }
+    }
+}
+
+constexpr size_t kDqLds = (size_t)(4 * kBk * kKp + 2 * kHd * kTp) * sizeof(uint16_t);
+constexpr size_t kDkvLds = (size_t)(4 * kBk * kKp + 4 * kHd * kTp) * sizeof(uint16_t) + 4 * kBk * sizeof(float);
+static_assert(kDkvLds <= 160 * 1024, "the key/value gradient kernel's tiles fit the LDS of a compute unit");
+
 static f8_status check_attn(const void* q, int64_t ldq, const void* k, int64_t ldk, int64_t B, int64_t S, int64_t Hq,
                             int64_t Hkv, int64_t hd)
 {
@@ -263,6 +509,48 @@ f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64
     sdpa_fwd_kernel<<<(unsigned)nb, kAttnThreads, 0, (hipStream_t)stream>>>(
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)k_bf16, ldk, (const uint16_t*)vt_bf16, B * S, (int)S, (int)Hq,
         (int)(Hq / Hkv), scale_log2e, (uint16_t*)o_bf16, ldo, lse, (int)nqt);
+    return last_launch_status();
+}
+
+f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, const void* k_bf16, int64_t ldk,
+                      const void* kt_bf16, const void* v_bf16, int64_t ldv, const void* o_bf16, int64_t ldo,
+                      const void* do_bf16, int64_t lddo, const void* dot_bf16, const float* lse, int64_t B, int64_t S,
+                      int64_t Hq, int64_t Hkv, int64_t hd, void* dq_bf16, int64_t lddq, void* dk_bf16, int64_t lddk,
+                      void* dv_bf16, int64_t lddv, float* delta, void* stream)
+{
+    f8_status s = check_attn(q_bf16, ldq, k_bf16, ldk, B, S, Hq, Hkv, hd);
+    if (s != F8_OK) return s;
+    if (!qt_bf16 || !kt_bf16 || !v_bf16 || !o_bf16 || !do_bf16 || !dot_bf16 || !lse || !dq_bf16 || !dk_bf16 || !dv_bf16 || !delta)
+        return F8_ERR_NULL;
+    const int64_t wq = Hq * hd, wk = Hkv * hd;
+    if (ldv < wk || ldo < wq || lddo < wq || lddq < wq || lddk < wk || lddv < wk || (ldv % 8) || (ldo % 8) || (lddo % 8) ||
+        (lddq % 8) || (lddk % 8) || (lddv % 8))
+        return F8_ERR_SHAPE;
+    if (!aligned16(qt_bf16) || !aligned16(kt_bf16) || !aligned16(v_bf16) || !aligned16(o_bf16) || !aligned16(do_bf16) ||
+        !aligned16(dot_bf16) || !aligned16(dq_bf16) || !aligned16(dk_bf16) || !aligned16(dv_bf16))
+        return F8_ERR_ALIGN;
+    if (B == 0 || S == 0) return F8_OK;
+    static bool configured = false;
+    if (!configured) {
+        // more dynamic LDS than the default limit of a launch: raise it once per process
+        if (hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) != hipSuccess ||
+            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkvLds) != hipSuccess)
+            return F8_ERR_LAUNCH;
+        configured = true;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t M = B * S, nt = (S + kBq - 1) / kBq;
+    if (nt * Hq * B > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
+    const double sc = 1.0 / sqrt((double)hd);
+    const float scale = (float)sc, scale_log2e = (float)(sc * 1.4426950408889634074);
+    sdpa_bwd_dq_kernel<<<(unsigned)(nt * Hq * B), kAttnThreads, kDqLds, st>>>(
+        (const uint16_t*)q_bf16, ldq, (const uint16_t*)k_bf16, ldk, (const uint16_t*)kt_bf16, (const uint16_t*)v_bf16, ldv,
+        (const uint16_t*)o_bf16, ldo, (const uint16_t*)do_bf16, lddo, lse, M, (int)S, (int)Hq, (int)(Hq / Hkv), scale_log2e, scale,
+        (uint16_t*)dq_bf16, lddq, delta, (int)nt);
+    sdpa_bwd_dkv_kernel<<<(unsigned)(nt * Hkv * B), kAttnThreads, kDkvLds, st>>>(
+        (const uint16_t*)q_bf16, ldq, (const uint16_t*)qt_bf16, (const uint16_t*)k_bf16, ldk, (const uint16_t*)v_bf16, ldv,
+        (const uint16_t*)do_bf16, lddo, (const uint16_t*)dot_bf16, lse, delta, M, (int)S, (int)Hkv, (int)(Hq / Hkv), scale_log2e,
+        scale, (uint16_t*)dk_bf16, lddk, (uint16_t*)dv_bf16, lddv, (int)nt);
     return last_launch_status();
 }
 

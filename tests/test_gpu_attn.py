@@ -86,6 +86,59 @@ def test_sdpa_forward_peaked_scores_and_first_token():
             assert np.array_equal(got[b * 264, h * HD:(h + 1) * HD], vb[b * 264, :HD])
 
 
+def run_backward(a, do_t):
+    """do_t: [M, Hq * hd] bf16 on the host.  Returns device dq, dk, dv (slices of one [M, (Hq + 2 Hkv) hd]
+    tensor, the layout of the fused q|k|v linear's output gradient)."""
+    B, S, Hq, Hkv = a.B, a.S, a.Hq, a.Hkv
+    M = B * S
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    do = do_t.cuda()
+    qt, kt, dot = torch.empty((Hq * HD, M), **bf), torch.empty((Hkv * HD, M), **bf), torch.empty((Hq * HD, M), **bf)
+    f8.transpose_bf16(a.q, qt)
+    f8.transpose_bf16(a.k, kt)
+    f8.transpose_bf16(do, dot)
+    dqkv = torch.zeros((M, (Hq + 2 * Hkv) * HD), **bf)
+    dq, dk, dv = dqkv[:, :Hq * HD], dqkv[:, Hq * HD:(Hq + Hkv) * HD], dqkv[:, (Hq + Hkv) * HD:]
+    delta = torch.empty((Hq, M), device="cuda")
+    f8.sdpa_bwd(a.q, qt, a.k, kt, a.v, a.o, do, dot, a.lse, B, S, Hq, Hkv, HD, dq, dk, dv, delta)
+    torch.cuda.synchronize()
+    return dqkv, delta
+
+
+def check_backward(a, do_t, dqkv, delta):
+    qb, kb, vb = a.host_bits()
+    B, S, Hq, Hkv = a.B, a.S, a.Hq, a.Hkv
+    q, k, v, do = f64(qb), f64(kb), f64(vb), f64(bits(do_t))
+    rdq, rdk, rdv = bo.sdpa_bwd_f64(q, k, v, do, B, S, Hq, Hkv, HD)
+    got = f64(bits(dqkv))
+    gq, gk, gv = got[:, :Hq * HD], got[:, Hq * HD:(Hq + Hkv) * HD], got[:, (Hq + Hkv) * HD:]
+    assert np.isfinite(got).all()
+    # delta against its definition with the GPU's own (bf16) output O
+    o_gpu = f64(bits(a.o))
+    rdelta = (o_gpu * do).reshape(B, S, Hq, HD).sum(axis=3).transpose(2, 0, 1).reshape(Hq, B * S)
+    mag = (np.abs(o_gpu) * np.abs(do)).reshape(B, S, Hq, HD).sum(axis=3).transpose(2, 0, 1).reshape(Hq, B * S)
+    assert (np.abs(delta.cpu().numpy() - rdelta) <= 1e-5 * mag + 1e-30).all()
+    # P, dS (2^-9 relative each) and O (inside delta) are rounded to bf16 and the sums run in fp32:
+    # the same criterion as for the GEMMs of the linear, max |error| against max |reference|, per output
+    for name, g_, r_ in (("dq", gq, rdq), ("dk", gk, rdk), ("dv", gv, rdv)):
+        err = np.abs(g_ - r_)
+        assert err.max() <= 1e-2 * np.abs(r_).max(), (name, err.max(), np.abs(r_).max())
+        # on average: three bf16 roundings on the way (the P or dS operand, O inside delta, the output), 2^-9 each
+        assert err.mean() <= 3 * 2.0 ** -9 * np.abs(r_).mean(), (name, err.mean(), np.abs(r_).mean())
+
+
+@pytest.mark.parametrize("B,S,Hq,Hkv", [(1, 8, 1, 1), (1, 128, 2, 1), (2, 200, 4, 2), (1, 520, 8, 2), (3, 64, 2, 2)])
+def test_sdpa_backward(B, S, Hq, Hkv):
+    a = Attn(B, S, Hq, Hkv, seed=S + Hq + 1)
+    a.forward()
+    do_t = gen((B * S, Hq * HD), S, 1e-2)
+    dqkv, delta = run_backward(a, do_t)
+    check_backward(a, do_t, dqkv, delta)
+    # reproducible: no atomics anywhere
+    dqkv2, _ = run_backward(a, do_t)
+    assert torch.equal(dqkv.view(torch.int16), dqkv2.view(torch.int16))
+
+
 def test_sdpa_argument_errors():
     a = Attn(1, 64, 2, 1, seed=1)
     with pytest.raises(f8.F8Error) as e:
