@@ -1,0 +1,124 @@
+"""Call sequence of one Llama transformer block, forward and backward, on the C-ABI entry points
+(Section 2.1: the TransformerBlock is the unit the paper wraps, shards and recomputes; Section
+2.2.2: its linear layers run in Float8, everything between them in bf16).
+
+Buffers and the order of calls only: every step runs in the library's kernels.
+
+    x -> rmsnorm -> [wq|wk|wv] -> rope(q), rope(k) -> causal attention -> wo -> + x = h1
+    h1 -> rmsnorm -> [w1|w3] -> silu(a) * b -> w2 -> + h1 = out
+
+The Float8 linears use dynamic tensorwise scaling; where a producer already knows the amax of
+what it wrote (rmsnorm, the glue) the consumer's cast takes it instead of a pass of its own.
+"""
+import torch
+
+from . import f8
+
+
+class TransformerBlock:
+    def __init__(self, B, S, D, H, Hq, Hkv, hd=128, eps=1e-5, theta=500000.0, grad_format=f8.E4M3, device="cuda"):
+        assert D == Hq * hd
+        self.B, self.S, self.D, self.H, self.Hq, self.Hkv, self.hd = B, S, D, H, Hq, Hkv, hd
+        self.eps, self.theta = eps, theta
+        M = self.M = B * S
+        self.Nqkv = (Hq + 2 * Hkv) * hd
+        bf = dict(dtype=torch.bfloat16, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        E = lambda *shape: torch.empty(shape, **bf)
+        self.d_qkv = f8.linear_desc(M, D, self.Nqkv, False, grad_format)
+        self.d_o = f8.linear_desc(M, D, D, False, grad_format)
+        self.d_13 = f8.linear_desc(M, D, 2 * H, False, grad_format)
+        self.d_2 = f8.linear_desc(M, H, D, False, grad_format)
+        self.s_qkv, self.s_o = f8.Saved(M, D, self.Nqkv), f8.Saved(M, D, D)
+        self.s_13, self.s_2 = f8.Saved(M, D, 2 * H), f8.Saved(M, H, D)
+        big = max(M, D, 2 * H, self.Nqkv)
+        self.ws = f8.new_workspace(big, big, device)
+        # forward activations (all kept: the backward reads them)
+        self.xn, self.rstd1, self.a_xn = E(M, D), torch.empty(M, **f32), torch.empty(1, **f32)
+        self.qkv = E(M, self.Nqkv)
+        self.qr, self.kr = E(M, Hq * hd), E(M, Hkv * hd)                 # rotated q, k
+        self.qt, self.kt, self.vt = E(Hq * hd, M), E(Hkv * hd, M), E(Hkv * hd, M)
+        self.att, self.lse = E(M, D), torch.empty((Hq, M), **f32)
+        self.yo, self.h1 = E(M, D), E(M, D)
+        self.hn, self.rstd2, self.a_hn = E(M, D), torch.empty(M, **f32), torch.empty(1, **f32)
+        self.ab, self.hh, self.a_hh = E(M, 2 * H), E(M, H), torch.empty(1, **f32)
+        self.y2, self.out = E(M, D), E(M, D)
+        # backward
+        self.dhh, self.dab, self.a_dab = E(M, H), E(M, 2 * H), torch.empty(1, **f32)
+        self.dhn, self.dnorm2, self.dh1 = E(M, D), E(M, D), E(M, D)
+        self.datt, self.datt_t = E(M, D), E(D, M)
+        self.dqr, self.dkr, self.delta = E(M, Hq * hd), E(M, Hkv * hd), torch.empty((Hq, M), **f32)
+        self.dqkv = E(M, self.Nqkv)
+        self.dxn, self.dnorm1, self.dx = E(M, D), E(M, D), E(M, D)
+        self.dg1, self.dg2 = torch.empty(D, **f32), torch.empty(D, **f32)
+        self.dWqkv, self.dWo = E(self.Nqkv, D), E(D, D)
+        self.dW13, self.dW2 = E(2 * H, D), E(D, H)
+
+    def _slices(self, t):
+        Hq, Hkv, hd = self.Hq, self.Hkv, self.hd
+        return t[:, :Hq * hd], t[:, Hq * hd:(Hq + Hkv) * hd], t[:, (Hq + Hkv) * hd:]
+
+    def forward_stages(self, x, w, stream=None):
+        """w: dict with g1, g2 [D], Wqkv [(Hq + 2 Hkv) hd, D], Wo [D, D], W13 [2 H, D], W2 [D, H] (bf16).
+        Returns [(name, call, flops, algorithmic bytes)] in execution order."""
+        s, M, D, H, B, S = self, self.M, self.D, self.H, self.B, self.S
+        Hq, Hkv, hd = self.Hq, self.Hkv, self.hd
+        q, k, v = self._slices(self.qkv)
+        att_flops = 4 * B * S * S * Hq * hd // 2
+        return [
+            ("rmsnorm 1", lambda: f8.rmsnorm(x, w["g1"], s.eps, s.xn, s.rstd1, s.a_xn, s.ws, stream), 0, 4 * M * D),
+            ("linear wq|wk|wv fwd", lambda: f8.linear_fwd_chained(s.d_qkv, s.xn, s.a_xn, w["Wqkv"], s.qkv, None, s.s_qkv, s.ws, stream),
+             2 * M * D * s.Nqkv, 0),
+            ("rope q (+ transposed copy)", lambda: f8.rope(q, S, Hq, hd, s.qr, s.qt, s.theta, False, stream), 0, 6 * M * Hq * hd),
+            ("rope k (+ transposed copy)", lambda: f8.rope(k, S, Hkv, hd, s.kr, s.kt, s.theta, False, stream), 0, 6 * M * Hkv * hd),
+            ("transpose v", lambda: f8.transpose_bf16(v, s.vt, stream), 0, 4 * M * Hkv * hd),
+            ("attention fwd", lambda: f8.sdpa_fwd(s.qr, s.kr, s.vt, B, S, Hq, Hkv, hd, s.att, s.lse, stream), att_flops, 0),
+            ("linear wo fwd", lambda: f8.linear_fwd(s.d_o, s.att, w["Wo"], s.yo, s.s_o, s.ws, stream), 2 * M * D * D, 0),
+            ("residual 1", lambda: f8.add(x, s.yo, s.h1, stream), 0, 6 * M * D),
+            ("rmsnorm 2", lambda: f8.rmsnorm(s.h1, w["g2"], s.eps, s.hn, s.rstd2, s.a_hn, s.ws, stream), 0, 4 * M * D),
+            ("linear w1|w3 fwd", lambda: f8.linear_fwd_chained(s.d_13, s.hn, s.a_hn, w["W13"], s.ab, None, s.s_13, s.ws, stream),
+             2 * M * D * 2 * H, 0),
+            ("silu_mul", lambda: f8.silu_mul(s.ab, s.hh, s.a_hh, s.ws, stream), 0, 6 * M * H),
+            ("linear w2 fwd", lambda: f8.linear_fwd_chained(s.d_2, s.hh, s.a_hh, w["W2"], s.y2, None, s.s_2, s.ws, stream),
+             2 * M * H * D, 0),
+            ("residual 2", lambda: f8.add(s.h1, s.y2, s.out, stream), 0, 6 * M * D),
+        ]
+
+    def backward_stages(self, x, w, dout, stream=None):
+        s, M, D, H, B, S = self, self.M, self.D, self.H, self.B, self.S
+        Hq, Hkv, hd = self.Hq, self.Hkv, self.hd
+        q, k, v = self._slices(self.qkv)
+        dq, dk, dv = self._slices(self.dqkv)
+        att_flops = 4 * B * S * S * Hq * hd // 2
+        return [
+            ("linear w2 bwd", lambda: f8.linear_bwd(s.d_2, dout, s.s_2, s.dhh, s.dW2, s.ws, stream), 4 * M * H * D, 0),
+            ("silu_mul bwd", lambda: f8.silu_mul_bwd(s.ab, s.dhh, s.dab, s.a_dab, s.ws, stream), 0, 10 * M * H),
+            ("linear w1|w3 bwd", lambda: f8.linear_bwd_chained(s.d_13, s.dab, s.a_dab, s.s_13, s.dhn, None, s.dW13, s.ws, stream),
+             4 * M * D * 2 * H, 0),
+            ("rmsnorm 2 bwd", lambda: f8.rmsnorm_bwd(s.h1, w["g2"], s.rstd2, s.dhn, s.dnorm2, s.dg2, s.ws, stream), 0, 10 * M * D),
+            ("residual 2 bwd", lambda: f8.add(dout, s.dnorm2, s.dh1, stream), 0, 6 * M * D),
+            ("linear wo bwd", lambda: f8.linear_bwd(s.d_o, s.dh1, s.s_o, s.datt, s.dWo, s.ws, stream), 4 * M * D * D, 0),
+            ("transpose dO", lambda: f8.transpose_bf16(s.datt, s.datt_t, stream), 0, 4 * M * D),
+            ("attention bwd", lambda: f8.sdpa_bwd(s.qr, s.qt, s.kr, s.kt, v, s.att, s.datt, s.datt_t, s.lse, B, S, Hq, Hkv, hd,
+                                                  s.dqr, s.dkr, dv, s.delta, stream), 5 * att_flops // 2, 0),
+            ("rope q bwd", lambda: f8.rope(s.dqr, S, Hq, hd, dq, None, s.theta, True, stream), 0, 4 * M * Hq * hd),
+            ("rope k bwd", lambda: f8.rope(s.dkr, S, Hkv, hd, dk, None, s.theta, True, stream), 0, 4 * M * Hkv * hd),
+            ("linear wq|wk|wv bwd", lambda: f8.linear_bwd(s.d_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream),
+             4 * M * D * s.Nqkv, 0),
+            ("rmsnorm 1 bwd", lambda: f8.rmsnorm_bwd(x, w["g1"], s.rstd1, s.dxn, s.dnorm1, s.dg1, s.ws, stream), 0, 10 * M * D),
+            ("residual 1 bwd", lambda: f8.add(s.dh1, s.dnorm1, s.dx, stream), 0, 6 * M * D),
+        ]
+
+    def forward(self, x, w, stream=None):
+        for _, call, _, _ in self.forward_stages(x, w, stream):
+            call()
+        return self.out
+
+    def backward(self, x, w, dout, stream=None, recompute=False):
+        """recompute: run the forward again first, as under full activation checkpointing
+        (Section 2.2.1): the backward then depends on x and the weights only."""
+        if recompute:
+            self.forward(x, w, stream)
+        for _, call, _, _ in self.backward_stages(x, w, dout, stream):
+            call()
+        return self.dx
