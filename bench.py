@@ -20,6 +20,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+PEAK_BF16_TFLOPS = 2500.0   # dense bf16 MFMA peak of MI355X
 PEAK_FP8_TFLOPS = 5000.0   # MI355X dense fp8 MFMA (published: 5.0 PFLOP/s)
 PEAK_HBM_GBS = 8000.0      # MI355X HBM3E
 
@@ -38,6 +39,8 @@ def parse():
                          "handing the amax from the producing GEMM's epilogue to the consumer's cast")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into a HIP graph once and time its replays")
+    ap.add_argument("--recompute", action="store_true",
+                    help="llama8b_layer: run the forward again inside the backward (full activation checkpointing)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16-context", action="store_true",
                     help="skip timing torch.matmul in bf16 on the same shapes (context only)")
@@ -105,6 +108,8 @@ def main():
     w = wl.WORKLOADS[args.workload]
     if w.key == "llama8b_ffn":
         return ffn_main(args, w)
+    if w.key == "llama8b_layer":
+        return layer_main(args, w)
     gran, gfmt = (args.variant.split(":") if args.variant else w.variants[0])
     rowwise = gran == "rowwise"
     grad_fmt = f8.E5M2 if gfmt == "e5m2" else f8.E4M3
@@ -435,6 +440,97 @@ def ffn_main(args, w):
                                "are those of the linear workloads)", "bound": "hbm",
                      "achieved": round(glue_bytes / (glue_ms * 1e-3) / 1e9, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                      "frac": round(glue_bytes / (glue_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4), "traffic": None},
+        "legs": legs,
+    }
+    print(json.dumps(out))
+
+
+def layer_main(args, w):
+    """One whole transformer block, forward and backward: the Float8 linears chained through the
+    bf16 operations between them.  `value` counts the linears' FLOPs only (6 M K N each), as for
+    every other workload; the attention's FLOPs and every bf16 stage's time are inside the step
+    and itemised in `legs`."""
+    import torch
+    from paper_2410_06511_amd import workloads as wl
+    from paper_2410_06511_amd.block import TransformerBlock
+    if args.scaling != "dynamic":
+        print("bench.py: the transformer block runs with dynamic scaling", file=sys.stderr)
+        sys.exit(2)
+    sh = wl.LAYER_SHAPE[w.key]
+    B, S, Hq, Hkv, hd, D, H = (sh[k] for k in ("B", "S", "Hq", "Hkv", "hd", "D", "H"))
+    M = B * S
+    g = torch.Generator("cpu")
+    g.manual_seed(wl.seed_for(w.config_index, 0, "x"))
+    x = wl.randn_bf16((M, D), 1.0, 0, generator=g).cuda()
+    dout = wl.randn_bf16((M, D), 1e-3, 0, generator=g).cuda()
+    # weights: N(0, 0.02) as in the other workloads, except that wq, wk are larger so that the
+    # attention is not uniform (scores of order one)
+    weights = {"g1": torch.ones(D, dtype=torch.bfloat16, device="cuda"), "g2": torch.ones(D, dtype=torch.bfloat16, device="cuda"),
+               "Wqkv": wl.randn_bf16(((Hq + 2 * Hkv) * hd, D), 0.05, 0, generator=g).cuda(),
+               "Wo": wl.randn_bf16((D, D), 0.02, 0, generator=g).cuda(),
+               "W13": wl.randn_bf16((2 * H, D), 0.02, 0, generator=g).cuda(),
+               "W2": wl.randn_bf16((D, H), 0.02, 0, generator=g).cuda()}
+    blk = TransformerBlock(B, S, D, H, Hq, Hkv, hd)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        blk.forward(x, weights, stream)
+        blk.backward(x, weights, dout, stream, recompute=args.recompute)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    flops_step = sum(l.flops for l in w.linears)
+    tflops = flops_step / (ms_per_step * 1e-3) / 1e12
+
+    calls = blk.forward_stages(x, weights, stream) + blk.backward_stages(x, weights, dout, stream)
+    reps = max(3, min(args.steps, 10))
+    evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls] for _ in range(reps)]
+    for r in range(reps):
+        for (a, b), (_, fn, _, _) in zip(evs[r], calls):
+            a.record(stream)
+            fn()
+            b.record(stream)
+    torch.cuda.synchronize()
+    legs, lin_ms, att_ms, att_flops, glue_ms, glue_bytes = [], 0.0, 0.0, 0, 0.0, 0
+    for i, (name, _, fl, by) in enumerate(calls):
+        ms = sum(evs[r][i][0].elapsed_time(evs[r][i][1]) for r in range(reps)) / reps
+        leg = {"call": name, "ms": round(ms, 4)}
+        if fl:
+            leg["tflops"] = round(fl / (ms * 1e-3) / 1e12, 1)
+            if name.startswith("attention"):
+                att_ms, att_flops = att_ms + ms, att_flops + fl
+            else:
+                lin_ms += ms
+        if by:
+            leg["gbs"] = round(by / (ms * 1e-3) / 1e9, 1)
+            glue_ms, glue_bytes = glue_ms + ms, glue_bytes + by
+        legs.append(leg)
+    att_tflops = att_flops / (att_ms * 1e-3) / 1e12
+    out = {
+        "metric": "Float8 linear fwd+bwd TFLOP/s (% FP8 MFMA peak) + amax/cast HBM GB/s",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "fp8 (e4m3) x fp8 -> fp32 accumulate -> bf16 (linears); bf16 x bf16 -> fp32 (attention)", "data": "synthetic",
+        "config": {"workload": f"{w.key}: one Llama 3.1 8B transformer block, {B} x {S} tokens, hidden {D}, FFN {H}, "
+                               f"{Hq} query / {Hkv} key-value heads of {hd}: rmsnorm -> wq|wk|wv -> rope -> causal attention -> wo -> "
+                               "+x -> rmsnorm -> w1|w3 -> silu(a)*b -> w2 -> +h, and the backward of every stage",
+                   "scaling_granularity": "tensorwise", "scaling_strategy": "dynamic", "grad_format": "e4m3",
+                   "chained": True, "recompute_in_backward": bool(args.recompute), "flops_per_step": flops_step,
+                   "attention_flops_per_step_not_counted": att_flops},
+        "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
+        "linears_ms": round(lin_ms, 4), "attention_ms": round(att_ms, 4), "bf16_glue_ms": round(glue_ms, 4),
+        "roofline": {"kernel": "sdpa_fwd_kernel + sdpa_bwd_dq_kernel + sdpa_bwd_dkv_kernel (the attention, which is what this "
+                               "workload adds; the GEMM figures are those of the linear workloads); causal FLOPs: "
+                               "4 S^2 Hq hd / 2 forward, 2.5 times that backward (recomputed scores not counted)",
+                     "bound": "mfma", "achieved": round(att_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+        "glue_gbs": round(glue_bytes / (glue_ms * 1e-3) / 1e9, 1),
         "legs": legs,
     }
     print(json.dumps(out))

@@ -82,7 +82,17 @@ WORKLOADS = {
         "llama8b_ffn", 7,
         [Linear("w13", 8192, 4096, 28672), Linear("w2", 8192, 14336, 4096)],
         note="chained feed-forward block; X and the weights are seeded, the intermediate tensors are computed"),
+    # One whole Llama 3.1 8B transformer block on one sequence of 8192 tokens (the paper's 8B
+    # runs: sequence length 8192, local batch 1): the four Float8 linears (q|k|v and w1|w3 fused)
+    # joined by the bf16 operations between them (RMSNorm, rotary embedding, causal attention
+    # with 32 query and 8 key/value heads, SiLU gate, residuals), forward and backward.
+    "llama8b_layer": Workload(
+        "llama8b_layer", 8,
+        [Linear("wqkv", 8192, 4096, 6144), Linear("wo", 8192, 4096, 4096),
+         Linear("w13", 8192, 4096, 28672), Linear("w2", 8192, 14336, 4096)],
+        note="whole transformer block as a chain; x, dOut and the weights are seeded, everything between is computed"),
 }
+LAYER_SHAPE = {"llama8b_layer": dict(B=1, S=8192, Hq=32, Hkv=8, hd=128, D=4096, H=14336)}
 
 
 def seed_for(config_index: int, linear_index: int, which: str) -> int:
