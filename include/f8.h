@@ -434,15 +434,20 @@ f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64
  * (f8_transpose_bf16 of do); lse from the forward.  Outputs: dq [B*S, Hq*hd],
  * dk, dv [B*S, Hkv*hd] bf16 with their pitches (dq and dk are gradients of the
  * ROTATED q and k: f8_rope with inverse != 0 turns them back), and delta
- * [Hq, B*S] fp32, scratch that the call fills.  No atomics: results are
- * reproducible.  dS and P are rounded to bf16 before they enter a product.
+ * [Hq, B*S] fp32, scratch that the call fills.  With grouped heads (Hq > Hkv)
+ * every query head's share of dk and dv is kept in fp32 in the workspace
+ * (f8_sdpa_bwd_workspace_bytes: 2 * B*S * Hq*hd * 4 bytes; 0 and no workspace
+ * when Hq == Hkv) and the shares are summed in head order.  No atomics:
+ * results are reproducible.  dS and P are rounded to bf16 before they enter a
+ * product.
  */
 f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, const void* k_bf16, int64_t ldk,
                       const void* kt_bf16, const void* v_bf16, int64_t ldv, const void* o_bf16,
                       int64_t ldo, const void* do_bf16, int64_t lddo, const void* dot_bf16,
                       const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t hd,
                       void* dq_bf16, int64_t lddq, void* dk_bf16, int64_t lddk, void* dv_bf16,
-                      int64_t lddv, float* delta, void* stream);
+                      int64_t lddv, float* delta, void* workspace, size_t workspace_bytes, void* stream);
+size_t f8_sdpa_bwd_workspace_bytes(int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t hd);
 
 /*
  * Backward of f8_rmsnorm: with r = rstd[m] from the forward,

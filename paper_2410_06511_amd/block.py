@@ -48,6 +48,7 @@ class TransformerBlock:
         self.dhn, self.dnorm2, self.dh1 = E(M, D), E(M, D), E(M, D)
         self.datt, self.datt_t = E(M, D), E(D, M)
         self.dqr, self.dkr, self.delta = E(M, Hq * hd), E(M, Hkv * hd), torch.empty((Hq, M), **f32)
+        self.att_ws = torch.empty(max(16, f8.sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd)), dtype=torch.uint8, device=device)
         self.dqkv = E(M, self.Nqkv)
         self.dxn, self.dnorm1, self.dx = E(M, D), E(M, D), E(M, D)
         self.dg1, self.dg2 = torch.empty(D, **f32), torch.empty(D, **f32)
@@ -100,7 +101,7 @@ class TransformerBlock:
             ("linear wo bwd", lambda: f8.linear_bwd(s.d_o, s.dh1, s.s_o, s.datt, s.dWo, s.ws, stream), 4 * M * D * D, 0),
             ("transpose dO", lambda: f8.transpose_bf16(s.datt, s.datt_t, stream), 0, 4 * M * D),
             ("attention bwd", lambda: f8.sdpa_bwd(s.qr, s.qt, s.kr, s.kt, v, s.att, s.datt, s.datt_t, s.lse, B, S, Hq, Hkv, hd,
-                                                  s.dqr, s.dkr, dv, s.delta, stream), 5 * att_flops // 2, 0),
+                                                  s.dqr, s.dkr, dv, s.delta, s.att_ws, stream), 5 * att_flops // 2, 0),
             ("rope q bwd", lambda: f8.rope(s.dqr, S, Hq, hd, dq, None, s.theta, True, stream), 0, 4 * M * Hq * hd),
             ("rope k bwd", lambda: f8.rope(s.dkr, S, Hkv, hd, dk, None, s.theta, True, stream), 0, 4 * M * Hkv * hd),
             ("linear wq|wk|wv bwd", lambda: f8.linear_bwd(s.d_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream),

@@ -107,7 +107,7 @@ struct ColTile {
 // ---- forward ------------------------------------------------------------------------------
 // One block: 128 queries of one (sequence, head); each wave owns 32 of them.  Loop over 64-key
 // steps up to the diagonal; K and V^T tiles double-buffered in LDS.
-__global__ __launch_bounds__(kAttnThreads) void sdpa_fwd_kernel(const uint16_t* __restrict__ Q, int64_t ldq,
+__global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_t* __restrict__ Q, int64_t ldq,
                                                                 const uint16_t* __restrict__ K, int64_t ldk,
                                                                 const uint16_t* __restrict__ Vt, int64_t M, int S, int Hq,
                                                                 int group, float scale_log2e, uint16_t* __restrict__ O,
@@ -116,8 +116,9 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_fwd_kernel(const uint16_t* 
     __shared__ __attribute__((aligned(16))) uint16_t sK[2][kBk * kKp];
     __shared__ __attribute__((aligned(16))) uint16_t sV[2][kHd * kTp];
 
-    const int qt = nqt - 1 - (int)(blockIdx.x % nqt);  // long (late) query tiles first
-    const int bh = blockIdx.x / nqt, h = bh % Hq, b = bh / Hq, kvh = h / group;
+    // long (late) query tiles first, over all heads: the tile index varies slowest
+    const int nbh = Hq * (int)(M / S), qt = nqt - 1 - (int)(blockIdx.x / nbh);
+    const int bh = blockIdx.x % nbh, h = bh % Hq, b = bh / Hq, kvh = h / group;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
     const int q_first = qt * kBq + wave * 32;  // of this wave
     const int q_pos = q_first + ln;            // position of this lane's query in its sequence
@@ -239,19 +240,20 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_fwd_kernel(const uint16_t* 
 // of the group, S orientation: one key per lane).
 
 // dQ^T = K^T dS^T.  Per 64-key step: S^T = K Q^T, dP^T = V dO^T, dS^T, then the product over keys.
-__global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dq_kernel(
+__global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
     const uint16_t* __restrict__ Q, int64_t ldq, const uint16_t* __restrict__ K, int64_t ldk, const uint16_t* __restrict__ Kt,
     const uint16_t* __restrict__ V, int64_t ldv, const uint16_t* __restrict__ O, int64_t ldo, const uint16_t* __restrict__ dO,
     int64_t lddo, const float* __restrict__ lse, int64_t M, int S, int Hq, int group, float scale_log2e, float scale,
     uint16_t* __restrict__ dQ, int64_t lddq, float* __restrict__ delta, int nqt)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t* sK = smem;                       // [2][kBk * kKp]
-    uint16_t* sV = sK + 2 * kBk * kKp;         // [2][kBk * kKp]
-    uint16_t* sKt = sV + 2 * kBk * kKp;        // [2][kHd * kTp]
+    // one buffer per tile: two blocks share a compute unit and cover each other's barriers
+    uint16_t* sK = smem;                   // [kBk * kKp]
+    uint16_t* sV = sK + kBk * kKp;         // [kBk * kKp]
+    uint16_t* sKt = sV + kBk * kKp;        // [kHd * kTp]
 
-    const int qt = nqt - 1 - (int)(blockIdx.x % nqt);
-    const int bh = blockIdx.x / nqt, h = bh % Hq, b = bh / Hq, kvh = h / group;
+    const int nbh = Hq * (int)(M / S), qt = nqt - 1 - (int)(blockIdx.x / nbh);
+    const int bh = blockIdx.x % nbh, h = bh % Hq, b = bh / Hq, kvh = h / group;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
     const int q_first = qt * kBq + wave * 32, q_pos = q_first + ln;
     const int64_t tok0 = (int64_t)b * S;
@@ -295,10 +297,11 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dq_kernel(
     v_regs.load(Vb, ldv, 0, S);
     kt_regs.load(Ktb, M, 0, S);
     for (int t = 0; t < nkt; ++t) {
-        const int buf = t & 1, key0 = t * kBk;
-        k_regs.store(sK + buf * kBk * kKp);
-        v_regs.store(sV + buf * kBk * kKp);
-        kt_regs.store(sKt + buf * kHd * kTp);
+        const int key0 = t * kBk;
+        if (t) __syncthreads();  // the previous step's tiles have been read
+        k_regs.store(sK);
+        v_regs.store(sV);
+        kt_regs.store(sKt);
         __syncthreads();
         if (t + 1 < nkt) {
             k_regs.load(Kb, ldk, key0 + kBk, S);
@@ -306,10 +309,10 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dq_kernel(
             kt_regs.load(Ktb, M, key0 + kBk, S);
         }
         if (key0 > q_first + 31) continue;
-        const uint16_t *tK = sK + buf * kBk * kKp, *tV = sV + buf * kBk * kKp, *tKt = sKt + buf * kHd * kTp;
+        const uint16_t *tK = sK, *tV = sV, *tKt = sKt;
         const bool diagonal = key0 + kBk - 1 > q_first;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {  // one 32-key block at a time
+#pragma unroll 1
+        for (int kb = 0; kb < 2; ++kb) {  // one 32-key block at a time (not unrolled: registers)
             f32x16 sc = f32x16{0}, dp = f32x16{0};
 #pragma unroll
             for (int s = 0; s < kHd / 16; ++s) {
@@ -350,22 +353,27 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dq_kernel(
 // dK^T = Q^T dS, dV^T = dO^T P.  One block: 128 keys of one (sequence, key/value head), 32 per
 // wave, one key per lane; loop over 64-query steps from the diagonal on, for every query head of
 // the group.
-__global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dkv_kernel(
+__global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dkv_kernel(
     const uint16_t* __restrict__ Q, int64_t ldq, const uint16_t* __restrict__ Qt, const uint16_t* __restrict__ K, int64_t ldk,
     const uint16_t* __restrict__ V, int64_t ldv, const uint16_t* __restrict__ dO, int64_t lddo, const uint16_t* __restrict__ dOt,
-    const float* __restrict__ lse, const float* __restrict__ delta, int64_t M, int S, int Hkv, int group, float scale_log2e,
-    float scale, uint16_t* __restrict__ dK, int64_t lddk, uint16_t* __restrict__ dV, int64_t lddv, int nkt)
+    const float* __restrict__ lse, const float* __restrict__ delta, int64_t M, int S, int Hq, int group, float scale_log2e,
+    float scale, uint16_t* __restrict__ dK, int64_t lddk, uint16_t* __restrict__ dV, int64_t lddv,
+    float* __restrict__ part_k, float* __restrict__ part_v)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t* sQ = smem;                        // [2][kBk * kKp]   (kBk = queries per step here)
-    uint16_t* sD = sQ + 2 * kBk * kKp;          // [2][kBk * kKp]
-    uint16_t* sQt = sD + 2 * kBk * kKp;         // [2][kHd * kTp]
-    uint16_t* sDt = sQt + 2 * kHd * kTp;        // [2][kHd * kTp]
-    float* sLse = reinterpret_cast<float*>(sDt + 2 * kHd * kTp);  // [2][kBk], already times log2(e)
-    float* sDel = sLse + 2 * kBk;                                // [2][kBk]
+    // one buffer per tile and no prefetch registers (the accumulators and the key / value
+    // operands already take 192 registers): two blocks share a compute unit and cover each
+    // other's loads and barriers
+    uint16_t* sQ = smem;                    // [kBk * kKp]   (kBk = queries per step here)
+    uint16_t* sD = sQ + kBk * kKp;          // [kBk * kKp]
+    uint16_t* sQt = sD + kBk * kKp;         // [kHd * kTp]
+    uint16_t* sDt = sQt + kHd * kTp;        // [kHd * kTp]
+    float* sLse = reinterpret_cast<float*>(sDt + kHd * kTp);  // [kBk], already times log2(e)
+    float* sDel = sLse + kBk;                                // [kBk]
 
-    const int kt = blockIdx.x % nkt;  // early key tiles see the most queries and come first
-    const int bk = blockIdx.x / nkt, kvh = bk % Hkv, b = bk / Hkv;
+    // early key tiles see the most queries: they are the slowest-varying index, so they start first
+    const int bh = blockIdx.x % (Hq * (int)(M / S)), kt = blockIdx.x / (Hq * (int)(M / S));
+    const int hq = bh % Hq, b = bh / Hq, kvh = hq / group, gi = hq % group;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
     const int key_first = kt * kBq + wave * 32, key_pos = key_first + ln;
     const int64_t tok0 = (int64_t)b * S;
@@ -387,42 +395,36 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dkv_kernel(
     for (int d = 0; d < kHd / 32; ++d) acc_k[d] = f32x16{0}, acc_v[d] = f32x16{0};
 
     const int q_start = kt * kBq;                       // a multiple of the 64-query step
-    const int nqs = (S - q_start + kBk - 1) / kBk;      // >= 1: the block exists only if q_start < S
-    const int steps = nqs * group;
+    const int steps = (S - q_start + kBk - 1) / kBk;    // >= 1: the block exists only if q_start < S
 
-    RowTile<kBk> q_regs, d_regs;
-    ColTile<kBk> qt_regs, dt_regs;
-    float stat_reg = 0.0f;  // threads 0..63: lse of query threadIdx.x of the step; 64..127: delta
-    auto load_step = [&](int it) {
-        const int hq = kvh * group + it / nqs, q0 = q_start + (it % nqs) * kBk;
-        q_regs.load(Q + tok0 * ldq + (int64_t)hq * kHd, ldq, q0, S);
-        d_regs.load(dO + tok0 * lddo + (int64_t)hq * kHd, lddo, q0, S);
-        qt_regs.load(Qt + (int64_t)hq * kHd * M + tok0, M, q0, S);
-        dt_regs.load(dOt + (int64_t)hq * kHd * M + tok0, M, q0, S);
-        if (threadIdx.x < 2 * kBk) {
-            const int i = threadIdx.x & (kBk - 1);
-            const float* src = threadIdx.x < kBk ? lse : delta;
-            stat_reg = (q0 + i < S) ? src[(int64_t)hq * M + tok0 + q0 + i] : 0.0f;
-            if (threadIdx.x < kBk) stat_reg *= 1.4426950408889634074f;
-        }
-    };
-    load_step(0);
     for (int it = 0; it < steps; ++it) {
-        const int buf = it & 1, q0 = q_start + (it % nqs) * kBk;
-        q_regs.store(sQ + buf * kBk * kKp);
-        d_regs.store(sD + buf * kBk * kKp);
-        qt_regs.store(sQt + buf * kHd * kTp);
-        dt_regs.store(sDt + buf * kHd * kTp);
-        if (threadIdx.x < kBk) sLse[buf * kBk + threadIdx.x] = stat_reg;
-        else if (threadIdx.x < 2 * kBk) sDel[buf * kBk + threadIdx.x - kBk] = stat_reg;
+        const int q0 = q_start + it * kBk;
+        if (it) __syncthreads();  // the previous step's tiles have been read
+        {
+            RowTile<kBk> rt;
+            rt.load(Q + tok0 * ldq + (int64_t)hq * kHd, ldq, q0, S);
+            rt.store(sQ);
+            rt.load(dO + tok0 * lddo + (int64_t)hq * kHd, lddo, q0, S);
+            rt.store(sD);
+            ColTile<kBk> ct;
+            ct.load(Qt + (int64_t)hq * kHd * M + tok0, M, q0, S);
+            ct.store(sQt);
+            ct.load(dOt + (int64_t)hq * kHd * M + tok0, M, q0, S);
+            ct.store(sDt);
+            if (threadIdx.x < 2 * kBk) {
+                const int i = threadIdx.x & (kBk - 1);
+                const float* src = threadIdx.x < kBk ? lse : delta;
+                float v = (q0 + i < S) ? src[(int64_t)hq * M + tok0 + q0 + i] : 0.0f;
+                if (threadIdx.x < kBk) sLse[i] = v * 1.4426950408889634074f;
+                else sDel[i] = v;
+            }
+        }
         __syncthreads();
-        if (it + 1 < steps) load_step(it + 1);
         if (q0 + kBk - 1 < key_first) continue;  // every query of the step lies before every key of the wave
-        const uint16_t *tQ = sQ + buf * kBk * kKp, *tD = sD + buf * kBk * kKp;
-        const uint16_t *tQt = sQt + buf * kHd * kTp, *tDt = sDt + buf * kHd * kTp;
+        const uint16_t *tQ = sQ, *tD = sD, *tQt = sQt, *tDt = sDt;
         // one 32-query block at a time; registers: queries 32 qb + 8 j + 4 g + i of the step; lane: one key
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+#pragma unroll 1
+        for (int qb = 0; qb < 2; ++qb) {  // not unrolled: two blocks in flight would not fit the registers
             f32x16 sc = f32x16{0}, dp = f32x16{0};
 #pragma unroll
             for (int s = 0; s < kHd / 16; ++s) {
@@ -434,8 +436,8 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dkv_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int ql = 32 * qb + 8 * j + 4 * g;
-                const float4 l4 = *reinterpret_cast<const float4*>(sLse + buf * kBk + ql);
-                const float4 d4 = *reinterpret_cast<const float4*>(sDel + buf * kBk + ql);
+                const float4 l4 = *reinterpret_cast<const float4*>(sLse + ql);
+                const float4 d4 = *reinterpret_cast<const float4*>(sDel + ql);
                 const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -457,7 +459,8 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dkv_kernel(
             }
         }
     }
-    if (k_ok) {
+    if (!k_ok) return;
+    if (group == 1) {
         uint16_t* krow = dK + tok * lddk + (int64_t)kvh * kHd + 4 * g;
         uint16_t* vrow = dV + tok * lddv + (int64_t)kvh * kHd + 4 * g;
 #pragma unroll
@@ -470,12 +473,49 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_bwd_dkv_kernel(
                 *reinterpret_cast<uint2*>(vrow + 32 * d + 8 * j) =
                     make_uint2(pack2(acc_v[d][4 * j], acc_v[d][4 * j + 1]), pack2(acc_v[d][4 * j + 2], acc_v[d][4 * j + 3]));
             }
+    } else {
+        // this query head's share, fp32: [group][token][Hkv * hd]; summed in a fixed order afterwards
+        const int64_t w = (int64_t)(Hq / group) * kHd;
+        float* krow = part_k + ((int64_t)gi * M + tok) * w + (int64_t)kvh * kHd + 4 * g;
+        float* vrow = part_v + ((int64_t)gi * M + tok) * w + (int64_t)kvh * kHd + 4 * g;
+#pragma unroll
+        for (int d = 0; d < kHd / 32; ++d)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                *reinterpret_cast<float4*>(krow + 32 * d + 8 * j) =
+                    make_float4(acc_k[d][4 * j] * scale, acc_k[d][4 * j + 1] * scale, acc_k[d][4 * j + 2] * scale, acc_k[d][4 * j + 3] * scale);
+                *reinterpret_cast<float4*>(vrow + 32 * d + 8 * j) =
+                    make_float4(acc_v[d][4 * j], acc_v[d][4 * j + 1], acc_v[d][4 * j + 2], acc_v[d][4 * j + 3]);
+            }
     }
 }
 
-constexpr size_t kDqLds = (size_t)(4 * kBk * kKp + 2 * kHd * kTp) * sizeof(uint16_t);
-constexpr size_t kDkvLds = (size_t)(4 * kBk * kKp + 4 * kHd * kTp) * sizeof(uint16_t) + 4 * kBk * sizeof(float);
-static_assert(kDkvLds <= 160 * 1024, "the key/value gradient kernel's tiles fit the LDS of a compute unit");
+// out[tok][c] = bf16(sum over the group's query heads, in order, of part[gi][tok][c]); 8 columns per thread
+__global__ __launch_bounds__(kAttnThreads) void sdpa_group_sum_kernel(const float* __restrict__ part_k, const float* __restrict__ part_v,
+                                                                      int64_t M, int64_t w, int group,
+                                                                      uint16_t* __restrict__ dK, int64_t lddk,
+                                                                      uint16_t* __restrict__ dV, int64_t lddv)
+{
+    const int64_t chunks = M * (w / 8);
+    for (int64_t c = (int64_t)blockIdx.x * kAttnThreads + threadIdx.x; c < 2 * chunks; c += (int64_t)gridDim.x * kAttnThreads) {
+        const bool is_v = c >= chunks;
+        const int64_t cc = is_v ? c - chunks : c, tok = cc / (w / 8), col = (cc % (w / 8)) * 8;
+        const float* src = (is_v ? part_v : part_k) + tok * w + col;
+        float4 a = *reinterpret_cast<const float4*>(src), b2 = *reinterpret_cast<const float4*>(src + 4);
+        for (int gi = 1; gi < group; ++gi) {
+            const float4 x = *reinterpret_cast<const float4*>(src + (int64_t)gi * M * w);
+            const float4 y = *reinterpret_cast<const float4*>(src + (int64_t)gi * M * w + 4);
+            a.x += x.x, a.y += x.y, a.z += x.z, a.w += x.w;
+            b2.x += y.x, b2.y += y.y, b2.z += y.z, b2.w += y.w;
+        }
+        uint16_t* dst = is_v ? dV + tok * lddv + col : dK + tok * lddk + col;
+        *reinterpret_cast<uint4*>(dst) = make_uint4(pack2(a.x, a.y), pack2(a.z, a.w), pack2(b2.x, b2.y), pack2(b2.z, b2.w));
+    }
+}
+
+constexpr size_t kDqLds = (size_t)(2 * kBk * kKp + kHd * kTp) * sizeof(uint16_t);
+constexpr size_t kDkvLds = (size_t)(2 * kBk * kKp + 2 * kHd * kTp) * sizeof(uint16_t) + 2 * kBk * sizeof(float);
+static_assert(2 * kDkvLds <= 160 * 1024 && 2 * kDqLds <= 160 * 1024, "two blocks' tiles fit the LDS of a compute unit");
 
 static f8_status check_attn(const void* q, int64_t ldq, const void* k, int64_t ldk, int64_t B, int64_t S, int64_t Hq,
                             int64_t Hkv, int64_t hd)
@@ -512,11 +552,17 @@ f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64
     return last_launch_status();
 }
 
+size_t f8_sdpa_bwd_workspace_bytes(int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t hd)
+{
+    if (B <= 0 || S <= 0 || Hq <= 0 || Hkv <= 0 || hd <= 0 || (Hq % Hkv) || Hq == Hkv) return 0;
+    return (size_t)2 * (size_t)(B * S) * (size_t)(Hq * hd) * sizeof(float);  // dk and dv shares of every query head
+}
+
 f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, const void* k_bf16, int64_t ldk,
                       const void* kt_bf16, const void* v_bf16, int64_t ldv, const void* o_bf16, int64_t ldo,
                       const void* do_bf16, int64_t lddo, const void* dot_bf16, const float* lse, int64_t B, int64_t S,
                       int64_t Hq, int64_t Hkv, int64_t hd, void* dq_bf16, int64_t lddq, void* dk_bf16, int64_t lddk,
-                      void* dv_bf16, int64_t lddv, float* delta, void* stream)
+                      void* dv_bf16, int64_t lddv, float* delta, void* workspace, size_t workspace_bytes_, void* stream)
 {
     f8_status s = check_attn(q_bf16, ldq, k_bf16, ldk, B, S, Hq, Hkv, hd);
     if (s != F8_OK) return s;
@@ -529,6 +575,9 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
     if (!aligned16(qt_bf16) || !aligned16(kt_bf16) || !aligned16(v_bf16) || !aligned16(o_bf16) || !aligned16(do_bf16) ||
         !aligned16(dot_bf16) || !aligned16(dq_bf16) || !aligned16(dk_bf16) || !aligned16(dv_bf16))
         return F8_ERR_ALIGN;
+    const int64_t group = Hq / Hkv;
+    if (group > 1 && (!workspace || workspace_bytes_ < f8_sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd))) return F8_ERR_WORKSPACE;
+    if (group > 1 && !aligned16(workspace)) return F8_ERR_ALIGN;
     if (B == 0 || S == 0) return F8_OK;
     static bool configured = false;
     if (!configured) {
@@ -547,10 +596,18 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)k_bf16, ldk, (const uint16_t*)kt_bf16, (const uint16_t*)v_bf16, ldv,
         (const uint16_t*)o_bf16, ldo, (const uint16_t*)do_bf16, lddo, lse, M, (int)S, (int)Hq, (int)(Hq / Hkv), scale_log2e, scale,
         (uint16_t*)dq_bf16, lddq, delta, (int)nt);
-    sdpa_bwd_dkv_kernel<<<(unsigned)(nt * Hkv * B), kAttnThreads, kDkvLds, st>>>(
+    float* part_k = group > 1 ? (float*)workspace : nullptr;
+    float* part_v = group > 1 ? part_k + group * M * wk : nullptr;
+    sdpa_bwd_dkv_kernel<<<(unsigned)(nt * Hq * B), kAttnThreads, kDkvLds, st>>>(
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)qt_bf16, (const uint16_t*)k_bf16, ldk, (const uint16_t*)v_bf16, ldv,
-        (const uint16_t*)do_bf16, lddo, (const uint16_t*)dot_bf16, lse, delta, M, (int)S, (int)Hkv, (int)(Hq / Hkv), scale_log2e,
-        scale, (uint16_t*)dk_bf16, lddk, (uint16_t*)dv_bf16, lddv, (int)nt);
+        (const uint16_t*)do_bf16, lddo, (const uint16_t*)dot_bf16, lse, delta, M, (int)S, (int)Hq, (int)group, scale_log2e,
+        scale, (uint16_t*)dk_bf16, lddk, (uint16_t*)dv_bf16, lddv, part_k, part_v);
+    if (group > 1) {
+        int64_t nb = (2 * M * (wk / 8) + kAttnThreads - 1) / kAttnThreads;
+        if (nb > 8192) nb = 8192;
+        sdpa_group_sum_kernel<<<(unsigned)nb, kAttnThreads, 0, st>>>(part_k, part_v, M, wk, (int)group, (uint16_t*)dk_bf16, lddk,
+                                                                   (uint16_t*)dv_bf16, lddv);
+    }
     return last_launch_status();
 }
 

@@ -28,7 +28,7 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise",
            "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq",
            "f8_silu_mul_bwd_quantise_delayed", "f8_linear_bwd_dyq",
-           "f8_rope", "f8_transpose_bf16", "f8_add", "f8_rmsnorm_bwd", "f8_sdpa_fwd", "f8_sdpa_bwd"]
+           "f8_rope", "f8_transpose_bf16", "f8_add", "f8_rmsnorm_bwd", "f8_sdpa_fwd", "f8_sdpa_bwd", "f8_sdpa_bwd_workspace_bytes"]
 
 
 class F8Error(RuntimeError):
@@ -101,9 +101,11 @@ def lib():
         l.f8_rmsnorm_bwd.argtypes = [_p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_sdpa_fwd.argtypes = [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _p, _p]
         l.f8_sdpa_bwd.argtypes = [_p, _i64, _p, _p, _i64, _p, _p, _i64, _p, _i64, _p, _i64, _p, _p, _i64, _i64, _i64, _i64,
-                                  _i64, _p, _i64, _p, _i64, _p, _i64, _p, _p]
+                                  _i64, _p, _i64, _p, _i64, _p, _i64, _p, _p, C.c_size_t, _p]
+        l.f8_sdpa_bwd_workspace_bytes.argtypes = [_i64] * 5
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
+        l.f8_sdpa_bwd_workspace_bytes.restype = C.c_size_t
         _lib = l
     return _lib
 
@@ -366,8 +368,13 @@ def sdpa_fwd(q, k, vt, B, S, Hq, Hkv, hd, o, lse, stream=None):
                              _ptr(lse), _stream(stream)))
 
 
-def sdpa_bwd(q, qt, k, kt, v, o, do, dot, lse, B, S, Hq, Hkv, hd, dq, dk, dv, delta, stream=None):
+def sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd):
+    return int(lib().f8_sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd))
+
+
+def sdpa_bwd(q, qt, k, kt, v, o, do, dot, lse, B, S, Hq, Hkv, hd, dq, dk, dv, delta, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
     _check(lib().f8_sdpa_bwd(_ptr(q), q.stride(0), _ptr(qt), _ptr(k), k.stride(0), _ptr(kt), _ptr(v), v.stride(0),
                              _ptr(o), o.stride(0), _ptr(do), do.stride(0), _ptr(dot), _ptr(lse), B, S, Hq, Hkv, hd,
                              _ptr(dq), dq.stride(0), _ptr(dk), dk.stride(0), _ptr(dv), dv.stride(0), _ptr(delta),
-                             _stream(stream)))
+                             wp, wb, _stream(stream)))

@@ -100,7 +100,9 @@ def run_backward(a, do_t):
     dqkv = torch.zeros((M, (Hq + 2 * Hkv) * HD), **bf)
     dq, dk, dv = dqkv[:, :Hq * HD], dqkv[:, Hq * HD:(Hq + Hkv) * HD], dqkv[:, (Hq + Hkv) * HD:]
     delta = torch.empty((Hq, M), device="cuda")
-    f8.sdpa_bwd(a.q, qt, a.k, kt, a.v, a.o, do, dot, a.lse, B, S, Hq, Hkv, HD, dq, dk, dv, delta)
+    ws = torch.empty(max(16, f8.sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, HD)), dtype=torch.uint8, device="cuda")
+    assert (ws.numel() > 16) == (Hq != Hkv)
+    f8.sdpa_bwd(a.q, qt, a.k, kt, a.v, a.o, do, dot, a.lse, B, S, Hq, Hkv, HD, dq, dk, dv, delta, ws)
     torch.cuda.synchronize()
     return dqkv, delta
 
