@@ -235,9 +235,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
 // ---- backward -----------------------------------------------------------------------------
 // With P = exp(S / sqrt(hd) - lse) recomputed from the saved lse and delta[q] = sum_d dO O:
 //   dV = P^T dO,  dP = dO V^T,  dS = P (dP - delta),  dQ = dS K / sqrt(hd),  dK = dS^T Q / sqrt(hd)
-// Two kernels, neither with atomics: dQ per query tile (loop over keys, S^T orientation, which
-// also produces delta), then dK and dV per key tile (loop over the queries of every query head
-// of the group, S orientation: one key per lane).
+// Three kernels, none with atomics: dQ per query tile (loop over keys, S^T orientation, which
+// also produces delta), then dK and dV per key tile and query head (loop over queries, S
+// orientation: one key per lane); with grouped heads the shares of a group's query heads are
+// kept in fp32 and summed in head order by a small fourth kernel.
 
 // dQ^T = K^T dS^T.  Per 64-key step: S^T = K Q^T, dP^T = V dO^T, dS^T, then the product over keys.
 __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
@@ -350,26 +351,27 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
     }
 }
 
-// dK^T = Q^T dS, dV^T = dO^T P.  One block: 128 keys of one (sequence, key/value head), 32 per
-// wave, one key per lane; loop over 64-query steps from the diagonal on, for every query head of
-// the group.
+// dK^T = Q^T dS and dV^T = dO^T P, as two instantiations of one kernel (DK: the dK half).  One
+// block: 128 keys of one (sequence, query head), 32 per wave, one key per lane; loop over
+// QS-query steps from the diagonal on (64 for dV; 32 for dK, whose prefetch registers for three
+// tiles would not fit otherwise).  Both halves recompute S = Q K^T; taken together they
+// would need the key and value operands, two sets of accumulators and four tiles per step, more
+// than the 256 registers of a wave at two blocks per compute unit, and would run without the
+// register prefetch of the next step's tiles.
+template <bool DK, int QS>
 __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dkv_kernel(
     const uint16_t* __restrict__ Q, int64_t ldq, const uint16_t* __restrict__ Qt, const uint16_t* __restrict__ K, int64_t ldk,
     const uint16_t* __restrict__ V, int64_t ldv, const uint16_t* __restrict__ dO, int64_t lddo, const uint16_t* __restrict__ dOt,
     const float* __restrict__ lse, const float* __restrict__ delta, int64_t M, int S, int Hq, int group, float scale_log2e,
-    float scale, uint16_t* __restrict__ dK, int64_t lddk, uint16_t* __restrict__ dV, int64_t lddv,
-    float* __restrict__ part_k, float* __restrict__ part_v)
+    float scale, uint16_t* __restrict__ dst, int64_t ldd, float* __restrict__ part)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    // one buffer per tile and no prefetch registers (the accumulators and the key / value
-    // operands already take 192 registers): two blocks share a compute unit and cover each
-    // other's loads and barriers
-    uint16_t* sQ = smem;                    // [kBk * kKp]   (kBk = queries per step here)
-    uint16_t* sD = sQ + kBk * kKp;          // [kBk * kKp]
-    uint16_t* sQt = sD + kBk * kKp;         // [kHd * kTp]
-    uint16_t* sDt = sQt + kHd * kTp;        // [kHd * kTp]
-    float* sLse = reinterpret_cast<float*>(sDt + kHd * kTp);  // [kBk], already times log2(e)
-    float* sDel = sLse + kBk;                                // [kBk]
+    constexpr int TP = ColTile<QS>::P;  // row pitch of the [hd][queries] tile
+    uint16_t* sQ = smem;                                   // [QS queries][hd]: Q rows
+    uint16_t* sT = sQ + QS * kKp;                         // [kHd * TP]   DK: Q^T, else dO^T
+    uint16_t* sD = sT + kHd * TP;                         // [QS * kKp]   DK only: dO rows
+    float* sLse = reinterpret_cast<float*>(sD + (DK ? QS * kKp : 0));  // [QS], already times log2(e)
+    float* sDel = sLse + QS;                              // [QS], DK only
 
     // early key tiles see the most queries: they are the slowest-varying index, so they start first
     const int bh = blockIdx.x % (Hq * (int)(M / S)), kt = blockIdx.x / (Hq * (int)(M / S));
@@ -380,113 +382,113 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dkv_kernel(
     const bool k_ok = key_pos < S;
     const int64_t tok = tok0 + (k_ok ? key_pos : 0);
 
-    uint4 kf[kHd / 16], vf[kHd / 16];
+    uint4 kf[kHd / 16], vf[DK ? kHd / 16 : 1];
     {
         const uint16_t* krow = K + tok * ldk + (int64_t)kvh * kHd + 8 * g;
         const uint16_t* vrow = V + tok * ldv + (int64_t)kvh * kHd + 8 * g;
 #pragma unroll
         for (int s = 0; s < kHd / 16; ++s) {
             kf[s] = k_ok ? *reinterpret_cast<const uint4*>(krow + 16 * s) : make_uint4(0, 0, 0, 0);
-            vf[s] = k_ok ? *reinterpret_cast<const uint4*>(vrow + 16 * s) : make_uint4(0, 0, 0, 0);
+            if constexpr (DK) vf[s] = k_ok ? *reinterpret_cast<const uint4*>(vrow + 16 * s) : make_uint4(0, 0, 0, 0);
         }
     }
-    f32x16 acc_k[kHd / 32], acc_v[kHd / 32];
+    f32x16 acc[kHd / 32];
 #pragma unroll
-    for (int d = 0; d < kHd / 32; ++d) acc_k[d] = f32x16{0}, acc_v[d] = f32x16{0};
+    for (int d = 0; d < kHd / 32; ++d) acc[d] = f32x16{0};
 
-    const int q_start = kt * kBq;                       // a multiple of the 64-query step
-    const int steps = (S - q_start + kBk - 1) / kBk;    // >= 1: the block exists only if q_start < S
+    const int q_start = kt * kBq;                       // a multiple of the query step
+    const int steps = (S - q_start + QS - 1) / QS;    // >= 1: the block exists only if q_start < S
+    const uint16_t* Qb = Q + tok0 * ldq + (int64_t)hq * kHd;
+    const uint16_t* Db = dO + tok0 * lddo + (int64_t)hq * kHd;
+    const uint16_t* Tb = (DK ? Qt : dOt) + (int64_t)hq * kHd * M + tok0;
+    const float* lse_b = lse + (int64_t)hq * M + tok0;
+    const float* del_b = delta + (int64_t)hq * M + tok0;
 
-    for (int it = 0; it < steps; ++it) {
-        const int q0 = q_start + it * kBk;
-        if (it) __syncthreads();  // the previous step's tiles have been read
-        {
-            RowTile<kBk> rt;
-            rt.load(Q + tok0 * ldq + (int64_t)hq * kHd, ldq, q0, S);
-            rt.store(sQ);
-            rt.load(dO + tok0 * lddo + (int64_t)hq * kHd, lddo, q0, S);
-            rt.store(sD);
-            ColTile<kBk> ct;
-            ct.load(Qt + (int64_t)hq * kHd * M + tok0, M, q0, S);
-            ct.store(sQt);
-            ct.load(dOt + (int64_t)hq * kHd * M + tok0, M, q0, S);
-            ct.store(sDt);
-            if (threadIdx.x < 2 * kBk) {
-                const int i = threadIdx.x & (kBk - 1);
-                const float* src = threadIdx.x < kBk ? lse : delta;
-                float v = (q0 + i < S) ? src[(int64_t)hq * M + tok0 + q0 + i] : 0.0f;
-                if (threadIdx.x < kBk) sLse[i] = v * 1.4426950408889634074f;
-                else sDel[i] = v;
-            }
+    RowTile<QS> q_regs, d_regs;
+    ColTile<QS> t_regs;
+    float stat_reg = 0.0f;  // threads 0..63: lse of query threadIdx.x of the step; 64..127: delta (DK)
+    auto load_step = [&](int q0) {
+        q_regs.load(Qb, ldq, q0, S);
+        t_regs.load(Tb, M, q0, S);
+        if constexpr (DK) d_regs.load(Db, lddo, q0, S);
+        if (threadIdx.x < (DK ? 2 : 1) * QS) {
+            const int i = threadIdx.x & (QS - 1);
+            const float* src = threadIdx.x < QS ? lse_b : del_b;
+            stat_reg = (q0 + i < S) ? src[q0 + i] : 0.0f;
+            if (threadIdx.x < QS) stat_reg *= 1.4426950408889634074f;
         }
+    };
+    load_step(q_start);
+    for (int it = 0; it < steps; ++it) {
+        const int q0 = q_start + it * QS;
+        if (it) __syncthreads();  // the previous step's tiles have been read
+        q_regs.store(sQ);
+        t_regs.store(sT);
+        if constexpr (DK) d_regs.store(sD);
+        if (threadIdx.x < QS) sLse[threadIdx.x] = stat_reg;
+        else if (DK && threadIdx.x < 2 * QS) sDel[threadIdx.x - QS] = stat_reg;
         __syncthreads();
-        if (q0 + kBk - 1 < key_first) continue;  // every query of the step lies before every key of the wave
-        const uint16_t *tQ = sQ, *tD = sD, *tQt = sQt, *tDt = sDt;
+        if (it + 1 < steps) load_step(q0 + QS);
+        if (q0 + QS - 1 < key_first) continue;  // every query of the step lies before every key of the wave
         // one 32-query block at a time; registers: queries 32 qb + 8 j + 4 g + i of the step; lane: one key
 #pragma unroll 1
-        for (int qb = 0; qb < 2; ++qb) {  // not unrolled: two blocks in flight would not fit the registers
+        for (int qb = 0; qb < QS / 32; ++qb) {  // not unrolled: two blocks in flight would not fit the registers
             f32x16 sc = f32x16{0}, dp = f32x16{0};
 #pragma unroll
             for (int s = 0; s < kHd / 16; ++s) {
-                const uint4 qfr = *reinterpret_cast<const uint4*>(tQ + (32 * qb + ln) * kKp + 16 * s + 8 * g);
-                const uint4 dfr = *reinterpret_cast<const uint4*>(tD + (32 * qb + ln) * kKp + 16 * s + 8 * g);
+                const uint4 qfr = *reinterpret_cast<const uint4*>(sQ + (32 * qb + ln) * kKp + 16 * s + 8 * g);
                 sc = mma(qfr, kf[s], sc);
-                dp = mma(dfr, vf[s], dp);
+                if constexpr (DK) {
+                    const uint4 dfr = *reinterpret_cast<const uint4*>(sD + (32 * qb + ln) * kKp + 16 * s + 8 * g);
+                    dp = mma(dfr, vf[s], dp);
+                }
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int ql = 32 * qb + 8 * j + 4 * g;
                 const float4 l4 = *reinterpret_cast<const float4*>(sLse + ql);
-                const float4 d4 = *reinterpret_cast<const float4*>(sDel + ql);
-                const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dv[4] = {d4.x, d4.y, d4.z, d4.w};
+                const float lv[4] = {l4.x, l4.y, l4.z, l4.w};
+                float dv[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                if constexpr (DK) {
+                    const float4 d4 = *reinterpret_cast<const float4*>(sDel + ql);
+                    dv[0] = d4.x, dv[1] = d4.y, dv[2] = d4.z, dv[3] = d4.w;
+                }
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int r = 4 * j + i, qp = q0 + ql + i;
                     float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - lv[i]);
                     if (key_pos > qp || qp >= S) p = 0.0f;
-                    sc[r] = p;
-                    dp[r] = p * (dp[r] - dv[i]);
+                    sc[r] = DK ? p * (dp[r] - dv[i]) : p;
                 }
             }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const uint4 pf = slots(sc, u), df = slots(dp, u);
+                const uint4 f = slots(sc, u);
 #pragma unroll
-                for (int d = 0; d < kHd / 32; ++d) {
-                    acc_v[d] = mma(token_slots(tDt + (32 * d + ln) * kTp, 32 * qb, u, g), pf, acc_v[d]);
-                    acc_k[d] = mma(token_slots(tQt + (32 * d + ln) * kTp, 32 * qb, u, g), df, acc_k[d]);
-                }
+                for (int d = 0; d < kHd / 32; ++d) acc[d] = mma(token_slots(sT + (32 * d + ln) * TP, 32 * qb, u, g), f, acc[d]);
             }
         }
     }
     if (!k_ok) return;
+    const float mul = DK ? scale : 1.0f;
     if (group == 1) {
-        uint16_t* krow = dK + tok * lddk + (int64_t)kvh * kHd + 4 * g;
-        uint16_t* vrow = dV + tok * lddv + (int64_t)kvh * kHd + 4 * g;
+        uint16_t* row = dst + tok * ldd + (int64_t)kvh * kHd + 4 * g;
 #pragma unroll
         for (int d = 0; d < kHd / 32; ++d)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                *reinterpret_cast<uint2*>(krow + 32 * d + 8 * j) =
-                    make_uint2(pack2(acc_k[d][4 * j] * scale, acc_k[d][4 * j + 1] * scale),
-                               pack2(acc_k[d][4 * j + 2] * scale, acc_k[d][4 * j + 3] * scale));
-                *reinterpret_cast<uint2*>(vrow + 32 * d + 8 * j) =
-                    make_uint2(pack2(acc_v[d][4 * j], acc_v[d][4 * j + 1]), pack2(acc_v[d][4 * j + 2], acc_v[d][4 * j + 3]));
-            }
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<uint2*>(row + 32 * d + 8 * j) =
+                    make_uint2(pack2(acc[d][4 * j] * mul, acc[d][4 * j + 1] * mul), pack2(acc[d][4 * j + 2] * mul, acc[d][4 * j + 3] * mul));
     } else {
         // this query head's share, fp32: [group][token][Hkv * hd]; summed in a fixed order afterwards
         const int64_t w = (int64_t)(Hq / group) * kHd;
-        float* krow = part_k + ((int64_t)gi * M + tok) * w + (int64_t)kvh * kHd + 4 * g;
-        float* vrow = part_v + ((int64_t)gi * M + tok) * w + (int64_t)kvh * kHd + 4 * g;
+        float* row = part + ((int64_t)gi * M + tok) * w + (int64_t)kvh * kHd + 4 * g;
 #pragma unroll
         for (int d = 0; d < kHd / 32; ++d)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                *reinterpret_cast<float4*>(krow + 32 * d + 8 * j) =
-                    make_float4(acc_k[d][4 * j] * scale, acc_k[d][4 * j + 1] * scale, acc_k[d][4 * j + 2] * scale, acc_k[d][4 * j + 3] * scale);
-                *reinterpret_cast<float4*>(vrow + 32 * d + 8 * j) =
-                    make_float4(acc_v[d][4 * j], acc_v[d][4 * j + 1], acc_v[d][4 * j + 2], acc_v[d][4 * j + 3]);
-            }
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<float4*>(row + 32 * d + 8 * j) =
+                    make_float4(acc[d][4 * j] * mul, acc[d][4 * j + 1] * mul, acc[d][4 * j + 2] * mul, acc[d][4 * j + 3] * mul);
     }
 }
 
@@ -514,8 +516,10 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_group_sum_kernel(const floa
 }
 
 constexpr size_t kDqLds = (size_t)(2 * kBk * kKp + kHd * kTp) * sizeof(uint16_t);
-constexpr size_t kDkvLds = (size_t)(2 * kBk * kKp + 2 * kHd * kTp) * sizeof(uint16_t) + 2 * kBk * sizeof(float);
-static_assert(2 * kDkvLds <= 160 * 1024 && 2 * kDqLds <= 160 * 1024, "two blocks' tiles fit the LDS of a compute unit");
+constexpr int kDkQs = 32, kDvQs = 64;  // queries per step of the dK and the dV kernel
+constexpr size_t kDkLds = (size_t)(2 * kDkQs * kKp + kHd * ColTile<kDkQs>::P) * sizeof(uint16_t) + 2 * kDkQs * sizeof(float);
+constexpr size_t kDvLds = (size_t)(kDvQs * kKp + kHd * ColTile<kDvQs>::P) * sizeof(uint16_t) + 2 * kDvQs * sizeof(float);
+static_assert(2 * kDkLds <= 160 * 1024 && 2 * kDqLds <= 160 * 1024, "two blocks' tiles fit the LDS of a compute unit");
 
 static f8_status check_attn(const void* q, int64_t ldq, const void* k, int64_t ldk, int64_t B, int64_t S, int64_t Hq,
                             int64_t Hkv, int64_t hd)
@@ -583,7 +587,8 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
     if (!configured) {
         // more dynamic LDS than the default limit of a launch: raise it once per process
         if (hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) != hipSuccess ||
-            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkvLds) != hipSuccess)
+            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<true, kDkQs>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkLds) != hipSuccess ||
+            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) != hipSuccess)
             return F8_ERR_LAUNCH;
         configured = true;
     }
@@ -598,10 +603,14 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
         (uint16_t*)dq_bf16, lddq, delta, (int)nt);
     float* part_k = group > 1 ? (float*)workspace : nullptr;
     float* part_v = group > 1 ? part_k + group * M * wk : nullptr;
-    sdpa_bwd_dkv_kernel<<<(unsigned)(nt * Hq * B), kAttnThreads, kDkvLds, st>>>(
+    sdpa_bwd_dkv_kernel<true, kDkQs><<<(unsigned)(nt * Hq * B), kAttnThreads, kDkLds, st>>>(
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)qt_bf16, (const uint16_t*)k_bf16, ldk, (const uint16_t*)v_bf16, ldv,
         (const uint16_t*)do_bf16, lddo, (const uint16_t*)dot_bf16, lse, delta, M, (int)S, (int)Hq, (int)group, scale_log2e,
-        scale, (uint16_t*)dk_bf16, lddk, (uint16_t*)dv_bf16, lddv, part_k, part_v);
+        scale, (uint16_t*)dk_bf16, lddk, part_k);
+    sdpa_bwd_dkv_kernel<false, kDvQs><<<(unsigned)(nt * Hq * B), kAttnThreads, kDvLds, st>>>(
+        (const uint16_t*)q_bf16, ldq, (const uint16_t*)qt_bf16, (const uint16_t*)k_bf16, ldk, (const uint16_t*)v_bf16, ldv,
+        (const uint16_t*)do_bf16, lddo, (const uint16_t*)dot_bf16, lse, delta, M, (int)S, (int)Hq, (int)group, scale_log2e,
+        scale, (uint16_t*)dv_bf16, lddv, part_v);
     if (group > 1) {
         int64_t nb = (2 * M * (wk / 8) + kAttnThreads - 1) / kAttnThreads;
         if (nb > 8192) nb = 8192;
