@@ -141,7 +141,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
     f32x16 acc_o[kHd / 32];
 #pragma unroll
     for (int d = 0; d < kHd / 32; ++d) acc_o[d] = f32x16{0};
-    float m_run = -INFINITY, l_run = 0.0f;  // running maximum (log2 domain) and this lane's share of the sum
+    float m_run = -INFINITY, l_run = 0.0f;  // running maximum of the raw scores and this lane's share of the sum
 
     RowTile<kBk> kt_regs;
     ColTile<kBk> vt_regs;
@@ -169,38 +169,41 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
                 sc[kb] = mma(kf, qf[s], sc[kb]);
             }
         }
+        // The maximum is taken over the raw scores (the scale is positive), so the scaling and the
+        // subtraction of the maximum are one fused multiply-add per score.
         const bool diagonal = key0 + kBk - 1 > q_first;
         float mx = -INFINITY;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                float v = sc[kb][r] * scale_log2e;
                 if (diagonal) {
                     const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
-                    if (key > q_pos) v = -INFINITY;
+                    if (key > q_pos) sc[kb][r] = -INFINITY;
                 }
-                sc[kb][r] = v;
-                mx = fmaxf(mx, v);
+                mx = fmaxf(mx, sc[kb][r]);
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
         m_run = m_new;
+        const float neg_m = -m_new * scale_log2e;
         float psum = 0.0f;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const float p = __builtin_amdgcn_exp2f(sc[kb][r] - m_new);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[kb][r], scale_log2e, neg_m));
                 sc[kb][r] = p;
                 psum += p;
             }
         l_run = l_run * alpha + psum;
+        if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {  // after the first few steps the maximum rarely moves
 #pragma unroll
-        for (int d = 0; d < kHd / 32; ++d)
+            for (int d = 0; d < kHd / 32; ++d)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc_o[d][r] *= alpha;
+                for (int r = 0; r < 16; ++r) acc_o[d][r] *= alpha;
+        }
 
         // O^T += V^T P^T: [128 hd][32 queries], contraction over the 64 keys in four 16-slot steps
 #pragma unroll
@@ -228,7 +231,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
                                            pack2(acc_o[d][4 * j + 2] * inv, acc_o[d][4 * j + 3] * inv));
                 *reinterpret_cast<uint2*>(orow + 32 * d + 8 * j) = w;
             }
-        if (g == 0) lse[(int64_t)h * M + tok0 + q_pos] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+        if (g == 0) lse[(int64_t)h * M + tok0 + q_pos] = (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
     }
 }
 
