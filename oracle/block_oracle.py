@@ -71,7 +71,7 @@ def _unheads(x):
 def _probabilities(q, k, hd):
     """q [B, Hq, S, hd], k [B, Hq, S, hd] (already repeated) -> P [B, Hq, S, S], lse [B, Hq, S]."""
     S = q.shape[2]
-    s = np.einsum("bhqd,bhkd->bhqk", q, k) / np.sqrt(float(hd))
+    s = np.matmul(q, np.swapaxes(k, 2, 3)) / np.sqrt(float(hd))
     mask = np.tril(np.ones((S, S), dtype=bool))
     s = np.where(mask, s, -np.inf)
     m = s.max(axis=-1, keepdims=True)
@@ -86,7 +86,7 @@ def sdpa_f64(q, k, v, B, S, Hq, Hkv, hd):
     kh = np.repeat(_heads(k, B, S, Hkv, hd), g, axis=1)
     vh = np.repeat(_heads(v, B, S, Hkv, hd), g, axis=1)
     P, lse = _probabilities(qh, kh, hd)
-    return _unheads(np.einsum("bhqk,bhkd->bhqd", P, vh)), lse
+    return _unheads(np.matmul(P, vh)), lse
 
 
 def sdpa(q_bits, k_bits, v_bits, B, S, Hq, Hkv, hd):
@@ -101,12 +101,12 @@ def sdpa_bwd_f64(q, k, v, do, B, S, Hq, Hkv, hd):
     kh = np.repeat(_heads(k, B, S, Hkv, hd), g, axis=1)
     vh = np.repeat(_heads(v, B, S, Hkv, hd), g, axis=1)
     P, _ = _probabilities(qh, kh, hd)
-    dv = np.einsum("bhqk,bhqd->bhkd", P, doh)
-    dP = np.einsum("bhqd,bhkd->bhqk", doh, vh)
+    dv = np.matmul(np.swapaxes(P, 2, 3), doh)
+    dP = np.matmul(doh, np.swapaxes(vh, 2, 3))
     dS = P * (dP - (P * dP).sum(axis=-1, keepdims=True))
     sc = 1.0 / np.sqrt(float(hd))
-    dq = np.einsum("bhqk,bhkd->bhqd", dS, kh) * sc
-    dk = np.einsum("bhqk,bhqd->bhkd", dS, qh) * sc
+    dq = np.matmul(dS, kh) * sc
+    dk = np.matmul(np.swapaxes(dS, 2, 3), qh) * sc
     # the query heads of one group share a key/value head: their gradients add
     dk = dk.reshape(B, Hkv, g, S, hd).sum(axis=2)
     dv = dv.reshape(B, Hkv, g, S, hd).sum(axis=2)
@@ -116,6 +116,56 @@ def sdpa_bwd_f64(q, k, v, do, B, S, Hq, Hkv, hd):
 def sdpa_bwd(q_bits, k_bits, v_bits, do_bits, B, S, Hq, Hkv, hd):
     dq, dk, dv = sdpa_bwd_f64(_f64(q_bits), _f64(k_bits), _f64(v_bits), _f64(do_bits), B, S, Hq, Hkv, hd)
     return _bf16(dq), _bf16(dk), _bf16(dv)
+
+
+def _rows_probabilities(q, k, v, rows, S, Hq, Hkv, hd):
+    """The definition restricted to the query tokens `rows` (global token indices): P [Hq, R, B*S]
+    over ALL tokens (zero outside the row's own sequence and after its position), lse [Hq, R]."""
+    g = Hq // Hkv
+    rows = np.asarray(rows)
+    M = k.shape[0]
+    tok = np.arange(M)
+    visible = (tok[None, :] // S == rows[:, None] // S) & (tok[None, :] <= rows[:, None])      # [R, M]
+    P = np.empty((Hq, len(rows), M))
+    lse = np.empty((Hq, len(rows)))
+    for h in range(Hq):
+        kh = k[:, (h // g) * hd:(h // g + 1) * hd]
+        s = np.where(visible, q[rows, h * hd:(h + 1) * hd] @ kh.T / np.sqrt(float(hd)), -np.inf)
+        m = s.max(axis=1, keepdims=True)
+        e = np.exp(s - m)
+        z = e.sum(axis=1, keepdims=True)
+        P[h], lse[h] = e / z, (m + np.log(z))[:, 0]
+    return P, lse
+
+
+def sdpa_rows_f64(q, k, v, rows, B, S, Hq, Hkv, hd):
+    """O[rows] [R, Hq*hd] and lse [Hq, R] of the attention for the query tokens `rows` only (for
+    sizes at which the full S x S probabilities are too slow to form)."""
+    g = Hq // Hkv
+    P, lse = _rows_probabilities(q, k, v, rows, S, Hq, Hkv, hd)
+    o = np.concatenate([P[h] @ v[:, (h // g) * hd:(h // g + 1) * hd] for h in range(Hq)], axis=1)
+    return o, lse
+
+
+def sdpa_bwd_rows_f64(q, k, v, do, rows, B, S, Hq, Hkv, hd):
+    """dq[rows] [R, Hq*hd], and the contribution of the query tokens `rows` to dk and dv
+    [B*S, Hkv*hd]: complete for every key that no other query can see (with rows = all tokens
+    from t on of the last sequence, complete for the keys from t on)."""
+    g = Hq // Hkv
+    rows = np.asarray(rows)
+    P, _ = _rows_probabilities(q, k, v, rows, S, Hq, Hkv, hd)
+    sc = 1.0 / np.sqrt(float(hd))
+    dq = np.empty((len(rows), Hq * hd))
+    dk, dv = np.zeros_like(k), np.zeros_like(v)
+    for h in range(Hq):
+        hs, ks = slice(h * hd, (h + 1) * hd), slice((h // g) * hd, (h // g + 1) * hd)
+        doh = do[rows, hs]
+        dP = doh @ v[:, ks].T
+        dS = P[h] * (dP - (P[h] * dP).sum(axis=1, keepdims=True))
+        dq[:, hs] = dS @ k[:, ks] * sc
+        dk[:, ks] += dS.T @ q[rows, hs] * sc
+        dv[:, ks] += P[h].T @ doh
+    return dq, dk, dv
 
 
 # ---- RMSNorm backward, residual ----------------------------------------------------------

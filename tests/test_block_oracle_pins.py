@@ -136,6 +136,29 @@ def test_sdpa_bwd_equals_torch_autograd_and_finite_differences():
         assert np.isclose((f(*args_p) - f(*args_m)) / (2 * h), grad[idx], rtol=1e-6, atol=1e-9)
 
 
+def test_row_restricted_attention_equals_the_full_definition():
+    """sdpa_rows_f64 / sdpa_bwd_rows_f64 (used at sizes where S x S is too slow) against the full
+    oracle: sampled rows anywhere, and the key gradients of the last tokens from the last rows."""
+    B, S, Hq, Hkv, hd = 2, 24, 4, 2, 8
+    M = B * S
+    q, k, v = rnd((M, Hq * hd), 30), rnd((M, Hkv * hd), 31), rnd((M, Hkv * hd), 32)
+    do = rnd((M, Hq * hd), 33)
+    o, lse = bo.sdpa_f64(q, k, v, B, S, Hq, Hkv, hd)
+    dq, dk, dv = bo.sdpa_bwd_f64(q, k, v, do, B, S, Hq, Hkv, hd)
+    rows = [0, 3, 23, 24, 30, 47]
+    o_r, lse_r = bo.sdpa_rows_f64(q, k, v, rows, B, S, Hq, Hkv, hd)
+    assert np.allclose(o_r, o[rows], rtol=1e-12, atol=1e-13)
+    full_lse = lse.transpose(1, 0, 2).reshape(Hq, M)
+    assert np.allclose(lse_r, full_lse[:, rows], rtol=1e-12)
+    dq_r, _, _ = bo.sdpa_bwd_rows_f64(q, k, v, do, rows, B, S, Hq, Hkv, hd)
+    assert np.allclose(dq_r, dq[rows], rtol=1e-10, atol=1e-13)
+    t = M - 7                                             # the last 7 tokens of the last sequence
+    tail = list(range(t, M))
+    _, dk_t, dv_t = bo.sdpa_bwd_rows_f64(q, k, v, do, tail, B, S, Hq, Hkv, hd)
+    assert np.allclose(dk_t[t:], dk[t:], rtol=1e-10, atol=1e-13) and np.allclose(dv_t[t:], dv[t:], rtol=1e-10, atol=1e-13)
+    assert not np.allclose(dk_t[t - 3:t], dk[t - 3:t])    # earlier keys are seen by other queries too
+
+
 # ---- rmsnorm backward, residual -----------------------------------------------------------
 
 def test_rmsnorm_bwd_equals_torch_autograd_and_closed_form():

@@ -141,6 +141,35 @@ def test_sdpa_backward(B, S, Hq, Hkv):
     assert torch.equal(dqkv.view(torch.int16), dqkv2.view(torch.int16))
 
 
+def test_sdpa_full_size_sampled_against_oracle():
+    """The 8B shape that bench.py times (1 x 8192 tokens, 32 query / 8 key-value heads), in the same
+    launch configuration.  The 8192 x 8192 probabilities of 32 heads are too slow for the oracle,
+    so it computes them for sampled query tokens (every head): the outputs, log-sum-exp and dq of
+    those tokens, and dk, dv of the last 192 keys (which only the last 192 queries see)."""
+    B, S, Hq, Hkv = 1, 8192, 32, 8
+    a = Attn(B, S, Hq, Hkv, seed=99)
+    a.forward()
+    do_t = gen((B * S, Hq * HD), 98, 1e-2)
+    dqkv, _ = run_backward(a, do_t)
+    qb, kb, vb = a.host_bits()
+    q, k, v, do = f64(qb), f64(kb), f64(vb), f64(bits(do_t))
+    t = S - 192
+    rows = sorted(set([0, 1, 31, 32, 63, 64, 127, 128, 129, 1000, 2047, 2048, 4095, 4100, 6143, 7000]) | set(range(t, S)))
+    ref, lse = bo.sdpa_rows_f64(q, k, v, rows, B, S, Hq, Hkv, HD)
+    weight, _ = bo.sdpa_rows_f64(q, k, np.abs(v), rows, B, S, Hq, Hkv, HD)
+    got = f64(bits(a.o))[rows]
+    assert (np.abs(got - ref) <= 2.0 ** -7 * weight + 1e-30).all()
+    got_lse = a.lse.cpu().numpy().astype(np.float64)[:, rows]
+    assert np.abs(got_lse - lse).max() <= 1e-4 * (1.0 + np.abs(lse).max())
+    rdq, rdk, rdv = bo.sdpa_bwd_rows_f64(q, k, v, do, rows, B, S, Hq, Hkv, HD)
+    g_ = f64(bits(dqkv))
+    nq, nk = Hq * HD, Hkv * HD
+    for name, gg, rr in (("dq", g_[rows, :nq], rdq), ("dk", g_[t:, nq:nq + nk], rdk[t:]), ("dv", g_[t:, nq + nk:], rdv[t:])):
+        e = np.abs(gg - rr)
+        assert e.max() <= 1e-2 * np.abs(rr).max(), (name, e.max(), np.abs(rr).max())
+        assert e.mean() <= 3 * 2.0 ** -9 * np.abs(rr).mean(), (name, e.mean(), np.abs(rr).mean())
+
+
 def test_sdpa_argument_errors():
     a = Attn(1, 64, 2, 1, seed=1)
     with pytest.raises(f8.F8Error) as e:
