@@ -24,7 +24,8 @@ constexpr int kHd = 128;   // head dimension of every model the paper trains
 constexpr int kBq = 128;   // queries per block: 32 per wave
 constexpr int kBk = 64;    // keys per step
 constexpr int kKp = kHd + 8;   // LDS row pitch (bf16) of a [tokens][hd] tile: 272 bytes
-constexpr int kTp = kBk + 8;   // LDS row pitch (bf16) of a [hd][tokens] tile: 144 bytes
+constexpr int kTp = kBk + 4;   // LDS row pitch (bf16) of a [hd][tokens] tile: 136 bytes = 34 words, an odd multiple of 2:
+                               // the 8-byte reads of 32 consecutive rows fall into 32 different bank pairs
 
 __device__ inline f32x16 mma(uint4 first, uint4 second, f32x16 acc)
 {
@@ -58,15 +59,16 @@ __device__ inline uint4 token_slots(const uint16_t* tile_row, int t0, int u, int
 
 // Tile loaders: global -> registers (issued early) -> LDS (after the barrier that frees it).
 // [ROWS tokens][kHd] from a token-major tensor; rows at or beyond `limit` read as zero.
-template <int ROWS>
+template <int ROWS, int NT = kAttnThreads>
 struct RowTile {
-    static constexpr int N = ROWS * (kHd / 8) / kAttnThreads;
+    static constexpr int N = ROWS * (kHd / 8) / NT;
+    static_assert(N >= 1 && N * NT == ROWS * (kHd / 8), "the tile's chunks divide evenly over the threads");
     uint4 v[N];
     __device__ void load(const uint16_t* base, int64_t ld, int row0, int limit)
     {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const int c = threadIdx.x + kAttnThreads * i, r = c / (kHd / 8), cc = c % (kHd / 8);
+            const int c = threadIdx.x + NT * i, r = c / (kHd / 8), cc = c % (kHd / 8);
             v[i] = (row0 + r < limit) ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + r) * ld + cc * 8) : make_uint4(0, 0, 0, 0);
         }
     }
@@ -74,23 +76,24 @@ struct RowTile {
     {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const int c = threadIdx.x + kAttnThreads * i, r = c / (kHd / 8), cc = c % (kHd / 8);
+            const int c = threadIdx.x + NT * i, r = c / (kHd / 8), cc = c % (kHd / 8);
             *reinterpret_cast<uint4*>(lds + r * kKp + cc * 8) = v[i];
         }
     }
 };
 // [kHd][COLS tokens] from a transposed (token-minor) tensor with row pitch ld; columns at or beyond
 // `limit` read as zero (limit and col0 are multiples of 8).
-template <int COLS>
+template <int COLS, int NT = kAttnThreads>
 struct ColTile {
-    static constexpr int N = kHd * (COLS / 8) / kAttnThreads;
-    static constexpr int P = COLS + 8;
+    static constexpr int N = kHd * (COLS / 8) / NT;
+    static_assert(N >= 1 && N * NT == kHd * (COLS / 8), "the tile's chunks divide evenly over the threads");
+    static constexpr int P = COLS + 4;  // rows are 8-byte aligned only: stored as two 8-byte halves
     uint4 v[N];
     __device__ void load(const uint16_t* base, int64_t ld, int col0, int limit)
     {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const int c = threadIdx.x + kAttnThreads * i, r = c / (COLS / 8), cc = c % (COLS / 8);
+            const int c = threadIdx.x + NT * i, r = c / (COLS / 8), cc = c % (COLS / 8);
             v[i] = (col0 + cc * 8 < limit) ? *reinterpret_cast<const uint4*>(base + (int64_t)r * ld + col0 + cc * 8) : make_uint4(0, 0, 0, 0);
         }
     }
@@ -98,8 +101,9 @@ struct ColTile {
     {
 #pragma unroll
         for (int i = 0; i < N; ++i) {
-            const int c = threadIdx.x + kAttnThreads * i, r = c / (COLS / 8), cc = c % (COLS / 8);
-            *reinterpret_cast<uint4*>(lds + r * P + cc * 8) = v[i];
+            const int c = threadIdx.x + NT * i, r = c / (COLS / 8), cc = c % (COLS / 8);
+            *reinterpret_cast<uint2*>(lds + r * P + cc * 8) = make_uint2(v[i].x, v[i].y);
+            *reinterpret_cast<uint2*>(lds + r * P + cc * 8 + 4) = make_uint2(v[i].z, v[i].w);
         }
     }
 };
@@ -355,32 +359,33 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
 }
 
 // dK^T = Q^T dS and dV^T = dO^T P, as two instantiations of one kernel (DK: the dK half).  One
-// block: 128 keys of one (sequence, query head), 32 per wave, one key per lane; loop over
-// QS-query steps from the diagonal on (64 for dV; 32 for dK, whose prefetch registers for three
-// tiles would not fit otherwise).  Both halves recompute S = Q K^T; taken together they
+// block: NW waves, 32 keys each (one key per lane), of one (sequence, query head); loop over
+// QS-query steps.  Eight waves (256 keys) per block: every block streams the Q / dO tiles of all
+// later queries of its head, and a larger key tile halves that traffic and the prefetch
+// registers per thread.  Both halves recompute S = Q K^T; taken together they
 // would need the key and value operands, two sets of accumulators and four tiles per step, more
 // than the 256 registers of a wave at two blocks per compute unit, and would run without the
 // register prefetch of the next step's tiles.
-template <bool DK, int QS>
-__global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dkv_kernel(
+template <bool DK, int QS, int NW>
+__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
     const uint16_t* __restrict__ Q, int64_t ldq, const uint16_t* __restrict__ Qt, const uint16_t* __restrict__ K, int64_t ldk,
     const uint16_t* __restrict__ V, int64_t ldv, const uint16_t* __restrict__ dO, int64_t lddo, const uint16_t* __restrict__ dOt,
     const float* __restrict__ lse, const float* __restrict__ delta, int64_t M, int S, int Hq, int group, float scale_log2e,
     float scale, uint16_t* __restrict__ dst, int64_t ldd, float* __restrict__ part)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    constexpr int TP = ColTile<QS>::P;  // row pitch of the [hd][queries] tile
-    uint16_t* sQ = smem;                                   // [QS queries][hd]: Q rows
-    uint16_t* sT = sQ + QS * kKp;                         // [kHd * TP]   DK: Q^T, else dO^T
-    uint16_t* sD = sT + kHd * TP;                         // [QS * kKp]   DK only: dO rows
-    float* sLse = reinterpret_cast<float*>(sD + (DK ? QS * kKp : 0));  // [QS], already times log2(e)
-    float* sDel = sLse + QS;                              // [QS], DK only
+    constexpr int NT = 64 * NW, KB = 32 * NW;  // threads and keys per block
+    constexpr int TP = ColTile<QS, NT>::P;     // row pitch of the [hd][queries] tile
+    // every tile twice: the next step's tiles are stored while slower waves still read this step's
+    constexpr int kTileElems = QS * kKp + kHd * TP + (DK ? QS * kKp : 0);  // bf16 elements of one buffer
+    constexpr int kBufElems = kTileElems + 4 * QS;                          // + lse and delta (2 QS floats)
+    static_assert((kBufElems * 2) % 16 == 0, "buffers stay 16-byte aligned");
 
     // early key tiles see the most queries: they are the slowest-varying index, so they start first
     const int bh = blockIdx.x % (Hq * (int)(M / S)), kt = blockIdx.x / (Hq * (int)(M / S));
     const int hq = bh % Hq, b = bh / Hq, kvh = hq / group, gi = hq % group;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
-    const int key_first = kt * kBq + wave * 32, key_pos = key_first + ln;
+    const int key_first = kt * KB + wave * 32, key_pos = key_first + ln;
     const int64_t tok0 = (int64_t)b * S;
     const bool k_ok = key_pos < S;
     const int64_t tok = tok0 + (k_ok ? key_pos : 0);
@@ -399,7 +404,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dkv_kernel(
 #pragma unroll
     for (int d = 0; d < kHd / 32; ++d) acc[d] = f32x16{0};
 
-    const int q_start = kt * kBq;                       // a multiple of the query step
+    const int q_start = kt * KB;                        // a multiple of the query step
     const int steps = (S - q_start + QS - 1) / QS;    // >= 1: the block exists only if q_start < S
     const uint16_t* Qb = Q + tok0 * ldq + (int64_t)hq * kHd;
     const uint16_t* Db = dO + tok0 * lddo + (int64_t)hq * kHd;
@@ -407,8 +412,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dkv_kernel(
     const float* lse_b = lse + (int64_t)hq * M + tok0;
     const float* del_b = delta + (int64_t)hq * M + tok0;
 
-    RowTile<QS> q_regs, d_regs;
-    ColTile<QS> t_regs;
+    RowTile<QS, NT> q_regs, d_regs;
+    ColTile<QS, NT> t_regs;
     float stat_reg = 0.0f;  // threads 0..63: lse of query threadIdx.x of the step; 64..127: delta (DK)
     auto load_step = [&](int q0) {
         q_regs.load(Qb, ldq, q0, S);
@@ -421,21 +426,27 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dkv_kernel(
             if (threadIdx.x < QS) stat_reg *= 1.4426950408889634074f;
         }
     };
-    load_step(q_start);
+    // Queries from the end of the sequence down to the diagonal: the blocks of one head (which share
+    // an XCD: the head index is the fastest-varying part of blockIdx) then walk the same Q / dO tiles
+    // at the same time.
+    load_step(q_start + (steps - 1) * QS);
     for (int it = 0; it < steps; ++it) {
-        const int q0 = q_start + it * QS;
-        if (it) __syncthreads();  // the previous step's tiles have been read
+        const int q0 = q_start + (steps - 1 - it) * QS;
+        uint16_t* sQ = smem + (it & 1) * kBufElems;            // [QS queries][hd]: Q rows
+        uint16_t* sT = sQ + QS * kKp;                          // [hd][QS]: DK: Q^T, else dO^T
+        uint16_t* sD = sT + kHd * TP;                          // [QS][hd], DK only: dO rows
+        float* sLse = reinterpret_cast<float*>(sQ + kTileElems);  // [QS], already times log2(e)
+        float* sDel = sLse + QS;                               // [QS], DK only
         q_regs.store(sQ);
         t_regs.store(sT);
         if constexpr (DK) d_regs.store(sD);
         if (threadIdx.x < QS) sLse[threadIdx.x] = stat_reg;
         else if (DK && threadIdx.x < 2 * QS) sDel[threadIdx.x - QS] = stat_reg;
         __syncthreads();
-        if (it + 1 < steps) load_step(q0 + QS);
+        if (it + 1 < steps) load_step(q0 - QS);
         if (q0 + QS - 1 < key_first) continue;  // every query of the step lies before every key of the wave
         // one 32-query block at a time; registers: queries 32 qb + 8 j + 4 g + i of the step; lane: one key
-#pragma unroll 1
-        for (int qb = 0; qb < QS / 32; ++qb) {  // not unrolled: two blocks in flight would not fit the registers
+        auto block32 = [&](int qb) {
             f32x16 sc = f32x16{0}, dp = f32x16{0};
 #pragma unroll
             for (int s = 0; s < kHd / 16; ++s) {
@@ -470,6 +481,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dkv_kernel(
 #pragma unroll
                 for (int d = 0; d < kHd / 32; ++d) acc[d] = mma(token_slots(sT + (32 * d + ln) * TP, 32 * qb, u, g), f, acc[d]);
             }
+        };
+        if constexpr (DK) {
+#pragma unroll 1
+            for (int qb = 0; qb < QS / 32; ++qb) block32(qb);  // not unrolled: two blocks in flight would not fit the registers
+        } else {
+#pragma unroll
+            for (int qb = 0; qb < QS / 32; ++qb) block32(qb);  // unrolled: one block's exponentials overlap the other's products
         }
     }
     if (!k_ok) return;
@@ -519,10 +537,11 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_group_sum_kernel(const floa
 }
 
 constexpr size_t kDqLds = (size_t)(2 * kBk * kKp + kHd * kTp) * sizeof(uint16_t);
-constexpr int kDkQs = 32, kDvQs = 64;  // queries per step of the dK and the dV kernel
-constexpr size_t kDkLds = (size_t)(2 * kDkQs * kKp + kHd * ColTile<kDkQs>::P) * sizeof(uint16_t) + 2 * kDkQs * sizeof(float);
-constexpr size_t kDvLds = (size_t)(kDvQs * kKp + kHd * ColTile<kDvQs>::P) * sizeof(uint16_t) + 2 * kDvQs * sizeof(float);
-static_assert(2 * kDkLds <= 160 * 1024 && 2 * kDqLds <= 160 * 1024, "two blocks' tiles fit the LDS of a compute unit");
+constexpr int kDkvWaves = 8;             // 256 keys per block, one block per compute unit
+constexpr int kDkQs = 64, kDvQs = 64;    // queries per step of the dK and the dV kernel
+constexpr size_t kDkLds = 2 * ((size_t)(2 * kDkQs * kKp + kHd * ColTile<kDkQs>::P) * sizeof(uint16_t) + 2 * kDkQs * sizeof(float));
+constexpr size_t kDvLds = 2 * ((size_t)(kDvQs * kKp + kHd * ColTile<kDvQs>::P) * sizeof(uint16_t) + 2 * kDvQs * sizeof(float));
+static_assert(kDkLds <= 160 * 1024 && kDvLds <= 160 * 1024 && 2 * kDqLds <= 160 * 1024, "the tiles fit the LDS of a compute unit");
 
 static f8_status check_attn(const void* q, int64_t ldq, const void* k, int64_t ldk, int64_t B, int64_t S, int64_t Hq,
                             int64_t Hkv, int64_t hd)
@@ -590,8 +609,8 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
     if (!configured) {
         // more dynamic LDS than the default limit of a launch: raise it once per process
         if (hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) != hipSuccess ||
-            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<true, kDkQs>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkLds) != hipSuccess ||
-            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) != hipSuccess)
+            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<true, kDkQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkLds) != hipSuccess ||
+            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) != hipSuccess)
             return F8_ERR_LAUNCH;
         configured = true;
     }
@@ -606,11 +625,12 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
         (uint16_t*)dq_bf16, lddq, delta, (int)nt);
     float* part_k = group > 1 ? (float*)workspace : nullptr;
     float* part_v = group > 1 ? part_k + group * M * wk : nullptr;
-    sdpa_bwd_dkv_kernel<true, kDkQs><<<(unsigned)(nt * Hq * B), kAttnThreads, kDkLds, st>>>(
+    const int64_t nkt = (S + 32 * kDkvWaves - 1) / (32 * kDkvWaves);
+    sdpa_bwd_dkv_kernel<true, kDkQs, kDkvWaves><<<(unsigned)(nkt * Hq * B), 64 * kDkvWaves, kDkLds, st>>>(
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)qt_bf16, (const uint16_t*)k_bf16, ldk, (const uint16_t*)v_bf16, ldv,
         (const uint16_t*)do_bf16, lddo, (const uint16_t*)dot_bf16, lse, delta, M, (int)S, (int)Hq, (int)group, scale_log2e,
         scale, (uint16_t*)dk_bf16, lddk, part_k);
-    sdpa_bwd_dkv_kernel<false, kDvQs><<<(unsigned)(nt * Hq * B), kAttnThreads, kDvLds, st>>>(
+    sdpa_bwd_dkv_kernel<false, kDvQs, kDkvWaves><<<(unsigned)(nkt * Hq * B), 64 * kDkvWaves, kDvLds, st>>>(
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)qt_bf16, (const uint16_t*)k_bf16, ldk, (const uint16_t*)v_bf16, ldv,
         (const uint16_t*)do_bf16, lddo, (const uint16_t*)dot_bf16, lse, delta, M, (int)S, (int)Hq, (int)group, scale_log2e,
         scale, (uint16_t*)dv_bf16, lddv, part_v);
