@@ -453,8 +453,8 @@ def layer_main(args, w):
     import torch
     from paper_2410_06511_amd import workloads as wl
     from paper_2410_06511_amd.block import TransformerBlock
-    if args.scaling != "dynamic":
-        print("bench.py: the transformer block runs with dynamic scaling", file=sys.stderr)
+    if args.scaling == "static":
+        print("bench.py: the transformer block runs with dynamic or delayed scaling", file=sys.stderr)
         sys.exit(2)
     sh = wl.LAYER_SHAPE[w.key]
     B, S, Hq, Hkv, hd, D, H = (sh[k] for k in ("B", "S", "Hq", "Hkv", "hd", "D", "H"))
@@ -470,7 +470,7 @@ def layer_main(args, w):
                "Wo": wl.randn_bf16((D, D), 0.02, 0, generator=g).cuda(),
                "W13": wl.randn_bf16((2 * H, D), 0.02, 0, generator=g).cuda(),
                "W2": wl.randn_bf16((D, H), 0.02, 0, generator=g).cuda()}
-    blk = TransformerBlock(B, S, D, H, Hq, Hkv, hd)
+    blk = TransformerBlock(B, S, D, H, Hq, Hkv, hd, scaling=args.scaling)
     stream = torch.cuda.current_stream()
 
     def step():
@@ -520,7 +520,7 @@ def layer_main(args, w):
         "config": {"workload": f"{w.key}: one Llama 3.1 8B transformer block, {B} x {S} tokens, hidden {D}, FFN {H}, "
                                f"{Hq} query / {Hkv} key-value heads of {hd}: rmsnorm -> wq|wk|wv -> rope -> causal attention -> wo -> "
                                "+x -> rmsnorm -> w1|w3 -> silu(a)*b -> w2 -> +h, and the backward of every stage",
-                   "scaling_granularity": "tensorwise", "scaling_strategy": "dynamic", "grad_format": "e4m3",
+                   "scaling_granularity": "tensorwise", "scaling_strategy": args.scaling, "grad_format": "e4m3",
                    "chained": True, "recompute_in_backward": bool(args.recompute), "flops_per_step": flops_step,
                    "attention_flops_per_step_not_counted": att_flops},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),

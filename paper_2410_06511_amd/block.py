@@ -7,8 +7,11 @@ Buffers and the order of calls only: every step runs in the library's kernels.
     x -> rmsnorm -> [wq|wk|wv] -> rope(q), rope(k) -> causal attention -> wo -> + x = h1
     h1 -> rmsnorm -> [w1|w3] -> silu(a) * b -> w2 -> + h1 = out
 
-The Float8 linears use dynamic tensorwise scaling; where a producer already knows the amax of
-what it wrote (rmsnorm, the glue) the consumer's cast takes it instead of a pass of its own.
+scaling="dynamic": the Float8 linears use dynamic tensorwise scaling; where a producer already
+knows the amax of what it wrote (rmsnorm, the glue) the consumer's cast takes it instead of a pass
+of its own.  scaling="delayed": every scale comes from the amax history of earlier steps, every
+cast is a single pass, and the feed-forward glue is fused into the casts of its consumers (h and
+dAB are never written).
 """
 import torch
 
@@ -16,8 +19,12 @@ from . import f8
 
 
 class TransformerBlock:
-    def __init__(self, B, S, D, H, Hq, Hkv, hd=128, eps=1e-5, theta=500000.0, grad_format=f8.E4M3, device="cuda"):
-        assert D == Hq * hd
+    def __init__(self, B, S, D, H, Hq, Hkv, hd=128, eps=1e-5, theta=500000.0, grad_format=f8.E4M3, device="cuda",
+                 scaling="dynamic", history_len=16):
+        assert D == Hq * hd and scaling in ("dynamic", "delayed")
+        self.delayed, self.gfmt = scaling == "delayed", grad_format
+        if self.delayed:
+            self.st_qkv, self.st_o, self.st_13, self.st_2 = (f8.ScalingState(f8.DELAYED, history_len, device) for _ in range(4))
         self.B, self.S, self.D, self.H, self.Hq, self.Hkv, self.hd = B, S, D, H, Hq, Hkv, hd
         self.eps, self.theta = eps, theta
         M = self.M = B * S
@@ -66,6 +73,26 @@ class TransformerBlock:
         Hq, Hkv, hd = self.Hq, self.Hkv, self.hd
         q, k, v = self._slices(self.qkv)
         att_flops = 4 * B * S * S * Hq * hd // 2
+        if self.delayed:
+            return [
+                ("rmsnorm 1", lambda: f8.rmsnorm(x, w["g1"], s.eps, s.xn, s.rstd1, None, None, stream), 0, 4 * M * D),
+                ("linear wq|wk|wv fwd", lambda: f8.linear_fwd_scaled(s.d_qkv, s.st_qkv, s.xn, w["Wqkv"], s.qkv, s.s_qkv, s.ws, stream),
+                 2 * M * D * s.Nqkv, 0),
+                ("rope q (+ transposed copy)", lambda: f8.rope(q, S, Hq, hd, s.qr, s.qt, s.theta, False, stream), 0, 6 * M * Hq * hd),
+                ("rope k (+ transposed copy)", lambda: f8.rope(k, S, Hkv, hd, s.kr, s.kt, s.theta, False, stream), 0, 6 * M * Hkv * hd),
+                ("transpose v", lambda: f8.transpose_bf16(v, s.vt, stream), 0, 4 * M * Hkv * hd),
+                ("attention fwd", lambda: f8.sdpa_fwd(s.qr, s.kr, s.vt, B, S, Hq, Hkv, hd, s.att, s.lse, stream), att_flops, 0),
+                ("linear wo fwd", lambda: f8.linear_fwd_scaled(s.d_o, s.st_o, s.att, w["Wo"], s.yo, s.s_o, s.ws, stream), 2 * M * D * D, 0),
+                ("residual 1", lambda: f8.add(x, s.yo, s.h1, stream), 0, 6 * M * D),
+                ("rmsnorm 2", lambda: f8.rmsnorm(s.h1, w["g2"], s.eps, s.hn, s.rstd2, None, None, stream), 0, 4 * M * D),
+                ("linear w1|w3 fwd", lambda: f8.linear_fwd_scaled(s.d_13, s.st_13, s.hn, w["W13"], s.ab, s.s_13, s.ws, stream),
+                 2 * M * D * 2 * H, 0),
+                ("silu_mul fused into the cast of h", lambda: f8.silu_mul_quantise_delayed(s.ab, f8.E4M3, s.st_2.hist_x, s.st_2.scale_x,
+                                                                                          s.s_2.x, s.ws, stream), 0, 6 * M * H),
+                ("linear w2 fwd (input already quantised)", lambda: f8.linear_fwd_xq(s.d_2, s.st_2, w["W2"], s.y2, s.s_2, s.ws, stream),
+                 2 * M * H * D, 0),
+                ("residual 2", lambda: f8.add(s.h1, s.y2, s.out, stream), 0, 6 * M * D),
+            ]
         return [
             ("rmsnorm 1", lambda: f8.rmsnorm(x, w["g1"], s.eps, s.xn, s.rstd1, s.a_xn, s.ws, stream), 0, 4 * M * D),
             ("linear wq|wk|wv fwd", lambda: f8.linear_fwd_chained(s.d_qkv, s.xn, s.a_xn, w["Wqkv"], s.qkv, None, s.s_qkv, s.ws, stream),
@@ -91,21 +118,35 @@ class TransformerBlock:
         q, k, v = self._slices(self.qkv)
         dq, dk, dv = self._slices(self.dqkv)
         att_flops = 4 * B * S * S * Hq * hd // 2
-        return [
-            ("linear w2 bwd", lambda: f8.linear_bwd(s.d_2, dout, s.s_2, s.dhh, s.dW2, s.ws, stream), 4 * M * H * D, 0),
-            ("silu_mul bwd", lambda: f8.silu_mul_bwd(s.ab, s.dhh, s.dab, s.a_dab, s.ws, stream), 0, 10 * M * H),
-            ("linear w1|w3 bwd", lambda: f8.linear_bwd_chained(s.d_13, s.dab, s.a_dab, s.s_13, s.dhn, None, s.dW13, s.ws, stream),
-             4 * M * D * 2 * H, 0),
+        if self.delayed:
+            ffn = [
+                ("linear w2 bwd", lambda: f8.linear_bwd_scaled(s.d_2, s.st_2, dout, s.s_2, s.dhh, s.dW2, s.ws, stream), 4 * M * H * D, 0),
+                ("silu_mul bwd fused into the cast of dAB", lambda: f8.silu_mul_bwd_quantise_delayed(
+                    s.ab, s.dhh, s.gfmt, s.st_13.hist_dy, s.st_13.scale_dy, s.s_13.dy, s.ws, stream), 0, 10 * M * H),
+                ("linear w1|w3 bwd (gradient already quantised)", lambda: f8.linear_bwd_dyq(s.d_13, s.s_13, s.dhn, s.dW13, stream),
+                 4 * M * D * 2 * H, 0),
+            ]
+            lin_o = lambda: f8.linear_bwd_scaled(s.d_o, s.st_o, s.dh1, s.s_o, s.datt, s.dWo, s.ws, stream)
+            lin_qkv = lambda: f8.linear_bwd_scaled(s.d_qkv, s.st_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream)
+        else:
+            ffn = [
+                ("linear w2 bwd", lambda: f8.linear_bwd(s.d_2, dout, s.s_2, s.dhh, s.dW2, s.ws, stream), 4 * M * H * D, 0),
+                ("silu_mul bwd", lambda: f8.silu_mul_bwd(s.ab, s.dhh, s.dab, s.a_dab, s.ws, stream), 0, 10 * M * H),
+                ("linear w1|w3 bwd", lambda: f8.linear_bwd_chained(s.d_13, s.dab, s.a_dab, s.s_13, s.dhn, None, s.dW13, s.ws, stream),
+                 4 * M * D * 2 * H, 0),
+            ]
+            lin_o = lambda: f8.linear_bwd(s.d_o, s.dh1, s.s_o, s.datt, s.dWo, s.ws, stream)
+            lin_qkv = lambda: f8.linear_bwd(s.d_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream)
+        return ffn + [
             ("rmsnorm 2 bwd", lambda: f8.rmsnorm_bwd(s.h1, w["g2"], s.rstd2, s.dhn, s.dnorm2, s.dg2, s.ws, stream), 0, 10 * M * D),
             ("residual 2 bwd", lambda: f8.add(dout, s.dnorm2, s.dh1, stream), 0, 6 * M * D),
-            ("linear wo bwd", lambda: f8.linear_bwd(s.d_o, s.dh1, s.s_o, s.datt, s.dWo, s.ws, stream), 4 * M * D * D, 0),
+            ("linear wo bwd", lin_o, 4 * M * D * D, 0),
             ("transpose dO", lambda: f8.transpose_bf16(s.datt, s.datt_t, stream), 0, 4 * M * D),
             ("attention bwd", lambda: f8.sdpa_bwd(s.qr, s.qt, s.kr, s.kt, v, s.att, s.datt, s.datt_t, s.lse, B, S, Hq, Hkv, hd,
                                                   s.dqr, s.dkr, dv, s.delta, s.att_ws, stream), 5 * att_flops // 2, 0),
             ("rope q bwd", lambda: f8.rope(s.dqr, S, Hq, hd, dq, None, s.theta, True, stream), 0, 4 * M * Hq * hd),
             ("rope k bwd", lambda: f8.rope(s.dkr, S, Hkv, hd, dk, None, s.theta, True, stream), 0, 4 * M * Hkv * hd),
-            ("linear wq|wk|wv bwd", lambda: f8.linear_bwd(s.d_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream),
-             4 * M * D * s.Nqkv, 0),
+            ("linear wq|wk|wv bwd", lin_qkv, 4 * M * D * s.Nqkv, 0),
             ("rmsnorm 1 bwd", lambda: f8.rmsnorm_bwd(x, w["g1"], s.rstd1, s.dxn, s.dnorm1, s.dg1, s.ws, stream), 0, 10 * M * D),
             ("residual 1 bwd", lambda: f8.add(s.dh1, s.dnorm1, s.dx, stream), 0, 6 * M * D),
         ]

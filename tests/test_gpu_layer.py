@@ -164,3 +164,34 @@ def test_transformer_block_end_to_end_and_recompute():
     assert torch.equal(out.view(torch.int16), blk.out.view(torch.int16))
     for a, b in zip(grads, (blk.dWqkv, blk.dWo, blk.dW13, blk.dW2, blk.dg1, blk.dg2)):
         assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+def test_transformer_block_delayed_scaling_converges_to_dynamic():
+    """Delayed scaling with a history of one step on a constant input: the scale a cast uses is
+    then FMAX / amax of the same tensor one step earlier.  The first linear's input does not depend
+    on any scale, so from the second step on its scale is the dynamic one; every later stage
+    follows one step behind its producer.  After as many steps as there are stages the whole
+    block, with the glue fused into the casts, gives the bits of the dynamic block."""
+    B, S, Hq, Hkv, hd, H = 1, 272, 2, 1, 128, 512
+    D, M = Hq * hd, B * S
+    x, dout = gen((M, D), 21).cuda(), gen((M, D), 22, 1e-2).cuda()
+    w = {"g1": (gen((D,), 23, 0.3) + 1).bfloat16().cuda(), "g2": (gen((D,), 24, 0.3) + 1).bfloat16().cuda(),
+         "Wqkv": gen(((Hq + 2 * Hkv) * hd, D), 25, 0.05).cuda(), "Wo": gen((D, D), 26, 0.05).cuda(),
+         "W13": gen((2 * H, D), 27, 0.05).cuda(), "W2": gen((D, H), 28, 0.05).cuda()}
+    dyn = TransformerBlock(B, S, D, H, Hq, Hkv, hd)
+    dyn.forward(x, w)
+    dyn.backward(x, w, dout)
+    dl = TransformerBlock(B, S, D, H, Hq, Hkv, hd, scaling="delayed", history_len=1)
+    for _ in range(10):
+        dl.forward(x, w)
+        dl.backward(x, w, dout)
+    torch.cuda.synchronize()
+    for n in ("out", "dx", "dWqkv", "dWo", "dW13", "dW2", "dg1", "dg2", "att", "dqkv"):
+        a, b = getattr(dyn, n), getattr(dl, n)
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), n
+    # and the first step, whose scales are the initial ones (1.0), is not the dynamic result
+    fresh = TransformerBlock(B, S, D, H, Hq, Hkv, hd, scaling="delayed", history_len=1)
+    fresh.forward(x, w)
+    torch.cuda.synchronize()
+    assert not torch.equal(fresh.out.view(torch.int16), dyn.out.view(torch.int16))
+
