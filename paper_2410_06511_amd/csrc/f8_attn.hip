@@ -446,6 +446,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
         if (it + 1 < steps) load_step(q0 - QS);
         if (q0 + QS - 1 < key_first) continue;  // every query of the step lies before every key of the wave
         // one 32-query block at a time; registers: queries 32 qb + 8 j + 4 g + i of the step; lane: one key
+        // only the steps at the diagonal or at the end of the sequence have anything to mask (wave-uniform)
+        const bool edge = q0 < key_first + 32 || q0 + QS > S;
         auto block32 = [&](int qb) {
             f32x16 sc = f32x16{0}, dp = f32x16{0};
 #pragma unroll
@@ -471,7 +473,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
                 for (int i = 0; i < 4; ++i) {
                     const int r = 4 * j + i, qp = q0 + ql + i;
                     float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - lv[i]);
-                    if (key_pos > qp || qp >= S) p = 0.0f;
+                    if (edge && (key_pos > qp || qp >= S)) p = 0.0f;
                     sc[r] = DK ? p * (dp[r] - dv[i]) : p;
                 }
             }
