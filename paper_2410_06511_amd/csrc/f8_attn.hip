@@ -27,6 +27,11 @@ constexpr int kKp = kHd + 8;   // LDS row pitch (bf16) of a [tokens][hd] tile: 2
 constexpr int kTp = kBk + 4;   // LDS row pitch (bf16) of a [hd][tokens] tile: 136 bytes = 34 words, an odd multiple of 2:
                                // the 8-byte reads of 32 consecutive rows fall into 32 different bank pairs
 
+template <bool B>
+struct BoolC {
+    static constexpr bool value = B;
+};
+
 __device__ inline f32x16 mma(uint4 first, uint4 second, f32x16 acc)
 {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, first), __builtin_bit_cast(bf16x8, second), acc,
@@ -177,16 +182,19 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
         // subtraction of the maximum are one fused multiply-add per score.
         const bool diagonal = key0 + kBk - 1 > q_first;
         float mx = -INFINITY;
+        if (diagonal) {  // wave-uniform: only the steps at the diagonal have anything to mask
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                if (diagonal) {
+                for (int r = 0; r < 16; ++r) {
                     const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
                     if (key > q_pos) sc[kb][r] = -INFINITY;
                 }
-                mx = fmaxf(mx, sc[kb][r]);
-            }
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[kb][r]);
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
         const float m_new = fmaxf(m_run, mx);  // finite: key 0 is visible to every query
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2e);
@@ -319,8 +327,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
         if (key0 > q_first + 31) continue;
         const uint16_t *tK = sK, *tV = sV, *tKt = sKt;
         const bool diagonal = key0 + kBk - 1 > q_first;
-#pragma unroll 1
-        for (int kb = 0; kb < 2; ++kb) {  // one 32-key block at a time (not unrolled: registers)
+        auto block32 = [&](int kb, auto masked) {  // masked: BoolC, two versions of the code
             f32x16 sc = f32x16{0}, dp = f32x16{0};
 #pragma unroll
             for (int s = 0; s < kHd / 16; ++s) {
@@ -332,7 +339,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - lse2);
-                if (diagonal) {
+                if constexpr (decltype(masked)::value) {
                     const int key = key0 + 32 * kb + 8 * (r >> 2) + 4 * g + (r & 3);
                     if (key > q_pos) p = 0.0f;
                 }
@@ -344,6 +351,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
 #pragma unroll
                 for (int d = 0; d < kHd / 32; ++d) acc[d] = mma(token_slots(tKt + (32 * d + ln) * kTp, 32 * kb, u, g), df, acc[d]);
             }
+        };
+        if (diagonal) {
+#pragma unroll 1
+            for (int kb = 0; kb < 2; ++kb) block32(kb, BoolC<true>{});   // one 32-key block at a time (not unrolled: registers)
+        } else {
+#pragma unroll 1
+            for (int kb = 0; kb < 2; ++kb) block32(kb, BoolC<false>{});
         }
     }
     if (q_ok) {
@@ -448,7 +462,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
         // one 32-query block at a time; registers: queries 32 qb + 8 j + 4 g + i of the step; lane: one key
         // only the steps at the diagonal or at the end of the sequence have anything to mask (wave-uniform)
         const bool edge = q0 < key_first + 32 || q0 + QS > S;
-        auto block32 = [&](int qb) {
+        auto block32 = [&](int qb, auto masked) {  // masked: integral_constant<bool>, two versions of the code
             f32x16 sc = f32x16{0}, dp = f32x16{0};
 #pragma unroll
             for (int s = 0; s < kHd / 16; ++s) {
@@ -473,7 +487,9 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
                 for (int i = 0; i < 4; ++i) {
                     const int r = 4 * j + i, qp = q0 + ql + i;
                     float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - lv[i]);
-                    if (edge && (key_pos > qp || qp >= S)) p = 0.0f;
+                    if constexpr (decltype(masked)::value) {
+                        if (key_pos > qp || qp >= S) p = 0.0f;
+                    }
                     sc[r] = DK ? p * (dp[r] - dv[i]) : p;
                 }
             }
@@ -484,13 +500,17 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
                 for (int d = 0; d < kHd / 32; ++d) acc[d] = mma(token_slots(sT + (32 * d + ln) * TP, 32 * qb, u, g), f, acc[d]);
             }
         };
-        if constexpr (DK) {
+        auto step = [&](auto masked) {
+            if constexpr (DK) {
 #pragma unroll 1
-            for (int qb = 0; qb < QS / 32; ++qb) block32(qb);  // not unrolled: two blocks in flight would not fit the registers
-        } else {
+                for (int qb = 0; qb < QS / 32; ++qb) block32(qb, masked);  // not unrolled: two blocks in flight would not fit the registers
+            } else {
 #pragma unroll
-            for (int qb = 0; qb < QS / 32; ++qb) block32(qb);  // unrolled: one block's exponentials overlap the other's products
-        }
+                for (int qb = 0; qb < QS / 32; ++qb) block32(qb, masked);  // unrolled: one block's exponentials overlap the other's products
+            }
+        };
+        if (edge) step(BoolC<true>{});
+        else step(BoolC<false>{});
     }
     if (!k_ok) return;
     const float mul = DK ? scale : 1.0f;
