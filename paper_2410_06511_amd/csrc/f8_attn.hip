@@ -168,14 +168,24 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
         if (key0 > q_first + 31) continue;  // every key of the step lies after every query of the wave
 
         // S^T = K Q^T: [64 keys][32 queries] as two 32x32 results
-        f32x16 sc[2];
+        // The operand reads run kAhead products ahead of their use (the scheduler is told so:
+        // otherwise every pair of products waits out the LDS latency of its own operands).
+        f32x16 sc[2] = {f32x16{0}, f32x16{0}};
+        {
+            constexpr int kN = 2 * (kHd / 16), kAhead = 4;
+            auto frag = [&](int i) {  // i = 8 kb + s
+                return *reinterpret_cast<const uint4*>(&sK[buf][(32 * (i / (kHd / 16)) + ln) * kKp + 16 * (i % (kHd / 16)) + 8 * g]);
+            };
+            uint4 kf[kN];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            sc[kb] = f32x16{0};
+            for (int i = 0; i < kAhead; ++i) kf[i] = frag(i);
+            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);  // DS reads
 #pragma unroll
-            for (int s = 0; s < kHd / 16; ++s) {
-                const uint4 kf = *reinterpret_cast<const uint4*>(&sK[buf][(32 * kb + ln) * kKp + 16 * s + 8 * g]);
-                sc[kb] = mma(kf, qf[s], sc[kb]);
+            for (int i = 0; i < kN; ++i) {
+                if (i + kAhead < kN) kf[i + kAhead] = frag(i + kAhead);
+                sc[i / (kHd / 16)] = mma(kf[i], qf[i % (kHd / 16)], sc[i / (kHd / 16)]);
+                if (i + kAhead < kN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
             }
         }
         // The maximum is taken over the raw scores (the scale is positive), so the scaling and the
