@@ -23,6 +23,8 @@ constexpr int kAttnThreads = 256;
 constexpr int kHd = 128;   // head dimension of every model the paper trains
 constexpr int kBq = 128;   // queries per block: 32 per wave
 constexpr int kBk = 64;    // keys per step
+// operand reads ahead of their product in the backward kernels: more does not fit their registers
+constexpr int kDqAhead = 2, kDkvAhead = 2;
 constexpr int kKp = kHd + 8;   // LDS row pitch (bf16) of a [tokens][hd] tile: 272 bytes
 constexpr int kTp = kBk + 4;   // LDS row pitch (bf16) of a [hd][tokens] tile: 136 bytes = 34 words, an odd multiple of 2:
                                // the 8-byte reads of 32 consecutive rows fall into 32 different bank pairs
@@ -60,6 +62,25 @@ __device__ inline uint4 token_slots(const uint16_t* tile_row, int t0, int u, int
     const uint2 a = *reinterpret_cast<const uint2*>(tile_row + t0 + 16 * u + 4 * g);
     const uint2 b = *reinterpret_cast<const uint2*>(tile_row + t0 + 16 * u + 8 + 4 * g);
     return make_uint4(a.x, a.y, b.x, b.y);
+}
+
+// N products use(i, frag(i)) whose LDS operand reads (one DS instruction each) run AHEAD products
+// ahead of their use.  Left to itself the scheduler reads each operand right before its product
+// and every product waits out the LDS latency; the group barriers pin the interleaving.
+template <int N, int AHEAD, class Frag, class Use>
+__device__ inline void pipelined_products(Frag frag, Use use)
+{
+    uint4 f[N];
+#pragma unroll
+    for (int i = 0; i < AHEAD && i < N; ++i) f[i] = frag(i);
+    __builtin_amdgcn_sched_group_barrier(0x100, AHEAD < N ? AHEAD : N, 0);  // DS reads
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        if (i + AHEAD < N) f[i + AHEAD] = frag(i + AHEAD);
+        use(i, f[i]);
+        if (i + AHEAD < N) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                  // one MFMA
+    }
 }
 
 // Tile loaders: global -> registers (issued early) -> LDS (after the barrier that frees it).
@@ -168,26 +189,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
         if (key0 > q_first + 31) continue;  // every key of the step lies after every query of the wave
 
         // S^T = K Q^T: [64 keys][32 queries] as two 32x32 results
-        // The operand reads run kAhead products ahead of their use (the scheduler is told so:
-        // otherwise every pair of products waits out the LDS latency of its own operands).
         f32x16 sc[2] = {f32x16{0}, f32x16{0}};
-        {
-            constexpr int kN = 2 * (kHd / 16), kAhead = 4;
-            auto frag = [&](int i) {  // i = 8 kb + s
-                return *reinterpret_cast<const uint4*>(&sK[buf][(32 * (i / (kHd / 16)) + ln) * kKp + 16 * (i % (kHd / 16)) + 8 * g]);
-            };
-            uint4 kf[kN];
-#pragma unroll
-            for (int i = 0; i < kAhead; ++i) kf[i] = frag(i);
-            __builtin_amdgcn_sched_group_barrier(0x100, kAhead, 0);  // DS reads
-#pragma unroll
-            for (int i = 0; i < kN; ++i) {
-                if (i + kAhead < kN) kf[i + kAhead] = frag(i + kAhead);
-                sc[i / (kHd / 16)] = mma(kf[i], qf[i % (kHd / 16)], sc[i / (kHd / 16)]);
-                if (i + kAhead < kN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
-            }
-        }
+        pipelined_products<2 * (kHd / 16), 4>(
+            [&](int i) { return *reinterpret_cast<const uint4*>(&sK[buf][(32 * (i / 8) + ln) * kKp + 16 * (i % 8) + 8 * g]); },
+            [&](int i, uint4 kf) { sc[i / 8] = mma(kf, qf[i % 8], sc[i / 8]); });
         // The maximum is taken over the raw scores (the scale is positive), so the scaling and the
         // subtraction of the maximum are one fused multiply-add per score.
         const bool diagonal = key0 + kBk - 1 > q_first;
@@ -228,17 +233,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
         }
 
         // O^T += V^T P^T: [128 hd][32 queries], contraction over the 64 keys in four 16-slot steps
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const uint4 pf = slots(sc[kb], u);
-#pragma unroll
-                for (int d = 0; d < kHd / 32; ++d) {
-                    const uint4 vf = token_slots(&sV[buf][(32 * d + ln) * kTp], 32 * kb, u, g);
-                    acc_o[d] = mma(vf, pf, acc_o[d]);
-                }
-            }
+        const uint4 pf[4] = {slots(sc[0], 0), slots(sc[0], 1), slots(sc[1], 0), slots(sc[1], 1)};  // [2 kb + u]
+        pipelined_products<16, 4>(
+            [&](int i) { return token_slots(&sV[buf][(32 * (i % 4) + ln) * kTp], 32 * (i / 8), (i / 4) % 2, g); },
+            [&](int i, uint4 vf) { acc_o[i % 4] = mma(vf, pf[i / 4], acc_o[i % 4]); });
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
@@ -339,13 +337,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
         const bool diagonal = key0 + kBk - 1 > q_first;
         auto block32 = [&](int kb, auto masked) {  // masked: BoolC, two versions of the code
             f32x16 sc = f32x16{0}, dp = f32x16{0};
-#pragma unroll
-            for (int s = 0; s < kHd / 16; ++s) {
-                const uint4 kf = *reinterpret_cast<const uint4*>(tK + (32 * kb + ln) * kKp + 16 * s + 8 * g);
-                const uint4 vf = *reinterpret_cast<const uint4*>(tV + (32 * kb + ln) * kKp + 16 * s + 8 * g);
-                sc = mma(kf, qf[s], sc);
-                dp = mma(vf, dof[s], dp);
-            }
+            pipelined_products<2 * (kHd / 16), kDqAhead>(  // even: a K operand for S^T, odd: a V operand for dP^T
+                [&](int i) { return *reinterpret_cast<const uint4*>(((i & 1) ? tV : tK) + (32 * kb + ln) * kKp + 16 * (i / 2) + 8 * g); },
+                [&](int i, uint4 f) {
+                    if (i & 1) dp = mma(f, dof[i / 2], dp);
+                    else sc = mma(f, qf[i / 2], sc);
+                });
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 float p = __builtin_amdgcn_exp2f(sc[r] * scale_log2e - lse2);
@@ -355,12 +352,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
                 }
                 sc[r] = p * (dp[r] - dl);
             }
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const uint4 df = slots(sc, u);
-#pragma unroll
-                for (int d = 0; d < kHd / 32; ++d) acc[d] = mma(token_slots(tKt + (32 * d + ln) * kTp, 32 * kb, u, g), df, acc[d]);
-            }
+            const uint4 df[2] = {slots(sc, 0), slots(sc, 1)};
+            pipelined_products<8, kDqAhead>(
+                [&](int i) { return token_slots(tKt + (32 * (i % 4) + ln) * kTp, 32 * kb, i / 4, g); },
+                [&](int i, uint4 f) { acc[i % 4] = mma(f, df[i / 4], acc[i % 4]); });
         };
         if (diagonal) {
 #pragma unroll 1
@@ -474,14 +469,17 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
         const bool edge = q0 < key_first + 32 || q0 + QS > S;
         auto block32 = [&](int qb, auto masked) {  // masked: integral_constant<bool>, two versions of the code
             f32x16 sc = f32x16{0}, dp = f32x16{0};
-#pragma unroll
-            for (int s = 0; s < kHd / 16; ++s) {
-                const uint4 qfr = *reinterpret_cast<const uint4*>(sQ + (32 * qb + ln) * kKp + 16 * s + 8 * g);
-                sc = mma(qfr, kf[s], sc);
-                if constexpr (DK) {
-                    const uint4 dfr = *reinterpret_cast<const uint4*>(sD + (32 * qb + ln) * kKp + 16 * s + 8 * g);
-                    dp = mma(dfr, vf[s], dp);
-                }
+            if constexpr (DK) {
+                pipelined_products<2 * (kHd / 16), kDkvAhead>(  // even: a Q operand for S, odd: a dO operand for dP
+                    [&](int i) { return *reinterpret_cast<const uint4*>(((i & 1) ? sD : sQ) + (32 * qb + ln) * kKp + 16 * (i / 2) + 8 * g); },
+                    [&](int i, uint4 f) {
+                        if (i & 1) dp = mma(f, vf[i / 2], dp);
+                        else sc = mma(f, kf[i / 2], sc);
+                    });
+            } else {
+                pipelined_products<kHd / 16, kDkvAhead>(
+                    [&](int i) { return *reinterpret_cast<const uint4*>(sQ + (32 * qb + ln) * kKp + 16 * i + 8 * g); },
+                    [&](int i, uint4 f) { sc = mma(f, kf[i], sc); });
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -503,12 +501,10 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
                     sc[r] = DK ? p * (dp[r] - dv[i]) : p;
                 }
             }
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const uint4 f = slots(sc, u);
-#pragma unroll
-                for (int d = 0; d < kHd / 32; ++d) acc[d] = mma(token_slots(sT + (32 * d + ln) * TP, 32 * qb, u, g), f, acc[d]);
-            }
+            const uint4 pf[2] = {slots(sc, 0), slots(sc, 1)};
+            pipelined_products<8, kDkvAhead>(
+                [&](int i) { return token_slots(sT + (32 * (i % 4) + ln) * TP, 32 * qb, i / 4, g); },
+                [&](int i, uint4 f) { acc[i % 4] = mma(f, pf[i / 4], acc[i % 4]); });
         };
         auto step = [&](auto masked) {
             if constexpr (DK) {
