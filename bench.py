@@ -39,8 +39,9 @@ def parse():
                          "handing the amax from the producing GEMM's epilogue to the consumer's cast")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step into a HIP graph once and time its replays")
-    ap.add_argument("--recompute", action="store_true",
-                    help="llama8b_layer: run the forward again inside the backward (full activation checkpointing)")
+    ap.add_argument("--recompute", nargs="?", const="full", default=None, choices=["full", "selective"],
+                    help="llama8b_layer: activation checkpointing: run the forward again inside the backward (full), "
+                         "or only its cheap bf16 operations, keeping the outputs of the products and of the attention (selective)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16-context", action="store_true",
                     help="skip timing torch.matmul in bf16 on the same shapes (context only)")
@@ -475,7 +476,7 @@ def layer_main(args, w):
 
     def step():
         blk.forward(x, weights, stream)
-        blk.backward(x, weights, dout, stream, recompute=args.recompute)
+        blk.backward(x, weights, dout, stream, recompute={"full": True, "selective": "selective", None: False}[args.recompute])
 
     for _ in range(args.warmup):
         step()
@@ -521,7 +522,7 @@ def layer_main(args, w):
                                f"{Hq} query / {Hkv} key-value heads of {hd}: rmsnorm -> wq|wk|wv -> rope -> causal attention -> wo -> "
                                "+x -> rmsnorm -> w1|w3 -> silu(a)*b -> w2 -> +h, and the backward of every stage",
                    "scaling_granularity": "tensorwise", "scaling_strategy": args.scaling, "grad_format": "e4m3",
-                   "chained": True, "recompute_in_backward": bool(args.recompute), "flops_per_step": flops_step,
+                   "chained": True, "recompute_in_backward": args.recompute or "none", "flops_per_step": flops_step,
                    "attention_flops_per_step_not_counted": att_flops},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
         "linears_ms": round(lin_ms, 4), "attention_ms": round(att_ms, 4), "bf16_glue_ms": round(glue_ms, 4),

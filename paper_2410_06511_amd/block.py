@@ -156,10 +156,23 @@ class TransformerBlock:
             call()
         return self.out
 
+    # what selective recomputation runs again: everything the backward reads that is not the output
+    # of a matrix product or of the attention (those are kept, as are the fp8 codes of the linears)
+    SELECTIVE = ("rmsnorm 1", "rope q (+ transposed copy)", "rope k (+ transposed copy)", "residual 1", "rmsnorm 2")
+
     def backward(self, x, w, dout, stream=None, recompute=False):
-        """recompute: run the forward again first, as under full activation checkpointing
-        (Section 2.2.1): the backward then depends on x and the weights only."""
-        if recompute:
+        """recompute (Section 2.2.1, activation checkpointing):
+        True / "full": run the whole forward again first; the backward then depends on x and the
+        weights only.
+        "selective": keep the outputs of the matrix products and of the attention (and the fp8
+        codes saved by the linears) and run again only the cheap operations whose results the
+        backward reads: the normalisation statistics, the rotated q and k with their transposed
+        copies, and the first residual sum."""
+        if recompute == "selective":
+            for name, call, _, _ in self.forward_stages(x, w, stream):
+                if name in self.SELECTIVE:
+                    call()
+        elif recompute:
             self.forward(x, w, stream)
         for _, call, _, _ in self.backward_stages(x, w, dout, stream):
             call()

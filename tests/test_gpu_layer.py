@@ -164,6 +164,16 @@ def test_transformer_block_end_to_end_and_recompute():
     assert torch.equal(out.view(torch.int16), blk.out.view(torch.int16))
     for a, b in zip(grads, (blk.dWqkv, blk.dWo, blk.dW13, blk.dW2, blk.dg1, blk.dg2)):
         assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+    # selective recomputation: the outputs of the products and of the attention are kept, the
+    # cheap tensors are scrambled and come back
+    for n in ("xn", "qr", "qt", "kr", "kt", "vt", "h1", "hn", "hh"):
+        getattr(blk, n).fill_(-3.0)
+    blk.rstd1.fill_(9.0), blk.rstd2.fill_(9.0)
+    dx3 = blk.backward(x, w, dout, recompute="selective")
+    torch.cuda.synchronize()
+    assert torch.equal(dx.view(torch.int16), dx3.view(torch.int16))
+    for a, b in zip(grads, (blk.dWqkv, blk.dWo, blk.dW13, blk.dW2, blk.dg1, blk.dg2)):
+        assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
 
 
 def test_transformer_block_delayed_scaling_converges_to_dynamic():
