@@ -410,8 +410,11 @@ __global__ __launch_bounds__(kThreads) void cast_tile_kernel(
     float s = 0.0f;
     if constexpr (!DYN && GRAN == F8_TENSORWISE) s = scale[0];
 
-    const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kTile;
-    const int64_t c0 = (int64_t)(blockIdx.x % tiles_c) * kTile;
+    // After an amax pass (which sweeps the tensor front to back) the tiles are taken back to front:
+    // what the sweep read last is what the memory-side cache still holds.
+    const unsigned tile_id = DYN ? gridDim.x - 1 - blockIdx.x : blockIdx.x;
+    const int64_t r0 = (int64_t)(tile_id / tiles_c) * kTile;
+    const int64_t c0 = (int64_t)(tile_id % tiles_c) * kTile;
 
     // phase 1: thread (rr, cc) converts the 16-byte chunk cc of rows rr, rr+16, ...
     const int cc = threadIdx.x & 15, rr = threadIdx.x >> 4;
