@@ -17,6 +17,10 @@ Each function is the textbook definition written out:
   add           bf16(a + b)
 Pinned in tests/test_block_oracle_pins.py against closed forms, invariants, PyTorch's own CPU
 attention and complex multiplication, PyTorch autograd and finite differences.
+The paper prints none of these formulas (it names the Llama 3.1 models, Section 3); what the pins
+cannot fix are the choices of that architecture itself, taken here as readings: adjacent-pair
+(interleaved) rotation with theta = 500000, positions counted per sequence, 1 / sqrt(hd) scaling
+with a causal mask, query head h reading key/value head h // (Hq / Hkv), eps inside the root.
 """
 import numpy as np
 
