@@ -633,15 +633,13 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
     if (group > 1 && (!workspace || workspace_bytes_ < f8_sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd))) return F8_ERR_WORKSPACE;
     if (group > 1 && !aligned16(workspace)) return F8_ERR_ALIGN;
     if (B == 0 || S == 0) return F8_OK;
-    static bool configured = false;
-    if (!configured) {
-        // more dynamic LDS than the default limit of a launch: raise it once per process
-        if (hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) != hipSuccess ||
-            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<true, kDkQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkLds) != hipSuccess ||
-            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) != hipSuccess)
-            return F8_ERR_LAUNCH;
-        configured = true;
-    }
+    // more dynamic LDS than the default limit of a launch: raised once per process (the
+    // initialisation of a function-local static is thread-safe)
+    static const bool configured =
+        hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) == hipSuccess &&
+        hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<true, kDkQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkLds) == hipSuccess &&
+        hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) == hipSuccess;
+    if (!configured) return F8_ERR_LAUNCH;
     hipStream_t st = (hipStream_t)stream;
     const int64_t M = B * S, nt = (S + kBq - 1) / kBq;
     if (nt * Hq * B > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
