@@ -23,8 +23,8 @@ constexpr int kAttnThreads = 256;
 constexpr int kHd = 128;   // head dimension of every model the paper trains
 constexpr int kBq = 128;   // queries per block: 32 per wave
 constexpr int kBk = 64;    // keys per step
-// operand reads ahead of their product in the backward kernels: more does not fit their registers
-constexpr int kDqAhead = 2, kDkvAhead = 2;
+// operand reads ahead of their product in the backward kernels: as many as their registers allow
+constexpr int kDqAhead = 4, kDkvAhead = 2;
 constexpr int kKp = kHd + 8;   // LDS row pitch (bf16) of a [tokens][hd] tile: 272 bytes
 constexpr int kTp = kBk + 4;   // LDS row pitch (bf16) of a [hd][tokens] tile: 136 bytes = 34 words, an odd multiple of 2:
                                // the 8-byte reads of 32 consecutive rows fall into 32 different bank pairs
@@ -264,22 +264,22 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
 // kept in fp32 and summed in head order by a small fourth kernel.
 
 // dQ^T = K^T dS^T.  Per 64-key step: S^T = K Q^T, dP^T = V dO^T, dS^T, then the product over keys.
-__global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
+template <int NW>
+__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dq_kernel(
     const uint16_t* __restrict__ Q, int64_t ldq, const uint16_t* __restrict__ K, int64_t ldk, const uint16_t* __restrict__ Kt,
     const uint16_t* __restrict__ V, int64_t ldv, const uint16_t* __restrict__ O, int64_t ldo, const uint16_t* __restrict__ dO,
     int64_t lddo, const float* __restrict__ lse, int64_t M, int S, int Hq, int group, float scale_log2e, float scale,
     uint16_t* __restrict__ dQ, int64_t lddq, float* __restrict__ delta, int nqt)
 {
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    // one buffer per tile: two blocks share a compute unit and cover each other's barriers
-    uint16_t* sK = smem;                   // [kBk * kKp]
-    uint16_t* sV = sK + kBk * kKp;         // [kBk * kKp]
-    uint16_t* sKt = sV + kBk * kKp;        // [kHd * kTp]
+    constexpr int NT = 64 * NW, QB = 32 * NW;  // threads and queries per block
+    constexpr int kBufElems = 2 * kBk * kKp + kHd * kTp;  // K rows, V rows, K^T; twice: the next step's
+                                                          // tiles are stored while slower waves still read this step's
 
     const int nbh = Hq * (int)(M / S), qt = nqt - 1 - (int)(blockIdx.x / nbh);
     const int bh = blockIdx.x % nbh, h = bh % Hq, b = bh / Hq, kvh = h / group;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
-    const int q_first = qt * kBq + wave * 32, q_pos = q_first + ln;
+    const int q_first = qt * QB + wave * 32, q_pos = q_first + ln;
     const int64_t tok0 = (int64_t)b * S;
     const uint16_t* Kb = K + tok0 * ldk + (int64_t)kvh * kHd;
     const uint16_t* Vb = V + tok0 * ldv + (int64_t)kvh * kHd;
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
     if (q_ok && g == 0) delta[(int64_t)h * M + tok] = dl;
     const float lse2 = q_ok ? lse[(int64_t)h * M + tok] * 1.4426950408889634074f : 0.0f;
 
-    int key_end = (qt + 1) * kBq;
+    int key_end = (qt + 1) * QB;
     if (key_end > S) key_end = S;
     const int nkt = (key_end + kBk - 1) / kBk;
 
@@ -315,14 +315,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_bwd_dq_kernel(
 #pragma unroll
     for (int d = 0; d < kHd / 32; ++d) acc[d] = f32x16{0};
 
-    RowTile<kBk> k_regs, v_regs;
-    ColTile<kBk> kt_regs;
+    RowTile<kBk, NT> k_regs, v_regs;
+    ColTile<kBk, NT> kt_regs;
     k_regs.load(Kb, ldk, 0, S);
     v_regs.load(Vb, ldv, 0, S);
     kt_regs.load(Ktb, M, 0, S);
     for (int t = 0; t < nkt; ++t) {
         const int key0 = t * kBk;
-        if (t) __syncthreads();  // the previous step's tiles have been read
+        uint16_t* sK = smem + (t & 1) * kBufElems;  // [kBk][hd]
+        uint16_t* sV = sK + kBk * kKp;              // [kBk][hd]
+        uint16_t* sKt = sV + kBk * kKp;             // [hd][kBk]
         k_regs.store(sK);
         v_regs.store(sV);
         kt_regs.store(sKt);
@@ -564,12 +566,13 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_group_sum_kernel(const floa
     }
 }
 
-constexpr size_t kDqLds = (size_t)(2 * kBk * kKp + kHd * kTp) * sizeof(uint16_t);
+constexpr int kDqWaves = 8;  // 256 queries per block, one block per compute unit
+constexpr size_t kDqLds = 2 * (size_t)(2 * kBk * kKp + kHd * kTp) * sizeof(uint16_t);
 constexpr int kDkvWaves = 8;             // 256 keys per block, one block per compute unit
 constexpr int kDkQs = 64, kDvQs = 64;    // queries per step of the dK and the dV kernel
 constexpr size_t kDkLds = 2 * ((size_t)(2 * kDkQs * kKp + kHd * ColTile<kDkQs>::P) * sizeof(uint16_t) + 2 * kDkQs * sizeof(float));
 constexpr size_t kDvLds = 2 * ((size_t)(kDvQs * kKp + kHd * ColTile<kDvQs>::P) * sizeof(uint16_t) + 2 * kDvQs * sizeof(float));
-static_assert(kDkLds <= 160 * 1024 && kDvLds <= 160 * 1024 && 2 * kDqLds <= 160 * 1024, "the tiles fit the LDS of a compute unit");
+static_assert(kDkLds <= 160 * 1024 && kDvLds <= 160 * 1024 && kDqLds <= 160 * 1024, "the tiles fit the LDS of a compute unit");
 
 static f8_status check_attn(const void* q, int64_t ldq, const void* k, int64_t ldk, int64_t B, int64_t S, int64_t Hq,
                             int64_t Hkv, int64_t hd)
@@ -636,7 +639,7 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
     // more dynamic LDS than the default limit of a launch: raised once per process (the
     // initialisation of a function-local static is thread-safe)
     static const bool configured =
-        hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) == hipSuccess &&
+        hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel<kDqWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) == hipSuccess &&
         hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<true, kDkQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkLds) == hipSuccess &&
         hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) == hipSuccess;
     if (!configured) return F8_ERR_LAUNCH;
@@ -645,10 +648,11 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
     if (nt * Hq * B > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
     const double sc = 1.0 / sqrt((double)hd);
     const float scale = (float)sc, scale_log2e = (float)(sc * 1.4426950408889634074);
-    sdpa_bwd_dq_kernel<<<(unsigned)(nt * Hq * B), kAttnThreads, kDqLds, st>>>(
+    const int64_t nqt = (S + 32 * kDqWaves - 1) / (32 * kDqWaves);
+    sdpa_bwd_dq_kernel<kDqWaves><<<(unsigned)(nqt * Hq * B), 64 * kDqWaves, kDqLds, st>>>(
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)k_bf16, ldk, (const uint16_t*)kt_bf16, (const uint16_t*)v_bf16, ldv,
         (const uint16_t*)o_bf16, ldo, (const uint16_t*)do_bf16, lddo, lse, M, (int)S, (int)Hq, (int)(Hq / Hkv), scale_log2e, scale,
-        (uint16_t*)dq_bf16, lddq, delta, (int)nt);
+        (uint16_t*)dq_bf16, lddq, delta, (int)nqt);
     float* part_k = group > 1 ? (float*)workspace : nullptr;
     float* part_v = group > 1 ? part_k + group * M * wk : nullptr;
     const int64_t nkt = (S + 32 * kDkvWaves - 1) / (32 * kDkvWaves);
