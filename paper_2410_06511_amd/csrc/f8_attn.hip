@@ -23,8 +23,8 @@ constexpr int kAttnThreads = 256;
 constexpr int kHd = 128;   // head dimension of every model the paper trains
 constexpr int kBq = 128;   // queries per block: 32 per wave
 constexpr int kBk = 64;    // keys per step
-// operand reads ahead of their product in the backward kernels: as many as their registers allow
-constexpr int kDqAhead = 4, kDkvAhead = 2;
+// operand reads ahead of their product: deeper did not help the forward, and is all the dK kernel's registers allow
+constexpr int kFwdAhead = 4, kDqAhead = 4, kDkvAhead = 2;
 constexpr int kKp = kHd + 8;   // LDS row pitch (bf16) of a [tokens][hd] tile: 272 bytes
 constexpr int kTp = kBk + 4;   // LDS row pitch (bf16) of a [hd][tokens] tile: 136 bytes = 34 words, an odd multiple of 2:
                                // the 8-byte reads of 32 consecutive rows fall into 32 different bank pairs
@@ -135,14 +135,16 @@ struct ColTile {
 };
 
 // ---- forward ------------------------------------------------------------------------------
-// One block: 128 queries of one (sequence, head); each wave owns 32 of them.  Loop over 64-key
+// One block: NW waves of 32 queries each of one (sequence, head).  Loop over 64-key
 // steps up to the diagonal; K and V^T tiles double-buffered in LDS.
-__global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_t* __restrict__ Q, int64_t ldq,
+template <int NW>
+__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_fwd_kernel(const uint16_t* __restrict__ Q, int64_t ldq,
                                                                 const uint16_t* __restrict__ K, int64_t ldk,
                                                                 const uint16_t* __restrict__ Vt, int64_t M, int S, int Hq,
                                                                 int group, float scale_log2e, uint16_t* __restrict__ O,
                                                                 int64_t ldo, float* __restrict__ lse, int nqt)
 {
+    constexpr int NT = 64 * NW, QB = 32 * NW;  // threads and queries per block
     __shared__ __attribute__((aligned(16))) uint16_t sK[2][kBk * kKp];
     __shared__ __attribute__((aligned(16))) uint16_t sV[2][kHd * kTp];
 
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
     const int nbh = Hq * (int)(M / S), qt = nqt - 1 - (int)(blockIdx.x / nbh);
     const int bh = blockIdx.x % nbh, h = bh % Hq, b = bh / Hq, kvh = h / group;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ln = lane & 31, g = lane >> 5;
-    const int q_first = qt * kBq + wave * 32;  // of this wave
+    const int q_first = qt * QB + wave * 32;  // of this wave
     const int q_pos = q_first + ln;            // position of this lane's query in its sequence
     const int64_t tok0 = (int64_t)b * S;
     const uint16_t* Kb = K + tok0 * ldk + (int64_t)kvh * kHd;
@@ -164,7 +166,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
         for (int s = 0; s < kHd / 16; ++s) qf[s] = ok ? *reinterpret_cast<const uint4*>(row + 16 * s) : make_uint4(0, 0, 0, 0);
     }
 
-    int key_end = (qt + 1) * kBq;  // keys at or beyond it are masked for every query of the block
+    int key_end = (qt + 1) * QB;  // keys at or beyond it are masked for every query of the block
     if (key_end > S) key_end = S;
     const int nkt = (key_end + kBk - 1) / kBk;
 
@@ -173,8 +175,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
     for (int d = 0; d < kHd / 32; ++d) acc_o[d] = f32x16{0};
     float m_run = -INFINITY, l_run = 0.0f;  // running maximum of the raw scores and this lane's share of the sum
 
-    RowTile<kBk> kt_regs;
-    ColTile<kBk> vt_regs;
+    RowTile<kBk, NT> kt_regs;
+    ColTile<kBk, NT> vt_regs;
     kt_regs.load(Kb, ldk, 0, S);
     vt_regs.load(Vb, M, 0, S);
     for (int t = 0; t < nkt; ++t) {
@@ -190,7 +192,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
 
         // S^T = K Q^T: [64 keys][32 queries] as two 32x32 results
         f32x16 sc[2] = {f32x16{0}, f32x16{0}};
-        pipelined_products<2 * (kHd / 16), 4>(
+        pipelined_products<2 * (kHd / 16), kFwdAhead>(
             [&](int i) { return *reinterpret_cast<const uint4*>(&sK[buf][(32 * (i / 8) + ln) * kKp + 16 * (i % 8) + 8 * g]); },
             [&](int i, uint4 kf) { sc[i / 8] = mma(kf, qf[i % 8], sc[i / 8]); });
         // The maximum is taken over the raw scores (the scale is positive), so the scaling and the
@@ -234,7 +236,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void sdpa_fwd_kernel(const uint16_
 
         // O^T += V^T P^T: [128 hd][32 queries], contraction over the 64 keys in four 16-slot steps
         const uint4 pf[4] = {slots(sc[0], 0), slots(sc[0], 1), slots(sc[1], 0), slots(sc[1], 1)};  // [2 kb + u]
-        pipelined_products<16, 4>(
+        pipelined_products<16, kFwdAhead>(
             [&](int i) { return token_slots(&sV[buf][(32 * (i % 4) + ln) * kTp], 32 * (i / 8), (i / 4) % 2, g); },
             [&](int i, uint4 vf) { acc_o[i % 4] = mma(vf, pf[i / 4], acc_o[i % 4]); });
     }
@@ -600,10 +602,11 @@ f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64
     if (ldo < Hq * hd || (ldo % 8)) return F8_ERR_SHAPE;
     if (!aligned16(vt_bf16) || !aligned16(o_bf16)) return F8_ERR_ALIGN;
     if (B == 0 || S == 0) return F8_OK;
-    const int64_t nqt = (S + kBq - 1) / kBq, nb = nqt * Hq * B;
+    constexpr int kFwdWaves = 8;  // 256 queries per block, one block per compute unit
+    const int64_t nqt = (S + 32 * kFwdWaves - 1) / (32 * kFwdWaves), nb = nqt * Hq * B;
     if (nb > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
     const float scale_log2e = (float)(1.4426950408889634074 / sqrt((double)hd));
-    sdpa_fwd_kernel<<<(unsigned)nb, kAttnThreads, 0, (hipStream_t)stream>>>(
+    sdpa_fwd_kernel<kFwdWaves><<<(unsigned)nb, 64 * kFwdWaves, 0, (hipStream_t)stream>>>(
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)k_bf16, ldk, (const uint16_t*)vt_bf16, B * S, (int)S, (int)Hq,
         (int)(Hq / Hkv), scale_log2e, (uint16_t*)o_bf16, ldo, lse, (int)nqt);
     return last_launch_status();
