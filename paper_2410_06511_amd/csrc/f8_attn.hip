@@ -21,7 +21,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kAttnThreads = 256;
 constexpr int kHd = 128;   // head dimension of every model the paper trains
-constexpr int kBq = 128;   // queries per block: 32 per wave
 constexpr int kBk = 64;    // keys per step
 // operand reads ahead of their product: deeper did not help the forward, and is all the dK kernel's registers allow
 constexpr int kFwdAhead = 4, kDqAhead = 4, kDkvAhead = 2;
@@ -647,8 +646,8 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
         hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) == hipSuccess;
     if (!configured) return F8_ERR_LAUNCH;
     hipStream_t st = (hipStream_t)stream;
-    const int64_t M = B * S, nt = (S + kBq - 1) / kBq;
-    if (nt * Hq * B > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
+    const int64_t M = B * S;
+    if ((S + 255) / 256 * Hq * B > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;  // one block per 256 tokens and head
     const double sc = 1.0 / sqrt((double)hd);
     const float scale = (float)sc, scale_log2e = (float)(sc * 1.4426950408889634074);
     const int64_t nqt = (S + 32 * kDqWaves - 1) / (32 * kDqWaves);
