@@ -22,8 +22,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kAttnThreads = 256;
 constexpr int kHd = 128;   // head dimension of every model the paper trains
 constexpr int kBk = 64;    // keys per step
-// operand reads ahead of their product: deeper did not help the forward, and is all the dK kernel's registers allow
-constexpr int kFwdAhead = 4, kDqAhead = 4, kDkvAhead = 2;
+// operand reads ahead of their product (deeper did not help)
+constexpr int kFwdAhead = 4, kDqAhead = 4, kDkvAhead = 4;
 constexpr int kKp = kHd + 8;   // LDS row pitch (bf16) of a [tokens][hd] tile: 272 bytes
 constexpr int kTp = kBk + 4;   // LDS row pitch (bf16) of a [hd][tokens] tile: 136 bytes = 34 words, an odd multiple of 2:
                                // the 8-byte reads of 32 consecutive rows fall into 32 different bank pairs
