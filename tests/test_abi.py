@@ -81,6 +81,39 @@ def test_argument_errors_are_reported_before_any_launch():
     assert l.f8_linear_bwd(C.byref(bad), FAKE, C.byref(sv), FAKE, FAKE, FAKE, 1 << 20, None) == 4
 
 
+def test_block_entry_points_reject_bad_arguments_before_any_launch():
+    l = f8.lib()
+    # rope: no output; head dimension not a multiple of 8 / too large; pitch smaller than the row; sequence length 0
+    assert l.f8_rope(FAKE, 128, 16, 16, 1, 128, 500000.0, 0, None, 0, None, None) == 1
+    assert l.f8_rope(FAKE, 128, 16, 16, 1, 12, 500000.0, 0, FAKE, 128, None, None) == 2
+    assert l.f8_rope(FAKE, 512, 16, 16, 1, 512, 500000.0, 0, FAKE, 512, None, None) == 2
+    assert l.f8_rope(FAKE, 64, 16, 16, 1, 128, 500000.0, 0, FAKE, 128, None, None) == 2
+    assert l.f8_rope(FAKE, 128, 16, 0, 1, 128, 500000.0, 0, FAKE, 128, None, None) == 2
+    assert l.f8_rope(FAKE + 2, 128, 16, 16, 1, 128, 500000.0, 0, FAKE, 128, None, None) == 3
+    # transpose, add
+    assert l.f8_transpose_bf16(FAKE, 16, 16, 20, FAKE, None) == 2
+    assert l.f8_transpose_bf16(FAKE, 32, 16, 32, None, None) == 1
+    assert l.f8_add(FAKE, FAKE, 12, FAKE, None) == 2
+    assert l.f8_add(FAKE, None, 16, FAKE, None) == 1
+    # rmsnorm backward: neither output; dg without workspace
+    assert l.f8_rmsnorm_bwd(FAKE, FAKE, FAKE, FAKE, 16, 16, None, None, None, 0, None) == 1
+    assert l.f8_rmsnorm_bwd(FAKE, FAKE, FAKE, FAKE, 16, 16, FAKE, FAKE, None, 0, None) == 5
+    assert l.f8_rmsnorm_bwd(FAKE, FAKE, FAKE, FAKE, 16, 24, FAKE, None, None, 0, None) == 2
+    # attention: head dimension, sequence length, head grouping, pitches, workspace of the grouped backward
+    fwd = lambda B, S, Hq, Hkv, hd, ldq=4096, ldk=1024, vt=FAKE: l.f8_sdpa_fwd(FAKE, ldq, FAKE, ldk, vt, B, S, Hq, Hkv, hd, FAKE, 4096, FAKE, None)
+    assert fwd(1, 64, 32, 8, 64) == 2
+    assert fwd(1, 60, 32, 8, 128) == 2
+    assert fwd(1, 64, 32, 5, 128) == 2
+    assert fwd(1, 64, 32, 8, 128, ldq=2048) == 2
+    assert fwd(1, 64, 32, 8, 128, vt=None) == 1
+    assert f8.sdpa_bwd_workspace_bytes(1, 8192, 32, 8, 128) == 2 * 8192 * 4096 * 4
+    assert f8.sdpa_bwd_workspace_bytes(1, 8192, 8, 8, 128) == 0
+    bwd = lambda ws, nbytes: l.f8_sdpa_bwd(FAKE, 4096, FAKE, FAKE, 1024, FAKE, FAKE, 1024, FAKE, 4096, FAKE, 4096, FAKE, FAKE,
+                                           1, 64, 32, 8, 128, FAKE, 4096, FAKE, 1024, FAKE, 1024, FAKE, ws, nbytes, None)
+    assert bwd(None, 0) == 5
+    assert bwd(FAKE, 1024) == 5
+
+
 def test_binding_raises_with_message():
     with pytest.raises(f8.F8Error) as e:
         f8._check(5)
