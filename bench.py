@@ -513,6 +513,32 @@ def layer_main(args, w):
             glue_ms, glue_bytes = glue_ms + ms, glue_bytes + by
         legs.append(leg)
     att_tflops = att_flops / (att_ms * 1e-3) / 1e12
+    context = None
+    if not args.no_bf16_context:
+        # Context, not part of the path: the library attention (torch's scaled_dot_product_attention,
+        # forward and backward through autograd) on tensors of the same shape.
+        F = torch.nn.functional
+        qh = torch.randn((B, Hq, S, hd), dtype=torch.bfloat16, device="cuda", requires_grad=True)
+        kh = torch.randn((B, Hkv, S, hd), dtype=torch.bfloat16, device="cuda", requires_grad=True)
+        vh = torch.randn((B, Hkv, S, hd), dtype=torch.bfloat16, device="cuda", requires_grad=True)
+        go = torch.randn((B, Hq, S, hd), dtype=torch.bfloat16, device="cuda") * 1e-2
+        try:
+            def lib_attention():
+                o = F.scaled_dot_product_attention(qh, kh, vh, is_causal=True, enable_gqa=True)
+                o.backward(go)
+                qh.grad = kh.grad = vh.grad = None
+            for _ in range(2):
+                lib_attention()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(5):
+                lib_attention()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            context = {"ms_fwd_bwd": round(e0.elapsed_time(e1) / 5, 4),
+                       "what": "torch.nn.functional.scaled_dot_product_attention (is_causal, enable_gqa) forward + autograd backward, same shape"}
+        except Exception as exc:  # the library path is context only
+            context = {"error": str(exc)[:200]}
     out = {
         "metric": "Float8 linear fwd+bwd TFLOP/s (% FP8 MFMA peak) + amax/cast HBM GB/s",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -532,6 +558,7 @@ def layer_main(args, w):
                      "bound": "mfma", "achieved": round(att_tflops, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(att_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
         "glue_gbs": round(glue_bytes / (glue_ms * 1e-3) / 1e9, 1),
+        "library_attention_context": context,
         "legs": legs,
     }
     print(json.dumps(out))
