@@ -175,14 +175,20 @@ __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dg_partial_kernel(const u
     }
 }
 
+// dg[c] = sum over the strips, always in the same order: 64 columns per block, four groups of
+// threads take every fourth strip each, their four sums are added in group order.
 __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dg_final_kernel(const float* __restrict__ partial, int strips, int64_t D,
                                                                        float* __restrict__ dg)
 {
-    const int64_t c = (int64_t)blockIdx.x * kBlkThreads + threadIdx.x;
-    if (c >= D) return;
+    __shared__ float red[4][64];
+    const int cl = threadIdx.x & 63, part = threadIdx.x >> 6;
+    const int64_t c = (int64_t)blockIdx.x * 64 + cl;
     float s = 0.0f;
-    for (int i = 0; i < strips; ++i) s += partial[(int64_t)i * D + c];
-    dg[c] = s;
+    if (c < D)
+        for (int i = part; i < strips; i += 4) s += partial[(int64_t)i * D + c];
+    red[part][cl] = s;
+    __syncthreads();
+    if (part == 0 && c < D) dg[c] = ((red[0][cl] + red[1][cl]) + red[2][cl]) + red[3][cl];
 }
 
 static int elementwise_blocks(int64_t chunks)
@@ -276,7 +282,7 @@ f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rs
         if (strips)
             rmsnorm_dg_partial_kernel<<<(unsigned)(strips * tiles_c), kBlkThreads, 0, st>>>(
                 (const uint16_t*)x_bf16, rstd, (const uint16_t*)dy_bf16, M, D, strip_rows, (float*)workspace, (int)tiles_c);
-        rmsnorm_dg_final_kernel<<<(unsigned)((D + kBlkThreads - 1) / kBlkThreads), kBlkThreads, 0, st>>>(
+        rmsnorm_dg_final_kernel<<<(unsigned)((D + 63) / 64), kBlkThreads, 0, st>>>(
             (const float*)workspace, (int)strips, D, dg);
     }
     return last_launch_status();
