@@ -26,62 +26,78 @@ __device__ inline uint32_t rotate_word(uint32_t w, float c, float s)
     return pack_bf16(x0 * c - x1 * s, x0 * s + x1 * c);
 }
 
-// x [rows, cols] (row pitch ldx) -> out [rows, cols] (row pitch ldo; ROTATE: pairs of adjacent
-// columns turned by pos * freq) and out_t [cols, rows] (packed).  One block per 64x64 tile; rows,
-// cols and the pitches are multiples of 8.
+// x [rows, nh * hd] (row pitch ldx) -> out (row pitch ldo; ROTATE: pairs of adjacent columns turned
+// by pos * freq) and out_t [nh * hd, rows] (packed).  One block: a 64x64 tile at the same place of
+// `hpb` consecutive heads, one head after the other: the sines and cosines depend on the row and
+// on the column inside the head only, so they are taken once and used for every head.  rows, hd
+// and the pitches are multiples of 8.  (The plain transposition is the case of one head of width
+// cols.)
 template <bool ROTATE, bool OUT, bool OUT_T>
-__global__ __launch_bounds__(kBlkThreads) void rope_tile_kernel(const uint16_t* __restrict__ x, int64_t rows, int64_t cols,
-                                                                int64_t ldx, int64_t ldo, int64_t S, int hd, float sign, RopeFreq fr,
+__global__ __launch_bounds__(kBlkThreads) void rope_tile_kernel(const uint16_t* __restrict__ x, int64_t rows, int nh, int hd,
+                                                                int hpb, int64_t ldx, int64_t ldo, int64_t S, float sign, RopeFreq fr,
                                                                 uint16_t* __restrict__ out, uint16_t* __restrict__ out_t,
-                                                                int tiles_c)
+                                                                int tiles_c /* per row of tiles: tiles per head x head groups */)
 {
     __shared__ uint16_t tile[kRt * kRtStride];
-    const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kRt, c0 = (int64_t)(blockIdx.x % tiles_c) * kRt;
+    const int tph = (hd + kRt - 1) / kRt;  // tiles per head
+    const int tc = blockIdx.x % tiles_c;
+    const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kRt;
+    const int c0 = (tc % tph) * kRt, h0 = (tc / tph) * hpb;  // column inside the head, first head
     const int cc = threadIdx.x & 7, rr = threadIdx.x >> 3;
-    const int64_t col = c0 + cc * 8;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int rl = rr + 32 * i;
-        const int64_t r = r0 + rl;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (col < cols && r < rows) {
-            v = *reinterpret_cast<const uint4*>(x + r * ldx + col);
-            if constexpr (ROTATE) {
-                const double pos = (double)(r % S);
-                const int j0 = (int)(col % hd) >> 1;
-                uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    // the angle reaches thousands of radians: product and reduction to
-                    // [-pi, pi] in fp64, sine and cosine of the remainder in fp32
-                    const double a = pos * fr.f[j0 + j];
-                    const double red = a - 6.283185307179586476925286766559 * rint(a * 0.15915494309189533576888376337251);
-                    float sn, cs;
-                    sincosf((float)red, &sn, &cs);
-                    w[j] = rotate_word(w[j], cs, sign * sn);
-                }
-                v = make_uint4(w[0], w[1], w[2], w[3]);
-            }
-            if constexpr (OUT) *reinterpret_cast<uint4*>(out + r * ldo + col) = v;
-        }
-        if constexpr (OUT_T) {
-            uint32_t* t32 = reinterpret_cast<uint32_t*>(tile + rl * kRtStride + cc * 8);  // 4-byte aligned: pitch and cc*8 are even
-            t32[0] = v.x, t32[1] = v.y, t32[2] = v.z, t32[3] = v.w;
-        }
-    }
-    if constexpr (OUT_T) {
-        __syncthreads();
-        const int rb = threadIdx.x & 7, cb = threadIdx.x >> 3;
-        const int64_t rbase = r0 + 8 * rb;
+    const int cih = c0 + cc * 8;            // this thread's column inside the head
+    const bool col_ok = cih < hd;
+    float cs[2][4], sn[2][4];
+    if constexpr (ROTATE) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int c = cb + 32 * i;
-            uint32_t o[4];
+            const int64_t r = r0 + rr + 32 * i;
+            const double pos = (double)(r % S);
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                o[j] = (uint32_t)tile[(8 * rb + 2 * j) * kRtStride + c] | ((uint32_t)tile[(8 * rb + 2 * j + 1) * kRtStride + c] << 16);
-            if (rbase < rows && c0 + c < cols)  // rows is a multiple of 8: the piece is all in or all out
-                *reinterpret_cast<uint4*>(out_t + (c0 + c) * rows + rbase) = make_uint4(o[0], o[1], o[2], o[3]);
+            for (int j = 0; j < 4; ++j) {
+                // the angle reaches thousands of radians: product and reduction to
+                // [-pi, pi] in fp64, sine and cosine of the remainder in fp32
+                const double a = pos * fr.f[col_ok ? (cih >> 1) + j : 0];
+                const double red = a - 6.283185307179586476925286766559 * rint(a * 0.15915494309189533576888376337251);
+                sincosf((float)red, &sn[i][j], &cs[i][j]);
+                sn[i][j] *= sign;
+            }
+        }
+    }
+    const int h_end = h0 + hpb < nh ? h0 + hpb : nh;
+    for (int h = h0; h < h_end; ++h) {
+        const int64_t col = (int64_t)h * hd + cih;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int rl = rr + 32 * i;
+            const int64_t r = r0 + rl;
+            uint4 v = make_uint4(0, 0, 0, 0);
+            if (col_ok && r < rows) {
+                v = *reinterpret_cast<const uint4*>(x + r * ldx + col);
+                if constexpr (ROTATE)
+                    v = make_uint4(rotate_word(v.x, cs[i][0], sn[i][0]), rotate_word(v.y, cs[i][1], sn[i][1]),
+                                   rotate_word(v.z, cs[i][2], sn[i][2]), rotate_word(v.w, cs[i][3], sn[i][3]));
+                if constexpr (OUT) *reinterpret_cast<uint4*>(out + r * ldo + col) = v;
+            }
+            if constexpr (OUT_T) {
+                uint32_t* t32 = reinterpret_cast<uint32_t*>(tile + rl * kRtStride + cc * 8);  // 4-byte aligned: pitch and cc*8 are even
+                t32[0] = v.x, t32[1] = v.y, t32[2] = v.z, t32[3] = v.w;
+            }
+        }
+        if constexpr (OUT_T) {
+            __syncthreads();
+            const int rb = threadIdx.x & 7, cb = threadIdx.x >> 3;
+            const int64_t rbase = r0 + 8 * rb;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int c = cb + 32 * i;
+                uint32_t o[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    o[j] = (uint32_t)tile[(8 * rb + 2 * j) * kRtStride + c] | ((uint32_t)tile[(8 * rb + 2 * j + 1) * kRtStride + c] << 16);
+                if (rbase < rows && c0 + c < hd)  // rows is a multiple of 8: the piece is all in or all out
+                    *reinterpret_cast<uint4*>(out_t + ((int64_t)h * hd + c0 + c) * rows + rbase) = make_uint4(o[0], o[1], o[2], o[3]);
+            }
+            __syncthreads();  // the tile is free for the next head
         }
     }
 }
@@ -200,16 +216,22 @@ static int elementwise_blocks(int64_t chunks)
 }
 
 template <bool ROTATE>
-static f8_status launch_rope_tiles(const void* x, int64_t rows, int64_t cols, int64_t ldx, int64_t ldo, int64_t S, int hd, float sign, const RopeFreq& fr,
-                                   void* out, void* out_t, hipStream_t st)
+static f8_status launch_rope_tiles(const void* x, int64_t rows, int64_t nh, int64_t hd, int64_t ldx, int64_t ldo, int64_t S,
+                                   float sign, const RopeFreq& fr, void* out, void* out_t, hipStream_t st)
 {
-    const int64_t tiles_r = (rows + kRt - 1) / kRt, tiles_c = (cols + kRt - 1) / kRt;
+    // heads per block: as many as leave about four blocks per compute unit
+    const int64_t tiles_r = (rows + kRt - 1) / kRt, tph = (hd + kRt - 1) / kRt;
+    int64_t hpb = (tiles_r * tph * nh) / 1024;
+    if (hpb < 1) hpb = 1;
+    if (hpb > 8) hpb = 8;
+    if (hpb > nh) hpb = nh;
+    const int64_t tiles_c = tph * ((nh + hpb - 1) / hpb);
     const int64_t nb = tiles_r * tiles_c;
     if (nb == 0) return F8_OK;
     if (nb > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
-#define F8_ROPE_LAUNCH(O, T)                                                                                  \
-    rope_tile_kernel<ROTATE, O, T><<<(unsigned)nb, kBlkThreads, 0, st>>>((const uint16_t*)x, rows, cols, ldx, ldo, S, hd, sign, fr, \
-                                                                         (uint16_t*)out, (uint16_t*)out_t, (int)tiles_c)
+#define F8_ROPE_LAUNCH(O, T)                                                                                              \
+    rope_tile_kernel<ROTATE, O, T><<<(unsigned)nb, kBlkThreads, 0, st>>>((const uint16_t*)x, rows, (int)nh, (int)hd, (int)hpb, ldx, \
+                                                                         ldo, S, sign, fr, (uint16_t*)out, (uint16_t*)out_t, (int)tiles_c)
     if (out && out_t) F8_ROPE_LAUNCH(true, true);
     else if (out) F8_ROPE_LAUNCH(true, false);
     else F8_ROPE_LAUNCH(false, true);
@@ -233,7 +255,7 @@ f8_status f8_rope(const void* x_bf16, int64_t ldx, int64_t M, int64_t S, int64_t
     if (!aligned16(x_bf16) || (out_bf16 && !aligned16(out_bf16)) || (out_t_bf16 && !aligned16(out_t_bf16))) return F8_ERR_ALIGN;
     RopeFreq fr;
     for (int i = 0; i < 128; ++i) fr.f[i] = i < hd / 2 ? pow(theta, -2.0 * (double)i / (double)hd) : 0.0;
-    return launch_rope_tiles<true>(x_bf16, M, n_heads * hd, ldx, ldo, S, (int)hd, inverse ? -1.0f : 1.0f, fr, out_bf16, out_t_bf16,
+    return launch_rope_tiles<true>(x_bf16, M, n_heads, hd, ldx, ldo, S, inverse ? -1.0f : 1.0f, fr, out_bf16, out_t_bf16,
                                    (hipStream_t)stream);
 }
 
@@ -243,7 +265,8 @@ f8_status f8_transpose_bf16(const void* x_bf16, int64_t ldx, int64_t rows, int64
     if (rows < 0 || cols < 0 || (rows % 8) || (cols % 8) || ldx < cols || (ldx % 8)) return F8_ERR_SHAPE;
     if (!aligned16(x_bf16) || !aligned16(out_t_bf16)) return F8_ERR_ALIGN;
     RopeFreq fr = {};
-    return launch_rope_tiles<false>(x_bf16, rows, cols, ldx, cols, 1, 8, 1.0f, fr, nullptr, out_t_bf16, (hipStream_t)stream);
+    if (cols >= ((int64_t)1 << 31)) return F8_ERR_SHAPE;
+    return launch_rope_tiles<false>(x_bf16, rows, 1, cols, ldx, cols, 1, 1.0f, fr, nullptr, out_t_bf16, (hipStream_t)stream);
 }
 
 f8_status f8_add(const void* a_bf16, const void* b_bf16, int64_t n, void* out_bf16, void* stream)
