@@ -129,7 +129,9 @@ __device__ inline uint32_t dx_word(uint32_t x, uint32_t g, uint32_t d, float r, 
     return pack_bf16(r * (bf16_lo(g) * bf16_lo(d)) - bf16_lo(x) * k, r * (bf16_hi(g) * bf16_hi(d)) - bf16_hi(x) * k);
 }
 
-// one wave per row: the row is read twice (the second time from the caches)
+// one wave per row.  NC > 0: at most NC 16-byte chunks per lane, x and dy are kept in registers
+// between the two passes; NC = 0: any row length, the rows are read twice (second time from the caches)
+template <int NC>
 __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dx_kernel(const uint4* __restrict__ x, const uint4* __restrict__ g,
                                                                  const float* __restrict__ rstd, const uint4* __restrict__ dy,
                                                                  int64_t M, int64_t dc, float inv_d, uint4* __restrict__ dx)
@@ -138,18 +140,38 @@ __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dx_kernel(const uint4* __
     for (int64_t m = (int64_t)blockIdx.x * kBlkWaves + wave; m < M; m += (int64_t)gridDim.x * kBlkWaves) {
         const uint4 *xr = x + m * dc, *dr = dy + m * dc;
         float t = 0.0f;
-        for (int64_t c = lane; c < dc; c += kWave) {
-            const uint4 v = xr[c], w = g[c], d = dr[c];
-            t += (xgd_word(v.x, w.x, d.x) + xgd_word(v.y, w.y, d.y)) + (xgd_word(v.z, w.z, d.z) + xgd_word(v.w, w.w, d.w));
+        uint4 kx[NC > 0 ? NC : 1], kd[NC > 0 ? NC : 1];
+        auto term = [&](uint4 v, uint4 w, uint4 d) {
+            return (xgd_word(v.x, w.x, d.x) + xgd_word(v.y, w.y, d.y)) + (xgd_word(v.z, w.z, d.z) + xgd_word(v.w, w.w, d.w));
+        };
+        if constexpr (NC > 0) {
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                const int64_t c = lane + (int64_t)kWave * i;
+                kx[i] = c < dc ? xr[c] : make_uint4(0, 0, 0, 0);
+                kd[i] = c < dc ? dr[c] : make_uint4(0, 0, 0, 0);
+                if (c < dc) t += term(kx[i], g[c], kd[i]);
+            }
+        } else {
+            for (int64_t c = lane; c < dc; c += kWave) t += term(xr[c], g[c], dr[c]);
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) t += __shfl_xor(t, off, kWave);
         const float r = rstd[m];
         const float k = ((r * r) * r) * (t * inv_d);
-        for (int64_t c = lane; c < dc; c += kWave) {
-            const uint4 v = xr[c], w = g[c], d = dr[c];
+        auto emit = [&](int64_t c, uint4 v, uint4 d) {
+            const uint4 w = g[c];
             dx[m * dc + c] = make_uint4(dx_word(v.x, w.x, d.x, r, k), dx_word(v.y, w.y, d.y, r, k),
                                         dx_word(v.z, w.z, d.z, r, k), dx_word(v.w, w.w, d.w, r, k));
+        };
+        if constexpr (NC > 0) {
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                const int64_t c = lane + (int64_t)kWave * i;
+                if (c < dc) emit(c, kx[i], kd[i]);
+            }
+        } else {
+            for (int64_t c = lane; c < dc; c += kWave) emit(c, xr[c], dr[c]);
         }
     }
 }
@@ -296,8 +318,12 @@ f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rs
     if (dx_bf16 && M) {
         int64_t nb = (M + kBlkWaves - 1) / kBlkWaves;
         if (nb > 8192) nb = 8192;
-        rmsnorm_dx_kernel<<<(unsigned)nb, kBlkThreads, 0, st>>>((const uint4*)x_bf16, (const uint4*)g_bf16, rstd,
-                                                                (const uint4*)dy_bf16, M, D / 8, 1.0f / (float)D, (uint4*)dx_bf16);
+#define F8_DX_LAUNCH(NC)                                                                                      \
+    rmsnorm_dx_kernel<NC><<<(unsigned)nb, kBlkThreads, 0, st>>>((const uint4*)x_bf16, (const uint4*)g_bf16, rstd, \
+                                                                (const uint4*)dy_bf16, M, D / 8, 1.0f / (float)D, (uint4*)dx_bf16)
+        if (D <= 8 * kWave * 8) F8_DX_LAUNCH(8);  // rows up to 4096 elements stay in registers
+        else F8_DX_LAUNCH(0);
+#undef F8_DX_LAUNCH
     }
     if (dg) {
         const int64_t tiles_c = (D + 63) / 64;

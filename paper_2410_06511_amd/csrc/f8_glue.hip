@@ -85,6 +85,9 @@ __device__ inline uint32_t scale_word(uint32_t x, uint32_t g, float r)
     return pack_bf16((bf16_lo(x) * r) * bf16_lo(g), (bf16_hi(x) * r) * bf16_hi(g));
 }
 
+// NC > 0: a row has at most NC 16-byte chunks per lane and is kept in registers between the two
+// passes; NC = 0: any row length, the second pass reads the row again (from the caches).
+template <int NC>
 __global__ __launch_bounds__(kGlueThreads) void rmsnorm_kernel(const uint4* __restrict__ x, const uint4* __restrict__ g,
                                                               int64_t M, int64_t dc /* 16-byte chunks per row */,
                                                               float inv_d, float eps, uint4* __restrict__ y,
@@ -96,21 +99,40 @@ __global__ __launch_bounds__(kGlueThreads) void rmsnorm_kernel(const uint4* __re
     for (int64_t m = (int64_t)blockIdx.x * kGlueWaves + wave; m < M; m += (int64_t)gridDim.x * kGlueWaves) {
         const uint4* row = x + m * dc;
         float ss = 0.0f;
-        for (int64_t c = lane; c < dc; c += kWave) {
-            const uint4 v = row[c];
-            ss += (sumsq_word(v.x) + sumsq_word(v.y)) + (sumsq_word(v.z) + sumsq_word(v.w));
+        uint4 keep[NC > 0 ? NC : 1];
+        if constexpr (NC > 0) {
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                const int64_t c = lane + (int64_t)kWave * i;
+                keep[i] = c < dc ? row[c] : make_uint4(0, 0, 0, 0);
+                ss += (sumsq_word(keep[i].x) + sumsq_word(keep[i].y)) + (sumsq_word(keep[i].z) + sumsq_word(keep[i].w));
+            }
+        } else {
+            for (int64_t c = lane; c < dc; c += kWave) {
+                const uint4 v = row[c];
+                ss += (sumsq_word(v.x) + sumsq_word(v.y)) + (sumsq_word(v.z) + sumsq_word(v.w));
+            }
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) ss += __shfl_xor(ss, off, kWave);
         const float r = 1.0f / sqrtf(ss * inv_d + eps);
         if (lane == 0 && rstd) rstd[m] = r;
-        for (int64_t c = lane; c < dc; c += kWave) {
-            const uint4 v = row[c], w = g[c];
+        auto emit = [&](int64_t c, uint4 v) {
+            const uint4 w = g[c];
             uint4 o;
             o.x = scale_word(v.x, w.x, r), o.y = scale_word(v.y, w.y, r);
             o.z = scale_word(v.z, w.z, r), o.w = scale_word(v.w, w.w, r);
             y[m * dc + c] = o;
             acc = absmax_acc(acc, o);
+        };
+        if constexpr (NC > 0) {
+#pragma unroll
+            for (int i = 0; i < NC; ++i) {
+                const int64_t c = lane + (int64_t)kWave * i;
+                if (c < dc) emit(c, keep[i]);
+            }
+        } else {
+            for (int64_t c = lane; c < dc; c += kWave) emit(c, row[c]);
         }
     }
     if (partial) {
@@ -189,8 +211,13 @@ f8_status f8_rmsnorm(const void* x_bf16, const void* g_bf16, int64_t M, int64_t 
     if (M > 0 && D > 0) {
         int64_t b = (M + kGlueWaves - 1) / kGlueWaves;
         nb = (int)(b > kGlueMaxBlocks ? kGlueMaxBlocks : b);
-        rmsnorm_kernel<<<nb, kGlueThreads, 0, st>>>((const uint4*)x_bf16, (const uint4*)g_bf16, M, D / 8, 1.0f / (float)D, eps,
-                                                    (uint4*)y_bf16, rstd, amax_y ? (uint32_t*)workspace : nullptr);
+#define F8_RMSNORM_LAUNCH(NC)                                                                                         \
+    rmsnorm_kernel<NC><<<nb, kGlueThreads, 0, st>>>((const uint4*)x_bf16, (const uint4*)g_bf16, M, D / 8, 1.0f / (float)D, eps, \
+                                                    (uint4*)y_bf16, rstd, amax_y ? (uint32_t*)workspace : nullptr)
+        if (D <= 8 * kWave * 8) F8_RMSNORM_LAUNCH(8);         // rows up to 4096 elements stay in registers
+        else if (D <= 8 * kWave * 16) F8_RMSNORM_LAUNCH(16);  // up to 8192
+        else F8_RMSNORM_LAUNCH(0);
+#undef F8_RMSNORM_LAUNCH
     }
     if (amax_y) glue_amax_final_kernel<<<1, kGlueThreads, 0, st>>>((const uint32_t*)workspace, nb, amax_y);
     return last_launch_status();
