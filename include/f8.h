@@ -461,6 +461,11 @@ size_t f8_sdpa_bwd_workspace_bytes(int64_t B, int64_t S, int64_t Hq, int64_t Hkv
 f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16,
                          int64_t M, int64_t D, void* dx_bf16, float* dg, void* workspace,
                          size_t workspace_bytes, void* stream);
+/* The same with the residual branch's gradient added: dx = bf16(add + bf16(dx above)), the bits
+ * that f8_rmsnorm_bwd followed by f8_add gives, without writing and re-reading the first. */
+f8_status f8_rmsnorm_bwd_add(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16,
+                             const void* add_bf16, int64_t M, int64_t D, void* dx_bf16, float* dg,
+                             void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Forward of the linear whose input is already quantised in saved->x (codes in

@@ -52,12 +52,12 @@ class TransformerBlock:
         self.y2, self.out = E(M, D), E(M, D)
         # backward
         self.dhh, self.dab, self.a_dab = E(M, H), E(M, 2 * H), torch.empty(1, **f32)
-        self.dhn, self.dnorm2, self.dh1 = E(M, D), E(M, D), E(M, D)
+        self.dhn, self.dh1 = E(M, D), E(M, D)
         self.datt, self.datt_t = E(M, D), E(D, M)
         self.dqr, self.dkr, self.delta = E(M, Hq * hd), E(M, Hkv * hd), torch.empty((Hq, M), **f32)
         self.att_ws = torch.empty(max(16, f8.sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd)), dtype=torch.uint8, device=device)
         self.dqkv = E(M, self.Nqkv)
-        self.dxn, self.dnorm1, self.dx = E(M, D), E(M, D), E(M, D)
+        self.dxn, self.dx = E(M, D), E(M, D)
         self.dg1, self.dg2 = torch.empty(D, **f32), torch.empty(D, **f32)
         self.dWqkv, self.dWo = E(self.Nqkv, D), E(D, D)
         self.dW13, self.dW2 = E(2 * H, D), E(D, H)
@@ -138,8 +138,8 @@ class TransformerBlock:
             lin_o = lambda: f8.linear_bwd(s.d_o, s.dh1, s.s_o, s.datt, s.dWo, s.ws, stream)
             lin_qkv = lambda: f8.linear_bwd(s.d_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream)
         return ffn + [
-            ("rmsnorm 2 bwd", lambda: f8.rmsnorm_bwd(s.h1, w["g2"], s.rstd2, s.dhn, s.dnorm2, s.dg2, s.ws, stream), 0, 10 * M * D),
-            ("residual 2 bwd", lambda: f8.add(dout, s.dnorm2, s.dh1, stream), 0, 6 * M * D),
+            ("rmsnorm 2 bwd + residual", lambda: f8.rmsnorm_bwd_add(s.h1, w["g2"], s.rstd2, s.dhn, dout, s.dh1, s.dg2, s.ws, stream),
+             0, 12 * M * D),
             ("linear wo bwd", lin_o, 4 * M * D * D, 0),
             ("transpose dO", lambda: f8.transpose_bf16(s.datt, s.datt_t, stream), 0, 4 * M * D),
             ("attention bwd", lambda: f8.sdpa_bwd(s.qr, s.qt, s.kr, s.kt, v, s.att, s.datt, s.datt_t, s.lse, B, S, Hq, Hkv, hd,
@@ -147,8 +147,8 @@ class TransformerBlock:
             ("rope q bwd", lambda: f8.rope(s.dqr, S, Hq, hd, dq, None, s.theta, True, stream), 0, 4 * M * Hq * hd),
             ("rope k bwd", lambda: f8.rope(s.dkr, S, Hkv, hd, dk, None, s.theta, True, stream), 0, 4 * M * Hkv * hd),
             ("linear wq|wk|wv bwd", lin_qkv, 4 * M * D * s.Nqkv, 0),
-            ("rmsnorm 1 bwd", lambda: f8.rmsnorm_bwd(x, w["g1"], s.rstd1, s.dxn, s.dnorm1, s.dg1, s.ws, stream), 0, 10 * M * D),
-            ("residual 1 bwd", lambda: f8.add(s.dh1, s.dnorm1, s.dx, stream), 0, 6 * M * D),
+            ("rmsnorm 1 bwd + residual", lambda: f8.rmsnorm_bwd_add(x, w["g1"], s.rstd1, s.dxn, s.dh1, s.dx, s.dg1, s.ws, stream),
+             0, 12 * M * D),
         ]
 
     def forward(self, x, w, stream=None):

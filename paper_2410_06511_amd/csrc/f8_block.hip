@@ -19,6 +19,11 @@ struct RopeFreq {
     double f[128];  // theta^(-2 i / hd), i < hd / 2 <= 128
 };
 
+__device__ inline uint32_t add_word(uint32_t a, uint32_t b)
+{
+    return pack_bf16(bf16_lo(a) + bf16_lo(b), bf16_hi(a) + bf16_hi(b));
+}
+
 // rotate the pair (lo, hi) of one word by (c, s)
 __device__ inline uint32_t rotate_word(uint32_t w, float c, float s)
 {
@@ -102,10 +107,6 @@ __global__ __launch_bounds__(kBlkThreads) void rope_tile_kernel(const uint16_t* 
     }
 }
 
-__device__ inline uint32_t add_word(uint32_t a, uint32_t b)
-{
-    return pack_bf16(bf16_lo(a) + bf16_lo(b), bf16_hi(a) + bf16_hi(b));
-}
 
 __global__ __launch_bounds__(kBlkThreads) void add_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b, int64_t n,
                                                           uint4* __restrict__ out)
@@ -134,7 +135,8 @@ __device__ inline uint32_t dx_word(uint32_t x, uint32_t g, uint32_t d, float r, 
 template <int NC>
 __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dx_kernel(const uint4* __restrict__ x, const uint4* __restrict__ g,
                                                                  const float* __restrict__ rstd, const uint4* __restrict__ dy,
-                                                                 int64_t M, int64_t dc, float inv_d, uint4* __restrict__ dx)
+                                                                 int64_t M, int64_t dc, float inv_d, uint4* __restrict__ dx,
+                                                                 const uint4* __restrict__ res /* nullable: added to dx */)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     for (int64_t m = (int64_t)blockIdx.x * kBlkWaves + wave; m < M; m += (int64_t)gridDim.x * kBlkWaves) {
@@ -161,8 +163,13 @@ __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dx_kernel(const uint4* __
         const float k = ((r * r) * r) * (t * inv_d);
         auto emit = [&](int64_t c, uint4 v, uint4 d) {
             const uint4 w = g[c];
-            dx[m * dc + c] = make_uint4(dx_word(v.x, w.x, d.x, r, k), dx_word(v.y, w.y, d.y, r, k),
-                                        dx_word(v.z, w.z, d.z, r, k), dx_word(v.w, w.w, d.w, r, k));
+            uint4 o = make_uint4(dx_word(v.x, w.x, d.x, r, k), dx_word(v.y, w.y, d.y, r, k),
+                                 dx_word(v.z, w.z, d.z, r, k), dx_word(v.w, w.w, d.w, r, k));
+            if (res) {  // the residual branch's gradient: the same two roundings as f8_add after this call
+                const uint4 a = res[m * dc + c];
+                o = make_uint4(add_word(a.x, o.x), add_word(a.y, o.y), add_word(a.z, o.z), add_word(a.w, o.w));
+            }
+            dx[m * dc + c] = o;
         };
         if constexpr (NC > 0) {
 #pragma unroll
@@ -302,8 +309,8 @@ f8_status f8_add(const void* a_bf16, const void* b_bf16, int64_t n, void* out_bf
     return last_launch_status();
 }
 
-f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16, int64_t M,
-                         int64_t D, void* dx_bf16, float* dg, void* workspace, size_t workspace_bytes_, void* stream)
+static f8_status rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16, const void* add_bf16,
+                             int64_t M, int64_t D, void* dx_bf16, float* dg, void* workspace, size_t workspace_bytes_, void* stream)
 {
     if (!x_bf16 || !g_bf16 || !rstd || !dy_bf16 || (!dx_bf16 && !dg)) return F8_ERR_NULL;
     if (M < 0 || D < 0 || (M % 16) || (D % 16)) return F8_ERR_SHAPE;
@@ -320,7 +327,8 @@ f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rs
         if (nb > 8192) nb = 8192;
 #define F8_DX_LAUNCH(NC)                                                                                      \
     rmsnorm_dx_kernel<NC><<<(unsigned)nb, kBlkThreads, 0, st>>>((const uint4*)x_bf16, (const uint4*)g_bf16, rstd, \
-                                                                (const uint4*)dy_bf16, M, D / 8, 1.0f / (float)D, (uint4*)dx_bf16)
+                                                                (const uint4*)dy_bf16, M, D / 8, 1.0f / (float)D, (uint4*)dx_bf16, \
+                                                                (const uint4*)add_bf16)
         if (D <= 8 * kWave * 8) F8_DX_LAUNCH(8);  // rows up to 4096 elements stay in registers
         else F8_DX_LAUNCH(0);
 #undef F8_DX_LAUNCH
@@ -335,6 +343,21 @@ f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rs
             (const float*)workspace, (int)strips, D, dg);
     }
     return last_launch_status();
+}
+
+f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16, int64_t M,
+                         int64_t D, void* dx_bf16, float* dg, void* workspace, size_t workspace_bytes_, void* stream)
+{
+    return rmsnorm_bwd(x_bf16, g_bf16, rstd, dy_bf16, nullptr, M, D, dx_bf16, dg, workspace, workspace_bytes_, stream);
+}
+
+f8_status f8_rmsnorm_bwd_add(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16,
+                             const void* add_bf16, int64_t M, int64_t D, void* dx_bf16, float* dg, void* workspace,
+                             size_t workspace_bytes_, void* stream)
+{
+    if (!add_bf16 || !dx_bf16) return F8_ERR_NULL;
+    if (!aligned16(add_bf16)) return F8_ERR_ALIGN;
+    return rmsnorm_bwd(x_bf16, g_bf16, rstd, dy_bf16, add_bf16, M, D, dx_bf16, dg, workspace, workspace_bytes_, stream);
 }
 
 }  // extern "C"

@@ -28,7 +28,8 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise",
            "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq",
            "f8_silu_mul_bwd_quantise_delayed", "f8_linear_bwd_dyq",
-           "f8_rope", "f8_transpose_bf16", "f8_add", "f8_rmsnorm_bwd", "f8_sdpa_fwd", "f8_sdpa_bwd", "f8_sdpa_bwd_workspace_bytes"]
+           "f8_rope", "f8_transpose_bf16", "f8_add", "f8_rmsnorm_bwd", "f8_sdpa_fwd", "f8_sdpa_bwd", "f8_sdpa_bwd_workspace_bytes",
+           "f8_rmsnorm_bwd_add"]
 
 
 class F8Error(RuntimeError):
@@ -99,6 +100,7 @@ def lib():
         l.f8_transpose_bf16.argtypes = [_p, _i64, _i64, _i64, _p, _p]
         l.f8_add.argtypes = [_p, _p, _i64, _p, _p]
         l.f8_rmsnorm_bwd.argtypes = [_p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
+        l.f8_rmsnorm_bwd_add.argtypes = [_p, _p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_sdpa_fwd.argtypes = [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _p, _p]
         l.f8_sdpa_bwd.argtypes = [_p, _i64, _p, _p, _i64, _p, _p, _i64, _p, _i64, _p, _i64, _p, _p, _i64, _i64, _i64, _i64,
                                   _i64, _p, _i64, _p, _i64, _p, _i64, _p, _p, C.c_size_t, _p]
@@ -361,6 +363,13 @@ def rmsnorm_bwd(x, g, rstd, dy, dx, dg, workspace=None, stream=None):
     M, D = x.shape
     wp, wb = _ws(workspace)
     _check(lib().f8_rmsnorm_bwd(_ptr(x), _ptr(g), _ptr(rstd), _ptr(dy), M, D, _ptr(dx), _ptr(dg), wp, wb, _stream(stream)))
+
+
+def rmsnorm_bwd_add(x, g, rstd, dy, add_t, dx, dg, workspace=None, stream=None):
+    M, D = x.shape
+    wp, wb = _ws(workspace)
+    _check(lib().f8_rmsnorm_bwd_add(_ptr(x), _ptr(g), _ptr(rstd), _ptr(dy), _ptr(add_t), M, D, _ptr(dx), _ptr(dg), wp, wb,
+                                    _stream(stream)))
 
 
 def sdpa_fwd(q, k, vt, B, S, Hq, Hkv, hd, o, lse, stream=None):

@@ -119,6 +119,13 @@ def test_rmsnorm_backward(M, D):
     f8.rmsnorm_bwd(x.cuda(), g.cuda(), rstd, dy.cuda(), None, dg2, ws)
     torch.cuda.synchronize()
     assert torch.equal(dx.view(torch.int16), dx2.view(torch.int16)) and torch.equal(dg, dg2)
+    # with the residual branch's gradient added inside: the bits of the two calls in sequence
+    res = gen((M, D), 5 * M + D, 1e-2).cuda()
+    ref_sum, fused, dg3 = torch.empty_like(dx), torch.empty_like(dx), torch.empty_like(dg)
+    f8.add(res, dx, ref_sum)
+    f8.rmsnorm_bwd_add(x.cuda(), g.cuda(), rstd, dy.cuda(), res, fused, dg3, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ref_sum.view(torch.int16), fused.view(torch.int16)) and torch.equal(dg, dg3)
 
 
 def test_block_glue_argument_errors():

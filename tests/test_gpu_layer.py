@@ -59,16 +59,16 @@ def oracle_block(x, w, dout, B, S, Hq, Hkv, hd, eps):
     r["dhh"], r["dW2"], _ = o.linear_bwd(dout, xq_2, wq_2)
     r["dab"], r["a_dab"] = o.silu_mul_bwd(r["ab"], r["dhh"])
     r["dhn"], r["dW13"], _ = o.linear_bwd(r["dab"], xq_13, wq_13)
-    r["dnorm2"], r["dg2"] = bo.rmsnorm_bwd(r["h1"], w["g2"], r["dhn"], eps)
-    r["dh1"] = bo.add(dout, r["dnorm2"])
+    dnorm2, r["dg2"] = bo.rmsnorm_bwd(r["h1"], w["g2"], r["dhn"], eps)
+    r["dh1"] = bo.add(dout, dnorm2)
     r["datt"], r["dWo"], _ = o.linear_bwd(r["dh1"], xq_o, wq_o)
     r["datt_t"] = bo.transpose(r["datt"])
     r["dqr"], r["dkr"], dv = bo.sdpa_bwd(r["qr"], r["kr"], v, r["datt"], B, S, Hq, Hkv, hd)
     dq, dk = bo.rope(r["dqr"], S, hd, inverse=True), bo.rope(r["dkr"], S, hd, inverse=True)
     r["dqkv"] = np.ascontiguousarray(np.concatenate([dq, dk, dv], axis=1))
     r["dxn"], r["dWqkv"], _ = o.linear_bwd(r["dqkv"], xq_qkv, wq_qkv)
-    r["dnorm1"], r["dg1"] = bo.rmsnorm_bwd(x, w["g1"], r["dxn"], eps)
-    r["dx"] = bo.add(r["dh1"], r["dnorm1"])
+    dnorm1, r["dg1"] = bo.rmsnorm_bwd(x, w["g1"], r["dxn"], eps)
+    r["dx"] = bo.add(r["dh1"], dnorm1)
     return r
 
 
@@ -79,9 +79,9 @@ WRITES = {
     "linear wo fwd": ["yo"], "residual 1": ["h1"], "rmsnorm 2": ["hn", "rstd2", "a_hn"], "linear w1|w3 fwd": ["ab"],
     "silu_mul": ["hh", "a_hh"], "linear w2 fwd": ["y2"], "residual 2": ["out"],
     "linear w2 bwd": ["dhh", "dW2"], "silu_mul bwd": ["dab", "a_dab"], "linear w1|w3 bwd": ["dhn", "dW13"],
-    "rmsnorm 2 bwd": ["dnorm2", "dg2"], "residual 2 bwd": ["dh1"], "linear wo bwd": ["datt", "dWo"],
+    "rmsnorm 2 bwd + residual": ["dh1", "dg2"], "linear wo bwd": ["datt", "dWo"],
     "transpose dO": ["datt_t"], "attention bwd": ["dqr", "dkr"], "rope q bwd": [], "rope k bwd": [],
-    "linear wq|wk|wv bwd": ["dxn", "dWqkv"], "rmsnorm 1 bwd": ["dnorm1", "dg1"], "residual 1 bwd": ["dx"],
+    "linear wq|wk|wv bwd": ["dxn", "dWqkv"], "rmsnorm 1 bwd + residual": ["dx", "dg1"],
 }
 EXACT = {"vt", "datt_t"}                      # copies of a tensor that the oracle's has replaced
 TRANSPOSED_WITH = {"qt": "qr", "kt": "kr"}    # written by the same call as their untransposed twin
