@@ -135,7 +135,8 @@ struct ColTile {
 
 // ---- forward ------------------------------------------------------------------------------
 // One block: NW waves of 32 queries each of one (sequence, head).  Loop over 64-key
-// steps up to the diagonal; K and V^T tiles double-buffered in LDS.
+// steps up to the diagonal; K and V^T tiles double-buffered in LDS, the next step's tiles
+// prefetched into registers while this step computes.
 template <int NW>
 __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_fwd_kernel(const uint16_t* __restrict__ Q, int64_t ldq,
                                                                 const uint16_t* __restrict__ K, int64_t ldk,
@@ -386,8 +387,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dq_kernel(
 // later queries of its head, and a larger key tile halves that traffic and the prefetch
 // registers per thread.  Both halves recompute S = Q K^T; taken together they
 // would need the key and value operands, two sets of accumulators and four tiles per step, more
-// than the 256 registers of a wave at two blocks per compute unit, and would run without the
-// register prefetch of the next step's tiles.
+// than the 256 registers a wave has at two waves per SIMD.
 template <bool DK, int QS, int NW>
 __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
     const uint16_t* __restrict__ Q, int64_t ldq, const uint16_t* __restrict__ Qt, const uint16_t* __restrict__ K, int64_t ldk,
