@@ -417,11 +417,14 @@ f8_status f8_add(const void* a_bf16, const void* b_bf16, int64_t n, void* out_bf
  * fp32: the log of the softmax denominator (natural log, scaled scores), kept
  * for the backward.  Scores and probabilities are never written: bf16 matrix
  * instructions with fp32 accumulation, online softmax, probabilities rounded to
- * bf16 before they multiply the values.  S and the pitches multiples of 8.
+ * bf16 before they multiply the values.  amax_o (nullable, 1 float) receives
+ * the exact maximum magnitude of the bf16 values written to o, for
+ * f8_linear_fwd_chained of the output projection.  S and the pitches
+ * multiples of 8.
  */
 f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64_t ldk, const void* vt_bf16,
                       int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t hd, void* o_bf16,
-                      int64_t ldo, float* lse, void* stream);
+                      int64_t ldo, float* lse, float* amax_o, void* stream);
 
 /*
  * Backward of f8_sdpa_fwd.  With P recomputed from lse and delta[q] = sum_d dO O:

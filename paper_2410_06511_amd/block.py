@@ -45,7 +45,7 @@ class TransformerBlock:
         self.qkv = E(M, self.Nqkv)
         self.qr, self.kr = E(M, Hq * hd), E(M, Hkv * hd)                 # rotated q, k
         self.qt, self.kt, self.vt = E(Hq * hd, M), E(Hkv * hd, M), E(Hkv * hd, M)
-        self.att, self.lse = E(M, D), torch.empty((Hq, M), **f32)
+        self.att, self.lse, self.a_att = E(M, D), torch.empty((Hq, M), **f32), torch.empty(1, **f32)
         self.yo, self.h1 = E(M, D), E(M, D)
         self.hn, self.rstd2, self.a_hn = E(M, D), torch.empty(M, **f32), torch.empty(1, **f32)
         self.ab, self.hh, self.a_hh = E(M, 2 * H), E(M, H), torch.empty(1, **f32)
@@ -100,8 +100,8 @@ class TransformerBlock:
             ("rope q (+ transposed copy)", lambda: f8.rope(q, S, Hq, hd, s.qr, s.qt, s.theta, False, stream), 0, 6 * M * Hq * hd),
             ("rope k (+ transposed copy)", lambda: f8.rope(k, S, Hkv, hd, s.kr, s.kt, s.theta, False, stream), 0, 6 * M * Hkv * hd),
             ("transpose v", lambda: f8.transpose_bf16(v, s.vt, stream), 0, 4 * M * Hkv * hd),
-            ("attention fwd", lambda: f8.sdpa_fwd(s.qr, s.kr, s.vt, B, S, Hq, Hkv, hd, s.att, s.lse, stream), att_flops, 0),
-            ("linear wo fwd", lambda: f8.linear_fwd(s.d_o, s.att, w["Wo"], s.yo, s.s_o, s.ws, stream), 2 * M * D * D, 0),
+            ("attention fwd", lambda: f8.sdpa_fwd(s.qr, s.kr, s.vt, B, S, Hq, Hkv, hd, s.att, s.lse, stream, s.a_att), att_flops, 0),
+            ("linear wo fwd", lambda: f8.linear_fwd_chained(s.d_o, s.att, s.a_att, w["Wo"], s.yo, None, s.s_o, s.ws, stream), 2 * M * D * D, 0),
             ("residual 1", lambda: f8.add(x, s.yo, s.h1, stream), 0, 6 * M * D),
             ("rmsnorm 2", lambda: f8.rmsnorm(s.h1, w["g2"], s.eps, s.hn, s.rstd2, s.a_hn, s.ws, stream), 0, 4 * M * D),
             ("linear w1|w3 fwd", lambda: f8.linear_fwd_chained(s.d_13, s.hn, s.a_hn, w["W13"], s.ab, None, s.s_13, s.ws, stream),

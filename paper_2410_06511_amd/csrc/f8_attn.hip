@@ -142,7 +142,8 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_fwd_kernel(cons
                                                                 const uint16_t* __restrict__ K, int64_t ldk,
                                                                 const uint16_t* __restrict__ Vt, int64_t M, int S, int Hq,
                                                                 int group, float scale_log2e, uint16_t* __restrict__ O,
-                                                                int64_t ldo, float* __restrict__ lse, int nqt)
+                                                                int64_t ldo, float* __restrict__ lse, int nqt,
+                                                                uint32_t* __restrict__ amax_bits /* nullable */)
 {
     constexpr int NT = 64 * NW, QB = 32 * NW;  // threads and queries per block
     __shared__ __attribute__((aligned(16))) uint16_t sK[2][kBk * kKp];
@@ -242,6 +243,7 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_fwd_kernel(cons
     }
 
     const float l_tot = l_run + __shfl_xor(l_run, 32, kWave);
+    uint32_t mag = 0;  // packed pair of the largest 15-bit magnitudes written
     if (q_pos < S) {
         const float inv = 1.0f / l_tot;
         uint16_t* orow = O + (tok0 + q_pos) * ldo + (int64_t)h * kHd + 4 * g;
@@ -252,10 +254,19 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_fwd_kernel(cons
                 const uint2 w = make_uint2(pack2(acc_o[d][4 * j] * inv, acc_o[d][4 * j + 1] * inv),
                                            pack2(acc_o[d][4 * j + 2] * inv, acc_o[d][4 * j + 3] * inv));
                 *reinterpret_cast<uint2*>(orow + 32 * d + 8 * j) = w;
+                mag = pkmax(pkmax(mag, w.x & 0x7FFF7FFFu), w.y & 0x7FFF7FFFu);
             }
         if (g == 0) lse[(int64_t)h * M + tok0 + q_pos] = (m_run * scale_log2e + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
     }
+    if (amax_bits) {
+        // the exact maximum magnitude of the bf16 values written, as float bits: a maximum of
+        // non-negative floats is a maximum of their bit patterns, and does not depend on the order
+        const uint32_t m = wave_max_u32(pk_collapse(mag)) << 16;
+        if (lane == 0 && m > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, m);
+    }
 }
+
+__global__ void zero_amax_kernel(uint32_t* p) { p[0] = 0; }
 
 // ---- backward -----------------------------------------------------------------------------
 // With P = exp(S / sqrt(hd) - lse) recomputed from the saved lse and delta[q] = sum_d dO O:
@@ -593,21 +604,23 @@ using namespace f8;
 extern "C" {
 
 f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64_t ldk, const void* vt_bf16, int64_t B,
-                      int64_t S, int64_t Hq, int64_t Hkv, int64_t hd, void* o_bf16, int64_t ldo, float* lse, void* stream)
+                      int64_t S, int64_t Hq, int64_t Hkv, int64_t hd, void* o_bf16, int64_t ldo, float* lse, float* amax_o,
+                      void* stream)
 {
     f8_status s = check_attn(q_bf16, ldq, k_bf16, ldk, B, S, Hq, Hkv, hd);
     if (s != F8_OK) return s;
     if (!vt_bf16 || !o_bf16 || !lse) return F8_ERR_NULL;
     if (ldo < Hq * hd || (ldo % 8)) return F8_ERR_SHAPE;
     if (!aligned16(vt_bf16) || !aligned16(o_bf16)) return F8_ERR_ALIGN;
-    if (B == 0 || S == 0) return F8_OK;
+    if (amax_o) zero_amax_kernel<<<1, 1, 0, (hipStream_t)stream>>>(reinterpret_cast<uint32_t*>(amax_o));
+    if (B == 0 || S == 0) return last_launch_status();
     constexpr int kFwdWaves = 8;  // 256 queries per block, one block per compute unit
     const int64_t nqt = (S + 32 * kFwdWaves - 1) / (32 * kFwdWaves), nb = nqt * Hq * B;
     if (nb > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
     const float scale_log2e = (float)(1.4426950408889634074 / sqrt((double)hd));
     sdpa_fwd_kernel<kFwdWaves><<<(unsigned)nb, 64 * kFwdWaves, 0, (hipStream_t)stream>>>(
         (const uint16_t*)q_bf16, ldq, (const uint16_t*)k_bf16, ldk, (const uint16_t*)vt_bf16, B * S, (int)S, (int)Hq,
-        (int)(Hq / Hkv), scale_log2e, (uint16_t*)o_bf16, ldo, lse, (int)nqt);
+        (int)(Hq / Hkv), scale_log2e, (uint16_t*)o_bf16, ldo, lse, (int)nqt, reinterpret_cast<uint32_t*>(amax_o));
     return last_launch_status();
 }
 

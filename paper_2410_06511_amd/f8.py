@@ -101,7 +101,7 @@ def lib():
         l.f8_add.argtypes = [_p, _p, _i64, _p, _p]
         l.f8_rmsnorm_bwd.argtypes = [_p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_rmsnorm_bwd_add.argtypes = [_p, _p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
-        l.f8_sdpa_fwd.argtypes = [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _p, _p]
+        l.f8_sdpa_fwd.argtypes = [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _p, _p, _p]
         l.f8_sdpa_bwd.argtypes = [_p, _i64, _p, _p, _i64, _p, _p, _i64, _p, _i64, _p, _i64, _p, _p, _i64, _i64, _i64, _i64,
                                   _i64, _p, _i64, _p, _i64, _p, _i64, _p, _p, C.c_size_t, _p]
         l.f8_sdpa_bwd_workspace_bytes.argtypes = [_i64] * 5
@@ -372,9 +372,9 @@ def rmsnorm_bwd_add(x, g, rstd, dy, add_t, dx, dg, workspace=None, stream=None):
                                     _stream(stream)))
 
 
-def sdpa_fwd(q, k, vt, B, S, Hq, Hkv, hd, o, lse, stream=None):
+def sdpa_fwd(q, k, vt, B, S, Hq, Hkv, hd, o, lse, stream=None, amax_o=None):
     _check(lib().f8_sdpa_fwd(_ptr(q), q.stride(0), _ptr(k), k.stride(0), _ptr(vt), B, S, Hq, Hkv, hd, _ptr(o), o.stride(0),
-                             _ptr(lse), _stream(stream)))
+                             _ptr(lse), _ptr(amax_o), _stream(stream)))
 
 
 def sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd):

@@ -100,7 +100,7 @@ def test_block_entry_points_reject_bad_arguments_before_any_launch():
     assert l.f8_rmsnorm_bwd(FAKE, FAKE, FAKE, FAKE, 16, 16, FAKE, FAKE, None, 0, None) == 5
     assert l.f8_rmsnorm_bwd(FAKE, FAKE, FAKE, FAKE, 16, 24, FAKE, None, None, 0, None) == 2
     # attention: head dimension, sequence length, head grouping, pitches, workspace of the grouped backward
-    fwd = lambda B, S, Hq, Hkv, hd, ldq=4096, ldk=1024, vt=FAKE: l.f8_sdpa_fwd(FAKE, ldq, FAKE, ldk, vt, B, S, Hq, Hkv, hd, FAKE, 4096, FAKE, None)
+    fwd = lambda B, S, Hq, Hkv, hd, ldq=4096, ldk=1024, vt=FAKE: l.f8_sdpa_fwd(FAKE, ldq, FAKE, ldk, vt, B, S, Hq, Hkv, hd, FAKE, 4096, FAKE, None, None)
     assert fwd(1, 64, 32, 8, 64) == 2
     assert fwd(1, 60, 32, 8, 128) == 2
     assert fwd(1, 64, 32, 5, 128) == 2

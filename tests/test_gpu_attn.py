@@ -38,6 +38,7 @@ class Attn:
         self.vt = torch.empty((Hkv * HD, M), **bf)
         self.o = torch.empty((M, Hq * HD), **bf)
         self.lse = torch.empty((Hq, M), device="cuda")
+        self.amax = torch.full((1,), -1.0, device="cuda")
 
     def host_bits(self):
         b = bits(self.qkv)
@@ -46,7 +47,7 @@ class Attn:
 
     def forward(self):
         f8.transpose_bf16(self.v, self.vt)
-        f8.sdpa_fwd(self.q, self.k, self.vt, self.B, self.S, self.Hq, self.Hkv, HD, self.o, self.lse)
+        f8.sdpa_fwd(self.q, self.k, self.vt, self.B, self.S, self.Hq, self.Hkv, HD, self.o, self.lse, amax_o=self.amax)
         torch.cuda.synchronize()
 
 
@@ -62,6 +63,7 @@ def check_forward(a):
     err = np.abs(got - ref)
     assert (err <= 2.0 ** -7 * weight + 1e-30).all(), (err.max(), np.unravel_index(err.argmax(), err.shape))
     assert err.mean() <= 2.0 ** -10 * weight.mean()
+    assert a.amax.item() == o.amax(bits(a.o))[0]          # exactly the maximum magnitude of what was written
     got_lse = a.lse.cpu().numpy().astype(np.float64).reshape(Hq, B, S).transpose(1, 0, 2)
     assert np.abs(got_lse - lse).max() <= 1e-4 * (1.0 + np.abs(lse).max())
 

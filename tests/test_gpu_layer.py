@@ -47,6 +47,7 @@ def oracle_block(x, w, dout, B, S, Hq, Hkv, hd, eps):
     r["qt"], r["kt"], r["vt"] = bo.transpose(r["qr"]), bo.transpose(r["kr"]), bo.transpose(v)
     r["att"], lse = bo.sdpa(r["qr"], r["kr"], v, B, S, Hq, Hkv, hd)
     r["lse"] = np.ascontiguousarray(lse.transpose(1, 0, 2).reshape(Hq, M))
+    r["a_att"] = o.amax(r["att"])
     r["yo"], xq_o, wq_o = o.linear_fwd(r["att"], w["Wo"])
     r["h1"] = bo.add(x, r["yo"])
     r["hn"], r["rstd2"], r["a_hn"] = o.rmsnorm(r["h1"], w["g2"], eps)
@@ -75,7 +76,7 @@ def oracle_block(x, w, dout, B, S, Hq, Hkv, hd, eps):
 # what each stage writes (attribute names of TransformerBlock = keys of the oracle's dictionary)
 WRITES = {
     "rmsnorm 1": ["xn", "rstd1", "a_xn"], "linear wq|wk|wv fwd": ["qkv"], "rope q (+ transposed copy)": ["qr", "qt"],
-    "rope k (+ transposed copy)": ["kr", "kt"], "transpose v": ["vt"], "attention fwd": ["att", "lse"],
+    "rope k (+ transposed copy)": ["kr", "kt"], "transpose v": ["vt"], "attention fwd": ["att", "lse", "a_att"],
     "linear wo fwd": ["yo"], "residual 1": ["h1"], "rmsnorm 2": ["hn", "rstd2", "a_hn"], "linear w1|w3 fwd": ["ab"],
     "silu_mul": ["hh", "a_hh"], "linear w2 fwd": ["y2"], "residual 2": ["out"],
     "linear w2 bwd": ["dhh", "dW2"], "silu_mul bwd": ["dab", "a_dab"], "linear w1|w3 bwd": ["dhn", "dW13"],
