@@ -397,11 +397,18 @@ f8_status f8_linear_bwd_dyq(const f8_linear_desc* d, f8_saved* saved, void* dX, 
  * cosine and the rotation in fp32, one rounding to bf16.  hd a multiple of 8
  * and <= 256, M and the pitches multiples of 8.
  *
+ * amax_inout (nullable, 1 float, also in f8_rmsnorm_bwd_add and f8_sdpa_bwd):
+ * raised to the maximum magnitude of the bf16 values this call writes if that is
+ * larger (the caller sets it to 0 before the first producer of a tensor that
+ * several calls assemble, such as the gradient of a fused q|k|v output); exact
+ * and independent of the order of the updates.
+ *
  * f8_transpose_bf16: out_t [cols, rows] packed = x [rows, cols]^T (pitch ldx).
  * f8_add: out = bf16(a + b) over n elements (the residual), n multiple of 8.
  */
 f8_status f8_rope(const void* x_bf16, int64_t ldx, int64_t M, int64_t S, int64_t n_heads, int64_t hd,
-                  double theta, int inverse, void* out_bf16, int64_t ldo, void* out_t_bf16, void* stream);
+                  double theta, int inverse, void* out_bf16, int64_t ldo, void* out_t_bf16,
+                  float* amax_inout, void* stream);
 f8_status f8_transpose_bf16(const void* x_bf16, int64_t ldx, int64_t rows, int64_t cols, void* out_t_bf16,
                             void* stream);
 f8_status f8_add(const void* a_bf16, const void* b_bf16, int64_t n, void* out_bf16, void* stream);
@@ -442,14 +449,16 @@ f8_status f8_sdpa_fwd(const void* q_bf16, int64_t ldq, const void* k_bf16, int64
  * (f8_sdpa_bwd_workspace_bytes: 2 * B*S * Hq*hd * 4 bytes; 0 and no workspace
  * when Hq == Hkv) and the shares are summed in head order.  No atomics:
  * results are reproducible.  dS and P are rounded to bf16 before they enter a
- * product.
+ * product.  amax_dv_inout (nullable; grouped heads only, else F8_ERR_ENUM): see
+ * f8_rope.
  */
 f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, const void* k_bf16, int64_t ldk,
                       const void* kt_bf16, const void* v_bf16, int64_t ldv, const void* o_bf16,
                       int64_t ldo, const void* do_bf16, int64_t lddo, const void* dot_bf16,
                       const float* lse, int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t hd,
                       void* dq_bf16, int64_t lddq, void* dk_bf16, int64_t lddk, void* dv_bf16,
-                      int64_t lddv, float* delta, void* workspace, size_t workspace_bytes, void* stream);
+                      int64_t lddv, float* delta, float* amax_dv_inout, void* workspace,
+                      size_t workspace_bytes, void* stream);
 size_t f8_sdpa_bwd_workspace_bytes(int64_t B, int64_t S, int64_t Hq, int64_t Hkv, int64_t hd);
 
 /*
@@ -468,7 +477,7 @@ f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rs
  * that f8_rmsnorm_bwd followed by f8_add gives, without writing and re-reading the first. */
 f8_status f8_rmsnorm_bwd_add(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16,
                              const void* add_bf16, int64_t M, int64_t D, void* dx_bf16, float* dg,
-                             void* workspace, size_t workspace_bytes, void* stream);
+                             float* amax_dx_inout, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Forward of the linear whose input is already quantised in saved->x (codes in

@@ -57,6 +57,7 @@ class TransformerBlock:
         self.dqr, self.dkr, self.delta = E(M, Hq * hd), E(M, Hkv * hd), torch.empty((Hq, M), **f32)
         self.att_ws = torch.empty(max(16, f8.sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd)), dtype=torch.uint8, device=device)
         self.dqkv = E(M, self.Nqkv)
+        self.a_bwd = torch.zeros(2, **f32)   # amax of dh1 and of dqkv, raised by the calls that write them
         self.dxn, self.dx = E(M, D), E(M, D)
         self.dg1, self.dg2 = torch.empty(D, **f32), torch.empty(D, **f32)
         self.dWqkv, self.dWo = E(self.Nqkv, D), E(D, D)
@@ -128,6 +129,7 @@ class TransformerBlock:
             ]
             lin_o = lambda: f8.linear_bwd_scaled(s.d_o, s.st_o, s.dh1, s.s_o, s.datt, s.dWo, s.ws, stream)
             lin_qkv = lambda: f8.linear_bwd_scaled(s.d_qkv, s.st_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream)
+            a_dh1 = a_dqkv = None
         else:
             ffn = [
                 ("linear w2 bwd", lambda: f8.linear_bwd(s.d_2, dout, s.s_2, s.dhh, s.dW2, s.ws, stream), 4 * M * H * D, 0),
@@ -135,17 +137,31 @@ class TransformerBlock:
                 ("linear w1|w3 bwd", lambda: f8.linear_bwd_chained(s.d_13, s.dab, s.a_dab, s.s_13, s.dhn, None, s.dW13, s.ws, stream),
                  4 * M * D * 2 * H, 0),
             ]
-            lin_o = lambda: f8.linear_bwd(s.d_o, s.dh1, s.s_o, s.datt, s.dWo, s.ws, stream)
-            lin_qkv = lambda: f8.linear_bwd(s.d_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream)
-        return ffn + [
-            ("rmsnorm 2 bwd + residual", lambda: f8.rmsnorm_bwd_add(s.h1, w["g2"], s.rstd2, s.dhn, dout, s.dh1, s.dg2, s.ws, stream),
+            # the amax of dh1 and of dqkv come from the calls that write them
+            lin_o = lambda: f8.linear_bwd_chained(s.d_o, s.dh1, s.a_bwd[0:1], s.s_o, s.datt, None, s.dWo, s.ws, stream)
+            # (the attention backward reports the amax of dv only where it sums the shares of grouped heads)
+            a_dh1, a_dqkv = s.a_bwd[0:1], (s.a_bwd[1:2] if Hq > Hkv else None)
+            if a_dqkv is not None:
+                lin_qkv = lambda: f8.linear_bwd_chained(s.d_qkv, s.dqkv, a_dqkv, s.s_qkv, s.dxn, None, s.dWqkv, s.ws, stream)
+            else:
+                lin_qkv = lambda: f8.linear_bwd(s.d_qkv, s.dqkv, s.s_qkv, s.dxn, s.dWqkv, s.ws, stream)
+        def zero_amax():
+            if stream is None or stream == torch.cuda.current_stream():
+                s.a_bwd.zero_()
+            else:
+                with torch.cuda.stream(stream):
+                    s.a_bwd.zero_()
+
+        return [("zero the amax cells", zero_amax, 0, 0)] + ffn + [
+            ("rmsnorm 2 bwd + residual", lambda: f8.rmsnorm_bwd_add(s.h1, w["g2"], s.rstd2, s.dhn, dout, s.dh1, s.dg2, s.ws, stream, a_dh1),
              0, 12 * M * D),
             ("linear wo bwd", lin_o, 4 * M * D * D, 0),
             ("transpose dO", lambda: f8.transpose_bf16(s.datt, s.datt_t, stream), 0, 4 * M * D),
             ("attention bwd", lambda: f8.sdpa_bwd(s.qr, s.qt, s.kr, s.kt, v, s.att, s.datt, s.datt_t, s.lse, B, S, Hq, Hkv, hd,
-                                                  s.dqr, s.dkr, dv, s.delta, s.att_ws, stream), 5 * att_flops // 2, 0),
-            ("rope q bwd", lambda: f8.rope(s.dqr, S, Hq, hd, dq, None, s.theta, True, stream), 0, 4 * M * Hq * hd),
-            ("rope k bwd", lambda: f8.rope(s.dkr, S, Hkv, hd, dk, None, s.theta, True, stream), 0, 4 * M * Hkv * hd),
+                                                  s.dqr, s.dkr, dv, s.delta, s.att_ws, stream, a_dqkv),
+             5 * att_flops // 2, 0),
+            ("rope q bwd", lambda: f8.rope(s.dqr, S, Hq, hd, dq, None, s.theta, True, stream, a_dqkv), 0, 4 * M * Hq * hd),
+            ("rope k bwd", lambda: f8.rope(s.dkr, S, Hkv, hd, dk, None, s.theta, True, stream, a_dqkv), 0, 4 * M * Hkv * hd),
             ("linear wq|wk|wv bwd", lin_qkv, 4 * M * D * s.Nqkv, 0),
             ("rmsnorm 1 bwd + residual", lambda: f8.rmsnorm_bwd_add(x, w["g1"], s.rstd1, s.dxn, s.dh1, s.dx, s.dg1, s.ws, stream),
              0, 12 * M * D),

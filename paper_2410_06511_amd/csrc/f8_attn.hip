@@ -559,8 +559,10 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void sdpa_bwd_dkv_kernel(
 __global__ __launch_bounds__(kAttnThreads) void sdpa_group_sum_kernel(const float* __restrict__ part_k, const float* __restrict__ part_v,
                                                                       int64_t M, int64_t w, int group,
                                                                       uint16_t* __restrict__ dK, int64_t lddk,
-                                                                      uint16_t* __restrict__ dV, int64_t lddv)
+                                                                      uint16_t* __restrict__ dV, int64_t lddv,
+                                                                      uint32_t* __restrict__ amax_dv_bits /* nullable: max-updated */)
 {
+    uint32_t mag = 0;
     const int64_t chunks = M * (w / 8);
     for (int64_t c = (int64_t)blockIdx.x * kAttnThreads + threadIdx.x; c < 2 * chunks; c += (int64_t)gridDim.x * kAttnThreads) {
         const bool is_v = c >= chunks;
@@ -574,7 +576,13 @@ __global__ __launch_bounds__(kAttnThreads) void sdpa_group_sum_kernel(const floa
             b2.x += y.x, b2.y += y.y, b2.z += y.z, b2.w += y.w;
         }
         uint16_t* dst = is_v ? dV + tok * lddv + col : dK + tok * lddk + col;
-        *reinterpret_cast<uint4*>(dst) = make_uint4(pack2(a.x, a.y), pack2(a.z, a.w), pack2(b2.x, b2.y), pack2(b2.z, b2.w));
+        const uint4 o = make_uint4(pack2(a.x, a.y), pack2(a.z, a.w), pack2(b2.x, b2.y), pack2(b2.z, b2.w));
+        *reinterpret_cast<uint4*>(dst) = o;
+        if (is_v) mag = absmax_acc(mag, o);
+    }
+    if (amax_dv_bits) {
+        const uint32_t m = wave_max_u32(pk_collapse(mag)) << 16;
+        if ((threadIdx.x & (kWave - 1)) == 0 && m > __atomic_load_n(amax_dv_bits, __ATOMIC_RELAXED)) atomicMax(amax_dv_bits, m);
     }
 }
 
@@ -634,7 +642,8 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
                       const void* kt_bf16, const void* v_bf16, int64_t ldv, const void* o_bf16, int64_t ldo,
                       const void* do_bf16, int64_t lddo, const void* dot_bf16, const float* lse, int64_t B, int64_t S,
                       int64_t Hq, int64_t Hkv, int64_t hd, void* dq_bf16, int64_t lddq, void* dk_bf16, int64_t lddk,
-                      void* dv_bf16, int64_t lddv, float* delta, void* workspace, size_t workspace_bytes_, void* stream)
+                      void* dv_bf16, int64_t lddv, float* delta, float* amax_dv_inout, void* workspace, size_t workspace_bytes_,
+                      void* stream)
 {
     f8_status s = check_attn(q_bf16, ldq, k_bf16, ldk, B, S, Hq, Hkv, hd);
     if (s != F8_OK) return s;
@@ -648,6 +657,7 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
         !aligned16(dot_bf16) || !aligned16(dq_bf16) || !aligned16(dk_bf16) || !aligned16(dv_bf16))
         return F8_ERR_ALIGN;
     const int64_t group = Hq / Hkv;
+    if (amax_dv_inout && group == 1) return F8_ERR_ENUM;  // the amax of dv is taken where the heads' shares are summed
     if (group > 1 && (!workspace || workspace_bytes_ < f8_sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd))) return F8_ERR_WORKSPACE;
     if (group > 1 && !aligned16(workspace)) return F8_ERR_ALIGN;
     if (B == 0 || S == 0) return F8_OK;
@@ -683,7 +693,7 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
         int64_t nb = (2 * M * (wk / 8) + kAttnThreads - 1) / kAttnThreads;
         if (nb > 8192) nb = 8192;
         sdpa_group_sum_kernel<<<(unsigned)nb, kAttnThreads, 0, st>>>(part_k, part_v, M, wk, (int)group, (uint16_t*)dk_bf16, lddk,
-                                                                   (uint16_t*)dv_bf16, lddv);
+                                                                   (uint16_t*)dv_bf16, lddv, reinterpret_cast<uint32_t*>(amax_dv_inout));
     }
     return last_launch_status();
 }

@@ -41,9 +41,11 @@ template <bool ROTATE, bool OUT, bool OUT_T>
 __global__ __launch_bounds__(kBlkThreads) void rope_tile_kernel(const uint16_t* __restrict__ x, int64_t rows, int nh, int hd,
                                                                 int hpb, int64_t ldx, int64_t ldo, int64_t S, float sign, RopeFreq fr,
                                                                 uint16_t* __restrict__ out, uint16_t* __restrict__ out_t,
-                                                                int tiles_c /* per row of tiles: tiles per head x head groups */)
+                                                                int tiles_c /* per row of tiles: tiles per head x head groups */,
+                                                                uint32_t* __restrict__ amax_bits /* nullable: max-updated */)
 {
     __shared__ uint16_t tile[kRt * kRtStride];
+    uint32_t mag = 0;  // packed pair of the largest 15-bit magnitudes written
     const int tph = (hd + kRt - 1) / kRt;  // tiles per head
     const int tc = blockIdx.x % tiles_c;
     const int64_t r0 = (int64_t)(blockIdx.x / tiles_c) * kRt;
@@ -82,6 +84,7 @@ __global__ __launch_bounds__(kBlkThreads) void rope_tile_kernel(const uint16_t* 
                     v = make_uint4(rotate_word(v.x, cs[i][0], sn[i][0]), rotate_word(v.y, cs[i][1], sn[i][1]),
                                    rotate_word(v.z, cs[i][2], sn[i][2]), rotate_word(v.w, cs[i][3], sn[i][3]));
                 if constexpr (OUT) *reinterpret_cast<uint4*>(out + r * ldo + col) = v;
+                mag = absmax_acc(mag, v);
             }
             if constexpr (OUT_T) {
                 uint32_t* t32 = reinterpret_cast<uint32_t*>(tile + rl * kRtStride + cc * 8);  // 4-byte aligned: pitch and cc*8 are even
@@ -104,6 +107,10 @@ __global__ __launch_bounds__(kBlkThreads) void rope_tile_kernel(const uint16_t* 
             }
             __syncthreads();  // the tile is free for the next head
         }
+    }
+    if (amax_bits) {  // a maximum of non-negative floats is a maximum of their bit patterns: order-independent
+        const uint32_t m = wave_max_u32(pk_collapse(mag)) << 16;
+        if ((threadIdx.x & (kWave - 1)) == 0 && m > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, m);
     }
 }
 
@@ -136,9 +143,11 @@ template <int NC>
 __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dx_kernel(const uint4* __restrict__ x, const uint4* __restrict__ g,
                                                                  const float* __restrict__ rstd, const uint4* __restrict__ dy,
                                                                  int64_t M, int64_t dc, float inv_d, uint4* __restrict__ dx,
-                                                                 const uint4* __restrict__ res /* nullable: added to dx */)
+                                                                 const uint4* __restrict__ res /* nullable: added to dx */,
+                                                                 uint32_t* __restrict__ amax_bits /* nullable: max-updated */)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    uint32_t mag = 0;
     for (int64_t m = (int64_t)blockIdx.x * kBlkWaves + wave; m < M; m += (int64_t)gridDim.x * kBlkWaves) {
         const uint4 *xr = x + m * dc, *dr = dy + m * dc;
         float t = 0.0f;
@@ -170,6 +179,7 @@ __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dx_kernel(const uint4* __
                 o = make_uint4(add_word(a.x, o.x), add_word(a.y, o.y), add_word(a.z, o.z), add_word(a.w, o.w));
             }
             dx[m * dc + c] = o;
+            mag = absmax_acc(mag, o);
         };
         if constexpr (NC > 0) {
 #pragma unroll
@@ -180,6 +190,10 @@ __global__ __launch_bounds__(kBlkThreads) void rmsnorm_dx_kernel(const uint4* __
         } else {
             for (int64_t c = lane; c < dc; c += kWave) emit(c, xr[c], dr[c]);
         }
+    }
+    if (amax_bits) {
+        const uint32_t m = wave_max_u32(pk_collapse(mag)) << 16;
+        if (lane == 0 && m > __atomic_load_n(amax_bits, __ATOMIC_RELAXED)) atomicMax(amax_bits, m);
     }
 }
 
@@ -246,7 +260,7 @@ static int elementwise_blocks(int64_t chunks)
 
 template <bool ROTATE>
 static f8_status launch_rope_tiles(const void* x, int64_t rows, int64_t nh, int64_t hd, int64_t ldx, int64_t ldo, int64_t S,
-                                   float sign, const RopeFreq& fr, void* out, void* out_t, hipStream_t st)
+                                   float sign, const RopeFreq& fr, void* out, void* out_t, float* amax, hipStream_t st)
 {
     // heads per block: as many as leave about four blocks per compute unit
     const int64_t tiles_r = (rows + kRt - 1) / kRt, tph = (hd + kRt - 1) / kRt;
@@ -260,7 +274,8 @@ static f8_status launch_rope_tiles(const void* x, int64_t rows, int64_t nh, int6
     if (nb > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;
 #define F8_ROPE_LAUNCH(O, T)                                                                                              \
     rope_tile_kernel<ROTATE, O, T><<<(unsigned)nb, kBlkThreads, 0, st>>>((const uint16_t*)x, rows, (int)nh, (int)hd, (int)hpb, ldx, \
-                                                                         ldo, S, sign, fr, (uint16_t*)out, (uint16_t*)out_t, (int)tiles_c)
+                                                                         ldo, S, sign, fr, (uint16_t*)out, (uint16_t*)out_t, (int)tiles_c, \
+                                                                         reinterpret_cast<uint32_t*>(amax))
     if (out && out_t) F8_ROPE_LAUNCH(true, true);
     else if (out) F8_ROPE_LAUNCH(true, false);
     else F8_ROPE_LAUNCH(false, true);
@@ -275,7 +290,7 @@ using namespace f8;
 extern "C" {
 
 f8_status f8_rope(const void* x_bf16, int64_t ldx, int64_t M, int64_t S, int64_t n_heads, int64_t hd, double theta,
-                  int inverse, void* out_bf16, int64_t ldo, void* out_t_bf16, void* stream)
+                  int inverse, void* out_bf16, int64_t ldo, void* out_t_bf16, float* amax_inout, void* stream)
 {
     if (!x_bf16 || (!out_bf16 && !out_t_bf16)) return F8_ERR_NULL;
     if (M < 0 || S < 1 || n_heads < 1 || hd < 2 || hd > 256 || (hd % 8) || (M % 8) || !(theta > 0.0)) return F8_ERR_SHAPE;
@@ -285,7 +300,7 @@ f8_status f8_rope(const void* x_bf16, int64_t ldx, int64_t M, int64_t S, int64_t
     RopeFreq fr;
     for (int i = 0; i < 128; ++i) fr.f[i] = i < hd / 2 ? pow(theta, -2.0 * (double)i / (double)hd) : 0.0;
     return launch_rope_tiles<true>(x_bf16, M, n_heads, hd, ldx, ldo, S, inverse ? -1.0f : 1.0f, fr, out_bf16, out_t_bf16,
-                                   (hipStream_t)stream);
+                                   amax_inout, (hipStream_t)stream);
 }
 
 f8_status f8_transpose_bf16(const void* x_bf16, int64_t ldx, int64_t rows, int64_t cols, void* out_t_bf16, void* stream)
@@ -295,7 +310,7 @@ f8_status f8_transpose_bf16(const void* x_bf16, int64_t ldx, int64_t rows, int64
     if (!aligned16(x_bf16) || !aligned16(out_t_bf16)) return F8_ERR_ALIGN;
     RopeFreq fr = {};
     if (cols >= ((int64_t)1 << 31)) return F8_ERR_SHAPE;
-    return launch_rope_tiles<false>(x_bf16, rows, 1, cols, ldx, cols, 1, 1.0f, fr, nullptr, out_t_bf16, (hipStream_t)stream);
+    return launch_rope_tiles<false>(x_bf16, rows, 1, cols, ldx, cols, 1, 1.0f, fr, nullptr, out_t_bf16, nullptr, (hipStream_t)stream);
 }
 
 f8_status f8_add(const void* a_bf16, const void* b_bf16, int64_t n, void* out_bf16, void* stream)
@@ -310,7 +325,8 @@ f8_status f8_add(const void* a_bf16, const void* b_bf16, int64_t n, void* out_bf
 }
 
 static f8_status rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16, const void* add_bf16,
-                             int64_t M, int64_t D, void* dx_bf16, float* dg, void* workspace, size_t workspace_bytes_, void* stream)
+                             int64_t M, int64_t D, void* dx_bf16, float* dg, float* amax_dx, void* workspace,
+                             size_t workspace_bytes_, void* stream)
 {
     if (!x_bf16 || !g_bf16 || !rstd || !dy_bf16 || (!dx_bf16 && !dg)) return F8_ERR_NULL;
     if (M < 0 || D < 0 || (M % 16) || (D % 16)) return F8_ERR_SHAPE;
@@ -328,7 +344,7 @@ static f8_status rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float
 #define F8_DX_LAUNCH(NC)                                                                                      \
     rmsnorm_dx_kernel<NC><<<(unsigned)nb, kBlkThreads, 0, st>>>((const uint4*)x_bf16, (const uint4*)g_bf16, rstd, \
                                                                 (const uint4*)dy_bf16, M, D / 8, 1.0f / (float)D, (uint4*)dx_bf16, \
-                                                                (const uint4*)add_bf16)
+                                                                (const uint4*)add_bf16, reinterpret_cast<uint32_t*>(amax_dx))
         if (D <= 8 * kWave * 8) F8_DX_LAUNCH(8);  // rows up to 4096 elements stay in registers
         else F8_DX_LAUNCH(0);
 #undef F8_DX_LAUNCH
@@ -348,16 +364,17 @@ static f8_status rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float
 f8_status f8_rmsnorm_bwd(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16, int64_t M,
                          int64_t D, void* dx_bf16, float* dg, void* workspace, size_t workspace_bytes_, void* stream)
 {
-    return rmsnorm_bwd(x_bf16, g_bf16, rstd, dy_bf16, nullptr, M, D, dx_bf16, dg, workspace, workspace_bytes_, stream);
+    return rmsnorm_bwd(x_bf16, g_bf16, rstd, dy_bf16, nullptr, M, D, dx_bf16, dg, nullptr, workspace, workspace_bytes_, stream);
 }
 
 f8_status f8_rmsnorm_bwd_add(const void* x_bf16, const void* g_bf16, const float* rstd, const void* dy_bf16,
-                             const void* add_bf16, int64_t M, int64_t D, void* dx_bf16, float* dg, void* workspace,
-                             size_t workspace_bytes_, void* stream)
+                             const void* add_bf16, int64_t M, int64_t D, void* dx_bf16, float* dg, float* amax_dx_inout,
+                             void* workspace, size_t workspace_bytes_, void* stream)
 {
     if (!add_bf16 || !dx_bf16) return F8_ERR_NULL;
     if (!aligned16(add_bf16)) return F8_ERR_ALIGN;
-    return rmsnorm_bwd(x_bf16, g_bf16, rstd, dy_bf16, add_bf16, M, D, dx_bf16, dg, workspace, workspace_bytes_, stream);
+    return rmsnorm_bwd(x_bf16, g_bf16, rstd, dy_bf16, add_bf16, M, D, dx_bf16, dg, amax_dx_inout, workspace, workspace_bytes_,
+                       stream);
 }
 
 }  // extern "C"

@@ -96,14 +96,14 @@ def lib():
         l.f8_silu_mul_bwd_quantise_delayed.argtypes = [_p, _p, _i64, _i64, _int, _p, _i64, _p, C.POINTER(QTensorStruct),
                                                        _p, C.c_size_t, _p]
         l.f8_linear_bwd_dyq.argtypes = [C.POINTER(LinearDesc), C.POINTER(SavedStruct), _p, _p, _p]
-        l.f8_rope.argtypes = [_p, _i64, _i64, _i64, _i64, _i64, C.c_double, _int, _p, _i64, _p, _p]
+        l.f8_rope.argtypes = [_p, _i64, _i64, _i64, _i64, _i64, C.c_double, _int, _p, _i64, _p, _p, _p]
         l.f8_transpose_bf16.argtypes = [_p, _i64, _i64, _i64, _p, _p]
         l.f8_add.argtypes = [_p, _p, _i64, _p, _p]
         l.f8_rmsnorm_bwd.argtypes = [_p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
-        l.f8_rmsnorm_bwd_add.argtypes = [_p, _p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
+        l.f8_rmsnorm_bwd_add.argtypes = [_p, _p, _p, _p, _p, _i64, _i64, _p, _p, _p, _p, C.c_size_t, _p]
         l.f8_sdpa_fwd.argtypes = [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _p, _p, _p]
         l.f8_sdpa_bwd.argtypes = [_p, _i64, _p, _p, _i64, _p, _p, _i64, _p, _i64, _p, _i64, _p, _p, _i64, _i64, _i64, _i64,
-                                  _i64, _p, _i64, _p, _i64, _p, _i64, _p, _p, C.c_size_t, _p]
+                                  _i64, _p, _i64, _p, _i64, _p, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_sdpa_bwd_workspace_bytes.argtypes = [_i64] * 5
         for name in EXPORTS[2:]:
             getattr(l, name).restype = _int
@@ -344,11 +344,11 @@ def linear_bwd_dyq(desc, saved, dX, dW, stream=None):
 
 # ---- the bf16 operations between the Float8 linears of a transformer block -----------
 
-def rope(x, S, n_heads, hd, out=None, out_t=None, theta=500000.0, inverse=False, stream=None):
+def rope(x, S, n_heads, hd, out=None, out_t=None, theta=500000.0, inverse=False, stream=None, amax_inout=None):
     """x, out: 2-D (possibly column slices of wider tensors: the row pitch is taken from stride(0))."""
     M = x.shape[0]
     _check(lib().f8_rope(_ptr(x), x.stride(0), M, S, n_heads, hd, float(theta), int(bool(inverse)), _ptr(out),
-                         out.stride(0) if out is not None else 0, _ptr(out_t), _stream(stream)))
+                         out.stride(0) if out is not None else 0, _ptr(out_t), _ptr(amax_inout), _stream(stream)))
 
 
 def transpose_bf16(x, out_t, stream=None):
@@ -365,11 +365,11 @@ def rmsnorm_bwd(x, g, rstd, dy, dx, dg, workspace=None, stream=None):
     _check(lib().f8_rmsnorm_bwd(_ptr(x), _ptr(g), _ptr(rstd), _ptr(dy), M, D, _ptr(dx), _ptr(dg), wp, wb, _stream(stream)))
 
 
-def rmsnorm_bwd_add(x, g, rstd, dy, add_t, dx, dg, workspace=None, stream=None):
+def rmsnorm_bwd_add(x, g, rstd, dy, add_t, dx, dg, workspace=None, stream=None, amax_dx_inout=None):
     M, D = x.shape
     wp, wb = _ws(workspace)
-    _check(lib().f8_rmsnorm_bwd_add(_ptr(x), _ptr(g), _ptr(rstd), _ptr(dy), _ptr(add_t), M, D, _ptr(dx), _ptr(dg), wp, wb,
-                                    _stream(stream)))
+    _check(lib().f8_rmsnorm_bwd_add(_ptr(x), _ptr(g), _ptr(rstd), _ptr(dy), _ptr(add_t), M, D, _ptr(dx), _ptr(dg),
+                                    _ptr(amax_dx_inout), wp, wb, _stream(stream)))
 
 
 def sdpa_fwd(q, k, vt, B, S, Hq, Hkv, hd, o, lse, stream=None, amax_o=None):
@@ -381,9 +381,10 @@ def sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd):
     return int(lib().f8_sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd))
 
 
-def sdpa_bwd(q, qt, k, kt, v, o, do, dot, lse, B, S, Hq, Hkv, hd, dq, dk, dv, delta, workspace=None, stream=None):
+def sdpa_bwd(q, qt, k, kt, v, o, do, dot, lse, B, S, Hq, Hkv, hd, dq, dk, dv, delta, workspace=None, stream=None,
+             amax_dv_inout=None):
     wp, wb = _ws(workspace)
     _check(lib().f8_sdpa_bwd(_ptr(q), q.stride(0), _ptr(qt), _ptr(k), k.stride(0), _ptr(kt), _ptr(v), v.stride(0),
                              _ptr(o), o.stride(0), _ptr(do), do.stride(0), _ptr(dot), _ptr(lse), B, S, Hq, Hkv, hd,
                              _ptr(dq), dq.stride(0), _ptr(dk), dk.stride(0), _ptr(dv), dv.stride(0), _ptr(delta),
-                             wp, wb, _stream(stream)))
+                             _ptr(amax_dv_inout), wp, wb, _stream(stream)))

@@ -84,12 +84,12 @@ def test_argument_errors_are_reported_before_any_launch():
 def test_block_entry_points_reject_bad_arguments_before_any_launch():
     l = f8.lib()
     # rope: no output; head dimension not a multiple of 8 / too large; pitch smaller than the row; sequence length 0
-    assert l.f8_rope(FAKE, 128, 16, 16, 1, 128, 500000.0, 0, None, 0, None, None) == 1
-    assert l.f8_rope(FAKE, 128, 16, 16, 1, 12, 500000.0, 0, FAKE, 128, None, None) == 2
-    assert l.f8_rope(FAKE, 512, 16, 16, 1, 512, 500000.0, 0, FAKE, 512, None, None) == 2
-    assert l.f8_rope(FAKE, 64, 16, 16, 1, 128, 500000.0, 0, FAKE, 128, None, None) == 2
-    assert l.f8_rope(FAKE, 128, 16, 0, 1, 128, 500000.0, 0, FAKE, 128, None, None) == 2
-    assert l.f8_rope(FAKE + 2, 128, 16, 16, 1, 128, 500000.0, 0, FAKE, 128, None, None) == 3
+    assert l.f8_rope(FAKE, 128, 16, 16, 1, 128, 500000.0, 0, None, 0, None, None, None) == 1
+    assert l.f8_rope(FAKE, 128, 16, 16, 1, 12, 500000.0, 0, FAKE, 128, None, None, None) == 2
+    assert l.f8_rope(FAKE, 512, 16, 16, 1, 512, 500000.0, 0, FAKE, 512, None, None, None) == 2
+    assert l.f8_rope(FAKE, 64, 16, 16, 1, 128, 500000.0, 0, FAKE, 128, None, None, None) == 2
+    assert l.f8_rope(FAKE, 128, 16, 0, 1, 128, 500000.0, 0, FAKE, 128, None, None, None) == 2
+    assert l.f8_rope(FAKE + 2, 128, 16, 16, 1, 128, 500000.0, 0, FAKE, 128, None, None, None) == 3
     # transpose, add
     assert l.f8_transpose_bf16(FAKE, 16, 16, 20, FAKE, None) == 2
     assert l.f8_transpose_bf16(FAKE, 32, 16, 32, None, None) == 1
@@ -109,7 +109,7 @@ def test_block_entry_points_reject_bad_arguments_before_any_launch():
     assert f8.sdpa_bwd_workspace_bytes(1, 8192, 32, 8, 128) == 2 * 8192 * 4096 * 4
     assert f8.sdpa_bwd_workspace_bytes(1, 8192, 8, 8, 128) == 0
     bwd = lambda ws, nbytes: l.f8_sdpa_bwd(FAKE, 4096, FAKE, FAKE, 1024, FAKE, FAKE, 1024, FAKE, 4096, FAKE, 4096, FAKE, FAKE,
-                                           1, 64, 32, 8, 128, FAKE, 4096, FAKE, 1024, FAKE, 1024, FAKE, ws, nbytes, None)
+                                           1, 64, 32, 8, 128, FAKE, 4096, FAKE, 1024, FAKE, 1024, FAKE, None, ws, nbytes, None)
     assert bwd(None, 0) == 5
     assert bwd(FAKE, 1024) == 5
 

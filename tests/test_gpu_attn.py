@@ -104,8 +104,11 @@ def run_backward(a, do_t):
     delta = torch.empty((Hq, M), device="cuda")
     ws = torch.empty(max(16, f8.sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, HD)), dtype=torch.uint8, device="cuda")
     assert (ws.numel() > 16) == (Hq != Hkv)
-    f8.sdpa_bwd(a.q, qt, a.k, kt, a.v, a.o, do, dot, a.lse, B, S, Hq, Hkv, HD, dq, dk, dv, delta, ws)
+    cell = torch.zeros(1, device="cuda") if Hq != Hkv else None
+    f8.sdpa_bwd(a.q, qt, a.k, kt, a.v, a.o, do, dot, a.lse, B, S, Hq, Hkv, HD, dq, dk, dv, delta, ws, amax_dv_inout=cell)
     torch.cuda.synchronize()
+    if cell is not None:   # exactly the maximum magnitude of the dv written
+        assert cell.item() == o.amax(np.ascontiguousarray(bits(dqkv)[:, (Hq + Hkv) * HD:]))[0]
     return dqkv, delta
 
 

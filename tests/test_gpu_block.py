@@ -52,6 +52,15 @@ def test_rope_and_its_transposed_copy(M, S, nh, hd):
     torch.cuda.synchronize()
     assert_rope_close(bits(back), bo.rope(bits(x), S, hd, inverse=True), bits(x), "rope inverse")
     assert np.array_equal(bits(only_t), bits(back).T)
+    # amax cell: raised by each producer to the maximum of what it wrote
+    cell = torch.zeros(1, device="cuda")
+    f8.rope(x.cuda(), S, nh, hd, out, None, amax_inout=cell)
+    torch.cuda.synchronize()
+    first = cell.item()
+    assert first == o.amax(bits(out))[0]
+    f8.rope((x * 3).bfloat16().cuda(), S, nh, hd, back, None, amax_inout=cell)
+    torch.cuda.synchronize()
+    assert cell.item() == max(first, o.amax(bits(back))[0])
 
 
 def test_rope_long_sequence_positions_and_column_slices():
@@ -126,6 +135,15 @@ def test_rmsnorm_backward(M, D):
     f8.rmsnorm_bwd_add(x.cuda(), g.cuda(), rstd, dy.cuda(), res, fused, dg3, ws)
     torch.cuda.synchronize()
     assert torch.equal(ref_sum.view(torch.int16), fused.view(torch.int16)) and torch.equal(dg, dg3)
+    # the amax cell is raised to the maximum magnitude written, and never lowered
+    cell = torch.zeros(1, device="cuda")
+    f8.rmsnorm_bwd_add(x.cuda(), g.cuda(), rstd, dy.cuda(), res, fused, dg3, ws, amax_dx_inout=cell)
+    torch.cuda.synchronize()
+    assert cell.item() == o.amax(bits(fused))[0]
+    cell.fill_(1e9)
+    f8.rmsnorm_bwd_add(x.cuda(), g.cuda(), rstd, dy.cuda(), res, fused, dg3, ws, amax_dx_inout=cell)
+    torch.cuda.synchronize()
+    assert cell.item() == 1e9
 
 
 def test_block_glue_argument_errors():

@@ -75,6 +75,7 @@ def oracle_block(x, w, dout, B, S, Hq, Hkv, hd, eps):
 
 # what each stage writes (attribute names of TransformerBlock = keys of the oracle's dictionary)
 WRITES = {
+    "zero the amax cells": [],
     "rmsnorm 1": ["xn", "rstd1", "a_xn"], "linear wq|wk|wv fwd": ["qkv"], "rope q (+ transposed copy)": ["qr", "qt"],
     "rope k (+ transposed copy)": ["kr", "kt"], "transpose v": ["vt"], "attention fwd": ["att", "lse", "a_att"],
     "linear wo fwd": ["yo"], "residual 1": ["h1"], "rmsnorm 2": ["hn", "rstd2", "a_hn"], "linear w1|w3 fwd": ["ab"],
@@ -124,6 +125,10 @@ def test_transformer_block_stage_by_stage():
     for name, call, _, _ in blk.forward_stages(xd, wd) + blk.backward_stages(xd, wd, dd):
         call()
         torch.cuda.synchronize()
+        if name == "rmsnorm 2 bwd + residual":
+            # the amax handed to the output projection's backward is exactly that of the values written
+            assert blk.a_bwd[0].item() == o.amax(bits(blk.dh1))[0]
+            blk.a_bwd[0:1].copy_(torch.from_numpy(o.amax(ref["dh1"])))
         compare_then_replace(blk, ref, WRITES[name], name)
         if name in SAVED:
             # the fp8 state kept for the backward is the oracle's, bit for bit
@@ -137,7 +142,10 @@ def test_transformer_block_stage_by_stage():
             close(bits(blk.dqkv)[:, nq + nk:], ref["dqkv"][:, nq + nk:], "attention bwd: dv")
         if name == "rope k bwd":
             close(bits(blk.dqkv), ref["dqkv"], "dqkv assembled")
+            # all three producers (inverse rope of dq and dk, the summed dv) have raised the amax cell
+            assert blk.a_bwd[1].item() == o.amax(bits(blk.dqkv))[0]
             blk.dqkv.copy_(to_dev(ref["dqkv"]))
+            blk.a_bwd[1:2].copy_(torch.from_numpy(o.amax(ref["dqkv"])))
 
 
 def test_transformer_block_end_to_end_and_recompute():
