@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--recompute", nargs="?", const="full", default=None, choices=["full", "selective"],
                     help="llama8b_layer: activation checkpointing: run the forward again inside the backward (full), "
                          "or only its cheap bf16 operations, keeping the outputs of the products and of the attention (selective)")
+    ap.add_argument("--keep-weights", action="store_true",
+                    help="dynamic scaling: quantise the weights once before the timed steps and keep their codes "
+                         "(micro-batches of one optimizer step); the default recasts them on every forward")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16-context", action="store_true",
                     help="skip timing torch.matmul in bf16 on the same shapes (context only)")
@@ -152,6 +155,17 @@ def main():
                     f8.linear_bwd_chained(s.desc, states[prod[i]].dX, amax_dx[prod[i]], s.saved, s.dX, None, s.dW, ws)
                 else:
                     f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws)
+    elif args.scaling == "dynamic" and args.keep_weights:
+        # gradient accumulation: the weights' fp8 codes are taken once (outside the timed steps)
+        # and kept for the micro-batches that follow; NOT the headline accounting
+        for s in states:
+            f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws)
+
+        def step():
+            for s in states:
+                f8.linear_fwd_wq(s.desc, s.X, s.Y, s.saved, ws)
+            for s in reversed(states):
+                f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws)
     elif args.scaling == "dynamic":
         def step():
             for s in states:                       # forward in model order
@@ -311,6 +325,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.key}: " + ", ".join(f"{l.name}[M={l.M},K={l.K},N={l.N}]" for l in w.linears),
                    "scaling_granularity": gran, "scaling_strategy": args.scaling, "grad_format": gfmt, "chained": bool(args.chain), "hip_graph": bool(args.graph),
+                   "weights_recast_every_step": not args.keep_weights,
                    "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
         "roofline": roofline,

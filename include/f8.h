@@ -238,6 +238,16 @@ f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, v
                         f8_saved* saved, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * f8_linear_fwd with the weight already quantised: saved->w holds W's codes in
+ * both orientations and its scales from an earlier f8_linear_fwd (or
+ * f8_quantise) — weights change once per optimizer step, not per
+ * micro-batch (Section 2.2.4 recasts them on every forward; this is the
+ * caller's choice to keep them).  Quantises X, computes Y = X8 W8^T.
+ */
+f8_status f8_linear_fwd_wq(const f8_linear_desc* d, const void* X, void* Y, f8_saved* saved, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/*
  * Backward: quantise dY [M,N] into saved->dy, then
  *   dX [M,K] = dY8 W8      (rowwise: dY per row m, W per column k)
  *   dW [N,K] = dY8^T X8    (rowwise: dY per column n, X per column k)

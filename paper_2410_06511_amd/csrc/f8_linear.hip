@@ -192,6 +192,18 @@ f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, v
     return gemm_fwd(d, saved, Y, nullptr, st);
 }
 
+f8_status f8_linear_fwd_wq(const f8_linear_desc* d, const void* X, void* Y, f8_saved* saved, void* workspace,
+                           size_t workspace_bytes_, void* stream)
+{
+    // the weight's codes and scales in saved->w are the caller's (kept from an earlier call): X is a
+    // stand-in for W in the shared checks, which only test it for NULL and alignment
+    f8_status s = check_fwd(d, false, X, X, Y, saved, workspace, workspace_bytes_);
+    if (s != F8_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    if ((s = quantise_both(X, d->M, d->K, d->granularity == F8_ROWWISE, F8_E4M3, &saved->x, workspace, st)) != F8_OK) return s;
+    return gemm_fwd(d, saved, Y, nullptr, st);
+}
+
 f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved, void* dX, void* dW,
                         void* workspace, size_t workspace_bytes_, void* stream)
 {

@@ -150,3 +150,27 @@ def test_full_size_linear(key, li, rowwise, grad_fmt):
         assert np.array_equal(u8(saved.dy.q_t), qdyc.T)
         sampled_check("dX", bits(dX), o.NN, qdy, grad_fmt, qwc, o.E4M3, isdy, iswc, g, rng)
         sampled_check("dW", bits(dW), o.TN, qdyc, grad_fmt, qxc, o.E4M3, isdyc, isxc, g, rng)
+
+
+@pytest.mark.parametrize("rowwise", [False, True])
+def test_forward_with_kept_weight_codes(rowwise):
+    """A second micro-batch against the weight codes kept from the first: the same bits as a full
+    f8_linear_fwd on that micro-batch, and the weight's saved state is left untouched."""
+    M, K, N = 272, 336, 208
+    g = torch.Generator("cpu")
+    g.manual_seed(77)
+    X1, X2 = wl.randn_bf16((M, K), 1.0, 0, generator=g).cuda(), wl.randn_bf16((M, K), 2.0, 0, generator=g).cuda()
+    W = wl.randn_bf16((N, K), 0.02, 0, generator=g).cuda()
+    desc = f8.linear_desc(M, K, N, rowwise)
+    ws = f8.new_workspace(max(M, K, N), max(M, K, N))
+    kept, full = f8.Saved(M, K, N, rowwise), f8.Saved(M, K, N, rowwise)
+    Y1, Y2, Yref = (torch.empty((M, N), dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    f8.linear_fwd(desc, X1, W, Y1, kept, ws)
+    torch.cuda.synchronize()
+    w_before = kept.w.q.clone()
+    f8.linear_fwd_wq(desc, X2, Y2, kept, ws)
+    f8.linear_fwd(desc, X2, W, Yref, full, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y2.view(torch.int16), Yref.view(torch.int16))
+    assert torch.equal(kept.x.q, full.x.q) and torch.equal(kept.w.q, w_before)
+
