@@ -112,7 +112,7 @@ def run_backward(a, do_t):
     return dqkv, delta
 
 
-def check_backward(a, do_t, dqkv, delta):
+def check_backward(a, do_t, dqkv, delta, mean_factor=3 * 2.0 ** -9):
     qb, kb, vb = a.host_bits()
     B, S, Hq, Hkv = a.B, a.S, a.Hq, a.Hkv
     q, k, v, do = f64(qb), f64(kb), f64(vb), f64(bits(do_t))
@@ -131,7 +131,7 @@ def check_backward(a, do_t, dqkv, delta):
         err = np.abs(g_ - r_)
         assert err.max() <= 1e-2 * np.abs(r_).max(), (name, err.max(), np.abs(r_).max())
         # on average: three bf16 roundings on the way (the P or dS operand, O inside delta, the output), 2^-9 each
-        assert err.mean() <= 3 * 2.0 ** -9 * np.abs(r_).mean(), (name, err.mean(), np.abs(r_).mean())
+        assert err.mean() <= mean_factor * np.abs(r_).mean(), (name, err.mean(), np.abs(r_).mean())
 
 
 @pytest.mark.parametrize("B,S,Hq,Hkv", [(1, 8, 1, 1), (1, 128, 2, 1), (2, 200, 4, 2), (1, 520, 8, 2), (3, 64, 2, 2)])
@@ -144,6 +144,19 @@ def test_sdpa_backward(B, S, Hq, Hkv):
     # reproducible: no atomics anywhere
     dqkv2, _ = run_backward(a, do_t)
     assert torch.equal(dqkv.view(torch.int16), dqkv2.view(torch.int16))
+
+
+def test_sdpa_backward_peaked_scores():
+    """Scores of order ten (a softmax close to one-hot, where P (dP - delta) cancels strongly)."""
+    B, S, Hq, Hkv = 2, 264, 4, 2
+    a = Attn(B, S, Hq, Hkv, seed=5, std=3.0)
+    a.forward()
+    do_t = gen((B * S, Hq * HD), 6, 1e-2)
+    dqkv, delta = run_backward(a, do_t)
+    # dS = P (dP - delta) cancels where P is close to one-hot (dP of the dominating key is nearly
+    # delta itself): the bf16 rounding of O inside delta, 2^-9 of |delta|, is then a larger share of
+    # the small difference.  The bound on the largest error stays; the mean may reach 2^-6.
+    check_backward(a, do_t, dqkv, delta, mean_factor=2.0 ** -6)
 
 
 def test_sdpa_full_size_sampled_against_oracle():
