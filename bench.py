@@ -45,6 +45,9 @@ def parse():
     ap.add_argument("--keep-weights", action="store_true",
                     help="dynamic scaling: quantise the weights once before the timed steps and keep their codes "
                          "(micro-batches of one optimizer step); the default recasts them on every forward")
+    ap.add_argument("--transposed-copies", action="store_true",
+                    help="tensorwise: also write every code tensor transposed (+1 B/elem) and run the backward as F8_NT "
+                         "products on the copies, instead of reading the codes in place (F8_NN / F8_TN)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-bf16-context", action="store_true",
                     help="skip timing torch.matmul in bf16 on the same shapes (context only)")
@@ -57,7 +60,7 @@ def parse():
 class LinearState:
     """Device tensors of one linear of the workload."""
 
-    def __init__(self, f8, wl, w, li, rowwise, grad_fmt, scaling="dynamic", ws=None):
+    def __init__(self, f8, wl, w, li, rowwise, grad_fmt, scaling="dynamic", ws=None, transposed=False):
         import torch
         lin = w.linears[li]
         X, W, dY = wl.make_linear_inputs(w, li)
@@ -68,7 +71,7 @@ class LinearState:
         self.Y = torch.empty((M, N), **bf)
         self.dX = torch.empty((M, K), **bf)
         self.dW = torch.empty((N, K), **bf)
-        self.saved = f8.Saved(M, K, N, rowwise)
+        self.saved = f8.Saved(M, K, N, rowwise, transposed=transposed)
         self.desc = f8.linear_desc(M, K, N, rowwise, grad_fmt)
         self.state = None
         if scaling != "dynamic":
@@ -124,7 +127,8 @@ def main():
         sys.exit(2)
     dmax = max(max(l.M, l.K, l.N) for l in w.linears)
     ws = f8.new_workspace(dmax, dmax)
-    states = [LinearState(f8, wl, w, li, rowwise, grad_fmt, args.scaling, ws) for li in range(len(w.linears))]
+    states = [LinearState(f8, wl, w, li, rowwise, grad_fmt, args.scaling, ws, args.transposed_copies)
+              for li in range(len(w.linears))]
     stream = torch.cuda.current_stream()   # the per-kernel legs below; the step uses the current stream
 
     chain_pairs = []
@@ -241,12 +245,20 @@ def main():
         dy_is_t = sv.dy.inv_scale_t if rowwise else sv.dy.inv_scale
         x_is_t = sv.x.inv_scale_t if rowwise else sv.x.inv_scale
         ops.append(("cast", li, cast_op(s.dY, sv.dy, grad_fmt), s.dY.numel(), "dY"))
-        ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, w_is_t=w_is_t: f8.gemm(
-            f8.NT, M, K, N, sv.dy.q, grad_fmt, sv.w.q_t, f8.E4M3, sv.dy.inv_scale, w_is_t, g, s.dX, stream)),
-            2 * M * K * N, "dX = dY W"))
-        ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, dy_is_t=dy_is_t, x_is_t=x_is_t: f8.gemm(
-            f8.NT, N, K, M, sv.dy.q_t, grad_fmt, sv.x.q_t, f8.E4M3, dy_is_t, x_is_t, g, s.dW, stream)),
-            2 * M * K * N, "dW = dY^T X"))
+        if sv.w.q_t is not None:   # rowwise, or --transposed-copies: F8_NT products on the transposed codes
+            ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, w_is_t=w_is_t: f8.gemm(
+                f8.NT, M, K, N, sv.dy.q, grad_fmt, sv.w.q_t, f8.E4M3, sv.dy.inv_scale, w_is_t, g, s.dX, stream)),
+                2 * M * K * N, "dX = dY W"))
+            ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, dy_is_t=dy_is_t, x_is_t=x_is_t: f8.gemm(
+                f8.NT, N, K, M, sv.dy.q_t, grad_fmt, sv.x.q_t, f8.E4M3, dy_is_t, x_is_t, g, s.dW, stream)),
+                2 * M * K * N, "dW = dY^T X"))
+        else:                      # the codes read in place: W and both of dY, X are k-major operands
+            ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N: f8.gemm(
+                f8.NN, M, K, N, sv.dy.q, grad_fmt, sv.w.q, f8.E4M3, sv.dy.inv_scale, sv.w.inv_scale, g, s.dX, stream)),
+                2 * M * K * N, "dX = dY W"))
+            ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N: f8.gemm(
+                f8.TN, N, K, M, sv.dy.q, grad_fmt, sv.x.q, f8.E4M3, sv.dy.inv_scale, sv.x.inv_scale, g, s.dW, stream)),
+                2 * M * K * N, "dW = dY^T X"))
 
     evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]
            for _ in range(reps)]
@@ -298,8 +310,8 @@ def main():
     }
     cast = None
     if cast_ms > 0:
-        # dynamic tensorwise amax+cast: 2 B amax read + 2 B cast re-read + 1 B write per element;
-        # the transposed fp8 copy (+1 B/elem) is a design cost and not counted.
+        # dynamic tensorwise amax+cast: 2 B amax read + 2 B cast re-read + 1 B write per element
+        # (with --transposed-copies a second code tensor is written: +1 B/elem moved, not counted).
         # delayed / static scaling: the scale is known beforehand, one pass: 2 B read + 1 B write.
         # rowwise: one amax pass yields the per-row and the per-column maxima (2 B), one cast pass
         # re-reads x (2 B) and writes the two differently scaled code sets (1 + 1 B): 6 B/elem.
@@ -307,7 +319,7 @@ def main():
         gbs = bpe * cast_elems / (cast_ms * 1e-3) / 1e9
         cast = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_elem": bpe,
-                "moved_gbs_incl_transposed_copy": round((bpe + (0 if rowwise else 1)) * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
+                "moved_gbs": round((bpe + (1 if (args.transposed_copies and not rowwise) else 0)) * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
                 "ms_per_step": round(cast_ms, 4)}
 
     out = {
@@ -325,7 +337,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.key}: " + ", ".join(f"{l.name}[M={l.M},K={l.K},N={l.N}]" for l in w.linears),
                    "scaling_granularity": gran, "scaling_strategy": args.scaling, "grad_format": gfmt, "chained": bool(args.chain), "hip_graph": bool(args.graph),
-                   "weights_recast_every_step": not args.keep_weights,
+                   "weights_recast_every_step": not args.keep_weights, "transposed_code_copies": bool(args.transposed_copies or rowwise),
                    "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
         "roofline": roofline,

@@ -65,7 +65,10 @@ typedef enum { F8_TENSORWISE = 0, F8_ROWWISE = 1, F8_COLWISE = 2 } f8_granularit
 /* Operand layouts of f8_gemm; D is always [M, N].
  *   F8_NT: A[M,K], B[N,K]   (both contraction-contiguous)
  *   F8_NN: A[M,K], B[K,N]
- *   F8_TN: A[K,M], B[K,N] */
+ *   F8_TN: A[K,M], B[K,N]
+ * All three run on the same tiled kernel when K is a multiple of 256 (operands
+ * whose contraction index is the slow one are turned inside the kernel);
+ * otherwise a slower generic kernel takes over. */
 typedef enum { F8_NT = 0, F8_NN = 1, F8_TN = 2 } f8_layout;
 
 /* Bytes of device workspace that is enough for any call of this library on
@@ -184,9 +187,13 @@ f8_status f8_gemm(f8_layout layout, int64_t M, int64_t N, int64_t K, const uint8
 /*
  * One quantised tensor T[rows, cols] as the linear layer keeps it between
  * forward and backward.  All members are caller-allocated device memory.
- *   Tensorwise: q [rows, cols] and q_t [cols, rows] hold the same codes;
- *     amax / scale / inv_scale have 1 entry; the *_t scale members are unused
- *     (may be NULL).
+ *   Tensorwise: q [rows, cols] holds the codes; amax / scale / inv_scale have 1
+ *     entry; the *_t scale members are unused (may be NULL).  q_t may be NULL
+ *     (the normal case): the backward products then read q in place, turning
+ *     the operand inside the GEMM kernel.  If q_t [cols, rows] is given it
+ *     receives the same codes transposed (+1 byte written per element) and
+ *     the backward products run on the transposed copies instead; dW does so
+ *     only if both dY's and X's q_t are given.
  *   Rowwise: q is scaled per row (amax, scale, inv_scale: rows entries); q_t is
  *     the transposed tensor scaled per ITS row, i.e. per column of T (amax_t,
  *     scale_t, inv_scale_t: cols entries).  The two hold different codes.
@@ -211,9 +218,9 @@ typedef struct f8_saved {
 
 /*
  * The quantisation the linear layer applies to one bf16 tensor T [rows, cols]
- * (leading dimension cols) under dynamic scaling, both orientations at once:
+ * (leading dimension cols) under dynamic scaling:
  *   g = F8_TENSORWISE: q->amax / scale / inv_scale (1 entry), q->q [rows, cols]
- *     and q->q_t [cols, rows] with the same codes.
+ *     and, if q->q_t is not NULL, q->q_t [cols, rows] with the same codes.
  *   g = F8_ROWWISE: q->q with one scale per row (amax, scale, inv_scale: rows
  *     entries) and q->q_t with one scale per column of T (amax_t, scale_t,
  *     inv_scale_t: cols entries); T is read once for both casts.
@@ -230,19 +237,20 @@ typedef struct f8_linear_desc {
 
 /*
  * Forward of the Float8 linear: quantise X [M,K] and W [N,K] (bf16) with
- * dynamic scaling into saved->x, saved->w (both orientations, for backward),
- * then Y [M,N] (bf16) = X8 W8^T with the scales folded into the epilogue.
+ * dynamic scaling into saved->x, saved->w (kept for the backward), then
+ * Y [M,N] (bf16) = X8 W8^T with the scales folded into the epilogue.
  * Rowwise: Y uses X per row m and W per row n.
  */
 f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, void* Y,
                         f8_saved* saved, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * f8_linear_fwd with the weight already quantised: saved->w holds W's codes in
- * both orientations and its scales from an earlier f8_linear_fwd (or
- * f8_quantise) — weights change once per optimizer step, not per
- * micro-batch (Section 2.2.4 recasts them on every forward; this is the
- * caller's choice to keep them).  Quantises X, computes Y = X8 W8^T.
+ * f8_linear_fwd with the weight already quantised: saved->w holds W's codes
+ * and its scales from an earlier f8_linear_fwd (or f8_quantise) — weights
+ * change once per optimizer step, not per micro-batch.  (Under dynamic scaling
+ * as this library reads Section 2.2.4 the weight is recast on every forward;
+ * keeping the codes is the caller's choice.)  Quantises X, computes
+ * Y = X8 W8^T.
  */
 f8_status f8_linear_fwd_wq(const f8_linear_desc* d, const void* X, void* Y, f8_saved* saved, void* workspace,
                            size_t workspace_bytes, void* stream);
@@ -362,7 +370,7 @@ f8_status f8_rmsnorm(const void* x_bf16, const void* g_bf16, int64_t M, int64_t 
  * scaling (where the scale is known before the tensor exists; this is the kind
  * of producer/cast fusion the paper gets from torch.compile): from ab [M, 2H]
  * = [a | b] it forms h = bf16(silu(a) * b) in registers and writes only its fp8
- * codes: q->q [M, H], q->q_t [H, M], cast with scale[0]; q->scale / inv_scale
+ * codes: q->q [M, H] (and q->q_t [H, M] if given), cast with scale[0]; q->scale / inv_scale
  * receive the scale used, q->amax the amax of h, which is then pushed into
  * history (f8_amax_history_push) and scale[0] becomes the next step's scale.
  * Same results as f8_silu_mul followed by the delayed-scaling quantisation of
@@ -376,7 +384,7 @@ f8_status f8_silu_mul_quantise_delayed(const void* ab_bf16, int64_t M, int64_t H
 /*
  * The same fusion for the backward of the glue: from ab [M, 2H] and dh [M, H]
  * it forms dab = [dh * b * silu'(a) | dh * silu(a)] in registers and writes
- * only its fp8 codes q->q [M, 2H], q->q_t [2H, M] (delayed scaling as above;
+ * only its fp8 codes q->q [M, 2H] (and q->q_t [2H, M] if given; delayed scaling as above;
  * fmt is the gradient format).  Same results as f8_silu_mul_bwd followed by the
  * delayed-scaling quantisation of dab.  workspace: f8_workspace_bytes(M, 2H).
  */
@@ -387,7 +395,7 @@ f8_status f8_silu_mul_bwd_quantise_delayed(const void* ab_bf16, const void* dh_b
 
 /*
  * Backward of the linear whose output gradient is already quantised in
- * saved->dy (codes in both orientations, inv_scale; in d->grad_format): the
+ * saved->dy (codes, inv_scale; in d->grad_format): the
  * two GEMMs dX = dY8 W8, dW = dY8^T X8 only.  Tensorwise only.
  */
 f8_status f8_linear_bwd_dyq(const f8_linear_desc* d, f8_saved* saved, void* dX, void* dW, void* stream);
@@ -491,7 +499,7 @@ f8_status f8_rmsnorm_bwd_add(const void* x_bf16, const void* g_bf16, const float
 
 /*
  * Forward of the linear whose input is already quantised in saved->x (codes in
- * both orientations, scale, inv_scale; e.g. by f8_silu_mul_quantise_delayed):
+ * saved->x.q, scale, inv_scale; e.g. by f8_silu_mul_quantise_delayed):
  * quantises W [N,K] as state->mode says (the w members of the state; for
  * F8_DYNAMIC they are unused), then Y = X8 W8^T.  Tensorwise only.
  */

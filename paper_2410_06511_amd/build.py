@@ -21,8 +21,24 @@ FLAGS = [
 ]
 
 
+GEMM_INST = "f8_gemm_inst.hip"   # compiled once per (format of A, format of B, layout)
+
+
 def sources():
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    """(source file, extra flags, object name) of every translation unit."""
+    units = []
+    for src in sorted(glob.glob(os.path.join(CSRC, "*.hip"))):
+        name = os.path.basename(src)
+        if name == GEMM_INST:
+            for fa in (0, 1):
+                for fb in (0, 1):
+                    for layout in (0, 1, 2):
+                        units.append((src, [f"-DF8_INST_FA={fa}", f"-DF8_INST_FB={fb}", f"-DF8_INST_LAYOUT={layout}"],
+                                      f"f8_gemm_inst_{fa}{fb}{layout}.o"))
+        else:
+            units.append((src, [], name + ".o"))
+    # the GEMM instances take longest: start them first
+    return sorted(units, key=lambda u: os.path.basename(u[0]) != GEMM_INST)
 
 
 def build(extra=(), verbose=False) -> str:
@@ -31,9 +47,10 @@ def build(extra=(), verbose=False) -> str:
     import tempfile
     compile_flags = [f for f in FLAGS if f != "-shared"]
     with tempfile.TemporaryDirectory(prefix="f8build_") as tmp:
-        def compile_one(src):
-            obj = os.path.join(tmp, os.path.basename(src) + ".o")
-            cmd = [HIPCC] + compile_flags + list(extra) + ["-c", src, "-o", obj]
+        def compile_one(unit):
+            src, defs, objname = unit
+            obj = os.path.join(tmp, objname)
+            cmd = [HIPCC] + compile_flags + list(extra) + defs + ["-c", src, "-o", obj]
             if verbose:
                 print(" ".join(cmd), flush=True)
             subprocess.run(cmd, check=True)

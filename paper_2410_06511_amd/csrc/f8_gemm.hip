@@ -5,14 +5,25 @@
 
 namespace f8 {
 
-#define F8_DECLARE_GEMM(NAME)                                                                                     \
-    void NAME(int layout, int g, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb, \
-              const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits, hipStream_t st)
-F8_DECLARE_GEMM(gemm_e4m3_e4m3);
-F8_DECLARE_GEMM(gemm_e5m2_e4m3);
-F8_DECLARE_GEMM(gemm_e4m3_e5m2);
-F8_DECLARE_GEMM(gemm_e5m2_e5m2);
+// gemm_inst_<format of A>_<format of B>_<layout>: one object file each (f8_gemm_inst.hip)
+typedef void (*gemm_fn)(int g, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                        const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                        hipStream_t st);
+#define F8_DECLARE_GEMM(fa, fb, l)                                                                              \
+    void gemm_inst_##fa##_##fb##_##l(int g, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, \
+                                     int64_t ldb, const float* isa, const float* isb, uint16_t* D, int64_t ldd,  \
+                                     uint32_t* amax_bits, hipStream_t st);
+#define F8_DECLARE_LAYOUTS(fa, fb) F8_DECLARE_GEMM(fa, fb, 0) F8_DECLARE_GEMM(fa, fb, 1) F8_DECLARE_GEMM(fa, fb, 2)
+F8_DECLARE_LAYOUTS(0, 0)
+F8_DECLARE_LAYOUTS(0, 1)
+F8_DECLARE_LAYOUTS(1, 0)
+F8_DECLARE_LAYOUTS(1, 1)
+#undef F8_DECLARE_LAYOUTS
 #undef F8_DECLARE_GEMM
+static_assert(F8_E4M3 == 0 && F8_E5M2 == 1 && F8_NT == 0 && F8_NN == 1 && F8_TN == 2, "table order below");
+#define F8_ROW(fa, fb) {gemm_inst_##fa##_##fb##_0, gemm_inst_##fa##_##fb##_1, gemm_inst_##fa##_##fb##_2}
+static const gemm_fn kGemmTable[2][2][3] = {{F8_ROW(0, 0), F8_ROW(0, 1)}, {F8_ROW(1, 0), F8_ROW(1, 1)}};
+#undef F8_ROW
 
 __global__ void zero_word_kernel(uint32_t* p) { p[0] = 0; }
 
@@ -25,10 +36,7 @@ f8_status gemm(int layout, int64_t M, int64_t N, int64_t K, const uint8_t* A, in
     if (M == 0 || N == 0) return last_launch_status();
     uint16_t* d = static_cast<uint16_t*>(D);
     const int m = (int)M, n = (int)N, k = (int)K;
-    if (fa == F8_E4M3 && fb == F8_E4M3) gemm_e4m3_e4m3(layout, g, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, amax_bits, st);
-    else if (fa == F8_E5M2 && fb == F8_E4M3) gemm_e5m2_e4m3(layout, g, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, amax_bits, st);
-    else if (fa == F8_E4M3 && fb == F8_E5M2) gemm_e4m3_e5m2(layout, g, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, amax_bits, st);
-    else gemm_e5m2_e5m2(layout, g, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, amax_bits, st);
+    kGemmTable[fa][fb][layout](g, m, n, k, A, lda, B, ldb, isa, isb, d, ldd, amax_bits, st);
     return last_launch_status();
 }
 

@@ -3,12 +3,17 @@
 // f8_gemm_inst_*.hip one operand-format pair each, so that they compile in parallel).
 //
 // Two kernels:
-//   gemm_nt_kernel      the fast path.  Both operands contraction-contiguous
-//                       ("NT"), K a multiple of 256.  Persistent workgroups,
-//                       global -> LDS direct loads (no VGPR staging), two LDS
-//                       stages of XOR-swizzled 128-byte rows,
-//                       v_mfma_f32_32x32x64_f8f6f4, scales folded into the
-//                       fp32 epilogue, bf16 stores staged through LDS.
+//   gemm_tile_kernel    the fast path, K a multiple of 256, all three layouts.
+//                       Persistent workgroups, global -> LDS direct loads (no
+//                       VGPR staging), two LDS stages, v_mfma_f32_32x32x64_f8f6f4,
+//                       scales folded into the fp32 epilogue, bf16 stores staged
+//                       through LDS.  An operand whose contraction index is the
+//                       fast one in memory ("row-major in K": both of F8_NT, A of
+//                       F8_NN) is staged as XOR-swizzled 128-byte rows; one whose
+//                       contraction index is the slow one ("k-major": B of F8_NN,
+//                       both of F8_TN) is staged as it lies in memory and turned
+//                       on its way from LDS to the registers by the transposing
+//                       LDS read, so no transposed copy of any operand is needed.
 //   gemm_generic_kernel any layout, any multiple-of-16 shape; 64x64 tiles and
 //                       the 16x16x32 fp8 MFMA.  The fallback.
 //
@@ -103,7 +108,7 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
 }
 
 // ---------------------------------------------------------------------------
-// fast NT kernel
+// fast kernel
 // ---------------------------------------------------------------------------
 // Persistent workgroups (one or two per CU) walk over BM x BN output tiles.  K
 // advances in steps of 128 bytes = one LDS stage of 128-byte rows (a full cache
@@ -125,15 +130,46 @@ typedef __bf16 b2 __attribute__((ext_vector_type(2)));
 // rows (128-byte bank window) and any aligned 16 rows (256-byte window).
 __device__ inline int swz(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2); }
 
+// ---- k-major operand tiles ----------------------------------------------------------
+// An operand stored [K, R-direction] (B of F8_NN, both operands of F8_TN) is staged as it
+// lies in memory: per stage 128 k-rows of R = BM or BN bytes.  The MFMA wants, per lane, 32
+// consecutive k of one row of the operand; ds_read_b64_tr_b8 forms them: within each group
+// of 16 lanes, lane i receives byte i % 8 of the 8-byte pieces addressed by lanes i / 8,
+// 2 + i / 8, ..., 14 + i / 8.  With lane s of the group pointing at k-row k0 + s / 2, bytes
+// r0 + 8 (s % 2) .. + 7 of it, lane i ends up with k0 .. k0 + 7 of operand row r0 + i, in
+// natural k order; four such reads make one 32-byte fragment.  The 16-lane groups of a
+// wavefront take rows 0-15 / 16-31 of the 32-row MFMA tile and the two k halves, which is
+// the lane layout of the row-major path.
+// The 16-byte chunks of a k-row are permuted so that the 8 k-rows x 16 bytes of one group,
+// and the 16 chunks of the two groups that differ in the row half, fall on different banks.
+template <int R>
+__device__ inline int kswz(int chunk, int krow)  // logical chunk of k-row -> physical chunk
+{
+    if constexpr (R == 256) return ((chunk & 1) << 3) | ((chunk >> 1) ^ (krow & 7));
+    else return chunk ^ (krow & 7);
+}
+template <int R>
+__device__ inline int kswz_inv(int phys, int krow)
+{
+    if constexpr (R == 256) return (((phys & 7) ^ (krow & 7)) << 1) | (phys >> 3);
+    else return phys ^ (krow & 7);
+}
+typedef int v2i __attribute__((ext_vector_type(2)));
+__device__ inline v2i lds_read_tr8(const uint8_t* p)
+{
+    return __builtin_amdgcn_ds_read_tr8_b64_v2i32((__attribute__((address_space(3))) v2i*)p);
+}
+
 // s_waitcnt immediate (gfx9 encoding: vmcnt[3:0] bits 3:0, vmcnt[5:4] bits 15:14, expcnt 6:4,
 // lgkmcnt 11:8): wait for all vector-memory operations and all LDS operations.
 constexpr int kWaitAllVmLgkm = 0x0070;
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN, bool AMAX = false>
-__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
+// AKM / BKM: operand A / B is k-major (A[K, M] with leading dimension lda, B[K, N] with ldb).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN, bool AMAX, bool AKM, bool BKM>
+__global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ D, int M,
     int N, int K, int64_t lda, int64_t ldb, int64_t ldd, const float* __restrict__ isa,
-    const float* __restrict__ isb, int tiles_m, int tiles_n, uint32_t* __restrict__ amax_bits = nullptr)
+    const float* __restrict__ isb, int tiles_m, int tiles_n, uint32_t* __restrict__ amax_bits)
 {
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
@@ -142,6 +178,8 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     constexpr int A_LOADS = BM / 8 / NW, B_LOADS = BN / 8 / NW;  // 1 KB (8 rows) per wave load
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
     static_assert(NW == 4, "four waves");
+    static_assert(!(AKM || BKM) || (WAVES_M == 2 && WAVES_N == 2 && (BM == 256 || BM == 128) && (BN == 256 || BN == 128)),
+                  "k-major addressing assumes 2 x 2 waves on 128- or 256-wide tiles");
     constexpr int EP_STRIDE = 64 * 2 + 16;    // bytes per staged epilogue row: 64 bf16 + padding
     static_assert(TN % 2 == 0, "the epilogue stages two MFMA tiles side by side");
 
@@ -170,22 +208,61 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     // its row and chunk (three VALU operations), which is cheaper than carrying sixteen offsets
     // in registers across the whole K loop.
     int ld_tile = blockIdx.x;
-    const int a_row = wave * (BM / NW) + (lane >> 3);  // row of piece 0 in the A tile
+    // row-major operand: lane's row of piece 0 in the tile, and its chunk terms (the swizzle of
+    // row + 8 * j differs from that of row only for odd j, bit 2)
+    const int a_row = wave * (BM / NW) + (lane >> 3);
     const int b_row = wave * (BN / NW) + (lane >> 3);
-    // chunk terms: the swizzle of row + 8 * j differs from that of row only for odd j (bit 2)
-    const uint32_t a_c0 = 16 * ((lane & 7) ^ swz(a_row)), a_c1 = 16 * ((lane & 7) ^ swz(a_row + 8));
-    const uint32_t b_c0 = 16 * ((lane & 7) ^ swz(b_row)), b_c1 = 16 * ((lane & 7) ^ swz(b_row + 8));
+    // k-major operand: a 1 KB load covers 1024 / R k-rows; lane i lands at k-row i / (R / 16),
+    // physical chunk i % (R / 16) of them and fetches the logical chunk that belongs there.  The
+    // wave fills k-rows [32 * wave, 32 * wave + 32).  Of the k-row only its low three bits
+    // enter the permutation: they are those of 4 * (load number % 2) + lane's row for R = 256
+    // (four rows per load), of the lane's row for R = 128 (eight rows per load).
+    constexpr int A_CPR = BM / 16, B_CPR = BN / 16;  // chunks per k-row
+    const int a_kr = lane / A_CPR, b_kr = lane / B_CPR;
+    uint32_t a_c0, a_c1, b_c0, b_c1;  // byte offset of the lane's chunk for even / odd load numbers
+    if constexpr (AKM) {
+        a_c0 = 16 * kswz_inv<BM>(lane % A_CPR, a_kr);
+        a_c1 = 16 * kswz_inv<BM>(lane % A_CPR, a_kr + (BM == 256 ? 4 : 0));
+    } else {
+        a_c0 = 16 * ((lane & 7) ^ swz(a_row)), a_c1 = 16 * ((lane & 7) ^ swz(a_row + 8));
+    }
+    if constexpr (BKM) {
+        b_c0 = 16 * kswz_inv<BN>(lane % B_CPR, b_kr);
+        b_c1 = 16 * kswz_inv<BN>(lane % B_CPR, b_kr + (BN == 256 ? 4 : 0));
+    } else {
+        b_c0 = 16 * ((lane & 7) ^ swz(b_row)), b_c1 = 16 * ((lane & 7) ^ swz(b_row + 8));
+    }
     static_assert((BM / NW) % 16 == 0 && (BN / NW) % 16 == 0, "swizzle period");
+    const uint32_t a_krow_off = (uint32_t)(wave * (kBK / NW) + a_kr) * (uint32_t)lda;  // k-major: lane's k-row of load 0
+    const uint32_t b_krow_off = (uint32_t)(wave * (kBK / NW) + b_kr) * (uint32_t)ldb;
     const uint8_t* a_base = A;
     const uint8_t* b_base = B;
-    int a_rmax = 0, b_rmax = 0;  // last valid row of the current load tile, relative to its origin
+    // row-major: last valid row of the current load tile, relative to its origin (rows past the
+    // edge re-read the last row; never stored).  k-major: the lane's whole offset for even / odd
+    // load numbers, with chunks past the edge re-reading the last valid chunk of the k-row.
+    int a_rmax = 0, b_rmax = 0;
+    uint32_t a_o0 = 0, a_o1 = 0, b_o0 = 0, b_o1 = 0;
     auto load_context = [&](int tile) {
         int tm, tn;
         tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
-        a_base = A + (int64_t)tm * BM * lda;
-        b_base = B + (int64_t)tn * BN * ldb;
-        a_rmax = M - 1 - tm * BM;  // rows past the edge re-read the last row; never stored
-        b_rmax = N - 1 - tn * BN;
+        if constexpr (AKM) {
+            a_base = A + (int64_t)tm * BM;
+            const uint32_t cmax = (uint32_t)(M - 16 - tm * BM);
+            a_o0 = a_krow_off + (a_c0 < cmax ? a_c0 : cmax);
+            a_o1 = a_krow_off + (a_c1 < cmax ? a_c1 : cmax);
+        } else {
+            a_base = A + (int64_t)tm * BM * lda;
+            a_rmax = M - 1 - tm * BM;
+        }
+        if constexpr (BKM) {
+            b_base = B + (int64_t)tn * BN;
+            const uint32_t cmax = (uint32_t)(N - 16 - tn * BN);
+            b_o0 = b_krow_off + (b_c0 < cmax ? b_c0 : cmax);
+            b_o1 = b_krow_off + (b_c1 < cmax ? b_c1 : cmax);
+        } else {
+            b_base = B + (int64_t)tn * BN * ldb;
+            b_rmax = N - 1 - tn * BN;
+        }
     };
     // Load number `idx` (0 .. LOADS-1: first the A pieces, then the B pieces) of K step `kt` of
     // the stream's current tile, into stage S.  Written as asm: 32-bit lane offset next to a
@@ -194,21 +271,35 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     auto issue_one = [&](int kt, auto S, auto IDX) {
         constexpr int idx = decltype(IDX)::value;
         if constexpr (idx < A_LOADS) {
-            const uint8_t* gp = a_base + (int64_t)kt * kBK;
             uint8_t* lp = stage_ptr(S) + wave * (BM / NW) * kBK + idx * 1024;
             const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
-            int r = a_row + 8 * idx;
-            r = r < a_rmax ? r : a_rmax;
-            const uint32_t o = (uint32_t)r * (uint32_t)lda + ((idx & 1) ? a_c1 : a_c0);
+            const uint8_t* gp;
+            uint32_t o;
+            if constexpr (AKM) {
+                gp = a_base + ((int64_t)kt * kBK + idx * (1024 / BM)) * lda;
+                o = (idx & 1) ? a_o1 : a_o0;
+            } else {
+                gp = a_base + (int64_t)kt * kBK;
+                int r = a_row + 8 * idx;
+                r = r < a_rmax ? r : a_rmax;
+                o = (uint32_t)r * (uint32_t)lda + ((idx & 1) ? a_c1 : a_c0);
+            }
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
         } else {
             constexpr int j = idx - A_LOADS;
-            const uint8_t* gp = b_base + (int64_t)kt * kBK;
             uint8_t* lp = stage_ptr(S) + A_BYTES + wave * (BN / NW) * kBK + j * 1024;
             const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
-            int r = b_row + 8 * j;
-            r = r < b_rmax ? r : b_rmax;
-            const uint32_t o = (uint32_t)r * (uint32_t)ldb + ((j & 1) ? b_c1 : b_c0);
+            const uint8_t* gp;
+            uint32_t o;
+            if constexpr (BKM) {
+                gp = b_base + ((int64_t)kt * kBK + j * (1024 / BN)) * ldb;
+                o = (j & 1) ? b_o1 : b_o0;
+            } else {
+                gp = b_base + (int64_t)kt * kBK;
+                int r = b_row + 8 * j;
+                r = r < b_rmax ? r : b_rmax;
+                o = (uint32_t)r * (uint32_t)ldb + ((j & 1) ? b_c1 : b_c0);
+            }
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
         }
     };
@@ -221,33 +312,62 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
         if (ld_tile < total_tiles) load_context(ld_tile);
     };
 
-    // ---- LDS -> register addressing: lane reads row (l % 32) of a 32-row MFMA tile; in
-    // half-step h the logical chunks 4h + 2g and 4h + 2g + 1 (g = l / 32): 32 K bytes.
+    // ---- LDS -> register addressing.  Row-major operand: lane reads row (l % 32) of a 32-row
+    // MFMA tile; in half-step h the logical chunks 4h + 2g and 4h + 2g + 1 (g = l / 32): 32 K bytes.
     const int fr = lane & 31, fg = lane >> 5;
     const int pc0 = (2 * fg) ^ swz(fr);
-    const int a_rd = (wm * WM + fr) * kBK + 16 * pc0;  // + 32-row tile * 4096
-    const int b_rd = A_BYTES + (wn * WN + fr) * kBK + 16 * pc0;
     const int flip1 = ((pc0 ^ 1) - pc0) * 16;          // to the second chunk of the pair
     const int fliph = ((pc0 ^ 4) - pc0) * 16;          // to the same chunk of half-step 1
+    // k-major operand: lane s of 16-lane group q points at k-row 32 (q / 2) + s / 2 (+ 8 t for the
+    // t-th of the four reads, + 64 for half-step 1) and at the 8 bytes (s % 2) of the chunk that
+    // holds rows 16 (q % 2) .. + 15 of the MFMA tile.  Going to MFMA tile idx of the wave moves
+    // two chunks on, which the permutation turns into an XOR of the address.
+    const int kq = lane >> 4, ks = lane & 15;
+    auto km_read_base = [&](auto R_, int wave_row0) {
+        constexpr int R = decltype(R_)::value;
+        return (32 * (kq >> 1) + (ks >> 1)) * R + 16 * kswz<R>(wave_row0 / 16 + (kq & 1), ks >> 1) + 8 * (ks & 1);
+    };
+    int a_rd, b_rd;
+    if constexpr (AKM) a_rd = km_read_base(integral_constant<int, BM>{}, wm * WM);
+    else a_rd = (wm * WM + fr) * kBK + 16 * pc0;  // + 32-row tile * 4096
+    if constexpr (BKM) b_rd = A_BYTES + km_read_base(integral_constant<int, BN>{}, wn * WN);
+    else b_rd = A_BYTES + (wn * WN + fr) * kBK + 16 * pc0;
+    constexpr int A_XSTEP = BM == 256 ? 16 : 32, B_XSTEP = BN == 256 ? 16 : 32;
 
     struct Frags {
         v8i a[TM];
         v8i b[TN];
     };
+    auto read_km = [&](const uint8_t* p, auto R_) {
+        constexpr int R = decltype(R_)::value;
+        const v2i t0 = lds_read_tr8(p), t1 = lds_read_tr8(p + 8 * R), t2 = lds_read_tr8(p + 16 * R),
+                  t3 = lds_read_tr8(p + 24 * R);
+        return v8i{t0.x, t0.y, t1.x, t1.y, t2.x, t2.y, t3.x, t3.y};
+    };
     // fragment number `idx` of a half-step: 0 .. TM-1 are the A fragments, TM .. TM+TN-1 the B ones
     auto read_frag = [&](Frags& f, auto S, auto H, auto IDX) {
         constexpr int idx = decltype(IDX)::value;
-        const int hoff = decltype(H)::value ? fliph : 0;
+        constexpr int h = decltype(H)::value;
+        const int hoff = h ? fliph : 0;
         if constexpr (idx < TM) {
-            const uint8_t* sa = stage_ptr(S) + a_rd + hoff + idx * 32 * kBK;
-            const int4 lo = *reinterpret_cast<const int4*>(sa);
-            const int4 hi = *reinterpret_cast<const int4*>(sa + flip1);
-            f.a[idx] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            if constexpr (AKM) {
+                f.a[idx] = read_km(stage_ptr(S) + (a_rd ^ (idx * A_XSTEP)) + h * 64 * BM, integral_constant<int, BM>{});
+            } else {
+                const uint8_t* sa = stage_ptr(S) + a_rd + hoff + idx * 32 * kBK;
+                const int4 lo = *reinterpret_cast<const int4*>(sa);
+                const int4 hi = *reinterpret_cast<const int4*>(sa + flip1);
+                f.a[idx] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            }
         } else {
-            const uint8_t* sb = stage_ptr(S) + b_rd + hoff + (idx - TM) * 32 * kBK;
-            const int4 lo = *reinterpret_cast<const int4*>(sb);
-            const int4 hi = *reinterpret_cast<const int4*>(sb + flip1);
-            f.b[idx - TM] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            constexpr int j = idx - TM;
+            if constexpr (BKM) {
+                f.b[j] = read_km(stage_ptr(S) + (b_rd ^ (j * B_XSTEP)) + h * 64 * BN, integral_constant<int, BN>{});
+            } else {
+                const uint8_t* sb = stage_ptr(S) + b_rd + hoff + j * 32 * kBK;
+                const int4 lo = *reinterpret_cast<const int4*>(sb);
+                const int4 hi = *reinterpret_cast<const int4*>(sb + flip1);
+                f.b[j] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            }
         }
     };
     auto read_frags = [&](Frags& f, auto S, auto H) {
@@ -410,16 +530,12 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_nt_kernel(
     constexpr int NF = TM + TN;                       // fragments per half-step
     constexpr int SLOTS = 2 * NMFMA;
     // f1's fragment reads are spread over slots [0, F1_SPAN), f0's over [SYNC_B, SLOTS).  The two
-    // tunables (for the 16-MFMA half-steps of the 256x256 tile) were chosen by measurement.
-#ifndef F8_SCHED_COVER
-#define F8_SCHED_COVER 2
-#endif
-#ifndef F8_SCHED_F0_SPAN
-#define F8_SCHED_F0_SPAN 12
-#endif
+    // constants for the 16-MFMA half-steps of the 256x256 tile (MFMA slots between the last read
+    // of f1 and barrier A; slots over which f0's reads are spread) were chosen by measurement.
+    constexpr int kCoverSlots = 2, kF0Span = 12;
     constexpr int F1_SPAN = NF < NMFMA / 2 ? NF : NMFMA / 2;
-    constexpr int F0_SPAN = NMFMA >= 16 ? F8_SCHED_F0_SPAN : F1_SPAN;
-    constexpr int SYNC_A = F1_SPAN + (NMFMA >= 16 ? F8_SCHED_COVER : 1);
+    constexpr int F0_SPAN = NMFMA >= 16 ? kF0Span : F1_SPAN;
+    constexpr int SYNC_A = F1_SPAN + (NMFMA >= 16 ? kCoverSlots : 1);
     constexpr int SYNC_B = SLOTS - F0_SPAN;
     constexpr auto f1_slot = [](int n) { return n * F1_SPAN / NF; };            // fragment n (in read order)
     constexpr auto f0_slot = [](int n) { return SYNC_B + n * F0_SPAN / NF; };
@@ -601,19 +717,19 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 // host side
 // ---------------------------------------------------------------------------
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN>
-static void launch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
-                      const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
-                      int max_blocks, hipStream_t st)
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN, bool AKM, bool BKM>
+static void launch_tile(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                        const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                        int max_blocks, hipStream_t st)
 {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
     const int grid = total < max_blocks ? total : max_blocks;
     if (amax_bits)
-        gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN, true><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
+        gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN, true, AKM, BKM><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
             A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tiles_m, tiles_n, amax_bits);
     else
-        gemm_nt_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN, false><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
+        gemm_tile_kernel<BM, BN, WAVES_M, WAVES_N, FA, FB, GRAN, false, AKM, BKM><<<grid, WAVES_M * WAVES_N * 64, 0, st>>>(
             A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tiles_m, tiles_n, nullptr);
 }
 
@@ -625,10 +741,10 @@ static int cu_count()
     return n - n % kXcds;  // the persistent tile order assumes a multiple of the XCD count
 }
 
-template <int FA, int FB, int GRAN>
-static void dispatch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
-                        const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
-                        hipStream_t st)
+template <int FA, int FB, int GRAN, bool AKM, bool BKM>
+static void dispatch_tile(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                          const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                          hipStream_t st)
 {
     // Tile configuration by estimated time, in units of one 256x256 tile's time on one compute
     // unit: T tiles on `cus` persistent workgroups take ceil(T / cus) rounds; a 256x128 tile costs
@@ -650,26 +766,30 @@ static void dispatch_nt(int M, int N, int K, const uint8_t* A, int64_t lda, cons
     const double c_half = rounds(tiles(256, 128)) * kHalfTile;
     const double c_quarter = rounds(tiles(128, 128)) * kQuarterTile;
     const bool rw = GRAN != F8_TENSORWISE;
+#define F8_TILE(BM_, BN_) launch_tile<BM_, BN_, 2, 2, FA, FB, GRAN, AKM, BKM>
     if (c_full <= c_half && c_full <= c_quarter) {
         if (split_rows) {
             const int m1 = (int)(whole / tn) * 256;
-            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(m1, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
-            launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M - m1, N, K, A + (int64_t)m1 * lda, lda, B, ldb, rw ? isa + m1 : isa,
-                                                    isb, D + (int64_t)m1 * ldd, ldd, amax_bits, cus, st);
+            // rows m1 .. M-1 of A: m1 rows down (row-major) or m1 bytes along each k-row (k-major)
+            const uint8_t* A2 = AKM ? A + m1 : A + (int64_t)m1 * lda;
+            F8_TILE(256, 256)(m1, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+            F8_TILE(256, 128)(M - m1, N, K, A2, lda, B, ldb, rw ? isa + m1 : isa, isb, D + (int64_t)m1 * ldd, ldd,
+                              amax_bits, cus, st);
         } else if (split_cols) {
             const int n1 = (int)(whole / tm) * 256;
-            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, n1, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
-            launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N - n1, K, A, lda, B + (int64_t)n1 * ldb, ldb, isa,
-                                                    rw ? isb + n1 : isb, D + n1, ldd, amax_bits, cus, st);
+            const uint8_t* B2 = BKM ? B + n1 : B + (int64_t)n1 * ldb;
+            F8_TILE(256, 256)(M, n1, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+            F8_TILE(256, 128)(M, N - n1, K, A, lda, B2, ldb, isa, rw ? isb + n1 : isb, D + n1, ldd, amax_bits, cus, st);
         } else {
-            launch_nt<256, 256, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+            F8_TILE(256, 256)(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
         }
     } else if (c_half <= c_quarter) {
-        launch_nt<256, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
+        F8_TILE(256, 128)(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, cus, st);
     } else {
         // LDS allows two 128x128 workgroups per compute unit
-        launch_nt<128, 128, 2, 2, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, 2 * cus, st);
+        F8_TILE(128, 128)(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, 2 * cus, st);
     }
+#undef F8_TILE
 }
 
 template <int LAYOUT, int FA, int FB, int GRAN>
@@ -682,33 +802,30 @@ static void launch_generic(int M, int N, int K, const uint8_t* A, int64_t lda, c
                                                                     amax_bits);
 }
 
-template <int FA, int FB, int GRAN>
-static void dispatch_layout(int layout, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B,
-                            int64_t ldb, const float* isa, const float* isb, uint16_t* D, int64_t ldd,
-                            uint32_t* amax_bits, hipStream_t st)
+// One layout of one operand-format pair: the fast kernel when the contraction length allows it
+// (it alternates two LDS stages of 128 per tile), else the generic one.
+template <int LAYOUT, int FA, int FB, int GRAN>
+static void dispatch_layout(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                            const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                            hipStream_t st)
 {
-    if (layout == F8_NT) {
-        if (K % (2 * kBK) == 0 && K > 0)  // the fast kernel alternates two LDS stages per tile
-            dispatch_nt<FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
-        else
-            launch_generic<F8_NT, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
-    } else if (layout == F8_NN) {
-        launch_generic<F8_NN, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
-    } else {
-        launch_generic<F8_TN, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
-    }
+    if (K % (2 * kBK) == 0 && K > 0)
+        dispatch_tile<FA, FB, GRAN, LAYOUT == F8_TN, LAYOUT != F8_NT>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd,
+                                                                       amax_bits, st);
+    else
+        launch_generic<LAYOUT, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
 }
 
-// All launches of one operand-format pair: granularity and layout are run-time choices.
-template <int FA, int FB>
-static void gemm_formats(int layout, int g, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B,
-                         int64_t ldb, const float* isa, const float* isb, uint16_t* D, int64_t ldd,
-                         uint32_t* amax_bits, hipStream_t st)
+// All launches of one operand-format pair and layout: the granularity is a run-time choice.
+template <int LAYOUT, int FA, int FB>
+static void gemm_formats(int g, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                         const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
+                         hipStream_t st)
 {
     if (g == F8_TENSORWISE)
-        dispatch_layout<FA, FB, F8_TENSORWISE>(layout, M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+        dispatch_layout<LAYOUT, FA, FB, F8_TENSORWISE>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
     else
-        dispatch_layout<FA, FB, F8_ROWWISE>(layout, M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+        dispatch_layout<LAYOUT, FA, FB, F8_ROWWISE>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
 }
 
 }  // namespace f8

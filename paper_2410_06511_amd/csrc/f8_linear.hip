@@ -2,11 +2,16 @@
 // quantisation (amax -> scale -> cast) and the fp8 GEMM, all enqueued on one
 // stream with no host synchronisation in between.
 //
-// The GEMM kernels want both operands contraction-contiguous, so every tensor
-// is cast into both orientations while it is being read anyway:
-//   Y  [M,N] = X8  [M,K] . W8  [N,K]^T     contraction K
-//   dX [M,K] = dY8 [M,N] . W8t [K,N]^T     contraction N
-//   dW [N,K] = dY8t[N,M] . X8t [K,M]^T     contraction M
+// Tensorwise scaling keeps ONE code tensor per operand; the backward products read them in
+// the orientation they were written in (the GEMM kernel turns k-major operands on their way
+// from LDS to the registers):
+//   Y  [M,N] = X8  [M,K] . W8 [N,K]^T     F8_NT, contraction K
+//   dX [M,K] = dY8 [M,N] . W8 [N,K]       F8_NN, contraction N
+//   dW [N,K] = dY8 [M,N]^T . X8 [M,K]     F8_TN, contraction M
+// A caller that also passes transposed code tensors (q_t) gets them filled, and the backward
+// then runs as F8_NT products on them.  Rowwise scaling needs two differently scaled code sets
+// per tensor anyway (per row for one product, per column for the other); the second is kept
+// transposed in q_t.
 #include "f8_host.hpp"
 
 namespace f8 {
@@ -23,9 +28,9 @@ static f8_status check_desc(const f8_linear_desc* d)
 
 static f8_status check_q(const f8_qtensor* q, bool rowwise)
 {
-    if (!q->q || !q->q_t || !q->amax || !q->scale || !q->inv_scale) return F8_ERR_NULL;
-    if (rowwise && (!q->amax_t || !q->scale_t || !q->inv_scale_t)) return F8_ERR_NULL;
-    if (!aligned16(q->q) || !aligned16(q->q_t)) return F8_ERR_ALIGN;
+    if (!q->q || !q->amax || !q->scale || !q->inv_scale) return F8_ERR_NULL;
+    if (rowwise && (!q->q_t || !q->amax_t || !q->scale_t || !q->inv_scale_t)) return F8_ERR_NULL;
+    if (!aligned16(q->q) || !aligned16(q->q_t)) return F8_ERR_ALIGN;  // a null q_t counts as aligned
     if (rowwise && (!aligned16(q->scale) || !aligned16(q->inv_scale) || !aligned16(q->scale_t) ||
                     !aligned16(q->inv_scale_t)))
         return F8_ERR_ALIGN;
@@ -132,19 +137,29 @@ static f8_status gemm_fwd(const f8_linear_desc* d, const f8_saved* sv, void* Y, 
                 sv->w.inv_scale, d->granularity, Y, d->N, y_amax, st);
 }
 
-// dX [M,K] = dY8 [M,N] . (W8t [K,N])^T : dY per row m; W per column k = per row of W8t
-// dW [N,K] = dY8t [N,M] . (X8t [K,M])^T : dY per column n, X per column k
+// dX [M,K] = dY8 [M,N] . W8 [N,K]: contraction N, W read k-major; with a transposed copy of W's
+//   codes as dY8 . (W8t [K,N])^T.  Rowwise: dY per row m; W per column k = per row of W8t.
+// dW [N,K] = dY8 [M,N]^T . X8 [M,K]: contraction M, both read k-major; with transposed copies of
+//   both as dY8t [N,M] . (X8t [K,M])^T.  Rowwise: dY per column n, X per column k.
 static f8_status gemms_bwd(const f8_linear_desc* d, const f8_saved* sv, void* dX, float* dx_amax, void* dW,
                            hipStream_t st)
 {
     const int64_t M = d->M, K = d->K, N = d->N;
     const int gf = d->grad_format;
     const bool rw = d->granularity == F8_ROWWISE;
-    f8_status s = gemm(F8_NT, M, K, N, sv->dy.q, gf, N, sv->w.q_t, F8_E4M3, N, sv->dy.inv_scale,
-                       rw ? sv->w.inv_scale_t : sv->w.inv_scale, d->granularity, dX, K, dx_amax, st);
+    f8_status s;
+    if (sv->w.q_t)
+        s = gemm(F8_NT, M, K, N, sv->dy.q, gf, N, sv->w.q_t, F8_E4M3, N, sv->dy.inv_scale,
+                 rw ? sv->w.inv_scale_t : sv->w.inv_scale, d->granularity, dX, K, dx_amax, st);
+    else
+        s = gemm(F8_NN, M, K, N, sv->dy.q, gf, N, sv->w.q, F8_E4M3, K, sv->dy.inv_scale, sv->w.inv_scale,
+                 d->granularity, dX, K, dx_amax, st);
     if (s != F8_OK) return s;
-    return gemm(F8_NT, N, K, M, sv->dy.q_t, gf, M, sv->x.q_t, F8_E4M3, M, rw ? sv->dy.inv_scale_t : sv->dy.inv_scale,
-                rw ? sv->x.inv_scale_t : sv->x.inv_scale, d->granularity, dW, K, nullptr, st);
+    if (sv->dy.q_t && sv->x.q_t)
+        return gemm(F8_NT, N, K, M, sv->dy.q_t, gf, M, sv->x.q_t, F8_E4M3, M, rw ? sv->dy.inv_scale_t : sv->dy.inv_scale,
+                    rw ? sv->x.inv_scale_t : sv->x.inv_scale, d->granularity, dW, K, nullptr, st);
+    return gemm(F8_TN, N, K, M, sv->dy.q, gf, N, sv->x.q, F8_E4M3, K, sv->dy.inv_scale, sv->x.inv_scale,
+                d->granularity, dW, K, nullptr, st);
 }
 
 }  // namespace f8

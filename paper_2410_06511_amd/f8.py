@@ -182,13 +182,15 @@ def gemm(layout, M, N, K, A, fa, B, fb, inv_scale_a, inv_scale_b, g, D, stream=N
 
 
 class QTensor:
-    """Device buffers of one quantised tensor T[rows, cols] (see f8_qtensor)."""
+    """Device buffers of one quantised tensor T[rows, cols] (see f8_qtensor).  q_t (the codes
+    transposed) exists under rowwise scaling, where it holds the per-column-scaled codes, and
+    with transposed=True; otherwise it is None and the backward products read q in place."""
 
-    def __init__(self, rows, cols, rowwise, device="cuda"):
+    def __init__(self, rows, cols, rowwise, device="cuda", transposed=False):
         u8 = dict(dtype=torch.uint8, device=device)
         f32 = dict(dtype=torch.float32, device=device)
         self.q = torch.empty((rows, cols), **u8)
-        self.q_t = torch.empty((cols, rows), **u8)
+        self.q_t = torch.empty((cols, rows), **u8) if (rowwise or transposed) else None
         n = rows if rowwise else 1
         self.amax, self.scale, self.inv_scale = (torch.empty(n, **f32) for _ in range(3))
         if rowwise:
@@ -204,10 +206,10 @@ class QTensor:
 class Saved:
     """f8_saved for one linear: X [M,K], W [N,K], dY [M,N]."""
 
-    def __init__(self, M, K, N, rowwise=False, device="cuda"):
-        self.x = QTensor(M, K, rowwise, device)
-        self.w = QTensor(N, K, rowwise, device)
-        self.dy = QTensor(M, N, rowwise, device)
+    def __init__(self, M, K, N, rowwise=False, device="cuda", transposed=False):
+        self.x = QTensor(M, K, rowwise, device, transposed)
+        self.w = QTensor(N, K, rowwise, device, transposed)
+        self.dy = QTensor(M, N, rowwise, device, transposed)
         self._struct = SavedStruct(self.x.struct(), self.w.struct(), self.dy.struct())
 
     def struct(self):

@@ -27,6 +27,16 @@ def f32(t):
     return t.detach().cpu().contiguous().numpy()
 
 
+def qt_matches(q, expect_t):
+    """The transposed code tensor of a QTensor equals expect_t (numpy), when there is one."""
+    return q.q_t is None or np.array_equal(u8(q.q_t), expect_t)
+
+
+def codes_t(q):
+    """The tensor to snapshot for a QTensor's second orientation (q itself if it keeps none)."""
+    return q.q if q.q_t is None else q.q_t
+
+
 def bf16_from_f32(a):
     return torch.from_numpy(np.asarray(a, dtype=np.float32)).to(torch.bfloat16)
 

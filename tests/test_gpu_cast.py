@@ -272,12 +272,13 @@ def test_quantise_both_orientations(rows, cols, fmt):
     x[:, 5] *= 0.01
     xb = bits(x)
     ws = f8.new_workspace(rows, cols)
-    q = f8.QTensor(rows, cols, False)
-    f8.quantise(x.cuda(), f8.TENSORWISE, fmt, q, ws)
-    torch.cuda.synchronize()
     a, s, inv, codes = o.amax_cast(xb, o.TENSORWISE, fmt)
-    assert f32(q.amax)[0] == a[0] and f32(q.scale)[0] == s[0] and f32(q.inv_scale)[0] == inv[0]
-    assert np.array_equal(u8(q.q), codes) and np.array_equal(u8(q.q_t), codes.T)
+    for transposed in (True, False):   # with and without the optional transposed copy
+        q = f8.QTensor(rows, cols, False, transposed=transposed)
+        f8.quantise(x.cuda(), f8.TENSORWISE, fmt, q, ws)
+        torch.cuda.synchronize()
+        assert f32(q.amax)[0] == a[0] and f32(q.scale)[0] == s[0] and f32(q.inv_scale)[0] == inv[0]
+        assert np.array_equal(u8(q.q), codes) and (not transposed or np.array_equal(u8(q.q_t), codes.T))
     q = f8.QTensor(rows, cols, True)
     f8.quantise(x.cuda(), f8.ROWWISE, fmt, q, ws)
     torch.cuda.synchronize()

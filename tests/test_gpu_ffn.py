@@ -7,7 +7,7 @@ import torch
 import oracle as o
 from paper_2410_06511_amd import f8
 from paper_2410_06511_amd import workloads as wl
-from helpers import bits, u8, f32, assert_gemm_close
+from helpers import bits, u8, f32, assert_gemm_close, codes_t
 
 pytestmark = pytest.mark.gpu
 
@@ -120,7 +120,7 @@ def test_ffn_chained_equals_unchained(M, D, H):
         f.forward(X, W13, W2, chained)
         f.backward(dY, chained)
         torch.cuda.synchronize()
-        outs.append((f.Y, f.dX, f.dW13, f.dW2, f.Hh, f.dAB, f.s2.x.q, f.s13.dy.q_t, f.s2.x.scale, f.s13.dy.scale))
+        outs.append((f.Y, f.dX, f.dW13, f.dW2, f.Hh, f.dAB, f.s2.x.q, codes_t(f.s13.dy), f.s2.x.scale, f.s13.dy.scale))
     for a, b in zip(*outs):
         assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
 
@@ -240,7 +240,7 @@ def test_norm_then_feed_forward_chain():
         else:
             f.forward(xn, W13, W2, chained=False)
         torch.cuda.synchronize()
-        outs.append((f.Y, f.s13.x.q, f.s13.x.scale, f.s2.x.q_t))
+        outs.append((f.Y, f.s13.x.q, f.s13.x.scale, codes_t(f.s2.x)))
     for a, b in zip(*outs):
         assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
 
@@ -272,7 +272,7 @@ def test_glue_fused_into_the_delayed_cast(M, D, H):
                 f8.silu_mul(AB, h)
                 f8.linear_fwd_scaled(desc, st, h, W2, Y, saved, ws)
             torch.cuda.synchronize()
-            snaps.append([t.clone() for t in (Y, saved.x.q, saved.x.q_t, saved.x.amax, saved.x.scale, saved.x.inv_scale,
+            snaps.append([t.clone() for t in (Y, saved.x.q, codes_t(saved.x), saved.x.amax, saved.x.scale, saved.x.inv_scale,
                                               saved.w.q, st.hist_x, st.scale_x, st.hist_w, st.scale_w)])
         results.append(snaps)
     for a_step, b_step in zip(*results):
@@ -323,7 +323,7 @@ def test_glue_backward_fused_into_the_delayed_cast(M, D, H):
                 f8.silu_mul_bwd(AB, dh, dAB)
                 f8.linear_bwd_scaled(desc, st, dAB, saved, dX, dW, ws)
             torch.cuda.synchronize()
-            snaps.append([t.clone() for t in (dX, dW, saved.dy.q, saved.dy.q_t, saved.dy.amax, saved.dy.scale,
+            snaps.append([t.clone() for t in (dX, dW, saved.dy.q, codes_t(saved.dy), saved.dy.amax, saved.dy.scale,
                                               saved.dy.inv_scale, st.hist_dy, st.scale_dy)])
         results.append(snaps)
     for a_step, b_step in zip(*results):
@@ -335,12 +335,10 @@ def test_glue_backward_fused_into_the_delayed_cast(M, D, H):
     used_scale = f32(results[1][-1][5])
     ref_codes = o.cast(rd, used_scale, o.TENSORWISE, o.E4M3)
     got = u8(results[1][-1][2])
-    got_t = u8(results[1][-1][3])
     f8.silu_mul_bwd(AB, dh, dAB)
     torch.cuda.synchronize()
     same = bits(dAB) == rd
     assert same.mean() > 0.97 and np.array_equal(got[same], ref_codes[same])
-    assert np.array_equal(got_t, got.T)
 
 
 def test_fused_glue_backward_argument_checks():

@@ -103,6 +103,53 @@ def test_gemm_exact_arithmetic_bit_for_bit(layout, M, N, K):
     assert np.array_equal(got, o.gemm(layout, A, o.E4M3, B, o.E4M3, inv, inv))
 
 
+# More tiles than compute units, so that persistent workgroups walk several tiles (the load
+# stream runs across tile boundaries) and the two-launch dispatch is taken: 8192 x 4096 = 512
+# tiles of 256 x 256 (two rounds); 14336 x 4096 = 896 tiles = 3.5 rounds (whole rounds on a range
+# of tile rows, the rest as 256 x 128 tiles); 4096 x 14336 likewise on a range of tile columns.
+@pytest.mark.parametrize("layout", [o.NT, o.NN, o.TN])
+@pytest.mark.parametrize("g", [f8.TENSORWISE, f8.ROWWISE])
+@pytest.mark.parametrize("M,N,K", [(8192, 4096, 1024), (14336, 4096, 512), (4096, 14336, 512)])
+def test_gemm_exact_arithmetic_multi_round(layout, g, M, N, K):
+    """The exact-arithmetic grid (see above) at sizes where a workgroup computes several tiles:
+    bit for bit against the fp64 product rounded once to bf16, scales powers of two (one per
+    tensor, or one per row and per column)."""
+    rng = np.random.default_rng(77 + layout + M)
+    vals = np.array([0, 64, -64, 128, -128, 256, -256, 448, -448], np.float32)
+    grid = o.encode(vals, o.E4M3)
+    sa, sb = shapes_of(layout, M, N, K)
+    A, B = grid[rng.integers(0, 9, sa)], grid[rng.integers(0, 9, sb)]
+    if g == f8.TENSORWISE:
+        isa, isb = np.float32(2.0 ** -7), np.float32(2.0 ** -6)
+        sc = np.float64(2.0 ** -13)
+    else:
+        isa = (2.0 ** -(5.0 + (np.arange(M) % 4))).astype(np.float32)
+        isb = (2.0 ** -(6.0 + (np.arange(N) % 3))).astype(np.float32)
+        sc = isa.astype(np.float64)[:, None] * isb.astype(np.float64)[None, :]
+    got = run_gemm(layout, M, N, K, A, o.E4M3, B, o.E4M3, isa, isb, g)
+    a = torch.from_numpy(o.decode(A, o.E4M3).astype(np.float64))
+    b = torch.from_numpy(o.decode(B, o.E4M3).astype(np.float64))
+    exact = {o.NT: lambda: a @ b.T, o.NN: lambda: a @ b, o.TN: lambda: a.T @ b}[layout]() * torch.from_numpy(np.asarray(sc))
+    closed = exact.to(torch.bfloat16).view(torch.uint16).numpy()
+    assert np.array_equal(got, closed)
+
+
+def test_gemm_exact_arithmetic_long_contraction():
+    """The same grid with the 8B forward shape's contraction length (every sum still below 2^30
+    in units of 2^12): the full-size launch configuration, zero tolerance."""
+    rng = np.random.default_rng(5)
+    M, N, K = 8192, 4096, 4096
+    vals = np.array([0, 64, -64, 128, -128, 256, -256, 448, -448], np.float32)
+    grid = o.encode(vals, o.E4M3)
+    A, B = grid[rng.integers(0, 9, (M, K))], grid[rng.integers(0, 9, (K, N))]
+    inv = np.float32(2.0 ** -7)
+    got = run_gemm(o.NN, M, N, K, A, o.E4M3, B, o.E4M3, inv, inv, f8.TENSORWISE)
+    a = torch.from_numpy(o.decode(A, o.E4M3).astype(np.float64))
+    b = torch.from_numpy(o.decode(B, o.E4M3).astype(np.float64))
+    closed = ((a @ b) * 2.0 ** -14).to(torch.bfloat16).view(torch.uint16).numpy()
+    assert np.array_equal(got, closed)
+
+
 def test_gemm_output_guard_band_and_ldd():
     """D with a leading dimension larger than N: columns beyond N stay untouched."""
     rng = np.random.default_rng(5)
@@ -189,17 +236,19 @@ def test_gemm_amax_of_empty_output_is_zero():
 # second launch with 256x128 tiles, ragged edge included.
 @pytest.mark.parametrize("M,N,K", [(4112, 4144, 256), (2064, 3600, 512), (4368, 4112, 512), (272, 65552, 256),
                                    (4368, 4000, 256), (4000, 4368, 256)])
-def test_gemm_fast_kernel_ragged_big_tiles(M, N, K, g):
+@pytest.mark.parametrize("layout", [o.NT, o.NN, o.TN])
+def test_gemm_fast_kernel_ragged_big_tiles(M, N, K, g, layout):
     rng = np.random.default_rng(M + N)
-    A, B = rand_codes(rng, (M, K), o.E4M3), rand_codes(rng, (N, K), o.E5M2)
+    sa, sb = shapes_of(layout, M, N, K)
+    A, B = rand_codes(rng, sa, o.E4M3), rand_codes(rng, sb, o.E5M2)
     if g == f8.TENSORWISE:
         isa, isb = np.float32(2.0 ** -5), np.float32(2.0 ** -9)
     else:
         isa = (rng.uniform(0.5, 2.0, M) * 2.0 ** -5).astype(np.float32)
         isb = (rng.uniform(0.5, 2.0, N) * 2.0 ** -9).astype(np.float32)
-    got = run_gemm(o.NT, M, N, K, A, o.E4M3, B, o.E5M2, isa, isb, g)
-    ref = o.gemm(o.NT, A, o.E4M3, B, o.E5M2, isa, isb, g)
-    assert_gemm_close(got, ref, (M, N, K, g))
+    got = run_gemm(layout, M, N, K, A, o.E4M3, B, o.E5M2, isa, isb, g)
+    ref = o.gemm(layout, A, o.E4M3, B, o.E5M2, isa, isb, g)
+    assert_gemm_close(got, ref, (M, N, K, g, layout))
     # per-row check as well, so that a wrong edge row cannot hide behind the global maximum
     gf, rf = o.bf16_to_f32(got).astype(np.float64), o.bf16_to_f32(ref).astype(np.float64)
     row_err = np.abs(gf - rf).max(axis=1)
@@ -208,14 +257,16 @@ def test_gemm_fast_kernel_ragged_big_tiles(M, N, K, g):
     assert (col_err <= 1e-2 * np.abs(rf).max()).all()
 
 
+@pytest.mark.parametrize("layout", [f8.NT, f8.NN, f8.TN])
 @pytest.mark.parametrize("M,N,K", [(8192, 4096, 4096), (8192, 1024, 4096), (1024, 4096, 8192)])
-def test_gemm_is_deterministic(M, N, K):
+def test_gemm_is_deterministic(M, N, K, layout):
     """The persistent kernel's LDS pipeline has no run-to-run freedom: repeated launches (one per
     tile configuration of the 8B shapes), interleaved with a launch that disturbs the caches,
     give identical bits."""
     rng = np.random.default_rng(K)
-    Ad = torch.from_numpy(rand_codes(rng, (M, K), o.E4M3)).cuda()
-    Bd = torch.from_numpy(rand_codes(rng, (N, K), o.E4M3)).cuda()
+    sa, sb = shapes_of(layout, M, N, K)
+    Ad = torch.from_numpy(rand_codes(rng, sa, o.E4M3)).cuda()
+    Bd = torch.from_numpy(rand_codes(rng, sb, o.E4M3)).cuda()
     one = torch.ones(1, device="cuda")
     big = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
     outs = []
@@ -223,7 +274,7 @@ def test_gemm_is_deterministic(M, N, K):
         D = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
         if i % 2:
             big.fill_(i)
-        f8.gemm(f8.NT, M, N, K, Ad, o.E4M3, Bd, o.E4M3, one, one, f8.TENSORWISE, D)
+        f8.gemm(layout, M, N, K, Ad, o.E4M3, Bd, o.E4M3, one, one, f8.TENSORWISE, D)
         outs.append(D)
     torch.cuda.synchronize()
     for D in outs[1:]:

@@ -45,7 +45,7 @@ def test_captured_step_replays_like_eager(mode):
 
     def snapshot():
         torch.cuda.synchronize()
-        out = [t.clone() for t in (Y, dX, dW, saved.x.q, saved.w.q_t, saved.dy.q, saved.x.scale, saved.dy.scale)]
+        out = [t.clone() for t in (Y, dX, dW, saved.x.q, saved.w.q, saved.dy.q, saved.x.scale, saved.dy.scale)]
         if mode == "delayed":
             out += [state.hist_x.clone(), state.scale_x.clone(), state.scale_dy.clone()]
         if mode == "chained":

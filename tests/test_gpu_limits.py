@@ -37,7 +37,7 @@ def test_quantise_at_the_size_limits(rows, cols):
     g = torch.Generator("cpu")
     g.manual_seed(rows % 97)
     x = (torch.randn((rows, cols), generator=g) * 2).to(torch.bfloat16)
-    q = f8.QTensor(rows, cols, False)
+    q = f8.QTensor(rows, cols, False, transposed=True)
     ws = f8.new_workspace(rows, cols)
     f8.quantise(x.cuda(), f8.TENSORWISE, f8.E4M3, q, ws)
     torch.cuda.synchronize()

@@ -6,16 +6,18 @@ import torch
 import oracle as o
 from paper_2410_06511_amd import f8
 from paper_2410_06511_amd import workloads as wl
-from helpers import bits, u8, f32, assert_gemm_close, sampled_check
+from helpers import bits, u8, f32, assert_gemm_close, sampled_check, qt_matches
 
 pytestmark = pytest.mark.gpu
 
 
-def run_linear(X, W, dY, rowwise=False, grad_fmt=f8.E4M3):
+def run_linear(X, W, dY, rowwise=False, grad_fmt=f8.E4M3, transposed=False):
+    """transposed: also keep transposed code tensors (tensorwise), which the backward then reads
+    as F8_NT products; without them it reads the codes in place (F8_NN, F8_TN)."""
     M, K = X.shape
     N = W.shape[0]
     desc = f8.linear_desc(M, K, N, rowwise, grad_fmt)
-    saved = f8.Saved(M, K, N, rowwise)
+    saved = f8.Saved(M, K, N, rowwise, transposed=transposed)
     ws = f8.new_workspace(max(M, K, N), max(M, K, N))
     Xd, Wd, dYd = X.cuda(), W.cuda(), dY.cuda()
     Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
@@ -39,15 +41,18 @@ def check_quantised(q, ref, rowwise):
         assert np.array_equal(f32(q.inv_scale_t), ref.inv_scale_c)
         assert np.array_equal(u8(q.q_t), ref.q_c.T)
     else:
-        assert np.array_equal(u8(q.q_t), ref.q.T)
+        assert qt_matches(q, ref.q.T)
 
 
-@pytest.mark.parametrize("rowwise,grad_fmt", [(False, f8.E4M3), (False, f8.E5M2), (True, f8.E4M3), (True, f8.E5M2)])
-def test_single_linear_config(rowwise, grad_fmt):
+@pytest.mark.parametrize("rowwise,grad_fmt,transposed", [(False, f8.E4M3, False), (False, f8.E5M2, False),
+                                                        (False, f8.E4M3, True), (False, f8.E5M2, True),
+                                                        (True, f8.E4M3, False), (True, f8.E5M2, False)])
+def test_single_linear_config(rowwise, grad_fmt, transposed):
     """The small configuration: X [256,512] ~ N(0,1), W [1024,512] ~ N(0,0.02), dY [256,1024]
     ~ N(0,1e-3), seed 0.  Scales and codes bit-exact, Y / dX / dW within tolerance, in full."""
     X, W, dY = wl.make_linear_inputs(wl.WORKLOADS["single"], 0)
-    Y, dX, dW, saved = run_linear(X, W, dY, rowwise, grad_fmt)
+    Y, dX, dW, saved = run_linear(X, W, dY, rowwise, grad_fmt, transposed)
+    assert (saved.x.q_t is not None) == (rowwise or transposed)
     rY, xq, wq = o.linear_fwd(bits(X), bits(W), rowwise)
     rdX, rdW, dyq = o.linear_bwd(bits(dY), xq, wq, rowwise, grad_fmt)
     check_quantised(saved.x, xq, rowwise)
@@ -66,8 +71,8 @@ def test_ragged_linear():
     X = wl.randn_bf16((M, K), 1.0, 0, generator=g)
     W = wl.randn_bf16((N, K), 0.02, 0, generator=g)
     dY = wl.randn_bf16((M, N), 1e-3, 0, generator=g)
-    for rowwise in (False, True):
-        Y, dX, dW, saved = run_linear(X, W, dY, rowwise, f8.E5M2)
+    for rowwise, transposed in ((False, False), (False, True), (True, False)):
+        Y, dX, dW, saved = run_linear(X, W, dY, rowwise, f8.E5M2, transposed)
         rY, xq, wq = o.linear_fwd(bits(X), bits(W), rowwise)
         rdX, rdW, dyq = o.linear_bwd(bits(dY), xq, wq, rowwise, o.E5M2)
         check_quantised(saved.x, xq, rowwise)
@@ -89,8 +94,8 @@ def test_linear_exact_case_bit_for_bit():
     M, K, N = 512, 768, 256
     X, W, dY = draw((M, K)), draw((N, K)), draw((M, N))
     tb = lambda a: torch.from_numpy(a).to(torch.bfloat16)
-    for gf in (f8.E4M3, f8.E5M2):
-        Y, dX, dW, saved = run_linear(tb(X), tb(W), tb(dY), False, gf)
+    for gf, transposed in ((f8.E4M3, False), (f8.E5M2, False), (f8.E4M3, True)):
+        Y, dX, dW, saved = run_linear(tb(X), tb(W), tb(dY), False, gf, transposed)
         assert f32(saved.x.scale)[0] == 128.0 and f32(saved.dy.scale)[0] == o.fmax(gf) / 3.5
         x64, w64, d64 = X.astype(np.float64), W.astype(np.float64), dY.astype(np.float64)
         ex = lambda a: torch.from_numpy(a).to(torch.bfloat16).view(torch.uint16).numpy()
@@ -112,20 +117,24 @@ def _full_size_cases():
                 continue  # w3 repeats w1's shape, wv wk's, wo wq's; the fused block repeats wo and w2
             seen.add((lin.M, lin.K, lin.N, w.variants))
             for gran, gfmt in w.variants:
-                cases.append(pytest.param(key, li, gran == "rowwise", f8.E5M2 if gfmt == "e5m2" else f8.E4M3,
+                cases.append(pytest.param(key, li, gran == "rowwise", f8.E5M2 if gfmt == "e5m2" else f8.E4M3, False,
                                           id=f"{key}-{lin.name}-{gran}-{gfmt}"))
+    # the backward on transposed code copies (F8_NT products) at two 8B shapes
+    for li in (1, 4):
+        cases.append(pytest.param("llama8b", li, False, f8.E4M3, True,
+                                  id=f"llama8b-{wl.WORKLOADS['llama8b'].linears[li].name}-tensorwise-e4m3-transposed-copies"))
     return cases
 
 
-@pytest.mark.parametrize("key,li,rowwise,grad_fmt", _full_size_cases())
-def test_full_size_linear(key, li, rowwise, grad_fmt):
+@pytest.mark.parametrize("key,li,rowwise,grad_fmt,transposed", _full_size_cases())
+def test_full_size_linear(key, li, rowwise, grad_fmt, transposed):
     """Full-size linears of the Llama-shaped workloads, exactly as the benchmark launches them.
     amax / scales / codes compared in full; Y, dX, dW on at least 64 whole rows and 64 whole
     columns each (seeded, plus the lines on both sides of 256-tile boundaries), computed by the
     oracle from the same codes."""
     w = wl.WORKLOADS[key]
     X, W, dY = wl.make_linear_inputs(w, li)
-    Y, dX, dW, saved = run_linear(X, W, dY, rowwise, grad_fmt)
+    Y, dX, dW, saved = run_linear(X, W, dY, rowwise, grad_fmt, transposed)
     g = o.ROWWISE if rowwise else o.TENSORWISE
     rng = np.random.default_rng(li)
     xb, wb, dyb = bits(X), bits(W), bits(dY)
@@ -137,9 +146,10 @@ def test_full_size_linear(key, li, rowwise, grad_fmt):
         assert np.array_equal(u8(q.q), c)
     sampled_check("Y", bits(Y), o.NT, qx, o.E4M3, qw, o.E4M3, isx, isw, g, rng)
     if not rowwise:
-        assert torch.equal(saved.x.q_t, saved.x.q.t().contiguous())
-        assert torch.equal(saved.w.q_t, saved.w.q.t().contiguous())
-        assert torch.equal(saved.dy.q_t, saved.dy.q.t().contiguous())
+        for q in (saved.x, saved.w, saved.dy):
+            assert (q.q_t is not None) == transposed
+            if transposed:
+                assert torch.equal(q.q_t, q.q.t().contiguous())
         sampled_check("dX", bits(dX), o.NN, qdy, grad_fmt, qw, o.E4M3, isdy, isw, g, rng)
         sampled_check("dW", bits(dW), o.TN, qdy, grad_fmt, qx, o.E4M3, isdy, isx, g, rng)
     else:
@@ -174,3 +184,20 @@ def test_forward_with_kept_weight_codes(rowwise):
     assert torch.equal(Y2.view(torch.int16), Yref.view(torch.int16))
     assert torch.equal(kept.x.q, full.x.q) and torch.equal(kept.w.q, w_before)
 
+
+
+@pytest.mark.parametrize("M,K,N,grad_fmt", [(528, 768, 784, f8.E4M3), (4368, 512, 4112, f8.E5M2), (2048, 1024, 4096, f8.E4M3)])
+def test_backward_in_place_equals_backward_on_transposed_copies(M, K, N, grad_fmt):
+    """dX and dW from the codes read in place (F8_NN / F8_TN: the kernel turns the k-major
+    operand) against the same products on transposed code copies (F8_NT): the same k order
+    inside every matrix instruction and the same tiles, so the same bits."""
+    g = torch.Generator("cpu")
+    g.manual_seed(M + K + N)
+    X = wl.randn_bf16((M, K), 1.0, 0, generator=g)
+    W = wl.randn_bf16((N, K), 0.02, 0, generator=g)
+    dY = wl.randn_bf16((M, N), 1e-3, 0, generator=g)
+    Y0, dX0, dW0, s0 = run_linear(X, W, dY, False, grad_fmt, transposed=False)
+    Y1, dX1, dW1, s1 = run_linear(X, W, dY, False, grad_fmt, transposed=True)
+    assert torch.equal(s0.dy.q, s1.dy.q) and torch.equal(s1.dy.q_t, s1.dy.q.t().contiguous())
+    for a, b in ((Y0, Y1), (dX0, dX1), (dW0, dW1)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))

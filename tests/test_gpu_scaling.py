@@ -8,7 +8,7 @@ import torch
 import oracle as o
 from paper_2410_06511_amd import f8
 from paper_2410_06511_amd import workloads as wl
-from helpers import bits, u8, f32, assert_gemm_close, sampled_check
+from helpers import bits, u8, f32, assert_gemm_close, sampled_check, qt_matches, codes_t
 
 pytestmark = pytest.mark.gpu
 
@@ -91,7 +91,7 @@ def _seed(state_gpu, state_ref, X, W, dY, gfmt, ws):
 
 
 def _check_q(q, ref, with_amax=True):
-    assert np.array_equal(u8(q.q), ref.q) and np.array_equal(u8(q.q_t), ref.q.T)
+    assert np.array_equal(u8(q.q), ref.q) and qt_matches(q, ref.q.T)
     assert f32(q.scale)[0] == ref.scale[0] and f32(q.inv_scale)[0] == ref.inv_scale[0]
     if with_amax:
         assert f32(q.amax)[0] == ref.amax[0]
@@ -183,7 +183,7 @@ def test_scaled_dynamic_mode_is_the_dynamic_linear():
             f8.linear_fwd(desc, X.cuda(), W.cuda(), Y, saved, ws)
             f8.linear_bwd(desc, dY.cuda(), saved, dX, dW, ws)
         torch.cuda.synchronize()
-        outs.append((Y, dX, dW, saved.x.q, saved.dy.q_t))
+        outs.append((Y, dX, dW, saved.x.q, codes_t(saved.dy)))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
 
@@ -238,7 +238,7 @@ def test_full_size_delayed_linear():
             codes = o.cast(tb, s, o.TENSORWISE, o.E4M3)
             a = o.amax(tb)
             st_ref.scale[key], _ = o.history_push(st_ref.hist[key], a[0], o.E4M3)
-            assert np.array_equal(u8(q.q), codes) and np.array_equal(u8(q.q_t), codes.T)
+            assert np.array_equal(u8(q.q), codes) and qt_matches(q, codes.T)
             assert f32(q.amax)[0] == a[0] and f32(q.scale)[0] == s[0]
             assert f32(getattr(st, "scale_" + key))[0] == st_ref.scale[key][0]
             qs[key] = (codes, np.float32(1.0) / s)
