@@ -28,8 +28,9 @@
  *   - Arguments are checked on the host before anything is launched; on an
  *     error return nothing has been enqueued or written.  A failed launch
  *     returns F8_ERR_LAUNCH.  No exception or abort crosses this boundary.
- *   - No global mutable state: calls on different streams with disjoint
- *     buffers (including disjoint workspaces) may run concurrently.
+ *   - No global mutable state (f8_linear_fwd_noalloc is the one exception, see
+ *     there): calls on different streams with disjoint buffers (including
+ *     disjoint workspaces) may run concurrently.
  *   - Inputs are expected to be finite.  With a caller-given finite scale,
  *     f8_cast maps NaN to one of the format's NaN codes and +-Inf to the
  *     +-FMAX code; amax over non-finite data is unspecified.
@@ -254,6 +255,28 @@ f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, v
  */
 f8_status f8_linear_fwd_wq(const f8_linear_desc* d, const void* X, void* Y, f8_saved* saved, void* workspace,
                            size_t workspace_bytes, void* stream);
+
+/*
+ * f8_linear_fwd for callers that cannot allocate and have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments minus the workspace, same results bit for
+ * bit.  The partial maxima that f8_linear_fwd keeps in the caller's workspace
+ * live in a built-in device array of F8_NOALLOC_SCRATCH_BYTES (8 MiB) that each
+ * GPU the library runs on holds until the process ends; the call allocates and
+ * frees nothing and calls no allocating routine.  Its first call on a device
+ * looks up the array's address there (hipGetSymbolAddress), so make that call
+ * outside a stream capture.
+ * Limits: tensorwise scaling fits for every shape; rowwise scaling needs
+ * max(f8_workspace_bytes(M, K), f8_workspace_bytes(N, K)) bytes, and a shape
+ * needing more than the array returns F8_ERR_WORKSPACE with nothing launched.
+ * This is the library's only shared state: every call on a GPU uses that GPU's
+ * one array (nothing in it has to be cleared between calls: each quantisation
+ * writes its partial maxima before it reads them), so calls that overlap on one
+ * GPU - on different streams, or from different threads - race; serialise them.
+ */
+#define F8_NOALLOC_SCRATCH_BYTES (8u << 20)
+f8_status f8_linear_fwd_noalloc(const f8_linear_desc* d, const void* X, const void* W, void* Y,
+                                f8_saved* saved, void* stream);
 
 /*
  * Backward: quantise dY [M,N] into saved->dy, then

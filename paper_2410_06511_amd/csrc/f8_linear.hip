@@ -12,6 +12,8 @@
 // then runs as F8_NT products on them.  Rowwise scaling needs two differently scaled code sets
 // per tensor anyway (per row for one product, per column for the other); the second is kept
 // transposed in q_t.
+#include <mutex>
+
 #include "f8_host.hpp"
 
 namespace f8 {
@@ -100,7 +102,7 @@ static f8_status check_state(const f8_scaling_state* st, bool fwd)
 
 // Argument checks shared by the forward entry points (every check before any launch).
 static f8_status check_fwd(const f8_linear_desc* d, bool tensorwise_only, const void* X, const void* W, const void* Y,
-                           const f8_saved* saved, const void* ws, size_t ws_bytes)
+                           const f8_saved* saved, const void* ws, size_t ws_bytes, bool check_workspace = true)
 {
     f8_status s = check_desc(d);
     if (s != F8_OK) return s;
@@ -110,7 +112,7 @@ static f8_status check_fwd(const f8_linear_desc* d, bool tensorwise_only, const 
     const bool rw = d->granularity == F8_ROWWISE;
     if ((s = check_q(&saved->x, rw)) != F8_OK) return s;
     if ((s = check_q(&saved->w, rw)) != F8_OK) return s;
-    if (!ws || ws_bytes < linear_workspace(d)) return F8_ERR_WORKSPACE;
+    if (check_workspace && (!ws || ws_bytes < linear_workspace(d))) return F8_ERR_WORKSPACE;
     return F8_OK;
 }
 
@@ -162,11 +164,65 @@ static f8_status gemms_bwd(const f8_linear_desc* d, const f8_saved* sv, void* dX
                 d->granularity, dW, K, nullptr, st);
 }
 
+// ---- the forward that allocates nothing and takes no workspace ---------------------------
+// Its partial maxima live in a file-scope device array instead of a caller's workspace.  In
+// host code the array's name is only a handle for hipGetSymbolAddress; kernels get the device
+// address that call returns, one per device (every GPU holds its own copy of the array).
+constexpr size_t kScratchBytes = F8_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void* scratch_ptr[kMaxDevices];  // device address of `scratch` per device; null = not asked yet
+
+static f8_status scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return F8_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();  // do not leave the error for a later, unrelated call
+            return F8_ERR_LAUNCH;
+        }
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return F8_OK;
+}
+
+// What the forward's quantisations really need: the tensorwise partials fit the minimum; rowwise
+// needs the per-column and per-row partials of its larger tensor.
+static size_t fwd_scratch_need(const f8_linear_desc* d)
+{
+    if (d->granularity != F8_ROWWISE) return kMinWorkspaceBytes;
+    const size_t x = workspace_bytes(d->M, d->K), w = workspace_bytes(d->N, d->K);
+    return x > w ? x : w;
+}
+
 }  // namespace f8
 
 using namespace f8;
 
 extern "C" {
+
+f8_status f8_linear_fwd_noalloc(const f8_linear_desc* d, const void* X, const void* W, void* Y, f8_saved* saved,
+                                void* stream)
+{
+    f8_status s = check_fwd(d, false, X, W, Y, saved, nullptr, 0, false);
+    if (s != F8_OK) return s;
+    if (fwd_scratch_need(d) > kScratchBytes) return F8_ERR_WORKSPACE;  // beyond the built-in scratch
+    void* ws = nullptr;
+    if ((s = scratch_of_current_device(&ws)) != F8_OK) return s;
+    hipStream_t st = (hipStream_t)stream;
+    const bool rw = d->granularity == F8_ROWWISE;
+    // the partial maxima are written before they are read within each quantisation: nothing in
+    // the scratch has to start at zero
+    if ((s = quantise_both(X, d->M, d->K, rw, F8_E4M3, &saved->x, ws, st)) != F8_OK) return s;
+    if ((s = quantise_both(W, d->N, d->K, rw, F8_E4M3, &saved->w, ws, st)) != F8_OK) return s;
+    return gemm_fwd(d, saved, Y, nullptr, st);
+}
 
 const char* f8_status_string(f8_status s)
 {
@@ -176,7 +232,7 @@ const char* f8_status_string(f8_status s)
         case F8_ERR_SHAPE: return "bad shape: sizes and leading dimensions must be non-negative multiples of 16, ld >= cols";
         case F8_ERR_ALIGN: return "a data pointer is not 16-byte aligned";
         case F8_ERR_ENUM: return "an enum argument is out of range";
-        case F8_ERR_WORKSPACE: return "workspace is NULL or too small (see f8_workspace_bytes)";
+        case F8_ERR_WORKSPACE: return "workspace is NULL or too small (see f8_workspace_bytes), or the shape is beyond the built-in scratch of f8_linear_fwd_noalloc";
         case F8_ERR_LAUNCH: return "kernel launch failed";
     }
     return "unknown status";

@@ -29,7 +29,7 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq",
            "f8_silu_mul_bwd_quantise_delayed", "f8_linear_bwd_dyq",
            "f8_rope", "f8_transpose_bf16", "f8_add", "f8_rmsnorm_bwd", "f8_sdpa_fwd", "f8_sdpa_bwd", "f8_sdpa_bwd_workspace_bytes",
-           "f8_rmsnorm_bwd_add", "f8_linear_fwd_wq"]
+           "f8_rmsnorm_bwd_add", "f8_linear_fwd_wq", "f8_linear_fwd_noalloc"]
 
 
 class F8Error(RuntimeError):
@@ -101,6 +101,7 @@ def lib():
         l.f8_add.argtypes = [_p, _p, _i64, _p, _p]
         l.f8_rmsnorm_bwd.argtypes = [_p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_linear_fwd_wq.argtypes = [C.POINTER(LinearDesc), _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
+        l.f8_linear_fwd_noalloc.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, C.POINTER(SavedStruct), _p]
         l.f8_rmsnorm_bwd_add.argtypes = [_p, _p, _p, _p, _p, _i64, _i64, _p, _p, _p, _p, C.c_size_t, _p]
         l.f8_sdpa_fwd.argtypes = [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _p, _p, _p]
         l.f8_sdpa_bwd.argtypes = [_p, _i64, _p, _p, _i64, _p, _p, _i64, _p, _i64, _p, _i64, _p, _p, _i64, _i64, _i64, _i64,
@@ -232,6 +233,11 @@ def linear_fwd(desc, X, W, Y, saved, workspace, stream=None):
     wp, wb = _ws(workspace)
     _check(lib().f8_linear_fwd(C.byref(desc), _ptr(X), _ptr(W), _ptr(Y), C.byref(saved.struct()), wp, wb,
                                _stream(stream)))
+
+
+def linear_fwd_noalloc(desc, X, W, Y, saved, stream=None):
+    """linear_fwd on the library's built-in scratch: no workspace argument, nothing allocated."""
+    _check(lib().f8_linear_fwd_noalloc(C.byref(desc), _ptr(X), _ptr(W), _ptr(Y), C.byref(saved.struct()), _stream(stream)))
 
 
 def linear_fwd_wq(desc, X, Y, saved, workspace, stream=None):
