@@ -1,12 +1,15 @@
 #!/usr/bin/env python3
 """Benchmark of the Float8 linear hot path on one MI355X.
 
-A step = forward + backward of the seven Float8 linears of the Llama-3.1-8B
-workload at M = 8192 tokens (casts included), every tensor already resident in
-HBM.  Prints ONE JSON line: whole-step TFLOP/s (6*M*K*N per linear), the
-roofline of the dominant kernel (the fp8 GEMM, timed per launch with HIP
-events on the launch stream), the amax+cast bandwidth, and the CPU oracle
-timed on a bounded sample of the same workload.
+A step = forward + backward of the seven Float8 linears of a Llama-3.1-8B
+transformer block at M = 16384 tokens (the largest single-GPU configuration;
+casts included), every tensor already resident in HBM.  Prints ONE JSON line:
+whole-step TFLOP/s (6*M*K*N per linear), the roofline of the dominant kernel
+(the fp8 GEMM, timed per launch with HIP events on the launch stream), the
+amax+cast bandwidth, the shader clock of the timed steps, ceilings measured in
+the same process (matrix pipes alone, device copy and read), one record per
+other configuration (8B at M = 8192, 70B and 405B slices in their variants) in
+`configs`, and the CPU oracle timed on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload KEY]
 """
@@ -30,7 +33,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="llama8b")
+    ap.add_argument("--workload", default=None,
+                    help="default: llama8b_block (the seven 8B linears at M = 16384, the largest configuration) as the "
+                         "headline, plus one record per other configuration in `configs`")
+    ap.add_argument("--no-configs", action="store_true", help="default run: skip the other configurations")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the measured ceilings (MFMA-only loop, copy, read)")
     ap.add_argument("--variant", default=None, help="granularity:gradfmt, e.g. tensorwise:e4m3")
     ap.add_argument("--scaling", default="dynamic", choices=["dynamic", "delayed", "static"],
                     help="per-tensor scaling strategy (delayed/static: tensorwise only, single-pass casts)")
@@ -60,12 +67,11 @@ def parse():
 class LinearState:
     """Device tensors of one linear of the workload."""
 
-    def __init__(self, f8, wl, w, li, rowwise, grad_fmt, scaling="dynamic", ws=None, transposed=False):
+    def __init__(self, f8, w, li, inputs, rowwise, grad_fmt, scaling="dynamic", ws=None, transposed=False):
         import torch
         lin = w.linears[li]
-        X, W, dY = wl.make_linear_inputs(w, li)
         self.lin = lin
-        self.X, self.W, self.dY = X.cuda(), W.cuda(), dY.cuda()
+        self.X, self.W, self.dY = inputs
         M, K, N = lin.M, lin.K, lin.N
         bf = dict(dtype=torch.bfloat16, device="cuda")
         self.Y = torch.empty((M, N), **bf)
@@ -84,61 +90,14 @@ class LinearState:
                 f8.amax_history_push(getattr(self.state, "hist_" + key), a, fmt, getattr(self.state, "scale_" + key))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    from paper_2410_06511_amd import f8, workloads as wl
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    f8.lib()  # fail loudly if the HIP library is missing
-    torch.cuda.set_device(0)
-
-    if args.copy_calibration:
-        # 1 GiB read + 1 GiB written per launch, by a plain elementwise copy kernel
-        n = 1 << 29
-        x = torch.ones(n, dtype=torch.bfloat16, device="cuda")
-        y = torch.empty_like(x)
-        for _ in range(4):
-            y.copy_(x)
-        torch.cuda.synchronize()
-        print(json.dumps({"copy_calibration": {"bytes_read_per_launch": 2 * n, "bytes_written_per_launch": 2 * n,
-                                                "launches": 4}}))
-        return
-
-    w = wl.WORKLOADS[args.workload]
-    if w.key == "llama8b_ffn":
-        return ffn_main(args, w)
-    if w.key == "llama8b_layer":
-        return layer_main(args, w)
-    gran, gfmt = (args.variant.split(":") if args.variant else w.variants[0])
-    rowwise = gran == "rowwise"
-    grad_fmt = f8.E5M2 if gfmt == "e5m2" else f8.E4M3
-
-    if args.scaling != "dynamic" and rowwise:
-        print("bench.py: delayed and static scaling are per-tensor strategies; use a tensorwise variant",
-              file=sys.stderr)
-        sys.exit(2)
-    dmax = max(max(l.M, l.K, l.N) for l in w.linears)
-    ws = f8.new_workspace(dmax, dmax)
-    states = [LinearState(f8, wl, w, li, rowwise, grad_fmt, args.scaling, ws, args.transposed_copies)
-              for li in range(len(w.linears))]
-    stream = torch.cuda.current_stream()   # the per-kernel legs below; the step uses the current stream
-
-    chain_pairs = []
+def make_step(f8, torch, args, states, ws, rowwise):
+    """The timed step of a linear workload: forward of every linear in model order, backward in reverse."""
     if args.chain:
         names = [s.lin.name for s in states]
         if args.scaling != "dynamic" or rowwise or names != ["wq", "wk", "wv", "wo", "w1", "w3", "w2"]:
             print("bench.py: --chain needs an 8B-shaped workload with dynamic tensorwise scaling", file=sys.stderr)
             sys.exit(2)
         chain_pairs = [(0, 3), (4, 6)]   # producer -> consumer: wq -> wo, w1 -> w2
-    if chain_pairs:
         prod = {p: c for p, c in chain_pairs}
         cons = {c: p for p, c in chain_pairs}
         amax_y = {p: torch.empty(1, device="cuda") for p in prod}      # max |Y| of the producer
@@ -182,6 +141,24 @@ def main():
                 f8.linear_fwd_scaled(s.desc, s.state, s.X, s.W, s.Y, s.saved, ws)
             for s in reversed(states):
                 f8.linear_bwd_scaled(s.desc, s.state, s.dY, s.saved, s.dX, s.dW, ws)
+    return step
+
+
+def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, inputs=None):
+    """Times `steps` steps of one linear workload in one variant and then its per-call legs.
+    Returns (record, inputs): the record holds the step time, the whole-step rate, the GEMM and the
+    cast legs; the device inputs are handed back so that another variant of the same workload can
+    reuse them."""
+    rowwise = gran == "rowwise"
+    grad_fmt = f8.E5M2 if gfmt == "e5m2" else f8.E4M3
+    dmax = max(max(l.M, l.K, l.N) for l in w.linears)
+    ws = f8.new_workspace(dmax, dmax)
+    if inputs is None:
+        inputs = [tuple(t.cuda() for t in wl.make_linear_inputs(w, li)) for li in range(len(w.linears))]
+    states = [LinearState(f8, w, li, inputs[li], rowwise, grad_fmt, args.scaling, ws, args.transposed_copies)
+              for li in range(len(w.linears))]
+    stream = torch.cuda.current_stream()   # the step and the per-call legs run on the current stream
+    step = make_step(f8, torch, args, states, ws, rowwise)
 
     run_step = step
     if args.graph:
@@ -193,43 +170,45 @@ def main():
         with torch.cuda.graph(graph, stream=torch.cuda.Stream()):
             step()
         run_step = graph.replay
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         run_step()
+    clk = torch.zeros((2, 32), dtype=torch.int64, device="cuda")
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    f8.probe_clock(clk[0], stream)
+    marks[0].record(stream)
+    for i in range(steps):
         run_step()
+        marks[i + 1].record(stream)
+    f8.probe_clock(clk[1], stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    ms_median = per_step[len(per_step) // 2]
+    c = clk.cpu().tolist()
+    # shader-clock cycles over 100 MHz ticks between the two sampling kernels that bracket the steps
+    clock_ghz = f8.clock_ghz_between(c[0], c[1]) or 0.0
     flops_step = sum(s.lin.flops for s in states)
     tflops = flops_step / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-kernel legs, HIP events on the launch stream --------------------------------
+    # ---- per-call legs, HIP events on the launch stream ----------------------------------
     # An instrumented pass issues the step's own sequence of library calls (every tensor's
     # amax+cast and every GEMM, forward in model order, backward in reverse, through the same
     # C entry points the linear composes), each call between two events.  Same kernels, same
     # order and therefore the same cache state as in the timed steps.
-    def timed(fn, reps):
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-        for a, b in ev:
-            a.record(stream)
-            fn()
-            b.record(stream)
-        torch.cuda.synchronize()
-        return sum(a.elapsed_time(b) for a, b in ev) / reps  # ms
-
     g = f8.ROWWISE if rowwise else f8.TENSORWISE
-    reps = max(3, min(args.steps, 10))
+    reps = max(3, min(steps, 10))
 
     def cast_op(t, q, fmt):
-        if args.scaling == "dynamic":   # the linear's own quantisation of one tensor, both orientations
+        if args.scaling == "dynamic":   # the linear's own quantisation of one tensor
             return lambda: f8.quantise(t, g, fmt, q, ws, stream)
         if args.scaling == "delayed":
             return lambda: f8.cast_amax(t, q.scale, fmt, q.amax, q.q, q.q_t, ws, stream)
         return lambda: f8.cast(t, q.scale, f8.TENSORWISE, fmt, q.q, q.q_t, stream)
 
-    ops = []  # (kind, linear index, call, flop or elements)
+    ops = []  # (kind, linear index, call, flop or elements, name)
     for li, s in enumerate(states):
         M, K, N = s.lin.M, s.lin.K, s.lin.N
         sv = s.saved
@@ -296,13 +275,13 @@ def main():
 
     gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "gemm_nt_kernel (fp8 MFMA 32x32x64)",
+        "kernel": "gemm_tile_kernel (fp8 MFMA 32x32x64; F8_NT forward, F8_NN and F8_TN backward)",
         "bound": "mfma",
         "achieved": round(gemm_tflops, 1),
         "peak": PEAK_FP8_TFLOPS,
         "unit": "TFLOP/s",
         "frac": round(gemm_tflops / PEAK_FP8_TFLOPS, 4),
-        "traffic": committed_traffic(),
+        "traffic": None,
         "launches_per_step": gemm_launches,
         "tflops_by_product": by_product,
         "avg_launch_ms": round(gemm_ms / gemm_launches, 4),
@@ -317,10 +296,144 @@ def main():
         # re-reads x (2 B) and writes the two differently scaled code sets (1 + 1 B): 6 B/elem.
         bpe = (6 if rowwise else 5) if args.scaling == "dynamic" else 3
         gbs = bpe * cast_elems / (cast_ms * 1e-3) / 1e9
+        moved = bpe + (1 if (args.transposed_copies and not rowwise) else 0)
         cast = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_elem": bpe,
-                "moved_gbs": round((bpe + (1 if (args.transposed_copies and not rowwise) else 0)) * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
+                "moved_gbs": round(moved * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
                 "ms_per_step": round(cast_ms, 4)}
+    rec = {"workload": w.key, "ms_per_step": ms_per_step, "ms_per_step_median_of_events": ms_median,
+           "tflops": tflops, "flops_step": flops_step, "shader_clock_ghz": clock_ghz,
+           "roofline": roofline, "cast_roofline": cast, "per_linear": per_linear,
+           "rowwise": rowwise, "grad_fmt": grad_fmt, "gran": gran, "gfmt": gfmt, "states": states, "reps": reps}
+    return rec, inputs
+
+
+def brief(rec):
+    """One configuration's line of the `configs` object."""
+    out = {"ms_per_step": round(rec["ms_per_step"], 4), "tflops": round(rec["tflops"], 1),
+           "frac_of_fp8_peak": round(rec["tflops"] / PEAK_FP8_TFLOPS, 4),
+           "gemm_kernels_tflops": rec["roofline"]["achieved"], "gemm_frac": rec["roofline"]["frac"],
+           "shader_clock_ghz": round(rec["shader_clock_ghz"], 3),
+           "variant": f"{rec['gran']}:{rec['gfmt']}"}
+    if rec["cast_roofline"]:
+        c = rec["cast_roofline"]
+        out.update({"cast_gbs": c["achieved"], "cast_frac_of_hbm_peak": c["frac"], "cast_bytes_per_elem": c["bytes_per_elem"],
+                    "cast_ms": c["ms_per_step"]})
+    out["gemm_tflops_by_linear"] = {l["name"]: l["gemm_tflops"] for l in rec["per_linear"]}
+    return out
+
+
+# (config number of the task statement, workload key, variants) of the `configs` object of the default run
+ALL_CONFIGS = [(2, "llama8b", [("tensorwise", "e4m3")]),
+               (3, "llama70b_tp8", [("tensorwise", "e4m3"), ("tensorwise", "e5m2")]),
+               (4, "llama405b_tp8", [("tensorwise", "e4m3"), ("rowwise", "e4m3")])]
+HEADLINE = "llama8b_block"   # config 5, the largest single-GPU configuration (21.4 TFLOP per step)
+
+
+def measure_ceilings(f8, torch, codes):
+    """What the chip delivers with nothing else in the way, measured in this process: the fp8 matrix
+    pipes alone (constant operands, and the codes of a quantised tensor of this workload, whose
+    switching activity is the GEMM's), a 1 GiB device copy and a 1 GiB device read."""
+    stream = torch.cuda.current_stream()
+    out = {}
+
+    def time_ms(fn, reps):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    ticks = torch.zeros(2, dtype=torch.int64, device="cuda")
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    n = 1 << 24
+    const = torch.full((n,), 0x38, dtype=torch.uint8, device="cuda")          # 1.0 everywhere
+    flat = codes.reshape(-1)
+    real = flat[: 1 << (flat.numel().bit_length() - 1)][:n].contiguous()       # a power of two of real codes
+    iters = 4000
+    for name, buf in (("constant_operands", const), ("workload_codes", real)):
+        fl = [0]
+
+        def fn(buf=buf):
+            fl[0] = f8.probe_mfma(buf, iters, ticks, sink, stream)
+        ms = time_ms(fn, 3)
+        t = ticks.cpu().tolist()
+        out["mfma_only_" + name] = {"tflops": round(fl[0] / (ms * 1e-3) / 1e12, 1),
+                                    "frac_of_nominal": round(fl[0] / (ms * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 4),
+                                    "shader_clock_ghz": round(0.1 * t[0] / max(1, t[1]), 3),
+                                    "cycles_per_mfma": round(t[0] / (iters * 16), 2)}
+    gib = 1 << 30
+    src = torch.empty(gib, dtype=torch.uint8, device="cuda")
+    src.random_(0, 256)
+    dst = torch.empty_like(src)
+    sink32 = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ms = time_ms(lambda: f8.probe_copy(src, dst, stream), 5)
+    out["copy_1GiB"] = {"gbs_read_plus_write": round(2 * gib / (ms * 1e-3) / 1e9, 1), "frac_of_nominal": round(2 * gib / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    ms = time_ms(lambda: f8.probe_read(src, sink32, stream), 5)
+    out["read_1GiB"] = {"gbs": round(gib / (ms * 1e-3) / 1e9, 1), "frac_of_nominal": round(gib / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
+    out["what"] = ("f8_probe_mfma: one wave per SIMD, 16 independent 32x32x64 fp8 MFMAs per iteration, operands in registers, "
+                   "no LDS or memory traffic; f8_probe_copy / f8_probe_read: grid-stride 16-byte copy / read of 1 GiB")
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_06511_amd import f8, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    f8.lib()  # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        # 1 GiB read + 1 GiB written per launch, by the plain copy kernel of known size
+        n = 1 << 30
+        x = torch.ones(n, dtype=torch.uint8, device="cuda")
+        y = torch.empty_like(x)
+        for _ in range(4):
+            f8.probe_copy(x, y)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"kernel": "probe_copy_kernel", "bytes_read_per_launch": n,
+                                                "bytes_written_per_launch": n, "launches": 4}}))
+        return
+
+    default_run = args.workload is None
+    w = wl.WORKLOADS[args.workload or HEADLINE]
+    if w.key == "llama8b_ffn":
+        return ffn_main(args, w)
+    if w.key == "llama8b_layer":
+        return layer_main(args, w)
+    gran, gfmt = (args.variant.split(":") if args.variant else w.variants[0])
+    if args.scaling != "dynamic" and gran == "rowwise":
+        print("bench.py: delayed and static scaling are per-tensor strategies; use a tensorwise variant",
+              file=sys.stderr)
+        sys.exit(2)
+
+    rec, inputs = run_linear_workload(f8, wl, torch, args, w, gran, gfmt, args.steps, args.warmup)
+    states, rowwise, grad_fmt = rec["states"], rec["rowwise"], rec["grad_fmt"]
+    tflops, ms_per_step, flops_step = rec["tflops"], rec["ms_per_step"], rec["flops_step"]
+    roofline = rec["roofline"]
+    roofline["traffic"], roofline["traffic_source"] = committed_traffic()
+    stream = torch.cuda.current_stream()
+
+    def timed(fn, reps):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in ev:
+            a.record(stream)
+            fn()
+            b.record(stream)
+        torch.cuda.synchronize()
+        return sum(a.elapsed_time(b) for a, b in ev) / reps  # ms
 
     out = {
         "metric": "Float8 linear fwd+bwd TFLOP/s (% FP8 MFMA peak) + amax/cast HBM GB/s",
@@ -340,13 +453,45 @@ def main():
                    "weights_recast_every_step": not args.keep_weights, "transposed_code_copies": bool(args.transposed_copies or rowwise),
                    "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
+        "ms_per_step_median_of_events": round(rec["ms_per_step_median_of_events"], 4),
+        "shader_clock_ghz_during_timed_steps": round(rec["shader_clock_ghz"], 3),
         "roofline": roofline,
-        "cast_roofline": cast,
-        "per_linear": per_linear,
+        "cast_roofline": rec["cast_roofline"],
+        "per_linear": rec["per_linear"],
     }
 
+    if not args.no_ceilings:
+        ceil = measure_ceilings(f8, torch, states[0].saved.x.q)
+        out["ceilings"] = ceil
+        m = ceil["mfma_only_workload_codes"]["tflops"]
+        roofline["frac_of_measured_mfma_only_ceiling"] = round(roofline["achieved"] / m, 4)
+        out["frac_of_measured_mfma_only_ceiling"] = round(tflops / m, 4)
+        if rec["cast_roofline"]:
+            rec["cast_roofline"]["frac_of_measured_copy_rate"] = round(
+                rec["cast_roofline"]["achieved"] / ceil["copy_1GiB"]["gbs_read_plus_write"], 4)
+        # the matrix pipes' rate at the clock the timed steps ran at
+        at_clock = 256 * 4 * 2048 * rec["shader_clock_ghz"] * 1e9 / 1e12
+        out["fp8_peak_at_measured_clock_tflops"] = round(at_clock, 1)
+        roofline["frac_of_peak_at_measured_clock"] = round(roofline["achieved"] / at_clock, 4)
     if not args.no_bf16_context:
-        out["bf16_matmul_context"] = bf16_context(states, timed, reps, flops_step)
+        out["bf16_matmul_context"] = bf16_context(states, timed, rec["reps"], flops_step)
+        if not rowwise and grad_fmt == f8.E4M3:
+            out["fp8_library_gemm_context"] = fp8_library_context(states, timed, rec["reps"], flops_step)
+    if default_run and not args.no_configs:
+        # every other configuration of the benchmark spec, each in the variants it names: fewer
+        # steps, the same measurement
+        configs = {f"config5 {w.key} {gran}:{gfmt}": brief(rec)}
+        del rec, states, inputs
+        torch.cuda.empty_cache()
+        for num, key, variants in ALL_CONFIGS:
+            cw, cin = wl.WORKLOADS[key], None
+            for cg, cf in variants:
+                crec, cin = run_linear_workload(f8, wl, torch, args, cw, cg, cf, max(3, min(args.steps, 8)), 2, cin)
+                configs[f"config{num} {key} {cg}:{cf}"] = brief(crec)
+                del crec
+            del cin
+            torch.cuda.empty_cache()
+        out["configs"] = configs
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_rows, rowwise, grad_fmt, args.scaling)
     print(json.dumps(out))
@@ -607,18 +752,50 @@ def bf16_context(states, timed, reps, flops_step):
             "what": f"torch.matmul bf16 (hipBLASLt), the same {3 * len(states)} products, no casts"}
 
 
+TRAFFIC_SUMMARY = "gemm_cast_llama8b_block_hbm_traffic.md"
+
+
+def fp8_library_context(states, timed, reps, flops_step):
+    """Context, not part of the path: the vendor library's fp8 GEMM (torch._scaled_mm, which goes
+    to hipBLASLt) on the same products, fed the codes this library produced, with the operands
+    that call wants transposed copied beforehand (untimed).  E4M3 tensorwise only."""
+    import torch
+    try:
+        total = 0.0
+        for s in states:
+            sv = s.saved
+            x8, w8, dy8 = (t.view(torch.float8_e4m3fn) for t in (sv.x.q, sv.w.q, sv.dy.q))
+            w8t, dy8t, x8t = w8.t().contiguous(), dy8.t().contiguous(), x8.t().contiguous()
+            isx, isw, isdy = sv.x.inv_scale.reshape(()), sv.w.inv_scale.reshape(()), sv.dy.inv_scale.reshape(())
+            fns = [lambda: torch._scaled_mm(x8, w8.t(), isx, isw, out_dtype=torch.bfloat16),          # Y  = X W^T
+                   lambda: torch._scaled_mm(dy8, w8t.t(), isdy, isw, out_dtype=torch.bfloat16),       # dX = dY W
+                   lambda: torch._scaled_mm(dy8t, x8t.t(), isdy, isx, out_dtype=torch.bfloat16)]      # dW = dY^T X
+            for fn in fns:
+                fn()
+                total += timed(fn, reps)
+        return {"ms_per_step": round(total, 4), "tflops": round(flops_step / (total * 1e-3) / 1e12, 1),
+                "what": f"torch._scaled_mm fp8 e4m3 (hipBLASLt), the same {3 * len(states)} products on this library's codes, "
+                        "operands pre-transposed as that call wants them, no casts"}
+    except Exception as exc:   # context only
+        return {"error": str(exc)[:300]}
+
+
 def committed_traffic():
-    """Bytes per GEMM launch between L2 and the fabric / HBM, from the two rocprofv3 --pmc runs
-    (FETCH_SIZE, WRITE_SIZE, scaled by a copy of known size) summarised under profiles/; None if
-    that summary is absent.  It is measured on this workload, not in this process."""
-    path = os.path.join(ROOT, "profiles", "gemm_cast_llama8b_hbm_traffic.md")
+    """(bytes per GEMM launch between L2 and the fabric / HBM, where the figure comes from): taken
+    from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, scaled by a copy of known size)
+    summarised under profiles/, which also names the source revision it was measured at; (None,
+    reason) if that summary is absent.  Measured on the default workload, not in this process."""
+    path = os.path.join(ROOT, "profiles", TRAFFIC_SUMMARY)
+    val, rev = None, "unknown revision"
     try:
         for ln in open(path):
             if ln.startswith("traffic_bytes_per_gemm_launch:"):
-                return int(ln.split(":")[1])
+                val = int(ln.split(":")[1])
+            if ln.startswith("measured_at_revision:"):
+                rev = ln.split(":", 1)[1].strip()
     except OSError:
-        pass
-    return None
+        return None, "profiles/" + TRAFFIC_SUMMARY + " is absent"
+    return val, f"profiles/{TRAFFIC_SUMMARY}, kernels as of {rev}"
 
 
 def cpu_baseline(w, rows, rowwise, grad_fmt, scaling="dynamic"):

@@ -530,6 +530,38 @@ f8_status f8_linear_fwd_xq(const f8_linear_desc* d, const f8_scaling_state* stat
                            void* Y, f8_saved* saved, void* workspace, size_t workspace_bytes,
                            void* stream);
 
+/*
+ * Measuring helpers (not part of the linear layer): what the chip delivers
+ * with nothing else in the way, so that a benchmark can quote the kernels
+ * above against measured ceilings beside the nominal peaks.
+ *
+ * f8_probe_mfma: one wavefront per SIMD on every compute unit issues
+ *   iters x 16 fp8 matrix instructions (32x32x64, E4M3 x E4M3) on sixteen
+ *   accumulators, with four A and four B register fragments per wavefront read
+ *   once from `operands` (operand_bytes: a power of two, 64 KiB .. 1 GiB,
+ *   32-byte aligned; fill it with the codes whose switching activity is to be
+ *   measured: constant, or a quantised tensor): the GEMM kernel's matrix work
+ *   with no LDS and no memory traffic.  flops_out (host, nullable) receives the
+ *   floating-point operations of the launch; ticks (device, nullable, 2 words):
+ *   shader-clock cycles and 100 MHz ticks that workgroup 0 spent in its loop;
+ *   sink: one float of device memory that is (practically) never written.
+ * f8_probe_copy / f8_probe_read: grid-stride 16-byte copy of `bytes` bytes
+ *   (read + write) / read of them; bytes a multiple of 16.  The copy is also
+ *   the kernel of known size against which the HBM byte counters are scaled.
+ * f8_probe_clock: a few one-thread workgroups each read the shader-clock cycle
+ *   counter and the 100 MHz counter and file them under the accelerator die
+ *   (XCD) they run on: out[4 d + 0] = 1 (slot filled; the caller zeroes out
+ *   first), out[4 d + 1] = cycles, out[4 d + 2] = 100 MHz ticks, for die d in
+ *   0..7 (out: 32 words of device memory).  The dies' cycle counters need not
+ *   agree, so compare two calls (before and after a region on one stream) die
+ *   by die: mean shader clock = 0.1 GHz x d(cycles) / d(ticks).
+ */
+f8_status f8_probe_mfma(const uint8_t* operands, int64_t operand_bytes, int iters, uint64_t* ticks,
+                        float* sink, int64_t* flops_out, void* stream);
+f8_status f8_probe_copy(const void* src, void* dst, int64_t bytes, void* stream);
+f8_status f8_probe_read(const void* src, int64_t bytes, uint32_t* sink, void* stream);
+f8_status f8_probe_clock(uint64_t* out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

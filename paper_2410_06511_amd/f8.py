@@ -29,7 +29,8 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq",
            "f8_silu_mul_bwd_quantise_delayed", "f8_linear_bwd_dyq",
            "f8_rope", "f8_transpose_bf16", "f8_add", "f8_rmsnorm_bwd", "f8_sdpa_fwd", "f8_sdpa_bwd", "f8_sdpa_bwd_workspace_bytes",
-           "f8_rmsnorm_bwd_add", "f8_linear_fwd_wq", "f8_linear_fwd_noalloc"]
+           "f8_rmsnorm_bwd_add", "f8_linear_fwd_wq", "f8_linear_fwd_noalloc",
+           "f8_probe_mfma", "f8_probe_copy", "f8_probe_read", "f8_probe_clock"]
 
 
 class F8Error(RuntimeError):
@@ -102,6 +103,10 @@ def lib():
         l.f8_rmsnorm_bwd.argtypes = [_p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_linear_fwd_wq.argtypes = [C.POINTER(LinearDesc), _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         l.f8_linear_fwd_noalloc.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, C.POINTER(SavedStruct), _p]
+        l.f8_probe_mfma.argtypes = [_p, _i64, _int, _p, _p, C.POINTER(_i64), _p]
+        l.f8_probe_copy.argtypes = [_p, _p, _i64, _p]
+        l.f8_probe_read.argtypes = [_p, _i64, _p, _p]
+        l.f8_probe_clock.argtypes = [_p, _p]
         l.f8_rmsnorm_bwd_add.argtypes = [_p, _p, _p, _p, _p, _i64, _i64, _p, _p, _p, _p, C.c_size_t, _p]
         l.f8_sdpa_fwd.argtypes = [_p, _i64, _p, _i64, _p, _i64, _i64, _i64, _i64, _i64, _p, _i64, _p, _p, _p]
         l.f8_sdpa_bwd.argtypes = [_p, _i64, _p, _p, _i64, _p, _p, _i64, _p, _i64, _p, _i64, _p, _p, _i64, _i64, _i64, _i64,
@@ -403,3 +408,39 @@ def sdpa_bwd(q, qt, k, kt, v, o, do, dot, lse, B, S, Hq, Hkv, hd, dq, dk, dv, de
                              _ptr(o), o.stride(0), _ptr(do), do.stride(0), _ptr(dot), _ptr(lse), B, S, Hq, Hkv, hd,
                              _ptr(dq), dq.stride(0), _ptr(dk), dk.stride(0), _ptr(dv), dv.stride(0), _ptr(delta),
                              _ptr(amax_dv_inout), wp, wb, _stream(stream)))
+
+
+# ---- measuring helpers ---------------------------------------------------------------
+
+def probe_mfma(operands, iters, ticks=None, sink=None, stream=None):
+    """Launches the matrix-pipe-only loop; returns the floating-point operations of the launch."""
+    if sink is None:
+        sink = torch.zeros(1, dtype=torch.float32, device=operands.device)
+    fl = _i64(0)
+    _check(lib().f8_probe_mfma(_ptr(operands), operands.numel() * operands.element_size(), int(iters), _ptr(ticks),
+                               _ptr(sink), C.byref(fl), _stream(stream)))
+    return fl.value
+
+
+def probe_copy(src, dst, stream=None):
+    _check(lib().f8_probe_copy(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _stream(stream)))
+
+
+def probe_read(src, sink, stream=None):
+    _check(lib().f8_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
+
+
+def probe_clock(out, stream=None):
+    """out: 32 x int64 on the device, zeroed: per die d, out[4d] = 1, out[4d+1] = shader-clock cycles,
+    out[4d+2] = 100 MHz ticks."""
+    _check(lib().f8_probe_clock(_ptr(out), _stream(stream)))
+
+
+def clock_ghz_between(before, after):
+    """Mean shader clock between two probe_clock samples (host lists of 32 ints), averaged over
+    the dies that filled their slot in both; None if no die did."""
+    vals = []
+    for d in range(8):
+        if before[4 * d] and after[4 * d] and after[4 * d + 2] > before[4 * d + 2]:
+            vals.append(0.1 * (after[4 * d + 1] - before[4 * d + 1]) / (after[4 * d + 2] - before[4 * d + 2]))
+    return sum(vals) / len(vals) if vals else None

@@ -64,5 +64,6 @@ def test_bench_refuses_more_than_one_gpu():
 def test_bench_reads_the_committed_traffic_summary():
     sys.path.insert(0, ROOT)
     import bench
-    t = bench.committed_traffic()
-    assert isinstance(t, int) and 1e8 < t < 5e9
+    t, source = bench.committed_traffic()
+    assert isinstance(t, int) and 1e8 < t < 5e9 and "revision" not in source.split("as of")[0]
+    assert os.path.exists(os.path.join(ROOT, "profiles", bench.TRAFFIC_SUMMARY))
