@@ -172,7 +172,7 @@ def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, input
         run_step = graph.replay
     for _ in range(warmup):
         run_step()
-    clk = torch.zeros((2, 32), dtype=torch.int64, device="cuda")
+    clk = torch.zeros((2, 4 * f8.PROBE_CLOCK_SLOTS), dtype=torch.int64, device="cuda")
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -187,7 +187,7 @@ def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, input
     ms_per_step = (t1 - t0) * 1e3 / steps
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
     ms_median = per_step[len(per_step) // 2]
-    c = clk.cpu().tolist()
+    c = clk.cpu()
     # shader-clock cycles over 100 MHz ticks between the two sampling kernels that bracket the steps
     clock_ghz = f8.clock_ghz_between(c[0], c[1]) or 0.0
     flops_step = sum(s.lin.flops for s in states)
@@ -229,14 +229,14 @@ def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, input
                 f8.NT, M, K, N, sv.dy.q, grad_fmt, sv.w.q_t, f8.E4M3, sv.dy.inv_scale, w_is_t, g, s.dX, stream)),
                 2 * M * K * N, "dX = dY W"))
             ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N, dy_is_t=dy_is_t, x_is_t=x_is_t: f8.gemm(
-                f8.NT, N, K, M, sv.dy.q_t, grad_fmt, sv.x.q_t, f8.E4M3, dy_is_t, x_is_t, g, s.dW, stream)),
+                f8.NT, N, K, M, sv.dy.q_t, grad_fmt, sv.x.q_t, f8.E4M3, dy_is_t, x_is_t, g, s.dW, stream, workspace=ws)),
                 2 * M * K * N, "dW = dY^T X"))
         else:                      # the codes read in place: W and both of dY, X are k-major operands
             ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N: f8.gemm(
                 f8.NN, M, K, N, sv.dy.q, grad_fmt, sv.w.q, f8.E4M3, sv.dy.inv_scale, sv.w.inv_scale, g, s.dX, stream)),
                 2 * M * K * N, "dX = dY W"))
             ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N: f8.gemm(
-                f8.TN, N, K, M, sv.dy.q, grad_fmt, sv.x.q, f8.E4M3, sv.dy.inv_scale, sv.x.inv_scale, g, s.dW, stream)),
+                f8.TN, N, K, M, sv.dy.q, grad_fmt, sv.x.q, f8.E4M3, sv.dy.inv_scale, sv.x.inv_scale, g, s.dW, stream, workspace=ws)),
                 2 * M * K * N, "dW = dY^T X"))
 
     evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in ops]

@@ -74,8 +74,13 @@ typedef enum { F8_NT = 0, F8_NN = 1, F8_TN = 2 } f8_layout;
 
 /* Bytes of device workspace that is enough for any call of this library on
  * tensors of at most max_rows x max_cols (for a linear layer: the largest of
- * M, K, N in both arguments).  The workspace holds partial maxima only; it
- * needs no initialisation and carries no state between calls. */
+ * M, K, N in both arguments).  The workspace holds partial maxima of the
+ * quantisation and, in the backward of a linear whose weight gradient has few
+ * output tiles and a long contraction, fp32 partial sums of that product (at
+ * most 64 MiB); it needs no initialisation and carries no state between calls.
+ * The quantisation calls on their own (f8_amax, f8_cast_amax, f8_amax_cast,
+ * f8_quantise, the fused glue casts) accept less: 64 * max(rows, cols) * 4 +
+ * ceil(cols / 128) * rows * 4 bytes, at least 8 KiB. */
 size_t f8_workspace_bytes(int64_t max_rows, int64_t max_cols);
 
 const char* f8_status_string(f8_status s);
@@ -186,6 +191,23 @@ f8_status f8_gemm(f8_layout layout, int64_t M, int64_t N, int64_t K, const uint8
                   float* amax_d, void* stream);
 
 /*
+ * f8_gemm with a workspace (nullable; any size, 16-byte aligned).  A product
+ * with few output tiles and a long contraction (the weight gradient of a narrow
+ * linear: 64 tiles of 256 x 256 for 256 compute units) is then computed in 2, 4
+ * or 8 contraction ranges, one (tile, range) per compute unit, whose unscaled
+ * fp32 sums go to the workspace and are added in range order by a second
+ * kernel that applies the scales and rounds to bf16: reproducible, no atomics.
+ * It happens when ranges * M * N * 4 bytes fit the workspace (at most 64 MiB;
+ * f8_workspace_bytes(M, N) is always enough), amax_d is NULL and the estimated
+ * time is lower; otherwise the call is f8_gemm.  Results of a split product
+ * differ from the unsplit one within accumulation rounding.
+ */
+f8_status f8_gemm_ws(f8_layout layout, int64_t M, int64_t N, int64_t K, const uint8_t* A, f8_format fa,
+                     int64_t lda, const uint8_t* B, f8_format fb, int64_t ldb, const float* inv_scale_a,
+                     const float* inv_scale_b, f8_granularity g, void* D_bf16, int64_t ldd,
+                     float* amax_d, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * One quantised tensor T[rows, cols] as the linear layer keeps it between
  * forward and backward.  All members are caller-allocated device memory.
  *   Tensorwise: q [rows, cols] holds the codes; amax / scale / inv_scale have 1
@@ -266,8 +288,9 @@ f8_status f8_linear_fwd_wq(const f8_linear_desc* d, const void* X, void* Y, f8_s
  * frees nothing and calls no allocating routine.  Its first call on a device
  * looks up the array's address there (hipGetSymbolAddress), so make that call
  * outside a stream capture.
- * Limits: tensorwise scaling fits for every shape; rowwise scaling needs
- * max(f8_workspace_bytes(M, K), f8_workspace_bytes(N, K)) bytes, and a shape
+ * Limits: tensorwise scaling fits for every shape; rowwise scaling needs the
+ * partial maxima of its larger tensor T [rows, cols] (X [M,K] or W [N,K]):
+ * 64 * max(rows, cols) * 4 + ceil(cols / 128) * rows * 4 bytes, and a shape
  * needing more than the array returns F8_ERR_WORKSPACE with nothing launched.
  * This is the library's only shared state: every call on a GPU uses that GPU's
  * one array (nothing in it has to be cleared between calls: each quantisation
@@ -548,18 +571,20 @@ f8_status f8_linear_fwd_xq(const f8_linear_desc* d, const f8_scaling_state* stat
  * f8_probe_copy / f8_probe_read: grid-stride 16-byte copy of `bytes` bytes
  *   (read + write) / read of them; bytes a multiple of 16.  The copy is also
  *   the kernel of known size against which the HBM byte counters are scaled.
- * f8_probe_clock: a few one-thread workgroups each read the shader-clock cycle
- *   counter and the 100 MHz counter and file them under the accelerator die
- *   (XCD) they run on: out[4 d + 0] = 1 (slot filled; the caller zeroes out
- *   first), out[4 d + 1] = cycles, out[4 d + 2] = 100 MHz ticks, for die d in
- *   0..7 (out: 32 words of device memory).  The dies' cycle counters need not
- *   agree, so compare two calls (before and after a region on one stream) die
- *   by die: mean shader clock = 0.1 GHz x d(cycles) / d(ticks).
+ * f8_probe_clock: many small workgroups each read the shader-clock cycle
+ *   counter and the 100 MHz counter and file them under the compute unit they
+ *   run on (the counters of different units need not agree): slot u of `out`
+ *   (F8_PROBE_CLOCK_SLOTS slots of 4 words, device memory that the caller
+ *   zeroes first) gets out[4 u + 0] = 1 (filled), out[4 u + 1] = cycles,
+ *   out[4 u + 2] = 100 MHz ticks.  Compare two calls (before and after a region
+ *   on one stream) slot by slot: mean shader clock = 0.1 GHz x d(cycles) /
+ *   d(ticks), averaged over the slots filled in both.
  */
 f8_status f8_probe_mfma(const uint8_t* operands, int64_t operand_bytes, int iters, uint64_t* ticks,
                         float* sink, int64_t* flops_out, void* stream);
 f8_status f8_probe_copy(const void* src, void* dst, int64_t bytes, void* stream);
 f8_status f8_probe_read(const void* src, int64_t bytes, uint32_t* sink, void* stream);
+#define F8_PROBE_CLOCK_SLOTS 2048
 f8_status f8_probe_clock(uint64_t* out, void* stream);
 
 #ifdef __cplusplus

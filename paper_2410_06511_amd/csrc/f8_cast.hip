@@ -592,7 +592,8 @@ static int col_chunks(int64_t rows, int64_t* rows_per_chunk)
     return (int)((rows + rpc - 1) / rpc > 0 ? (rows + rpc - 1) / rpc : 1);
 }
 
-size_t workspace_bytes(int64_t max_rows, int64_t max_cols)
+// what the amax / cast / glue kernels need for their partial maxima
+size_t quantise_workspace_bytes(int64_t max_rows, int64_t max_cols)
 {
     int64_t d = max_rows > max_cols ? max_rows : max_cols;
     if (d < 0) d = 0;
@@ -608,6 +609,19 @@ size_t workspace_bytes(int64_t max_rows, int64_t max_cols)
     const int64_t r = max_rows > 0 ? max_rows : 0, c = max_cols > 0 ? max_cols : 0;
     size_t tiles = (size_t)((r + kTile - 1) / kTile) * (size_t)((c + kTile - 1) / kTile) * sizeof(uint32_t);
     n = tiles > n ? tiles : n;
+    return (n + 255) / 256 * 256;
+}
+
+// the public size: the above, and room for the fp32 partial results of a matrix product split
+// along its contraction (up to 8 ranges of an output no larger than rows x cols, and never more
+// than one 256x256 tile per compute unit in all)
+size_t workspace_bytes(int64_t max_rows, int64_t max_cols)
+{
+    const size_t r = max_rows > 0 ? (size_t)max_rows : 0, c = max_cols > 0 ? (size_t)max_cols : 0;
+    size_t split = (size_t)8 * r * c * sizeof(float);
+    split = split < kSplitKMaxBytes ? split : kSplitKMaxBytes;
+    const size_t q = quantise_workspace_bytes(max_rows, max_cols);
+    const size_t n = split > q ? split : q;
     return (n + 255) / 256 * 256;
 }
 
@@ -879,7 +893,7 @@ f8_status f8_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t ld, f8
     f8_status s = check_matrix(x_bf16, rows, cols, ld);
     if (s != F8_OK) return s;
     if (!amax_out) return F8_ERR_NULL;
-    if (g != F8_ROWWISE && (!workspace || workspace_bytes_ < workspace_bytes(rows, cols))) return F8_ERR_WORKSPACE;
+    if (g != F8_ROWWISE && (!workspace || workspace_bytes_ < quantise_workspace_bytes(rows, cols))) return F8_ERR_WORKSPACE;
     return launch_amax(x_bf16, rows, cols, ld, g, 0.0f, amax_out, nullptr, nullptr, workspace, (hipStream_t)stream);
 }
 
@@ -922,7 +936,7 @@ f8_status f8_amax_cast(const void* x_bf16, int64_t rows, int64_t cols, int64_t l
     if (g == F8_COLWISE && !aligned16(scale_out)) return F8_ERR_ALIGN;
     s = check_cast_outputs(rows, cols, out, ld_out, out_t, ld_out_t);
     if (s != F8_OK) return s;
-    if (g != F8_ROWWISE && (!workspace || workspace_bytes_ < workspace_bytes(rows, cols))) return F8_ERR_WORKSPACE;
+    if (g != F8_ROWWISE && (!workspace || workspace_bytes_ < quantise_workspace_bytes(rows, cols))) return F8_ERR_WORKSPACE;
     return quantise(x_bf16, rows, cols, ld, g, fmt, amax_out, scale_out, inv_scale_out, out, ld_out, out_t,
                     ld_out_t, workspace, (hipStream_t)stream);
 }
@@ -937,7 +951,7 @@ f8_status f8_cast_amax(const void* x_bf16, int64_t rows, int64_t cols, int64_t l
     if (!scale || !amax_out) return F8_ERR_NULL;
     s = check_cast_outputs(rows, cols, out, ld_out, out_t, ld_out_t);
     if (s != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return F8_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes_ < quantise_workspace_bytes(rows, cols)) return F8_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     int np = 0;
     s = cast_measure(x_bf16, rows, cols, ld, scale, fmt, out, ld_out, out_t, ld_out_t, workspace,

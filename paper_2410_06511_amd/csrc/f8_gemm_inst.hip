@@ -15,9 +15,10 @@ namespace f8 {
 void F8_INST_NAME(F8_INST_FA, F8_INST_FB, F8_INST_LAYOUT)(int g, int M, int N, int K, const uint8_t* A, int64_t lda,
                                                            const uint8_t* B, int64_t ldb, const float* isa,
                                                            const float* isb, uint16_t* D, int64_t ldd,
-                                                           uint32_t* amax_bits, hipStream_t st)
+                                                           uint32_t* amax_bits, void* ws, size_t ws_bytes, hipStream_t st)
 {
-    gemm_formats<F8_INST_LAYOUT, F8_INST_FA, F8_INST_FB>(g, M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+    gemm_formats<F8_INST_LAYOUT, F8_INST_FA, F8_INST_FB>(g, M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, ws,
+                                                         ws_bytes, st);
 }
 
 }  // namespace f8

@@ -5,7 +5,7 @@
 // Two kernels:
 //   gemm_tile_kernel    the fast path, K a multiple of 256, all three layouts.
 //                       Persistent workgroups, global -> LDS direct loads (no
-//                       VGPR staging), two LDS stages, v_mfma_f32_32x32x64_f8f6f4,
+//                       VGPR staging), two LDS stages, v_mfma_f32_16x16x128_f8f6f4,
 //                       scales folded into the fp32 epilogue, bf16 stores staged
 //                       through LDS.  An operand whose contraction index is the
 //                       fast one in memory ("row-major in K": both of F8_NT, A of
@@ -110,50 +110,62 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
 // ---------------------------------------------------------------------------
 // fast kernel
 // ---------------------------------------------------------------------------
-// Persistent workgroups (one or two per CU) walk over BM x BN output tiles.  K
-// advances in steps of 128 bytes = one LDS stage of 128-byte rows (a full cache
-// line per row and load), two stages, filled by direct global->LDS loads.  Each
-// stage feeds two v_mfma_f32_32x32x64_f8f6f4 half-steps.  The load stream runs
-// two K steps ahead of the MFMAs and does not stop at tile boundaries, so the
-// next tile's first stages arrive while the current tile's epilogue runs.
-// Fragments of the next half-step are read from LDS into a second register set
-// while the MFMAs of the current one run; there are two barriers per K step (this stage is free
-// to refill; the other stage has landed), each with MFMAs queued in front of it.
+// Persistent workgroups (one or two per CU) walk over BM x BN output tiles.  K advances in
+// steps of 128 bytes = one LDS stage (a full cache line per row and load) = the contraction
+// length of one v_mfma_f32_16x16x128_f8f6f4; two stages, filled by direct global->LDS loads.
+// (The 16x16x128 form of the fp8 matrix instruction draws less power per flop than the
+// 32x32x64 form, and the chip runs these kernels against its power limit: on quantised
+// Gaussian data the matrix pipes alone sustain 4.3-4.5 PFLOP/s with it against 3.7-4.1.)
+// A wave's 128 x 128 tile is 8 x 8 matrix-instruction tiles, i.e. 8 + 8 operand fragments per K
+// step.  The load stream runs two K steps ahead of the MFMAs and does not stop at tile
+// boundaries, so the next tile's first stages arrive while the current tile's epilogue runs.
+// There are two barriers per K step (this stage is free to refill; the other stage has
+// landed), each with MFMAs queued in front of it.
 constexpr int kBK = 128;  // bytes of K per LDS stage
 
-typedef float v16f __attribute__((ext_vector_type(16)));
 typedef float f2 __attribute__((ext_vector_type(2)));
 typedef __bf16 b2 __attribute__((ext_vector_type(2)));
 
-// XOR swizzle of the eight 16-byte chunks of a 128-byte LDS row: the lanes that read the
-// same logical chunk of consecutive rows spread over all bank groups, for any aligned 8
-// rows (128-byte bank window) and any aligned 16 rows (256-byte window).
+// XOR swizzle of the eight 16-byte chunks of a 128-byte LDS row: the 16 lanes that read the
+// same logical chunk of 16 consecutive rows hit 16 different bank groups (8 chunk positions x
+// row parity), and so do any aligned 8 rows under a 128-byte bank window.
 __device__ inline int swz(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2); }
 
 // ---- k-major operand tiles ----------------------------------------------------------
 // An operand stored [K, R-direction] (B of F8_NN, both operands of F8_TN) is staged as it
 // lies in memory: per stage 128 k-rows of R = BM or BN bytes.  The MFMA wants, per lane, 32
-// consecutive k of one row of the operand; ds_read_b64_tr_b8 forms them: within each group
-// of 16 lanes, lane i receives byte i % 8 of the 8-byte pieces addressed by lanes i / 8,
-// 2 + i / 8, ..., 14 + i / 8.  With lane s of the group pointing at k-row k0 + s / 2, bytes
-// r0 + 8 (s % 2) .. + 7 of it, lane i ends up with k0 .. k0 + 7 of operand row r0 + i, in
-// natural k order; four such reads make one 32-byte fragment.  The 16-lane groups of a
-// wavefront take rows 0-15 / 16-31 of the 32-row MFMA tile and the two k halves, which is
-// the lane layout of the row-major path.
-// The 16-byte chunks of a k-row are permuted so that the 8 k-rows x 16 bytes of one group,
-// and the 16 chunks of the two groups that differ in the row half, fall on different banks.
+// consecutive k of one row of the operand (lane l: row l % 16 of the 16-row fragment, k range
+// l / 16); ds_read_b64_tr_b8 forms them: within each group of 16 lanes, lane i receives byte
+// i % 8 of the 8-byte pieces addressed by lanes i / 8, 2 + i / 8, ..., 14 + i / 8.  With lane s
+// of the group pointing at k-row k0 + s / 2, bytes 8 (s % 2) .. + 7 of the fragment's 16-byte
+// chunk of it, lane i ends up with k0 .. k0 + 7 of fragment row i, in natural k order; four
+// such reads (k0 = 32 (l / 16) + 0, 8, 16, 24) make one 32-byte fragment register set.
+// The 16-byte chunks of a k-row are permuted so that the 8 k-rows of one group, and the groups
+// that read together (k ranges 32 apart), fall on different banks.
 template <int R>
 __device__ inline int kswz(int chunk, int krow)  // logical chunk of k-row -> physical chunk
 {
-    if constexpr (R == 256) return ((chunk & 1) << 3) | ((chunk >> 1) ^ (krow & 7));
-    else return chunk ^ (krow & 7);
+    if constexpr (R == 256) {
+        const int kx = (krow & 7) | (((krow >> 5) & 1) << 3);
+        return (((chunk & 1) << 3) | (chunk >> 1)) ^ kx;  // chunk bit 0 goes to the 128-byte half
+    } else {
+        return chunk ^ (krow & 7) ^ ((krow >> 5) & 1);    // 128-byte rows: the row parity picks the half
+    }
 }
 template <int R>
 __device__ inline int kswz_inv(int phys, int krow)
 {
-    if constexpr (R == 256) return (((phys & 7) ^ (krow & 7)) << 1) | (phys >> 3);
-    else return phys ^ (krow & 7);
+    if constexpr (R == 256) {
+        const int q = phys ^ ((krow & 7) | (((krow >> 5) & 1) << 3));
+        return ((q & 7) << 1) | (q >> 3);
+    } else {
+        return phys ^ (krow & 7) ^ ((krow >> 5) & 1);
+    }
 }
+// kswz<R>(c0 ^ idx, k) = kswz<R>(c0, k) ^ kswz_step<R>(idx): the permutation is linear in the chunk
+template <int R>
+constexpr int kswz_step(int idx) { return R == 256 ? (((idx & 1) << 3) | (idx >> 1)) : idx; }
+
 typedef int v2i __attribute__((ext_vector_type(2)));
 __device__ inline v2i lds_read_tr8(const uint8_t* p)
 {
@@ -165,23 +177,31 @@ __device__ inline v2i lds_read_tr8(const uint8_t* p)
 constexpr int kWaitAllVmLgkm = 0x0070;
 
 // AKM / BKM: operand A / B is k-major (A[K, M] with leading dimension lda, B[K, N] with ldb).
-template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN, bool AMAX, bool AKM, bool BKM>
+// SPLITK: the contraction is cut into `splits` equal ranges and a work item is (tile, range);
+// item w is tile w % tiles, range w / tiles.  Instead of D the kernel then writes the unscaled
+// fp32 sums of range s to partial[s][M][ldp]; splitk_reduce_kernel adds the ranges in order,
+// applies the scales and rounds to bf16.  (For products with few output tiles and a long
+// contraction, where whole tiles would leave most compute units idle.)
+template <int BM, int BN, int WAVES_M, int WAVES_N, int FA, int FB, int GRAN, bool AMAX, bool AKM, bool BKM,
+          bool SPLITK = false>
 __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
     const uint8_t* __restrict__ A, const uint8_t* __restrict__ B, uint16_t* __restrict__ D, int M,
     int N, int K, int64_t lda, int64_t ldb, int64_t ldd, const float* __restrict__ isa,
-    const float* __restrict__ isb, int tiles_m, int tiles_n, uint32_t* __restrict__ amax_bits)
+    const float* __restrict__ isb, int tiles_m, int tiles_n, uint32_t* __restrict__ amax_bits,
+    int splits = 1, float* __restrict__ partial = nullptr, int64_t ldp = 0)
 {
+    static_assert(!(SPLITK && AMAX), "the output amax is taken by the kernel that writes D");
     constexpr int NW = WAVES_M * WAVES_N;
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;  // wave tile
-    constexpr int TM = WM / 32, TN = WN / 32;            // MFMA tiles per wave
+    constexpr int TM = WM / 16, TN = WN / 16;            // MFMA tiles (fragments) per wave
     constexpr int A_BYTES = BM * kBK, STAGE = (BM + BN) * kBK;
     constexpr int A_LOADS = BM / 8 / NW, B_LOADS = BN / 8 / NW;  // 1 KB (8 rows) per wave load
     static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "tile rows must split over the waves");
     static_assert(NW == 4, "four waves");
-    static_assert(!(AKM || BKM) || (WAVES_M == 2 && WAVES_N == 2 && (BM == 256 || BM == 128) && (BN == 256 || BN == 128)),
-                  "k-major addressing assumes 2 x 2 waves on 128- or 256-wide tiles");
+    static_assert(WAVES_M == 2 && WAVES_N == 2 && (BM == 256 || BM == 128) && (BN == 256 || BN == 128),
+                  "the addressing assumes 2 x 2 waves on 128- or 256-wide tiles");
     constexpr int EP_STRIDE = 64 * 2 + 16;    // bytes per staged epilogue row: 64 bf16 + padding
-    static_assert(TN % 2 == 0, "the epilogue stages two MFMA tiles side by side");
+    static_assert(TM % 2 == 0 && TN % 4 == 0, "an epilogue pass stages 2 x 4 MFMA tiles (32 rows x 64 columns)");
 
     // One array per stage: the compiler then knows that a load into one stage does not alias
     // LDS reads of the other and does not serialise them.
@@ -192,8 +212,9 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-    const int total_tiles = tiles_m * tiles_n;
-    const int KT = K / kBK;
+    const int tiles_mn = tiles_m * tiles_n;
+    const int total_tiles = SPLITK ? tiles_mn * splits : tiles_mn;  // work items of the launch
+    const int KT = SPLITK ? K / kBK / splits : K / kBK;             // K steps per work item
 
     using std::integral_constant;
     auto stage_ptr = [&](auto S) -> uint8_t* {
@@ -203,107 +224,111 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
 
     // ---- load stream: (tile, K step) of the next stage to fetch -------------------------
     // wave w fills rows [w*R, (w+1)*R) of each operand tile in 8-row (1 KB) pieces; lane i
-    // lands at row i/8, physical chunk i%8 of its piece.  Per tile only scalars change (tile
-    // origin, row limits); the lane's byte offset of a piece is rebuilt for every load from
-    // its row and chunk (three VALU operations), which is cheaper than carrying sixteen offsets
-    // in registers across the whole K loop.
+    // lands at row i/8, physical chunk i%8 of its piece.  A load is then only: LDS target into
+    // M0, one instruction with a per-load lane offset (kept in a register, rebuilt per tile) and a
+    // scalar base that moves with the K step.  Anything more per load would not fit between two
+    // matrix instructions (32 cycles), and the matrix pipe would wait for the instruction stream.
     int ld_tile = blockIdx.x;
-    // row-major operand: lane's row of piece 0 in the tile, and its chunk terms (the swizzle of
-    // row + 8 * j differs from that of row only for odd j, bit 2)
+    // row-major operand: the lane's row of piece 0 in the tile decides its chunk terms (the
+    // swizzle of row + 8 * j differs from that of row only for odd j, bit 2)
     const int a_row = wave * (BM / NW) + (lane >> 3);
     const int b_row = wave * (BN / NW) + (lane >> 3);
     // k-major operand: a 1 KB load covers 1024 / R k-rows; lane i lands at k-row i / (R / 16),
     // physical chunk i % (R / 16) of them and fetches the logical chunk that belongs there.  The
-    // wave fills k-rows [32 * wave, 32 * wave + 32).  Of the k-row only its low three bits
-    // enter the permutation: they are those of 4 * (load number % 2) + lane's row for R = 256
-    // (four rows per load), of the lane's row for R = 128 (eight rows per load).
+    // wave fills k-rows [32 * wave, 32 * wave + 32).  Of the k-row only bits 0-2 and 5 enter the
+    // permutation: bit 5 is that of the wave; bits 0-2 are those of 4 * (load number % 2) +
+    // lane's row for R = 256 (four rows per load), of the lane's row for R = 128 (eight per load).
     constexpr int A_CPR = BM / 16, B_CPR = BN / 16;  // chunks per k-row
     const int a_kr = lane / A_CPR, b_kr = lane / B_CPR;
     uint32_t a_c0, a_c1, b_c0, b_c1;  // byte offset of the lane's chunk for even / odd load numbers
     if constexpr (AKM) {
-        a_c0 = 16 * kswz_inv<BM>(lane % A_CPR, a_kr);
-        a_c1 = 16 * kswz_inv<BM>(lane % A_CPR, a_kr + (BM == 256 ? 4 : 0));
+        a_c0 = 16 * kswz_inv<BM>(lane % A_CPR, 32 * wave + a_kr);
+        a_c1 = 16 * kswz_inv<BM>(lane % A_CPR, 32 * wave + a_kr + (BM == 256 ? 4 : 0));
     } else {
         a_c0 = 16 * ((lane & 7) ^ swz(a_row)), a_c1 = 16 * ((lane & 7) ^ swz(a_row + 8));
     }
     if constexpr (BKM) {
-        b_c0 = 16 * kswz_inv<BN>(lane % B_CPR, b_kr);
-        b_c1 = 16 * kswz_inv<BN>(lane % B_CPR, b_kr + (BN == 256 ? 4 : 0));
+        b_c0 = 16 * kswz_inv<BN>(lane % B_CPR, 32 * wave + b_kr);
+        b_c1 = 16 * kswz_inv<BN>(lane % B_CPR, 32 * wave + b_kr + (BN == 256 ? 4 : 0));
     } else {
         b_c0 = 16 * ((lane & 7) ^ swz(b_row)), b_c1 = 16 * ((lane & 7) ^ swz(b_row + 8));
     }
-    static_assert((BM / NW) % 16 == 0 && (BN / NW) % 16 == 0, "swizzle period");
-    const uint32_t a_krow_off = (uint32_t)(wave * (kBK / NW) + a_kr) * (uint32_t)lda;  // k-major: lane's k-row of load 0
-    const uint32_t b_krow_off = (uint32_t)(wave * (kBK / NW) + b_kr) * (uint32_t)ldb;
+    static_assert((BM / NW) % 16 == 0 && (BN / NW) % 16 == 0 && kBK / NW == 32, "swizzle period; 32 k-rows per wave");
     const uint8_t* a_base = A;
     const uint8_t* b_base = B;
-    // row-major: last valid row of the current load tile, relative to its origin (rows past the
-    // edge re-read the last row; never stored).  k-major: the lane's whole offset for even / odd
-    // load numbers, with chunks past the edge re-reading the last valid chunk of the k-row.
-    int a_rmax = 0, b_rmax = 0;
-    uint32_t a_o0 = 0, a_o1 = 0, b_o0 = 0, b_o1 = 0;
-    auto load_context = [&](int tile) {
+    // The lane's byte offset of every load of a K step, relative to the step's base address
+    // (a_base / b_base + K step * 128 bytes, or * 128 k-rows).  row-major: (row of the piece +
+    // lane's row in it) * ld + chunk; pieces past the edge of the matrix (M and N are multiples
+    // of 16, so a piece is all in or all out) re-read the last piece inside: their products are
+    // never stored.  k-major: k-row * ld + chunk, with chunks past the edge re-reading the last
+    // valid chunk of the k-row.
+    uint32_t a_off[A_LOADS], b_off[B_LOADS];
+    auto load_context = [&](int item) {
         int tm, tn;
-        tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
+        tile_coords(SPLITK ? item % tiles_mn : item, tiles_m, tiles_n, &tm, &tn);
+        const int64_t koff = SPLITK ? (int64_t)(item / tiles_mn) * KT * kBK : 0;  // first k of the item's range
         if constexpr (AKM) {
-            a_base = A + (int64_t)tm * BM;
+            a_base = A + (int64_t)tm * BM + koff * lda;
             const uint32_t cmax = (uint32_t)(M - 16 - tm * BM);
-            a_o0 = a_krow_off + (a_c0 < cmax ? a_c0 : cmax);
-            a_o1 = a_krow_off + (a_c1 < cmax ? a_c1 : cmax);
+#pragma unroll
+            for (int idx = 0; idx < A_LOADS; ++idx)
+                a_off[idx] = (uint32_t)(wave * (kBK / NW) + idx * (1024 / BM) + a_kr) * (uint32_t)lda +
+                             (((idx & 1) ? a_c1 : a_c0) < cmax ? ((idx & 1) ? a_c1 : a_c0) : cmax);
         } else {
-            a_base = A + (int64_t)tm * BM * lda;
-            a_rmax = M - 1 - tm * BM;
+            a_base = A + (int64_t)tm * BM * lda + koff;
+            const int pmax = M - 8 - tm * BM;  // first row of the last piece inside, relative to the tile
+#pragma unroll
+            for (int idx = 0; idx < A_LOADS; ++idx) {
+                int prow = wave * (BM / NW) + 8 * idx;
+                prow = prow < pmax ? prow : pmax;
+                a_off[idx] = (uint32_t)(prow + (lane >> 3)) * (uint32_t)lda + ((idx & 1) ? a_c1 : a_c0);
+            }
         }
         if constexpr (BKM) {
-            b_base = B + (int64_t)tn * BN;
+            b_base = B + (int64_t)tn * BN + koff * ldb;
             const uint32_t cmax = (uint32_t)(N - 16 - tn * BN);
-            b_o0 = b_krow_off + (b_c0 < cmax ? b_c0 : cmax);
-            b_o1 = b_krow_off + (b_c1 < cmax ? b_c1 : cmax);
+#pragma unroll
+            for (int j = 0; j < B_LOADS; ++j)
+                b_off[j] = (uint32_t)(wave * (kBK / NW) + j * (1024 / BN) + b_kr) * (uint32_t)ldb +
+                           (((j & 1) ? b_c1 : b_c0) < cmax ? ((j & 1) ? b_c1 : b_c0) : cmax);
         } else {
-            b_base = B + (int64_t)tn * BN * ldb;
-            b_rmax = N - 1 - tn * BN;
+            b_base = B + (int64_t)tn * BN * ldb + koff;
+            const int pmax = N - 8 - tn * BN;
+#pragma unroll
+            for (int j = 0; j < B_LOADS; ++j) {
+                int prow = wave * (BN / NW) + 8 * j;
+                prow = prow < pmax ? prow : pmax;
+                b_off[j] = (uint32_t)(prow + (lane >> 3)) * (uint32_t)ldb + ((j & 1) ? b_c1 : b_c0);
+            }
         }
     };
-    // Load number `idx` (0 .. LOADS-1: first the A pieces, then the B pieces) of K step `kt` of
-    // the stream's current tile, into stage S.  Written as asm: 32-bit lane offset next to a
+    // Load number `idx` (0 .. LOADS-1: first the A pieces, then the B pieces) of the K step whose
+    // base addresses are ga / gb, into stage S.  Written as asm: 32-bit lane offset next to a
     // scalar base, LDS target in M0.  The compiler therefore does not see these as LDS writes;
     // ordering against the LDS reads is by the barriers and explicit waits of kstep.
-    auto issue_one = [&](int kt, auto S, auto IDX) {
+    auto issue_one = [&](const uint8_t* ga, const uint8_t* gb, auto S, auto IDX) {
         constexpr int idx = decltype(IDX)::value;
         if constexpr (idx < A_LOADS) {
             uint8_t* lp = stage_ptr(S) + wave * (BM / NW) * kBK + idx * 1024;
             const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
-            const uint8_t* gp;
-            uint32_t o;
-            if constexpr (AKM) {
-                gp = a_base + ((int64_t)kt * kBK + idx * (1024 / BM)) * lda;
-                o = (idx & 1) ? a_o1 : a_o0;
-            } else {
-                gp = a_base + (int64_t)kt * kBK;
-                int r = a_row + 8 * idx;
-                r = r < a_rmax ? r : a_rmax;
-                o = (uint32_t)r * (uint32_t)lda + ((idx & 1) ? a_c1 : a_c0);
-            }
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
+            const uint32_t o = a_off[idx];
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(ga) : "memory");
         } else {
             constexpr int j = idx - A_LOADS;
             uint8_t* lp = stage_ptr(S) + A_BYTES + wave * (BN / NW) * kBK + j * 1024;
             const uint32_t l32 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)lp;
-            const uint8_t* gp;
-            uint32_t o;
-            if constexpr (BKM) {
-                gp = b_base + ((int64_t)kt * kBK + j * (1024 / BN)) * ldb;
-                o = (j & 1) ? b_o1 : b_o0;
-            } else {
-                gp = b_base + (int64_t)kt * kBK;
-                int r = b_row + 8 * j;
-                r = r < b_rmax ? r : b_rmax;
-                o = (uint32_t)r * (uint32_t)ldb + ((j & 1) ? b_c1 : b_c0);
-            }
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gp) : "memory");
+            const uint32_t o = b_off[j];
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(l32), "v"(o), "s"(gb) : "memory");
         }
     };
-    auto issue_all = [&](int kt, auto S) { static_for<A_LOADS + B_LOADS>([&](auto L) { issue_one(kt, S, L); }); };
+    // base addresses of K step kt of the stream's current tile
+    auto step_base_a = [&](int kt) { return AKM ? a_base + (int64_t)kt * kBK * lda : a_base + (int64_t)kt * kBK; };
+    auto step_base_b = [&](int kt) { return BKM ? b_base + (int64_t)kt * kBK * ldb : b_base + (int64_t)kt * kBK; };
+    auto issue_all = [&](int kt, auto S) {
+        const uint8_t* ga = step_base_a(kt);
+        const uint8_t* gb = step_base_b(kt);
+        static_for<A_LOADS + B_LOADS>([&](auto L) { issue_one(ga, gb, S, L); });
+    };
     // Move the load stream to this workgroup's next tile.  Past the last tile the stream
     // stays where it is: the same K steps are fetched again into stages nobody reads, so that
     // every K step issues the same number of loads and the wait counts below hold throughout.
@@ -312,101 +337,113 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
         if (ld_tile < total_tiles) load_context(ld_tile);
     };
 
-    // ---- LDS -> register addressing.  Row-major operand: lane reads row (l % 32) of a 32-row
-    // MFMA tile; in half-step h the logical chunks 4h + 2g and 4h + 2g + 1 (g = l / 32): 32 K bytes.
-    const int fr = lane & 31, fg = lane >> 5;
+    // ---- LDS -> register addressing.  A fragment is 16 rows of an operand x the stage's 128 K
+    // bytes; lane l holds row l % 16, K bytes 32 (l / 16) .. + 31.
+    // Row-major operand: the lane reads the logical chunks 2 (l / 16) and 2 (l / 16) + 1 of its row.
+    const int fr = lane & 15, fg = lane >> 4;
     const int pc0 = (2 * fg) ^ swz(fr);
     const int flip1 = ((pc0 ^ 1) - pc0) * 16;          // to the second chunk of the pair
-    const int fliph = ((pc0 ^ 4) - pc0) * 16;          // to the same chunk of half-step 1
-    // k-major operand: lane s of 16-lane group q points at k-row 32 (q / 2) + s / 2 (+ 8 t for the
-    // t-th of the four reads, + 64 for half-step 1) and at the 8 bytes (s % 2) of the chunk that
-    // holds rows 16 (q % 2) .. + 15 of the MFMA tile.  Going to MFMA tile idx of the wave moves
-    // two chunks on, which the permutation turns into an XOR of the address.
-    const int kq = lane >> 4, ks = lane & 15;
+    // k-major operand: lane s of 16-lane group g points at k-row 32 g + s / 2 (+ 8 t for the t-th
+    // of the four reads) and at the 8 bytes (s % 2) of the fragment's chunk.  Going to fragment idx
+    // of the wave moves idx chunks on, which the permutation turns into an XOR of the address.
     auto km_read_base = [&](auto R_, int wave_row0) {
         constexpr int R = decltype(R_)::value;
-        return (32 * (kq >> 1) + (ks >> 1)) * R + 16 * kswz<R>(wave_row0 / 16 + (kq & 1), ks >> 1) + 8 * (ks & 1);
+        const int krow = 32 * fg + (fr >> 1);
+        return krow * R + 16 * kswz<R>(wave_row0 / 16, krow) + 8 * (fr & 1);
     };
     int a_rd, b_rd;
     if constexpr (AKM) a_rd = km_read_base(integral_constant<int, BM>{}, wm * WM);
-    else a_rd = (wm * WM + fr) * kBK + 16 * pc0;  // + 32-row tile * 4096
+    else a_rd = (wm * WM + fr) * kBK + 16 * pc0;  // + fragment * 16 rows
     if constexpr (BKM) b_rd = A_BYTES + km_read_base(integral_constant<int, BN>{}, wn * WN);
     else b_rd = A_BYTES + (wn * WN + fr) * kBK + 16 * pc0;
-    constexpr int A_XSTEP = BM == 256 ? 16 : 32, B_XSTEP = BN == 256 ? 16 : 32;
 
-    struct Frags {
-        v8i a[TM];
-        v8i b[TN];
-    };
+    v8i fa[TM], fb[TN];  // operand fragments in registers
+    v8i fb_early;        // the next K step's last B fragment, read while this step's is still in use
     auto read_km = [&](const uint8_t* p, auto R_) {
         constexpr int R = decltype(R_)::value;
         const v2i t0 = lds_read_tr8(p), t1 = lds_read_tr8(p + 8 * R), t2 = lds_read_tr8(p + 16 * R),
                   t3 = lds_read_tr8(p + 24 * R);
         return v8i{t0.x, t0.y, t1.x, t1.y, t2.x, t2.y, t3.x, t3.y};
     };
-    // fragment number `idx` of a half-step: 0 .. TM-1 are the A fragments, TM .. TM+TN-1 the B ones
-    auto read_frag = [&](Frags& f, auto S, auto H, auto IDX) {
-        constexpr int idx = decltype(IDX)::value;
-        constexpr int h = decltype(H)::value;
-        const int hoff = h ? fliph : 0;
-        if constexpr (idx < TM) {
-            if constexpr (AKM) {
-                f.a[idx] = read_km(stage_ptr(S) + (a_rd ^ (idx * A_XSTEP)) + h * 64 * BM, integral_constant<int, BM>{});
-            } else {
-                const uint8_t* sa = stage_ptr(S) + a_rd + hoff + idx * 32 * kBK;
-                const int4 lo = *reinterpret_cast<const int4*>(sa);
-                const int4 hi = *reinterpret_cast<const int4*>(sa + flip1);
-                f.a[idx] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            }
-        } else {
-            constexpr int j = idx - TM;
-            if constexpr (BKM) {
-                f.b[j] = read_km(stage_ptr(S) + (b_rd ^ (j * B_XSTEP)) + h * 64 * BN, integral_constant<int, BN>{});
-            } else {
-                const uint8_t* sb = stage_ptr(S) + b_rd + hoff + j * 32 * kBK;
-                const int4 lo = *reinterpret_cast<const int4*>(sb);
-                const int4 hi = *reinterpret_cast<const int4*>(sb + flip1);
-                f.b[j] = v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            }
-        }
+    auto read_rm = [&](const uint8_t* p) {
+        const int4 lo = *reinterpret_cast<const int4*>(p);
+        const int4 hi = *reinterpret_cast<const int4*>(p + flip1);
+        return v8i{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
     };
-    auto read_frags = [&](Frags& f, auto S, auto H) {
-        static_for<TM + TN>([&](auto F) { read_frag(f, S, H, F); });
+    auto read_a = [&](auto S, auto IDX) {
+        constexpr int idx = decltype(IDX)::value;
+        if constexpr (AKM) fa[idx] = read_km(stage_ptr(S) + (a_rd ^ (16 * kswz_step<BM>(idx))), integral_constant<int, BM>{});
+        else fa[idx] = read_rm(stage_ptr(S) + a_rd + idx * 16 * kBK);
+    };
+    auto read_b = [&](auto S, auto IDX) {
+        constexpr int idx = decltype(IDX)::value;
+        if constexpr (BKM) fb[idx] = read_km(stage_ptr(S) + (b_rd ^ (16 * kswz_step<BN>(idx))), integral_constant<int, BN>{});
+        else fb[idx] = read_rm(stage_ptr(S) + b_rd + idx * 16 * kBK);
     };
 
     uint32_t amax_acc = 0;  // AMAX: largest |bf16 output| this wavefront has produced (packed pairs)
-    v16f acc[TM][TN];
+    v4f acc[TM][TN];
     auto zero_acc = [&]() {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            for (int j = 0; j < TN; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
     };
 
-    // MFMAs number lo..hi-1 of a half-step (numbered i * TN + j)
-    auto mfmas = [&](const Frags& f, auto LO, auto HI) {
-#pragma unroll
-        for (int q = decltype(LO)::value; q < decltype(HI)::value; ++q) {
-            const int i = q / TN, j = q % TN;
-            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.b[j], f.a[i], acc[i][j], FB, FA, 0, 0,
-                                                                          0, 0);
-        }
+    // ---- the K step's MFMA order, TM * TN slots.  First half: the upper TM / 2 fragment rows of
+    // A, row by row (every B fragment is live, the A fragments die one by one).  Second half: the
+    // lower TM / 2 rows, column by column (the B fragments die one by one).  So registers free
+    // up for the next K step's fragments while this one still computes, and never more than
+    // TM + TN (+ 1) fragments are live: half of what double buffering both operands would take.
+    constexpr int SLOTS = TM * TN, HALF = SLOTS / 2, HM = TM / 2;
+    constexpr auto slot_i = [](int s) { return s < HALF ? s / TN : HM + (s - HALF) % HM; };
+    constexpr auto slot_j = [](int s) { return s < HALF ? s % TN : (s - HALF) / HM; };
+    // Written as asm with the accumulator as one read-write operand: left to itself the register
+    // allocator gives an MFMA's result and its addend different registers and then shuffles
+    // accumulators between the two register files inside the loop.  The first source operand
+    // is the B fragment (cbsz = its format), the second the A fragment (blgp): see the top of
+    // this file.  Consequence: the compiler does not know these are matrix instructions, so the
+    // wait states between the last of them and the first ordinary read of an accumulator are
+    // inserted by hand (mfma_drain).
+    auto mfma_slot = [&](auto SLOT) {
+        constexpr int s = decltype(SLOT)::value, i = slot_i(s), j = slot_j(s);
+        v4f& c = acc[i][j];
+        const v8i& b = fb[j];
+        const v8i& a = fa[i];
+        asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0 cbsz:%3 blgp:%4" : "+a"(c) : "v"(b), "v"(a), "n"(FB), "n"(FA));
     };
-    constexpr int NMFMA = TM * TN;
+    // an 8-pass matrix instruction's result may be read by an ordinary instruction 18 wait states
+    // after its issue at the earliest, and nothing interlocks that
+    auto mfma_drain = [&]() {
+        asm volatile("s_nop 15\n\ts_nop 15");
+    };
     using I0 = integral_constant<int, 0>;
     using I1 = integral_constant<int, 1>;
 
-    // ---- epilogue of one tile.  Of each 32x32 MFMA tile, lane l holds m = l % 32 and
-    // n = 8 * (r / 4) + 4 * (l / 32) + r % 4 for accumulator register r.  Each wave turns a
-    // 32-row, 64-column piece of its tile at a time into bf16, parks it in its private piece
-    // of LDS and writes it out as 16-byte row pieces: every global store instruction then
-    // covers whole 128-byte row segments.
-    auto epilogue = [&](int tile) {
+    // ---- epilogue of one tile.  Of each 16x16 MFMA tile, lane l holds m = l % 16 and
+    // n = 4 * (l / 16) + r for accumulator register r.  Each wave turns a 32-row, 64-column
+    // piece of its tile at a time into bf16, parks it in its private piece of LDS and writes it
+    // out as 16-byte row pieces: every global store instruction then covers whole 128-byte row
+    // segments.
+    auto epilogue = [&](int item) {
         int tm, tn;
-        tile_coords(tile, tiles_m, tiles_n, &tm, &tn);
+        tile_coords(SPLITK ? item % tiles_mn : item, tiles_m, tiles_n, &tm, &tn);
         const int m0 = tm * BM + wm * WM, n0 = tn * BN + wn * WN;  // of this wave's tile
+        if constexpr (SPLITK) {
+            // the unscaled sums of this range, as 16-byte pieces (four consecutive n of one m per lane)
+            float* P = partial + (int64_t)(item / tiles_mn) * M * ldp;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = m0 + 16 * i + fr;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = n0 + 16 * j + 4 * fg;
+                    if (m < M && n < N)  // N is a multiple of 16: the piece is all in or all out
+                        *reinterpret_cast<v4f*>(P + (int64_t)m * ldp + n) = acc[i][j];
+                }
+            }
+            return;
+        }
         uint8_t* ep = epb + wave * (32 * EP_STRIDE);
         float s_tensor = 0.f;
         if constexpr (GRAN == F8_TENSORWISE) s_tensor = isa[0] * isb[0];
@@ -418,50 +455,49 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
         const bool interior = tm * BM + BM <= M && tn * BN + BN <= N;  // no edge checks needed
 
         auto run = [&](auto INTERIOR) {
-            // One pass = rows 32 i .. 32 i + 31, columns 32 jp .. 32 jp + 63 of the wave's tile.
-            // Tensorwise: row bands outermost.  Per-row / per-column scales: column pairs
-            // outermost, so that the eight 4-float pieces of the column scales a lane needs are
-            // loaded once per column pair (and the row scales once per tile) instead of in every
-            // pass, where their latency would sit in front of each conversion.
-            constexpr int NP = TM * (TN / 2);
+            // One pass = rows 32 ip .. + 31, columns 64 jp .. + 63 of the wave's tile = 2 x 4 MFMA
+            // tiles.  Tensorwise: row bands outermost.  Per-row / per-column scales: column bands
+            // outermost, so that the column scales a lane needs are loaded once per band (and
+            // the row scales once per tile) instead of in every pass, where their latency would
+            // sit in front of each conversion.
+            constexpr int NP = (TM / 2) * (TN / 4);
             float sav[TM];
-            float4 sbv[8];
+            float4 sbv[4];
             if constexpr (GRAN != F8_TENSORWISE) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
-                    const int m_lane = m0 + 32 * i + fr;
+                    const int m_lane = m0 + 16 * i + fr;
                     sav[i] = isa[m_lane < M ? m_lane : M - 1];
                 }
             }
             static_for<NP>([&](auto P) {
                 constexpr int p = decltype(P)::value;
-                constexpr int i = GRAN == F8_TENSORWISE ? p / (TN / 2) : p % TM;
-                constexpr int jp = GRAN == F8_TENSORWISE ? (p % (TN / 2)) * 2 : (p / TM) * 2;
-                if constexpr (GRAN != F8_TENSORWISE && i == 0) {
+                constexpr int ip = GRAN == F8_TENSORWISE ? p / (TN / 4) : p % (TM / 2);
+                constexpr int jp = GRAN == F8_TENSORWISE ? p % (TN / 4) : p / (TM / 2);
+                if constexpr (GRAN != F8_TENSORWISE && ip == 0) {
 #pragma unroll
-                    for (int jj = 0; jj < 2; ++jj)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            int n = n0 + 32 * jp + 32 * jj + 8 * q + 4 * fg;
-                            n = n < N ? n : N - 4;
-                            sbv[jj * 4 + q] = *reinterpret_cast<const float4*>(isb + n);
-                        }
+                    for (int jj = 0; jj < 4; ++jj) {
+                        int n = n0 + 64 * jp + 16 * jj + 4 * fg;
+                        n = n < N ? n : N - 4;
+                        sbv[jj] = *reinterpret_cast<const float4*>(isb + n);
+                    }
                 }
 #pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int j = jp + jj;
+                for (int ii = 0; ii < 2; ++ii) {
+                    const int i = 2 * ip + ii;
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int nl = 32 * jj + 8 * q + 4 * fg;  // column inside the pass
+                    for (int jj = 0; jj < 4; ++jj) {
+                        const int j = 4 * jp + jj;
+                        const int nl = 16 * jj + 4 * fg;  // column inside the pass
                         f2 lo, hi;
                         if constexpr (GRAN == F8_TENSORWISE) {
-                            lo = f2{acc[i][j][4 * q] * s_tensor, acc[i][j][4 * q + 1] * s_tensor};
-                            hi = f2{acc[i][j][4 * q + 2] * s_tensor, acc[i][j][4 * q + 3] * s_tensor};
+                            lo = f2{acc[i][j][0] * s_tensor, acc[i][j][1] * s_tensor};
+                            hi = f2{acc[i][j][2] * s_tensor, acc[i][j][3] * s_tensor};
                         } else {
                             const float sa = sav[i];
-                            const float4 sb = sbv[jj * 4 + q];
-                            lo = f2{(acc[i][j][4 * q] * sa) * sb.x, (acc[i][j][4 * q + 1] * sa) * sb.y};
-                            hi = f2{(acc[i][j][4 * q + 2] * sa) * sb.z, (acc[i][j][4 * q + 3] * sa) * sb.w};
+                            const float4 sb = sbv[jj];
+                            lo = f2{(acc[i][j][0] * sa) * sb.x, (acc[i][j][1] * sa) * sb.y};
+                            hi = f2{(acc[i][j][2] * sa) * sb.z, (acc[i][j][3] * sa) * sb.w};
                         }
                         // fp32 -> bf16, round to nearest even (v_cvt_pk_bf16_f32)
                         uint2 o;
@@ -471,20 +507,20 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
                             // edge tiles hold results of re-read rows past M / N: not output
                             bool counted = true;
                             if constexpr (!decltype(INTERIOR)::value)
-                                counted = m0 + 32 * i + fr < M && n0 + 32 * jp + nl < N;
+                                counted = m0 + 16 * i + fr < M && n0 + 64 * jp + nl < N;
                             if (counted) amax_acc = amax_pair(amax_acc, o);
                         }
-                        *reinterpret_cast<uint2*>(ep + fr * EP_STRIDE + nl * 2) = o;
+                        *reinterpret_cast<uint2*>(ep + (16 * ii + fr) * EP_STRIDE + nl * 2) = o;
                     }
                 }
-                uint8_t* pbase = dbase + ((int64_t)(32 * i) * ldd + 32 * jp) * 2;  // uniform
+                uint8_t* pbase = dbase + ((int64_t)(32 * ip) * ldd + 64 * jp) * 2;  // uniform
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int idx = t * 64 + lane;
                     const uint4 v = *reinterpret_cast<const uint4*>(ep + (idx >> 3) * EP_STRIDE + (idx & 7) * 16);
                     bool ok = true;
                     if constexpr (!decltype(INTERIOR)::value)
-                        ok = m0 + 32 * i + (idx >> 3) < M && n0 + 32 * jp + (idx & 7) * 8 < N;
+                        ok = m0 + 32 * ip + (idx >> 3) < M && n0 + 64 * jp + (idx & 7) * 8 < N;
                     // Streaming store: D is not read again by this library, and lines that
                     // linger dirty in the L2 / Infinity Cache would be written back during the
                     // next, bandwidth-bound kernel instead of during this compute-bound one.
@@ -503,59 +539,62 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
             run(std::false_type{});
     };
 
-    // ---- prologue: two stages in flight, first half-step into registers ----------------
+    // The fragments a K step starts with: the upper half of A's and all of B's, from stage S.
+    auto read_first_set = [&](auto S) {
+        static_for<HM>([&](auto I) { read_a(S, I); });
+        static_for<TN>([&](auto J) { read_b(S, J); });
+    };
+
+    // ---- prologue: two stages in flight, the first K step's starting fragments into registers
     load_context(ld_tile);  // the grid never exceeds the tile count
     issue_all(0, I0{});
     issue_all(1, I1{});
-    Frags f0, f1;
     zero_acc();
     __builtin_amdgcn_s_waitcnt(kWaitAllVmLgkm);
     __syncthreads();
-    read_frags(f0, I0{}, I0{});
+    read_first_set(I0{});
 
-    // One K step out of stage S = 2 * NMFMA MFMA slots, in a fixed order (every slot ends with a
-    // scheduling fence).  On entry f0 holds the fragments of the first half-step.
-    //   slots [0, NF):        + LDS reads of the second half-step's fragments (stage S) into f1
-    //   after slot SYNC_A-1:  barrier: every wave is done reading stage S
-    //   slots [SYNC_A, ...):  + the loads that refill stage S with the stream's next K step,
-    //                         at most one per slot and with gaps: a wave's load blocks its
-    //                         instruction issue until the CU's address unit accepts it (16 cycles
-    //                         per 1 KB load, shared by the four waves), so bunched loads would
-    //                         starve the matrix pipe
-    //   after slot SYNC_B-1:  wait until only this step's PRE_B loads are in flight (the
-    //                         previous step's have then landed), barrier: the other stage is
-    //                         complete for every wave
-    //   slots [2*NMFMA-NF, 2*NMFMA): + LDS reads of the next K step's first fragments into f0
+    // One K step out of stage S = SLOTS MFMA slots in a fixed order (every slot ends with a
+    // scheduling fence).  On entry fa[0 .. HM) and all of fb hold this step's fragments.
+    //   slots [0, HM):         + LDS reads of this step's lower A fragments fa[HM .. TM) (stage S)
+    //   after slot SYNC_A-1:   barrier: every wave is done reading stage S
+    //   slots [SYNC_A, L_END): + the loads that refill stage S with the stream's next K step,
+    //                          at most one per slot and with gaps: a wave's load blocks its
+    //                          instruction issue until the CU's address unit accepts it (16 cycles
+    //                          per 1 KB load, shared by the four waves), so bunched loads would
+    //                          starve the matrix pipe
+    //   after slot SYNC_B-1:   wait until only this step's PRE_B loads are in flight (the
+    //                          previous step's have then landed), barrier: the other stage is
+    //                          complete for every wave
+    //   slots [HALF, SLOTS):   + LDS reads of the next K step's starting fragments from the other
+    //                          stage, each into the registers of a fragment that has just died:
+    //                          the upper A fragments at once, B fragment j when column j is done
     // The MFMAs issued just before a barrier keep the matrix pipe busy while the wave waits.
-    constexpr int NF = TM + TN;                       // fragments per half-step
-    constexpr int SLOTS = 2 * NMFMA;
-    // f1's fragment reads are spread over slots [0, F1_SPAN), f0's over [SYNC_B, SLOTS).  The two
-    // constants for the 16-MFMA half-steps of the 256x256 tile (MFMA slots between the last read
-    // of f1 and barrier A; slots over which f0's reads are spread) were chosen by measurement.
-    constexpr int kCoverSlots = 2, kF0Span = 12;
-    constexpr int F1_SPAN = NF < NMFMA / 2 ? NF : NMFMA / 2;
-    constexpr int F0_SPAN = NMFMA >= 16 ? kF0Span : F1_SPAN;
-    constexpr int SYNC_A = F1_SPAN + (NMFMA >= 16 ? kCoverSlots : 1);
-    constexpr int SYNC_B = SLOTS - F0_SPAN;
-    constexpr auto f1_slot = [](int n) { return n * F1_SPAN / NF; };            // fragment n (in read order)
-    constexpr auto f0_slot = [](int n) { return SYNC_B + n * F0_SPAN / NF; };
+    constexpr int SYNC_A = HM + (SLOTS >= 64 ? 8 : SLOTS >= 32 ? 4 : 1);  // the reads of slots [0, HM) are back by then
+    constexpr int SYNC_B = HALF - 2;
     constexpr int LOADS = A_LOADS + B_LOADS;
-    constexpr int LOAD_SLOTS = SLOTS - SYNC_A;
-    static_assert(SYNC_A <= SYNC_B && LOAD_SLOTS > 0, "schedule does not fit");
-    // load l goes into slot SYNC_A + floor(l * LOAD_SLOTS / LOADS): evenly spread
-    constexpr auto slot_of_load = [](int l) { return SYNC_A + l * LOAD_SLOTS / LOADS; };
+    constexpr int L_END = SLOTS;  // spread as thinly as possible (measured: better than leaving the last slots free)
+    static_assert(SYNC_A <= SYNC_B && L_END - SYNC_A >= LOADS / 2, "schedule does not fit");
+    constexpr auto slot_of_load = [](int l) { return SYNC_A + l * (L_END - SYNC_A) / LOADS; };
     constexpr int PRE_B = [&] {
         int n = 0;
         for (int l = 0; l < LOADS; ++l) n += slot_of_load(l) < SYNC_B;
         return n;
     }();
-    // i-major MFMA order needs fragments in the order a0, b0 .. b(TN-1), a1 .. a(TM-1)
-    constexpr auto frag_order = [](int n) { return n == 0 ? 0 : (n <= TN ? TM + n - 1 : n - TN); };
+    // B fragment j dies with the last MFMA of column j; the last columns' successors are read a
+    // little early (into spare registers) so that they are back when the next step needs them
+    constexpr auto slot_of_next_b = [](int j) {
+        const int s = HALF + (j + 1) * HM - 1;
+        return s < SLOTS - 3 ? s : SLOTS - 3;
+    };
     // s_waitcnt vmcnt(PRE_B) lgkmcnt(0)
     constexpr int kWaitB = (PRE_B & 15) | ((PRE_B >> 4) << 14) | 0x0070;
 
     auto kstep = [&](auto S, int fetch_kt) {
         constexpr int s = decltype(S)::value;
+        using OTHER = integral_constant<int, 1 - s>;
+        const uint8_t* ga = step_base_a(fetch_kt);
+        const uint8_t* gb = step_base_b(fetch_kt);
         static_for<SLOTS>([&](auto SLOT) {
             constexpr int slot = decltype(SLOT)::value;
             if constexpr (slot == SYNC_A) {
@@ -568,18 +607,26 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if constexpr (slot < NMFMA)
-                mfmas(f0, SLOT, integral_constant<int, slot + 1>{});
-            else
-                mfmas(f1, integral_constant<int, slot - NMFMA>{}, integral_constant<int, slot - NMFMA + 1>{});
-            static_for<NF>([&](auto F) {
-                constexpr int n = decltype(F)::value;
-                if constexpr (f1_slot(n) == slot) read_frag(f1, S, I1{}, integral_constant<int, frag_order(n)>{});
-                if constexpr (f0_slot(n) == slot)
-                    read_frag(f0, integral_constant<int, 1 - s>{}, I0{}, integral_constant<int, frag_order(n)>{});
+            mfma_slot(SLOT);
+            if constexpr (slot < HM) read_a(S, integral_constant<int, HM + slot>{});
+            if constexpr (slot >= HALF && slot < HALF + HM) read_a(OTHER{}, integral_constant<int, slot - HALF>{});
+            static_for<TN>([&](auto J) {
+                constexpr int j = decltype(J)::value;
+                if constexpr (slot_of_next_b(j) == slot) {
+                    if constexpr (slot < HALF + (j + 1) * HM - 1) {  // fb[j] is still needed: park its successor
+                        static_assert(j == TN - 1, "one spare fragment");
+                        const v8i keep = fb[j];
+                        read_b(OTHER{}, J);
+                        fb_early = fb[j];
+                        fb[j] = keep;
+                    } else {
+                        read_b(OTHER{}, J);
+                    }
+                }
             });
+            if constexpr (slot == SLOTS - 1 && slot_of_next_b(TN - 1) < SLOTS - 1) fb[TN - 1] = fb_early;
             static_for<LOADS>([&](auto L) {
-                if constexpr (slot_of_load(decltype(L)::value) == slot) issue_one(fetch_kt, S, L);
+                if constexpr (slot_of_load(decltype(L)::value) == slot) issue_one(ga, gb, S, L);
             });
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -601,12 +648,14 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
             kstep(I0{}, f);
             kstep(I1{}, f + 1);
         }
+        mfma_drain();
         epilogue(tile);
         zero_acc();
-        // The next tile's first fragments are read again here rather than kept in registers
-        // across the epilogue (the last K step already fetched them once): 64 registers less
-        // for the epilogue to fight over.  Stage 0 is complete since that step's second barrier.
-        read_frags(f0, I0{}, I0{});
+        // The next tile's starting fragments are read again here rather than kept in registers
+        // across the epilogue (the last K step already fetched them once): registers less for
+        // the epilogue to fight over.  Stage 0 is complete since that step's second barrier.
+        read_first_set(I0{});
+        asm volatile("s_nop 7");  // accumulators just written by ordinary instructions: let them settle
     }
     // no load may still be writing LDS when the workgroup ends
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
@@ -714,6 +763,48 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// split-K: sum of the ranges' partial results, scales, bf16
+// ---------------------------------------------------------------------------
+// partial[s][M][ldp] fp32, s < splits, added in the order s = 0, 1, ... (fixed: results are
+// reproducible run to run).  A thread owns eight consecutive n of one m.
+template <int GRAN>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial, int splits, int M,
+                                                            int N, int64_t ldp, const float* __restrict__ isa,
+                                                            const float* __restrict__ isb, uint16_t* __restrict__ D,
+                                                            int64_t ldd)
+{
+    const int chunks = N / 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)M * chunks) return;
+    const int m = (int)(idx / chunks), n = (int)(idx % chunks) * 8;
+    const float* p = partial + (int64_t)m * ldp + n;
+    const int64_t stride = (int64_t)M * ldp;
+    v4f lo = *reinterpret_cast<const v4f*>(p), hi = *reinterpret_cast<const v4f*>(p + 4);
+    for (int s = 1; s < splits; ++s) {
+        lo += *reinterpret_cast<const v4f*>(p + s * stride);
+        hi += *reinterpret_cast<const v4f*>(p + s * stride + 4);
+    }
+    float r[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    if constexpr (GRAN == F8_TENSORWISE) {
+        const float st = isa[0] * isb[0];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] *= st;
+    } else {
+        const float sa = isa[m];
+        const float4 s0 = *reinterpret_cast<const float4*>(isb + n), s1 = *reinterpret_cast<const float4*>(isb + n + 4);
+        const float sb[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) r[i] = (r[i] * sa) * sb[i];
+    }
+    uint4 o;
+    o.x = f32_to_bf16_bits(r[0]) | (f32_to_bf16_bits(r[1]) << 16);
+    o.y = f32_to_bf16_bits(r[2]) | (f32_to_bf16_bits(r[3]) << 16);
+    o.z = f32_to_bf16_bits(r[4]) | (f32_to_bf16_bits(r[5]) << 16);
+    o.w = f32_to_bf16_bits(r[6]) | (f32_to_bf16_bits(r[7]) << 16);
+    *reinterpret_cast<uint4*>(D + (int64_t)m * ldd + n) = o;
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 
@@ -741,10 +832,33 @@ static int cu_count()
     return n - n % kXcds;  // the persistent tile order assumes a multiple of the XCD count
 }
 
+// Number of contraction ranges for a product whose 256x256 tiles would occupy at most half of
+// the compute units, or 1.  A range must be a multiple of 256 (two LDS stages) and at least 1024
+// long, ranges x tiles must fit the compute units (one work item each), and the partial results
+// must fit the workspace.  Chosen by estimated time, in units of one whole-K 256x256 tile:
+// 1 / ranges + 0.04 for the fp32 epilogue + the reduction pass (a launch, ranges + 1/2 passes
+// over an M x N fp32 matrix at about 5 TB/s) against the best unsplit configuration.
+static int splitk_ranges(int M, int N, int K, int cus, double best_unsplit, size_t ws_bytes)
+{
+    const int64_t T = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
+    if (2 * T > cus || K < 2048) return 1;
+    const double tile_us = (double)(K / kBK) * 1.05;  // a K step of a 256x256 tile takes about 2100 cycles
+    int best = 1;
+    double best_cost = best_unsplit;
+    for (int s = 2; s <= 8; s *= 2) {
+        if (s * T > cus || K % (s * 2 * kBK) || K / s < 1024) break;
+        if ((size_t)s * (size_t)M * (size_t)N * sizeof(float) > ws_bytes) break;
+        const double reduce_us = 3.0 + (s + 0.5) * (double)M * (double)N * 4.0 / 5.0e6;
+        const double cost = 1.0 / s + 0.04 + reduce_us / tile_us;
+        if (cost < best_cost) best = s, best_cost = cost;
+    }
+    return best;
+}
+
 template <int FA, int FB, int GRAN, bool AKM, bool BKM>
 static void dispatch_tile(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
                           const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
-                          hipStream_t st)
+                          void* ws, size_t ws_bytes, hipStream_t st)
 {
     // Tile configuration by estimated time, in units of one 256x256 tile's time on one compute
     // unit: T tiles on `cus` persistent workgroups take ceil(T / cus) rounds; a 256x128 tile costs
@@ -766,6 +880,19 @@ static void dispatch_tile(int M, int N, int K, const uint8_t* A, int64_t lda, co
     const double c_half = rounds(tiles(256, 128)) * kHalfTile;
     const double c_quarter = rounds(tiles(128, 128)) * kQuarterTile;
     const bool rw = GRAN != F8_TENSORWISE;
+    if (ws && !amax_bits) {
+        const double best = c_full < c_half ? (c_full < c_quarter ? c_full : c_quarter) : (c_half < c_quarter ? c_half : c_quarter);
+        const int ranges = splitk_ranges(M, N, K, cus, best, ws_bytes);
+        if (ranges > 1) {
+            float* partial = static_cast<float*>(ws);
+            gemm_tile_kernel<256, 256, 2, 2, FA, FB, GRAN, false, AKM, BKM, true><<<(unsigned)(T * ranges), 256, 0, st>>>(
+                A, B, D, M, N, K, lda, ldb, ldd, isa, isb, tm, tn, nullptr, ranges, partial, (int64_t)N);
+            const int64_t threads = (int64_t)M * (N / 8);
+            splitk_reduce_kernel<GRAN><<<(unsigned)((threads + 255) / 256), 256, 0, st>>>(partial, ranges, M, N, (int64_t)N,
+                                                                                         isa, isb, D, ldd);
+            return;
+        }
+    }
 #define F8_TILE(BM_, BN_) launch_tile<BM_, BN_, 2, 2, FA, FB, GRAN, AKM, BKM>
     if (c_full <= c_half && c_full <= c_quarter) {
         if (split_rows) {
@@ -807,11 +934,11 @@ static void launch_generic(int M, int N, int K, const uint8_t* A, int64_t lda, c
 template <int LAYOUT, int FA, int FB, int GRAN>
 static void dispatch_layout(int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
                             const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
-                            hipStream_t st)
+                            void* ws, size_t ws_bytes, hipStream_t st)
 {
     if (K % (2 * kBK) == 0 && K > 0)
         dispatch_tile<FA, FB, GRAN, LAYOUT == F8_TN, LAYOUT != F8_NT>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd,
-                                                                       amax_bits, st);
+                                                                       amax_bits, ws, ws_bytes, st);
     else
         launch_generic<LAYOUT, FA, FB, GRAN>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
 }
@@ -820,12 +947,12 @@ static void dispatch_layout(int M, int N, int K, const uint8_t* A, int64_t lda, 
 template <int LAYOUT, int FA, int FB>
 static void gemm_formats(int g, int M, int N, int K, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
                          const float* isa, const float* isb, uint16_t* D, int64_t ldd, uint32_t* amax_bits,
-                         hipStream_t st)
+                         void* ws, size_t ws_bytes, hipStream_t st)
 {
     if (g == F8_TENSORWISE)
-        dispatch_layout<LAYOUT, FA, FB, F8_TENSORWISE>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+        dispatch_layout<LAYOUT, FA, FB, F8_TENSORWISE>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, ws, ws_bytes, st);
     else
-        dispatch_layout<LAYOUT, FA, FB, F8_ROWWISE>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, st);
+        dispatch_layout<LAYOUT, FA, FB, F8_ROWWISE>(M, N, K, A, lda, B, ldb, isa, isb, D, ldd, amax_bits, ws, ws_bytes, st);
 }
 
 }  // namespace f8

@@ -15,7 +15,8 @@ inline f8_status last_launch_status() { return hipGetLastError() == hipSuccess ?
 // Never less than kMinWorkspaceBytes: room for the per-block partial maxima of the kernels
 // whose grid does not depend on the shape (tensorwise amax, feed-forward glue).
 constexpr size_t kMinWorkspaceBytes = 8192;
-size_t workspace_bytes(int64_t max_rows, int64_t max_cols);
+size_t workspace_bytes(int64_t max_rows, int64_t max_cols);           // what f8_workspace_bytes returns
+size_t quantise_workspace_bytes(int64_t max_rows, int64_t max_cols);  // the partial maxima alone
 
 // amax -> scale -> cast of one validated tensor (dynamic scaling), any granularity.
 f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g, int fmt,
@@ -53,9 +54,14 @@ f8_status quantise_known_amax(const void* x, int64_t rows, int64_t cols, int64_t
                               float* amax_out, float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,
                               uint8_t* out_t, int64_t ld_out_t, hipStream_t st);
 
-// Validated GEMM launch (see f8_gemm); amax_d may be null.
+// Validated GEMM launch (see f8_gemm); amax_d may be null.  ws (nullable): device scratch of
+// ws_bytes for the fp32 partial results of a product that is better split along its
+// contraction (few output tiles, long contraction); without it such a product runs unsplit.
 f8_status gemm(int layout, int64_t M, int64_t N, int64_t K, const uint8_t* A, int fa, int64_t lda,
                const uint8_t* B, int fb, int64_t ldb, const float* isa, const float* isb, int g,
-               void* D, int64_t ldd, float* amax_d, hipStream_t st);
+               void* D, int64_t ldd, float* amax_d, hipStream_t st, void* ws = nullptr, size_t ws_bytes = 0);
+// Largest scratch a split product can use (ranges x output elements x 4 bytes, with ranges x tiles
+// at most one per compute unit): part of what workspace_bytes returns.
+constexpr size_t kSplitKMaxBytes = (size_t)256 * 256 * 256 * sizeof(float);
 
 }  // namespace f8

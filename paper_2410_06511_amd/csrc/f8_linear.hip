@@ -144,7 +144,7 @@ static f8_status gemm_fwd(const f8_linear_desc* d, const f8_saved* sv, void* Y, 
 // dW [N,K] = dY8 [M,N]^T . X8 [M,K]: contraction M, both read k-major; with transposed copies of
 //   both as dY8t [N,M] . (X8t [K,M])^T.  Rowwise: dY per column n, X per column k.
 static f8_status gemms_bwd(const f8_linear_desc* d, const f8_saved* sv, void* dX, float* dx_amax, void* dW,
-                           hipStream_t st)
+                           hipStream_t st, void* ws = nullptr, size_t ws_bytes = 0)
 {
     const int64_t M = d->M, K = d->K, N = d->N;
     const int gf = d->grad_format;
@@ -159,9 +159,9 @@ static f8_status gemms_bwd(const f8_linear_desc* d, const f8_saved* sv, void* dX
     if (s != F8_OK) return s;
     if (sv->dy.q_t && sv->x.q_t)
         return gemm(F8_NT, N, K, M, sv->dy.q_t, gf, M, sv->x.q_t, F8_E4M3, M, rw ? sv->dy.inv_scale_t : sv->dy.inv_scale,
-                    rw ? sv->x.inv_scale_t : sv->x.inv_scale, d->granularity, dW, K, nullptr, st);
+                    rw ? sv->x.inv_scale_t : sv->x.inv_scale, d->granularity, dW, K, nullptr, st, ws, ws_bytes);
     return gemm(F8_TN, N, K, M, sv->dy.q, gf, N, sv->x.q, F8_E4M3, K, sv->dy.inv_scale, sv->x.inv_scale,
-                d->granularity, dW, K, nullptr, st);
+                d->granularity, dW, K, nullptr, st, ws, ws_bytes);
 }
 
 // ---- the forward that allocates nothing and takes no workspace ---------------------------
@@ -197,7 +197,7 @@ static f8_status scratch_of_current_device(void** out)
 static size_t fwd_scratch_need(const f8_linear_desc* d)
 {
     if (d->granularity != F8_ROWWISE) return kMinWorkspaceBytes;
-    const size_t x = workspace_bytes(d->M, d->K), w = workspace_bytes(d->N, d->K);
+    const size_t x = quantise_workspace_bytes(d->M, d->K), w = quantise_workspace_bytes(d->N, d->K);
     return x > w ? x : w;
 }
 
@@ -247,7 +247,7 @@ f8_status f8_quantise(const void* t_bf16, int64_t rows, int64_t cols, f8_granula
     if (!aligned16(t_bf16)) return F8_ERR_ALIGN;
     f8_status s = check_q(q, g == F8_ROWWISE);
     if (s != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < workspace_bytes(rows, cols)) return F8_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes_ < quantise_workspace_bytes(rows, cols)) return F8_ERR_WORKSPACE;
     return quantise_both(t_bf16, rows, cols, g == F8_ROWWISE, fmt, q, workspace, (hipStream_t)stream);
 }
 
@@ -283,7 +283,7 @@ f8_status f8_linear_bwd(const f8_linear_desc* d, const void* dY, f8_saved* saved
     hipStream_t st = (hipStream_t)stream;
     if ((s = quantise_both(dY, d->M, d->N, d->granularity == F8_ROWWISE, d->grad_format, &saved->dy, workspace, st)) != F8_OK)
         return s;
-    return gemms_bwd(d, saved, dX, nullptr, dW, st);
+    return gemms_bwd(d, saved, dX, nullptr, dW, st, workspace, workspace_bytes_);
 }
 
 f8_status f8_linear_fwd_scaled(const f8_linear_desc* d, const f8_scaling_state* state, const void* X,
@@ -316,7 +316,7 @@ f8_status f8_linear_bwd_scaled(const f8_linear_desc* d, const f8_scaling_state* 
     if ((s = quantise_scaled(dY, d->M, d->N, d->grad_format, state->mode, state->history_len, state->hist_dy,
                              state->scale_dy, &saved->dy, workspace, workspace_bytes_, st)) != F8_OK)
         return s;
-    return gemms_bwd(d, saved, dX, nullptr, dW, st);
+    return gemms_bwd(d, saved, dX, nullptr, dW, st, workspace, workspace_bytes_);
 }
 
 f8_status f8_linear_fwd_chained(const f8_linear_desc* d, const void* X, const float* x_amax, const void* W,
@@ -352,7 +352,7 @@ f8_status f8_linear_bwd_chained(const f8_linear_desc* d, const void* dY, const f
     else
         s = quantise_both(dY, M, N, false, gf, &saved->dy, workspace, st);
     if (s != F8_OK) return s;
-    return gemms_bwd(d, saved, dX, dx_amax, dW, st);
+    return gemms_bwd(d, saved, dX, dx_amax, dW, st, workspace, workspace_bytes_);
 }
 
 f8_status f8_silu_mul_quantise_delayed(const void* ab_bf16, int64_t M, int64_t H, f8_format fmt, float* history,
@@ -365,7 +365,7 @@ f8_status f8_silu_mul_quantise_delayed(const void* ab_bf16, int64_t M, int64_t H
     if (!aligned16(ab_bf16)) return F8_ERR_ALIGN;
     f8_status s = check_q(q, false);
     if (s != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < workspace_bytes(M, H)) return F8_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes_ < quantise_workspace_bytes(M, H)) return F8_ERR_WORKSPACE;
     return quantise_scaled(ab_bf16, M, H, fmt, F8_DELAYED, history_len, history, scale, q, workspace, workspace_bytes_,
                            (hipStream_t)stream, 1);
 }
@@ -381,7 +381,7 @@ f8_status f8_silu_mul_bwd_quantise_delayed(const void* ab_bf16, const void* dh_b
     if (!aligned16(ab_bf16) || !aligned16(dh_bf16)) return F8_ERR_ALIGN;
     f8_status s = check_q(q, false);
     if (s != F8_OK) return s;
-    if (!workspace || workspace_bytes_ < workspace_bytes(M, 2 * H)) return F8_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes_ < quantise_workspace_bytes(M, 2 * H)) return F8_ERR_WORKSPACE;
     return quantise_scaled(ab_bf16, M, 2 * H, fmt, F8_DELAYED, history_len, history, scale, q, workspace,
                            workspace_bytes_, (hipStream_t)stream, 2, dh_bf16);
 }

@@ -79,18 +79,23 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u4v* __restrict__
     if ((acc.x | acc.y | acc.z | acc.w) == 0x9E3779B9u) sink[0] = acc.x;  // practically never true
 }
 
-// The shader-clock counter is read per accelerator die (XCD), and the dies' counters need not
-// agree: every workgroup files its reading under the die it runs on (XCC_ID, hardware register
-// 20, bits 3:0), so that two samples are compared die by die.  Workgroups on the same die write
-// nearly the same values to the same slot; whichever lands last stays.
+// The shader-clock counters of different compute units need not agree (they are not one chip-wide
+// counter), so every workgroup files its reading under the compute unit it runs on: the die
+// (XCC_ID, hardware register 20, bits 3:0) and the shader-engine / array / CU fields of HW_ID
+// (hardware register 4, bits 15:8).  Two samples are then compared unit by unit.  Workgroups that
+// land on the same unit write nearly the same values to the same slot; whichever lands last stays.
+constexpr int kClockSlots = 2048;  // 8 dies x 256 values of HW_ID[15:8]
+
 __global__ void probe_clock_kernel(uint64_t* __restrict__ out)
 {
     const uint32_t xcc = __builtin_amdgcn_s_getreg(20 | (0 << 6) | ((4 - 1) << 11)) & 7u;
+    const uint32_t cu = __builtin_amdgcn_s_getreg(4 | (8 << 6) | ((8 - 1) << 11)) & 255u;
     const uint64_t c = __builtin_readcyclecounter();      // shader clock cycles
     const uint64_t r = __builtin_amdgcn_s_memrealtime();  // constant 100 MHz
-    out[4 * xcc + 1] = c;
-    out[4 * xcc + 2] = r;
-    out[4 * xcc + 0] = 1;  // this die's slot is filled
+    uint64_t* slot = out + 4 * (xcc * 256 + cu);
+    slot[1] = c;
+    slot[2] = r;
+    slot[0] = 1;  // this unit's slot is filled
 }
 
 static int probe_cu_count()
@@ -145,7 +150,7 @@ f8_status f8_probe_read(const void* src, int64_t bytes, uint32_t* sink, void* st
 f8_status f8_probe_clock(uint64_t* out, void* stream)
 {
     if (!out) return F8_ERR_NULL;
-    probe_clock_kernel<<<64, 1, 0, (hipStream_t)stream>>>(out);  // consecutive workgroups go round the dies
+    probe_clock_kernel<<<4096, 64, 0, (hipStream_t)stream>>>(out);  // enough workgroups to visit most compute units
     return last_launch_status();
 }
 

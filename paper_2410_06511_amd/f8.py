@@ -23,7 +23,7 @@ _lib = None
 _i64, _int, _p = C.c_int64, C.c_int, C.c_void_p
 
 EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_cast", "f8_encode_f32",
-           "f8_amax_cast", "f8_gemm", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
+           "f8_amax_cast", "f8_gemm", "f8_gemm_ws", "f8_linear_fwd", "f8_linear_bwd", "f8_cast_amax",
            "f8_amax_history_push", "f8_linear_fwd_scaled", "f8_linear_bwd_scaled",
            "f8_linear_fwd_chained", "f8_linear_bwd_chained", "f8_quantise",
            "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq",
@@ -74,6 +74,8 @@ def lib():
         l.f8_amax_cast.argtypes = [_p, _i64, _i64, _i64, _int, _int, _p, _p, _p, _p, _i64, _p, _i64, _p,
                                    C.c_size_t, _p]
         l.f8_gemm.argtypes = [_int, _i64, _i64, _i64, _p, _int, _i64, _p, _int, _i64, _p, _p, _int, _p, _i64, _p, _p]
+        l.f8_gemm_ws.argtypes = [_int, _i64, _i64, _i64, _p, _int, _i64, _p, _int, _i64, _p, _p, _int, _p, _i64, _p, _p,
+                                 C.c_size_t, _p]
         l.f8_linear_fwd.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         l.f8_linear_bwd.argtypes = [C.POINTER(LinearDesc), _p, C.POINTER(SavedStruct), _p, _p, _p, C.c_size_t, _p]
         l.f8_cast_amax.argtypes = [_p, _i64, _i64, _i64, _p, _int, _p, _i64, _p, _i64, _p, _p, C.c_size_t, _p]
@@ -181,10 +183,17 @@ def amax_cast(x, g, fmt, amax_out, scale_out, inv_scale_out, out=None, out_t=Non
                               _ptr(out_t), 0 if out_t is None else out_t.stride(0), wp, wb, _stream(stream)))
 
 
-def gemm(layout, M, N, K, A, fa, B, fb, inv_scale_a, inv_scale_b, g, D, stream=None, amax_d=None):
-    _check(lib().f8_gemm(layout, M, N, K, _ptr(A), fa, A.stride(0), _ptr(B), fb, B.stride(0),
-                         _ptr(inv_scale_a), _ptr(inv_scale_b), g, _ptr(D), D.stride(0), _ptr(amax_d),
-                         _stream(stream)))
+def gemm(layout, M, N, K, A, fa, B, fb, inv_scale_a, inv_scale_b, g, D, stream=None, amax_d=None, workspace=None):
+    """f8_gemm, or f8_gemm_ws when a workspace is given."""
+    if workspace is None:
+        _check(lib().f8_gemm(layout, M, N, K, _ptr(A), fa, A.stride(0), _ptr(B), fb, B.stride(0),
+                             _ptr(inv_scale_a), _ptr(inv_scale_b), g, _ptr(D), D.stride(0), _ptr(amax_d),
+                             _stream(stream)))
+        return
+    wp, wb = _ws(workspace)
+    _check(lib().f8_gemm_ws(layout, M, N, K, _ptr(A), fa, A.stride(0), _ptr(B), fb, B.stride(0),
+                            _ptr(inv_scale_a), _ptr(inv_scale_b), g, _ptr(D), D.stride(0), _ptr(amax_d), wp, wb,
+                            _stream(stream)))
 
 
 class QTensor:
@@ -430,17 +439,21 @@ def probe_read(src, sink, stream=None):
     _check(lib().f8_probe_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream(stream)))
 
 
+PROBE_CLOCK_SLOTS = 2048
+
+
 def probe_clock(out, stream=None):
-    """out: 32 x int64 on the device, zeroed: per die d, out[4d] = 1, out[4d+1] = shader-clock cycles,
-    out[4d+2] = 100 MHz ticks."""
+    """out: 4 * PROBE_CLOCK_SLOTS int64 on the device, zeroed: per compute unit u, out[4u] = 1,
+    out[4u+1] = shader-clock cycles, out[4u+2] = 100 MHz ticks."""
     _check(lib().f8_probe_clock(_ptr(out), _stream(stream)))
 
 
 def clock_ghz_between(before, after):
-    """Mean shader clock between two probe_clock samples (host lists of 32 ints), averaged over
-    the dies that filled their slot in both; None if no die did."""
-    vals = []
-    for d in range(8):
-        if before[4 * d] and after[4 * d] and after[4 * d + 2] > before[4 * d + 2]:
-            vals.append(0.1 * (after[4 * d + 1] - before[4 * d + 1]) / (after[4 * d + 2] - before[4 * d + 2]))
-    return sum(vals) / len(vals) if vals else None
+    """Mean shader clock between two probe_clock samples (CPU int64 tensors of 4 * PROBE_CLOCK_SLOTS),
+    the median over the compute units that filled their slot in both; None if none did."""
+    b, a = before.view(-1, 4), after.view(-1, 4)
+    ok = (b[:, 0] == 1) & (a[:, 0] == 1) & (a[:, 2] > b[:, 2])
+    if not bool(ok.any()):
+        return None
+    ghz = 0.1 * (a[ok, 1] - b[ok, 1]).double() / (a[ok, 2] - b[ok, 2]).double()
+    return float(ghz.median())

@@ -30,12 +30,15 @@ def shapes_of(layout, M, N, K):
     return sa, sb
 
 
-def run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, g):
+def run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, g, workspace=None):
     Ad, Bd = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
     sa = torch.from_numpy(np.atleast_1d(isa).astype(np.float32)).cuda()
     sb = torch.from_numpy(np.atleast_1d(isb).astype(np.float32)).cuda()
     D = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
-    f8.gemm(layout, M, N, K, Ad, fa, Bd, fb, sa, sb, g, D)
+    f8.gemm(layout, M, N, K, Ad, fa, Bd, fb, sa, sb, g, D, workspace=workspace)
+    if workspace is not None:
+        torch.cuda.synchronize()
+        return bits(D)
     # the same product with the output amax taken in the epilogue: identical D, and the amax
     # is exactly the largest magnitude among the stored bf16 values
     D2 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
@@ -148,6 +151,57 @@ def test_gemm_exact_arithmetic_long_contraction():
     b = torch.from_numpy(o.decode(B, o.E4M3).astype(np.float64))
     closed = ((a @ b) * 2.0 ** -14).to(torch.bfloat16).view(torch.uint16).numpy()
     assert np.array_equal(got, closed)
+
+
+@pytest.mark.parametrize("layout", [o.NT, o.NN, o.TN])
+@pytest.mark.parametrize("g", [f8.TENSORWISE, f8.ROWWISE])
+@pytest.mark.parametrize("M,N,K", [(512, 1024, 4096), (272, 400, 2048), (2048, 4096, 8192)])
+def test_gemm_split_contraction_exact_arithmetic(layout, g, M, N, K):
+    """f8_gemm_ws on products with few output tiles and a long contraction (8, 4 and 128 tiles of
+    256 x 256): computed in contraction ranges whose fp32 sums a second kernel adds.  On the
+    exact-arithmetic grid every partial sum is exact, so the result is bit for bit the fp64
+    product rounded once to bf16 - and equal to the unsplit f8_gemm."""
+    rng = np.random.default_rng(13 + layout + M)
+    vals = np.array([0, 64, -64, 128, -128, 256, -256, 448, -448], np.float32)
+    grid = o.encode(vals, o.E4M3)
+    sa, sb = shapes_of(layout, M, N, K)
+    A, B = grid[rng.integers(0, 9, sa)], grid[rng.integers(0, 9, sb)]
+    if g == f8.TENSORWISE:
+        isa, isb = np.float32(2.0 ** -7), np.float32(2.0 ** -6)
+        sc = np.float64(2.0 ** -13)
+    else:
+        isa = (2.0 ** -(5.0 + (np.arange(M) % 4))).astype(np.float32)
+        isb = (2.0 ** -(6.0 + (np.arange(N) % 3))).astype(np.float32)
+        sc = isa.astype(np.float64)[:, None] * isb.astype(np.float64)[None, :]
+    ws = f8.new_workspace(M, N)
+    got = run_gemm(layout, M, N, K, A, o.E4M3, B, o.E4M3, isa, isb, g, workspace=ws)
+    a = torch.from_numpy(o.decode(A, o.E4M3).astype(np.float64))
+    b = torch.from_numpy(o.decode(B, o.E4M3).astype(np.float64))
+    exact = {o.NT: lambda: a @ b.T, o.NN: lambda: a @ b, o.TN: lambda: a.T @ b}[layout]() * torch.from_numpy(np.asarray(sc))
+    assert np.array_equal(got, exact.to(torch.bfloat16).view(torch.uint16).numpy())
+    assert np.array_equal(got, run_gemm(layout, M, N, K, A, o.E4M3, B, o.E4M3, isa, isb, g))
+
+
+@pytest.mark.parametrize("layout,fa,fb", [(o.TN, o.E5M2, o.E4M3), (o.NT, o.E4M3, o.E4M3), (o.NN, o.E4M3, o.E5M2)])
+def test_gemm_split_contraction_random_codes(layout, fa, fb):
+    """Random codes: the split product against the oracle and the fp64 bound element by element,
+    deterministic over repeated calls, and a workspace too small for the partial sums gives the
+    unsplit product's bits."""
+    M, N, K = 1024, 528, 4096
+    rng = np.random.default_rng(layout + 400)
+    sa, sb = shapes_of(layout, M, N, K)
+    A, B = rand_codes(rng, sa, fa), rand_codes(rng, sb, fb)
+    isa, isb = np.float32(0.0131), np.float32(0.73)
+    ws = f8.new_workspace(M, N)
+    got = run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, f8.TENSORWISE, workspace=ws)
+    assert_gemm_close(got, o.gemm(layout, A, fa, B, fb, isa, isb), (layout, fa, fb))
+    d64, dabs = o.gemm_f64(layout, A, fa, B, fb, isa, isb)
+    assert_gemm_tight(got, d64, dabs, K, (layout, fa, fb))
+    for _ in range(2):
+        assert np.array_equal(got, run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, f8.TENSORWISE, workspace=ws))
+    small = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    unsplit = run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, f8.TENSORWISE)
+    assert np.array_equal(unsplit, run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, f8.TENSORWISE, workspace=small))
 
 
 def test_gemm_output_guard_band_and_ldd():
