@@ -5,7 +5,7 @@ import torch
 
 import oracle as o
 from paper_2410_06511_amd import f8
-from helpers import bits, u8, assert_gemm_close, assert_gemm_tight
+from helpers import bits, u8, assert_gemm_close, assert_gemm_tight, group_max_sum
 
 pytestmark = pytest.mark.gpu
 
@@ -68,7 +68,7 @@ def test_gemm_small_full_compare(layout, fa, fb, M, N, K):
     ref = o.gemm(layout, A, fa, B, fb, isa, isb)
     assert_gemm_close(got, ref, (layout, fa, fb, M, N, K))
     d64, dabs = o.gemm_f64(layout, A, fa, B, fb, isa, isb)
-    assert_gemm_tight(got, d64, dabs, K, (layout, fa, fb, M, N, K))
+    assert_gemm_tight(got, d64, dabs, K, (layout, fa, fb, M, N, K), group_max_sum(layout, A, fa, B, fb, isa, isb))
 
 
 @pytest.mark.parametrize("layout", [o.NT, o.NN, o.TN])
@@ -81,7 +81,7 @@ def test_gemm_rowwise_scales(layout, M, N, K):
     isb = (rng.uniform(0.5, 2.0, N) * 1e-1).astype(np.float32)
     got = run_gemm(layout, M, N, K, A, o.E4M3, B, o.E4M3, isa, isb, f8.ROWWISE)
     d64, dabs = o.gemm_f64(layout, A, o.E4M3, B, o.E4M3, isa, isb, o.ROWWISE)
-    assert_gemm_tight(got, d64, dabs, K, (layout, M, N, K))
+    assert_gemm_tight(got, d64, dabs, K, (layout, M, N, K), group_max_sum(layout, A, o.E4M3, B, o.E4M3, isa, isb, True))
     assert_gemm_close(got, o.gemm(layout, A, o.E4M3, B, o.E4M3, isa, isb, o.ROWWISE))
 
 
@@ -196,7 +196,7 @@ def test_gemm_split_contraction_random_codes(layout, fa, fb):
     got = run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, f8.TENSORWISE, workspace=ws)
     assert_gemm_close(got, o.gemm(layout, A, fa, B, fb, isa, isb), (layout, fa, fb))
     d64, dabs = o.gemm_f64(layout, A, fa, B, fb, isa, isb)
-    assert_gemm_tight(got, d64, dabs, K, (layout, fa, fb))
+    assert_gemm_tight(got, d64, dabs, K, (layout, fa, fb), group_max_sum(layout, A, fa, B, fb, isa, isb))
     for _ in range(2):
         assert np.array_equal(got, run_gemm(layout, M, N, K, A, fa, B, fb, isa, isb, f8.TENSORWISE, workspace=ws))
     small = torch.empty(4096, dtype=torch.uint8, device="cuda")
