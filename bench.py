@@ -407,6 +407,8 @@ def main():
                                                 "bytes_written_per_launch": n, "launches": 4}}))
         return
 
+    if args.workload == "attention":
+        return attention_main(args)
     default_run = args.workload is None
     w = wl.WORKLOADS[args.workload or HEADLINE]
     if w.key == "llama8b_ffn":
@@ -616,6 +618,61 @@ def ffn_main(args, w):
         "legs": legs,
     }
     print(json.dumps(out))
+
+
+def attention_main(args):
+    """The block's causal grouped-query attention alone, forward and backward, at the Llama 3.1 8B
+    shape (one sequence of 8192 tokens, 32 query and 8 key/value heads of 128) on seeded inputs;
+    also the program that the attention kernels' counter summaries under profiles/ are collected
+    on.  `value` is the attention's own rate on causal FLOPs (4 S^2 Hq hd / 2 forward, 2.5 times that
+    backward), against the bf16 matrix peak."""
+    import torch
+    from paper_2410_06511_amd import f8
+    B, S, Hq, Hkv, HD = 1, 8192, 32, 8, 128
+    M = B * S
+    g = torch.Generator("cpu")
+    g.manual_seed(8192)
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    qkv = torch.randn((M, (Hq + 2 * Hkv) * HD), generator=g).bfloat16().cuda()
+    do = (torch.randn((M, Hq * HD), generator=g) * 0.01).bfloat16().cuda()
+    q, k, v = qkv[:, :Hq * HD], qkv[:, Hq * HD:(Hq + Hkv) * HD], qkv[:, (Hq + Hkv) * HD:]
+    vt, o = torch.empty((Hkv * HD, M), **bf), torch.empty((M, Hq * HD), **bf)
+    qt, kt, dot = torch.empty((Hq * HD, M), **bf), torch.empty((Hkv * HD, M), **bf), torch.empty((Hq * HD, M), **bf)
+    lse, delta = torch.empty((Hq, M), device="cuda"), torch.empty((Hq, M), device="cuda")
+    dqkv = torch.zeros((M, (Hq + 2 * Hkv) * HD), **bf)
+    dq, dk, dv = dqkv[:, :Hq * HD], dqkv[:, Hq * HD:(Hq + Hkv) * HD], dqkv[:, (Hq + Hkv) * HD:]
+    ws = torch.empty(f8.sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, HD), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    for src, dst in ((v, vt), (q, qt), (k, kt), (do, dot)):
+        f8.transpose_bf16(src, dst)
+    fwd = lambda: f8.sdpa_fwd(q, k, vt, B, S, Hq, Hkv, HD, o, lse)
+    bwd = lambda: f8.sdpa_bwd(q, qt, k, kt, v, o, do, dot, lse, B, S, Hq, Hkv, HD, dq, dk, dv, delta, ws)
+    for _ in range(args.warmup):
+        fwd(), bwd()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * args.steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev[0].record(stream)
+    for i in range(args.steps):
+        fwd()
+        ev[2 * i + 1].record(stream)
+        bwd()
+        ev[2 * i + 2].record(stream)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    f_ms = sum(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(args.steps)) / args.steps
+    b_ms = sum(ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(args.steps)) / args.steps
+    f_fl = 4 * B * S * S * Hq * HD // 2
+    fl = f_fl + 5 * f_fl // 2
+    tf = fl / (ms_per_step * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "causal attention fwd+bwd TFLOP/s (bf16 MFMA)", "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 x bf16 -> fp32", "data": "synthetic",
+        "config": {"workload": f"attention: causal GQA, {B} x {S} tokens, {Hq} query / {Hkv} key-value heads of {HD}"},
+        "forward_ms": round(f_ms, 4), "backward_ms": round(b_ms, 4),
+        "roofline": {"kernel": "sdpa_fwd_kernel + sdpa_bwd_dq_kernel + sdpa_bwd_dkv_kernel", "bound": "mfma", "achieved": round(tf, 1),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tf / PEAK_BF16_TFLOPS, 4), "traffic": None}}))
 
 
 def layer_main(args, w):

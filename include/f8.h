@@ -448,7 +448,7 @@ f8_status f8_linear_bwd_dyq(const f8_linear_desc* d, f8_saved* saved, void* dX, 
 
 /*
  * The bf16 operations that join the Float8 linears of one transformer block
- * (Section 2.2.2 applies Float8 to the linear layers only; Section 2.1 names
+ * (Section 2.2.4 applies Float8 to the linear layers only; Section 2.1 names
  * the TransformerBlock as the unit that is wrapped, sharded and recomputed).
  *
  * f8_rope: rotary position embedding of x [M, n_heads * hd] bf16 (row pitch

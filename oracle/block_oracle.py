@@ -1,10 +1,11 @@
 """CPU oracle for the bf16 operations that join the Float8 linears of one transformer block
-(Section 2.2.2 of the paper applies Float8 to the linear layers only; everything between them
+(Section 2.2.4 of the paper applies Float8 to the linear layers only; everything between them
 stays in bf16): rotary position embedding, causal grouped-query attention, the backward of
 RMSNorm and the residual addition.
 
-Test infrastructure only: plain numpy in fp64 on the values of the bf16 inputs, one rounding to
-bf16 at the end, no blocking, no online softmax, no fusion.  The product never imports this.
+Test infrastructure only: plain numpy in fp64 on the values of the bf16 inputs, rounded at the end
+to fp32 and from there to bf16 (two roundings to nearest even), no blocking, no online softmax, no
+fusion.  The product never imports this.
 
 Each function is the textbook definition written out:
   rope          (x0, x1) -> (x0 cos t - x1 sin t, x0 sin t + x1 cos t), t = pos * theta^(-2i/hd)

@@ -433,7 +433,8 @@ void f8o_history_push(float* history, int64_t len, float amax_new, int fmt, floa
  * With W1 and W3 stacked into one linear its output row is [a | b] (H values each) and the
  * next linear's input is h = silu(a) * b.  The paper does not spell this out (it trains
  * Llama 3.1 models); it is the textbook definition, evaluated here in double precision and
- * rounded once to bf16.  The backward formulas are its derivatives:
+ * rounded to fp32 and from there to bf16 (two roundings to nearest even: within half a bf16
+ * unit plus one part in 2^16 of the single rounding).  The backward formulas are its derivatives:
  *   dh/da = b * s'(a),  s'(t) = sig(t) * (1 + t * (1 - sig(t))),  sig(t) = 1 / (1 + e^-t)
  *   dh/db = silu(a).
  * Each function also returns the amax of what it wrote (the next cast's input). */
@@ -477,7 +478,8 @@ void f8o_silu_mul_bwd(const uint16_t* ab, const uint16_t* dh, int64_t M, int64_t
 
 /* RMS normalisation in front of the attention and feed-forward linears of a Llama block:
  *   y[m, :] = x[m, :] * rstd[m] * g,   rstd[m] = 1 / sqrt(mean_d x[m, d]^2 + eps)
- * The textbook definition, in double precision, one rounding to bf16 (y) or fp32 (rstd).  Only
+ * The textbook definition, in double precision, rounded to fp32 and from there to bf16 (y), or
+ * once to fp32 (rstd).  Only
  * the forward is here: it is the producer of a Float8 linear's input; the backward of the
  * normalisation does not touch the Float8 path. */
 void f8o_rmsnorm(const uint16_t* x, const uint16_t* g, int64_t M, int64_t D, double eps, uint16_t* y,

@@ -1,6 +1,6 @@
 """Call sequence of one Llama transformer block, forward and backward, on the C-ABI entry points
 (Section 2.1: the TransformerBlock is the unit the paper wraps, shards and recomputes; Section
-2.2.2: its linear layers run in Float8, everything between them in bf16).
+2.2.4: its linear layers run in Float8, everything between them in bf16).
 
 Buffers and the order of calls only: every step runs in the library's kernels.
 
@@ -25,6 +25,7 @@ class TransformerBlock:
         self.delayed, self.gfmt = scaling == "delayed", grad_format
         if self.delayed:
             self.st_qkv, self.st_o, self.st_13, self.st_2 = (f8.ScalingState(f8.DELAYED, history_len, device) for _ in range(4))
+            self._replay = None   # static states on the saved scales, for recomputation (made on first use)
         self.B, self.S, self.D, self.H, self.Hq, self.Hkv, self.hd = B, S, D, H, Hq, Hkv, hd
         self.eps, self.theta = eps, theta
         M = self.M = B * S
@@ -67,13 +68,38 @@ class TransformerBlock:
         Hq, Hkv, hd = self.Hq, self.Hkv, self.hd
         return t[:, :Hq * hd], t[:, Hq * hd:(Hq + Hkv) * hd], t[:, (Hq + Hkv) * hd:]
 
-    def forward_stages(self, x, w, stream=None):
+    def forward_stages(self, x, w, stream=None, replay=False):
         """w: dict with g1, g2 [D], Wqkv [(Hq + 2 Hkv) hd, D], Wo [D, D], W13 [2 H, D], W2 [D, H] (bf16).
-        Returns [(name, call, flops, algorithmic bytes)] in execution order."""
+        Returns [(name, call, flops, algorithmic bytes)] in execution order.
+        replay (delayed scaling only): the forward run AGAIN inside the backward.  It must
+        reproduce the forward whose output fed the loss, so every cast uses the scale that forward
+        used (kept next to the codes) and no amax history is touched; the glue is run unfused (h is
+        written and cast with the saved scale: the same codes)."""
         s, M, D, H, B, S = self, self.M, self.D, self.H, self.B, self.S
         Hq, Hkv, hd = self.Hq, self.Hkv, self.hd
         q, k, v = self._slices(self.qkv)
         att_flops = 4 * B * S * S * Hq * hd // 2
+        if self.delayed and replay:
+            if self._replay is None:
+                self._replay = tuple(f8.ReplayState(sv) for sv in (s.s_qkv, s.s_o, s.s_13, s.s_2))
+            r_qkv, r_o, r_13, r_2 = self._replay
+            return [
+                ("rmsnorm 1", lambda: f8.rmsnorm(x, w["g1"], s.eps, s.xn, s.rstd1, None, None, stream), 0, 4 * M * D),
+                ("linear wq|wk|wv fwd", lambda: f8.linear_fwd_scaled(s.d_qkv, r_qkv, s.xn, w["Wqkv"], s.qkv, s.s_qkv, s.ws, stream),
+                 2 * M * D * s.Nqkv, 0),
+                ("rope q (+ transposed copy)", lambda: f8.rope(q, S, Hq, hd, s.qr, s.qt, s.theta, False, stream), 0, 6 * M * Hq * hd),
+                ("rope k (+ transposed copy)", lambda: f8.rope(k, S, Hkv, hd, s.kr, s.kt, s.theta, False, stream), 0, 6 * M * Hkv * hd),
+                ("transpose v", lambda: f8.transpose_bf16(v, s.vt, stream), 0, 4 * M * Hkv * hd),
+                ("attention fwd", lambda: f8.sdpa_fwd(s.qr, s.kr, s.vt, B, S, Hq, Hkv, hd, s.att, s.lse, stream), att_flops, 0),
+                ("linear wo fwd", lambda: f8.linear_fwd_scaled(s.d_o, r_o, s.att, w["Wo"], s.yo, s.s_o, s.ws, stream), 2 * M * D * D, 0),
+                ("residual 1", lambda: f8.add(x, s.yo, s.h1, stream), 0, 6 * M * D),
+                ("rmsnorm 2", lambda: f8.rmsnorm(s.h1, w["g2"], s.eps, s.hn, s.rstd2, None, None, stream), 0, 4 * M * D),
+                ("linear w1|w3 fwd", lambda: f8.linear_fwd_scaled(s.d_13, r_13, s.hn, w["W13"], s.ab, s.s_13, s.ws, stream),
+                 2 * M * D * 2 * H, 0),
+                ("silu_mul", lambda: f8.silu_mul(s.ab, s.hh, None, None, stream), 0, 6 * M * H),
+                ("linear w2 fwd", lambda: f8.linear_fwd_scaled(s.d_2, r_2, s.hh, w["W2"], s.y2, s.s_2, s.ws, stream), 2 * M * H * D, 0),
+                ("residual 2", lambda: f8.add(s.h1, s.y2, s.out, stream), 0, 6 * M * D),
+            ]
         if self.delayed:
             return [
                 ("rmsnorm 1", lambda: f8.rmsnorm(x, w["g1"], s.eps, s.xn, s.rstd1, None, None, stream), 0, 4 * M * D),
@@ -179,7 +205,9 @@ class TransformerBlock:
     def backward(self, x, w, dout, stream=None, recompute=False):
         """recompute (Section 2.2.1, activation checkpointing):
         True / "full": run the whole forward again first; the backward then depends on x and the
-        weights only.
+        weights only (and, under delayed scaling, on the scales the first forward used, which
+        stay next to the fp8 codes: the second forward casts with them and leaves the amax
+        histories alone).
         "selective": keep the outputs of the matrix products and of the attention (and the fp8
         codes saved by the linears) and run again only the cheap operations whose results the
         backward reads: the normalisation statistics, the rotated q and k with their transposed
@@ -189,7 +217,8 @@ class TransformerBlock:
                 if name in self.SELECTIVE:
                     call()
         elif recompute:
-            self.forward(x, w, stream)
+            for _, call, _, _ in self.forward_stages(x, w, stream, replay=self.delayed):
+                call()
         for _, call, _, _ in self.backward_stages(x, w, dout, stream):
             call()
         return self.dx

@@ -1,5 +1,5 @@
 // Causal grouped-query attention in bf16 between the Float8 linears of a transformer block
-// (Section 2.2.2 keeps everything but the linear layers in bf16).  Flash-style: scores are never
+// (Section 2.2.4 applies Float8 to the linear layers only: everything else stays in bf16).  Flash-style: scores are never
 // written; bf16 MFMA (v_mfma_f32_32x32x16_bf16) with fp32 accumulation and an online softmax.
 //
 // Orientation.  Of a 32x32 MFMA result, a lane holds one column (the row index of the SECOND
@@ -11,6 +11,8 @@
 // only has to present the same keys in the same slots: it is read from a copy that is contiguous
 // along tokens (V^T here; Q^T, K^T, dO^T in the backward), which the producers write on the way
 // (f8_rope's transposed output, f8_transpose_bf16).  No operand is transposed in registers.
+#include <atomic>
+
 #include "f8_device.hpp"
 #include "f8_host.hpp"
 
@@ -661,13 +663,21 @@ f8_status f8_sdpa_bwd(const void* q_bf16, int64_t ldq, const void* qt_bf16, cons
     if (group > 1 && (!workspace || workspace_bytes_ < f8_sdpa_bwd_workspace_bytes(B, S, Hq, Hkv, hd))) return F8_ERR_WORKSPACE;
     if (group > 1 && !aligned16(workspace)) return F8_ERR_ALIGN;
     if (B == 0 || S == 0) return F8_OK;
-    // more dynamic LDS than the default limit of a launch: raised once per process (the
-    // initialisation of a function-local static is thread-safe)
-    static const bool configured =
-        hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel<kDqWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) == hipSuccess &&
-        hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<true, kDkQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkLds) == hipSuccess &&
-        hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) == hipSuccess;
-    if (!configured) return F8_ERR_LAUNCH;
+    // More dynamic LDS than the default limit of a launch: raised once per process.  Only success
+    // is remembered, so that a failure (a call made while the stream is being captured, a
+    // transient error) is tried again by the next call instead of being final.
+    static std::atomic<bool> configured{false};
+    if (!configured.load(std::memory_order_acquire)) {
+        const bool ok =
+            hipFuncSetAttribute((const void*)sdpa_bwd_dq_kernel<kDqWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDqLds) == hipSuccess &&
+            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<true, kDkQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDkLds) == hipSuccess &&
+            hipFuncSetAttribute((const void*)sdpa_bwd_dkv_kernel<false, kDvQs, kDkvWaves>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kDvLds) == hipSuccess;
+        if (!ok) {
+            (void)hipGetLastError();
+            return F8_ERR_LAUNCH;
+        }
+        configured.store(true, std::memory_order_release);
+    }
     hipStream_t st = (hipStream_t)stream;
     const int64_t M = B * S;
     if ((S + 255) / 256 * Hq * B > (int64_t)0x7FFFFFFF) return F8_ERR_SHAPE;  // one block per 256 tokens and head

@@ -1,4 +1,4 @@
-// The bf16 operations that join the Float8 linears of one transformer block (Section 2.2.2
+// The bf16 operations that join the Float8 linears of one transformer block (Section 2.2.4
 // applies Float8 to the linear layers only; everything between them stays in bf16): rotary
 // position embedding (also writing the transposed copy that the attention backward contracts
 // over tokens), a plain bf16 transposition, the residual addition and the backward of RMSNorm.

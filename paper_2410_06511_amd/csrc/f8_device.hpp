@@ -86,12 +86,9 @@ __device__ inline uint32_t encode_hw2(float y0, float y1)
     return (uint32_t)r & 0xFFFFu;
 }
 
-// The casts use the conversion instruction: the software rounding costs about a dozen integer
-// operations per element, which makes the cast ALU-bound instead of HBM-bound.  The GPU tests
-// compare the two encoders over every fp32 bit pattern.
-#ifndef F8_ENCODE_HW
-#define F8_ENCODE_HW 1
-#endif
+// The casts use the conversion instruction (encode_hw2): the integer rounding (encode_sw) costs
+// about a dozen operations per element, which would make the cast ALU-bound instead of HBM-bound.
+// The GPU tests compare the two encoders over every fp32 bit pattern (f8_encode_f32).
 
 // scale, saturate, round: two bf16 (one 32-bit word) -> two codes in bits 0..15.
 template <int FMT>
@@ -106,11 +103,7 @@ __device__ inline uint32_t cast2(uint32_t w, float s0, float s1)
     y0 = y0 < -FM ? -FM : y0;
     y1 = y1 > FM ? FM : y1;
     y1 = y1 < -FM ? -FM : y1;
-#if F8_ENCODE_HW
     return encode_hw2<FMT>(y0, y1);
-#else
-    return encode_sw<FMT>(y0) | (encode_sw<FMT>(y1) << 8);
-#endif
 }
 
 // Eight bf16 (a 16-byte chunk) with one scale -> eight codes (two words).

@@ -298,6 +298,21 @@ class ScalingState:
         return self._struct
 
 
+class ReplayState:
+    """f8_scaling_state in STATIC mode whose scales are the ones a Saved already holds, i.e. the
+    scales its last forward (and backward) used.  Running a forward again with it reproduces that
+    forward's codes bit for bit and records nothing in any amax history: what recomputation inside
+    the backward (activation checkpointing) needs under delayed scaling."""
+
+    def __init__(self, saved):
+        self.mode, self.history_len, self.saved = STATIC, 1, saved
+        self._struct = ScalingStateStruct(STATIC, 1, None, None, None, _ptr(saved.x.scale), _ptr(saved.w.scale),
+                                          _ptr(saved.dy.scale))
+
+    def struct(self):
+        return self._struct
+
+
 def linear_fwd_scaled(desc, state, X, W, Y, saved, workspace, stream=None):
     wp, wb = _ws(workspace)
     _check(lib().f8_linear_fwd_scaled(C.byref(desc), C.byref(state.struct()), _ptr(X), _ptr(W), _ptr(Y),

@@ -214,3 +214,34 @@ def test_transformer_block_delayed_scaling_converges_to_dynamic():
     torch.cuda.synchronize()
     assert not torch.equal(fresh.out.view(torch.int16), dyn.out.view(torch.int16))
 
+
+
+def test_delayed_scaling_recomputed_forward_reproduces_the_first():
+    """Activation checkpointing under delayed scaling: the forward that runs again inside the
+    backward casts with the scales the first forward used and pushes nothing into the amax
+    histories.  Over several steps with changing inputs, a block that recomputes gives the bits
+    of one that does not: outputs, gradients, histories and next-step scales."""
+    B, S, Hq, Hkv, hd, H = 1, 272, 2, 1, 128, 512
+    D, M = Hq * hd, B * S
+    w = {"g1": (gen((D,), 33, 0.3) + 1).bfloat16().cuda(), "g2": (gen((D,), 34, 0.3) + 1).bfloat16().cuda(),
+         "Wqkv": gen(((Hq + 2 * Hkv) * hd, D), 35, 0.05).cuda(), "Wo": gen((D, D), 36, 0.05).cuda(),
+         "W13": gen((2 * H, D), 37, 0.05).cuda(), "W2": gen((D, H), 38, 0.05).cuda()}
+    steps = [(gen((M, D), 40 + i, 1.0 + 0.7 * i).cuda(), gen((M, D), 50 + i, 1e-2 * (1 + i)).cuda()) for i in range(4)]
+    kept = TransformerBlock(B, S, D, H, Hq, Hkv, hd, scaling="delayed", history_len=3)
+    redo = TransformerBlock(B, S, D, H, Hq, Hkv, hd, scaling="delayed", history_len=3)
+    names = ("out", "dx", "dWqkv", "dWo", "dW13", "dW2", "dg1", "dg2")
+    for x, dout in steps:
+        kept.forward(x, w)
+        kept.backward(x, w, dout)
+        redo.forward(x, w)
+        out_first = redo.out.clone()
+        for n in ("xn", "qkv", "qr", "kr", "qt", "kt", "vt", "att", "yo", "h1", "hn", "ab", "y2", "out"):
+            getattr(redo, n).fill_(7.0)      # every activation is gone: the backward has to rebuild them
+        redo.backward(x, w, dout, recompute=True)
+        torch.cuda.synchronize()
+        assert torch.equal(redo.out.view(torch.int16), out_first.view(torch.int16))
+        for n in names:
+            assert torch.equal(getattr(kept, n).view(torch.uint8), getattr(redo, n).view(torch.uint8)), n
+        for a, b in zip((kept.st_qkv, kept.st_o, kept.st_13, kept.st_2), (redo.st_qkv, redo.st_o, redo.st_13, redo.st_2)):
+            for m in ("hist_x", "hist_w", "hist_dy", "scale_x", "scale_w", "scale_dy"):
+                assert torch.equal(getattr(a, m), getattr(b, m)), m
