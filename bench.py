@@ -212,8 +212,12 @@ def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, input
     for li, s in enumerate(states):
         M, K, N = s.lin.M, s.lin.K, s.lin.N
         sv = s.saved
-        ops.append(("cast", li, cast_op(s.X, sv.x, f8.E4M3), s.X.numel(), "X"))
-        ops.append(("cast", li, cast_op(s.W, sv.w, f8.E4M3), s.W.numel(), "W"))
+        if args.scaling == "dynamic":   # the forward's own quantisation: X and W in one call
+            ops.append(("cast", li, (lambda s=s, sv=sv: f8.linear_fwd_quantise(s.desc, s.X, s.W, sv, ws, stream)),
+                        s.X.numel() + s.W.numel(), "X+W"))
+        else:
+            ops.append(("cast", li, cast_op(s.X, sv.x, f8.E4M3), s.X.numel(), "X"))
+            ops.append(("cast", li, cast_op(s.W, sv.w, f8.E4M3), s.W.numel(), "W"))
         ops.append(("gemm", li, (lambda s=s, sv=sv, M=M, K=K, N=N: f8.gemm(
             f8.NT, M, N, K, sv.x.q, f8.E4M3, sv.w.q, f8.E4M3, sv.x.inv_scale, sv.w.inv_scale, g, s.Y, stream)),
             2 * M * K * N, "Y = X W^T"))

@@ -268,6 +268,18 @@ f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, v
                         f8_saved* saved, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The quantisation half of f8_linear_fwd alone (steps 1-3 of dynamic scaling,
+ * Section 2.2.4, for X and W; no product): fills saved->x and saved->w exactly
+ * as f8_linear_fwd does and with the same launches - tensorwise without
+ * transposed copies, ONE amax launch and ONE cast launch serve both tensors
+ * (the grid is split between them by size).  f8_linear_fwd is this call
+ * followed by f8_gemm(F8_NT) on the codes.  Same arguments, checks and
+ * workspace as f8_linear_fwd, minus Y.
+ */
+f8_status f8_linear_fwd_quantise(const f8_linear_desc* d, const void* X, const void* W, f8_saved* saved,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * f8_linear_fwd with the weight already quantised: saved->w holds W's codes
  * and its scales from an earlier f8_linear_fwd (or f8_quantise) — weights
  * change once per optimizer step, not per micro-batch.  (Under dynamic scaling

@@ -362,6 +362,106 @@ __global__ __launch_bounds__(kThreads) void cast_stream_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// tensorwise dynamic quantisation of one or two contiguous tensors per launch
+// ---------------------------------------------------------------------------
+// A linear's forward quantises X and W: with one launch per tensor and step the small tensor's
+// two launches cost more in launch and drain than in memory time.  Here the grid of the amax
+// launch and of the cast launch is split between the tensors in proportion to their sizes, so
+// that both parts end together.  Each tensor has its own range of partial maxima.
+struct StreamJob {
+    const uint4* x;      // n chunks of eight bf16
+    uint2* out;          // n chunks of eight codes
+    int64_t n;
+    uint32_t* partial;   // amax_blocks partial maxima
+    float *amax, *scale, *inv;
+    int amax_blocks, cast_blocks;
+};
+struct StreamJobs {
+    StreamJob j[2];  // blocks [0, j[0].blocks) work on j[0], the rest on j[1]
+};
+
+// Measured on the 8B block's tensors (16384 tokens): four loads in flight per thread beat two and
+// eight; 512 partial maxima in all beat 256 and 1024 (every cast block reduces them again); the
+// cast is fastest when a block makes one pass of four chunks per thread (32768 blocks cover 268 M
+// elements that way; 8192 blocks were 4 % slower, 4096 9 %).
+constexpr int kJobPartials = 512;
+constexpr int kJobCastBlocks = 32768;
+static_assert((size_t)2 * kJobPartials * sizeof(uint32_t) <= kMinWorkspaceBytes, "two ranges of partials fit the minimum");
+
+__global__ __launch_bounds__(kThreads) void amax_jobs_kernel(const StreamJobs jobs)
+{
+    __shared__ uint32_t red[kWaves];
+    const bool second = (int)blockIdx.x >= jobs.j[0].amax_blocks;
+    const StreamJob J = second ? jobs.j[1] : jobs.j[0];
+    const int b = (int)blockIdx.x - (second ? jobs.j[0].amax_blocks : 0);
+    const uint4* __restrict__ x = J.x;
+    const int64_t n = J.n, stride = (int64_t)J.amax_blocks * kThreads;
+    int64_t i = (int64_t)b * kThreads + threadIdx.x;
+    uint32_t acc = 0;
+    // four independent 16-byte loads in flight per thread
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const uint4 v0 = x[i], v1 = x[i + stride], v2 = x[i + 2 * stride], v3 = x[i + 3 * stride];
+        acc = absmax_acc(absmax_acc(absmax_acc(absmax_acc(acc, v0), v1), v2), v3);
+    }
+    for (; i < n; i += stride) acc = absmax_acc(acc, x[i]);
+    const uint32_t m = block_max_u32<kWaves>(pk_collapse(acc), red);
+    if (threadIdx.x == 0) J.partial[b] = m;
+}
+
+// Every block derives its tensor's scale from that tensor's partial maxima; the first block of
+// each tensor also publishes amax, scale and 1/scale.  A block's first four chunks are requested
+// before the partial maxima are reduced, so that the reduction's latency (a load, a wave
+// reduction, two barriers) passes while they are on their way.
+template <int FMT>
+__global__ __launch_bounds__(kThreads) void cast_jobs_kernel(const StreamJobs jobs)
+{
+    __shared__ uint32_t red[kWaves];
+    const bool second = (int)blockIdx.x >= jobs.j[0].cast_blocks;
+    const StreamJob J = second ? jobs.j[1] : jobs.j[0];
+    const int b = (int)blockIdx.x - (second ? jobs.j[0].cast_blocks : 0);
+    const uint4* __restrict__ x = J.x;
+    uint2* __restrict__ out = J.out;
+    const int64_t n = J.n, stride = (int64_t)J.cast_blocks * kThreads;
+    int64_t i = (int64_t)b * kThreads + threadIdx.x;
+
+    constexpr int PER_THREAD = (kJobPartials + kThreads - 1) / kThreads;
+    uint32_t p[PER_THREAD];
+#pragma unroll
+    for (int k = 0; k < PER_THREAD; ++k) {
+        const int idx = k * kThreads + (int)threadIdx.x;
+        p[k] = idx < J.amax_blocks ? J.partial[idx] : 0u;
+    }
+    const bool first_full = i + 3 * stride < n;
+    uint4 v0 = {}, v1 = {}, v2 = {}, v3 = {};
+    if (first_full) v0 = x[i], v1 = x[i + stride], v2 = x[i + 2 * stride], v3 = x[i + 3 * stride];
+    uint32_t m = p[0];
+#pragma unroll
+    for (int k = 1; k < PER_THREAD; ++k) m = p[k] > m ? p[k] : m;
+    const float a = mag_to_float(block_max_u32<kWaves>(m, red));
+    const float s = scale_from_amax(a, Fmt<FMT>::fmax);
+    if (b == 0 && threadIdx.x == 0) {
+        J.amax[0] = a;
+        J.scale[0] = s;
+        J.inv[0] = 1.0f / s;
+    }
+    if (first_full) {
+        out[i] = cast8<FMT>(v0, s);
+        out[i + stride] = cast8<FMT>(v1, s);
+        out[i + 2 * stride] = cast8<FMT>(v2, s);
+        out[i + 3 * stride] = cast8<FMT>(v3, s);
+        i += 4 * stride;
+    }
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const uint4 w0 = x[i], w1 = x[i + stride], w2 = x[i + 2 * stride], w3 = x[i + 3 * stride];
+        out[i] = cast8<FMT>(w0, s);
+        out[i + stride] = cast8<FMT>(w1, s);
+        out[i + 2 * stride] = cast8<FMT>(w2, s);
+        out[i + 3 * stride] = cast8<FMT>(w3, s);
+    }
+    for (; i < n; i += stride) out[i] = cast8<FMT>(x[i], s);
+}
+
+// ---------------------------------------------------------------------------
 // cast, tiled form: 128 x 128 tile per block, writes out and/or out_t.
 // The transposed copy goes through LDS so that both global writes are made of
 // full 128-byte row segments.
@@ -679,7 +779,7 @@ static void launch_cast_t(const void* x, int64_t rows, int64_t cols, int64_t ld,
     if (!out_t && GRAN != F8_COLWISE) {
         int64_t chunks = rows * (cols / 8);
         int64_t nb = (chunks + kThreads * 4 - 1) / (kThreads * 4);
-        if (nb > 8192) nb = 8192;
+        if (nb > kJobCastBlocks) nb = kJobCastBlocks;
         if (GRAN == F8_ROWWISE && nb > rows) nb = rows;
         cast_stream_kernel<FMT, GRAN, DYN><<<(unsigned)nb, kThreads, 0, st>>>(
             (const uint4*)x, rows, cols / 8, ld / 8, scale, partial, npartial, amax_out, scale_out,
@@ -739,12 +839,84 @@ static f8_status check_cast_outputs(int64_t rows, int64_t cols, const uint8_t* o
     return F8_OK;
 }
 
+// Grid shares of the job launches.  The amax launch has at most kJobPartials blocks in all, the
+// cast launch at most kJobCastBlocks; a tensor's share is proportional to its size, and a thread
+// has at least four chunks to work on.
+static void job_shares(int64_t n0, int64_t n1, int total, int* b0, int* b1)
+{
+    const int64_t per_block = (int64_t)kThreads * 4;
+    const int64_t want0 = (n0 + per_block - 1) / per_block, want1 = (n1 + per_block - 1) / per_block;
+    if (want0 + want1 <= total) {
+        *b0 = (int)want0, *b1 = (int)want1;
+        return;
+    }
+    int64_t s1 = n1 > 0 ? (int64_t)((double)total * (double)n1 / (double)(n0 + n1)) : 0;
+    if (n1 > 0 && s1 < 1) s1 = 1;
+    if (s1 > want1) s1 = want1;
+    int64_t s0 = total - s1;
+    if (s0 > want0) s0 = want0;
+    *b0 = (int)s0, *b1 = (int)s1;
+}
+
+// Tensorwise dynamic quantisation of one or two checked, contiguous, non-empty tensors (n1 = 0:
+// one) without transposed copies: two launches in all.  ws: kMinWorkspaceBytes.
+struct StreamTensor {
+    const void* x;
+    int64_t n;  // elements, a multiple of 8
+    float *amax, *scale, *inv;
+    uint8_t* out;
+};
+static f8_status quantise_stream(const StreamTensor& t0, const StreamTensor* t1, int fmt, void* ws, hipStream_t st)
+{
+    StreamJobs jobs{};
+    const StreamTensor* t[2] = {&t0, t1};
+    const int64_t n0 = t0.n / 8, n1 = t1 ? t1->n / 8 : 0;
+    int ab[2], cb[2];
+    job_shares(n0, n1, kJobPartials, &ab[0], &ab[1]);
+    job_shares(n0, n1, kJobCastBlocks, &cb[0], &cb[1]);
+    for (int k = 0; k < 2; ++k) {
+        StreamJob& J = jobs.j[k];
+        if (!t[k]) continue;
+        J.x = (const uint4*)t[k]->x, J.out = (uint2*)t[k]->out, J.n = t[k]->n / 8;
+        J.partial = (uint32_t*)ws + k * kJobPartials;
+        J.amax = t[k]->amax, J.scale = t[k]->scale, J.inv = t[k]->inv;
+        J.amax_blocks = ab[k], J.cast_blocks = cb[k];
+    }
+    amax_jobs_kernel<<<(unsigned)(ab[0] + ab[1]), kThreads, 0, st>>>(jobs);
+    if (fmt == F8_E4M3) cast_jobs_kernel<F8_E4M3><<<(unsigned)(cb[0] + cb[1]), kThreads, 0, st>>>(jobs);
+    else cast_jobs_kernel<F8_E5M2><<<(unsigned)(cb[0] + cb[1]), kThreads, 0, st>>>(jobs);
+    return last_launch_status();
+}
+
+static inline bool streamable(int64_t rows, int64_t cols, int64_t ld, int64_t ld_out, const uint8_t* out, const uint8_t* out_t)
+{
+    return rows > 0 && cols > 0 && ld == cols && ld_out == cols && out && !out_t;
+}
+
+// X and W of a linear's forward (tensorwise, same format, contiguous): both in two launches when
+// neither wants a transposed copy, else one after the other.
+f8_status quantise_pair(const void* x0, int64_t rows0, int64_t cols0, float* amax0, float* scale0, float* inv0,
+                        uint8_t* out0, uint8_t* out_t0, const void* x1, int64_t rows1, int64_t cols1, float* amax1,
+                        float* scale1, float* inv1, uint8_t* out1, uint8_t* out_t1, int fmt, void* ws, hipStream_t st)
+{
+    if (streamable(rows0, cols0, cols0, cols0, out0, out_t0) && streamable(rows1, cols1, cols1, cols1, out1, out_t1)) {
+        const StreamTensor a{x0, rows0 * cols0, amax0, scale0, inv0, out0}, b{x1, rows1 * cols1, amax1, scale1, inv1, out1};
+        // the larger tensor's blocks first, the smaller one's fill the tail
+        return a.n >= b.n ? quantise_stream(a, &b, fmt, ws, st) : quantise_stream(b, &a, fmt, ws, st);
+    }
+    f8_status s = quantise(x0, rows0, cols0, cols0, F8_TENSORWISE, fmt, amax0, scale0, inv0, out0, cols0, out_t0, rows0, ws, st);
+    if (s != F8_OK) return s;
+    return quantise(x1, rows1, cols1, cols1, F8_TENSORWISE, fmt, amax1, scale1, inv1, out1, cols1, out_t1, rows1, ws, st);
+}
+
 // Dynamic-scaling quantisation of one checked tensor (used by f8_amax_cast and the linear).
 f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g, int fmt,
                    float* amax_out, float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,
                    uint8_t* out_t, int64_t ld_out_t, void* ws, hipStream_t st)
 {
     const float fm = fmax_of(fmt);
+    if (g == F8_TENSORWISE && streamable(rows, cols, ld, ld_out, out, out_t))
+        return quantise_stream(StreamTensor{x, rows * cols, amax_out, scale_out, inv_out, out}, nullptr, fmt, ws, st);
     if (g == F8_TENSORWISE && rows > 0 && cols > 0) {
         // partial maxima, then the cast derives the scale from them itself: two launches
         const int nb = tensor_partial_blocks(rows, cols);

@@ -23,6 +23,13 @@ f8_status quantise(const void* x, int64_t rows, int64_t cols, int64_t ld, int g,
                    float* amax_out, float* scale_out, float* inv_out, uint8_t* out, int64_t ld_out,
                    uint8_t* out_t, int64_t ld_out_t, void* ws, hipStream_t st);
 
+// Tensorwise dynamic quantisation of two validated contiguous tensors of one format (a forward's X
+// and W; out_t nullable as in quantise): one amax launch and one cast launch for both when neither
+// wants a transposed copy.  ws: kMinWorkspaceBytes at least.
+f8_status quantise_pair(const void* x0, int64_t rows0, int64_t cols0, float* amax0, float* scale0, float* inv0,
+                        uint8_t* out0, uint8_t* out_t0, const void* x1, int64_t rows1, int64_t cols1, float* amax1,
+                        float* scale1, float* inv1, uint8_t* out1, uint8_t* out_t1, int fmt, void* ws, hipStream_t st);
+
 // Delayed / static scaling pieces (tensorwise, validated arguments).
 // cast with a given scale, leaving one partial maximum per 128x128 tile in ws
 // glue = 1: x is [rows, 2 * cols] = [a | b] (ld = its row length), the tensor cast is bf16(silu(a) * b);

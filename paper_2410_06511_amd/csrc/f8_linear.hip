@@ -68,6 +68,21 @@ static f8_status quantise_both(const void* T, int64_t rows, int64_t cols, bool r
     return cast_rows_and_cols(T, rows, cols, cols, fmt, q->scale, q->scale_t, q->q, cols, q->q_t, rows, st);
 }
 
+// X and W of a forward under dynamic scaling.  Tensorwise: one amax launch and one cast launch
+// for the two tensors together.
+static f8_status quantise_xw(const f8_linear_desc* d, const void* X, const void* W, const f8_saved* saved, void* ws,
+                             hipStream_t st)
+{
+    if (d->granularity != F8_ROWWISE) {
+        const f8_qtensor *x = &saved->x, *w = &saved->w;
+        return quantise_pair(X, d->M, d->K, x->amax, x->scale, x->inv_scale, x->q, x->q_t, W, d->N, d->K, w->amax,
+                             w->scale, w->inv_scale, w->q, w->q_t, F8_E4M3, ws, st);
+    }
+    f8_status s = quantise_both(X, d->M, d->K, true, F8_E4M3, &saved->x, ws, st);
+    if (s != F8_OK) return s;
+    return quantise_both(W, d->N, d->K, true, F8_E4M3, &saved->w, ws, st);
+}
+
 // One tensor under delayed or static scaling: cast with the state's scale into both
 // orientations; delayed also records the tensor's amax and derives the next scale.
 static f8_status quantise_scaled(const void* T, int64_t rows, int64_t cols, int fmt, int mode, int64_t hist_len,
@@ -216,11 +231,9 @@ f8_status f8_linear_fwd_noalloc(const f8_linear_desc* d, const void* X, const vo
     void* ws = nullptr;
     if ((s = scratch_of_current_device(&ws)) != F8_OK) return s;
     hipStream_t st = (hipStream_t)stream;
-    const bool rw = d->granularity == F8_ROWWISE;
     // the partial maxima are written before they are read within each quantisation: nothing in
     // the scratch has to start at zero
-    if ((s = quantise_both(X, d->M, d->K, rw, F8_E4M3, &saved->x, ws, st)) != F8_OK) return s;
-    if ((s = quantise_both(W, d->N, d->K, rw, F8_E4M3, &saved->w, ws, st)) != F8_OK) return s;
+    if ((s = quantise_xw(d, X, W, saved, ws, st)) != F8_OK) return s;
     return gemm_fwd(d, saved, Y, nullptr, st);
 }
 
@@ -257,10 +270,17 @@ f8_status f8_linear_fwd(const f8_linear_desc* d, const void* X, const void* W, v
     f8_status s = check_fwd(d, false, X, W, Y, saved, workspace, workspace_bytes_);
     if (s != F8_OK) return s;
     hipStream_t st = (hipStream_t)stream;
-    const bool rw = d->granularity == F8_ROWWISE;
-    if ((s = quantise_both(X, d->M, d->K, rw, F8_E4M3, &saved->x, workspace, st)) != F8_OK) return s;
-    if ((s = quantise_both(W, d->N, d->K, rw, F8_E4M3, &saved->w, workspace, st)) != F8_OK) return s;
+    if ((s = quantise_xw(d, X, W, saved, workspace, st)) != F8_OK) return s;
     return gemm_fwd(d, saved, Y, nullptr, st);
+}
+
+f8_status f8_linear_fwd_quantise(const f8_linear_desc* d, const void* X, const void* W, f8_saved* saved,
+                                 void* workspace, size_t workspace_bytes_, void* stream)
+{
+    // X stands in for Y in the shared checks, which only test it for NULL and alignment
+    f8_status s = check_fwd(d, false, X, W, X, saved, workspace, workspace_bytes_);
+    if (s != F8_OK) return s;
+    return quantise_xw(d, X, W, saved, workspace, (hipStream_t)stream);
 }
 
 f8_status f8_linear_fwd_wq(const f8_linear_desc* d, const void* X, void* Y, f8_saved* saved, void* workspace,
@@ -327,13 +347,15 @@ f8_status f8_linear_fwd_chained(const f8_linear_desc* d, const void* X, const fl
     if (s != F8_OK) return s;
     hipStream_t st = (hipStream_t)stream;
     const int64_t M = d->M, K = d->K, N = d->N;
-    if (x_amax)
+    if (x_amax) {
         s = quantise_known_amax(X, M, K, K, F8_E4M3, x_amax, saved->x.amax, saved->x.scale, saved->x.inv_scale,
                                 saved->x.q, K, saved->x.q_t, M, st);
-    else
-        s = quantise_both(X, M, K, false, F8_E4M3, &saved->x, workspace, st);
+        if (s != F8_OK) return s;
+        s = quantise_both(W, N, K, false, F8_E4M3, &saved->w, workspace, st);
+    } else {
+        s = quantise_xw(d, X, W, saved, workspace, st);
+    }
     if (s != F8_OK) return s;
-    if ((s = quantise_both(W, N, K, false, F8_E4M3, &saved->w, workspace, st)) != F8_OK) return s;
     return gemm_fwd(d, saved, Y, y_amax, st);
 }
 

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u4v* __restrict__
 // (XCC_ID, hardware register 20, bits 3:0) and the shader-engine / array / CU fields of HW_ID
 // (hardware register 4, bits 15:8).  Two samples are then compared unit by unit.  Workgroups that
 // land on the same unit write nearly the same values to the same slot; whichever lands last stays.
-constexpr int kClockSlots = 2048;  // 8 dies x 256 values of HW_ID[15:8]
+static_assert(F8_PROBE_CLOCK_SLOTS == 8 * 256, "one slot per die and value of HW_ID[15:8]");
 
 __global__ void probe_clock_kernel(uint64_t* __restrict__ out)
 {

@@ -29,7 +29,7 @@ EXPORTS = ["f8_workspace_bytes", "f8_status_string", "f8_amax", "f8_scale", "f8_
            "f8_silu_mul", "f8_silu_mul_bwd", "f8_rmsnorm", "f8_silu_mul_quantise_delayed", "f8_linear_fwd_xq",
            "f8_silu_mul_bwd_quantise_delayed", "f8_linear_bwd_dyq",
            "f8_rope", "f8_transpose_bf16", "f8_add", "f8_rmsnorm_bwd", "f8_sdpa_fwd", "f8_sdpa_bwd", "f8_sdpa_bwd_workspace_bytes",
-           "f8_rmsnorm_bwd_add", "f8_linear_fwd_wq", "f8_linear_fwd_noalloc",
+           "f8_rmsnorm_bwd_add", "f8_linear_fwd_wq", "f8_linear_fwd_noalloc", "f8_linear_fwd_quantise",
            "f8_probe_mfma", "f8_probe_copy", "f8_probe_read", "f8_probe_clock"]
 
 
@@ -78,6 +78,7 @@ def lib():
                                  C.c_size_t, _p]
         l.f8_linear_fwd.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         l.f8_linear_bwd.argtypes = [C.POINTER(LinearDesc), _p, C.POINTER(SavedStruct), _p, _p, _p, C.c_size_t, _p]
+        l.f8_linear_fwd_quantise.argtypes = [C.POINTER(LinearDesc), _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         l.f8_cast_amax.argtypes = [_p, _i64, _i64, _i64, _p, _int, _p, _i64, _p, _i64, _p, _p, C.c_size_t, _p]
         l.f8_amax_history_push.argtypes = [_p, _i64, _p, _int, _p, _p, _p]
         l.f8_linear_fwd_scaled.argtypes = [C.POINTER(LinearDesc), C.POINTER(ScalingStateStruct), _p, _p, _p,
@@ -247,6 +248,12 @@ def linear_fwd(desc, X, W, Y, saved, workspace, stream=None):
     wp, wb = _ws(workspace)
     _check(lib().f8_linear_fwd(C.byref(desc), _ptr(X), _ptr(W), _ptr(Y), C.byref(saved.struct()), wp, wb,
                                _stream(stream)))
+
+
+def linear_fwd_quantise(desc, X, W, saved, workspace, stream=None):
+    """The quantisation half of linear_fwd: X and W into saved.x, saved.w, no product."""
+    wp, wb = _ws(workspace)
+    _check(lib().f8_linear_fwd_quantise(C.byref(desc), _ptr(X), _ptr(W), C.byref(saved.struct()), wp, wb, _stream(stream)))
 
 
 def linear_fwd_noalloc(desc, X, W, Y, saved, stream=None):

@@ -180,6 +180,35 @@ def test_full_size_linear(key, li, rowwise, grad_fmt, transposed):
         sampled_check("dW", bits(dW), o.TN, qdyc, grad_fmt, qxc, o.E4M3, isdyc, isxc, g, rng)
 
 
+@pytest.mark.parametrize("M,K,N,transposed", [(16, 16, 16, False), (272, 336, 208, False), (16, 4096, 2048, False),
+                                              (4096, 4096, 1024, False), (2064, 2048, 4112, False), (272, 336, 208, True)])
+def test_forward_quantisation_of_x_and_w_together(M, K, N, transposed):
+    """f8_linear_fwd_quantise: X and W in one amax launch and one cast launch, the grid split between
+    them by size (X the larger, W the larger, both larger than one launch's block budget so that
+    the shares are proportional, tiny).  Each tensor's largest magnitude sits where only the last or
+    the first thread of its share looks.  Bit-exact against the oracle, and the same bits as
+    quantising each tensor by itself."""
+    g = torch.Generator("cpu")
+    g.manual_seed(1234 + M + N)
+    X, W = wl.randn_bf16((M, K), 1.0, 0, generator=g), wl.randn_bf16((N, K), 0.02, 0, generator=g)
+    X[-1, -1] = 37.5
+    W[0, 0] = -0.75
+    desc = f8.linear_desc(M, K, N, False)
+    ws = f8.new_workspace(max(M, K, N), max(M, K, N))
+    both, single = f8.Saved(M, K, N, False, transposed=transposed), f8.Saved(M, K, N, False, transposed=transposed)
+    Xd, Wd = X.cuda(), W.cuda()
+    f8.linear_fwd_quantise(desc, Xd, Wd, both, ws)
+    f8.quantise(Xd, f8.TENSORWISE, f8.E4M3, single.x, ws)
+    f8.quantise(Wd, f8.TENSORWISE, f8.E4M3, single.w, ws)
+    torch.cuda.synchronize()
+    for got, alone, t in ((both.x, single.x, X), (both.w, single.w, W)):
+        a, sc, inv, q = o.amax_cast(bits(t), o.TENSORWISE, o.E4M3)
+        assert np.array_equal(f32(got.amax), a) and np.array_equal(f32(got.scale), sc) and np.array_equal(f32(got.inv_scale), inv)
+        assert np.array_equal(u8(got.q), q)
+        assert qt_matches(got, q.T)
+        assert torch.equal(got.q, alone.q) and torch.equal(got.scale, alone.scale)
+
+
 @pytest.mark.parametrize("rowwise", [False, True])
 def test_forward_with_kept_weight_codes(rowwise):
     """A second micro-batch against the weight codes kept from the first: the same bits as a full
