@@ -8,6 +8,7 @@ import oracle as o
 from oracle import block_oracle as bo
 from paper_2410_06511_amd import f8
 from paper_2410_06511_amd import workloads as wl
+from attn_rounding_model import mean_relative_errors
 from helpers import bits
 
 pytestmark = pytest.mark.gpu
@@ -112,7 +113,7 @@ def run_backward(a, do_t):
     return dqkv, delta
 
 
-def check_backward(a, do_t, dqkv, delta, mean_factor=3 * 2.0 ** -9):
+def check_backward(a, do_t, dqkv, delta):
     qb, kb, vb = a.host_bits()
     B, S, Hq, Hkv = a.B, a.S, a.Hq, a.Hkv
     q, k, v, do = f64(qb), f64(kb), f64(vb), f64(bits(do_t))
@@ -125,13 +126,16 @@ def check_backward(a, do_t, dqkv, delta, mean_factor=3 * 2.0 ** -9):
     rdelta = (o_gpu * do).reshape(B, S, Hq, HD).sum(axis=3).transpose(2, 0, 1).reshape(Hq, B * S)
     mag = (np.abs(o_gpu) * np.abs(do)).reshape(B, S, Hq, HD).sum(axis=3).transpose(2, 0, 1).reshape(Hq, B * S)
     assert (np.abs(delta.cpu().numpy() - rdelta) <= 1e-5 * mag + 1e-30).all()
-    # P, dS (2^-9 relative each) and O (inside delta) are rounded to bf16 and the sums run in fp32:
-    # the same criterion as for the GEMMs of the linear, max |error| against max |reference|, per output
-    for name, g_, r_ in (("dq", gq, rdq), ("dk", gk, rdk), ("dv", gv, rdv)):
+    # The kernel rounds P, dS, O (inside delta) and its results to bf16 and sums in fp32.  What these
+    # roundings alone cost is computed, not assumed: the fp64 definition with the same roundings put
+    # in (attn_rounding_model) against the definition without them.  The kernel's mean error may
+    # exceed the model's by a tenth (its fp32 sums and its fast exponential are not in the model).
+    model = mean_relative_errors(q, k, v, do, B, S, Hq, Hkv, HD)
+    for name, g_, r_, m_ in (("dq", gq, rdq, model[0]), ("dk", gk, rdk, model[1]), ("dv", gv, rdv, model[2])):
         err = np.abs(g_ - r_)
+        # the largest error: the same criterion as for the GEMMs of the linear, max |error| against max |reference|
         assert err.max() <= 1e-2 * np.abs(r_).max(), (name, err.max(), np.abs(r_).max())
-        # on average: three bf16 roundings on the way (the P or dS operand, O inside delta, the output), 2^-9 each
-        assert err.mean() <= mean_factor * np.abs(r_).mean(), (name, err.mean(), np.abs(r_).mean())
+        assert err.mean() <= (1.1 * m_ + 2.0 ** -13) * np.abs(r_).mean(), (name, err.mean() / np.abs(r_).mean(), m_)
 
 
 @pytest.mark.parametrize("B,S,Hq,Hkv", [(1, 8, 1, 1), (1, 128, 2, 1), (2, 200, 4, 2), (1, 520, 8, 2), (3, 64, 2, 2)])
@@ -155,8 +159,9 @@ def test_sdpa_backward_peaked_scores():
     dqkv, delta = run_backward(a, do_t)
     # dS = P (dP - delta) cancels where P is close to one-hot (dP of the dominating key is nearly
     # delta itself): the bf16 rounding of O inside delta, 2^-9 of |delta|, is then a larger share of
-    # the small difference.  The bound on the largest error stays; the mean may reach 2^-6.
-    check_backward(a, do_t, dqkv, delta, mean_factor=2.0 ** -6)
+    # the small difference, and the mean error of dq and dk is about three times that of unpeaked
+    # scores - in the rounding model as on the GPU, which is what check_backward compares.
+    check_backward(a, do_t, dqkv, delta)
 
 
 def test_sdpa_full_size_sampled_against_oracle():
@@ -185,7 +190,9 @@ def test_sdpa_full_size_sampled_against_oracle():
     for name, gg, rr in (("dq", g_[rows, :nq], rdq), ("dk", g_[t:, nq:nq + nk], rdk[t:]), ("dv", g_[t:, nq + nk:], rdv[t:])):
         e = np.abs(gg - rr)
         assert e.max() <= 1e-2 * np.abs(rr).max(), (name, e.max(), np.abs(rr).max())
-        assert e.mean() <= 3 * 2.0 ** -9 * np.abs(rr).mean(), (name, e.mean(), np.abs(rr).mean())
+        # the rounding model (attn_rounding_model) is too slow at this size; for unit-variance inputs
+        # it gives 1.15 to 1.2 x 2^-9 at every size it can run (test_attn_rounding_model.py)
+        assert e.mean() <= 1.5 * 2.0 ** -9 * np.abs(rr).mean(), (name, e.mean() / np.abs(rr).mean() * 512)
 
 
 def test_sdpa_argument_errors():
