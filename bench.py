@@ -60,6 +60,9 @@ def parse():
                     help="skip timing torch.matmul in bf16 on the same shapes (context only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a device copy of known size (reference for the HBM byte counters)")
+    ap.add_argument("--clock-study", action="store_true",
+                    help="where the shader clock goes on the headline workload: the step, its GEMMs alone, its casts alone, "
+                         "one product back to back and with idle gaps, the matrix pipes alone; one JSON line")
     ap.add_argument("--cpu-sample-rows", type=int, default=8192)
     return ap.parse_args()
 
@@ -279,7 +282,7 @@ def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, input
 
     gemm_tflops = gemm_flops / (gemm_ms * 1e-3) / 1e12
     roofline = {
-        "kernel": "gemm_tile_kernel (fp8 MFMA 32x32x64; F8_NT forward, F8_NN and F8_TN backward)",
+        "kernel": "gemm_tile_kernel (fp8 MFMA 16x16x128; F8_NT forward, F8_NN and F8_TN backward)",
         "bound": "mfma",
         "achieved": round(gemm_tflops, 1),
         "peak": PEAK_FP8_TFLOPS,
@@ -304,6 +307,8 @@ def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, input
         cast = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": round(gbs / PEAK_HBM_GBS, 4), "bytes_per_elem": bpe,
                 "moved_gbs": round(moved * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
+                # the rate on the bytes a cast with a known scale would move (2 B read + 1 B written)
+                "useful_bytes_gbs": round(3 * cast_elems / (cast_ms * 1e-3) / 1e9, 1),
                 "ms_per_step": round(cast_ms, 4)}
     rec = {"workload": w.key, "ms_per_step": ms_per_step, "ms_per_step_median_of_events": ms_median,
            "tflops": tflops, "flops_step": flops_step, "shader_clock_ghz": clock_ghz,
@@ -357,18 +362,20 @@ def measure_ceilings(f8, torch, codes):
     const = torch.full((n,), 0x38, dtype=torch.uint8, device="cuda")          # 1.0 everywhere
     flat = codes.reshape(-1)
     real = flat[: 1 << (flat.numel().bit_length() - 1)][:n].contiguous()       # a power of two of real codes
-    iters = 4000
+    iters = 2000
     for name, buf in (("constant_operands", const), ("workload_codes", real)):
-        fl = [0]
+        for shape, suffix in ((0, ""), (1, "_32x32x64")):
+            fl = [0]
 
-        def fn(buf=buf):
-            fl[0] = f8.probe_mfma(buf, iters, ticks, sink, stream)
-        ms = time_ms(fn, 3)
-        t = ticks.cpu().tolist()
-        out["mfma_only_" + name] = {"tflops": round(fl[0] / (ms * 1e-3) / 1e12, 1),
-                                    "frac_of_nominal": round(fl[0] / (ms * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 4),
-                                    "shader_clock_ghz": round(0.1 * t[0] / max(1, t[1]), 3),
-                                    "cycles_per_mfma": round(t[0] / (iters * 16), 2)}
+            def fn(buf=buf, shape=shape):
+                fl[0] = f8.probe_mfma(buf, iters, ticks, sink, stream, shape=shape)
+            ms = time_ms(fn, 3)
+            t = ticks.cpu().tolist()
+            n_mfma = iters * (64 if shape == 0 else 32)
+            out["mfma_only_" + name + suffix] = {"tflops": round(fl[0] / (ms * 1e-3) / 1e12, 1),
+                                                 "frac_of_nominal": round(fl[0] / (ms * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 4),
+                                                 "shader_clock_ghz": round(0.1 * t[0] / max(1, t[1]), 3),
+                                                 "cycles_per_mfma": round(t[0] / n_mfma, 2)}
     gib = 1 << 30
     src = torch.empty(gib, dtype=torch.uint8, device="cuda")
     src.random_(0, 256)
@@ -378,7 +385,8 @@ def measure_ceilings(f8, torch, codes):
     out["copy_1GiB"] = {"gbs_read_plus_write": round(2 * gib / (ms * 1e-3) / 1e9, 1), "frac_of_nominal": round(2 * gib / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
     ms = time_ms(lambda: f8.probe_read(src, sink32, stream), 5)
     out["read_1GiB"] = {"gbs": round(gib / (ms * 1e-3) / 1e9, 1), "frac_of_nominal": round(gib / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)}
-    out["what"] = ("f8_probe_mfma: one wave per SIMD, 16 independent 32x32x64 fp8 MFMAs per iteration, operands in registers, "
+    out["what"] = ("f8_probe_mfma: one wave per SIMD, the 64 independent 16x16x128 fp8 MFMAs of a 128x128 wave tile per iteration "
+                   "(the GEMM kernel's instruction; _32x32x64: the other fp8 instruction, 32 per iteration), operands in registers, "
                    "no LDS or memory traffic; f8_probe_copy / f8_probe_read: grid-stride 16-byte copy / read of 1 GiB")
     return out
 
@@ -413,6 +421,8 @@ def main():
 
     if args.workload == "attention":
         return attention_main(args)
+    if args.clock_study:
+        return clock_study(args)
     default_run = args.workload is None
     w = wl.WORKLOADS[args.workload or HEADLINE]
     if w.key == "llama8b_ffn":
@@ -500,6 +510,96 @@ def main():
         out["configs"] = configs
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_rows, rowwise, grad_fmt, args.scaling)
+    print(json.dumps(out))
+
+
+def clock_study(args):
+    """The same kernels in different company, each region bracketed by two shader-clock samples:
+    how the clock (and with it the rate) depends on what else the chip is doing.  Rates are per
+    region; `mfma_busy_frac` = TFLOP/s over what 1024 matrix pipes deliver at the region's clock."""
+    import torch
+    from paper_2410_06511_amd import f8, workloads as wl
+    w = wl.WORKLOADS[HEADLINE]
+    stream = torch.cuda.current_stream()
+    dmax = max(max(l.M, l.K, l.N) for l in w.linears)
+    ws = f8.new_workspace(dmax, dmax)
+    inputs = [tuple(t.cuda() for t in wl.make_linear_inputs(w, li)) for li in range(len(w.linears))]
+    dyn = [LinearState(f8, w, li, inputs[li], False, f8.E4M3, "dynamic", ws) for li in range(len(w.linears))]
+    args.scaling = "dynamic"
+    step_dyn = make_step(f8, torch, args, dyn, ws, False)
+    step_dyn()
+    flops_step = sum(s.lin.flops for s in dyn)
+    elems_step = sum(s.X.numel() + s.W.numel() + s.dY.numel() for s in dyn)
+    one = dyn[4]   # w1: Y = X W^T, 16384 x 14336 x 4096
+
+    def gemms():
+        for s in dyn:
+            sv, l = s.saved, s.lin
+            f8.gemm(f8.NT, l.M, l.N, l.K, sv.x.q, f8.E4M3, sv.w.q, f8.E4M3, sv.x.inv_scale, sv.w.inv_scale, f8.TENSORWISE, s.Y, stream)
+        for s in reversed(dyn):
+            sv, l = s.saved, s.lin
+            f8.gemm(f8.NN, l.M, l.K, l.N, sv.dy.q, f8.E4M3, sv.w.q, f8.E4M3, sv.dy.inv_scale, sv.w.inv_scale, f8.TENSORWISE, s.dX, stream)
+            f8.gemm(f8.TN, l.N, l.K, l.M, sv.dy.q, f8.E4M3, sv.x.q, f8.E4M3, sv.dy.inv_scale, sv.x.inv_scale, f8.TENSORWISE, s.dW, stream, workspace=ws)
+
+    def casts():
+        for s in dyn:
+            f8.linear_fwd_quantise(s.desc, s.X, s.W, s.saved, ws, stream)
+        for s in reversed(dyn):
+            f8.quantise(s.dY, f8.TENSORWISE, f8.E4M3, s.saved.dy, ws, stream)
+
+    def one_product():
+        sv, l = one.saved, one.lin
+        f8.gemm(f8.NT, l.M, l.N, l.K, sv.x.q, f8.E4M3, sv.w.q, f8.E4M3, sv.x.inv_scale, sv.w.inv_scale, f8.TENSORWISE, one.Y, stream)
+
+    def region(fn, reps, warm=3):
+        for _ in range(warm):
+            fn()
+        clk = torch.zeros((2, 4 * f8.PROBE_CLOCK_SLOTS), dtype=torch.int64, device="cuda")
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        f8.probe_clock(clk[0], stream)
+        e0.record(stream)
+        for _ in range(reps):
+            fn()
+        e1.record(stream)
+        f8.probe_clock(clk[1], stream)
+        torch.cuda.synchronize()
+        c = clk.cpu()
+        return e0.elapsed_time(e1) / reps, f8.clock_ghz_between(c[0], c[1]) or 0.0
+
+    def rec(ms, ghz, flops=None, nbytes=None):
+        r = {"ms": round(ms, 4), "shader_clock_ghz": round(ghz, 3)}
+        if flops:
+            tf = flops / (ms * 1e-3) / 1e12
+            r.update({"tflops": round(tf, 1), "mfma_busy_frac": round(tf / (256 * 4 * 2048 * ghz * 1e-3), 4)})
+        if nbytes:
+            r["gbs"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+        return r
+
+    out = {"workload": w.key, "what": clock_study.__doc__.split("\n\n")[0].replace("\n    ", " ")}
+    out["step_dynamic_scaling"] = rec(*region(step_dyn, args.steps), flops=flops_step)
+    out["gemms_of_the_step_alone"] = rec(*region(gemms, args.steps), flops=flops_step)
+    out["casts_of_the_step_alone"] = rec(*region(casts, args.steps), nbytes=5 * elems_step)
+    one_flops = 2 * one.lin.M * one.lin.N * one.lin.K
+    out["one_product_back_to_back"] = rec(*region(one_product, 40), flops=one_flops)
+    out["one_product_back_to_back"]["product"] = f"w1 Y = X W^T, {one.lin.M} x {one.lin.N} x {one.lin.K}"
+    # the same launch after 20 ms of idle, ten times: the chip starts each from its idle state
+    gaps = []
+    for _ in range(10):
+        torch.cuda.synchronize()
+        time.sleep(0.02)
+        gaps.append(region(one_product, 1, warm=0))
+    out["one_product_after_idle_gaps"] = rec(sum(g[0] for g in gaps) / len(gaps), sum(g[1] for g in gaps) / len(gaps), flops=one_flops)
+    del dyn
+    torch.cuda.empty_cache()
+    # delayed scaling: every cast is one pass (3 instead of 5 bytes per element), the GEMMs are the same
+    dly = [LinearState(f8, w, li, inputs[li], False, f8.E4M3, "delayed", ws) for li in range(len(w.linears))]
+    args.scaling = "delayed"
+    step_dly = make_step(f8, torch, args, dly, ws, False)
+    out["step_delayed_scaling"] = rec(*region(step_dly, args.steps), flops=flops_step)
+    ceil = measure_ceilings(f8, torch, dly[0].saved.x.q)
+    for k in ("mfma_only_constant_operands", "mfma_only_workload_codes", "mfma_only_workload_codes_32x32x64"):
+        out[k] = ceil[k]
     print(json.dumps(out))
 
 
@@ -883,9 +983,20 @@ def cpu_baseline(w, rows, rowwise, grad_fmt, scaling="dynamic"):
         o.linear_bwd_scaled(dyb, xq, wq, st, grad_fmt)
         dt = time.perf_counter() - t0
     fl = 6 * rows * lin.K * lin.N
-    return {"value": round(fl / dt / 1e12, 6), "unit": "TFLOP/s", "cores": o.num_threads(), "kind": "oracle",
+    value = fl / dt / 1e12
+    # amax -> scale -> cast of that linear's whole X (O(elements), so timed at full size)
+    Xf = wl.bits(wl.make_linear_inputs(w, li)[0])
+    t0 = time.perf_counter()
+    o.amax_cast(Xf, o.ROWWISE if rowwise else o.TENSORWISE, o.E4M3)
+    dtc = time.perf_counter() - t0
+    step_flops = sum(l.flops for l in w.linears)
+    return {"value": round(value, 6), "unit": "TFLOP/s", "cores": o.num_threads(), "kind": "oracle",
             "sample": f"{w.key}/{lin.name} (K={lin.K}, N={lin.N}) first {rows} of {lin.M} tokens, fwd+bwd with casts",
-            "seconds": round(dt, 2)}
+            "seconds": round(dt, 2),
+            "amax_cast": {"gbs": round(5 * Xf.size / dtc / 1e9, 3), "bytes_per_elem": 5, "seconds": round(dtc, 3),
+                          "sample": f"{w.key}/{lin.name} X [{Xf.shape[0]}, {Xf.shape[1]}], whole tensor"},
+            "extrapolated": {"seconds_per_step_of_the_whole_workload": round(step_flops / (value * 1e12), 1),
+                             "how": "the workload's FLOPs per step at the sample's rate (the oracle's time is linear in M K N); not measured"}}
 
 
 if __name__ == "__main__":

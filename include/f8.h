@@ -570,16 +570,20 @@ f8_status f8_linear_fwd_xq(const f8_linear_desc* d, const f8_scaling_state* stat
  * with nothing else in the way, so that a benchmark can quote the kernels
  * above against measured ceilings beside the nominal peaks.
  *
- * f8_probe_mfma: one wavefront per SIMD on every compute unit issues
- *   iters x 16 fp8 matrix instructions (32x32x64, E4M3 x E4M3) on sixteen
- *   accumulators, with four A and four B register fragments per wavefront read
- *   once from `operands` (operand_bytes: a power of two, 64 KiB .. 1 GiB,
- *   32-byte aligned; fill it with the codes whose switching activity is to be
- *   measured: constant, or a quantised tensor): the GEMM kernel's matrix work
- *   with no LDS and no memory traffic.  flops_out (host, nullable) receives the
- *   floating-point operations of the launch; ticks (device, nullable, 2 words):
- *   shader-clock cycles and 100 MHz ticks that workgroup 0 spent in its loop;
- *   sink: one float of device memory that is (practically) never written.
+ * f8_probe_mfma: one wavefront per SIMD on every compute unit issues fp8
+ *   matrix instructions (E4M3 x E4M3) on register operands only, in the operand
+ *   pairing of a 128 x 128 wavefront tile: the GEMM kernel's matrix work with no
+ *   LDS and no memory traffic.  shape 0: iters x 64 of 16x16x128 (the
+ *   instruction and tile of the GEMM kernel; eight A and eight B fragments);
+ *   shape 1: iters x 32 of 32x32x64 (the other fp8 instruction of the same
+ *   nominal rate; four and four fragments): the same work per iteration.  The
+ *   fragments are read once from `operands` (operand_bytes: a power of two,
+ *   128 KiB .. 1 GiB, 32-byte aligned; fill it with the codes whose switching
+ *   activity is to be measured: constant, or a quantised tensor).  iters up to
+ *   2^19.  flops_out (host, nullable) receives the floating-point operations of
+ *   the launch; ticks (device, nullable, 2 words): shader-clock cycles and
+ *   100 MHz ticks that workgroup 0 spent in its loop; sink: one float of device
+ *   memory that is (practically) never written.
  * f8_probe_copy / f8_probe_read: grid-stride 16-byte copy of `bytes` bytes
  *   (read + write) / read of them; bytes a multiple of 16.  The copy is also
  *   the kernel of known size against which the HBM byte counters are scaled.
@@ -592,7 +596,7 @@ f8_status f8_linear_fwd_xq(const f8_linear_desc* d, const f8_scaling_state* stat
  *   on one stream) slot by slot: mean shader clock = 0.1 GHz x d(cycles) /
  *   d(ticks), averaged over the slots filled in both.
  */
-f8_status f8_probe_mfma(const uint8_t* operands, int64_t operand_bytes, int iters, uint64_t* ticks,
+f8_status f8_probe_mfma(int shape, const uint8_t* operands, int64_t operand_bytes, int iters, uint64_t* ticks,
                         float* sink, int64_t* flops_out, void* stream);
 f8_status f8_probe_copy(const void* src, void* dst, int64_t bytes, void* stream);
 f8_status f8_probe_read(const void* src, int64_t bytes, uint32_t* sink, void* stream);

@@ -9,42 +9,73 @@ namespace f8 {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-// Every wave holds four A and four B fragments (32 bytes per lane each, read once from
-// `operands`) and issues iters x 16 v_mfma_f32_32x32x64_f8f6f4 on sixteen accumulators, the
-// operand pairing of a 128 x 128 wave tile: the GEMM kernel's matrix-pipe work with no LDS and no
-// memory traffic.  Block 0 records the shader-clock and the 100 MHz counters around its loop.
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// The GEMM kernel's matrix-pipe work with no LDS and no memory traffic: every wave reads its
+// operand fragments once from `operands` (32 bytes per lane each) and then only issues MFMAs, in
+// the operand pairing of a 128 x 128 wave tile.
+//   SHAPE 0: v_mfma_f32_16x16x128_f8f6f4, eight A and eight B fragments, 64 accumulators of four
+//            registers: the instruction and the tile of gemm_tile_kernel; iters x 64 MFMAs.
+//   SHAPE 1: v_mfma_f32_32x32x64_f8f6f4, four and four fragments, 16 accumulators of sixteen
+//            registers: the other fp8 instruction of the same nominal rate; iters x 32 MFMAs
+//            (two passes over the pairs), so that both shapes do the same work per iteration.
+// Block 0 records the shader-clock and the 100 MHz counters around its loop.
+template <int SHAPE>
 __global__ __launch_bounds__(256) void probe_mfma_kernel(const uint8_t* __restrict__ operands, uint32_t operand_mask,
                                                          int iters, uint64_t* __restrict__ ticks,
                                                          float* __restrict__ sink)
 {
-    v8i a[4], b[4];
+    constexpr int F = SHAPE == 0 ? 8 : 4;
+    v8i a[F], b[F];
     const uint32_t t = blockIdx.x * 256u + threadIdx.x;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        a[i] = *reinterpret_cast<const v8i*>(operands + (((t * 8u + i) * 32u) & operand_mask));
-        b[i] = *reinterpret_cast<const v8i*>(operands + (((t * 8u + 4 + i) * 32u) & operand_mask));
+    for (int i = 0; i < F; ++i) {
+        a[i] = *reinterpret_cast<const v8i*>(operands + (((t * 16u + i) * 32u) & operand_mask));
+        b[i] = *reinterpret_cast<const v8i*>(operands + (((t * 16u + 8 + i) * 32u) & operand_mask));
     }
-    v16f acc[4][4];
+    float s = 0.f;
+    uint64_t c0, r0, c1, r1;
+    if constexpr (SHAPE == 0) {
+        v4f acc[8][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 8; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 8; ++j) acc[i][j] = v4f{0.f, 0.f, 0.f, 0.f};
+        c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+        for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-    const uint64_t c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
-    for (int it = 0; it < iters; ++it) {
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[j], a[i], acc[i][j], 0, 0, 0, 0, 0, 0);
+        }
+        c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += acc[i][j][(i + j) & 3];
+    } else {
+        v16f acc[4][4];
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], 0, 0, 0, 0, 0, 0);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        c0 = __builtin_readcyclecounter(), r0 = __builtin_amdgcn_s_memrealtime();
+        for (int it = 0; it < 2 * iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b[j], a[i], acc[i][j], 0, 0, 0, 0, 0, 0);
+        }
+        c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) s += acc[i][j][(i * 4 + j) & 15];
     }
-    const uint64_t c1 = __builtin_readcyclecounter(), r1 = __builtin_amdgcn_s_memrealtime();
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) s += acc[i][j][(i * 4 + j) & 15];
     if (s == 1.2345678e-30f) sink[0] = s;  // keeps the loop alive; practically never true
     if (ticks && blockIdx.x == 0 && threadIdx.x == 0) {
         ticks[0] = c1 - c0;
@@ -112,18 +143,22 @@ using namespace f8;
 
 extern "C" {
 
-f8_status f8_probe_mfma(const uint8_t* operands, int64_t operand_bytes, int iters, uint64_t* ticks, float* sink,
+f8_status f8_probe_mfma(int shape, const uint8_t* operands, int64_t operand_bytes, int iters, uint64_t* ticks, float* sink,
                         int64_t* flops_out, void* stream)
 {
+    if (shape != 0 && shape != 1) return F8_ERR_ENUM;
     if (!operands || !sink) return F8_ERR_NULL;
     // a power of two of at least one block's worth of fragments, so that offsets wrap with a mask
-    if (operand_bytes < 65536 || (operand_bytes & (operand_bytes - 1)) || operand_bytes > (int64_t)1 << 30 || iters < 0 ||
-        iters > (1 << 20))
+    if (operand_bytes < 131072 || (operand_bytes & (operand_bytes - 1)) || operand_bytes > (int64_t)1 << 30 || iters < 0 ||
+        iters > (1 << 19))
         return F8_ERR_SHAPE;
     if (!aligned16(operands) || (reinterpret_cast<uintptr_t>(operands) & 31u)) return F8_ERR_ALIGN;
     const int blocks = probe_cu_count();  // one wave per SIMD, as the GEMM kernel runs
-    if (flops_out) *flops_out = (int64_t)blocks * 4 * iters * 16 * (2LL * 32 * 32 * 64);
-    probe_mfma_kernel<<<blocks, 256, 0, (hipStream_t)stream>>>(operands, (uint32_t)(operand_bytes - 1), iters, ticks, sink);
+    // per wave and iteration: 64 x (2 * 16 * 16 * 128) = 32 x (2 * 32 * 32 * 64) flop
+    if (flops_out) *flops_out = (int64_t)blocks * 4 * iters * 64 * (2LL * 16 * 16 * 128);
+    const uint32_t mask = (uint32_t)(operand_bytes - 1);
+    if (shape == 0) probe_mfma_kernel<0><<<blocks, 256, 0, (hipStream_t)stream>>>(operands, mask, iters, ticks, sink);
+    else probe_mfma_kernel<1><<<blocks, 256, 0, (hipStream_t)stream>>>(operands, mask, iters, ticks, sink);
     return last_launch_status();
 }
 

@@ -106,7 +106,7 @@ def lib():
         l.f8_rmsnorm_bwd.argtypes = [_p, _p, _p, _p, _i64, _i64, _p, _p, _p, C.c_size_t, _p]
         l.f8_linear_fwd_wq.argtypes = [C.POINTER(LinearDesc), _p, _p, C.POINTER(SavedStruct), _p, C.c_size_t, _p]
         l.f8_linear_fwd_noalloc.argtypes = [C.POINTER(LinearDesc), _p, _p, _p, C.POINTER(SavedStruct), _p]
-        l.f8_probe_mfma.argtypes = [_p, _i64, _int, _p, _p, C.POINTER(_i64), _p]
+        l.f8_probe_mfma.argtypes = [_int, _p, _i64, _int, _p, _p, C.POINTER(_i64), _p]
         l.f8_probe_copy.argtypes = [_p, _p, _i64, _p]
         l.f8_probe_read.argtypes = [_p, _i64, _p, _p]
         l.f8_probe_clock.argtypes = [_p, _p]
@@ -443,12 +443,13 @@ def sdpa_bwd(q, qt, k, kt, v, o, do, dot, lse, B, S, Hq, Hkv, hd, dq, dk, dv, de
 
 # ---- measuring helpers ---------------------------------------------------------------
 
-def probe_mfma(operands, iters, ticks=None, sink=None, stream=None):
-    """Launches the matrix-pipe-only loop; returns the floating-point operations of the launch."""
+def probe_mfma(operands, iters, ticks=None, sink=None, stream=None, shape=0):
+    """Launches the matrix-pipe-only loop (shape 0: 16x16x128 as the GEMM kernel, 1: 32x32x64);
+    returns the floating-point operations of the launch."""
     if sink is None:
         sink = torch.zeros(1, dtype=torch.float32, device=operands.device)
     fl = _i64(0)
-    _check(lib().f8_probe_mfma(_ptr(operands), operands.numel() * operands.element_size(), int(iters), _ptr(ticks),
+    _check(lib().f8_probe_mfma(int(shape), _ptr(operands), operands.numel() * operands.element_size(), int(iters), _ptr(ticks),
                                _ptr(sink), C.byref(fl), _stream(stream)))
     return fl.value
 
