@@ -126,10 +126,14 @@ constexpr int kBK = 128;  // bytes of K per LDS stage
 typedef float f2 __attribute__((ext_vector_type(2)));
 typedef __bf16 b2 __attribute__((ext_vector_type(2)));
 
-// XOR swizzle of the eight 16-byte chunks of a 128-byte LDS row: the 16 lanes that read the
-// same logical chunk of 16 consecutive rows hit 16 different bank groups (8 chunk positions x
-// row parity), and so do any aligned 8 rows under a 128-byte bank window.
-__device__ inline int swz(int row) { return ((row >> 1) & 3) | (((row ^ (row >> 3)) & 1) << 2); }
+// XOR swizzle of the eight 16-byte chunks of a 128-byte LDS row.  The fragment read of a row-major
+// operand is two ds_read_b128 per lane: lane l takes row l % 16 of the fragment, logical chunks
+// 2 (l / 16) and 2 (l / 16) + 1.  LDS banks repeat every 256 bytes, so the row's parity already
+// picks one half of them; bits 1 and 2 of the row are folded into the chunk number.  Measured
+// with a four-wave read loop over all 4096 linear maps row -> chunk XOR: this one (like about a
+// quarter of them) runs such a read at the rate of a contiguous one, 4 cycles per kilobyte; maps
+// that also fold in bit 0 or bit 3 of the row take 8.
+__device__ inline int swz(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 1); }
 
 // ---- k-major operand tiles ----------------------------------------------------------
 // An operand stored [K, R-direction] (B of F8_NN, both operands of F8_TN) is staged as it
@@ -230,7 +234,7 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
     // matrix instructions (32 cycles), and the matrix pipe would wait for the instruction stream.
     int ld_tile = blockIdx.x;
     // row-major operand: the lane's row of piece 0 in the tile decides its chunk terms (the
-    // swizzle of row + 8 * j differs from that of row only for odd j, bit 2)
+    // swizzle looks at bits 1 and 2 of the row only, so every 8-row piece has the same)
     const int a_row = wave * (BM / NW) + (lane >> 3);
     const int b_row = wave * (BN / NW) + (lane >> 3);
     // k-major operand: a 1 KB load covers 1024 / R k-rows; lane i lands at k-row i / (R / 16),
