@@ -461,6 +461,36 @@ __global__ __launch_bounds__(kThreads) void cast_jobs_kernel(const StreamJobs jo
     for (; i < n; i += stride) out[i] = cast8<FMT>(x[i], s);
 }
 
+// Delayed scaling without a transposed copy: the scale is given, so one streaming pass casts the
+// tensor and takes its amax on the way; block b leaves the largest magnitude it read in
+// partial_out[b].  Contiguous tensors only (n chunks of eight elements).
+template <int FMT>
+__global__ __launch_bounds__(kThreads) void cast_measure_stream_kernel(
+    const uint4* __restrict__ x, int64_t n, const float* __restrict__ scale, uint2* __restrict__ out,
+    uint32_t* __restrict__ partial_out)
+{
+    __shared__ uint32_t red[kWaves];
+    const float s = scale[0];
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    uint32_t acc = 0;
+    for (; i + 3 * stride < n; i += 4 * stride) {
+        const uint4 v0 = x[i], v1 = x[i + stride], v2 = x[i + 2 * stride], v3 = x[i + 3 * stride];
+        out[i] = cast8<FMT>(v0, s);
+        out[i + stride] = cast8<FMT>(v1, s);
+        out[i + 2 * stride] = cast8<FMT>(v2, s);
+        out[i + 3 * stride] = cast8<FMT>(v3, s);
+        acc = absmax_acc(absmax_acc(absmax_acc(absmax_acc(acc, v0), v1), v2), v3);
+    }
+    for (; i < n; i += stride) {
+        const uint4 v = x[i];
+        out[i] = cast8<FMT>(v, s);
+        acc = absmax_acc(acc, v);
+    }
+    const uint32_t m = block_max_u32<kWaves>(pk_collapse(acc), red);
+    if (threadIdx.x == 0) partial_out[blockIdx.x] = m;
+}
+
 // ---------------------------------------------------------------------------
 // cast, tiled form: 128 x 128 tile per block, writes out and/or out_t.
 // The transposed copy goes through LDS so that both global writes are made of
@@ -942,6 +972,20 @@ f8_status cast_measure(const void* x, int64_t rows, int64_t cols, int64_t ld, co
     const int64_t tiles_r = (rows + kTile - 1) / kTile, tiles_c = (kcols + kTile - 1) / kTile;
     const int64_t nb = tiles_r * tiles_c;
     if (nb > (int64_t)0x7FFFFFFF || (size_t)nb * sizeof(uint32_t) > ws_bytes) return F8_ERR_WORKSPACE;
+    if (glue == 0 && streamable(rows, cols, ld, ld_out, out, out_t)) {
+        // one partial per block, never more blocks than the tiled form has tiles (the workspace
+        // is sized for those) and at least four chunks per thread
+        const int64_t chunks = rows * (cols / 8);
+        int64_t sb = (chunks + kThreads * 4 - 1) / (kThreads * 4);
+        sb = sb < nb ? sb : nb;
+        sb = sb < kJobCastBlocks ? sb : kJobCastBlocks;
+        if (fmt == F8_E4M3)
+            cast_measure_stream_kernel<F8_E4M3><<<(unsigned)sb, kThreads, 0, st>>>((const uint4*)x, chunks, scale, (uint2*)out, (uint32_t*)ws);
+        else
+            cast_measure_stream_kernel<F8_E5M2><<<(unsigned)sb, kThreads, 0, st>>>((const uint4*)x, chunks, scale, (uint2*)out, (uint32_t*)ws);
+        *npartial = (int)sb;
+        return last_launch_status();
+    }
 #define F8_LAUNCH_MEASURE_G(F, O, T, G)                                                                  \
     cast_tile_kernel<F, F8_TENSORWISE, false, O, T, true, G><<<(unsigned)nb, kThreads, 0, st>>>(         \
         (const uint16_t*)x, rows, kcols, ld, scale, nullptr, 0, nullptr, nullptr, nullptr, out, ld_out, out_t, \
