@@ -162,21 +162,27 @@ __global__ __launch_bounds__(kThreads) void amax_cols_partial_kernel(
         const bool col_ok = col0 < cols;
         const uint4* p = x + (col_ok ? (col0 >> 3) : 0);
         uint32_t* rp = row_partial + (int64_t)blockIdx.x * rows;
-        for (int64_t r = r_begin + rl; r < r_end; r += 32) {
-            const bool two = r + 16 < r_end;
-            uint4 v = make_uint4(0, 0, 0, 0), w = make_uint4(0, 0, 0, 0);
-            if (col_ok) {
-                v = p[r * ld_chunks];
-                if (two) w = p[(r + 16) * ld_chunks];
+        // four rows (16 apart) in flight per thread
+        for (int64_t r = r_begin + rl; r < r_end; r += 64) {
+            uint4 v[4];
+            bool in[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                in[k] = r + 16 * k < r_end;
+                v[k] = make_uint4(0, 0, 0, 0);
+                if (col_ok && in[k]) v[k] = p[(r + 16 * k) * ld_chunks];
             }
-            a0 = pkmax(a0, pkmax(v.x & 0x7FFF7FFFu, w.x & 0x7FFF7FFFu));
-            a1 = pkmax(a1, pkmax(v.y & 0x7FFF7FFFu, w.y & 0x7FFF7FFFu));
-            a2 = pkmax(a2, pkmax(v.z & 0x7FFF7FFFu, w.z & 0x7FFF7FFFu));
-            a3 = pkmax(a3, pkmax(v.w & 0x7FFF7FFFu, w.w & 0x7FFF7FFFu));
-            const uint32_t mv = row_piece_max(v), mw = row_piece_max(w);
-            if (cc == 0) {
-                rp[r] = mv;
-                if (two) rp[r + 16] = mw;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                a0 = pkmax(a0, v[k].x & 0x7FFF7FFFu);
+                a1 = pkmax(a1, v[k].y & 0x7FFF7FFFu);
+                a2 = pkmax(a2, v[k].z & 0x7FFF7FFFu);
+                a3 = pkmax(a3, v[k].w & 0x7FFF7FFFu);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t mk = row_piece_max(v[k]);  // every lane takes part, also for rows past the end
+                if (cc == 0 && in[k]) rp[r + 16 * k] = mk;
             }
         }
     }
@@ -202,13 +208,23 @@ __global__ __launch_bounds__(kThreads) void amax_cols_partial_kernel(
 // stage of the per-column maxima (n_outer row chunks, n_inner = cols) and of the per-row maxima
 // (n_outer column strips, n_inner = rows).  A block owns 64 consecutive j (coalesced reads)
 // and splits the outer index over its four wavefronts, which meet in LDS.
+// With blocks0 > 0 a second vector is finished by the blocks from blocks0 on (the per-row maxima
+// beside the per-column maxima of rowwise scaling: one launch for both).
 __global__ __launch_bounds__(kThreads) void amax_vector_final_kernel(
     const uint32_t* __restrict__ partial, int n_outer, int64_t n_inner, float fm,
-    float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out)
+    float* __restrict__ amax_out, float* __restrict__ scale_out, float* __restrict__ inv_out,
+    int blocks0 = 0, const uint32_t* __restrict__ partial1 = nullptr, int n_outer1 = 0, int64_t n_inner1 = 0,
+    float* __restrict__ amax_out1 = nullptr, float* __restrict__ scale_out1 = nullptr, float* __restrict__ inv_out1 = nullptr)
 {
     __shared__ uint32_t red[kWaves][kWave];
     const int lane = threadIdx.x & (kWave - 1), w = threadIdx.x / kWave;
-    const int64_t j = (int64_t)blockIdx.x * kWave + lane;
+    int64_t block = blockIdx.x;
+    if (blocks0 > 0 && block >= blocks0) {
+        block -= blocks0;
+        partial = partial1, n_outer = n_outer1, n_inner = n_inner1;
+        amax_out = amax_out1, scale_out = scale_out1, inv_out = inv_out1;
+    }
+    const int64_t j = block * kWave + lane;
     uint32_t m = 0;
     if (j < n_inner) {
         int i = w;
@@ -1061,10 +1077,9 @@ f8_status amax_rows_and_cols(const void* x, int64_t rows, int64_t cols, int64_t 
     uint32_t* rowp = colp + (size_t)kColChunksMax * (size_t)(rows > cols ? rows : cols);
     dim3 grid(strips, (unsigned)nch);
     amax_cols_partial_kernel<true><<<grid, kThreads, 0, st>>>((const uint4*)x, rows, cols, ld / 8, rpc, colp, rowp);
-    amax_vector_final_kernel<<<(unsigned)((cols + kWave - 1) / kWave), kThreads, 0, st>>>(colp, nch, cols, fm, amax_c,
-                                                                                         scale_c, inv_c);
-    amax_vector_final_kernel<<<(unsigned)((rows + kWave - 1) / kWave), kThreads, 0, st>>>(rowp, (int)strips, rows, fm,
-                                                                                         amax_r, scale_r, inv_r);
+    const unsigned bc = (unsigned)((cols + kWave - 1) / kWave), br = (unsigned)((rows + kWave - 1) / kWave);
+    amax_vector_final_kernel<<<bc + br, kThreads, 0, st>>>(colp, nch, cols, fm, amax_c, scale_c, inv_c, (int)bc, rowp,
+                                                           (int)strips, rows, amax_r, scale_r, inv_r);
     return last_launch_status();
 }
 
