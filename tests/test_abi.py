@@ -79,6 +79,18 @@ def test_argument_errors_are_reported_before_any_launch():
     assert l.f8_linear_fwd(C.byref(bad), FAKE, FAKE, FAKE, C.byref(sv), FAKE, 1 << 20, None) == 2
     bad = f8.LinearDesc(32, 32, 32, 2, 0)
     assert l.f8_linear_bwd(C.byref(bad), FAKE, C.byref(sv), FAKE, FAKE, FAKE, 1 << 20, None) == 4
+    # the same checks behind the entry points that take a scratch buffer or no product
+    assert l.f8_gemm_ws(0, 16, 16, 24, FAKE, 0, 32, FAKE, 0, 32, FAKE, FAKE, 0, FAKE, 16, None, FAKE, 1 << 20, None) == 2
+    assert l.f8_gemm_ws(2, 16, 16, 16, FAKE, 0, 16, FAKE, 0, 8, FAKE, FAKE, 0, FAKE, 16, None, None, 0, None) == 2
+    assert l.f8_gemm_ws(3, 16, 16, 16, FAKE, 0, 16, FAKE, 0, 16, FAKE, FAKE, 0, FAKE, 16, None, None, 0, None) == 4
+    assert l.f8_linear_fwd_quantise(None, FAKE, FAKE, C.byref(sv), FAKE, 1 << 20, None) == 1
+    assert l.f8_linear_fwd_quantise(C.byref(d), FAKE, None, C.byref(sv), FAKE, 1 << 20, None) == 1
+    assert l.f8_linear_fwd_quantise(C.byref(d), FAKE + 4, FAKE, C.byref(sv), FAKE, 1 << 20, None) == 3
+    assert l.f8_linear_fwd_noalloc(C.byref(bad), FAKE, FAKE, FAKE, C.byref(sv), None) == 4
+    assert l.f8_probe_mfma(2, FAKE, 1 << 20, 1, None, FAKE, None, None) == 4
+    assert l.f8_probe_mfma(0, FAKE, 3 << 18, 1, None, FAKE, None, None) == 2
+    assert l.f8_probe_copy(FAKE, FAKE, 24, None) == 2
+    assert l.f8_probe_clock(None, None) == 1
 
 
 def test_block_entry_points_reject_bad_arguments_before_any_launch():
