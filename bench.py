@@ -52,6 +52,9 @@ def parse():
     ap.add_argument("--keep-weights", action="store_true",
                     help="dynamic scaling: quantise the weights once before the timed steps and keep their codes "
                          "(micro-batches of one optimizer step); the default recasts them on every forward")
+    ap.add_argument("--own-inputs", action="store_true",
+                    help="llama8b_block: give wk, wv and w3 an input tensor and an input cast of their own instead of "
+                         "sharing wq's and w1's")
     ap.add_argument("--transposed-copies", action="store_true",
                     help="tensorwise: also write every code tensor transposed (+1 B/elem) and run the backward as F8_NT "
                          "products on the copies, instead of reading the codes in place (F8_NN / F8_TN)")
@@ -70,19 +73,26 @@ def parse():
 class LinearState:
     """Device tensors of one linear of the workload."""
 
-    def __init__(self, f8, w, li, inputs, rowwise, grad_fmt, scaling="dynamic", ws=None, transposed=False):
+    def __init__(self, f8, w, li, inputs, rowwise, grad_fmt, scaling="dynamic", ws=None, transposed=False, x_owner=None):
+        """x_owner: the LinearState of the linear whose input this one shares (it then reads that
+        linear's X and the fp8 codes of it that the owner's forward leaves), or None."""
         import torch
         lin = w.linears[li]
         self.lin = lin
         self.X, self.W, self.dY = inputs
+        self.x_owner = x_owner
         M, K, N = lin.M, lin.K, lin.N
         bf = dict(dtype=torch.bfloat16, device="cuda")
         self.Y = torch.empty((M, N), **bf)
         self.dX = torch.empty((M, K), **bf)
         self.dW = torch.empty((N, K), **bf)
-        self.saved = f8.Saved(M, K, N, rowwise, transposed=transposed)
+        if x_owner is not None:
+            self.X = x_owner.X
+            self.saved = f8.Saved(M, K, N, rowwise, transposed=transposed, x=x_owner.saved.x)
+        else:
+            self.saved = f8.Saved(M, K, N, rowwise, transposed=transposed)
         self.desc = f8.linear_desc(M, K, N, rowwise, grad_fmt)
-        self.state = None
+        self.state = f8.ScalingState(f8.DYNAMIC, 1) if x_owner is not None else None
         if scaling != "dynamic":
             # delayed: histories seeded with this batch's amax values (the first-step
             # initialisation); static: constant scales FMAX / amax of this batch
@@ -91,6 +101,22 @@ class LinearState:
             for key, t, fmt in (("x", self.X, f8.E4M3), ("w", self.W, f8.E4M3), ("dy", self.dY, grad_fmt)):
                 f8.amax(t, f8.TENSORWISE, a, ws)
                 f8.amax_history_push(getattr(self.state, "hist_" + key), a, fmt, getattr(self.state, "scale_" + key))
+
+
+def shares_inputs(w, args, rowwise):
+    """Whether the linears of `w` that read one activation share its cast in this run: the plain
+    step under tensorwise scaling (the chained and kept-weight variants keep one input per linear)."""
+    return bool(w.shared_x) and not rowwise and not args.own_inputs and not args.chain and not args.keep_weights
+
+
+def make_states(f8, w, inputs, rowwise, grad_fmt, args, ws):
+    states = []
+    share = shares_inputs(w, args, rowwise)
+    for li in range(len(w.linears)):
+        own = w.x_owner(li) if share else li
+        states.append(LinearState(f8, w, li, inputs[li], rowwise, grad_fmt, args.scaling, ws, args.transposed_copies,
+                                  x_owner=states[own] if own != li else None))
+    return states
 
 
 def make_step(f8, torch, args, states, ws, rowwise):
@@ -135,13 +161,19 @@ def make_step(f8, torch, args, states, ws, rowwise):
     elif args.scaling == "dynamic":
         def step():
             for s in states:                       # forward in model order
-                f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws)
+                if s.x_owner is None:
+                    f8.linear_fwd(s.desc, s.X, s.W, s.Y, s.saved, ws)
+                else:                              # the input's codes are the owner's: cast W, multiply
+                    f8.linear_fwd_xq(s.desc, s.state, s.W, s.Y, s.saved, ws)
             for s in reversed(states):             # backward in reverse
                 f8.linear_bwd(s.desc, s.dY, s.saved, s.dX, s.dW, ws)
     else:
         def step():
             for s in states:
-                f8.linear_fwd_scaled(s.desc, s.state, s.X, s.W, s.Y, s.saved, ws)
+                if s.x_owner is None:
+                    f8.linear_fwd_scaled(s.desc, s.state, s.X, s.W, s.Y, s.saved, ws)
+                else:
+                    f8.linear_fwd_xq(s.desc, s.state, s.W, s.Y, s.saved, ws)
             for s in reversed(states):
                 f8.linear_bwd_scaled(s.desc, s.state, s.dY, s.saved, s.dX, s.dW, ws)
     return step
@@ -158,8 +190,7 @@ def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, input
     ws = f8.new_workspace(dmax, dmax)
     if inputs is None:
         inputs = [tuple(t.cuda() for t in wl.make_linear_inputs(w, li)) for li in range(len(w.linears))]
-    states = [LinearState(f8, w, li, inputs[li], rowwise, grad_fmt, args.scaling, ws, args.transposed_copies)
-              for li in range(len(w.linears))]
+    states = make_states(f8, w, inputs, rowwise, grad_fmt, args, ws)
     stream = torch.cuda.current_stream()   # the step and the per-call legs run on the current stream
     step = make_step(f8, torch, args, states, ws, rowwise)
 
@@ -215,7 +246,9 @@ def run_linear_workload(f8, wl, torch, args, w, gran, gfmt, steps, warmup, input
     for li, s in enumerate(states):
         M, K, N = s.lin.M, s.lin.K, s.lin.N
         sv = s.saved
-        if args.scaling == "dynamic":   # the forward's own quantisation: X and W in one call
+        if s.x_owner is not None:       # X's codes are the owner's: only W is cast
+            ops.append(("cast", li, cast_op(s.W, sv.w, f8.E4M3), s.W.numel(), "W"))
+        elif args.scaling == "dynamic":   # the forward's own quantisation: X and W in one call
             ops.append(("cast", li, (lambda s=s, sv=sv: f8.linear_fwd_quantise(s.desc, s.X, s.W, sv, ws, stream)),
                         s.X.numel() + s.W.numel(), "X+W"))
         else:
@@ -466,6 +499,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.key}: " + ", ".join(f"{l.name}[M={l.M},K={l.K},N={l.N}]" for l in w.linears),
                    "scaling_granularity": gran, "scaling_strategy": args.scaling, "grad_format": gfmt, "chained": bool(args.chain), "hip_graph": bool(args.graph),
+                   "shared_inputs": [[w.linears[i].name for i in g] for g in w.shared_x] if shares_inputs(w, args, rowwise) else [],
                    "weights_recast_every_step": not args.keep_weights, "transposed_code_copies": bool(args.transposed_copies or rowwise),
                    "flops_per_step": flops_step},
         "frac_of_fp8_peak": round(tflops / PEAK_FP8_TFLOPS, 4),
@@ -524,12 +558,12 @@ def clock_study(args):
     dmax = max(max(l.M, l.K, l.N) for l in w.linears)
     ws = f8.new_workspace(dmax, dmax)
     inputs = [tuple(t.cuda() for t in wl.make_linear_inputs(w, li)) for li in range(len(w.linears))]
-    dyn = [LinearState(f8, w, li, inputs[li], False, f8.E4M3, "dynamic", ws) for li in range(len(w.linears))]
     args.scaling = "dynamic"
+    dyn = make_states(f8, w, inputs, False, f8.E4M3, args, ws)
     step_dyn = make_step(f8, torch, args, dyn, ws, False)
     step_dyn()
     flops_step = sum(s.lin.flops for s in dyn)
-    elems_step = sum(s.X.numel() + s.W.numel() + s.dY.numel() for s in dyn)
+    elems_step = sum((s.X.numel() if s.x_owner is None else 0) + s.W.numel() + s.dY.numel() for s in dyn)
     one = dyn[4]   # w1: Y = X W^T, 16384 x 14336 x 4096
 
     def gemms():
@@ -543,7 +577,10 @@ def clock_study(args):
 
     def casts():
         for s in dyn:
-            f8.linear_fwd_quantise(s.desc, s.X, s.W, s.saved, ws, stream)
+            if s.x_owner is None:
+                f8.linear_fwd_quantise(s.desc, s.X, s.W, s.saved, ws, stream)
+            else:
+                f8.quantise(s.W, f8.TENSORWISE, f8.E4M3, s.saved.w, ws, stream)
         for s in reversed(dyn):
             f8.quantise(s.dY, f8.TENSORWISE, f8.E4M3, s.saved.dy, ws, stream)
 
@@ -593,8 +630,8 @@ def clock_study(args):
     del dyn
     torch.cuda.empty_cache()
     # delayed scaling: every cast is one pass (3 instead of 5 bytes per element), the GEMMs are the same
-    dly = [LinearState(f8, w, li, inputs[li], False, f8.E4M3, "delayed", ws) for li in range(len(w.linears))]
     args.scaling = "delayed"
+    dly = make_states(f8, w, inputs, False, f8.E4M3, args, ws)
     step_dly = make_step(f8, torch, args, dly, ws, False)
     out["step_delayed_scaling"] = rec(*region(step_dly, args.steps), flops=flops_step)
     ceil = measure_ceilings(f8, torch, dly[0].saved.x.q)

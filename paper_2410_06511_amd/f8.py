@@ -222,8 +222,9 @@ class QTensor:
 class Saved:
     """f8_saved for one linear: X [M,K], W [N,K], dY [M,N]."""
 
-    def __init__(self, M, K, N, rowwise=False, device="cuda", transposed=False):
-        self.x = QTensor(M, K, rowwise, device, transposed)
+    def __init__(self, M, K, N, rowwise=False, device="cuda", transposed=False, x=None):
+        """x: the QTensor of another linear that reads the same input (its codes are then shared, not copied)."""
+        self.x = x if x is not None else QTensor(M, K, rowwise, device, transposed)
         self.w = QTensor(N, K, rowwise, device, transposed)
         self.dy = QTensor(M, N, rowwise, device, transposed)
         self._struct = SavedStruct(self.x.struct(), self.w.struct(), self.dy.struct())

@@ -44,6 +44,16 @@ class Workload:
     x_outlier_std: float = 100.0
     variants: tuple = (("tensorwise", "e4m3"),)  # (granularity, grad format) pairs to run
     note: str = ""
+    # Groups of linear indices that read ONE input tensor: the first of a group owns X (and its
+    # cast), the others take its X and its fp8 codes.  Empty: every linear has its own X.
+    shared_x: tuple = ()
+
+    def x_owner(self, li: int) -> int:
+        """Index of the linear whose X (and X codes) linear `li` reads: itself unless it follows in a group."""
+        for g in self.shared_x:
+            if li in g:
+                return g[0]
+        return li
 
 
 def _llama8b(M):
@@ -66,8 +76,10 @@ WORKLOADS = {
         [Linear("w1", 8192, 16384, 6656), Linear("w3", 8192, 16384, 6656),
          Linear("w2", 8192, 6656, 16384), Linear("wq", 8192, 16384, 2048)],
         w_std=0.01, variants=(("tensorwise", "e4m3"), ("rowwise", "e4m3"))),
-    "llama8b_block": Workload("llama8b_block", 5, _llama8b(16384),
-                              note="seven linears forward in model order, then backward in reverse"),
+    # wq, wk, wv read the same activation, and so do w1, w3: their X is one tensor, cast once
+    "llama8b_block": Workload("llama8b_block", 5, _llama8b(16384), shared_x=((0, 1, 2), (4, 5)),
+                              note="seven linears forward in model order, then backward in reverse; "
+                                   "wq / wk / wv share one input (cast once), w1 / w3 another"),
     # The same block with the projections that share an input fused along N: one X cast and one
     # wide GEMM for q|k|v (4096 + 1024 + 1024) and for w1|w3 (2 x 14336).  The fused dY then has
     # ONE tensorwise scale, so results differ from the unfused linears by quantisation noise.
@@ -129,7 +141,8 @@ def make_linear_inputs(wl: Workload, li: int, M: Optional[int] = None):
         W = randn_bf16((lin.N, lin.K), wl.w_std, 0, generator=g)
         dY = randn_bf16((m, lin.N), wl.dy_std, 0, generator=g)
         return X, W, dY
-    X = randn_bf16((m, lin.K), wl.x_std, seed_for(wl.config_index, li, "x"),
+    # linears that share their input draw the X of the group's first linear
+    X = randn_bf16((m, lin.K), wl.x_std, seed_for(wl.config_index, wl.x_owner(li), "x"),
                    wl.x_outlier_frac, wl.x_outlier_std)
     W = randn_bf16((lin.N, lin.K), wl.w_std, seed_for(wl.config_index, li, "w"))
     dY = randn_bf16((m, lin.N), wl.dy_std, seed_for(wl.config_index, li, "dy"))

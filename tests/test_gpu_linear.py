@@ -209,6 +209,35 @@ def test_forward_quantisation_of_x_and_w_together(M, K, N, transposed):
         assert torch.equal(got.q, alone.q) and torch.equal(got.scale, alone.scale)
 
 
+def test_linears_on_a_shared_input_reuse_its_codes():
+    """Two linears that read one activation (wq and wk): the second runs on the first's X codes
+    (f8_linear_fwd_xq, only its W is cast) and gives the bits of a forward + backward that casts X
+    itself."""
+    M, K, N1, N2 = 272, 336, 208, 96
+    g = torch.Generator("cpu")
+    g.manual_seed(91)
+    X = wl.randn_bf16((M, K), 1.0, 0, generator=g).cuda()
+    W1, W2 = wl.randn_bf16((N1, K), 0.02, 0, generator=g).cuda(), wl.randn_bf16((N2, K), 0.02, 0, generator=g).cuda()
+    dY2 = wl.randn_bf16((M, N2), 1e-3, 0, generator=g).cuda()
+    ws = f8.new_workspace(max(M, K, N1), max(M, K, N1))
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    d1, d2 = f8.linear_desc(M, K, N1), f8.linear_desc(M, K, N2)
+    s1 = f8.Saved(M, K, N1)
+    shared, own = f8.Saved(M, K, N2, x=s1.x), f8.Saved(M, K, N2)
+    Y1, Ya, Yb = torch.empty((M, N1), **bf), torch.empty((M, N2), **bf), torch.empty((M, N2), **bf)
+    f8.linear_fwd(d1, X, W1, Y1, s1, ws)
+    f8.linear_fwd_xq(d2, f8.ScalingState(f8.DYNAMIC, 1), W2, Ya, shared, ws)
+    f8.linear_fwd(d2, X, W2, Yb, own, ws)
+    dXa, dXb = torch.empty((M, K), **bf), torch.empty((M, K), **bf)
+    dWa, dWb = torch.empty((N2, K), **bf), torch.empty((N2, K), **bf)
+    f8.linear_bwd(d2, dY2, shared, dXa, dWa, ws)
+    f8.linear_bwd(d2, dY2, own, dXb, dWb, ws)
+    torch.cuda.synchronize()
+    assert shared.x.q.data_ptr() == s1.x.q.data_ptr() and torch.equal(s1.x.q, own.x.q)
+    for a_, b_ in ((Ya, Yb), (dXa, dXb), (dWa, dWb)):
+        assert torch.equal(a_.view(torch.int16), b_.view(torch.int16))
+
+
 @pytest.mark.parametrize("rowwise", [False, True])
 def test_forward_with_kept_weight_codes(rowwise):
     """A second micro-batch against the weight codes kept from the first: the same bits as a full

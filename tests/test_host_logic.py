@@ -67,3 +67,17 @@ def test_bench_reads_the_committed_traffic_summary():
     t, source = bench.committed_traffic()
     assert isinstance(t, int) and 1e8 < t < 5e9 and "revision" not in source.split("as of")[0]
     assert os.path.exists(os.path.join(ROOT, "profiles", bench.TRAFFIC_SUMMARY))
+
+
+def test_linears_that_share_an_input_draw_the_same_tensor():
+    """The 16384-token block: wq / wk / wv read one activation and w1 / w3 another, so their X is
+    the owner's tensor bit for bit (and cast once); weights and output gradients stay distinct."""
+    w = wl.WORKLOADS["llama8b_block"]
+    names = [l.name for l in w.linears]
+    assert [names[w.x_owner(i)] for i in range(7)] == ["wq", "wq", "wq", "wo", "w1", "w1", "w2"]
+    x0, w0, _ = wl.make_linear_inputs(w, 0, M=32)
+    x1, w1, _ = wl.make_linear_inputs(w, 1, M=32)
+    x3, _, _ = wl.make_linear_inputs(w, 3, M=32)
+    assert torch.equal(x0.view(torch.int16), x1.view(torch.int16)) and not torch.equal(x0.view(torch.int16), x3.view(torch.int16))
+    assert w0.shape != w1.shape
+    assert all(wl.WORKLOADS[k].shared_x == () for k in ("llama8b", "llama70b_tp8", "llama405b_tp8", "llama8b_fused"))
