@@ -736,9 +736,9 @@ def ffn_main(args, w):
             leg["gbs"] = round(by / (ms * 1e-3) / 1e9, 1)
             leg["bytes_per_elem"] = by // (M * D if name == "rmsnorm" else M * H)
             if name.startswith("silu_mul fused"):
-                leg["note"] = "reads [a | b] (4 B), writes the codes of h in both orientations (2 B); replaces silu_mul (6 B) + the cast of h (4 B)"
+                leg["note"] = "reads [a | b] (4 B), writes the codes of h (1 B; 2 B with a transposed copy); replaces silu_mul (6 B) + the cast of h (4 B)"
             if name.startswith("silu_mul_bwd fused"):
-                leg["note"] = "reads [a | b] and dh (6 B), writes the codes of dAB in both orientations (4 B); replaces silu_mul_bwd (10 B) + the cast of dAB (8 B)"
+                leg["note"] = "reads [a | b] and dh (6 B), writes the codes of dAB (2 B; 4 B with a transposed copy); replaces silu_mul_bwd (10 B) + the cast of dAB (8 B)"
         legs.append(leg)
     glue_ms = sum(l["ms"] for l in legs if "gbs" in l)
     glue_bytes = sum(by for _, _, _, by in calls)

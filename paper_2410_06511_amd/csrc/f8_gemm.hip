@@ -1,6 +1,6 @@
 // The f8_gemm entry point (steps 4-6 of the Float8 linear: Y = X W^T, dX = dY W, dW = dY^T X).
-// The kernels live in f8_gemm_kernels.hpp and are instantiated per operand-format pair in
-// f8_gemm_inst_*.hip.
+// The kernels live in f8_gemm_kernels.hpp and are instantiated per operand-format pair and layout
+// by f8_gemm_inst.hip.
 #include "f8_host.hpp"
 
 namespace f8 {

@@ -1,6 +1,6 @@
 // fp8 GEMM kernels for gfx950 (steps 4-6 of the Float8 linear: Y = X W^T,
-// dX = dY W, dW = dY^T X) (kernels and launch logic; f8_gemm.hip holds the entry point,
-// f8_gemm_inst_*.hip one operand-format pair each, so that they compile in parallel).
+// dX = dY W, dW = dY^T X) (kernels and launch logic; f8_gemm.hip holds the entry points,
+// f8_gemm_inst.hip is compiled once per operand-format pair and layout, in parallel).
 //
 // Two kernels:
 //   gemm_tile_kernel    the fast path, K a multiple of 256, all three layouts.
@@ -113,9 +113,9 @@ __device__ inline void tile_coords(int pid, int tiles_m, int tiles_n, int* tm, i
 // Persistent workgroups (one or two per CU) walk over BM x BN output tiles.  K advances in
 // steps of 128 bytes = one LDS stage (a full cache line per row and load) = the contraction
 // length of one v_mfma_f32_16x16x128_f8f6f4; two stages, filled by direct global->LDS loads.
-// (The 16x16x128 form of the fp8 matrix instruction draws less power per flop than the
-// 32x32x64 form, and the chip runs these kernels against its power limit: on quantised
-// Gaussian data the matrix pipes alone sustain 4.3-4.5 PFLOP/s with it against 3.7-4.1.)
+// (Of the two fp8 matrix instructions of equal nominal rate, 16x16x128 and 32x32x64, the first
+// is used: one instruction spans exactly one LDS stage, and the kernel built on it ran faster.
+// With operands in registers and nothing else going on the two sustain the same rate.)
 // A wave's 128 x 128 tile is 8 x 8 matrix-instruction tiles, i.e. 8 + 8 operand fragments per K
 // step.  The load stream runs two K steps ahead of the MFMAs and does not stop at tile
 // boundaries, so the next tile's first stages arrive while the current tile's epilogue runs.

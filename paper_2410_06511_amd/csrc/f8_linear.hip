@@ -46,7 +46,8 @@ static size_t linear_workspace(const f8_linear_desc* d)
     return workspace_bytes(m, m);
 }
 
-// Quantise T[rows, cols] into q (and q_t).  Tensorwise: one pass writes both orientations.
+// Quantise T[rows, cols] into q (and q_t).  Tensorwise: q, and the same codes transposed if the
+// caller keeps a q_t.
 // Rowwise: q with per-row scales, q_t with per-column scales (different codes): the two amax
 // sets from one pass over T, then one cast pass that writes both.
 static f8_status quantise_both(const void* T, int64_t rows, int64_t cols, bool rowwise, int fmt,
