@@ -209,11 +209,11 @@ def test_forward_quantisation_of_x_and_w_together(M, K, N, transposed):
         assert torch.equal(got.q, alone.q) and torch.equal(got.scale, alone.scale)
 
 
-def test_linears_on_a_shared_input_reuse_its_codes():
-    """Two linears that read one activation (wq and wk): the second runs on the first's X codes
-    (f8_linear_fwd_xq, only its W is cast) and gives the bits of a forward + backward that casts X
-    itself."""
-    M, K, N1, N2 = 272, 336, 208, 96
+@pytest.mark.parametrize("M,K,N1,N2", [(272, 336, 208, 96), (16384, 4096, 4096, 1024)])
+def test_linears_on_a_shared_input_reuse_its_codes(M, K, N1, N2):
+    """Two linears that read one activation (wq and wk; also at their size in the 16384-token block,
+    as the benchmark runs them): the second runs on the first's X codes (f8_linear_fwd_xq, only its
+    W is cast) and gives the bits of a forward + backward that casts X itself."""
     g = torch.Generator("cpu")
     g.manual_seed(91)
     X = wl.randn_bf16((M, K), 1.0, 0, generator=g).cuda()
