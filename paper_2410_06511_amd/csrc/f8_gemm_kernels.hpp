@@ -204,14 +204,18 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
     static_assert(NW == 4, "four waves");
     static_assert(WAVES_M == 2 && WAVES_N == 2 && (BM == 256 || BM == 128) && (BN == 256 || BN == 128),
                   "the addressing assumes 2 x 2 waves on 128- or 256-wide tiles");
-    constexpr int EP_STRIDE = 64 * 2 + 16;    // bytes per staged epilogue row: 64 bf16 + padding
-    static_assert(TM % 2 == 0 && TN % 4 == 0, "an epilogue pass stages 2 x 4 MFMA tiles (32 rows x 64 columns)");
+    // An epilogue pass stages 8 MFMA tiles: EPW of them side by side (the whole width of the wave's
+    // tile if that is 128 columns: a store instruction then covers 4 rows x 256 bytes, measured
+    // 1 % faster on the products than 8 rows x 128 bytes), 8 / EPW below each other
+    constexpr int EPW = TN >= 8 ? 8 : 4, EPR = 8 / EPW;
+    constexpr int EP_STRIDE = 16 * EPW * 2 + 16;    // bytes per staged epilogue row: the bf16 of a row + padding
+    static_assert(TM % EPR == 0 && TN % EPW == 0, "the wave tile is a whole number of epilogue passes");
 
     // One array per stage: the compiler then knows that a load into one stage does not alias
     // LDS reads of the other and does not serialise them.
     __shared__ __attribute__((aligned(1024))) uint8_t st0[STAGE];
     __shared__ __attribute__((aligned(1024))) uint8_t st1[STAGE];
-    __shared__ __attribute__((aligned(16))) uint8_t epb[NW * 32 * EP_STRIDE];
+    __shared__ __attribute__((aligned(16))) uint8_t epb[NW * 16 * EPR * EP_STRIDE];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -425,10 +429,10 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
     using I1 = integral_constant<int, 1>;
 
     // ---- epilogue of one tile.  Of each 16x16 MFMA tile, lane l holds m = l % 16 and
-    // n = 4 * (l / 16) + r for accumulator register r.  Each wave turns a 32-row, 64-column
-    // piece of its tile at a time into bf16, parks it in its private piece of LDS and writes it
-    // out as 16-byte row pieces: every global store instruction then covers whole 128-byte row
-    // segments.
+    // n = 4 * (l / 16) + r for accumulator register r.  Each wave turns a piece of 8 MFMA tiles
+    // (16 EPR rows x 16 EPW columns) of its tile at a time into bf16, parks it in its private
+    // piece of LDS and writes it out as 16-byte row pieces: every global store instruction then
+    // covers whole row segments of 32 EPW bytes (a multiple of the 128-byte line).
     auto epilogue = [&](int item) {
         int tm, tn;
         tile_coords(SPLITK ? item % tiles_mn : item, tiles_m, tiles_n, &tm, &tn);
@@ -448,25 +452,26 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
             }
             return;
         }
-        uint8_t* ep = epb + wave * (32 * EP_STRIDE);
+        uint8_t* ep = epb + wave * (16 * EPR * EP_STRIDE);
         float s_tensor = 0.f;
         if constexpr (GRAN == F8_TENSORWISE) s_tensor = isa[0] * isb[0];
-        // A lane stores four 16-byte pieces per pass: rows 8 t + lane / 8 of the 32-row band,
-        // columns 8 * (lane % 8) .. +7 of the 64-column pass: uniform base + 32-bit lane offset.
+        // A lane stores four 16-byte pieces per pass: row (64 / LPR) t + lane / LPR of the pass's
+        // rows, columns 8 * (lane % LPR) .. +7 of its columns: uniform base + 32-bit lane offset.
         uint8_t* dbase = reinterpret_cast<uint8_t*>(D + (int64_t)m0 * ldd + n0);
         const uint32_t ldd_b = (uint32_t)ldd * 2;
-        const uint32_t voff = (uint32_t)(lane >> 3) * ldd_b + (uint32_t)(lane & 7) * 16;
+        constexpr int LPR = 2 * EPW;  // lanes (16-byte pieces) per staged row
+        const uint32_t voff = (uint32_t)(lane / LPR) * ldd_b + (uint32_t)(lane % LPR) * 16;
         const bool interior = tm * BM + BM <= M && tn * BN + BN <= N;  // no edge checks needed
 
         auto run = [&](auto INTERIOR) {
-            // One pass = rows 32 ip .. + 31, columns 64 jp .. + 63 of the wave's tile = 2 x 4 MFMA
+            // One pass = rows 16 EPR ip .., columns 16 EPW jp .. of the wave's tile = EPR x EPW MFMA
             // tiles.  Tensorwise: row bands outermost.  Per-row / per-column scales: column bands
             // outermost, so that the column scales a lane needs are loaded once per band (and
             // the row scales once per tile) instead of in every pass, where their latency would
             // sit in front of each conversion.
-            constexpr int NP = (TM / 2) * (TN / 4);
+            constexpr int NP = (TM / EPR) * (TN / EPW);
             float sav[TM];
-            float4 sbv[4];
+            float4 sbv[EPW];
             if constexpr (GRAN != F8_TENSORWISE) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i) {
@@ -476,22 +481,22 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
             }
             static_for<NP>([&](auto P) {
                 constexpr int p = decltype(P)::value;
-                constexpr int ip = GRAN == F8_TENSORWISE ? p / (TN / 4) : p % (TM / 2);
-                constexpr int jp = GRAN == F8_TENSORWISE ? p % (TN / 4) : p / (TM / 2);
+                constexpr int ip = GRAN == F8_TENSORWISE ? p / (TN / EPW) : p % (TM / EPR);
+                constexpr int jp = GRAN == F8_TENSORWISE ? p % (TN / EPW) : p / (TM / EPR);
                 if constexpr (GRAN != F8_TENSORWISE && ip == 0) {
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        int n = n0 + 64 * jp + 16 * jj + 4 * fg;
+                    for (int jj = 0; jj < EPW; ++jj) {
+                        int n = n0 + 16 * EPW * jp + 16 * jj + 4 * fg;
                         n = n < N ? n : N - 4;
                         sbv[jj] = *reinterpret_cast<const float4*>(isb + n);
                     }
                 }
 #pragma unroll
-                for (int ii = 0; ii < 2; ++ii) {
-                    const int i = 2 * ip + ii;
+                for (int ii = 0; ii < EPR; ++ii) {
+                    const int i = EPR * ip + ii;
 #pragma unroll
-                    for (int jj = 0; jj < 4; ++jj) {
-                        const int j = 4 * jp + jj;
+                    for (int jj = 0; jj < EPW; ++jj) {
+                        const int j = EPW * jp + jj;
                         const int nl = 16 * jj + 4 * fg;  // column inside the pass
                         f2 lo, hi;
                         if constexpr (GRAN == F8_TENSORWISE) {
@@ -511,27 +516,27 @@ __global__ __launch_bounds__(WAVES_M* WAVES_N * 64) void gemm_tile_kernel(
                             // edge tiles hold results of re-read rows past M / N: not output
                             bool counted = true;
                             if constexpr (!decltype(INTERIOR)::value)
-                                counted = m0 + 16 * i + fr < M && n0 + 64 * jp + nl < N;
+                                counted = m0 + 16 * i + fr < M && n0 + 16 * EPW * jp + nl < N;
                             if (counted) amax_acc = amax_pair(amax_acc, o);
                         }
                         *reinterpret_cast<uint2*>(ep + (16 * ii + fr) * EP_STRIDE + nl * 2) = o;
                     }
                 }
-                uint8_t* pbase = dbase + ((int64_t)(32 * ip) * ldd + 64 * jp) * 2;  // uniform
+                uint8_t* pbase = dbase + ((int64_t)(16 * EPR * ip) * ldd + 16 * EPW * jp) * 2;  // uniform
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const int idx = t * 64 + lane;
-                    const uint4 v = *reinterpret_cast<const uint4*>(ep + (idx >> 3) * EP_STRIDE + (idx & 7) * 16);
+                    const uint4 v = *reinterpret_cast<const uint4*>(ep + (idx / LPR) * EP_STRIDE + (idx % LPR) * 16);
                     bool ok = true;
                     if constexpr (!decltype(INTERIOR)::value)
-                        ok = m0 + 32 * ip + (idx >> 3) < M && n0 + 64 * jp + (idx & 7) * 8 < N;
+                        ok = m0 + 16 * EPR * ip + idx / LPR < M && n0 + 16 * EPW * jp + (idx % LPR) * 8 < N;
                     // Streaming store: D is not read again by this library, and lines that
                     // linger dirty in the L2 / Infinity Cache would be written back during the
                     // next, bandwidth-bound kernel instead of during this compute-bound one.
                     typedef unsigned int u4v __attribute__((ext_vector_type(4)));
                     if (ok)
                         __builtin_nontemporal_store(u4v{v.x, v.y, v.z, v.w},
-                                                    reinterpret_cast<u4v*>(pbase + (voff + (uint32_t)(8 * t) * ldd_b)));
+                                                    reinterpret_cast<u4v*>(pbase + (voff + (uint32_t)(64 / LPR * t) * ldd_b)));
                 }
                 // one pass at a time: measured faster than letting the compiler interleave passes
                 __builtin_amdgcn_sched_barrier(0);
