@@ -531,6 +531,18 @@ def main():
         # every other configuration of the benchmark spec, each in the variants it names: fewer
         # steps, the same measurement
         configs = {f"config5 {w.key} {gran}:{gfmt}": brief(rec)}
+        if shares_inputs(w, args, rowwise):
+            # the same configuration with an input tensor and an input cast of its own for every linear
+            # (seven X casts instead of four), for comparison
+            import copy
+            own_args = copy.copy(args)
+            own_args.own_inputs = True
+            del rec, states
+            torch.cuda.empty_cache()
+            orec, _ = run_linear_workload(f8, wl, torch, own_args, w, gran, gfmt, max(3, min(args.steps, 8)), 2, None)
+            configs[f"config5 {w.key} {gran}:{gfmt}, every linear with its own input cast"] = brief(orec)
+            del orec
+            rec = states = None
         del rec, states, inputs
         torch.cuda.empty_cache()
         for num, key, variants in ALL_CONFIGS:
