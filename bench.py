@@ -972,6 +972,7 @@ def fp8_library_context(states, timed, reps, flops_step):
     import torch
     try:
         total = 0.0
+        by_product = {"Y = X W^T": [0.0, 0], "dX = dY W": [0.0, 0], "dW = dY^T X": [0.0, 0]}
         for s in states:
             sv = s.saved
             x8, w8, dy8 = (t.view(torch.float8_e4m3fn) for t in (sv.x.q, sv.w.q, sv.dy.q))
@@ -980,10 +981,14 @@ def fp8_library_context(states, timed, reps, flops_step):
             fns = [lambda: torch._scaled_mm(x8, w8.t(), isx, isw, out_dtype=torch.bfloat16),          # Y  = X W^T
                    lambda: torch._scaled_mm(dy8, w8t.t(), isdy, isw, out_dtype=torch.bfloat16),       # dX = dY W
                    lambda: torch._scaled_mm(dy8t, x8t.t(), isdy, isx, out_dtype=torch.bfloat16)]      # dW = dY^T X
-            for fn in fns:
+            for fn, name in zip(fns, by_product):
                 fn()
-                total += timed(fn, reps)
+                ms = timed(fn, reps)
+                total += ms
+                by_product[name][0] += ms
+                by_product[name][1] += 2 * s.lin.M * s.lin.K * s.lin.N
         return {"ms_per_step": round(total, 4), "tflops": round(flops_step / (total * 1e-3) / 1e12, 1),
+                "tflops_by_product": {k: round(fl / (ms * 1e-3) / 1e12, 1) for k, (ms, fl) in by_product.items()},
                 "what": f"torch._scaled_mm fp8 e4m3 (hipBLASLt), the same {3 * len(states)} products on this library's codes, "
                         "operands pre-transposed as that call wants them, no casts"}
     except Exception as exc:   # context only
